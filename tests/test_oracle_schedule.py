@@ -1,0 +1,203 @@
+"""Pins for the oracle's scheduler: the paper's theorems, brute force on tiny
+DAGs, closed-form special cases and hand-worked vectors. CPU only."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+import workloads
+from oracle import checks
+from oracle.schedule import schedule, transitive_closure, minimum_equivalent_graph
+from dag_util import random_dag, layered_dag
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "schedule_vectors.json")
+
+
+def tup(xs):
+    return [tuple(x) for x in xs]
+
+
+def tiny_dags(seed, count, nmin, nmax):
+    rng = np.random.default_rng(seed)
+    for _ in range(count):
+        n = int(rng.integers(nmin, nmax + 1))
+        yield n, random_dag(rng, n, float(rng.uniform(0.15, 0.6)))
+
+
+@pytest.mark.parametrize("vec", json.load(open(GOLDEN))["vectors"], ids=lambda v: v["name"])
+def test_hand_worked_vectors(vec):
+    s = schedule(vec["n"], tup(vec["edges"]))
+    assert s.meg == tup(vec["meg"])
+    assert s.matching == tup(vec["matching"])
+    assert s.chain_of == vec["chain_of"]
+    assert s.stream_of == vec["stream_of"]
+    assert s.sync == tup(vec["sync"])
+
+
+def test_closure_matches_relaxation():
+    for n, e in tiny_dags(1, 200, 2, 12):
+        reach = transitive_closure(n, e)
+        r = checks.reachable(n, e)
+        for u in range(n):
+            for v in range(n):
+                assert bool(reach[u] >> v & 1) == r[u][v]
+
+
+def test_meg_is_unique_minimal_and_equivalent():
+    # Section 4.2: the MEG of a DAG is unique -> an independent construction must agree;
+    # Lemma 1: an E' edge is the only path between its ends; reachability is preserved.
+    for n, e in tiny_dags(2, 300, 2, 12):
+        reach = transitive_closure(n, e)
+        meg = minimum_equivalent_graph(n, e, reach)
+        assert meg == checks.meg_by_edge_removal(n, e)
+        assert checks.reachable(n, meg) == checks.reachable(n, e)
+        for (u, v) in meg:
+            others = [x for x in set(e) if x != (u, v)]
+            assert not checks.reachable(n, others)[u][v]
+
+
+def test_theorem3_closed_form_and_lemma4():
+    # Theorem 3: Algorithm 1's assignment needs exactly |E'| - |M| synchronisations.
+    # Lemma 4: any max-concurrency assignment needs |E'| - |Q(f)|.
+    for n, e in tiny_dags(3, 400, 2, 14):
+        s = schedule(n, e)
+        cross = [(u, v) for u, v in s.meg if s.chain_of[u] != s.chain_of[v]]
+        assert len(cross) == len(s.meg) - len(s.matching)
+        assert checks.lemma4_count(n, s.meg, s.chain_of) == len(cross)
+        assert len(s.sync) == checks.lemma4_count(n, s.meg, s.stream_of)
+        if not s.phase3_changed:            # joining chains tail-to-head keeps the optimum
+            assert len(s.sync) == len(s.meg) - len(s.matching)
+
+
+def test_sync_count_matches_definition_of_min_sync():
+    # Appendix A: min_sync(G, f) is the size of the smallest safe plan. Enumerate plans.
+    done = 0
+    for n, e in tiny_dags(4, 400, 2, 7):
+        if len(set(e)) > 9:
+            continue
+        s = schedule(n, e)
+        assert checks.min_sync_by_definition(n, e, s.chain_of) == len(s.meg) - len(s.matching)
+        assert checks.min_sync_by_definition(n, e, s.stream_of) == len(s.sync)
+        assert checks.plan_is_safe(n, e, s.stream_of, s.sync)
+        done += 1
+    assert done > 100
+
+
+def test_theorem4_optimal_over_all_partitions():
+    # No assignment with maximum logical concurrency needs fewer synchronisations.
+    for n, e in tiny_dags(5, 120, 2, 7):
+        s = schedule(n, e)
+        best = checks.best_partition_sync(n, e, lambda f: checks.lemma4_count(n, s.meg, f))
+        assert best == len(s.meg) - len(s.matching)
+
+
+def test_theorem4_with_definitional_count():
+    for n, e in tiny_dags(6, 40, 2, 5):
+        if len(set(e)) > 7:
+            continue
+        s = schedule(n, e)
+        best = checks.best_partition_sync(n, e, lambda f: checks.min_sync_by_definition(n, e, f))
+        assert best == len(s.meg) - len(s.matching)
+
+
+def test_streams_are_chains_and_as_few_as_the_widest_antichain():
+    for n, e in tiny_dags(7, 400, 1, 13):
+        s = schedule(n, e)
+        assert checks.has_max_logical_concurrency(n, e, s.chain_of)
+        assert checks.has_max_logical_concurrency(n, e, s.stream_of)
+        assert s.n_streams == checks.max_antichain(n, e)
+        assert s.n_chains >= s.n_streams
+        assert sorted(set(s.stream_of)) == list(range(s.n_streams))
+        assert s.stream_of[0] == 0
+
+
+def test_execution_order_is_safe():
+    for n, e in tiny_dags(8, 400, 1, 14):
+        s = schedule(n, e)
+        assert checks.execution_respects_edges(n, e, s.stream_of, s.order, s.sync)
+        # events: one per distinct producer, numbered by producer id
+        prod = sorted({u for u, _ in s.sync})
+        assert [s.event_of[u] for u in prod] == list(range(len(prod)))
+        assert s.n_events == len(prod)
+        for v in range(n):
+            assert s.waits[v] == sorted(u for u, w in s.sync if w == v)
+
+
+def test_dropping_any_sync_edge_is_caught():
+    # the safety checker itself must notice a missing event (planted mistake)
+    rng = np.random.default_rng(9)
+    hit = 0
+    for n, e in tiny_dags(9, 100, 4, 12):
+        s = schedule(n, e)
+        if not s.sync:
+            continue
+        k = int(rng.integers(0, len(s.sync)))
+        broken = s.sync[:k] + s.sync[k + 1:]
+        assert not checks.execution_respects_edges(n, e, s.stream_of, s.order, broken)
+        hit += 1
+    assert hit > 30
+
+
+def test_special_cases():
+    # a path -> one stream, nothing to synchronise
+    s = schedule(10, [(i, i + 1) for i in range(9)])
+    assert s.n_streams == 1 and s.sync == [] and s.stream_of == [0] * 10
+    # k isolated nodes -> k streams, all forked from the origin
+    s = schedule(5, [])
+    assert s.n_streams == 5 and s.sync == [] and s.fork == [1, 2, 3, 4] and s.join == [1, 2, 3, 4]
+    # k parallel paths between one source and one sink -> k streams, 2(k-1) synchronisations
+    for k in range(1, 6):
+        for length in (1, 3):
+            edges, n = [], 1
+            tails = []
+            for _ in range(k):
+                prev = 0
+                for _ in range(length):
+                    edges.append((prev, n))
+                    prev = n
+                    n += 1
+                tails.append(prev)
+            edges += [(t, n) for t in tails]
+            s = schedule(n + 1, edges)
+            assert s.n_streams == k
+            assert len(s.sync) == 2 * (k - 1)
+            assert s.fork == []
+
+
+def test_fork_list_is_streams_whose_first_task_has_no_wait():
+    for n, e in tiny_dags(10, 200, 2, 12):
+        s = schedule(n, e)
+        for st in range(1, s.n_streams):
+            first = min(v for v in range(n) if s.stream_of[v] == st)
+            assert (st in s.fork) == (not s.waits[first])
+        assert s.join == list(range(1, s.n_streams))
+
+
+def test_layered_dags_medium():
+    rng = np.random.default_rng(11)
+    for _ in range(20):
+        n, e = layered_dag(rng, int(rng.integers(3, 8)), 5)
+        s = schedule(n, e)
+        assert checks.has_max_logical_concurrency(n, e, s.stream_of)
+        assert checks.execution_respects_edges(n, e, s.stream_of, s.order, s.sync)
+        if n <= 16:
+            assert s.n_streams == checks.max_antichain(n, e)
+
+
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_benchmark_configs(name):
+    w = workloads.make(name)
+    n, e = len(w.nodes), w.edges
+    s = schedule(n, e)
+    assert len(s.sync) == checks.lemma4_count(n, s.meg, s.stream_of)
+    cross1 = sum(s.chain_of[u] != s.chain_of[v] for u, v in s.meg)
+    assert cross1 == len(s.meg) - len(s.matching)
+    if n <= 210:
+        assert checks.has_max_logical_concurrency(n, e, s.stream_of)
+        assert checks.execution_respects_edges(n, e, s.stream_of, s.order, s.sync)
+    if name == "tiny_cell":
+        assert (n, s.n_streams, len(s.sync)) == (8, 2, 2)
+        assert checks.max_antichain(n, e) == 2
+    if name == "chain50":
+        assert s.n_streams == 1 and not s.sync
