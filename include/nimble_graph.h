@@ -1,0 +1,197 @@
+/*
+ * nimble_graph.h - C ABI of the ahead-of-time multi-stream DAG executor for MI355X.
+ *
+ * The calls follow the problem statement of the Nimble paper (arXiv 2012.02732):
+ *   1. register a static operator DAG with a fixed input shape (Section 4, "System
+ *      Design": the system takes a computation graph as input);
+ *   2. run the ahead-of-time pass once (Section 4.1 "Ahead-of-time (AoT) Scheduling",
+ *      Section 4.2 "Stream Assignment Algorithm", Algorithm 1, Appendix A);
+ *   3. replay the recorded task schedule for every new input (Section 4.1, last
+ *      paragraph: replay through a graph launch).
+ *
+ * General conventions
+ *   - Every function returns NG_OK (0) or a negative NG_E* code. Nothing throws or
+ *     aborts across this boundary. ng_last_error() gives a readable message for the
+ *     last failure on that graph.
+ *   - A graph is not thread-safe; use one graph from one thread at a time.
+ *   - Tensors are fp32, NCHW, dense.
+ *   - Ownership: the library owns the graph object, its schedule, task table, events
+ *     and HIP graph objects. The CALLER owns the arena, all weight buffers and all
+ *     streams, and must keep them alive and unchanged in address until ng_destroy().
+ *     Weight, arena and stream arguments are DEVICE-side handles (device pointers /
+ *     hipStream_t values passed as void*); every other pointer is a HOST pointer.
+ *   - Call order: ng_create -> ng_add_input / ng_add_node ... -> ng_mark_output ...
+ *     -> ng_schedule -> ng_plan_memory -> ng_bind -> ng_capture -> ng_replay / ng_sync.
+ *     A call made too early returns NG_ESTATE. Everything up to and including
+ *     ng_plan_memory is host-only and works on a machine without a GPU.
+ */
+#ifndef NIMBLE_GRAPH_H
+#define NIMBLE_GRAPH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NG_MAX_PREDS 8
+
+enum {
+    NG_OK = 0,
+    NG_EINVAL = -1, /* bad argument (null pointer, unknown id, unknown op, bad parameter) */
+    NG_ESHAPE = -2, /* operand shapes do not fit the operator */
+    NG_ESTATE = -3, /* call made in the wrong phase */
+    NG_ENOMEM = -4, /* arena too small or too few streams */
+    NG_EHIP = -5    /* a HIP runtime call failed; text in ng_last_error() */
+};
+
+/* Operator vocabulary: one node = one GPU task (the paper's operators may be several
+ * tasks, Section 1; here the DAG is registered at task granularity). */
+enum {
+    NG_OP_INPUT = 0,          /* network input, no kernel; the caller writes it into the arena */
+    NG_OP_CONV1X1 = 1,        /* pointwise conv, weights {W[cout][cin]} */
+    NG_OP_DWCONV = 2,         /* depthwise k x k, k in {3,5}, stride in {1,2}, pad = k/2, weights {W[c][k][k]} */
+    NG_OP_CONV3X3 = 3,        /* dense 3x3, stride in {1,2}, pad in {0,1}, weights {W[cout][cin][3][3]} */
+    NG_OP_BN_ACT = 4,         /* inference batch norm (+ReLU if relu != 0), weights {gamma, beta, mean, var}, each [c] */
+    NG_OP_RELU = 5,           /* max(x, 0) */
+    NG_OP_ADD_N = 6,          /* elementwise sum of 2..NG_MAX_PREDS tensors of equal shape */
+    NG_OP_CONCAT = 7,         /* channel slices [slice_lo[j], slice_hi[j]) of pred j stacked along C */
+    NG_OP_POOL = 8,           /* 3x3 window, pool_mode 0 = max, 1 = avg (divisor = in-bounds taps), stride {1,2}, pad {0,1} */
+    NG_OP_GLOBAL_AVGPOOL = 9, /* mean over H x W -> [n][c][1][1] */
+    NG_OP_FC = 10             /* y = W x + b on [n][cin][1][1], weights {W[cout][cin], b[cout]} */
+};
+
+typedef struct ng_op_params {
+    int32_t cout;      /* CONV1X1, CONV3X3, FC */
+    int32_t k;         /* DWCONV: 3 or 5 */
+    int32_t stride;    /* DWCONV, CONV3X3, POOL: 1 or 2 */
+    int32_t pad;       /* CONV3X3, POOL: 0 or 1 */
+    int32_t relu;      /* BN_ACT */
+    int32_t pool_mode; /* POOL: 0 max, 1 avg */
+    float eps;         /* BN_ACT */
+    int32_t slice_lo[NG_MAX_PREDS]; /* CONCAT; slice_hi[j] == 0 means "all channels of pred j" */
+    int32_t slice_hi[NG_MAX_PREDS];
+} ng_op_params;
+
+typedef struct ng_graph ng_graph; /* opaque */
+
+/* ---- 1. registration (Section 4: a DAG G = (V, E) of operators, fixed input shape) ---- */
+
+/* Create an empty graph. *out receives the handle (host pointer, library-owned). */
+int ng_create(ng_graph** out);
+/* Release everything the library owns (schedule, events, HIP graphs). NULL is allowed. */
+void ng_destroy(ng_graph* g);
+
+/* Add an input node of shape nchw[4] (host array). *id receives the node id. Node ids
+ * are 0, 1, 2, ... in registration order. */
+int ng_add_input(ng_graph* g, const int64_t nchw[4], int* id);
+
+/* Add an operator node. preds (host array of n_preds ids) must name existing nodes, so
+ * ids are a topological order of the DAG. dev_weights (host array of n_weights DEVICE
+ * pointers, caller-owned) are the operator's parameters in the order listed at the op
+ * enum; they may be NULL pointers until ng_capture (host-only use). The output shape is
+ * inferred here; a mismatch returns NG_ESHAPE and leaves the graph unchanged. */
+int ng_add_node(ng_graph* g, int op_kind, const ng_op_params* p,
+                const int* preds, int n_preds,
+                const void* const* dev_weights, int n_weights, int* id);
+
+/* Mark a node whose tensor the caller will read after a replay. */
+int ng_mark_output(ng_graph* g, int id);
+
+int ng_num_nodes(const ng_graph* g);
+/* Inferred output shape of a node into nchw[4] (host). */
+int ng_node_shape(const ng_graph* g, int id, int64_t nchw[4]);
+
+/* ---- 2a. ahead-of-time pass, host part (Section 4.2, Algorithm 1, Appendix A) ---- */
+
+/* Stream assignment and synchronisation plan. Closes registration.
+ *   Step 1   minimum equivalent graph G' = (V, E');
+ *   Step 2-3 maximum matching M of the bipartite graph of E' (augmenting paths, left and
+ *            right nodes in ascending id);
+ *   Step 4-5 chains = sets merged along M ("chain_of", Algorithm 1 verbatim);
+ *   then chains are joined tail-to-head along closure edges, and a final augmenting pass
+ *   over the closure makes the stream count equal the widest antichain ("stream_of");
+ *   Lambda = E' edges whose ends are on different streams (Appendix A: each must be
+ *   synchronised itself, Lemma 1); one event per distinct producer in Lambda.
+ * Submission order is ascending node id; node 0 is on stream 0, the capture origin. */
+int ng_schedule(ng_graph* g);
+
+/* Sizes of the arrays ng_get_schedule fills (any pointer may be NULL). */
+int ng_schedule_sizes(const ng_graph* g, int* n_nodes, int* n_streams, int* n_chains,
+                      int* n_meg_edges, int* n_matching, int* n_sync, int* n_events);
+
+/* Copy the schedule into caller-allocated HOST arrays (any may be NULL):
+ *   order[n_nodes], stream_of[n_nodes], chain_of[n_nodes], event_of[n_nodes] (-1 = none),
+ *   meg_src/meg_dst[n_meg_edges] sorted by (src, dst),
+ *   sync_src/sync_dst[n_sync] sorted by (src, dst). */
+int ng_get_schedule(const ng_graph* g, int* order, int* stream_of, int* chain_of, int* event_of,
+                    int* meg_src, int* meg_dst, int* sync_src, int* sync_dst);
+
+/* Capture scaffolding, not part of Lambda: fork[] = non-origin streams whose first task
+ * waits for nothing (they join the capture through an event recorded on the origin
+ * before its first task); join[] = non-origin streams the origin waits for after its
+ * last task. Arrays are caller-allocated with room for n_streams entries. */
+int ng_get_scaffold(const ng_graph* g, int* fork, int* n_fork, int* join, int* n_join);
+
+/* Static memory plan (Section 4.1: memory requests are identical on every run, so the
+ * exact amount is reserved once). One buffer per node output, 256-byte aligned, no reuse.
+ * *arena_bytes receives the total. */
+int ng_plan_memory(ng_graph* g, size_t* arena_bytes);
+/* offset[n_nodes], bytes[n_nodes] of each node's output inside the arena (host arrays). */
+int ng_get_offsets(const ng_graph* g, size_t* offset, size_t* bytes);
+
+/* Longest path of G under per-node weights t[n_nodes] (e.g. isolated kernel times):
+ * the critical-path time of Section 3. path[] (room for n_nodes) receives the node ids. */
+int ng_critical_path(const ng_graph* g, const float* t, float* total, int* path, int* n_path);
+
+/* ---- 2b. ahead-of-time pass, GPU part (Section 4.1: pre-run once, record the tasks) ---- */
+
+/* Attach caller-owned device memory and streams. arena: DEVICE pointer, 256-byte aligned,
+ * at least the planned size. hip_streams: HOST array of n_streams hipStream_t values, all
+ * on the current device, n_streams >= the scheduled stream count (NG_ENOMEM otherwise).
+ * Builds the task table: kernel, launch geometry and argument block with resolved device
+ * addresses for every node. */
+int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_streams, int n_streams);
+
+/* Pre-run the network once under stream capture on the bound streams, in submission
+ * order with the planned event records/waits, and instantiate executable HIP graphs: one
+ * for the multi-stream schedule, one with every task on the origin stream. The arena
+ * contents are overwritten with whatever the pre-run computes from its current input. */
+int ng_capture(ng_graph* g);
+
+/* Fixed DEVICE address of a node's output inside the bound arena (NULL on error). The
+ * caller writes the input tensor to ng_tensor_ptr(g, input_id) before ng_replay and reads
+ * outputs after ng_sync. */
+void* ng_tensor_ptr(const ng_graph* g, int id);
+
+/* ---- 3. replay (Section 4.1: raw submission of the recorded tasks) ---- */
+
+enum {
+    NG_MODE_GRAPH_MULTI = 0,  /* captured multi-stream graph, one hipGraphLaunch (default) */
+    NG_MODE_GRAPH_SINGLE = 1, /* captured single-stream graph */
+    NG_MODE_EAGER_SINGLE = 2, /* task table launched kernel by kernel on the origin stream */
+    NG_MODE_EAGER_MULTI = 3   /* task table launched on the assigned streams with real events */
+};
+int ng_replay_mode(ng_graph* g, int mode);
+/* Asynchronous: enqueue one inference on the origin stream (hip_streams[0]). */
+int ng_replay(ng_graph* g);
+/* Wait until the origin stream is idle. */
+int ng_sync(ng_graph* g);
+
+/* Isolated duration of one task in microseconds: the kernel is launched alone `reps`
+ * times on the origin stream, each launch timed by the device's own start/stop
+ * timestamps; *median_us receives the median (0 for input nodes). */
+int ng_time_task(ng_graph* g, int id, int reps, float* median_us);
+/* Name of the kernel bound to a node ("" for input nodes); valid until ng_destroy. */
+const char* ng_task_kernel(const ng_graph* g, int id);
+/* Algorithmic work of a node, from its shapes: bytes moved and flops (host doubles). */
+int ng_task_work(const ng_graph* g, int id, double* bytes, double* flops);
+
+const char* ng_last_error(const ng_graph* g);
+const char* ng_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NIMBLE_GRAPH_H */

@@ -1,0 +1,335 @@
+// Registration, shape inference, static memory plan and host-side queries.
+// Paper: Nimble (arXiv 2012.02732), Section 4 (input is a static operator DAG with a
+// fixed input shape) and Section 4.1 (all shapes and all memory are fixed ahead of time).
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "ng_internal.h"
+
+using namespace ng;
+
+namespace {
+
+int conv_out(int64_t size, int k, int stride, int pad) {
+    return (int)((size + 2 * pad - k) / stride + 1);
+}
+
+bool in_set(int v, int a, int b) { return v == a || v == b; }
+
+// Output shape of an operator, or an error text. Mirrors the operator table in the header.
+const char* infer_shape(const ng_graph* g, int op, ng_op_params& p, const int* preds, int n_preds,
+                        int n_weights, Shape& out, int& code) {
+    code = NG_EINVAL;
+    auto in = [&](int j) -> const Shape& { return g->nodes[preds[j]].out; };
+    auto need = [&](int np, int nw) { return n_preds == np && n_weights == nw; };
+    switch (op) {
+        case NG_OP_CONV1X1:
+            if (!need(1, 1)) return "conv1x1 takes 1 input and 1 weight";
+            if (p.cout <= 0) return "conv1x1: cout must be positive";
+            out = in(0);
+            out.c = p.cout;
+            return nullptr;
+        case NG_OP_DWCONV: {
+            if (!need(1, 1)) return "dwconv takes 1 input and 1 weight";
+            if (!in_set(p.k, 3, 5) || !in_set(p.stride, 1, 2)) return "dwconv: k in {3,5}, stride in {1,2}";
+            out = in(0);
+            out.h = conv_out(in(0).h, p.k, p.stride, p.k / 2);
+            out.w = conv_out(in(0).w, p.k, p.stride, p.k / 2);
+            break;
+        }
+        case NG_OP_CONV3X3:
+            if (!need(1, 1)) return "conv3x3 takes 1 input and 1 weight";
+            if (p.cout <= 0 || !in_set(p.stride, 1, 2) || !in_set(p.pad, 0, 1))
+                return "conv3x3: cout > 0, stride in {1,2}, pad in {0,1}";
+            out = in(0);
+            out.c = p.cout;
+            out.h = conv_out(in(0).h, 3, p.stride, p.pad);
+            out.w = conv_out(in(0).w, 3, p.stride, p.pad);
+            break;
+        case NG_OP_BN_ACT:
+            if (!need(1, 4)) return "bn_act takes 1 input and 4 weights";
+            if (!(p.eps >= 0.f)) return "bn_act: eps must be >= 0";
+            out = in(0);
+            return nullptr;
+        case NG_OP_RELU:
+            if (!need(1, 0)) return "relu takes 1 input and no weights";
+            out = in(0);
+            return nullptr;
+        case NG_OP_ADD_N:
+            if (n_preds < 2 || n_preds > NG_MAX_PREDS || n_weights != 0) return "add_n takes 2..8 inputs";
+            for (int j = 1; j < n_preds; ++j)
+                if (!(in(j) == in(0))) {
+                    code = NG_ESHAPE;
+                    return "add_n: inputs differ in shape";
+                }
+            out = in(0);
+            return nullptr;
+        case NG_OP_CONCAT: {
+            if (n_preds < 1 || n_preds > NG_MAX_PREDS || n_weights != 0) return "concat takes 1..8 inputs";
+            out = in(0);
+            out.c = 0;
+            for (int j = 0; j < n_preds; ++j) {
+                if (p.slice_hi[j] == 0) {
+                    p.slice_lo[j] = 0;
+                    p.slice_hi[j] = (int32_t)in(j).c;
+                }
+                if (in(j).n != in(0).n || in(j).h != in(0).h || in(j).w != in(0).w) {
+                    code = NG_ESHAPE;
+                    return "concat: inputs differ in n, h or w";
+                }
+                if (p.slice_lo[j] < 0 || p.slice_lo[j] >= p.slice_hi[j] || p.slice_hi[j] > in(j).c) {
+                    code = NG_ESHAPE;
+                    return "concat: channel slice out of range";
+                }
+                out.c += p.slice_hi[j] - p.slice_lo[j];
+            }
+            return nullptr;
+        }
+        case NG_OP_POOL:
+            if (!need(1, 0)) return "pool takes 1 input and no weights";
+            if (!in_set(p.pool_mode, 0, 1) || !in_set(p.stride, 1, 2) || !in_set(p.pad, 0, 1))
+                return "pool: mode in {0,1}, stride in {1,2}, pad in {0,1}";
+            out = in(0);
+            out.h = conv_out(in(0).h, 3, p.stride, p.pad);
+            out.w = conv_out(in(0).w, 3, p.stride, p.pad);
+            break;
+        case NG_OP_GLOBAL_AVGPOOL:
+            if (!need(1, 0)) return "global_avgpool takes 1 input and no weights";
+            out = in(0);
+            out.h = out.w = 1;
+            return nullptr;
+        case NG_OP_FC:
+            if (!need(1, 2)) return "fc takes 1 input and 2 weights";
+            if (p.cout <= 0) return "fc: cout must be positive";
+            if (in(0).h != 1 || in(0).w != 1) {
+                code = NG_ESHAPE;
+                return "fc: input must be [n][c][1][1]";
+            }
+            out = in(0);
+            out.c = p.cout;
+            return nullptr;
+        default:
+            return "unknown operator kind";
+    }
+    if (out.h <= 0 || out.w <= 0) {
+        code = NG_ESHAPE;
+        return "window does not fit the input";
+    }
+    return nullptr;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* ng_version(void) { return "nimble_graph 0.1 (gfx950)"; }
+
+int ng_create(ng_graph** out) {
+    if (!out) return NG_EINVAL;
+    *out = new (std::nothrow) ng_graph();
+    return *out ? NG_OK : NG_ENOMEM;
+}
+
+void ng_destroy(ng_graph* g) {
+    if (!g) return;
+    destroy_runtime(g);
+    delete g;
+}
+
+const char* ng_last_error(const ng_graph* g) { return g ? g->err.c_str() : "null graph"; }
+
+int ng_add_input(ng_graph* g, const int64_t nchw[4], int* id) {
+    if (!g) return NG_EINVAL;
+    if (!nchw || !id) return g->fail(NG_EINVAL, "ng_add_input: null argument");
+    if (g->phase != BUILDING) return g->fail(NG_ESTATE, "ng_add_input: registration is closed");
+    for (int i = 0; i < 4; ++i)
+        if (nchw[i] <= 0 || nchw[i] > (1 << 24)) return g->fail(NG_ESHAPE, "ng_add_input: bad extent %lld", (long long)nchw[i]);
+    Node nd;
+    nd.op = NG_OP_INPUT;
+    nd.out = Shape{nchw[0], nchw[1], nchw[2], nchw[3]};
+    g->nodes.push_back(nd);
+    *id = (int)g->nodes.size() - 1;
+    return NG_OK;
+}
+
+int ng_add_node(ng_graph* g, int op_kind, const ng_op_params* p, const int* preds, int n_preds,
+                const void* const* dev_weights, int n_weights, int* id) {
+    if (!g) return NG_EINVAL;
+    if (!id || n_preds < 0 || n_weights < 0 || (n_preds > 0 && !preds) || (n_weights > 0 && !dev_weights))
+        return g->fail(NG_EINVAL, "ng_add_node: null or negative argument");
+    if (g->phase != BUILDING) return g->fail(NG_ESTATE, "ng_add_node: registration is closed");
+    if (op_kind == NG_OP_INPUT) return g->fail(NG_EINVAL, "ng_add_node: use ng_add_input for inputs");
+    if (n_preds == 0 || n_preds > NG_MAX_PREDS) return g->fail(NG_EINVAL, "ng_add_node: needs 1..%d predecessors", NG_MAX_PREDS);
+    for (int j = 0; j < n_preds; ++j)
+        if (preds[j] < 0 || preds[j] >= (int)g->nodes.size())
+            return g->fail(NG_EINVAL, "ng_add_node: predecessor id %d does not exist", preds[j]);
+    Node nd;
+    nd.op = op_kind;
+    if (p) nd.p = *p;
+    int code = NG_EINVAL;
+    if (const char* msg = infer_shape(g, op_kind, nd.p, preds, n_preds, n_weights, nd.out, code))
+        return g->fail(code, "ng_add_node(node %d): %s", (int)g->nodes.size(), msg);
+    if (nd.out.elems() <= 0 || nd.out.elems() >= ((int64_t)1 << 31))
+        return g->fail(NG_ESHAPE, "ng_add_node: tensor of %lld elements is not supported", (long long)nd.out.elems());
+    nd.preds.assign(preds, preds + n_preds);
+    nd.weights.assign(dev_weights, dev_weights + n_weights);
+    g->nodes.push_back(std::move(nd));
+    *id = (int)g->nodes.size() - 1;
+    return NG_OK;
+}
+
+int ng_mark_output(ng_graph* g, int id) {
+    if (!g) return NG_EINVAL;
+    if (id < 0 || id >= (int)g->nodes.size()) return g->fail(NG_EINVAL, "ng_mark_output: no node %d", id);
+    g->nodes[id].is_output = true;
+    return NG_OK;
+}
+
+int ng_num_nodes(const ng_graph* g) { return g ? (int)g->nodes.size() : NG_EINVAL; }
+
+int ng_node_shape(const ng_graph* g, int id, int64_t nchw[4]) {
+    if (!g || !nchw || id < 0 || id >= (int)g->nodes.size()) return NG_EINVAL;
+    const Shape& s = g->nodes[id].out;
+    nchw[0] = s.n, nchw[1] = s.c, nchw[2] = s.h, nchw[3] = s.w;
+    return NG_OK;
+}
+
+int ng_schedule(ng_graph* g) {
+    if (!g) return NG_EINVAL;
+    if (g->phase != BUILDING) return g->fail(NG_ESTATE, "ng_schedule: already scheduled");
+    if (g->nodes.empty()) return g->fail(NG_EINVAL, "ng_schedule: empty graph");
+    std::vector<std::pair<int, int>> edges;
+    for (int v = 0; v < (int)g->nodes.size(); ++v)
+        for (int u : g->nodes[v].preds) edges.emplace_back(u, v);
+    compute_schedule((int)g->nodes.size(), edges, g->sched);
+    g->phase = SCHEDULED;
+    return NG_OK;
+}
+
+int ng_schedule_sizes(const ng_graph* g, int* n_nodes, int* n_streams, int* n_chains, int* n_meg_edges,
+                      int* n_matching, int* n_sync, int* n_events) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < SCHEDULED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_schedule_sizes: call ng_schedule first");
+    const Schedule& s = g->sched;
+    if (n_nodes) *n_nodes = (int)g->nodes.size();
+    if (n_streams) *n_streams = s.n_streams;
+    if (n_chains) *n_chains = s.n_chains;
+    if (n_meg_edges) *n_meg_edges = (int)s.meg.size();
+    if (n_matching) *n_matching = s.n_matching;
+    if (n_sync) *n_sync = (int)s.sync.size();
+    if (n_events) *n_events = s.n_events;
+    return NG_OK;
+}
+
+int ng_get_schedule(const ng_graph* g, int* order, int* stream_of, int* chain_of, int* event_of,
+                    int* meg_src, int* meg_dst, int* sync_src, int* sync_dst) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < SCHEDULED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_get_schedule: call ng_schedule first");
+    const Schedule& s = g->sched;
+    const size_t n = g->nodes.size();
+    if (order) std::copy(s.order.begin(), s.order.end(), order);
+    if (stream_of) std::copy(s.stream_of.begin(), s.stream_of.end(), stream_of);
+    if (chain_of) std::copy(s.chain_of.begin(), s.chain_of.end(), chain_of);
+    if (event_of) std::copy(s.event_of.begin(), s.event_of.end(), event_of);
+    (void)n;
+    for (size_t i = 0; i < s.meg.size(); ++i) {
+        if (meg_src) meg_src[i] = s.meg[i].first;
+        if (meg_dst) meg_dst[i] = s.meg[i].second;
+    }
+    for (size_t i = 0; i < s.sync.size(); ++i) {
+        if (sync_src) sync_src[i] = s.sync[i].first;
+        if (sync_dst) sync_dst[i] = s.sync[i].second;
+    }
+    return NG_OK;
+}
+
+int ng_get_scaffold(const ng_graph* g, int* fork, int* n_fork, int* join, int* n_join) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < SCHEDULED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_get_scaffold: call ng_schedule first");
+    const Schedule& s = g->sched;
+    if (fork) std::copy(s.fork.begin(), s.fork.end(), fork);
+    if (join) std::copy(s.join.begin(), s.join.end(), join);
+    if (n_fork) *n_fork = (int)s.fork.size();
+    if (n_join) *n_join = (int)s.join.size();
+    return NG_OK;
+}
+
+int ng_plan_memory(ng_graph* g, size_t* arena_bytes) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < SCHEDULED) return g->fail(NG_ESTATE, "ng_plan_memory: call ng_schedule first");
+    if (g->phase > PLANNED) return g->fail(NG_ESTATE, "ng_plan_memory: already bound");
+    const size_t n = g->nodes.size();
+    g->offset.assign(n, 0);
+    g->bytes.assign(n, 0);
+    size_t top = 0;
+    for (size_t v = 0; v < n; ++v) {            // one private buffer per node output, 256-byte aligned
+        g->offset[v] = top;
+        g->bytes[v] = (size_t)g->nodes[v].out.elems() * sizeof(float);
+        top += (g->bytes[v] + 255) & ~(size_t)255;
+    }
+    g->arena_bytes = top;
+    g->phase = PLANNED;
+    if (arena_bytes) *arena_bytes = top;
+    return NG_OK;
+}
+
+int ng_get_offsets(const ng_graph* g, size_t* offset, size_t* bytes) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < PLANNED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_get_offsets: call ng_plan_memory first");
+    if (offset) std::copy(g->offset.begin(), g->offset.end(), offset);
+    if (bytes) std::copy(g->bytes.begin(), g->bytes.end(), bytes);
+    return NG_OK;
+}
+
+int ng_critical_path(const ng_graph* g, const float* t, float* total, int* path, int* n_path) {
+    if (!g || !t) return NG_EINVAL;
+    const int n = (int)g->nodes.size();
+    if (n == 0) return NG_EINVAL;
+    std::vector<double> best(n);
+    std::vector<int> from(n, -1);
+    int last = 0;
+    for (int v = 0; v < n; ++v) {               // ids are a topological order
+        double b = 0;
+        for (int u : g->nodes[v].preds)
+            if (from[v] < 0 || best[u] > b) {
+                b = best[u];
+                from[v] = u;
+            }
+        best[v] = b + t[v];
+        if (best[v] > best[last]) last = v;
+    }
+    std::vector<int> rev;
+    for (int v = last; v >= 0; v = from[v]) rev.push_back(v);
+    if (total) *total = (float)best[last];
+    if (n_path) *n_path = (int)rev.size();
+    if (path) std::reverse_copy(rev.begin(), rev.end(), path);
+    return NG_OK;
+}
+
+int ng_task_work(const ng_graph* g, int id, double* bytes, double* flops) {
+    if (!g || id < 0 || id >= (int)g->nodes.size()) return NG_EINVAL;
+    const Node& nd = g->nodes[id];
+    const double out = (double)nd.out.elems();
+    double in0 = nd.preds.empty() ? 0 : (double)g->nodes[nd.preds[0]].out.elems();
+    double cin = nd.preds.empty() ? 0 : (double)g->nodes[nd.preds[0]].out.c;
+    double b = 0, f = 0;
+    switch (nd.op) {
+        case NG_OP_CONV1X1: b = 4 * (in0 + cin * nd.out.c + out); f = 2 * cin * out; break;
+        case NG_OP_DWCONV: b = 4 * (in0 + nd.out.c * nd.p.k * nd.p.k + out); f = 2.0 * nd.p.k * nd.p.k * out; break;
+        case NG_OP_CONV3X3: b = 4 * (in0 + 9 * cin * nd.out.c + out); f = 18 * cin * out; break;
+        case NG_OP_BN_ACT: b = 8 * out + 16.0 * nd.out.c; f = 2 * out; break;
+        case NG_OP_RELU: b = 8 * out; f = out; break;
+        case NG_OP_ADD_N: b = 4 * (nd.preds.size() + 1.0) * out; f = (nd.preds.size() - 1.0) * out; break;
+        case NG_OP_CONCAT: b = 8 * out; break;
+        case NG_OP_POOL: b = 4 * (in0 + out); f = 9 * out; break;
+        case NG_OP_GLOBAL_AVGPOOL: b = 4 * (in0 + out); f = in0; break;
+        case NG_OP_FC: b = 4 * (cin * nd.out.c + nd.out.c + in0 + out); f = 2 * cin * out; break;
+        default: break;
+    }
+    if (bytes) *bytes = b;
+    if (flops) *flops = f;
+    return NG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// Internal data model of the AoT multi-stream DAG executor (not part of the C ABI).
+#pragma once
+
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "nimble_graph.h"
+
+namespace ng {
+
+enum Phase { BUILDING = 0, SCHEDULED = 1, PLANNED = 2, BOUND = 3, CAPTURED = 4 };
+
+struct Shape {
+    int64_t n = 0, c = 0, h = 0, w = 0;
+    int64_t elems() const { return n * c * h * w; }
+    bool operator==(const Shape& o) const { return n == o.n && c == o.c && h == o.h && w == o.w; }
+};
+
+struct Node {
+    int op = 0;
+    ng_op_params p{};
+    std::vector<int> preds;
+    std::vector<const void*> weights;
+    Shape out;
+    bool is_output = false;
+};
+
+// Result of the stream-assignment pass (Algorithm 1 + Appendix A of the paper).
+struct Schedule {
+    std::vector<std::pair<int, int>> meg;      // E', sorted
+    int n_matching = 0;                        // |M| of Step 3
+    std::vector<int> chain_of;                 // Steps 4-5
+    int n_chains = 0;
+    std::vector<int> stream_of;
+    int n_streams = 0;
+    std::vector<std::pair<int, int>> sync;     // Lambda, sorted
+    std::vector<int> event_of;
+    int n_events = 0;
+    std::vector<int> order;
+    std::vector<std::vector<int>> waits;       // per consumer, producers ascending
+    std::vector<int> fork, join;
+};
+
+// One entry of the task table: everything a launch needs, resolved ahead of time.
+struct Task {
+    const void* fn = nullptr;                  // host-side kernel handle
+    const char* name = "";
+    unsigned grid[3] = {1, 1, 1};
+    unsigned block[3] = {1, 1, 1};
+    unsigned lds_bytes = 0;
+    alignas(16) unsigned char args[256];       // the kernel's single by-value argument struct
+    unsigned args_bytes = 0;
+};
+
+struct Runtime;  // HIP-side state, defined in ng_runtime.hip
+
+}  // namespace ng
+
+struct ng_graph {
+    ng::Phase phase = ng::BUILDING;
+    std::vector<ng::Node> nodes;
+    ng::Schedule sched;
+    std::vector<size_t> offset, bytes;
+    size_t arena_bytes = 0;
+    std::vector<ng::Task> tasks;
+    ng::Runtime* rt = nullptr;
+    int mode = NG_MODE_GRAPH_MULTI;
+    std::string err;
+
+    int fail(int code, const char* fmt, ...) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        err = buf;
+        return code;
+    }
+};
+
+namespace ng {
+// ng_schedule.cpp
+void compute_schedule(int n, const std::vector<std::pair<int, int>>& edges, Schedule& out);
+// ng_kernels.hip: fill the launch descriptor of node v (addresses resolved against `arena`).
+int build_task(ng_graph* g, int v, char* arena, Task& t);
+// ng_runtime.hip
+void destroy_runtime(ng_graph* g);
+}  // namespace ng

@@ -1,0 +1,232 @@
+// GPU part of the ahead-of-time pass and the replay path.
+//
+// Nimble (arXiv 2012.02732), Section 4.1: the network is pre-run once on the assigned
+// streams while every submitted GPU task is recorded (stream capture), the record is
+// turned into an executable graph, and each later inference is one graph launch - no
+// shape checks, no kernel dispatch, no allocator and no argument marshalling at run time
+// (the per-task steps listed in Section 2, "GPU Task Scheduling in DL Frameworks").
+// Here the library is itself the launcher, so "recording" means: build the task table
+// once (ng_bind), then issue it once under hipStreamBeginCapture (ng_capture).
+#include <hip/hip_ext.h>
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "ng_internal.h"
+
+namespace ng {
+
+struct Runtime {
+    char* arena = nullptr;
+    size_t arena_bytes = 0;
+    std::vector<hipStream_t> streams;
+    std::vector<hipEvent_t> events;        // one per producer in Lambda
+    hipEvent_t fork_event = nullptr;
+    std::vector<hipEvent_t> join_events;   // indexed by stream (entry 0 unused)
+    hipGraph_t graph[2] = {nullptr, nullptr};
+    hipGraphExec_t exec[2] = {nullptr, nullptr};
+    hipEvent_t t_start = nullptr, t_stop = nullptr;
+};
+
+namespace {
+
+#define NG_HIP(call)                                                                        \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return g->fail(NG_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__, __LINE__); \
+    } while (0)
+
+int launch(ng_graph* g, const Task& t, hipStream_t s) {
+    if (!t.fn) return NG_OK;                                   // input node: nothing to run
+    void* args[1] = {const_cast<unsigned char*>(t.args)};
+    NG_HIP(hipLaunchKernel(t.fn, dim3(t.grid[0], t.grid[1], t.grid[2]), dim3(t.block[0], t.block[1], t.block[2]),
+                           args, t.lds_bytes, s));
+    return NG_OK;
+}
+
+// Issue the whole task table once, in submission order. multi = true: every task on its
+// assigned stream with the planned event records / waits plus fork and join scaffolding;
+// multi = false: everything on the origin stream, no events at all.
+int issue_all(ng_graph* g, bool multi) {
+    Runtime& rt = *g->rt;
+    const Schedule& sc = g->sched;
+    hipStream_t origin = rt.streams[0];
+    if (!multi) {
+        for (int v : sc.order)
+            if (int rc = launch(g, g->tasks[v], origin)) return rc;
+        return NG_OK;
+    }
+    if (!sc.fork.empty()) {
+        NG_HIP(hipEventRecord(rt.fork_event, origin));
+        for (int s : sc.fork) NG_HIP(hipStreamWaitEvent(rt.streams[s], rt.fork_event, 0));
+    }
+    for (int v : sc.order) {
+        hipStream_t s = rt.streams[sc.stream_of[v]];
+        for (int u : sc.waits[v]) NG_HIP(hipStreamWaitEvent(s, rt.events[sc.event_of[u]], 0));
+        if (int rc = launch(g, g->tasks[v], s)) return rc;
+        if (sc.event_of[v] >= 0) NG_HIP(hipEventRecord(rt.events[sc.event_of[v]], s));
+    }
+    for (int s : sc.join) {
+        NG_HIP(hipEventRecord(rt.join_events[s], rt.streams[s]));
+        NG_HIP(hipStreamWaitEvent(origin, rt.join_events[s], 0));
+    }
+    return NG_OK;
+}
+
+int capture_one(ng_graph* g, bool multi, int slot) {
+    Runtime& rt = *g->rt;
+    hipStream_t origin = rt.streams[0];
+    NG_HIP(hipStreamBeginCapture(origin, hipStreamCaptureModeThreadLocal));
+    int rc = issue_all(g, multi);
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(origin, &graph);        // always end the capture, even after a failure
+    if (rc) {
+        if (graph) (void)hipGraphDestroy(graph);
+        return rc;
+    }
+    if (e != hipSuccess) return g->fail(NG_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
+    rt.graph[slot] = graph;
+    NG_HIP(hipGraphInstantiate(&rt.exec[slot], graph, nullptr, nullptr, 0));
+    return NG_OK;
+}
+
+}  // namespace
+
+void destroy_runtime(ng_graph* g) {
+    Runtime* rt = g->rt;
+    if (!rt) return;
+    for (int i = 0; i < 2; ++i) {
+        if (rt->exec[i]) (void)hipGraphExecDestroy(rt->exec[i]);
+        if (rt->graph[i]) (void)hipGraphDestroy(rt->graph[i]);
+    }
+    for (hipEvent_t e : rt->events) (void)hipEventDestroy(e);
+    for (hipEvent_t e : rt->join_events)
+        if (e) (void)hipEventDestroy(e);
+    if (rt->fork_event) (void)hipEventDestroy(rt->fork_event);
+    if (rt->t_start) (void)hipEventDestroy(rt->t_start);
+    if (rt->t_stop) (void)hipEventDestroy(rt->t_stop);
+    delete rt;
+    g->rt = nullptr;
+}
+
+}  // namespace ng
+
+using namespace ng;
+
+extern "C" {
+
+int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_streams, int n_streams) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < PLANNED) return g->fail(NG_ESTATE, "ng_bind: call ng_plan_memory first");
+    if (!arena || !hip_streams) return g->fail(NG_EINVAL, "ng_bind: null arena or stream array");
+    if ((reinterpret_cast<uintptr_t>(arena) & 255) != 0) return g->fail(NG_EINVAL, "ng_bind: arena must be 256-byte aligned");
+    if (arena_bytes < g->arena_bytes)
+        return g->fail(NG_ENOMEM, "ng_bind: arena has %zu bytes, the plan needs %zu", arena_bytes, g->arena_bytes);
+    if (n_streams < g->sched.n_streams)
+        return g->fail(NG_ENOMEM, "ng_bind: %d streams given, the schedule uses %d", n_streams, g->sched.n_streams);
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, arena) != hipSuccess || attr.type != hipMemoryTypeDevice) {
+        (void)hipGetLastError();
+        return g->fail(NG_EINVAL, "ng_bind: arena is not device memory");
+    }
+    destroy_runtime(g);
+    g->rt = new Runtime();
+    Runtime& rt = *g->rt;
+    rt.arena = static_cast<char*>(arena);
+    rt.arena_bytes = arena_bytes;
+    for (int s = 0; s < g->sched.n_streams; ++s) rt.streams.push_back(static_cast<hipStream_t>(hip_streams[s]));
+
+    g->tasks.assign(g->nodes.size(), Task());
+    for (int v = 0; v < (int)g->nodes.size(); ++v)
+        if (int rc = build_task(g, v, rt.arena, g->tasks[v])) return rc;
+
+    rt.events.resize(g->sched.n_events);
+    for (auto& e : rt.events) NG_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    rt.join_events.assign(g->sched.n_streams, nullptr);
+    for (int s : g->sched.join) NG_HIP(hipEventCreateWithFlags(&rt.join_events[s], hipEventDisableTiming));
+    NG_HIP(hipEventCreateWithFlags(&rt.fork_event, hipEventDisableTiming));
+    NG_HIP(hipEventCreate(&rt.t_start));
+    NG_HIP(hipEventCreate(&rt.t_stop));
+    g->phase = BOUND;
+    return NG_OK;
+}
+
+int ng_capture(ng_graph* g) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < BOUND) return g->fail(NG_ESTATE, "ng_capture: call ng_bind first");
+    Runtime& rt = *g->rt;
+    for (int i = 0; i < 2; ++i) {
+        if (rt.exec[i]) (void)hipGraphExecDestroy(rt.exec[i]), rt.exec[i] = nullptr;
+        if (rt.graph[i]) (void)hipGraphDestroy(rt.graph[i]), rt.graph[i] = nullptr;
+    }
+    if (int rc = capture_one(g, true, 0)) return rc;
+    if (int rc = capture_one(g, false, 1)) return rc;
+    // the pre-run itself: execute the recorded schedule once so that every kernel is loaded
+    NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
+    NG_HIP(hipStreamSynchronize(rt.streams[0]));
+    g->phase = CAPTURED;
+    return NG_OK;
+}
+
+void* ng_tensor_ptr(const ng_graph* g, int id) {
+    if (!g || g->phase < BOUND || id < 0 || id >= (int)g->nodes.size()) return nullptr;
+    return g->rt->arena + g->offset[id];
+}
+
+int ng_replay_mode(ng_graph* g, int mode) {
+    if (!g) return NG_EINVAL;
+    if (mode < NG_MODE_GRAPH_MULTI || mode > NG_MODE_EAGER_MULTI) return g->fail(NG_EINVAL, "ng_replay_mode: unknown mode %d", mode);
+    g->mode = mode;
+    return NG_OK;
+}
+
+int ng_replay(ng_graph* g) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_replay: call ng_capture first");
+    Runtime& rt = *g->rt;
+    switch (g->mode) {
+        case NG_MODE_GRAPH_MULTI: NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0])); return NG_OK;
+        case NG_MODE_GRAPH_SINGLE: NG_HIP(hipGraphLaunch(rt.exec[1], rt.streams[0])); return NG_OK;
+        case NG_MODE_EAGER_SINGLE: return issue_all(g, false);
+        default: return issue_all(g, true);
+    }
+}
+
+int ng_sync(ng_graph* g) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < BOUND) return g->fail(NG_ESTATE, "ng_sync: call ng_bind first");
+    NG_HIP(hipStreamSynchronize(g->rt->streams[0]));
+    return NG_OK;
+}
+
+int ng_time_task(ng_graph* g, int id, int reps, float* median_us) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < BOUND) return g->fail(NG_ESTATE, "ng_time_task: call ng_bind first");
+    if (id < 0 || id >= (int)g->nodes.size() || reps <= 0 || !median_us) return g->fail(NG_EINVAL, "ng_time_task: bad argument");
+    Runtime& rt = *g->rt;
+    const Task& t = g->tasks[id];
+    *median_us = 0.f;
+    if (!t.fn) return NG_OK;
+    hipStream_t s = rt.streams[0];
+    std::vector<float> ms(reps);
+    void* args[1] = {const_cast<unsigned char*>(t.args)};
+    for (int r = -2; r < reps; ++r) {                          // two untimed warm-ups
+        NG_HIP(hipExtLaunchKernel(t.fn, dim3(t.grid[0], t.grid[1], t.grid[2]), dim3(t.block[0], t.block[1], t.block[2]),
+                                  args, t.lds_bytes, s, rt.t_start, rt.t_stop, 0));
+        NG_HIP(hipEventSynchronize(rt.t_stop));
+        float v = 0.f;
+        NG_HIP(hipEventElapsedTime(&v, rt.t_start, rt.t_stop));
+        if (r >= 0) ms[r] = v;
+    }
+    std::sort(ms.begin(), ms.end());
+    *median_us = ms[reps / 2] * 1000.f;
+    return NG_OK;
+}
+
+const char* ng_task_kernel(const ng_graph* g, int id) {
+    if (!g || g->phase < BOUND || id < 0 || id >= (int)g->tasks.size()) return "";
+    return g->tasks[id].name;
+}
+
+}  // extern "C"

@@ -1,0 +1,129 @@
+"""Registers a workload description with the library and owns the torch plumbing.
+
+PyTorch is used for exactly three things: device memory (weights, the arena),
+stream handles, and host<->device copies of inputs/outputs. Every step of the
+method itself - shape inference, Algorithm 1, the memory plan, the task table,
+capture, replay and all kernels - runs inside libnimble_graph.so.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_OPS = {"conv1x1": B.NG_OP_CONV1X1, "dwconv": B.NG_OP_DWCONV, "conv3x3": B.NG_OP_CONV3X3,
+        "bn_act": B.NG_OP_BN_ACT, "relu": B.NG_OP_RELU, "add_n": B.NG_OP_ADD_N,
+        "concat": B.NG_OP_CONCAT, "pool": B.NG_OP_POOL, "global_avgpool": B.NG_OP_GLOBAL_AVGPOOL,
+        "fc": B.NG_OP_FC}
+
+
+def _params(nd) -> B.ng_op_params:
+    p, q = B.ng_op_params(), nd.params
+    p.cout = int(q.get("cout", 0))
+    p.k = int(q.get("k", 0))
+    p.stride = int(q.get("stride", 1))
+    p.pad = int(q.get("pad", 0))
+    p.relu = int(q.get("relu", 0))
+    p.pool_mode = 1 if q.get("mode") == "avg" else 0
+    p.eps = float(q.get("eps", 0.0))
+    for j, (lo, hi) in enumerate(zip(q.get("lo", []), q.get("hi", []))):
+        p.slice_lo[j], p.slice_hi[j] = int(lo), int(hi)
+    return p
+
+
+class GraphRunner:
+    """One registered DAG. ``device=None`` keeps everything on the host (scheduling
+    and planning only; weights are registered as null pointers)."""
+
+    def __init__(self, workload, device=None):
+        self.workload = workload
+        self.device = device
+        self.g = B.ng_create()
+        self._weights = []                       # keeps device tensors alive
+        self.arena = None
+        self.streams = []
+        for v, nd in enumerate(workload.nodes):
+            if nd.op == "input":
+                q = nd.params
+                vid = B.ng_add_input(self.g, (q["n"], q["c"], q["h"], q["w"]))
+            else:
+                ptrs = []
+                for w in nd.weights:
+                    if device is None:
+                        ptrs.append(0)
+                    else:
+                        t = torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).to(device)
+                        self._weights.append(t)
+                        ptrs.append(t.data_ptr())
+                vid = B.ng_add_node(self.g, _OPS[nd.op], _params(nd), nd.preds, ptrs)
+            assert vid == v
+        for o in workload.outputs:
+            B.ng_mark_output(self.g, o)
+
+    def close(self):
+        if self.g is not None:
+            if self.device is not None:
+                torch.cuda.synchronize(self.device)
+            B.ng_destroy(self.g)
+            self.g = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- host-only part of the AoT pass ------------------------------------------
+    def schedule(self) -> dict:
+        B.ng_schedule(self.g)
+        return B.ng_get_schedule(self.g)
+
+    def plan(self) -> int:
+        return B.ng_plan_memory(self.g)
+
+    # -- GPU part ----------------------------------------------------------------
+    def prepare(self):
+        """schedule -> plan -> bind -> capture, allocating arena and streams with torch."""
+        assert self.device is not None, "GraphRunner was created without a device"
+        sched = self.schedule()
+        nbytes = self.plan()
+        self.arena = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.device)
+        base = (self.arena.data_ptr() + 255) // 256 * 256
+        with torch.cuda.device(self.device):
+            self.streams = [torch.cuda.Stream(device=self.device) for _ in range(sched["n_streams"])]
+        torch.cuda.synchronize(self.device)
+        B.ng_bind(self.g, base, nbytes, [s.cuda_stream for s in self.streams])
+        self.set_input(self.workload.input)
+        B.ng_capture(self.g)
+        return sched
+
+    def _view(self, node_id) -> torch.Tensor:
+        shape = B.ng_node_shape(self.g, node_id)
+        off = B.ng_tensor_ptr(self.g, node_id) - self.arena.data_ptr()
+        n = int(np.prod(shape))
+        return self.arena[off:off + 4 * n].view(torch.float32).view(*shape)
+
+    def set_input(self, x: np.ndarray, node_id: int = 0):
+        t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+        self._view(node_id).copy_(t.to(self.device))
+        torch.cuda.synchronize(self.device)
+
+    def replay(self, mode=None):
+        if mode is not None:
+            B.ng_replay_mode(self.g, mode)
+        B.ng_replay(self.g)
+
+    def sync(self):
+        B.ng_sync(self.g)
+
+    def output(self, node_id) -> np.ndarray:
+        self.sync()
+        torch.cuda.synchronize(self.device)
+        return self._view(node_id).cpu().numpy()
+
+    def run(self, x=None, mode=None) -> dict:
+        if x is not None:
+            self.set_input(x)
+        self.replay(mode)
+        return {o: self.output(o) for o in self.workload.outputs}

@@ -1,0 +1,210 @@
+"""Host-only tests of the C-ABI library: it loads without a GPU, exports every declared
+symbol, infers shapes, and its scheduling pass matches the oracle bit for bit."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import workloads
+from workloads.model import Node, Workload
+from oracle.schedule import schedule as oracle_schedule
+from paper_2012_02732_amd import GraphRunner, binding as B
+from dag_util import random_dag, layered_dag
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def abstract_workload(n, edges):
+    """A DAG with no tensor meaning: sources are inputs, one predecessor -> relu, several -> add_n."""
+    preds = [[] for _ in range(n)]
+    for u, v in sorted(set(edges)):
+        preds[v].append(u)
+    nodes = []
+    for v in range(n):
+        if not preds[v]:
+            nodes.append(Node("input", [], dict(n=1, c=2, h=2, w=2), [], (1, 2, 2, 2)))
+        elif len(preds[v]) == 1:
+            nodes.append(Node("relu", preds[v], {}, [], (1, 2, 2, 2)))
+        else:
+            nodes.append(Node("add_n", preds[v], {}, [], (1, 2, 2, 2)))
+    return Workload("abstract", nodes, np.zeros((1, 2, 2, 2), np.float32), [n - 1])
+
+
+def assert_same_schedule(lib_sched, scaffold, o):
+    assert lib_sched["meg"] == o.meg
+    assert lib_sched["n_matching"] == len(o.matching)
+    assert lib_sched["chain_of"] == o.chain_of and lib_sched["n_chains"] == o.n_chains
+    assert lib_sched["stream_of"] == o.stream_of and lib_sched["n_streams"] == o.n_streams
+    assert lib_sched["sync"] == o.sync
+    assert lib_sched["event_of"] == o.event_of and lib_sched["n_events"] == o.n_events
+    assert lib_sched["order"] == o.order
+    assert scaffold == (o.fork, o.join)
+
+
+def test_header_symbols_are_exported():
+    header = open(os.path.join(ROOT, "include", "nimble_graph.h")).read()
+    declared = set(re.findall(r"\b(ng_[a-z_]+)\s*\(", header))
+    assert declared == set(B.SYMBOLS), declared ^ set(B.SYMBOLS)
+    for name in declared:
+        assert hasattr(B.lib, name), name
+    assert "gfx950" in B.ng_version()
+
+
+def test_schedule_parity_on_random_tiny_dags():
+    rng = np.random.default_rng(123)
+    for i in range(3000):
+        n = int(rng.integers(1, 17))
+        e = random_dag(rng, n, float(rng.uniform(0.1, 0.7)))
+        r = GraphRunner(abstract_workload(n, e))
+        s = r.schedule()
+        assert_same_schedule(s, B.ng_get_scaffold(r.g), oracle_schedule(n, e))
+        r.close()
+
+
+def test_schedule_parity_on_medium_dags():
+    rng = np.random.default_rng(7)
+    for _ in range(60):
+        n, e = layered_dag(rng, int(rng.integers(3, 15)), 9)
+        r = GraphRunner(abstract_workload(n, e))
+        assert_same_schedule(r.schedule(), B.ng_get_scaffold(r.g), oracle_schedule(n, e))
+        r.close()
+    for _ in range(20):
+        n = int(rng.integers(40, 160))
+        e = random_dag(rng, n, float(rng.uniform(0.01, 0.08)))
+        r = GraphRunner(abstract_workload(n, e))
+        assert_same_schedule(r.schedule(), B.ng_get_scaffold(r.g), oracle_schedule(n, e))
+        r.close()
+
+
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_configs_shapes_schedule_and_plan(name):
+    w = workloads.make(name)
+    r = GraphRunner(w)
+    for i, nd in enumerate(w.nodes):
+        assert B.ng_node_shape(r.g, i) == nd.shape
+    s = r.schedule()
+    assert_same_schedule(s, B.ng_get_scaffold(r.g), oracle_schedule(len(w.nodes), w.edges))
+    total = r.plan()
+    off, nbytes = B.ng_get_offsets(r.g)
+    assert nbytes == [4 * int(np.prod(nd.shape)) for nd in w.nodes]
+    spans = sorted(zip(off, nbytes))
+    for (o1, b1), (o2, _) in zip(spans, spans[1:]):
+        assert o1 % 256 == 0 and o1 + b1 <= o2              # aligned, disjoint: no buffer reuse
+    assert spans[-1][0] + spans[-1][1] <= total
+    r.close()
+
+
+def test_batch_changes_shapes_not_schedule():
+    a, b = workloads.make("inception_style", batch=1), workloads.make("inception_style", batch=32)
+    ra, rb = GraphRunner(a), GraphRunner(b)
+    assert ra.schedule() == rb.schedule()
+    assert B.ng_node_shape(rb.g, len(b.nodes) - 1) == (32, 1000, 1, 1)
+    assert rb.plan() > 30 * ra.plan() // 2
+
+
+def test_critical_path_matches_plain_dp():
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        n, e = layered_dag(rng, 6, 5)
+        w = abstract_workload(n, e)
+        r = GraphRunner(w)
+        t = rng.uniform(0.5, 5.0, n).astype(np.float32)
+        total, path = B.ng_critical_path(r.g, list(t))
+        best = np.zeros(n)
+        for v in range(n):
+            best[v] = t[v] + max([best[u] for u in w.nodes[v].preds], default=0.0)
+        assert abs(total - best.max()) < 1e-3
+        assert abs(sum(t[v] for v in path) - total) < 1e-3
+        for u, v in zip(path, path[1:]):
+            assert u in w.nodes[v].preds
+        r.close()
+
+
+def test_task_work_formulas():
+    w = workloads.make("random200")
+    r = GraphRunner(w)
+    for v, nd in enumerate(w.nodes):
+        nbytes, flops = B.ng_task_work(r.g, v)
+        n, c, h, wd = nd.shape
+        if nd.op == "conv1x1":
+            assert flops == 2 * 64 * 64 * 784 and nbytes == 4 * (2 * 64 * 784 + 64 * 64)
+        if nd.op == "dwconv":
+            assert flops == 18 * 64 * 784 and nbytes == 4 * (2 * 64 * 784 + 64 * 9)
+        if nd.op == "add_n":
+            assert nbytes == 4 * (len(nd.preds) + 1) * 64 * 784
+
+
+# ---- error paths (no exception or abort crosses the boundary) ----------------------
+def _g_with_input(shape=(1, 4, 8, 8)):
+    g = B.ng_create()
+    B.ng_add_input(g, shape)
+    return g
+
+
+def _code(fn, *a):
+    with pytest.raises(B.NgError) as ei:
+        fn(*a)
+    return ei.value.code
+
+
+def test_error_codes():
+    g = _g_with_input()
+    p = B.ng_op_params()
+    assert _code(B.ng_add_node, g, B.NG_OP_RELU, p, [5], []) == B.NG_EINVAL          # unknown predecessor
+    assert _code(B.ng_add_node, g, 99, p, [0], []) == B.NG_EINVAL                   # unknown op
+    assert _code(B.ng_add_node, g, B.NG_OP_RELU, p, [], []) == B.NG_EINVAL          # no predecessor
+    assert _code(B.ng_add_node, g, B.NG_OP_CONV1X1, p, [0], [0]) == B.NG_EINVAL     # cout = 0
+    assert _code(B.ng_add_node, g, B.NG_OP_BN_ACT, p, [0], [0]) == B.NG_EINVAL      # wrong weight count
+    p.k, p.stride = 4, 1
+    assert _code(B.ng_add_node, g, B.NG_OP_DWCONV, p, [0], [0]) == B.NG_EINVAL      # k not in {3,5}
+    p = B.ng_op_params()
+    p.cout = 3
+    assert _code(B.ng_add_node, g, B.NG_OP_FC, p, [0], [0, 0]) == B.NG_ESHAPE       # fc on an 8x8 map
+    small = B.ng_add_node(g, B.NG_OP_GLOBAL_AVGPOOL, B.ng_op_params(), [0], [])
+    assert _code(B.ng_add_node, g, B.NG_OP_ADD_N, B.ng_op_params(), [0, small], []) == B.NG_ESHAPE
+    q = B.ng_op_params()
+    q.slice_lo[0], q.slice_hi[0] = 2, 9
+    assert _code(B.ng_add_node, g, B.NG_OP_CONCAT, q, [0], []) == B.NG_ESHAPE       # slice past the last channel
+    q = B.ng_op_params()
+    q.stride, q.pad = 1, 0
+    assert _code(B.ng_add_node, g, B.NG_OP_POOL, q, [small], []) == B.NG_ESHAPE     # 3x3 window on a 1x1 map
+    assert _code(B.ng_mark_output, g, 77) == B.NG_EINVAL
+    assert B.ng_num_nodes(g) == 2                                                   # failed calls added nothing
+    # wrong call order
+    assert _code(B.ng_plan_memory, g) == B.NG_ESTATE
+    assert _code(B.ng_get_schedule, g) == B.NG_ESTATE
+    assert _code(B.ng_capture, g) == B.NG_ESTATE
+    assert _code(B.ng_replay, g) == B.NG_ESTATE
+    B.ng_schedule(g)
+    assert _code(B.ng_schedule, g) == B.NG_ESTATE
+    assert _code(B.ng_add_node, g, B.NG_OP_RELU, B.ng_op_params(), [0], []) == B.NG_ESTATE
+    assert _code(B.ng_add_input, g, (1, 1, 1, 1)) == B.NG_ESTATE
+    assert _code(B.ng_bind, g, 256, 1 << 20, [0]) == B.NG_ESTATE                    # bind before plan
+    B.ng_plan_memory(g)
+    assert _code(B.ng_replay_mode, g, 9) == B.NG_EINVAL
+    assert "ng_replay_mode" in B.ng_last_error(g)
+    B.ng_destroy(g)
+    B.ng_destroy(None)                                                              # allowed
+
+    e = B.ng_create()
+    assert _code(B.ng_schedule, e) == B.NG_EINVAL                                   # empty graph
+    assert _code(B.ng_add_input, e, (1, 0, 2, 2)) == B.NG_ESHAPE
+    B.ng_destroy(e)
+
+
+def test_bind_rejects_bad_resources_without_a_gpu():
+    g = _g_with_input()
+    B.ng_add_node(g, B.NG_OP_RELU, B.ng_op_params(), [0], [])
+    B.ng_schedule(g)
+    need = B.ng_plan_memory(g)
+    assert _code(B.ng_bind, g, 0, need, [0]) == B.NG_EINVAL                         # null arena
+    assert _code(B.ng_bind, g, 4096 + 4, need, [0]) == B.NG_EINVAL                  # misaligned
+    assert _code(B.ng_bind, g, 4096, need - 1, [0]) == B.NG_ENOMEM                  # arena too small
+    assert _code(B.ng_bind, g, 4096, need, []) in (B.NG_ENOMEM, B.NG_EINVAL)        # too few streams
+    buf = (C.c_char * (need + 512))()
+    host = (C.addressof(buf) + 255) // 256 * 256
+    assert _code(B.ng_bind, g, host, need, [0]) == B.NG_EINVAL                      # host memory is not an arena
+    assert B.ng_tensor_ptr(g, 0) == 0
+    B.ng_destroy(g)
