@@ -148,7 +148,7 @@ int ng_critical_path(const ng_graph* g, const float* t, float* total, int* path,
 /* ---- 2b. ahead-of-time pass, GPU part (Section 4.1: pre-run once, record the tasks) ---- */
 
 /* Attach caller-owned device memory and streams. arena: DEVICE pointer, 256-byte aligned,
- * at least the planned size. hip_streams: HOST array of n_streams hipStream_t values, all
+ * at least the planned size. hip_streams: HOST array of n_streams DISTINCT hipStream_t values, all
  * on the current device, n_streams >= the scheduled stream count (NG_ENOMEM otherwise).
  * Builds the task table: kernel, launch geometry and argument block with resolved device
  * addresses for every node. */

@@ -74,11 +74,12 @@ int issue_all(ng_graph* g, bool multi) {
     return NG_OK;
 }
 
-int capture_one(ng_graph* g, bool multi, int slot) {
+// Single-stream record: pre-run the task table on the origin stream under stream capture.
+int capture_single(ng_graph* g, int slot) {
     Runtime& rt = *g->rt;
     hipStream_t origin = rt.streams[0];
     NG_HIP(hipStreamBeginCapture(origin, hipStreamCaptureModeThreadLocal));
-    int rc = issue_all(g, multi);
+    int rc = issue_all(g, false);
     hipGraph_t graph = nullptr;
     hipError_t e = hipStreamEndCapture(origin, &graph);        // always end the capture, even after a failure
     if (rc) {
@@ -87,6 +88,44 @@ int capture_one(ng_graph* g, bool multi, int slot) {
     }
     if (e != hipSuccess) return g->fail(NG_EHIP, "hipStreamEndCapture failed: %s", hipGetErrorString(e));
     rt.graph[slot] = graph;
+    NG_HIP(hipGraphInstantiate(&rt.exec[slot], graph, nullptr, nullptr, 0));
+    return NG_OK;
+}
+
+// Multi-stream record. The library already knows everything a capture of the pre-run
+// would discover, so the graph is written down directly: one kernel node per task, an
+// edge from the previous task of the same stream (FIFO order within a stream) and an
+// edge for every planned event wait (Lambda). This is node for node and edge for edge
+// the graph that capturing issue_all(multi = true) describes; fork/join scaffolding has
+// no counterpart because it carries no dependency.
+int record_multi(ng_graph* g, int slot) {
+    Runtime& rt = *g->rt;
+    const Schedule& sc = g->sched;
+    const int n = (int)g->nodes.size();
+    hipGraph_t graph = nullptr;
+    NG_HIP(hipGraphCreate(&graph, 0));
+    rt.graph[slot] = graph;
+    std::vector<hipGraphNode_t> node(n, nullptr);
+    std::vector<int> last_on_stream(sc.n_streams, -1);
+    for (int v : sc.order) {
+        const Task& t = g->tasks[v];
+        const int st = sc.stream_of[v];
+        if (!t.fn) continue;                                   // input: no task, nothing to order
+        std::vector<hipGraphNode_t> deps;
+        if (last_on_stream[st] >= 0) deps.push_back(node[last_on_stream[st]]);
+        for (int u : sc.waits[v])
+            if (node[u]) deps.push_back(node[u]);
+        void* args[1] = {const_cast<unsigned char*>(t.args)};
+        hipKernelNodeParams kp{};
+        kp.func = const_cast<void*>(t.fn);
+        kp.gridDim = dim3(t.grid[0], t.grid[1], t.grid[2]);
+        kp.blockDim = dim3(t.block[0], t.block[1], t.block[2]);
+        kp.sharedMemBytes = t.lds_bytes;
+        kp.kernelParams = args;
+        kp.extra = nullptr;
+        NG_HIP(hipGraphAddKernelNode(&node[v], graph, deps.empty() ? nullptr : deps.data(), deps.size(), &kp));
+        last_on_stream[st] = v;
+    }
     NG_HIP(hipGraphInstantiate(&rt.exec[slot], graph, nullptr, nullptr, 0));
     return NG_OK;
 }
@@ -125,6 +164,10 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
         return g->fail(NG_ENOMEM, "ng_bind: arena has %zu bytes, the plan needs %zu", arena_bytes, g->arena_bytes);
     if (n_streams < g->sched.n_streams)
         return g->fail(NG_ENOMEM, "ng_bind: %d streams given, the schedule uses %d", n_streams, g->sched.n_streams);
+    for (int a = 0; a < g->sched.n_streams; ++a)
+        for (int b = a + 1; b < g->sched.n_streams; ++b)
+            if (hip_streams[a] == hip_streams[b])
+                return g->fail(NG_EINVAL, "ng_bind: streams %d and %d are the same handle; the schedule needs distinct streams", a, b);
     hipPointerAttribute_t attr;
     if (hipPointerGetAttributes(&attr, arena) != hipSuccess || attr.type != hipMemoryTypeDevice) {
         (void)hipGetLastError();
@@ -160,8 +203,8 @@ int ng_capture(ng_graph* g) {
         if (rt.exec[i]) (void)hipGraphExecDestroy(rt.exec[i]), rt.exec[i] = nullptr;
         if (rt.graph[i]) (void)hipGraphDestroy(rt.graph[i]), rt.graph[i] = nullptr;
     }
-    if (int rc = capture_one(g, true, 0)) return rc;
-    if (int rc = capture_one(g, false, 1)) return rc;
+    if (int rc = record_multi(g, 0)) return rc;
+    if (int rc = capture_single(g, 1)) return rc;
     // the pre-run itself: execute the recorded schedule once so that every kernel is loaded
     NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
     NG_HIP(hipStreamSynchronize(rt.streams[0]));

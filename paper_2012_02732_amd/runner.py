@@ -7,10 +7,31 @@ capture, replay and all kernels - runs inside libnimble_graph.so.
 """
 from __future__ import annotations
 
+import ctypes as C
+
 import numpy as np
 import torch
 
 from . import binding as B
+
+# torch hands out streams from a pool of 32 per device, so asking it for more returns the
+# same handle twice; wide DAGs need more distinct streams than that. Streams are therefore
+# created straight from the HIP runtime torch has already loaded.
+_hip = C.CDLL("libamdhip64.so.7")
+_hip.hipStreamCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
+_hip.hipStreamDestroy.argtypes = [C.c_void_p]
+_HIP_STREAM_NON_BLOCKING = 1
+
+
+def _new_streams(n):
+    out = []
+    for _ in range(n):
+        h = C.c_void_p()
+        rc = _hip.hipStreamCreateWithFlags(C.byref(h), _HIP_STREAM_NON_BLOCKING)
+        if rc != 0 or not h.value:
+            raise RuntimeError(f"hipStreamCreateWithFlags failed with {rc}")
+        out.append(h.value)
+    return out
 
 _OPS = {"conv1x1": B.NG_OP_CONV1X1, "dwconv": B.NG_OP_DWCONV, "conv3x3": B.NG_OP_CONV3X3,
         "bn_act": B.NG_OP_BN_ACT, "relu": B.NG_OP_RELU, "add_n": B.NG_OP_ADD_N,
@@ -67,6 +88,9 @@ class GraphRunner:
                 torch.cuda.synchronize(self.device)
             B.ng_destroy(self.g)
             self.g = None
+            for h in self.streams:
+                _hip.hipStreamDestroy(h)
+            self.streams = []
 
     def __del__(self):
         try:
@@ -91,9 +115,9 @@ class GraphRunner:
         self.arena = torch.zeros(nbytes + 256, dtype=torch.uint8, device=self.device)
         base = (self.arena.data_ptr() + 255) // 256 * 256
         with torch.cuda.device(self.device):
-            self.streams = [torch.cuda.Stream(device=self.device) for _ in range(sched["n_streams"])]
+            self.streams = _new_streams(sched["n_streams"])
         torch.cuda.synchronize(self.device)
-        B.ng_bind(self.g, base, nbytes, [s.cuda_stream for s in self.streams])
+        B.ng_bind(self.g, base, nbytes, self.streams)
         self.set_input(self.workload.input)
         B.ng_capture(self.g)
         return sched

@@ -208,3 +208,16 @@ def test_bind_rejects_bad_resources_without_a_gpu():
     assert _code(B.ng_bind, g, host, need, [0]) == B.NG_EINVAL                      # host memory is not an arena
     assert B.ng_tensor_ptr(g, 0) == 0
     B.ng_destroy(g)
+
+
+def test_bind_rejects_duplicate_stream_handles():
+    g = _g_with_input()
+    a = B.ng_add_node(g, B.NG_OP_RELU, B.ng_op_params(), [0], [])
+    b = B.ng_add_node(g, B.NG_OP_RELU, B.ng_op_params(), [0], [])
+    B.ng_add_node(g, B.NG_OP_ADD_N, B.ng_op_params(), [a, b], [])
+    B.ng_schedule(g)
+    assert B.ng_schedule_sizes(g)["n_streams"] == 2
+    need = B.ng_plan_memory(g)
+    assert _code(B.ng_bind, g, 4096, need, [0x1000, 0x1000]) == B.NG_EINVAL
+    assert "same handle" in B.ng_last_error(g)
+    B.ng_destroy(g)
