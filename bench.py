@@ -130,7 +130,7 @@ def main():
     k2 = max(20, args.steps // 5)
     modes = {}
     for name, mode in (("graph_single", B.NG_MODE_GRAPH_SINGLE), ("eager_single", B.NG_MODE_EAGER_SINGLE),
-                       ("eager_multi", B.NG_MODE_EAGER_MULTI)):
+                       ("eager_multi", B.NG_MODE_EAGER_MULTI), ("device_resident", B.NG_MODE_DEVICE_RESIDENT)):
         _, l2 = time_mode(runner, B, mode, k2, 5)
         modes[name] = statistics.median(l2)
     thr = throughput(runner, B, B.NG_MODE_GRAPH_MULTI, max(50, args.steps // 2))

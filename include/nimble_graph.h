@@ -171,13 +171,27 @@ enum {
     NG_MODE_GRAPH_MULTI = 0,  /* captured multi-stream graph, one hipGraphLaunch (default) */
     NG_MODE_GRAPH_SINGLE = 1, /* captured single-stream graph */
     NG_MODE_EAGER_SINGLE = 2, /* task table launched kernel by kernel on the origin stream */
-    NG_MODE_EAGER_MULTI = 3   /* task table launched on the assigned streams with real events */
+    NG_MODE_EAGER_MULTI = 3,  /* task table launched on the assigned streams with real events */
+    NG_MODE_DEVICE_RESIDENT = 4 /* one launch; persistent workgroups walk the recorded schedule themselves:
+                                   a stream = a gang of workgroups serving its tasks in FIFO order, an event =
+                                   a completion counter in device memory (record = release add, wait = poll +
+                                   acquire). Raw submission of the task schedule (Section 4.1) without the
+                                   command processor between dependent tasks. */
 };
 int ng_replay_mode(ng_graph* g, int mode);
 /* Asynchronous: enqueue one inference on the origin stream (hip_streams[0]). */
 int ng_replay(ng_graph* g);
 /* Wait until the origin stream is idle. */
 int ng_sync(ng_graph* g);
+
+/* Device-resident replay settings. workgroups_per_cu: resident workgroups per compute unit
+ * (0 = automatic; only before ng_capture). spin_limit: polls after which a waiting workgroup
+ * gives up (0 = default, a few seconds); every wait in the resident kernel is bounded by it.
+ * When a wait gives up, all workgroups leave, ng_sync returns NG_EHIP and the next replay
+ * starts from clean counters. */
+int ng_resident_config(ng_graph* g, int workgroups_per_cu, unsigned spin_limit);
+/* Layout chosen at ng_capture: resident workgroups and total (workgroup, task) entries. */
+int ng_resident_sizes(const ng_graph* g, int* n_workgroups, int* n_entries);
 
 /* Isolated duration of one task in microseconds: the kernel is launched alone `reps`
  * times on the origin stream, each launch timed by the device's own start/stop

@@ -15,7 +15,7 @@ NG_MAX_PREDS = 8
 NG_OK, NG_EINVAL, NG_ESHAPE, NG_ESTATE, NG_ENOMEM, NG_EHIP = 0, -1, -2, -3, -4, -5
 (NG_OP_INPUT, NG_OP_CONV1X1, NG_OP_DWCONV, NG_OP_CONV3X3, NG_OP_BN_ACT, NG_OP_RELU, NG_OP_ADD_N,
  NG_OP_CONCAT, NG_OP_POOL, NG_OP_GLOBAL_AVGPOOL, NG_OP_FC) = range(11)
-NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_EAGER_SINGLE, NG_MODE_EAGER_MULTI = range(4)
+NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_EAGER_SINGLE, NG_MODE_EAGER_MULTI, NG_MODE_DEVICE_RESIDENT = range(5)
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnimble_graph.so")
 
@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnimble_g
 SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_output", "ng_num_nodes",
            "ng_node_shape", "ng_schedule", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
            "ng_plan_memory", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
-           "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_time_task",
+           "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
+           "ng_resident_sizes", "ng_time_task",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
 
 
@@ -60,6 +61,8 @@ _sig = {
     "ng_replay_mode": (_I, [_P, _I]),
     "ng_replay": (_I, [_P]),
     "ng_sync": (_I, [_P]),
+    "ng_resident_config": (_I, [_P, _I, C.c_uint]),
+    "ng_resident_sizes": (_I, [_P, _IP, _IP]),
     "ng_time_task": (_I, [_P, _I, _I, _FP]),
     "ng_task_kernel": (C.c_char_p, [_P, _I]),
     "ng_task_work": (_I, [_P, _I, _DP, _DP]),
@@ -203,6 +206,16 @@ def ng_replay(g):
 
 def ng_sync(g):
     check(g, lib.ng_sync(g))
+
+
+def ng_resident_config(g, workgroups_per_cu=0, spin_limit=0):
+    check(g, lib.ng_resident_config(g, workgroups_per_cu, spin_limit))
+
+
+def ng_resident_sizes(g):
+    a, b = C.c_int(), C.c_int()
+    check(g, lib.ng_resident_sizes(g, C.byref(a), C.byref(b)))
+    return a.value, b.value
 
 
 def ng_time_task(g, node_id, reps) -> float:

@@ -1,0 +1,133 @@
+// Device-side records shared by the kernels and the runtime (not part of the C ABI).
+#pragma once
+
+#include <cstdint>
+
+#include "nimble_graph.h"
+
+namespace ng {
+
+// One id per compiled kernel body. A task = (kernel id, argument block, number of tiles);
+// a tile is the share of one 256-thread workgroup.
+enum Kid : int {
+    KID_NONE = 0,
+    KID_BN, KID_BN_V4, KID_ADD, KID_ADD_V4, KID_CONCAT, KID_CONCAT_V4, KID_POOL,
+    KID_DW_K3S1, KID_DW_K3S2, KID_DW_K5S1, KID_DW_K5S2, KID_GAP, KID_FC_GEMV,
+    KID_PW_32, KID_PW_64, KID_C3_T16S1, KID_C3_T16S2, KID_C3_T8S1, KID_C3_T8S2,
+    KID_COUNT
+};
+
+constexpr int kBlock = 256;          // threads per workgroup, every kernel
+constexpr int kArgBytes = 256;       // size of the per-task argument block
+
+// ---- argument blocks (plain data, <= kArgBytes) ---------------------------------------
+struct BnArgs {
+    const float* x;
+    float* y;
+    const float* gamma;   // nullptr => plain ReLU
+    const float* beta;
+    const float* mean;
+    const float* var;
+    float eps;
+    int relu;
+    int C, HW;
+    int total;            // elements
+};
+
+struct AddArgs {
+    const float* x[NG_MAX_PREDS];
+    float* y;
+    int k;
+    int total;
+};
+
+struct ConcatArgs {
+    const float* x[NG_MAX_PREDS];
+    float* y;
+    int cin[NG_MAX_PREDS];     // channel count of input j
+    int lo[NG_MAX_PREDS];      // first channel taken from input j
+    int first[NG_MAX_PREDS];   // first output channel of block j
+    int k;
+    int C, HW;                 // output channels, pixels per plane
+    int total;
+};
+
+struct PoolArgs {
+    const float* x;
+    float* y;
+    int H, W, Ho, Wo;
+    int stride, pad, mode;     // mode 0 max, 1 avg
+    int total;                 // output elements
+};
+
+struct DwArgs {
+    const float* x;
+    const float* w;            // [C][K][K]
+    float* y;
+    int C, H, W, Ho, Wo;
+    int total;                 // output elements
+};
+
+struct GapArgs {
+    const float* x;
+    float* y;
+    int HW, planes;
+};
+
+struct FcArgs {
+    const float* x;            // [N][Cin]
+    const float* w;            // [Cout][Cin]
+    const float* b;            // [Cout]
+    float* y;                  // [N][Cout]
+    int N, Cin, Cout;
+};
+
+struct PwArgs {
+    const float* x;            // [N][Cin][HW]
+    const float* w;            // [Cout][Cin]
+    const float* bias;         // [Cout] or nullptr
+    float* y;                  // [N][Cout][HW]
+    int Cin, Cout, HW, cols;   // cols = N * HW
+    int tiles_n;               // tiles along the column (pixel) axis
+};
+
+struct C3Args {
+    const float* x;            // [N][Cin][H][W]
+    const float* w;            // [Cout][Cin][3][3]
+    float* y;                  // [N][Cout][Ho][Wo]
+    int Cin, Cout, H, W, Ho, Wo;
+    int pad;
+    int tiles_x;               // pixel tiles along W
+    int tiles_xy;              // pixel tiles per image
+    int co_groups;             // channel groups (workgroups along Cout)
+};
+
+// ---- device-resident replay: the task schedule as data in device memory -------------------
+struct DevTask {
+    int kid;
+    int ntiles;
+    int n_parents;
+    int pad_;
+    int parent[NG_MAX_PREDS];        // tasks whose completion this task waits for
+    unsigned need[NG_MAX_PREDS];     // completions parent j publishes per replay
+    alignas(16) unsigned char args[kArgBytes];
+};
+
+struct DevEntry {                    // one task in one workgroup's list
+    int task;
+    int tile_begin;
+    int tile_step;
+    int pad_;
+};
+
+struct DevPlan {
+    const DevTask* tasks;            // [n_nodes]
+    const DevEntry* entries;         // concatenated per-workgroup lists, each in ascending task id
+    const int* wg_first;             // [n_wg + 1] offsets into entries
+    unsigned* done;                  // [n_nodes] completion counters, never reset between replays
+    int* error_dev;                  // != 0 once any wait ran out of spins
+    int* error_host;                 // same value in pinned host memory, for the host to read
+    unsigned spin_limit;
+};
+
+}  // namespace ng

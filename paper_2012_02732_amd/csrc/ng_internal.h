@@ -11,6 +11,7 @@
 
 namespace ng {
 
+constexpr unsigned kDefaultSpinLimit = 1u << 22;     // a few seconds of polling
 enum Phase { BUILDING = 0, SCHEDULED = 1, PLANNED = 2, BOUND = 3, CAPTURED = 4 };
 
 struct Shape {
@@ -42,12 +43,15 @@ struct Schedule {
     std::vector<int> order;
     std::vector<std::vector<int>> waits;       // per consumer, producers ascending
     std::vector<int> fork, join;
+    std::vector<char> solo;                    // node is comparable with every other node (no task can run beside it)
 };
 
 // One entry of the task table: everything a launch needs, resolved ahead of time.
 struct Task {
-    const void* fn = nullptr;                  // host-side kernel handle
+    const void* fn = nullptr;                  // host-side handle of the stand-alone kernel
     const char* name = "";
+    int kid = 0;                               // kernel id (ng_device.h)
+    long ntiles = 0;                           // workgroup-sized shares of the task
     unsigned grid[3] = {1, 1, 1};
     unsigned block[3] = {1, 1, 1};
     unsigned lds_bytes = 0;
@@ -68,6 +72,8 @@ struct ng_graph {
     std::vector<ng::Task> tasks;
     ng::Runtime* rt = nullptr;
     int mode = NG_MODE_GRAPH_MULTI;
+    int resident_wg_per_cu = 0;                          // 0 = pick automatically
+    unsigned resident_spin_limit = ng::kDefaultSpinLimit; // polls before a wait gives up
     std::string err;
 
     int fail(int code, const char* fmt, ...) {
@@ -86,6 +92,7 @@ namespace ng {
 void compute_schedule(int n, const std::vector<std::pair<int, int>>& edges, Schedule& out);
 // ng_kernels.hip: fill the launch descriptor of node v (addresses resolved against `arena`).
 int build_task(ng_graph* g, int v, char* arena, Task& t);
+const void* resident_kernel_handle();
 // ng_runtime.hip
 void destroy_runtime(ng_graph* g);
 }  // namespace ng

@@ -11,7 +11,9 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstring>
 
+#include "ng_device.h"
 #include "ng_internal.h"
 
 namespace ng {
@@ -26,6 +28,15 @@ struct Runtime {
     hipGraph_t graph[2] = {nullptr, nullptr};
     hipGraphExec_t exec[2] = {nullptr, nullptr};
     hipEvent_t t_start = nullptr, t_stop = nullptr;
+    // device-resident replay
+    DevPlan plan{};
+    void* d_tasks = nullptr;
+    void* d_entries = nullptr;
+    void* d_wg_first = nullptr;
+    int* h_error = nullptr;                // pinned host memory
+    int n_wg = 0, n_entries = 0;
+    unsigned epoch = 0;
+    bool counters_dirty = false;
 };
 
 namespace {
@@ -130,6 +141,114 @@ int record_multi(ng_graph* g, int slot) {
     return NG_OK;
 }
 
+// Device-resident replay: turn the schedule into per-workgroup task lists.
+//   * stream s is served by a gang of workgroups that all sit on XCD (s mod 8) - workgroup w
+//     of a 1-D grid runs on XCD (w mod 8) - so consecutive tasks of a stream find their
+//     inputs in that XCD's L2;
+//   * a task is split over min(tiles, gang size) workgroups of its stream's gang; a task that
+//     no other task can run beside (comparable with every node) and that has more tiles than
+//     its gang is split over all workgroups instead;
+//   * every list is in ascending task id and a task only waits for smaller ids, so with all
+//     workgroups resident no wait can depend on itself;
+//   * a task waits for every E' parent (same stream or not): inside the resident kernel FIFO
+//     order alone does not order two workgroups of a gang.
+int build_resident(ng_graph* g) {
+    Runtime& rt = *g->rt;
+    const Schedule& sc = g->sched;
+    const int n = (int)g->nodes.size();
+    int dev = 0, cus = 0, per_cu = 0;
+    NG_HIP(hipGetDevice(&dev));
+    NG_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    NG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel_handle(), kBlock, 0));
+    if (per_cu < 1 || cus < 8) return g->fail(NG_EHIP, "device-resident replay: kernel does not fit (%d per CU, %d CUs)", per_cu, cus);
+    per_cu = std::min(per_cu, g->resident_wg_per_cu > 0 ? g->resident_wg_per_cu : 2);
+    const int n_wg = cus * per_cu / 8 * 8;
+    const int per_xcd = n_wg / 8;
+    const int slots = (sc.n_streams + 7) / 8;
+    const int gang = std::max(1, per_xcd / slots);
+    const int max_slots = per_xcd / gang;
+    auto gang_wg = [&](int stream, int j) { return (stream % 8) + 8 * (((stream / 8) % max_slots) * gang + j); };
+
+    std::vector<DevTask> tasks(n);
+    std::vector<std::vector<DevEntry>> lists(n_wg);
+    std::vector<unsigned> parts(n, 0);
+    for (int v = 0; v < n; ++v) {
+        const Task& t = g->tasks[v];
+        DevTask& d = tasks[v];
+        std::memset(&d, 0, sizeof d);
+        if (!t.fn) continue;
+        d.kid = t.kid;
+        d.ntiles = (int)t.ntiles;
+        std::memcpy(d.args, t.args, sizeof t.args);
+        const bool wide = sc.solo[v] && t.ntiles > gang;
+        const int p = (int)std::min<long>(t.ntiles, wide ? n_wg : gang);
+        parts[v] = (unsigned)p;
+        for (int j = 0; j < p; ++j) lists[wide ? j : gang_wg(sc.stream_of[v], j)].push_back(DevEntry{v, j, p, 0});
+    }
+    for (auto& e : sc.meg) {
+        if (!g->tasks[e.first].fn || !g->tasks[e.second].fn) continue;
+        DevTask& d = tasks[e.second];
+        if (d.n_parents >= NG_MAX_PREDS) return g->fail(NG_EINVAL, "device-resident replay: node %d has too many parents", e.second);
+        d.parent[d.n_parents] = e.first;
+        d.need[d.n_parents] = parts[e.first];
+        ++d.n_parents;
+    }
+    std::vector<DevEntry> entries;
+    std::vector<int> wg_first(n_wg + 1, 0);
+    for (int w = 0; w < n_wg; ++w) {
+        wg_first[w] = (int)entries.size();
+        entries.insert(entries.end(), lists[w].begin(), lists[w].end());
+    }
+    wg_first[n_wg] = (int)entries.size();
+    if (entries.empty()) entries.push_back(DevEntry{0, 0, 1, 0});   // keeps the allocation non-empty; never read
+
+    unsigned* d_done = nullptr;
+    int* d_error = nullptr;
+    NG_HIP(hipMalloc(&rt.d_tasks, tasks.size() * sizeof(DevTask)));
+    NG_HIP(hipMalloc(&rt.d_entries, entries.size() * sizeof(DevEntry)));
+    NG_HIP(hipMalloc(&rt.d_wg_first, wg_first.size() * sizeof(int)));
+    NG_HIP(hipMalloc(&d_done, (size_t)n * sizeof(unsigned)));
+    NG_HIP(hipMalloc(&d_error, sizeof(int)));
+    NG_HIP(hipHostMalloc(reinterpret_cast<void**>(&rt.h_error), sizeof(int), hipHostMallocDefault));
+    *rt.h_error = 0;
+    NG_HIP(hipMemcpy(rt.d_tasks, tasks.data(), tasks.size() * sizeof(DevTask), hipMemcpyHostToDevice));
+    NG_HIP(hipMemcpy(rt.d_entries, entries.data(), entries.size() * sizeof(DevEntry), hipMemcpyHostToDevice));
+    NG_HIP(hipMemcpy(rt.d_wg_first, wg_first.data(), wg_first.size() * sizeof(int), hipMemcpyHostToDevice));
+    NG_HIP(hipMemset(d_done, 0, (size_t)n * sizeof(unsigned)));
+    NG_HIP(hipMemset(d_error, 0, sizeof(int)));
+    rt.plan.tasks = static_cast<const DevTask*>(rt.d_tasks);
+    rt.plan.entries = static_cast<const DevEntry*>(rt.d_entries);
+    rt.plan.wg_first = static_cast<const int*>(rt.d_wg_first);
+    rt.plan.done = d_done;
+    rt.plan.error_dev = d_error;
+    rt.plan.error_host = rt.h_error;
+    rt.plan.spin_limit = g->resident_spin_limit;
+    rt.n_wg = n_wg;
+    rt.n_entries = wg_first[n_wg];
+    rt.epoch = 0;
+    rt.counters_dirty = false;
+    return NG_OK;
+}
+
+int launch_resident(ng_graph* g) {
+    Runtime& rt = *g->rt;
+    if (!rt.d_tasks) return g->fail(NG_ESTATE, "device-resident replay was not prepared");
+    hipStream_t origin = rt.streams[0];
+    if (rt.counters_dirty) {                                   // a timed-out replay left partial counts behind
+        NG_HIP(hipStreamSynchronize(origin));
+        NG_HIP(hipMemset(rt.plan.done, 0, g->nodes.size() * sizeof(unsigned)));
+        NG_HIP(hipMemset(rt.plan.error_dev, 0, sizeof(int)));
+        *rt.h_error = 0;
+        rt.epoch = 0;
+        rt.counters_dirty = false;
+    }
+    rt.plan.spin_limit = g->resident_spin_limit;
+    unsigned epoch = ++rt.epoch;
+    void* args[2] = {&rt.plan, &epoch};
+    NG_HIP(hipLaunchKernel(resident_kernel_handle(), dim3(rt.n_wg), dim3(kBlock), args, 0, origin));
+    return NG_OK;
+}
+
 }  // namespace
 
 void destroy_runtime(ng_graph* g) {
@@ -145,6 +264,12 @@ void destroy_runtime(ng_graph* g) {
     if (rt->fork_event) (void)hipEventDestroy(rt->fork_event);
     if (rt->t_start) (void)hipEventDestroy(rt->t_start);
     if (rt->t_stop) (void)hipEventDestroy(rt->t_stop);
+    if (rt->d_tasks) (void)hipFree(rt->d_tasks);
+    if (rt->d_entries) (void)hipFree(rt->d_entries);
+    if (rt->d_wg_first) (void)hipFree(rt->d_wg_first);
+    if (rt->plan.done) (void)hipFree(rt->plan.done);
+    if (rt->plan.error_dev) (void)hipFree(rt->plan.error_dev);
+    if (rt->h_error) (void)hipHostFree(rt->h_error);
     delete rt;
     g->rt = nullptr;
 }
@@ -205,6 +330,8 @@ int ng_capture(ng_graph* g) {
     }
     if (int rc = record_multi(g, 0)) return rc;
     if (int rc = capture_single(g, 1)) return rc;
+    if (!rt.d_tasks)
+        if (int rc = build_resident(g)) return rc;
     // the pre-run itself: execute the recorded schedule once so that every kernel is loaded
     NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
     NG_HIP(hipStreamSynchronize(rt.streams[0]));
@@ -219,7 +346,7 @@ void* ng_tensor_ptr(const ng_graph* g, int id) {
 
 int ng_replay_mode(ng_graph* g, int mode) {
     if (!g) return NG_EINVAL;
-    if (mode < NG_MODE_GRAPH_MULTI || mode > NG_MODE_EAGER_MULTI) return g->fail(NG_EINVAL, "ng_replay_mode: unknown mode %d", mode);
+    if (mode < NG_MODE_GRAPH_MULTI || mode > NG_MODE_DEVICE_RESIDENT) return g->fail(NG_EINVAL, "ng_replay_mode: unknown mode %d", mode);
     g->mode = mode;
     return NG_OK;
 }
@@ -232,7 +359,8 @@ int ng_replay(ng_graph* g) {
         case NG_MODE_GRAPH_MULTI: NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0])); return NG_OK;
         case NG_MODE_GRAPH_SINGLE: NG_HIP(hipGraphLaunch(rt.exec[1], rt.streams[0])); return NG_OK;
         case NG_MODE_EAGER_SINGLE: return issue_all(g, false);
-        default: return issue_all(g, true);
+        case NG_MODE_EAGER_MULTI: return issue_all(g, true);
+        default: return launch_resident(g);
     }
 }
 
@@ -240,6 +368,30 @@ int ng_sync(ng_graph* g) {
     if (!g) return NG_EINVAL;
     if (g->phase < BOUND) return g->fail(NG_ESTATE, "ng_sync: call ng_bind first");
     NG_HIP(hipStreamSynchronize(g->rt->streams[0]));
+    if (g->rt->h_error && *g->rt->h_error != 0) {
+        const int task = *g->rt->h_error - 1;
+        g->rt->counters_dirty = true;
+        return g->fail(NG_EHIP, "device-resident replay: the wait before task %d ran out of spins; outputs are incomplete", task);
+    }
+    return NG_OK;
+}
+
+int ng_resident_config(ng_graph* g, int workgroups_per_cu, unsigned spin_limit) {
+    if (!g) return NG_EINVAL;
+    if (workgroups_per_cu < 0 || workgroups_per_cu > 8) return g->fail(NG_EINVAL, "ng_resident_config: workgroups_per_cu must be 0..8");
+    if (workgroups_per_cu > 0) {
+        if (g->phase >= CAPTURED) return g->fail(NG_ESTATE, "ng_resident_config: the gang layout is fixed at ng_capture");
+        g->resident_wg_per_cu = workgroups_per_cu;
+    }
+    g->resident_spin_limit = spin_limit ? spin_limit : kDefaultSpinLimit;
+    return NG_OK;
+}
+
+int ng_resident_sizes(const ng_graph* g, int* n_workgroups, int* n_entries) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_resident_sizes: call ng_capture first");
+    if (n_workgroups) *n_workgroups = g->rt->n_wg;
+    if (n_entries) *n_entries = g->rt->n_entries;
     return NG_OK;
 }
 

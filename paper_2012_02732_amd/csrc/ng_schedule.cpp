@@ -113,6 +113,14 @@ void compute_schedule(int n, const std::vector<std::pair<int, int>>& raw_edges, 
         for (int v = u + 1; v < n; ++v)
             if (reach.get(u, v)) anc.set(v, u);
 
+    s.solo.assign(n, 0);
+    for (int v = 0; v < n; ++v) {
+        int comparable = 0;
+        for (int w = 0; w < reach.words; ++w)
+            comparable += __builtin_popcountll(reach.row(v)[w]) + __builtin_popcountll(anc.row(v)[w]);
+        s.solo[v] = comparable == n - 1;
+    }
+
     // Step 1: (u, v) stays iff no node lies strictly between u and v.
     for (auto& e : edges) {
         const uint64_t* a = reach.row(e.first);

@@ -119,7 +119,8 @@ def test_fc(n, cin, cout):
     check_all_nodes(single_op(build))
 
 
-ALL_MODES = (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_EAGER_SINGLE, B.NG_MODE_EAGER_MULTI)
+ALL_MODES = (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_EAGER_SINGLE, B.NG_MODE_EAGER_MULTI,
+             B.NG_MODE_DEVICE_RESIDENT)
 
 
 @pytest.mark.parametrize("name", ["tiny_cell", "chain50", "random200", "nasnet_style"])
@@ -128,7 +129,8 @@ def test_config_every_tensor_every_mode(name):
 
 
 def test_config_inception_batch1():
-    check_all_nodes(workloads.make("inception_style"), (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_EAGER_MULTI))
+    check_all_nodes(workloads.make("inception_style"),
+                    (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_EAGER_MULTI, B.NG_MODE_DEVICE_RESIDENT))
 
 
 def test_config_inception_batch32_sampled_images():
@@ -140,6 +142,9 @@ def test_config_inception_batch32_sampled_images():
     try:
         got = r.run()[w.outputs[0]]
         assert got.shape == (32, 1000, 1, 1) and np.isfinite(got).all()
+        r.arena.zero_()
+        r.set_input(w.input)
+        assert np.array_equal(r.run(mode=B.NG_MODE_DEVICE_RESIDENT)[w.outputs[0]], got)
         w1 = workloads.make("inception_style", batch=1)
         for w_a, w_b in zip(w.nodes, w1.nodes):                      # same seed -> same weights
             assert all(np.array_equal(p, q) for p, q in zip(w_a.weights, w_b.weights))
@@ -182,5 +187,63 @@ def test_isolated_task_times_and_critical_path():
         total, path = B.ng_critical_path(r.g, t)
         assert path[0] == 0 and path[-1] == 7 and total <= sum(t) + 1e-3
         assert B.ng_task_kernel(r.g, 1).startswith("conv1x1") and B.ng_task_kernel(r.g, 0) == ""
+    finally:
+        r.close()
+
+
+@pytest.mark.parametrize("shape", [(1, 5, 7, 9), (2, 24, 17, 17)])
+def test_device_resident_single_ops(shape):
+    def build(b):
+        x = b.input(*shape)
+        a = b.bn_act(x, relu=True)
+        c = b.conv1x1(a, 19)
+        d = b.conv3x3(x, 19, 1, 1)
+        e = b.dwconv(d, 5, 1)
+        f = b.add_n([c, d, e])
+        p = b.pool(f, "avg", 2, 1)
+        q = b.concat([c, d])
+        b.fc(b.global_avgpool(q), 11)
+        b.relu(p)
+    check_all_nodes(single_op(build), (B.NG_MODE_DEVICE_RESIDENT, B.NG_MODE_GRAPH_MULTI))
+
+
+def test_device_resident_repeats_and_new_inputs():
+    w = workloads.make("nasnet_style")
+    r = GraphRunner(w, DEV)
+    r.prepare()
+    try:
+        n_wg, n_entries = B.ng_resident_sizes(r.g)
+        assert n_wg >= 256 and n_wg % 8 == 0 and n_entries >= len(w.nodes) - 1
+        out_id = w.outputs[0]
+        ref_graph = r.run(mode=B.NG_MODE_GRAPH_MULTI)[out_id].copy()
+        for i in range(100):                                        # counters are never reset between replays
+            assert np.array_equal(r.run(mode=B.NG_MODE_DEVICE_RESIDENT)[out_id], ref_graph), i
+        rng = np.random.default_rng(3)
+        x = rng.standard_normal(w.input.shape).astype(np.float32)
+        got = r.run(x, mode=B.NG_MODE_DEVICE_RESIDENT)[out_id]
+        assert rel_err(got, forward(w, x=x)[out_id]) <= TOL
+    finally:
+        r.close()
+
+
+def test_device_resident_wait_gives_up_and_recovers():
+    # the failure is forced from the host: with a spin limit of 1 every unsatisfied wait gives
+    # up at once, all workgroups leave normally, ng_sync reports it, the next replay is clean
+    w = workloads.make("random200")
+    r = GraphRunner(w, DEV)
+    r.prepare()
+    try:
+        good = r.run(mode=B.NG_MODE_DEVICE_RESIDENT)
+        B.ng_resident_config(r.g, 0, 1)
+        B.ng_replay(r.g)
+        with pytest.raises(B.NgError) as ei:
+            B.ng_sync(r.g)
+        assert ei.value.code == B.NG_EHIP and "ran out of spins" in str(ei.value)
+        B.ng_resident_config(r.g, 0, 0)
+        r.arena.zero_()
+        r.set_input(w.input)
+        again = r.run(mode=B.NG_MODE_DEVICE_RESIDENT)
+        for k in good:
+            assert np.array_equal(good[k], again[k])
     finally:
         r.close()
