@@ -185,13 +185,26 @@ int ng_replay(ng_graph* g);
 int ng_sync(ng_graph* g);
 
 /* Device-resident replay settings. workgroups_per_cu: resident workgroups per compute unit
- * (0 = automatic; only before ng_capture). spin_limit: polls after which a waiting workgroup
+ * (0 = automatic; only before ng_capture). xcds: number of XCDs (1, 2, 4 or 8; 0 = automatic;
+ * only before ng_capture) the streams are spread over; with 1 the whole DAG runs out of one
+ * XCD's L2 and no completion needs a device-scope fence. spin_limit: polls after which a waiting workgroup
  * gives up (0 = default, a few seconds); every wait in the resident kernel is bounded by it.
  * When a wait gives up, all workgroups leave, ng_sync returns NG_EHIP and the next replay
- * starts from clean counters. */
-int ng_resident_config(ng_graph* g, int workgroups_per_cu, unsigned spin_limit);
-/* Layout chosen at ng_capture: resident workgroups and total (workgroup, task) entries. */
-int ng_resident_sizes(const ng_graph* g, int* n_workgroups, int* n_entries);
+ * starts from clean counters. device_scope_everywhere != 0 (only before ng_capture) makes
+ * every completion a device-scope release/acquire; by default a tensor that stays on the
+ * XCD of its stream is handed over through that XCD's L2 and only the others pay for an L2
+ * write-back and invalidate. */
+int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned spin_limit, int device_scope_everywhere);
+/* Per-task timeline of device-resident replays. enable != 0 switches recording on (off for 0).
+ * If ticks is not NULL it first receives, for the last replay recorded, three device clock
+ * readings per node (HOST array of 3 * n_nodes values, 100 MHz clock, 0 for input nodes):
+ * wait for producers begins, inputs ready, all tiles of the first workgroup done. Waits for
+ * the origin stream to go idle. */
+int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks);
+/* Layout chosen at ng_capture: resident workgroups, total (workgroup, task) entries, XCDs in
+ * use, and the makespan in microseconds that the planner's cost model expects (any pointer
+ * may be NULL). */
+int ng_resident_sizes(const ng_graph* g, int* n_workgroups, int* n_entries, int* xcds, double* expected_us);
 
 /* Isolated duration of one task in microseconds: the kernel is launched alone `reps`
  * times on the origin stream, each launch timed by the device's own start/stop

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnimble_graph.so")
-SOURCES = ["ng_graph.cpp", "ng_schedule.cpp", "ng_kernels.hip", "ng_runtime.hip"]
+SOURCES = ["ng_graph.cpp", "ng_schedule.cpp", "ng_resident_plan.cpp", "ng_kernels.hip", "ng_runtime.hip"]
 
 
 def hipcc() -> str:

@@ -13,7 +13,7 @@ enum Kid : int {
     KID_NONE = 0,
     KID_BN, KID_BN_V4, KID_ADD, KID_ADD_V4, KID_CONCAT, KID_CONCAT_V4, KID_POOL,
     KID_DW_K3S1, KID_DW_K3S2, KID_DW_K5S1, KID_DW_K5S2, KID_GAP, KID_FC_GEMV,
-    KID_PW_32, KID_PW_64, KID_C3_T16S1, KID_C3_T16S2, KID_C3_T8S1, KID_C3_T8S2,
+    KID_PW_D4, KID_PW_D8, KID_PW_D16, KID_PW_64, KID_C3_T16S1, KID_C3_T16S2, KID_C3_T8S1, KID_C3_T8S2,
     KID_COUNT
 };
 
@@ -89,6 +89,9 @@ struct PwArgs {
     float* y;                  // [N][Cout][HW]
     int Cin, Cout, HW, cols;   // cols = N * HW
     int tiles_n;               // tiles along the column (pixel) axis
+    const float* wp;           // KID_PW_DIRECT: weights repacked into MFMA operand order
+    int ksteps;                // direct kernels: k steps of 4 in the packed copy (padded, multiple of 4 * chunk)
+    int mtiles;                // direct kernels: ceil(Cout / 16)
 };
 
 struct C3Args {
@@ -103,13 +106,22 @@ struct C3Args {
 };
 
 // ---- device-resident replay: the task schedule as data in device memory -------------------
+constexpr int kArgWords = 48;        // words of the argument block the resident kernel prefetches
+
 struct DevTask {
     int kid;
     int ntiles;
     int n_parents;
-    int pad_;
+    // 1: some reader of the output sits on another XCD, so the output is stored with
+    // device-scope (memory-side) stores; 0: all readers share this task's L2.
+    int release_far;
     int parent[NG_MAX_PREDS];        // tasks whose completion this task waits for
     unsigned need[NG_MAX_PREDS];     // completions parent j publishes per replay
+    // != 0: some operand was produced on another XCD; all activations of this task are then
+    // read with device-scope (memory-side) loads, and every producer of an operand stores
+    // with device-scope stores (so no operand has dirty lines in an XCD-private L2)
+    unsigned far_in;
+    unsigned pad_[3];
     alignas(16) unsigned char args[kArgBytes];
 };
 
@@ -128,6 +140,9 @@ struct DevPlan {
     int* error_dev;                  // != 0 once any wait ran out of spins
     int* error_host;                 // same value in pinned host memory, for the host to read
     unsigned spin_limit;
+    int done_stride;                 // words between two tasks' counters (spreads them over memory channels)
+    int poll_sleep;                  // 0, 1, 2: back-off between two polls (1, 4, 16 sleep units)
+    unsigned long long* trace;       // optional [n_nodes][3]: wait begins, inputs ready, tiles done (100 MHz clock)
 };
 
 }  // namespace ng

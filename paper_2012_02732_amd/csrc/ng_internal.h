@@ -8,6 +8,7 @@
 #include <vector>
 
 #include "nimble_graph.h"
+#include "ng_device.h"
 
 namespace ng {
 
@@ -59,6 +60,16 @@ struct Task {
     unsigned args_bytes = 0;
 };
 
+// Output of the device-resident planner (ng_resident_plan.cpp).
+struct ResidentPlan {
+    int n_wg = 0;                              // persistent workgroups (grid size)
+    int xcds = 0;                              // XCDs the streams are spread over
+    double est_us = 0;                         // makespan the planner's cost model expects
+    std::vector<DevTask> tasks;                // [n_nodes]
+    std::vector<DevEntry> entries;             // per-workgroup lists, concatenated
+    std::vector<int> wg_first;                 // [n_wg + 1]
+};
+
 struct Runtime;  // HIP-side state, defined in ng_runtime.hip
 
 }  // namespace ng
@@ -73,7 +84,9 @@ struct ng_graph {
     ng::Runtime* rt = nullptr;
     int mode = NG_MODE_GRAPH_MULTI;
     int resident_wg_per_cu = 0;                          // 0 = pick automatically
+    int resident_xcds = 0;                               // XCDs the resident kernel spreads over, 0 = all 8
     unsigned resident_spin_limit = ng::kDefaultSpinLimit; // polls before a wait gives up
+    bool resident_all_far = false;                       // treat every edge as crossing XCDs (device-scope fences everywhere)
     std::string err;
 
     int fail(int code, const char* fmt, ...) {
@@ -90,9 +103,14 @@ struct ng_graph {
 namespace ng {
 // ng_schedule.cpp
 void compute_schedule(int n, const std::vector<std::pair<int, int>>& edges, Schedule& out);
-// ng_kernels.hip: fill the launch descriptor of node v (addresses resolved against `arena`).
-int build_task(ng_graph* g, int v, char* arena, Task& t);
+// ng_kernels.hip: fill the launch descriptor of node v (addresses resolved against `arena`;
+// `packed` = node v's share of the library-owned constant memory, see packed_floats).
+int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t);
+size_t packed_floats(const ng_graph* g, int v);
+int pack_constants(ng_graph* g, int v, float* packed, void* stream);
 const void* resident_kernel_handle();
+// ng_resident_plan.cpp: xcds = 0 lets the cost model choose among 1, 2, 4, 8.
+int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan);
 // ng_runtime.hip
 void destroy_runtime(ng_graph* g);
 }  // namespace ng

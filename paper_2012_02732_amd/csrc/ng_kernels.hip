@@ -29,6 +29,36 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+// Access helpers. `far` is uniform per task. A far load/store is a relaxed device-scope atomic
+// access: it is served by the memory side (sc1), past the XCD-private L2, which is what makes a
+// tensor written on one XCD readable on another without flushing or invalidating either L2.
+__device__ __forceinline__ float ldg(const float* p, bool far) {
+    return far ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+}
+__device__ __forceinline__ float4 ldg4(const float* p, bool far) {
+    if (!far) return *reinterpret_cast<const float4*>(p);
+    float4 v;
+    v.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+}
+__device__ __forceinline__ void stg(float* p, float v, bool far) {
+    if (far) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+__device__ __forceinline__ void stg4(float* p, float4 v, bool far) {
+    if (!far) {
+        *reinterpret_cast<float4*>(p) = v;
+        return;
+    }
+    __hip_atomic_store(p + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // LDS floats every workgroup owns: the largest user is the conv3x3 input patch (4 x 33 x 34).
 constexpr int kSmemFloats = 4 * 33 * 34;
 
@@ -45,7 +75,7 @@ __device__ __forceinline__ void bn_coeff(const BnArgs& a, int c, float& s, float
     }
 }
 
-template <bool VEC4>
+template <bool VEC4, bool FIN, bool FOUT>
 __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*) {
     const int i = tile * kBlock + threadIdx.x;
     if (VEC4) {                                   // HW % 4 == 0: a float4 never straddles channels
@@ -53,52 +83,52 @@ __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*) {
         if (e >= a.total) return;
         float s, t;
         bn_coeff(a, (e / a.HW) % a.C, s, t);
-        float4 v = *reinterpret_cast<const float4*>(a.x + e);
+        float4 v = ldg4(a.x + e, FIN);
         v.x = fmaf(v.x, s, t), v.y = fmaf(v.y, s, t), v.z = fmaf(v.z, s, t), v.w = fmaf(v.w, s, t);
         if (a.relu) v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
-        *reinterpret_cast<float4*>(a.y + e) = v;
+        stg4(a.y + e, v, FOUT);
     } else {
         if (i >= a.total) return;
         float s, t;
         bn_coeff(a, (i / a.HW) % a.C, s, t);
-        float v = fmaf(a.x[i], s, t);
-        a.y[i] = a.relu ? fmaxf(v, 0.f) : v;
+        float v = fmaf(ldg(a.x + i, FIN), s, t);
+        stg(a.y + i, a.relu ? fmaxf(v, 0.f) : v, FOUT);
     }
 }
 
 // ------------------------------------------------------------------------------------
 // add_n: elementwise sum of k tensors, accumulated in argument order
 // ------------------------------------------------------------------------------------
-template <bool VEC4>
+template <bool VEC4, bool FIN, bool FOUT>
 __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*) {
     const int i = tile * kBlock + threadIdx.x;
     if (VEC4) {
         const int e = i * 4;
         if (e >= a.total) return;
-        float4 acc = *reinterpret_cast<const float4*>(a.x[0] + e);
+        float4 acc = ldg4(a.x[0] + e, FIN);
 #pragma unroll
         for (int j = 1; j < NG_MAX_PREDS; ++j) {
             if (j >= a.k) break;
-            const float4 v = *reinterpret_cast<const float4*>(a.x[j] + e);
+            const float4 v = ldg4(a.x[j] + e, FIN);
             acc.x += v.x, acc.y += v.y, acc.z += v.z, acc.w += v.w;
         }
-        *reinterpret_cast<float4*>(a.y + e) = acc;
+        stg4(a.y + e, acc, FOUT);
     } else {
         if (i >= a.total) return;
-        float acc = a.x[0][i];
+        float acc = ldg(a.x[0] + i, FIN);
 #pragma unroll
         for (int j = 1; j < NG_MAX_PREDS; ++j) {
             if (j >= a.k) break;
-            acc += a.x[j][i];
+            acc += ldg(a.x[j] + i, FIN);
         }
-        a.y[i] = acc;
+        stg(a.y + i, acc, FOUT);
     }
 }
 
 // ------------------------------------------------------------------------------------
 // concat: output channel block j = channels [lo_j, lo_j + cnt_j) of input j
 // ------------------------------------------------------------------------------------
-template <bool VEC4>
+template <bool VEC4, bool FIN, bool FOUT>
 __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float*) {
     const int i = tile * kBlock + threadIdx.x;
     const int e = VEC4 ? i * 4 : i;
@@ -112,59 +142,102 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
         if (q < a.k && c >= a.first[q]) base = a.x[q], cin = a.cin[q], lo = a.lo[q], first = a.first[q];
     const float* src = base + ((size_t)(n * cin + lo + c - first)) * a.HW + pix;
     if (VEC4)
-        *reinterpret_cast<float4*>(a.y + e) = *reinterpret_cast<const float4*>(src);
+        stg4(a.y + e, ldg4(src, FIN), FOUT);
     else
-        a.y[e] = *src;
+        stg(a.y + e, ldg(src, FIN), FOUT);
 }
 
 // ------------------------------------------------------------------------------------
 // pool3x3: max (out-of-bounds taps ignored) or average over the in-bounds taps
 // ------------------------------------------------------------------------------------
+// Outputs per thread of the windowed kernels: a task should fit its stream's gang in one
+// round, and one round costs one memory round trip however many loads are in flight.
+constexpr int kPoolPerThread = 1;
+
+template <bool FIN, bool FOUT>
 __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*) {
-    const int i = tile * kBlock + threadIdx.x;
-    if (i >= a.total) return;
-    const int ow = i % a.Wo, t = i / a.Wo;
-    const int oh = t % a.Ho, plane = t / a.Ho;
-    const float* src = a.x + (size_t)plane * a.H * a.W;
-    const int r0 = oh * a.stride - a.pad, c0 = ow * a.stride - a.pad;
-    float acc = a.mode == 0 ? -INFINITY : 0.f;
-    int cnt = 0;
+    constexpr int P = kPoolPerThread;
+    const int base = (tile * kBlock + threadIdx.x) * P;
+    if (base >= a.total) return;
+    // all taps of all P outputs are loaded unconditionally from clamped coordinates, so the
+    // loads are independent and in flight together; taps outside the image are masked afterwards
+    float v[P][9];
+    int r0[P], c0[P];
 #pragma unroll
-    for (int dr = 0; dr < 3; ++dr)
+    for (int p = 0; p < P; ++p) {
+        const int i = min(base + p, a.total - 1);
+        const int ow = i % a.Wo, t = i / a.Wo;
+        const int oh = t % a.Ho, plane = t / a.Ho;
+        const float* src = a.x + (size_t)plane * a.H * a.W;
+        r0[p] = oh * a.stride - a.pad, c0[p] = ow * a.stride - a.pad;
 #pragma unroll
-        for (int dc = 0; dc < 3; ++dc) {
-            const int r = r0 + dr, c = c0 + dc;
-            if (r >= 0 && r < a.H && c >= 0 && c < a.W) {
-                const float v = src[r * a.W + c];
-                acc = a.mode == 0 ? fmaxf(acc, v) : acc + v;
-                ++cnt;
+        for (int dr = 0; dr < 3; ++dr)
+#pragma unroll
+            for (int dc = 0; dc < 3; ++dc)
+                v[p][dr * 3 + dc] = ldg(src + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
+    }
+    __builtin_amdgcn_sched_barrier(0);                       // all loads are issued before the first use
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        float acc = a.mode == 0 ? -INFINITY : 0.f;
+        int cnt = 0;
+#pragma unroll
+        for (int dr = 0; dr < 3; ++dr)
+#pragma unroll
+            for (int dc = 0; dc < 3; ++dc) {
+                const int r = r0[p] + dr, c = c0[p] + dc;
+                const bool in = r >= 0 && r < a.H && c >= 0 && c < a.W;
+                if (a.mode == 0) acc = in ? fmaxf(acc, v[p][dr * 3 + dc]) : acc;
+                else acc += in ? v[p][dr * 3 + dc] : 0.f;
+                cnt += in;
             }
-        }
-    a.y[i] = a.mode == 0 ? acc : acc / (float)cnt;
+        if (base + p < a.total) stg(a.y + base + p, a.mode == 0 ? acc : acc / (float)cnt, FOUT);
+    }
 }
 
 // ------------------------------------------------------------------------------------
-// dwconv: depthwise K x K, pad K/2, stride S
+// dwconv: depthwise K x K, pad K/2, stride S; P outputs per thread
 // ------------------------------------------------------------------------------------
-template <int K, int S>
+constexpr int dw_per_thread(int k) { return 1; }
+
+template <int K, int S, bool FIN, bool FOUT>
 __device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*) {
-    const int i = tile * kBlock + threadIdx.x;
-    if (i >= a.total) return;
-    const int ow = i % a.Wo, t = i / a.Wo;
-    const int oh = t % a.Ho, plane = t / a.Ho;
-    const int c = plane % a.C;
-    const float* src = a.x + (size_t)plane * a.H * a.W;
-    const float* wt = a.w + c * K * K;
-    const int r0 = oh * S - K / 2, c0 = ow * S - K / 2;
-    float acc = 0.f;
+    constexpr int P = dw_per_thread(K);
+    const int base = (tile * kBlock + threadIdx.x) * P;
+    if (base >= a.total) return;
+    // unconditional loads from clamped coordinates (all in flight together), masked afterwards
+    float v[P][K * K], w[P][K * K];
+    int r0[P], c0[P];
 #pragma unroll
-    for (int dr = 0; dr < K; ++dr)
+    for (int p = 0; p < P; ++p) {
+        const int i = min(base + p, a.total - 1);
+        const int ow = i % a.Wo, t = i / a.Wo;
+        const int oh = t % a.Ho, plane = t / a.Ho;
+        const float* src = a.x + (size_t)plane * a.H * a.W;
+        const float* wt = a.w + (plane % a.C) * K * K;
+        r0[p] = oh * S - K / 2, c0[p] = ow * S - K / 2;
 #pragma unroll
-        for (int dc = 0; dc < K; ++dc) {
-            const int r = r0 + dr, cc = c0 + dc;
-            if (r >= 0 && r < a.H && cc >= 0 && cc < a.W) acc = fmaf(wt[dr * K + dc], src[r * a.W + cc], acc);
-        }
-    a.y[i] = acc;
+        for (int q = 0; q < K * K; ++q) w[p][q] = wt[q];
+#pragma unroll
+        for (int dr = 0; dr < K; ++dr)
+#pragma unroll
+            for (int dc = 0; dc < K; ++dc)
+                v[p][dr * K + dc] = ldg(src + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
+    }
+    __builtin_amdgcn_sched_barrier(0);                       // all loads are issued before the first use
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        float acc = 0.f;
+#pragma unroll
+        for (int dr = 0; dr < K; ++dr)
+#pragma unroll
+            for (int dc = 0; dc < K; ++dc) {
+                const int r = r0[p] + dr, cc = c0[p] + dc;
+                const bool in = r >= 0 && r < a.H && cc >= 0 && cc < a.W;
+                acc = fmaf(w[p][dr * K + dc], in ? v[p][dr * K + dc] : 0.f, acc);
+            }
+        if (base + p < a.total) stg(a.y + base + p, acc, FOUT);
+    }
 }
 
 // ------------------------------------------------------------------------------------
@@ -176,20 +249,22 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
+template <bool FIN, bool FOUT>
 __device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, float*) {
     const int lane = threadIdx.x & 63;
     const int plane = tile * (kBlock / 64) + (threadIdx.x >> 6);
     if (plane >= a.planes) return;
     const float* src = a.x + (size_t)plane * a.HW;
     float acc = 0.f;
-    for (int p = lane; p < a.HW; p += 64) acc += src[p];
+    for (int p = lane; p < a.HW; p += 64) acc += ldg(src + p, FIN);
     acc = wave_sum(acc);
-    if (lane == 0) a.y[plane] = acc / (float)a.HW;
+    if (lane == 0) stg(a.y + plane, acc / (float)a.HW, FOUT);
 }
 
 // ------------------------------------------------------------------------------------
 // fc (small batch): one wavefront per output feature; y[n][o] = <W[o], x[n]> + b[o]
 // ------------------------------------------------------------------------------------
+template <bool FIN, bool FOUT>
 __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*) {
     const int lane = threadIdx.x & 63;
     const int o = tile * (kBlock / 64) + (threadIdx.x >> 6);
@@ -201,15 +276,15 @@ __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*) 
         if ((a.Cin & 3) == 0) {
             for (int k = lane * 4; k < a.Cin; k += 256) {
                 const float4 wv = *reinterpret_cast<const float4*>(wr + k);
-                const float4 xv = *reinterpret_cast<const float4*>(xr + k);
+                const float4 xv = ldg4(xr + k, FIN);
                 acc = fmaf(wv.x, xv.x, acc), acc = fmaf(wv.y, xv.y, acc);
                 acc = fmaf(wv.z, xv.z, acc), acc = fmaf(wv.w, xv.w, acc);
             }
         } else {
-            for (int k = lane; k < a.Cin; k += 64) acc = fmaf(wr[k], xr[k], acc);
+            for (int k = lane; k < a.Cin; k += 64) acc = fmaf(wr[k], ldg(xr + k, FIN), acc);
         }
         acc = wave_sum(acc);
-        if (lane == 0) a.y[(size_t)n * a.Cout + o] = acc + a.b[o];
+        if (lane == 0) stg(a.y + (size_t)n * a.Cout + o, acc + a.b[o], FOUT);
     }
 }
 
@@ -220,12 +295,13 @@ __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*) 
 // A workgroup of four wavefronts (2 x 2) owns a TM x TN output tile; K is walked in
 // slices of KC staged through LDS (A transposed to [k][m] so both fragments read rows).
 // ------------------------------------------------------------------------------------
-template <int TM, int TN, int KC>
+template <int TM, int TN, int KC, bool FIN, bool FOUT>
 __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, float* smem) {
     constexpr int WM = TM / 2, WN = TN / 2;           // per-wavefront sub-tile
     constexpr int FM = WM / 16, FN = WN / 16;         // 16 x 16 fragments per wavefront
     constexpr int LDA = TM + 1, LDB = TN + 1;
     static_assert(KC * (LDA + LDB) <= kSmemFloats, "LDS budget");
+    static_assert(kBlock % KC == 0 && kBlock % TN == 0 && TM % (kBlock / KC) == 0 && KC % (kBlock / TN) == 0, "fill pattern");
     float* As = smem;                                 // [KC][LDA]
     float* Bs = smem + KC * LDA;                      // [KC][LDB]
 
@@ -241,22 +317,39 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
         for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     for (int k0 = 0; k0 < a.Cin; k0 += KC) {
-        // A slice: W[m0 + m][k0 + k] -> As[k][m]; consecutive threads walk k (contiguous in W)
-        for (int e = tid; e < TM * KC; e += kBlock) {
-            const int k = e % KC, m = e / KC;
-            const int gm = m0 + m, gk = k0 + k;
-            As[k * LDA + m] = (gm < a.Cout && gk < a.Cin) ? a.w[(size_t)gm * a.Cin + gk] : 0.f;
+        // A slice: W[m0 + m][k0 + k] -> As[k][m]; consecutive threads walk k (contiguous in W).
+        // Loads are unconditional from clamped indices (independent, all in flight), zeroed afterwards.
+        {
+            constexpr int RM = kBlock / KC;                       // rows covered per pass
+            const int k = tid % KC, gk = k0 + k;
+            float v[TM / RM];
+#pragma unroll
+            for (int p = 0; p < TM / RM; ++p) {
+                const int gm = m0 + tid / KC + p * RM;
+                v[p] = a.w[(size_t)min(gm, a.Cout - 1) * a.Cin + min(gk, a.Cin - 1)];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = 0; p < TM / RM; ++p) {
+                const int m = tid / KC + p * RM;
+                As[k * LDA + m] = (m0 + m < a.Cout && gk < a.Cin) ? v[p] : 0.f;
+            }
         }
         // B slice: X[k0 + k][n0 + n] -> Bs[k][n]; consecutive threads walk pixels
-        for (int e = tid; e < TN * KC; e += kBlock) {
-            const int n = e % TN, k = e / TN;
-            const int col = n0 + n, gk = k0 + k;
-            float v = 0.f;
-            if (col < a.cols && gk < a.Cin) {
-                const int img = col / a.HW, pix = col - img * a.HW;
-                v = a.x[((size_t)img * a.Cin + gk) * a.HW + pix];
+        {
+            constexpr int RK = kBlock / TN;                       // k rows covered per pass
+            const int n = tid % TN, col = n0 + n;
+            const int ccol = min(col, a.cols - 1);
+            const int img = ccol / a.HW, pix = ccol - img * a.HW;
+            const float* xc = a.x + (size_t)img * a.Cin * a.HW + pix;
+            float v[KC / RK];
+#pragma unroll
+            for (int p = 0; p < KC / RK; ++p) v[p] = ldg(xc + (size_t)min(k0 + tid / TN + p * RK, a.Cin - 1) * a.HW, FIN);
+#pragma unroll
+            for (int p = 0; p < KC / RK; ++p) {
+                const int k = tid / TN + p * RK;
+                Bs[k * LDB + n] = (col < a.cols && k0 + k < a.Cin) ? v[p] : 0.f;
             }
-            Bs[k * LDB + n] = v;
         }
         __syncthreads();
 #pragma unroll
@@ -287,10 +380,116 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
                 const int m = m0 + wm * WM + i * 16 + 4 * (lane >> 4) + r;
                 if (m < a.Cout) {
                     const float b = a.bias ? a.bias[m] : 0.f;
-                    a.y[((size_t)img * a.Cout + m) * a.HW + pix] = acc[i][j][r] + b;
+                    stg(a.y + ((size_t)img * a.Cout + m) * a.HW + pix, acc[i][j][r] + b, FOUT);
                 }
             }
         }
+}
+
+// ------------------------------------------------------------------------------------
+// conv1x1 for small problems (the batch-1 case): latency, not throughput, decides.
+// A workgroup owns a 32 x 32 output tile as 2 x 2 MFMA tiles; its four wavefronts split K
+// four ways, each accumulates all four MFMA tiles over its quarter of K with operands
+// loaded straight from global memory into registers - no LDS staging and no barrier in
+// the K loop, up to 64 loads in flight per lane - and the four partial results are summed
+// through LDS in a fixed order (wavefront 0 + 1 + 2 + 3), so the result does not depend
+// on timing. The weights are read from a copy repacked once, ahead of time, into the order
+// the A operand wants: block (row tile rt, k step ks) holds W[16 rt + l % 16][4 ks + l / 16]
+// for lane l = 0..63, zero outside the matrix, so one A load is one contiguous 256 bytes.
+// The copy is zero-padded along K to a multiple of 4 x chunk steps: every wavefront runs
+// whole chunks and the K loop needs no tail handling (a lone wavefront per SIMD issues one
+// instruction every few cycles, so instruction count is what these kernels pay for).
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void pack_pw_weights_kernel(const float* w, float* wp, int Cout, int Cin,
+                                                                  int ksteps, int total) {
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= total) return;
+    const int l = i & 63, blk = i >> 6;
+    const int ks = blk % ksteps, rt = blk / ksteps;
+    const int m = rt * 16 + (l & 15), k = ks * 4 + (l >> 4);
+    wp[i] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
+}
+
+template <int CH, bool FIN, bool FOUT>                      // CH k steps per chunk: 4 * CH loads in flight per lane
+__device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, float* smem) {
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
+    const int m0 = by * 32, n0 = bx * 32;
+    const int S = a.ksteps;                                  // padded: every wavefront owns S / 4 steps, a multiple of CH
+    const int steps = S >> 2;
+    const unsigned k_last = (unsigned)(a.Cin - 1) * (unsigned)a.HW;   // offset of the last real input row
+    const unsigned k_step = 4u * (unsigned)a.HW;
+
+    const float* ap[2];
+    const float* xb[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int rt = min(by * 2 + i, a.mtiles - 1);       // a row tile past the matrix repeats the last one; never stored
+        ap[i] = a.wp + ((size_t)rt * S + (size_t)wave * steps) * 64 + lane;
+        const int col = min(n0 + i * 16 + (lane & 15), a.cols - 1);
+        const int img = col / a.HW, pix = col - img * a.HW;
+        xb[i] = a.x + (size_t)img * a.Cin * a.HW + pix;
+    }
+    // offset of this lane's input row at the wavefront's first step; rows past Cin (zero
+    // weights there) are clamped onto the last real row so that every load stays in bounds
+    unsigned koff = (unsigned)(4 * wave * steps + (lane >> 4)) * (unsigned)a.HW;
+    f32x4 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int s0 = 0; s0 < steps; s0 += CH) {
+        float av[2][CH], bv[2][CH];
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {
+            const unsigned off = min(koff + (unsigned)q * k_step, k_last);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                av[i][q] = ap[i][q * 64];
+                bv[i][q] = ldg(xb[i] + off, FIN);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);                   // every load of the chunk is issued before the first use
+#pragma unroll
+        for (int q = 0; q < CH; ++q)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i][q], bv[j][q], acc[i][j], 0, 0, 0);
+        ap[0] += CH * 64, ap[1] += CH * 64;
+        koff += CH * k_step;
+    }
+    // partial sums -> LDS as red[wave][tile][reg][lane]; wavefront w then finishes MFMA tile w
+    static_assert(4 * 4 * 4 * 64 <= kSmemFloats, "LDS budget");
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) smem[((wave * 4 + i * 2 + j) * 4 + r) * 64 + lane] = acc[i][j][r];
+    __syncthreads();
+    {
+        const int ti = wave >> 1, tj = wave & 1;
+        const int col = n0 + tj * 16 + (lane & 15);
+        const int ccol = min(col, a.cols - 1);
+        const int img = ccol / a.HW, pix = ccol - img * a.HW;
+        float* yb = a.y + (size_t)img * a.Cout * a.HW + pix;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float sum = smem[((0 * 4 + wave) * 4 + r) * 64 + lane];
+#pragma unroll
+            for (int w2 = 1; w2 < 4; ++w2) sum += smem[((w2 * 4 + wave) * 4 + r) * 64 + lane];
+            const int m = m0 + ti * 16 + 4 * (lane >> 4) + r;
+            if (m < a.Cout && col < a.cols) {
+                const float b = a.bias ? a.bias[m] : 0.f;
+                stg(yb + (size_t)m * a.HW, sum + b, FOUT);
+            }
+        }
+    }
+    __syncthreads();                                         // LDS is reused by the next tile
 }
 
 // ------------------------------------------------------------------------------------
@@ -301,9 +500,9 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
 // TP = 8 : each wavefront owns the same 8 x 8 pixel tile and its own group of 8 channels.
 // Tile index = (image * co_groups + channel group) * tiles_xy + pixel tile.
 // ------------------------------------------------------------------------------------
-template <int TP, int S>
+template <int TP, int S, bool FIN, bool FOUT>
 __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* smem) {
-    constexpr int CIC = 4;                             // input channels per LDS slice
+    constexpr int CIC = S == 2 && TP == 16 ? 2 : 4;    // input channels per LDS slice
     constexpr int IW = (TP - 1) * S + 3;               // input patch edge
     constexpr int LDP = IW + 1;
     constexpr int GROUPS = TP == 16 ? 1 : 4;           // channel groups per workgroup
@@ -332,13 +531,29 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     for (int j = 0; j < CO; ++j) wrow[j] = a.w + (size_t)min(co0 + j, a.Cout - 1) * a.Cin * 9;
 
     for (int c0 = 0; c0 < a.Cin; c0 += CIC) {
-        for (int e = tid; e < CIC * IW * IW; e += kBlock) {
-            const int cx = e % IW, t = e / IW;
-            const int cy = t % IW, ci = t / IW;
-            const int gy = iy0 + cy, gx = ix0 + cx, gc = c0 + ci;
-            float v = 0.f;
-            if (gc < a.Cin && gy >= 0 && gy < a.H && gx >= 0 && gx < a.W) v = xin[((size_t)gc * a.H + gy) * a.W + gx];
-            patch[(ci * IW + cy) * LDP + cx] = v;
+        {
+            constexpr int NL = (CIC * IW * IW + kBlock - 1) / kBlock;   // loads per thread, all in flight
+            float pv[NL];
+#pragma unroll
+            for (int q = 0; q < NL; ++q) {
+                const int e = min(tid + q * kBlock, CIC * IW * IW - 1);
+                const int cx = e % IW, t = e / IW;
+                const int cy = t % IW, ci = t / IW;
+                const int gy = iy0 + cy, gx = ix0 + cx, gc = c0 + ci;
+                const bool in = gc < a.Cin && gy >= 0 && gy < a.H && gx >= 0 && gx < a.W;
+                const float v = ldg(xin + ((size_t)min(gc, a.Cin - 1) * a.H + min(max(gy, 0), a.H - 1)) * a.W + min(max(gx, 0), a.W - 1), FIN);
+                pv[q] = in ? v : 0.f;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int q = 0; q < NL; ++q) {
+                const int e = tid + q * kBlock;
+                if (e < CIC * IW * IW) {
+                    const int cx = e % IW, t = e / IW;
+                    const int cy = t % IW, ci = t / IW;
+                    patch[(ci * IW + cy) * LDP + cx] = pv[q];
+                }
+            }
         }
         __syncthreads();
         const int nci = min(CIC, a.Cin - c0);
@@ -360,48 +575,64 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     if (oy < a.Ho && ox < a.Wo) {
 #pragma unroll
         for (int j = 0; j < CO; ++j)
-            if (co0 + j < a.Cout) a.y[(((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox] = acc[j];
+            if (co0 + j < a.Cout) stg(a.y + (((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox, acc[j], FOUT);
     }
 }
 
 // ------------------------------------------------------------------------------------
 // kernel table: id -> argument type, tile function, name
 // ------------------------------------------------------------------------------------
+// FIN: activations are read with device-scope loads (some operand was produced on another
+// XCD); FOUT: the result is stored with device-scope stores (some reader sits on another XCD).
 template <int KID> struct KernelOf;
-#define NG_KERNEL(KID, ARGS, CALL, NAME)                                                       \
+#define NG_KERNEL(KID, ARGS, NAME, ...)                                                        \
     template <> struct KernelOf<KID> {                                                         \
         using Args = ARGS;                                                                     \
         static constexpr const char* name = NAME;                                              \
-        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem) { CALL(a, t, smem); } \
+        template <bool FIN, bool FOUT>                                                         \
+        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem) {       \
+            __VA_ARGS__, FIN, FOUT > (a, t, smem);                                             \
+        }                                                                                      \
     };
-NG_KERNEL(KID_BN, BnArgs, bn_act_tile<false>, "bn_act")
-NG_KERNEL(KID_BN_V4, BnArgs, bn_act_tile<true>, "bn_act_v4")
-NG_KERNEL(KID_ADD, AddArgs, add_n_tile<false>, "add_n")
-NG_KERNEL(KID_ADD_V4, AddArgs, add_n_tile<true>, "add_n_v4")
-NG_KERNEL(KID_CONCAT, ConcatArgs, concat_tile<false>, "concat")
-NG_KERNEL(KID_CONCAT_V4, ConcatArgs, concat_tile<true>, "concat_v4")
-NG_KERNEL(KID_POOL, PoolArgs, pool3x3_tile, "pool3x3")
-#define NG_DW(K, S) dwconv_tile<K, S>
-NG_KERNEL(KID_DW_K3S1, DwArgs, (NG_DW(3, 1)), "dwconv_k3s1")
-NG_KERNEL(KID_DW_K3S2, DwArgs, (NG_DW(3, 2)), "dwconv_k3s2")
-NG_KERNEL(KID_DW_K5S1, DwArgs, (NG_DW(5, 1)), "dwconv_k5s1")
-NG_KERNEL(KID_DW_K5S2, DwArgs, (NG_DW(5, 2)), "dwconv_k5s2")
-NG_KERNEL(KID_GAP, GapArgs, global_avgpool_tile, "global_avgpool")
-NG_KERNEL(KID_FC_GEMV, FcArgs, fc_gemv_tile, "fc_gemv")
-#define NG_PW(TM, TN, KC) conv1x1_mfma_tile<TM, TN, KC>
-NG_KERNEL(KID_PW_32, PwArgs, (NG_PW(32, 32, 32)), "conv1x1_mfma_32x32")
-NG_KERNEL(KID_PW_64, PwArgs, (NG_PW(64, 64, 16)), "conv1x1_mfma_64x64")
-#define NG_C3(TP, S) conv3x3_tile<TP, S>
-NG_KERNEL(KID_C3_T16S1, C3Args, (NG_C3(16, 1)), "conv3x3_t16s1")
-NG_KERNEL(KID_C3_T16S2, C3Args, (NG_C3(16, 2)), "conv3x3_t16s2")
-NG_KERNEL(KID_C3_T8S1, C3Args, (NG_C3(8, 1)), "conv3x3_t8s1")
-NG_KERNEL(KID_C3_T8S2, C3Args, (NG_C3(8, 2)), "conv3x3_t8s2")
+NG_KERNEL(KID_BN, BnArgs, "bn_act", bn_act_tile < false)
+NG_KERNEL(KID_BN_V4, BnArgs, "bn_act_v4", bn_act_tile < true)
+NG_KERNEL(KID_ADD, AddArgs, "add_n", add_n_tile < false)
+NG_KERNEL(KID_ADD_V4, AddArgs, "add_n_v4", add_n_tile < true)
+NG_KERNEL(KID_CONCAT, ConcatArgs, "concat", concat_tile < false)
+NG_KERNEL(KID_CONCAT_V4, ConcatArgs, "concat_v4", concat_tile < true)
+NG_KERNEL(KID_DW_K3S1, DwArgs, "dwconv_k3s1", dwconv_tile < 3, 1)
+NG_KERNEL(KID_DW_K3S2, DwArgs, "dwconv_k3s2", dwconv_tile < 3, 2)
+NG_KERNEL(KID_DW_K5S1, DwArgs, "dwconv_k5s1", dwconv_tile < 5, 1)
+NG_KERNEL(KID_DW_K5S2, DwArgs, "dwconv_k5s2", dwconv_tile < 5, 2)
+NG_KERNEL(KID_PW_D4, PwArgs, "conv1x1_mfma_d4", conv1x1_direct_tile < 4)
+NG_KERNEL(KID_PW_D8, PwArgs, "conv1x1_mfma_d8", conv1x1_direct_tile < 8)
+NG_KERNEL(KID_PW_D16, PwArgs, "conv1x1_mfma_d16", conv1x1_direct_tile < 16)
+NG_KERNEL(KID_PW_64, PwArgs, "conv1x1_mfma_64x64", conv1x1_mfma_tile < 64, 64, 16)
+NG_KERNEL(KID_C3_T16S1, C3Args, "conv3x3_t16s1", conv3x3_tile < 16, 1)
+NG_KERNEL(KID_C3_T16S2, C3Args, "conv3x3_t16s2", conv3x3_tile < 16, 2)
+NG_KERNEL(KID_C3_T8S1, C3Args, "conv3x3_t8s1", conv3x3_tile < 8, 1)
+NG_KERNEL(KID_C3_T8S2, C3Args, "conv3x3_t8s2", conv3x3_tile < 8, 2)
+#undef NG_KERNEL
+// kernels without further template arguments
+#define NG_KERNEL0(KID, ARGS, NAME, FN)                                                        \
+    template <> struct KernelOf<KID> {                                                         \
+        using Args = ARGS;                                                                     \
+        static constexpr const char* name = NAME;                                              \
+        template <bool FIN, bool FOUT>                                                         \
+        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem) {       \
+            FN<FIN, FOUT>(a, t, smem);                                                         \
+        }                                                                                      \
+    };
+NG_KERNEL0(KID_POOL, PoolArgs, "pool3x3", pool3x3_tile)
+NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
+NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
+#undef NG_KERNEL0
 
 // Stand-alone kernel of one tile function: one workgroup per tile.
 template <int KID>
 __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KID>::Args a) {
     __shared__ float smem[kSmemFloats];
-    KernelOf<KID>::tile(a, blockIdx.x, smem);
+    KernelOf<KID>::template tile<false, false>(a, blockIdx.x, smem);
 }
 
 // ------------------------------------------------------------------------------------
@@ -414,24 +645,34 @@ __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KI
 // so a stream's tensors stay in that XCD's L2); an event is a completion counter:
 // recording = each workgroup of the producer adds 1 with release semantics after its
 // tiles, waiting = polling until the counter reaches (workgroups of the producer) x
-// (replay number), then an acquire. Every wait is bounded: a workgroup that runs out of
+// (replay number), then dropping the compute unit's L1. A tensor that another XCD reads is
+// stored and loaded with device-scope accesses, so no L2 is ever flushed or invalidated. Every wait is bounded: a workgroup that runs out of
 // spins raises the error flag and every workgroup leaves.
 // ------------------------------------------------------------------------------------
 typedef const __attribute__((address_space(4))) DevTask* ConstTaskPtr;
 typedef const __attribute__((address_space(4))) DevEntry* ConstEntryPtr;
 typedef const __attribute__((address_space(4))) int* ConstIntPtr;
 
+struct ArgWords {
+    unsigned w[kArgWords];
+};
+
 template <int KID>
-__device__ __forceinline__ void run_tiles(ConstTaskPtr t, int tile, int step, int ntiles, float* smem) {
+__device__ __forceinline__ void run_tiles(const ArgWords& blk, int tile, int step, int ntiles, float* smem, bool fin,
+                                          bool fout) {
     using A = typename KernelOf<KID>::Args;
-    static_assert(sizeof(A) % 4 == 0, "argument blocks are copied word by word");
-    A a;                                                         // uniform address, read-only space: lands in SGPRs
-    const __attribute__((address_space(4))) unsigned* src =
-        reinterpret_cast<const __attribute__((address_space(4))) unsigned*>(t->args);
-    unsigned* dst = reinterpret_cast<unsigned*>(&a);
-#pragma unroll
-    for (unsigned i = 0; i < sizeof(A) / 4; ++i) dst[i] = src[i];
-    for (; tile < ntiles; tile += step) KernelOf<KID>::tile(a, tile, smem);
+    static_assert(sizeof(A) <= sizeof(ArgWords) && sizeof(A) % 4 == 0, "argument block does not fit the prefetch");
+    A a;
+    __builtin_memcpy(&a, blk.w, sizeof(A));
+    if (!fin && !fout) {
+        for (; tile < ntiles; tile += step) KernelOf<KID>::template tile<false, false>(a, tile, smem);
+    } else if (!fin) {
+        for (; tile < ntiles; tile += step) KernelOf<KID>::template tile<false, true>(a, tile, smem);
+    } else if (!fout) {
+        for (; tile < ntiles; tile += step) KernelOf<KID>::template tile<true, false>(a, tile, smem);
+    } else {
+        for (; tile < ntiles; tile += step) KernelOf<KID>::template tile<true, true>(a, tile, smem);
+    }
 }
 
 __global__ __launch_bounds__(kBlock) void resident_kernel(DevPlan plan, unsigned epoch) {
@@ -448,14 +689,26 @@ __global__ __launch_bounds__(kBlock) void resident_kernel(DevPlan plan, unsigned
     for (int e = e_begin; e < e_end; ++e) {
         const int task = entries[e].task, tile0 = entries[e].tile_begin, step = entries[e].tile_step;
         ConstTaskPtr t = tasks + task;
-        const int np = t->n_parents;
+        // Everything the task needs is fetched (uniform addresses, read-only space: scalar
+        // loads into SGPRs) before the wait, so the fetch overlaps with it.
+        const int kid = t->kid, ntiles = t->ntiles, np = t->n_parents;
+        const bool far_in = t->far_in != 0, far_out = t->release_far != 0;
+        ArgWords blk;
+        {
+            const __attribute__((address_space(4))) unsigned* src =
+                reinterpret_cast<const __attribute__((address_space(4))) unsigned*>(t->args);
+#pragma unroll
+            for (int i = 0; i < kArgWords; ++i) blk.w[i] = src[i];
+        }
+        const bool tracer = plan.trace != nullptr && tile0 == 0 && lane == 0;
+        if (tracer) plan.trace[3 * task] = wall_clock64();
         if (np > 0) {
             if (lane < 64) {                                    // first wavefront: lane j watches parent j
                 bool ok = true;
                 if (lane < np) {
                     const DevTask* tg = plan.tasks + task;      // per-lane index: ordinary loads
                     const unsigned target = tg->need[lane] * epoch;
-                    const unsigned* counter = plan.done + tg->parent[lane];
+                    const unsigned* counter = plan.done + (size_t)tg->parent[lane] * plan.done_stride;
                     unsigned spins = 0;
                     while ((int)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
                         if (++spins > plan.spin_limit ||
@@ -463,7 +716,9 @@ __global__ __launch_bounds__(kBlock) void resident_kernel(DevPlan plan, unsigned
                             ok = false;
                             break;
                         }
-                        __builtin_amdgcn_s_sleep(1);
+                        if (plan.poll_sleep == 0) __builtin_amdgcn_s_sleep(1);
+                        else if (plan.poll_sleep == 1) __builtin_amdgcn_s_sleep(4);
+                        else __builtin_amdgcn_s_sleep(16);
                     }
                     if (!ok && spins > plan.spin_limit) {
                         atomicExch(plan.error_dev, task + 1);
@@ -473,23 +728,34 @@ __global__ __launch_bounds__(kBlock) void resident_kernel(DevPlan plan, unsigned
                 if (__any(!ok)) {
                     if (lane == 0) s_abort = 1;
                 }
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // producers' data becomes visible to this CU
+                // Make the producers' stores visible to this compute unit. Producers on this
+                // XCD have their results in the shared L2 already: dropping this CU's vector
+                // L1 is enough (what a workgroup-scope acquire does when the waves of a
+                // workgroup sit on different CUs). Tensors produced on another XCD are never
+                // cached here at all: their loads are device-scope accesses (far_in mask).
+                asm volatile("buffer_inv sc0" ::: "memory");
             }
-            __syncthreads();
+            __syncthreads();                                    // also waits for the invalidate to finish
             if (s_abort) return;
         }
-        switch (t->kid) {
-#define NG_CASE(KID) case KID: run_tiles<KID>(t, tile0, step, t->ntiles, smem); break;
+        if (tracer) plan.trace[3 * task + 1] = wall_clock64();
+        switch (kid) {
+#define NG_CASE(KID) case KID: run_tiles<KID>(blk, tile0, step, ntiles, smem, far_in, far_out); break;
             NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4) NG_CASE(KID_CONCAT)
             NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
             NG_CASE(KID_DW_K5S1) NG_CASE(KID_DW_K5S2) NG_CASE(KID_GAP) NG_CASE(KID_FC_GEMV)
-            NG_CASE(KID_PW_32) NG_CASE(KID_PW_64) NG_CASE(KID_C3_T16S1) NG_CASE(KID_C3_T16S2)
+            NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_C3_T16S1) NG_CASE(KID_C3_T16S2)
             NG_CASE(KID_C3_T8S1) NG_CASE(KID_C3_T8S2)
 #undef NG_CASE
             default: break;
         }
-        __syncthreads();                                         // every thread's stores have been issued and counted
-        if (lane == 0) __hip_atomic_fetch_add(plan.done + task, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();                 // every thread's stores have reached L2 (write-through L1, counted stores)
+        if (tracer) plan.trace[3 * task + 2] = wall_clock64();
+        if (lane == 0) {
+            // Publish completion. Readers on this XCD see the data in the shared L2; if there
+            // are readers elsewhere the tile functions have stored through to the memory side.
+            __hip_atomic_fetch_add(plan.done + (size_t)task * plan.done_stride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
     }
 }
 
@@ -512,11 +778,45 @@ void set_kernel(Task& t, const typename KernelOf<KID>::Args& a, long ntiles) {
 
 long ceil_div(long a, long b) { return (a + b - 1) / b; }
 
+// Direct conv1x1: k steps per chunk by problem depth, and the padded step count of the packed copy.
+int pw_chunk(long cin) { return cin <= 64 ? 4 : (cin <= 128 ? 8 : 16); }
+int pw_padded_steps(long cin) {
+    const long unit = 4L * pw_chunk(cin);
+    return (int)(ceil_div(ceil_div(cin, 4), unit) * unit);
+}
+
 }  // namespace
 
 const void* resident_kernel_handle() { return reinterpret_cast<const void*>(&resident_kernel); }
 
-int build_task(ng_graph* g, int v, char* arena, Task& t) {
+// Floats of library-owned constant memory node v needs (repacked conv1x1 weights), 0 if none.
+// Large pointwise problems (many 64 x 64 tiles) keep the LDS-tiled throughput kernel.
+size_t packed_floats(const ng_graph* g, int v) {
+    const Node& nd = g->nodes[v];
+    if (nd.op != NG_OP_CONV1X1 && nd.op != NG_OP_FC) return 0;
+    const Shape& o = nd.out;
+    const long cin = g->nodes[nd.preds[0]].out.c;
+    if (nd.op == NG_OP_FC && o.n <= 8) return 0;
+    const long cols = o.n * o.h * o.w;
+    if (((o.c + 63) / 64) * ((cols + 63) / 64) >= 256) return 0;
+    return (size_t)((o.c + 15) / 16) * 64 * pw_padded_steps(cin);
+}
+
+// Fill node v's constant memory: one pass over the weights, at bind time.
+int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
+    const size_t n = packed_floats(g, v);
+    if (n == 0) return NG_OK;
+    const Node& nd = g->nodes[v];
+    const int cin = (int)g->nodes[nd.preds[0]].out.c, cout = (int)nd.out.c;
+    if (!nd.weights[0]) return g->fail(NG_EINVAL, "node %d: weight 0 is a null device pointer", v);
+    pack_pw_weights_kernel<<<dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const float*>(nd.weights[0]), packed, cout, cin, pw_padded_steps(cin), (int)n);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return g->fail(NG_EHIP, "pack_pw_weights_kernel: %s", hipGetErrorString(e));
+    return NG_OK;
+}
+
+int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
     const Node& nd = g->nodes[v];
     t = Task();
     t.block[0] = kBlock;
@@ -580,12 +880,12 @@ int build_task(ng_graph* g, int v, char* arena, Task& t) {
         case NG_OP_POOL: {
             PoolArgs a{buf(nd.preds[0]), buf(v), (int)i0.h, (int)i0.w, (int)o.h, (int)o.w,
                        nd.p.stride, nd.p.pad, nd.p.pool_mode, total};
-            set_kernel<KID_POOL>(t, a, ceil_div(total, kBlock));
+            set_kernel<KID_POOL>(t, a, ceil_div(total, kBlock * kPoolPerThread));
             break;
         }
         case NG_OP_DWCONV: {
             DwArgs a{buf(nd.preds[0]), wf(0), buf(v), (int)o.c, (int)i0.h, (int)i0.w, (int)o.h, (int)o.w, total};
-            const long n = ceil_div(total, kBlock);
+            const long n = ceil_div(total, kBlock * dw_per_thread(nd.p.k));
             if (nd.p.k == 3 && nd.p.stride == 1) set_kernel<KID_DW_K3S1>(t, a, n);
             else if (nd.p.k == 3) set_kernel<KID_DW_K3S2>(t, a, n);
             else if (nd.p.stride == 1) set_kernel<KID_DW_K5S1>(t, a, n);
@@ -605,15 +905,23 @@ int build_task(ng_graph* g, int v, char* arena, Task& t) {
                 set_kernel<KID_FC_GEMV>(t, a, ceil_div(a.Cout, kBlock / 64));
                 break;
             }
-            PwArgs a{buf(nd.preds[0]), wf(0), fc ? wf(1) : nullptr, buf(v), (int)i0.c, (int)o.c, hw_out,
-                     (int)(o.n * hw_out), 0};
-            const long big_tiles = ceil_div(a.Cout, 64) * ceil_div(a.cols, 64);
-            if (big_tiles >= 256) {
+            PwArgs a{};
+            a.x = buf(nd.preds[0]), a.w = wf(0), a.bias = fc ? wf(1) : nullptr, a.y = buf(v);
+            a.Cin = (int)i0.c, a.Cout = (int)o.c, a.HW = hw_out, a.cols = (int)(o.n * hw_out);
+            if (packed_floats(g, v) == 0) {
                 a.tiles_n = (int)ceil_div(a.cols, 64);
-                set_kernel<KID_PW_64>(t, a, big_tiles);
+                set_kernel<KID_PW_64>(t, a, (long)a.tiles_n * ceil_div(a.Cout, 64));
             } else {
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
+                a.wp = packed;
+                const int chunk = pw_chunk(a.Cin);
+                a.ksteps = pw_padded_steps(a.Cin);
+                a.mtiles = (int)ceil_div(a.Cout, 16);
                 a.tiles_n = (int)ceil_div(a.cols, 32);
-                set_kernel<KID_PW_32>(t, a, (long)a.tiles_n * ceil_div(a.Cout, 32));
+                const long n = (long)a.tiles_n * ceil_div(a.Cout, 32);
+                if (chunk == 4) set_kernel<KID_PW_D4>(t, a, n);
+                else if (chunk == 8) set_kernel<KID_PW_D8>(t, a, n);
+                else set_kernel<KID_PW_D16>(t, a, n);
             }
             break;
         }

@@ -1,0 +1,201 @@
+// Host-side planner of the device-resident replay: turns the task schedule into one static
+// task list per persistent workgroup. Pure host code (no HIP calls), so it is testable
+// without a GPU.
+//
+// Nimble (arXiv 2012.02732) fixes *everything* about a run ahead of time (Section 4.1) and
+// lets independent operators run side by side on different streams (Section 4.2). Here the
+// same two ideas are applied one level further down: which workgroup executes which tile of
+// which task, and in what order, is also decided ahead of time.
+//
+//   * A stream lives on one XCD (workgroup w of a 1-D grid runs on XCD w mod 8), so the
+//     tensors that flow along a stream stay in that XCD's L2. Streams are placed heaviest
+//     first on the XCD with the least work so far.
+//   * The workgroups of an XCD are shared by the streams placed on it. Tasks are taken in
+//     ascending id (the submission order of the schedule) and each is given the workgroups
+//     of its XCD that a simple cost model expects to be free first - classic list
+//     scheduling - trying 1..4 rounds of tiles per workgroup and keeping the earliest
+//     expected finish. Independent tasks therefore land on different workgroups and overlap;
+//     dependent ones reuse the workgroups that just finished their producer.
+//   * A task no other task can run beside, with more tiles than one XCD has workgroups, is
+//     spread over every participating XCD.
+//   * Every workgroup's list is a subsequence of one topological order and a task waits only
+//     for earlier tasks, so with all workgroups resident no wait can depend on itself.
+//   * A task waits for all of its E' parents (FIFO order inside a stream does not order two
+//     workgroups). Whether a hand-over needs a device-scope fence is decided per tensor from
+//     *all* direct readers (edges of E): a reader on another XCD reads the tensor itself, even
+//     when it only waits for an intermediate task.
+#include <algorithm>
+#include <cstring>
+#include <numeric>
+
+#include "ng_device.h"
+#include "ng_internal.h"
+
+namespace ng {
+
+namespace {
+
+constexpr double kSyncNearUs = 1.1;   // completion counter -> dependent workgroup running, same XCD (measured)
+constexpr double kSyncFarUs = 6.0;    // extra cost of a device-scope release + acquire (measured)
+
+// Expected time of one round (one tile per workgroup) of a task, in microseconds. Rough
+// figures from measurements of the tile functions inside the resident kernel; the planner
+// only needs them to be ordered sensibly.
+double tile_round_us(const ng_graph* g, int v) {
+    const Task& t = g->tasks[v];
+    const Node& nd = g->nodes[v];
+    const double cin = nd.preds.empty() ? 0.0 : (double)g->nodes[nd.preds[0]].out.c;
+    switch (t.kid) {
+        case KID_BN: case KID_BN_V4: return 0.8;
+        case KID_ADD: case KID_ADD_V4: return 0.5;
+        case KID_CONCAT: case KID_CONCAT_V4: return 0.8;
+        case KID_POOL: case KID_DW_K3S1: case KID_DW_K3S2: return 1.5;
+        case KID_DW_K5S1: case KID_DW_K5S2: return 1.9;
+        case KID_GAP: return 1.0;
+        case KID_FC_GEMV: return 1.0 + 0.001 * cin * (double)nd.out.n;
+        case KID_PW_D4: case KID_PW_D8: case KID_PW_D16: return 1.6 + 0.004 * cin;
+        case KID_PW_64: return 1.5 + 0.05 * cin;
+        case KID_C3_T16S1: case KID_C3_T16S2: case KID_C3_T8S1: case KID_C3_T8S2: return 1.0 + 0.75 * cin;
+        default: return 1.0;
+    }
+}
+
+struct Sim {
+    std::vector<std::vector<DevEntry>> lists;
+    std::vector<unsigned> parts;
+    std::vector<int> xcd;
+    double makespan = 0;
+};
+
+void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
+    const Schedule& sc = g->sched;
+    const int n = (int)g->nodes.size();
+    const int per_xcd = n_wg / 8;
+
+    std::vector<long> stream_work(sc.n_streams, 0);
+    for (int v = 0; v < n; ++v) stream_work[sc.stream_of[v]] += g->tasks[v].ntiles;
+    std::vector<int> by_work(sc.n_streams);
+    std::iota(by_work.begin(), by_work.end(), 0);
+    std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return stream_work[a] > stream_work[b]; });
+    std::vector<long> xcd_work(nx, 0);
+    std::vector<int> xcd_count(nx, 0), stream_xcd(sc.n_streams, 0);
+    for (int st : by_work) {
+        int best = 0;
+        for (int x = 1; x < nx; ++x)
+            if (xcd_work[x] < xcd_work[best] || (xcd_work[x] == xcd_work[best] && xcd_count[x] < xcd_count[best])) best = x;
+        stream_xcd[st] = best;
+        ++xcd_count[best];
+        xcd_work[best] += std::max<long>(stream_work[st], 1);
+    }
+
+    out.lists.assign(n_wg, {});
+    out.parts.assign(n, 0);
+    out.xcd.assign(n, -1);
+    std::vector<double> free_at(n_wg, 0.0), finish(n, 0.0);
+    std::vector<std::vector<int>> parents(n);
+    for (auto& e : sc.meg) parents[e.second].push_back(e.first);
+
+    std::vector<int> cand;
+    for (int v = 0; v < n; ++v) {
+        const Task& t = g->tasks[v];
+        if (!t.fn) continue;
+        const int home = stream_xcd[sc.stream_of[v]];
+        const bool wide = nx > 1 && sc.solo[v] && t.ntiles > per_xcd;
+        out.xcd[v] = nx == 1 ? 0 : (wide ? -1 : home);
+        cand.clear();
+        for (int w = 0; w < n_wg; ++w) {
+            const int x = w % 8;
+            if (x >= nx) continue;
+            if (wide || x == home) cand.push_back(w);
+        }
+        double ready = 0;
+        for (int u : parents[v]) {
+            if (!g->tasks[u].fn) continue;
+            const bool far = out.xcd[u] < 0 || out.xcd[v] < 0 || out.xcd[u] != out.xcd[v] || g->resident_all_far;
+            ready = std::max(ready, finish[u] + (far ? kSyncFarUs : 0.0));
+        }
+        // workgroups in the order they become available for this task
+        std::stable_sort(cand.begin(), cand.end(), [&](int a, int b) { return free_at[a] < free_at[b]; });
+        const double cost = tile_round_us(g, v);
+        int best_p = 1;
+        double best_finish = 1e300;
+        for (int rounds = 1; rounds <= 4; ++rounds) {
+            const int p = (int)std::min<long>((t.ntiles + rounds - 1) / rounds, (long)cand.size());
+            const long r = (t.ntiles + p - 1) / p;
+            const double f = std::max(ready, free_at[cand[p - 1]]) + r * cost + kSyncNearUs;
+            if (f < best_finish - 1e-9) best_finish = f, best_p = p;
+        }
+        const int p = best_p;
+        const long r = (t.ntiles + p - 1) / p;
+        out.parts[v] = (unsigned)p;
+        for (int j = 0; j < p; ++j) {
+            const int w = cand[j];
+            out.lists[w].push_back(DevEntry{v, j, p, 0});
+            free_at[w] = std::max(ready, free_at[w]) + r * cost + kSyncNearUs;
+        }
+        finish[v] = best_finish;
+        out.makespan = std::max(out.makespan, best_finish);
+    }
+}
+
+}  // namespace
+
+int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
+    const Schedule& sc = g->sched;
+    const int n = (int)g->nodes.size();
+    Sim best;
+    int best_nx = 0;
+    for (int nx : {1, 2, 4, 8}) {
+        if (xcds > 0 && nx != xcds) continue;
+        Sim s;
+        simulate(g, n_wg, nx, s);
+        if (best_nx == 0 || s.makespan < best.makespan) best = std::move(s), best_nx = nx;
+    }
+    plan.n_wg = n_wg;
+    plan.xcds = best_nx;
+    plan.est_us = best.makespan;
+
+    plan.tasks.assign(n, DevTask());
+    for (int v = 0; v < n; ++v) {
+        DevTask& d = plan.tasks[v];
+        std::memset(&d, 0, sizeof d);
+        const Task& t = g->tasks[v];
+        if (!t.fn) continue;
+        d.kid = t.kid;
+        d.ntiles = (int)t.ntiles;
+        std::memcpy(d.args, t.args, sizeof t.args);
+    }
+    // A tensor crosses XCDs when a direct reader (any edge of E, not only E') runs elsewhere.
+    for (int v = 0; v < n; ++v) {
+        if (!g->tasks[v].fn) continue;
+        const std::vector<int>& preds = g->nodes[v].preds;
+        for (size_t j = 0; j < preds.size(); ++j) {
+            const int u = preds[j];
+            if (!g->tasks[u].fn) continue;          // network input: written before the launch
+            const bool far = best.xcd[u] < 0 || best.xcd[v] < 0 || best.xcd[u] != best.xcd[v] || g->resident_all_far;
+            if (far) plan.tasks[v].far_in |= 1u << j;
+        }
+        if (plan.tasks[v].far_in)                    // one far operand: every operand comes through the memory side
+            for (int u : preds)
+                if (g->tasks[u].fn) plan.tasks[u].release_far = 1;
+        if (g->resident_all_far) plan.tasks[v].release_far = 1;
+    }
+    for (auto& e : sc.meg) {
+        if (!g->tasks[e.first].fn || !g->tasks[e.second].fn) continue;
+        DevTask& d = plan.tasks[e.second];
+        if (d.n_parents >= NG_MAX_PREDS) return NG_EINVAL;
+        d.parent[d.n_parents] = e.first;
+        d.need[d.n_parents] = best.parts[e.first];
+        ++d.n_parents;
+    }
+    plan.entries.clear();
+    plan.wg_first.assign(n_wg + 1, 0);
+    for (int w = 0; w < n_wg; ++w) {
+        plan.wg_first[w] = (int)plan.entries.size();
+        plan.entries.insert(plan.entries.end(), best.lists[w].begin(), best.lists[w].end());
+    }
+    plan.wg_first[n_wg] = (int)plan.entries.size();
+    return NG_OK;
+}
+
+}  // namespace ng

@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 #include "ng_device.h"
@@ -28,6 +29,7 @@ struct Runtime {
     hipGraph_t graph[2] = {nullptr, nullptr};
     hipGraphExec_t exec[2] = {nullptr, nullptr};
     hipEvent_t t_start = nullptr, t_stop = nullptr;
+    float* constants = nullptr;            // library-owned: repacked weights
     // device-resident replay
     DevPlan plan{};
     void* d_tasks = nullptr;
@@ -36,6 +38,9 @@ struct Runtime {
     int* h_error = nullptr;                // pinned host memory
     int n_wg = 0, n_entries = 0;
     unsigned epoch = 0;
+    size_t done_words = 0;
+    int xcds = 0;
+    double est_us = 0;
     bool counters_dirty = false;
 };
 
@@ -141,80 +146,45 @@ int record_multi(ng_graph* g, int slot) {
     return NG_OK;
 }
 
-// Device-resident replay: turn the schedule into per-workgroup task lists.
-//   * stream s is served by a gang of workgroups that all sit on XCD (s mod 8) - workgroup w
-//     of a 1-D grid runs on XCD (w mod 8) - so consecutive tasks of a stream find their
-//     inputs in that XCD's L2;
-//   * a task is split over min(tiles, gang size) workgroups of its stream's gang; a task that
-//     no other task can run beside (comparable with every node) and that has more tiles than
-//     its gang is split over all workgroups instead;
-//   * every list is in ascending task id and a task only waits for smaller ids, so with all
-//     workgroups resident no wait can depend on itself;
-//   * a task waits for every E' parent (same stream or not): inside the resident kernel FIFO
-//     order alone does not order two workgroups of a gang.
+// Device-resident replay: plan on the host (ng_resident_plan.cpp), upload, keep the handles.
 int build_resident(ng_graph* g) {
     Runtime& rt = *g->rt;
-    const Schedule& sc = g->sched;
     const int n = (int)g->nodes.size();
     int dev = 0, cus = 0, per_cu = 0;
     NG_HIP(hipGetDevice(&dev));
     NG_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     NG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel_handle(), kBlock, 0));
     if (per_cu < 1 || cus < 8) return g->fail(NG_EHIP, "device-resident replay: kernel does not fit (%d per CU, %d CUs)", per_cu, cus);
-    per_cu = std::min(per_cu, g->resident_wg_per_cu > 0 ? g->resident_wg_per_cu : 2);
+    per_cu = std::min(per_cu, g->resident_wg_per_cu > 0 ? g->resident_wg_per_cu : 1);   // one per CU: two slow each other's hand-overs down
     const int n_wg = cus * per_cu / 8 * 8;
-    const int per_xcd = n_wg / 8;
-    const int slots = (sc.n_streams + 7) / 8;
-    const int gang = std::max(1, per_xcd / slots);
-    const int max_slots = per_xcd / gang;
-    auto gang_wg = [&](int stream, int j) { return (stream % 8) + 8 * (((stream / 8) % max_slots) * gang + j); };
-
-    std::vector<DevTask> tasks(n);
-    std::vector<std::vector<DevEntry>> lists(n_wg);
-    std::vector<unsigned> parts(n, 0);
-    for (int v = 0; v < n; ++v) {
-        const Task& t = g->tasks[v];
-        DevTask& d = tasks[v];
-        std::memset(&d, 0, sizeof d);
-        if (!t.fn) continue;
-        d.kid = t.kid;
-        d.ntiles = (int)t.ntiles;
-        std::memcpy(d.args, t.args, sizeof t.args);
-        const bool wide = sc.solo[v] && t.ntiles > gang;
-        const int p = (int)std::min<long>(t.ntiles, wide ? n_wg : gang);
-        parts[v] = (unsigned)p;
-        for (int j = 0; j < p; ++j) lists[wide ? j : gang_wg(sc.stream_of[v], j)].push_back(DevEntry{v, j, p, 0});
-    }
-    for (auto& e : sc.meg) {
-        if (!g->tasks[e.first].fn || !g->tasks[e.second].fn) continue;
-        DevTask& d = tasks[e.second];
-        if (d.n_parents >= NG_MAX_PREDS) return g->fail(NG_EINVAL, "device-resident replay: node %d has too many parents", e.second);
-        d.parent[d.n_parents] = e.first;
-        d.need[d.n_parents] = parts[e.first];
-        ++d.n_parents;
-    }
-    std::vector<DevEntry> entries;
-    std::vector<int> wg_first(n_wg + 1, 0);
-    for (int w = 0; w < n_wg; ++w) {
-        wg_first[w] = (int)entries.size();
-        entries.insert(entries.end(), lists[w].begin(), lists[w].end());
-    }
-    wg_first[n_wg] = (int)entries.size();
+    ResidentPlan hp;
+    if (plan_resident(g, n_wg, g->resident_xcds, hp) != NG_OK)
+        return g->fail(NG_EINVAL, "device-resident replay: a node has more than %d E' parents", NG_MAX_PREDS);
+    std::vector<DevTask>& tasks = hp.tasks;
+    std::vector<DevEntry>& entries = hp.entries;
+    std::vector<int>& wg_first = hp.wg_first;
+    rt.xcds = hp.xcds;
+    rt.est_us = hp.est_us;
     if (entries.empty()) entries.push_back(DevEntry{0, 0, 1, 0});   // keeps the allocation non-empty; never read
 
     unsigned* d_done = nullptr;
     int* d_error = nullptr;
+    const char* env_stride = getenv("NG_DONE_STRIDE");
+    const char* env_sleep = getenv("NG_POLL_SLEEP");
+    rt.plan.done_stride = env_stride ? atoi(env_stride) : 64;    // one counter per 256 bytes
+    rt.plan.poll_sleep = env_sleep ? atoi(env_sleep) : 1;
+    rt.done_words = (size_t)n * rt.plan.done_stride;
     NG_HIP(hipMalloc(&rt.d_tasks, tasks.size() * sizeof(DevTask)));
     NG_HIP(hipMalloc(&rt.d_entries, entries.size() * sizeof(DevEntry)));
     NG_HIP(hipMalloc(&rt.d_wg_first, wg_first.size() * sizeof(int)));
-    NG_HIP(hipMalloc(&d_done, (size_t)n * sizeof(unsigned)));
+    NG_HIP(hipMalloc(&d_done, rt.done_words * sizeof(unsigned)));
     NG_HIP(hipMalloc(&d_error, sizeof(int)));
     NG_HIP(hipHostMalloc(reinterpret_cast<void**>(&rt.h_error), sizeof(int), hipHostMallocDefault));
     *rt.h_error = 0;
     NG_HIP(hipMemcpy(rt.d_tasks, tasks.data(), tasks.size() * sizeof(DevTask), hipMemcpyHostToDevice));
     NG_HIP(hipMemcpy(rt.d_entries, entries.data(), entries.size() * sizeof(DevEntry), hipMemcpyHostToDevice));
     NG_HIP(hipMemcpy(rt.d_wg_first, wg_first.data(), wg_first.size() * sizeof(int), hipMemcpyHostToDevice));
-    NG_HIP(hipMemset(d_done, 0, (size_t)n * sizeof(unsigned)));
+    NG_HIP(hipMemset(d_done, 0, rt.done_words * sizeof(unsigned)));
     NG_HIP(hipMemset(d_error, 0, sizeof(int)));
     rt.plan.tasks = static_cast<const DevTask*>(rt.d_tasks);
     rt.plan.entries = static_cast<const DevEntry*>(rt.d_entries);
@@ -236,7 +206,7 @@ int launch_resident(ng_graph* g) {
     hipStream_t origin = rt.streams[0];
     if (rt.counters_dirty) {                                   // a timed-out replay left partial counts behind
         NG_HIP(hipStreamSynchronize(origin));
-        NG_HIP(hipMemset(rt.plan.done, 0, g->nodes.size() * sizeof(unsigned)));
+        NG_HIP(hipMemset(rt.plan.done, 0, rt.done_words * sizeof(unsigned)));
         NG_HIP(hipMemset(rt.plan.error_dev, 0, sizeof(int)));
         *rt.h_error = 0;
         rt.epoch = 0;
@@ -264,11 +234,13 @@ void destroy_runtime(ng_graph* g) {
     if (rt->fork_event) (void)hipEventDestroy(rt->fork_event);
     if (rt->t_start) (void)hipEventDestroy(rt->t_start);
     if (rt->t_stop) (void)hipEventDestroy(rt->t_stop);
+    if (rt->constants) (void)hipFree(rt->constants);
     if (rt->d_tasks) (void)hipFree(rt->d_tasks);
     if (rt->d_entries) (void)hipFree(rt->d_entries);
     if (rt->d_wg_first) (void)hipFree(rt->d_wg_first);
     if (rt->plan.done) (void)hipFree(rt->plan.done);
     if (rt->plan.error_dev) (void)hipFree(rt->plan.error_dev);
+    if (rt->plan.trace) (void)hipFree(rt->plan.trace);
     if (rt->h_error) (void)hipHostFree(rt->h_error);
     delete rt;
     g->rt = nullptr;
@@ -305,9 +277,18 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
     rt.arena_bytes = arena_bytes;
     for (int s = 0; s < g->sched.n_streams; ++s) rt.streams.push_back(static_cast<hipStream_t>(hip_streams[s]));
 
+    // constant memory: weights repacked once, ahead of time, into the order the kernels read them
+    std::vector<size_t> const_off(g->nodes.size() + 1, 0);
+    for (size_t v = 0; v < g->nodes.size(); ++v) const_off[v + 1] = const_off[v] + ((packed_floats(g, (int)v) + 63) & ~(size_t)63);
+    if (const_off.back() > 0) {
+        NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.constants), const_off.back() * sizeof(float)));
+        for (int v = 0; v < (int)g->nodes.size(); ++v)
+            if (int rc = pack_constants(g, v, rt.constants + const_off[v], rt.streams[0])) return rc;
+        NG_HIP(hipStreamSynchronize(rt.streams[0]));
+    }
     g->tasks.assign(g->nodes.size(), Task());
     for (int v = 0; v < (int)g->nodes.size(); ++v)
-        if (int rc = build_task(g, v, rt.arena, g->tasks[v])) return rc;
+        if (int rc = build_task(g, v, rt.arena, rt.constants ? rt.constants + const_off[v] : nullptr, g->tasks[v])) return rc;
 
     rt.events.resize(g->sched.n_events);
     for (auto& e : rt.events) NG_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -376,22 +357,47 @@ int ng_sync(ng_graph* g) {
     return NG_OK;
 }
 
-int ng_resident_config(ng_graph* g, int workgroups_per_cu, unsigned spin_limit) {
+int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned spin_limit, int device_scope_everywhere) {
     if (!g) return NG_EINVAL;
     if (workgroups_per_cu < 0 || workgroups_per_cu > 8) return g->fail(NG_EINVAL, "ng_resident_config: workgroups_per_cu must be 0..8");
-    if (workgroups_per_cu > 0) {
+    if (xcds != 0 && xcds != 1 && xcds != 2 && xcds != 4 && xcds != 8) return g->fail(NG_EINVAL, "ng_resident_config: xcds must be 0, 1, 2, 4 or 8");
+    if (workgroups_per_cu > 0 || xcds > 0 || (device_scope_everywhere != 0) != g->resident_all_far) {
         if (g->phase >= CAPTURED) return g->fail(NG_ESTATE, "ng_resident_config: the gang layout is fixed at ng_capture");
-        g->resident_wg_per_cu = workgroups_per_cu;
+        if (workgroups_per_cu > 0) g->resident_wg_per_cu = workgroups_per_cu;
+        if (xcds > 0) g->resident_xcds = xcds;
+        g->resident_all_far = device_scope_everywhere != 0;
     }
     g->resident_spin_limit = spin_limit ? spin_limit : kDefaultSpinLimit;
     return NG_OK;
 }
 
-int ng_resident_sizes(const ng_graph* g, int* n_workgroups, int* n_entries) {
+int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED || !g->rt->d_tasks) return g->fail(NG_ESTATE, "ng_resident_trace: call ng_capture first");
+    Runtime& rt = *g->rt;
+    const size_t bytes = g->nodes.size() * 3 * sizeof(unsigned long long);
+    NG_HIP(hipStreamSynchronize(rt.streams[0]));
+    if (ticks) {
+        if (!rt.plan.trace) return g->fail(NG_ESTATE, "ng_resident_trace: tracing is off");
+        NG_HIP(hipMemcpy(ticks, rt.plan.trace, bytes, hipMemcpyDeviceToHost));
+    }
+    if (enable && !rt.plan.trace) {
+        NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.plan.trace), bytes));
+        NG_HIP(hipMemset(rt.plan.trace, 0, bytes));
+    } else if (!enable && rt.plan.trace) {
+        NG_HIP(hipFree(rt.plan.trace));
+        rt.plan.trace = nullptr;
+    }
+    return NG_OK;
+}
+
+int ng_resident_sizes(const ng_graph* g, int* n_workgroups, int* n_entries, int* xcds, double* expected_us) {
     if (!g) return NG_EINVAL;
     if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_resident_sizes: call ng_capture first");
     if (n_workgroups) *n_workgroups = g->rt->n_wg;
     if (n_entries) *n_entries = g->rt->n_entries;
+    if (xcds) *xcds = g->rt->xcds;
+    if (expected_us) *expected_us = g->rt->est_us;
     return NG_OK;
 }
 

@@ -212,7 +212,7 @@ def test_device_resident_repeats_and_new_inputs():
     r = GraphRunner(w, DEV)
     r.prepare()
     try:
-        n_wg, n_entries = B.ng_resident_sizes(r.g)
+        n_wg, n_entries, xcds, est_us = B.ng_resident_sizes(r.g)
         assert n_wg >= 256 and n_wg % 8 == 0 and n_entries >= len(w.nodes) - 1
         out_id = w.outputs[0]
         ref_graph = r.run(mode=B.NG_MODE_GRAPH_MULTI)[out_id].copy()
@@ -234,12 +234,12 @@ def test_device_resident_wait_gives_up_and_recovers():
     r.prepare()
     try:
         good = r.run(mode=B.NG_MODE_DEVICE_RESIDENT)
-        B.ng_resident_config(r.g, 0, 1)
+        B.ng_resident_config(r.g, spin_limit=1)
         B.ng_replay(r.g)
         with pytest.raises(B.NgError) as ei:
             B.ng_sync(r.g)
         assert ei.value.code == B.NG_EHIP and "ran out of spins" in str(ei.value)
-        B.ng_resident_config(r.g, 0, 0)
+        B.ng_resident_config(r.g, spin_limit=0)
         r.arena.zero_()
         r.set_input(w.input)
         again = r.run(mode=B.NG_MODE_DEVICE_RESIDENT)
