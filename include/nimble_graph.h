@@ -201,15 +201,32 @@ int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned sp
  * wait for producers begins, inputs ready, all tiles of the first workgroup done. Waits for
  * the origin stream to go idle. */
 int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks);
+/* Host-only rehearsal of the device-resident plan (needs ng_plan_memory, no GPU): plans for
+ * n_workgroups persistent workgroups (a multiple of 8) over xcds XCDs (0 = let the cost
+ * model choose) and reports the expected makespan in microseconds, the number of
+ * (workgroup, task) entries, the number of operands that cross XCDs, and whether the plan
+ * passed its self-check (every tile of every task assigned exactly once, every list in
+ * ascending task id, expected completion counts consistent). Any pointer may be NULL. */
+int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, double* expected_us, int* n_entries,
+                         int* n_far_edges, int* coverage_ok);
 /* Layout chosen at ng_capture: resident workgroups, total (workgroup, task) entries, XCDs in
  * use, and the makespan in microseconds that the planner's cost model expects (any pointer
  * may be NULL). */
 int ng_resident_sizes(const ng_graph* g, int* n_workgroups, int* n_entries, int* xcds, double* expected_us);
 
-/* Isolated duration of one task in microseconds: the kernel is launched alone `reps`
- * times on the origin stream, each launch timed by the device's own start/stop
- * timestamps; *median_us receives the median (0 for input nodes). */
-int ng_time_task(ng_graph* g, int id, int reps, float* median_us);
+/* Device time of one replay in the current mode: `reps` replays are enqueued back to back on
+ * the origin stream between two events recorded on that stream; *avg_us = elapsed / reps. */
+int ng_time_replay(ng_graph* g, int reps, float* avg_us);
+/* Raw timing primitive: a graph that is a chain of `reps` copies of node id's kernel (id = -1:
+ * an empty kernel) is launched on the origin stream and timed with events; *us_per_node
+ * receives elapsed / reps (best of three launches). Includes the dependent-dispatch gap. */
+int ng_time_chain(ng_graph* g, int id, int reps, float* us_per_node);
+/* Isolated duration of one task in microseconds, the weight used for the critical path
+ * (Section 3: "GPU active time" of an operator): chain time of the task's kernel minus the
+ * chain time of an empty kernel (that removes the dispatch gap) plus the duration of an
+ * empty kernel as the device's dispatch timestamps report it on this GPU (1.0 us).
+ * 0 for input nodes. */
+int ng_time_task(ng_graph* g, int id, int reps, float* isolated_us);
 /* Name of the kernel bound to a node ("" for input nodes); valid until ng_destroy. */
 const char* ng_task_kernel(const ng_graph* g, int id);
 /* Algorithmic work of a node, from its shapes: bytes moved and flops (host doubles). */

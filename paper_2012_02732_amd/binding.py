@@ -24,7 +24,7 @@ SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_ou
            "ng_node_shape", "ng_schedule", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
            "ng_plan_memory", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
-           "ng_resident_sizes", "ng_resident_trace", "ng_time_task",
+           "ng_resident_dry_plan", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
 
 
@@ -62,8 +62,11 @@ _sig = {
     "ng_replay": (_I, [_P]),
     "ng_sync": (_I, [_P]),
     "ng_resident_config": (_I, [_P, _I, _I, C.c_uint, _I]),
+    "ng_resident_dry_plan": (_I, [_P, _I, _I, _DP, _IP, _IP, _IP]),
     "ng_resident_sizes": (_I, [_P, _IP, _IP, _IP, _DP]),
     "ng_resident_trace": (_I, [_P, _I, C.POINTER(C.c_ulonglong)]),
+    "ng_time_replay": (_I, [_P, _I, _FP]),
+    "ng_time_chain": (_I, [_P, _I, _I, _FP]),
     "ng_time_task": (_I, [_P, _I, _I, _FP]),
     "ng_task_kernel": (C.c_char_p, [_P, _I]),
     "ng_task_work": (_I, [_P, _I, _DP, _DP]),
@@ -213,6 +216,12 @@ def ng_resident_config(g, workgroups_per_cu=0, xcds=0, spin_limit=0, device_scop
     check(g, lib.ng_resident_config(g, workgroups_per_cu, xcds, spin_limit, device_scope_everywhere))
 
 
+def ng_resident_dry_plan(g, n_workgroups=256, xcds=0) -> dict:
+    e, n, f, ok = C.c_double(), C.c_int(), C.c_int(), C.c_int()
+    check(g, lib.ng_resident_dry_plan(g, n_workgroups, xcds, C.byref(e), C.byref(n), C.byref(f), C.byref(ok)))
+    return {"expected_us": e.value, "n_entries": n.value, "n_far_edges": f.value, "ok": bool(ok.value)}
+
+
 def ng_resident_sizes(g):
     a, b, x, e = C.c_int(), C.c_int(), C.c_int(), C.c_double()
     check(g, lib.ng_resident_sizes(g, C.byref(a), C.byref(b), C.byref(x), C.byref(e)))
@@ -231,6 +240,18 @@ def ng_resident_trace(g, enable, fetch=False):
     vals = [v for v in buf if v]
     base = min(vals) if vals else 0
     return [tuple((buf[3 * i + j] - base) / 100.0 if buf[3 * i + j] else None for j in range(3)) for i in range(n)]
+
+
+def ng_time_replay(g, reps) -> float:
+    out = C.c_float()
+    check(g, lib.ng_time_replay(g, reps, C.byref(out)))
+    return out.value
+
+
+def ng_time_chain(g, node_id, reps) -> float:
+    out = C.c_float()
+    check(g, lib.ng_time_chain(g, node_id, reps, C.byref(out)))
+    return out.value
 
 
 def ng_time_task(g, node_id, reps) -> float:

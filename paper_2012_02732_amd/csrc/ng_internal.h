@@ -86,6 +86,7 @@ struct ng_graph {
     int resident_wg_per_cu = 0;                          // 0 = pick automatically
     int resident_xcds = 0;                               // XCDs the resident kernel spreads over, 0 = all 8
     unsigned resident_spin_limit = ng::kDefaultSpinLimit; // polls before a wait gives up
+    bool dry_run = false;                                // task table built for planning only (host, fake addresses)
     bool resident_all_far = false;                       // treat every edge as crossing XCDs (device-scope fences everywhere)
     std::string err;
 
@@ -109,6 +110,7 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t);
 size_t packed_floats(const ng_graph* g, int v);
 int pack_constants(ng_graph* g, int v, float* packed, void* stream);
 const void* resident_kernel_handle();
+const void* empty_kernel_handle();
 // ng_resident_plan.cpp: xcds = 0 lets the cost model choose among 1, 2, 4, 8.
 int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan);
 // ng_runtime.hip

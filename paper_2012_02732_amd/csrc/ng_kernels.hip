@@ -29,34 +29,52 @@ namespace {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-// Access helpers. `far` is uniform per task. A far load/store is a relaxed device-scope atomic
-// access: it is served by the memory side (sc1), past the XCD-private L2, which is what makes a
-// tensor written on one XCD readable on another without flushing or invalidating either L2.
-__device__ __forceinline__ float ldg(const float* p, bool far) {
-    return far ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
+// Access helpers. `far` is a compile-time constant at every call site. A far access is a
+// device-scope access (sc1): it is served by the memory side, past the XCD-private L2, which
+// is what makes a tensor written on one XCD readable on another without flushing or
+// invalidating either L2. Far accesses go through buffer instructions (uniform tensor base
+// + 32-bit byte offset), which carry the cache policy and come in 128-bit form; tensors are
+// far smaller than the 4 GiB a 32-bit offset spans.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+constexpr int kPolicyDeviceScope = 16;                       // cache-policy operand: sc1
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tensor_rsrc(const float* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, 0x7FFFFFFF, 0x00020000);
 }
-__device__ __forceinline__ float4 ldg4(const float* p, bool far) {
+__device__ __forceinline__ unsigned byte_offset(const float* base, const float* p) {
+    return (unsigned)(reinterpret_cast<const char*>(p) - reinterpret_cast<const char*>(base));
+}
+// base: wave-uniform start of the tensor; p: this lane's address inside it
+__device__ __forceinline__ float ldg(const float* base, const float* p, bool far) {
+    if (!far) return *p;
+    return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(tensor_rsrc(base), byte_offset(base, p), 0, kPolicyDeviceScope));
+}
+__device__ __forceinline__ float4 ldg4(const float* base, const float* p, bool far) {
     if (!far) return *reinterpret_cast<const float4*>(p);
-    float4 v;
-    v.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return v;
+    const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(tensor_rsrc(base), byte_offset(base, p), 0, kPolicyDeviceScope);
+    float4 f;
+    __builtin_memcpy(&f, &v, sizeof f);                     // the whole vector at once: extracting elements one by
+    return f;                                               // one makes this compiler shrink the load to one dword
 }
-__device__ __forceinline__ void stg(float* p, float v, bool far) {
-    if (far) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *p = v;
+__device__ __forceinline__ void stg(float* base, float* p, float v, bool far) {
+    if (!far) {
+        *p = v;
+        return;
+    }
+    __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(unsigned, v), tensor_rsrc(base), byte_offset(base, p), 0, kPolicyDeviceScope);
 }
-__device__ __forceinline__ void stg4(float* p, float4 v, bool far) {
+__device__ __forceinline__ void stg4(float* base, float* p, float4 v, bool far) {
     if (!far) {
         *reinterpret_cast<float4*>(p) = v;
         return;
     }
-    __hip_atomic_store(p + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __hip_atomic_store(p + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    u32x4 u;
+    __builtin_memcpy(&u, &v, sizeof u);
+    __builtin_amdgcn_raw_buffer_store_b128(u, tensor_rsrc(base), byte_offset(base, p), 0, kPolicyDeviceScope);
+}
+// per-lane tensor (concat picks its source per lane): single relaxed device-scope accesses
+__device__ __forceinline__ float ldg_any(const float* p, bool far) {
+    return far ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
 }
 
 // LDS floats every workgroup owns: the largest user is the conv3x3 input patch (4 x 33 x 34).
@@ -83,16 +101,16 @@ __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*) {
         if (e >= a.total) return;
         float s, t;
         bn_coeff(a, (e / a.HW) % a.C, s, t);
-        float4 v = ldg4(a.x + e, FIN);
+        float4 v = ldg4(a.x, a.x + e, FIN);
         v.x = fmaf(v.x, s, t), v.y = fmaf(v.y, s, t), v.z = fmaf(v.z, s, t), v.w = fmaf(v.w, s, t);
         if (a.relu) v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
-        stg4(a.y + e, v, FOUT);
+        stg4(a.y, a.y + e, v, FOUT);
     } else {
         if (i >= a.total) return;
         float s, t;
         bn_coeff(a, (i / a.HW) % a.C, s, t);
-        float v = fmaf(ldg(a.x + i, FIN), s, t);
-        stg(a.y + i, a.relu ? fmaxf(v, 0.f) : v, FOUT);
+        float v = fmaf(ldg(a.x, a.x + i, FIN), s, t);
+        stg(a.y, a.y + i, a.relu ? fmaxf(v, 0.f) : v, FOUT);
     }
 }
 
@@ -105,23 +123,23 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*) {
     if (VEC4) {
         const int e = i * 4;
         if (e >= a.total) return;
-        float4 acc = ldg4(a.x[0] + e, FIN);
+        float4 acc = ldg4(a.x[0], a.x[0] + e, FIN);
 #pragma unroll
         for (int j = 1; j < NG_MAX_PREDS; ++j) {
             if (j >= a.k) break;
-            const float4 v = ldg4(a.x[j] + e, FIN);
+            const float4 v = ldg4(a.x[j], a.x[j] + e, FIN);
             acc.x += v.x, acc.y += v.y, acc.z += v.z, acc.w += v.w;
         }
-        stg4(a.y + e, acc, FOUT);
+        stg4(a.y, a.y + e, acc, FOUT);
     } else {
         if (i >= a.total) return;
-        float acc = ldg(a.x[0] + i, FIN);
+        float acc = ldg(a.x[0], a.x[0] + i, FIN);
 #pragma unroll
         for (int j = 1; j < NG_MAX_PREDS; ++j) {
             if (j >= a.k) break;
-            acc += ldg(a.x[j] + i, FIN);
+            acc += ldg(a.x[j], a.x[j] + i, FIN);
         }
-        stg(a.y + i, acc, FOUT);
+        stg(a.y, a.y + i, acc, FOUT);
     }
 }
 
@@ -141,10 +159,14 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
     for (int q = 1; q < NG_MAX_PREDS; ++q)
         if (q < a.k && c >= a.first[q]) base = a.x[q], cin = a.cin[q], lo = a.lo[q], first = a.first[q];
     const float* src = base + ((size_t)(n * cin + lo + c - first)) * a.HW + pix;
-    if (VEC4)
-        stg4(a.y + e, ldg4(src, FIN), FOUT);
-    else
-        stg(a.y + e, ldg(src, FIN), FOUT);
+    if (VEC4) {
+        float4 v;
+        if (FIN) v = make_float4(ldg_any(src, true), ldg_any(src + 1, true), ldg_any(src + 2, true), ldg_any(src + 3, true));
+        else v = *reinterpret_cast<const float4*>(src);
+        stg4(a.y, a.y + e, v, FOUT);
+    } else {
+        stg(a.y, a.y + e, ldg_any(src, FIN), FOUT);
+    }
 }
 
 // ------------------------------------------------------------------------------------
@@ -174,7 +196,7 @@ __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*
         for (int dr = 0; dr < 3; ++dr)
 #pragma unroll
             for (int dc = 0; dc < 3; ++dc)
-                v[p][dr * 3 + dc] = ldg(src + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
+                v[p][dr * 3 + dc] = ldg(a.x, src + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
     }
     __builtin_amdgcn_sched_barrier(0);                       // all loads are issued before the first use
 #pragma unroll
@@ -191,7 +213,7 @@ __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*
                 else acc += in ? v[p][dr * 3 + dc] : 0.f;
                 cnt += in;
             }
-        if (base + p < a.total) stg(a.y + base + p, a.mode == 0 ? acc : acc / (float)cnt, FOUT);
+        if (base + p < a.total) stg(a.y, a.y + base + p, a.mode == 0 ? acc : acc / (float)cnt, FOUT);
     }
 }
 
@@ -222,7 +244,7 @@ __device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*) {
         for (int dr = 0; dr < K; ++dr)
 #pragma unroll
             for (int dc = 0; dc < K; ++dc)
-                v[p][dr * K + dc] = ldg(src + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
+                v[p][dr * K + dc] = ldg(a.x, src + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
     }
     __builtin_amdgcn_sched_barrier(0);                       // all loads are issued before the first use
 #pragma unroll
@@ -236,7 +258,7 @@ __device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*) {
                 const bool in = r >= 0 && r < a.H && cc >= 0 && cc < a.W;
                 acc = fmaf(w[p][dr * K + dc], in ? v[p][dr * K + dc] : 0.f, acc);
             }
-        if (base + p < a.total) stg(a.y + base + p, acc, FOUT);
+        if (base + p < a.total) stg(a.y, a.y + base + p, acc, FOUT);
     }
 }
 
@@ -256,9 +278,9 @@ __device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, 
     if (plane >= a.planes) return;
     const float* src = a.x + (size_t)plane * a.HW;
     float acc = 0.f;
-    for (int p = lane; p < a.HW; p += 64) acc += ldg(src + p, FIN);
+    for (int p = lane; p < a.HW; p += 64) acc += ldg(a.x, src + p, FIN);
     acc = wave_sum(acc);
-    if (lane == 0) stg(a.y + plane, acc / (float)a.HW, FOUT);
+    if (lane == 0) stg(a.y, a.y + plane, acc / (float)a.HW, FOUT);
 }
 
 // ------------------------------------------------------------------------------------
@@ -276,15 +298,15 @@ __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*) 
         if ((a.Cin & 3) == 0) {
             for (int k = lane * 4; k < a.Cin; k += 256) {
                 const float4 wv = *reinterpret_cast<const float4*>(wr + k);
-                const float4 xv = ldg4(xr + k, FIN);
+                const float4 xv = ldg4(a.x, xr + k, FIN);
                 acc = fmaf(wv.x, xv.x, acc), acc = fmaf(wv.y, xv.y, acc);
                 acc = fmaf(wv.z, xv.z, acc), acc = fmaf(wv.w, xv.w, acc);
             }
         } else {
-            for (int k = lane; k < a.Cin; k += 64) acc = fmaf(wr[k], ldg(xr + k, FIN), acc);
+            for (int k = lane; k < a.Cin; k += 64) acc = fmaf(wr[k], ldg(a.x, xr + k, FIN), acc);
         }
         acc = wave_sum(acc);
-        if (lane == 0) stg(a.y + (size_t)n * a.Cout + o, acc + a.b[o], FOUT);
+        if (lane == 0) stg(a.y, a.y + (size_t)n * a.Cout + o, acc + a.b[o], FOUT);
     }
 }
 
@@ -344,7 +366,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
             const float* xc = a.x + (size_t)img * a.Cin * a.HW + pix;
             float v[KC / RK];
 #pragma unroll
-            for (int p = 0; p < KC / RK; ++p) v[p] = ldg(xc + (size_t)min(k0 + tid / TN + p * RK, a.Cin - 1) * a.HW, FIN);
+            for (int p = 0; p < KC / RK; ++p) v[p] = ldg(a.x, xc + (size_t)min(k0 + tid / TN + p * RK, a.Cin - 1) * a.HW, FIN);
 #pragma unroll
             for (int p = 0; p < KC / RK; ++p) {
                 const int k = tid / TN + p * RK;
@@ -380,7 +402,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
                 const int m = m0 + wm * WM + i * 16 + 4 * (lane >> 4) + r;
                 if (m < a.Cout) {
                     const float b = a.bias ? a.bias[m] : 0.f;
-                    stg(a.y + ((size_t)img * a.Cout + m) * a.HW + pix, acc[i][j][r] + b, FOUT);
+                    stg(a.y, a.y + ((size_t)img * a.Cout + m) * a.HW + pix, acc[i][j][r] + b, FOUT);
                 }
             }
         }
@@ -448,7 +470,7 @@ __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, f
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
                 av[i][q] = ap[i][q * 64];
-                bv[i][q] = ldg(xb[i] + off, FIN);
+                bv[i][q] = ldg(a.x, xb[i] + off, FIN);
             }
         }
         __builtin_amdgcn_sched_barrier(0);                   // every load of the chunk is issued before the first use
@@ -485,7 +507,7 @@ __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, f
             const int m = m0 + ti * 16 + 4 * (lane >> 4) + r;
             if (m < a.Cout && col < a.cols) {
                 const float b = a.bias ? a.bias[m] : 0.f;
-                stg(yb + (size_t)m * a.HW, sum + b, FOUT);
+                stg(a.y, yb + (size_t)m * a.HW, sum + b, FOUT);
             }
         }
     }
@@ -541,7 +563,7 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
                 const int cy = t % IW, ci = t / IW;
                 const int gy = iy0 + cy, gx = ix0 + cx, gc = c0 + ci;
                 const bool in = gc < a.Cin && gy >= 0 && gy < a.H && gx >= 0 && gx < a.W;
-                const float v = ldg(xin + ((size_t)min(gc, a.Cin - 1) * a.H + min(max(gy, 0), a.H - 1)) * a.W + min(max(gx, 0), a.W - 1), FIN);
+                const float v = ldg(a.x, xin + ((size_t)min(gc, a.Cin - 1) * a.H + min(max(gy, 0), a.H - 1)) * a.W + min(max(gx, 0), a.W - 1), FIN);
                 pv[q] = in ? v : 0.f;
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -575,7 +597,7 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     if (oy < a.Ho && ox < a.Wo) {
 #pragma unroll
         for (int j = 0; j < CO; ++j)
-            if (co0 + j < a.Cout) stg(a.y + (((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox, acc[j], FOUT);
+            if (co0 + j < a.Cout) stg(a.y, a.y + (((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox, acc[j], FOUT);
     }
 }
 
@@ -789,6 +811,11 @@ int pw_padded_steps(long cin) {
 
 const void* resident_kernel_handle() { return reinterpret_cast<const void*>(&resident_kernel); }
 
+namespace {
+__global__ void empty_kernel() {}
+}  // namespace
+const void* empty_kernel_handle() { return reinterpret_cast<const void*>(&empty_kernel); }
+
 // Floats of library-owned constant memory node v needs (repacked conv1x1 weights), 0 if none.
 // Large pointwise problems (many 64 x 64 tiles) keep the LDS-tiled throughput kernel.
 size_t packed_floats(const ng_graph* g, int v) {
@@ -822,7 +849,7 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
     t.block[0] = kBlock;
     if (nd.op == NG_OP_INPUT) return NG_OK;
     for (size_t j = 0; j < nd.weights.size(); ++j)
-        if (!nd.weights[j]) return g->fail(NG_EINVAL, "node %d: weight %d is a null device pointer", v, (int)j);
+        if (!nd.weights[j] && !g->dry_run) return g->fail(NG_EINVAL, "node %d: weight %d is a null device pointer", v, (int)j);
 
     auto buf = [&](int id) { return reinterpret_cast<float*>(arena + g->offset[id]); };
     const Shape& o = nd.out;

@@ -36,7 +36,7 @@ namespace ng {
 namespace {
 
 constexpr double kSyncNearUs = 1.1;   // completion counter -> dependent workgroup running, same XCD (measured)
-constexpr double kSyncFarUs = 6.0;    // extra cost of a device-scope release + acquire (measured)
+constexpr double kSyncFarUs = 1.5;    // extra cost when producer and consumer sit on different XCDs (measured)
 
 // Expected time of one round (one tile per workgroup) of a task, in microseconds. Rough
 // figures from measurements of the tile functions inside the resident kernel; the planner
@@ -199,3 +199,56 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
 }
 
 }  // namespace ng
+
+extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, double* expected_us, int* n_entries,
+                                    int* n_far_edges, int* coverage_ok) {
+    using namespace ng;
+    if (!g) return NG_EINVAL;
+    if (g->phase < PLANNED) return g->fail(NG_ESTATE, "ng_resident_dry_plan: call ng_plan_memory first");
+    if (n_workgroups < 8 || n_workgroups % 8 != 0 || (xcds != 0 && xcds != 1 && xcds != 2 && xcds != 4 && xcds != 8))
+        return g->fail(NG_EINVAL, "ng_resident_dry_plan: workgroups must be a positive multiple of 8, xcds one of 0, 1, 2, 4, 8");
+    std::vector<Task> saved;
+    saved.swap(g->tasks);
+    g->dry_run = true;
+    g->tasks.assign(g->nodes.size(), Task());
+    int rc = NG_OK;
+    char* fake_arena = reinterpret_cast<char*>(0x100000000ull);
+    static float fake_constants;
+    for (int v = 0; v < (int)g->nodes.size() && rc == NG_OK; ++v) rc = build_task(g, v, fake_arena, &fake_constants, g->tasks[v]);
+    ResidentPlan plan;
+    if (rc == NG_OK && plan_resident(g, n_workgroups, xcds, plan) != NG_OK) rc = g->fail(NG_EINVAL, "too many E' parents");
+    if (rc == NG_OK) {
+        if (expected_us) *expected_us = plan.est_us;
+        if (n_entries) *n_entries = (int)plan.entries.size();
+        int far = 0;
+        for (auto& t : plan.tasks) far += __builtin_popcount(t.far_in);
+        if (n_far_edges) *n_far_edges = far;
+        // invariants: every tile of every task is covered exactly once, lists ascend in task id,
+        // the completions a consumer expects equal the workgroups its producer was split over
+        bool ok = true;
+        std::vector<std::vector<int>> hits(g->nodes.size());
+        std::vector<unsigned> parts(g->nodes.size(), 0);
+        for (int w = 0; w < plan.n_wg; ++w) {
+            int last = -1;
+            for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
+                const DevEntry& en = plan.entries[e];
+                ok = ok && en.task > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step;
+                last = en.task;
+                ++parts[en.task];
+                if (hits[en.task].empty()) hits[en.task].assign((size_t)g->tasks[en.task].ntiles, 0);
+                for (long t = en.tile_begin; t < g->tasks[en.task].ntiles; t += en.tile_step) ++hits[en.task][(size_t)t];
+            }
+        }
+        for (size_t v = 0; v < g->nodes.size(); ++v) {
+            if (!g->tasks[v].fn) continue;
+            ok = ok && hits[v].size() == (size_t)g->tasks[v].ntiles;
+            for (int h : hits[v]) ok = ok && h == 1;
+            const DevTask& d = plan.tasks[v];
+            for (int j = 0; j < d.n_parents; ++j) ok = ok && d.parent[j] < (int)v && d.need[j] == parts[d.parent[j]] && parts[d.parent[j]] > 0;
+        }
+        if (coverage_ok) *coverage_ok = ok;
+    }
+    g->dry_run = false;
+    g->tasks.swap(saved);
+    return rc;
+}

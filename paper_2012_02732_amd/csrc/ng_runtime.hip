@@ -30,6 +30,7 @@ struct Runtime {
     hipGraphExec_t exec[2] = {nullptr, nullptr};
     hipEvent_t t_start = nullptr, t_stop = nullptr;
     float* constants = nullptr;            // library-owned: repacked weights
+    float empty_chain_us = 0.f;            // per-node time of a chain of empty kernels (measured on demand)
     // device-resident replay
     DevPlan plan{};
     void* d_tasks = nullptr;
@@ -43,6 +44,10 @@ struct Runtime {
     double est_us = 0;
     bool counters_dirty = false;
 };
+
+// Duration of an empty kernel by the device's own dispatch timestamps on this GPU (the
+// smallest kernels in a rocprofv3 kernel trace last 1.0 - 1.1 us).
+constexpr float kEmptyKernelUs = 1.0f;
 
 namespace {
 
@@ -401,27 +406,97 @@ int ng_resident_sizes(const ng_graph* g, int* n_workgroups, int* n_entries, int*
     return NG_OK;
 }
 
-int ng_time_task(ng_graph* g, int id, int reps, float* median_us) {
+// Time per node of a graph that is a chain of `reps` copies of one kernel node, launched on
+// the origin stream: the device runs the copies back to back, each waiting for the one before.
+static int chain_time(ng_graph* g, const void* fn, const unsigned grid[3], const unsigned block[3], unsigned lds,
+                      void* arg_block, int reps, float* us_per_node) {
+    Runtime& rt = *g->rt;
+    hipStream_t s = rt.streams[0];
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    NG_HIP(hipGraphCreate(&graph, 0));
+    hipGraphNode_t prev = nullptr;
+    void* args[1] = {arg_block};
+    int rc = NG_OK;
+    for (int i = 0; i < reps && rc == NG_OK; ++i) {
+        hipKernelNodeParams kp{};
+        kp.func = const_cast<void*>(fn);
+        kp.gridDim = dim3(grid[0], grid[1], grid[2]);
+        kp.blockDim = dim3(block[0], block[1], block[2]);
+        kp.sharedMemBytes = lds;
+        kp.kernelParams = arg_block ? args : nullptr;
+        hipGraphNode_t node = nullptr;
+        const hipError_t e = hipGraphAddKernelNode(&node, graph, prev ? &prev : nullptr, prev ? 1 : 0, &kp);
+        if (e != hipSuccess) rc = g->fail(NG_EHIP, "hipGraphAddKernelNode failed: %s", hipGetErrorString(e));
+        prev = node;
+    }
+    hipError_t e = hipSuccess;
+    if (rc == NG_OK && (e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0)) != hipSuccess)
+        rc = g->fail(NG_EHIP, "hipGraphInstantiate failed: %s", hipGetErrorString(e));
+    float best = 1e30f;
+    for (int round = 0; round < 4 && rc == NG_OK; ++round) {      // round 0 warms up; best of the other three
+        if ((e = hipEventRecord(rt.t_start, s)) != hipSuccess || (e = hipGraphLaunch(exec, s)) != hipSuccess ||
+            (e = hipEventRecord(rt.t_stop, s)) != hipSuccess || (e = hipEventSynchronize(rt.t_stop)) != hipSuccess) {
+            rc = g->fail(NG_EHIP, "timing a kernel chain failed: %s", hipGetErrorString(e));
+            break;
+        }
+        float ms = 0.f;
+        if ((e = hipEventElapsedTime(&ms, rt.t_start, rt.t_stop)) != hipSuccess) {
+            rc = g->fail(NG_EHIP, "hipEventElapsedTime failed: %s", hipGetErrorString(e));
+            break;
+        }
+        if (round > 0) best = std::min(best, ms);
+    }
+    if (exec) (void)hipGraphExecDestroy(exec);
+    if (graph) (void)hipGraphDestroy(graph);
+    if (rc == NG_OK) *us_per_node = best * 1000.f / (float)reps;
+    return rc;
+}
+
+int ng_time_replay(ng_graph* g, int reps, float* avg_us) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_time_replay: call ng_capture first");
+    if (reps <= 0 || !avg_us) return g->fail(NG_EINVAL, "ng_time_replay: bad argument");
+    Runtime& rt = *g->rt;
+    hipStream_t s = rt.streams[0];
+    NG_HIP(hipEventRecord(rt.t_start, s));
+    for (int i = 0; i < reps; ++i)
+        if (int rc = ng_replay(g)) return rc;
+    NG_HIP(hipEventRecord(rt.t_stop, s));
+    if (int rc = ng_sync(g)) return rc;
+    float ms = 0.f;
+    NG_HIP(hipEventElapsedTime(&ms, rt.t_start, rt.t_stop));
+    *avg_us = ms * 1000.f / (float)reps;
+    return NG_OK;
+}
+
+int ng_time_chain(ng_graph* g, int id, int reps, float* us_per_node) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < BOUND) return g->fail(NG_ESTATE, "ng_time_chain: call ng_bind first");
+    if (id < -1 || id >= (int)g->nodes.size() || reps <= 0 || reps > 10000 || !us_per_node)
+        return g->fail(NG_EINVAL, "ng_time_chain: bad argument");
+    *us_per_node = 0.f;
+    if (id < 0) {
+        const unsigned one[3] = {1, 1, 1}, wave[3] = {64, 1, 1};
+        return chain_time(g, empty_kernel_handle(), one, wave, 0, nullptr, reps, us_per_node);
+    }
+    Task& t = g->tasks[id];
+    if (!t.fn) return NG_OK;
+    return chain_time(g, t.fn, t.grid, t.block, t.lds_bytes, t.args, reps, us_per_node);
+}
+
+int ng_time_task(ng_graph* g, int id, int reps, float* isolated_us) {
     if (!g) return NG_EINVAL;
     if (g->phase < BOUND) return g->fail(NG_ESTATE, "ng_time_task: call ng_bind first");
-    if (id < 0 || id >= (int)g->nodes.size() || reps <= 0 || !median_us) return g->fail(NG_EINVAL, "ng_time_task: bad argument");
+    if (id < 0 || id >= (int)g->nodes.size() || reps <= 0 || !isolated_us) return g->fail(NG_EINVAL, "ng_time_task: bad argument");
+    *isolated_us = 0.f;
+    if (!g->tasks[id].fn) return NG_OK;
     Runtime& rt = *g->rt;
-    const Task& t = g->tasks[id];
-    *median_us = 0.f;
-    if (!t.fn) return NG_OK;
-    hipStream_t s = rt.streams[0];
-    std::vector<float> ms(reps);
-    void* args[1] = {const_cast<unsigned char*>(t.args)};
-    for (int r = -2; r < reps; ++r) {                          // two untimed warm-ups
-        NG_HIP(hipExtLaunchKernel(t.fn, dim3(t.grid[0], t.grid[1], t.grid[2]), dim3(t.block[0], t.block[1], t.block[2]),
-                                  args, t.lds_bytes, s, rt.t_start, rt.t_stop, 0));
-        NG_HIP(hipEventSynchronize(rt.t_stop));
-        float v = 0.f;
-        NG_HIP(hipEventElapsedTime(&v, rt.t_start, rt.t_stop));
-        if (r >= 0) ms[r] = v;
-    }
-    std::sort(ms.begin(), ms.end());
-    *median_us = ms[reps / 2] * 1000.f;
+    if (rt.empty_chain_us <= 0.f)
+        if (int rc = ng_time_chain(g, -1, 200, &rt.empty_chain_us)) return rc;
+    float c = 0.f;
+    if (int rc = ng_time_chain(g, id, reps, &c)) return rc;
+    *isolated_us = std::max(c - rt.empty_chain_us, 0.f) + kEmptyKernelUs;
     return NG_OK;
 }
 

@@ -183,7 +183,11 @@ def test_isolated_task_times_and_critical_path():
     r.prepare()
     try:
         t = [B.ng_time_task(r.g, v, 20) for v in range(len(w.nodes))]
-        assert t[0] == 0.0 and all(0.2 < x < 500 for x in t[1:]), t
+        assert t[0] == 0.0 and all(0.9 < x < 500 for x in t[1:]), t
+        empty = B.ng_time_chain(r.g, -1, 100)
+        assert 0.3 < empty < 20 and all(B.ng_time_chain(r.g, v, 20) > 0.5 * empty for v in range(1, len(w.nodes)))
+        B.ng_replay_mode(r.g, B.NG_MODE_DEVICE_RESIDENT)
+        assert 1.0 < B.ng_time_replay(r.g, 20) < 1000
         total, path = B.ng_critical_path(r.g, t)
         assert path[0] == 0 and path[-1] == 7 and total <= sum(t) + 1e-3
         assert B.ng_task_kernel(r.g, 1).startswith("conv1x1") and B.ng_task_kernel(r.g, 0) == ""

@@ -221,3 +221,36 @@ def test_bind_rejects_duplicate_stream_handles():
     assert _code(B.ng_bind, g, 4096, need, [0x1000, 0x1000]) == B.NG_EINVAL
     assert "same handle" in B.ng_last_error(g)
     B.ng_destroy(g)
+
+
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+@pytest.mark.parametrize("n_wg,xcds", [(256, 0), (256, 1), (64, 4), (8, 8), (512, 2)])
+def test_device_resident_plan_covers_every_tile_once(name, n_wg, xcds):
+    """The per-workgroup task lists of the device-resident replay, rehearsed on the host:
+    every tile of every task is assigned exactly once, lists ascend in task id (so waits
+    only ever point backwards in every list: no cyclic wait), and the completion count a
+    consumer expects equals the number of workgroups its producer was split over."""
+    r = GraphRunner(workloads.make(name))
+    r.schedule()
+    r.plan()
+    d = B.ng_resident_dry_plan(r.g, n_wg, xcds)
+    assert d["ok"], d
+    n_tasks = sum(nd.op != "input" for nd in r.workload.nodes)
+    assert d["n_entries"] >= n_tasks and d["expected_us"] > 0
+    if xcds == 1:
+        assert d["n_far_edges"] == 0
+    r.close()
+
+
+def test_device_resident_plan_argument_checks():
+    r = GraphRunner(workloads.make("tiny_cell"))
+    with pytest.raises(B.NgError) as e:
+        B.ng_resident_dry_plan(r.g, 256, 0)
+    assert e.value.code == B.NG_ESTATE
+    r.schedule()
+    r.plan()
+    for bad in [(0, 0), (12, 0), (256, 3), (-8, 8)]:
+        with pytest.raises(B.NgError) as e:
+            B.ng_resident_dry_plan(r.g, *bad)
+        assert e.value.code == B.NG_EINVAL
+    r.close()
