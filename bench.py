@@ -26,6 +26,11 @@ if ROOT not in sys.path:
 
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 
+# HBM bytes of one device-resident replay, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
+# scaled by what the same counters read for a plain 256 MiB copy (2.00 and 1.00): the
+# summary with the commands is profiles/resident_kernel_nasnet_style.md.
+MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (38553.4 * 2.00 + 44405.0 * 1.00) * 1024}
+
 MODES = {"graph_multi": 0, "graph_single": 1, "eager_single": 2, "eager_multi": 3, "device_resident": 4}
 
 
@@ -98,6 +103,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-modes", action="store_true")
     ap.add_argument("--per-task", action="store_true", help="also print a per-kernel table to stderr")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy (scale reference for HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no multi-GPU part); use --gpus 1", file=sys.stderr)
@@ -117,6 +124,13 @@ def main():
     n_nodes = len(w.nodes)
     n_tasks = n_nodes - sum(nd.op == "input" for nd in w.nodes)
     mode = MODES[args.mode]
+
+    if args.copy_probe:
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: K replays of the whole DAG -----------------------------------------
     total, lat = time_mode(runner, B, mode, args.steps, args.warmup)
@@ -163,7 +177,8 @@ def main():
         # one launch of resident_kernel executes every task: algorithmic bytes = sum over the tasks
         achieved = all_bytes / dev_us * 1e-3
         roofline = {"kernel": "resident_kernel", "bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS,
-                    "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS, "traffic": None,
+                    "unit": "GB/s", "frac": achieved / PEAK_HBM_GBS,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((args.config, args.mode)),
                     "launches_per_step": 1, "avg_launch_us": dev_us, "algorithmic_bytes_per_launch": all_bytes,
                     "algorithmic_flops_per_launch": all_flops,
                     "note": "latency-bound by construction: the bound that matters is critical_path"}
