@@ -151,12 +151,17 @@ int ng_critical_path(const ng_graph* g, const float* t, float* total, int* path,
  * at least the planned size. hip_streams: HOST array of n_streams DISTINCT hipStream_t values, all
  * on the current device, n_streams >= the scheduled stream count (NG_ENOMEM otherwise).
  * Builds the task table: kernel, launch geometry and argument block with resolved device
- * addresses for every node. */
+ * addresses for every node. Also allocates a library-owned constants buffer (freed by
+ * ng_destroy) and fills it from the conv1x1 weights, repacked into matrix-core operand
+ * order: weight VALUES are read here, so a caller that changes them binds again. */
 int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_streams, int n_streams);
 
-/* Pre-run the network once under stream capture on the bound streams, in submission
- * order with the planned event records/waits, and instantiate executable HIP graphs: one
- * for the multi-stream schedule, one with every task on the origin stream. The arena
+/* Pre-run the network once and make the recorded schedule executable in every replay
+ * mode: a HIP graph of the multi-stream schedule (one kernel node per task in submission
+ * order, an edge from the previous task of the same stream and one per planned event
+ * wait), a HIP graph with every task on the origin stream (recorded by stream capture of
+ * the pre-run), and the device-resident plan (per-workgroup task lists, completion
+ * counters; NG_ENOMEM if the persistent workgroups cannot all be co-resident). The arena
  * contents are overwritten with whatever the pre-run computes from its current input. */
 int ng_capture(ng_graph* g);
 
