@@ -14,10 +14,27 @@ enum Kid : int {
     KID_BN, KID_BN_V4, KID_ADD, KID_ADD_V4, KID_CONCAT, KID_CONCAT_V4, KID_POOL,
     KID_DW_K3S1, KID_DW_K3S2, KID_DW_K5S1, KID_DW_K5S2, KID_GAP, KID_FC_GEMV,
     KID_PW_D4, KID_PW_D8, KID_PW_D16, KID_PW_64, KID_C3_T16S1, KID_C3_T16S2, KID_C3_T8S1, KID_C3_T8S2,
+    KID_BN_T32, KID_ADD_T32,         // elementwise tasks on the tile grid of the direct conv1x1 (resident replay only)
     KID_COUNT
 };
 
-constexpr int kBlock = 256;          // threads per workgroup, every kernel
+// How a kernel splits its output into tiles (see the elementwise tile functions): only tasks
+// with the same partition of same-shaped outputs have matching tiles.
+enum { PART_NONE = -1, PART_L256 = 0, PART_L1024 = 1, PART_T32 = 2 };
+constexpr int partition_of(int kid) {
+    return (kid == KID_BN || kid == KID_ADD || kid == KID_CONCAT || kid == KID_POOL || kid == KID_DW_K3S1 ||
+            kid == KID_DW_K3S2 || kid == KID_DW_K5S1 || kid == KID_DW_K5S2)
+               ? PART_L256
+               : (kid == KID_BN_V4 || kid == KID_ADD_V4 || kid == KID_CONCAT_V4)
+                     ? PART_L1024
+                     : (kid == KID_PW_D4 || kid == KID_PW_D8 || kid == KID_PW_D16 || kid == KID_BN_T32 || kid == KID_ADD_T32)
+                           ? PART_T32
+                           : PART_NONE;
+}
+
+constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
+constexpr int kSubs = 2;             // tiles a workgroup of the resident kernel works on at a time
+constexpr int kGroup = kBlock * kSubs;  // threads per workgroup of the resident kernel
 constexpr int kArgBytes = 256;       // size of the per-task argument block
 
 // ---- argument blocks (plain data, <= kArgBytes) ---------------------------------------
@@ -32,6 +49,7 @@ struct BnArgs {
     int relu;
     int C, HW;
     int total;            // elements
+    int cols, tiles_n;    // 32 x 32 partition: columns (N * HW) and tiles along them
 };
 
 struct AddArgs {
@@ -39,6 +57,7 @@ struct AddArgs {
     float* y;
     int k;
     int total;
+    int C, HW, cols, tiles_n;  // 32 x 32 partition: channels, pixels per plane, columns (N * HW), tiles along them
 };
 
 struct ConcatArgs {
@@ -125,17 +144,31 @@ struct DevTask {
     alignas(16) unsigned char args[kArgBytes];
 };
 
-struct DevEntry {                    // one task in one workgroup's list
+struct DevEntry {                    // one task in one workgroup's list; tiles are counted in units of kSubs
     int task;
     int tile_begin;
     int tile_step;
     int pad_;
 };
 
+// What the resident kernel reads: one self-contained record per (workgroup, task) entry, the
+// records of one workgroup contiguous, so that a workgroup copies its whole list into LDS
+// with coalesced loads and never waits for a task description while it runs.
+constexpr int kRecordWords = 24 + kArgWords;     // 288 bytes, a multiple of 16
+constexpr int kRecordsInLds = 128;               // records a workgroup holds in LDS at a time (then it reloads)
+struct DevRecord {
+    int task, kid, ntiles, n_parents;
+    int tile_begin, tile_step;                   // in units of kSubs tiles
+    int far_in, far_out;                         // != 0: device-scope loads of activations / stores of the result
+    int parent[NG_MAX_PREDS];
+    unsigned need[NG_MAX_PREDS];
+    unsigned args[kArgWords];
+};
+static_assert(sizeof(DevRecord) == kRecordWords * 4 && sizeof(DevRecord) % 16 == 0, "record layout");
+
 struct DevPlan {
-    const DevTask* tasks;            // [n_nodes]
-    const DevEntry* entries;         // concatenated per-workgroup lists, each in ascending task id
-    const int* wg_first;             // [n_wg + 1] offsets into entries
+    const DevRecord* records;        // concatenated per-workgroup lists, each in ascending task id
+    const int* wg_first;             // [n_wg + 1] offsets into records
     unsigned* done;                  // [n_nodes] completion counters, never reset between replays
     int* error_dev;                  // != 0 once any wait ran out of spins
     int* error_host;                 // same value in pinned host memory, for the host to read

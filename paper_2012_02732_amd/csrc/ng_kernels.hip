@@ -93,11 +93,40 @@ __device__ __forceinline__ void bn_coeff(const BnArgs& a, int c, float& s, float
     }
 }
 
-template <bool VEC4, bool FIN, bool FOUT>
-__device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*) {
-    const int i = tile * kBlock + threadIdx.x;
-    if (VEC4) {                                   // HW % 4 == 0: a float4 never straddles channels
-        const int e = i * 4;
+// Elementwise operators come in three partitions of the output into tiles, so that an
+// elementwise task can take over the partition of the task that feeds it (then tile i of
+// the consumer reads only what tile i of the producer wrote, and a workgroup that ran the
+// one can run the other without waiting for anybody else):
+//   PART_L256  tile t = elements [256 t, 256 t + 256), one per thread (pool, dwconv order)
+//   PART_L1024 tile t = elements [1024 t, 1024 t + 1024), one float4 per thread
+//   PART_T32   tile t = 32 channels x 32 columns (column = image * HW + pixel), the output
+//              tile of the direct conv1x1; thread = (row tid / 32 + 8 j, column tid % 32), j < 4
+
+// element offsets (and validity) of the up to 4 elements a thread owns in a PART_T32 tile
+struct T32Index {
+    int e[4];
+    bool ok[4];
+};
+__device__ __forceinline__ T32Index t32_index(int tile, int tid, int tiles_n, int C, int HW, int cols) {
+    const int by = tile / tiles_n, bx = tile - by * tiles_n;
+    const int col = bx * 32 + (tid & 31);
+    const int ccol = min(col, cols - 1);
+    const int img = ccol / HW, pix = ccol - img * HW;
+    T32Index r;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int m = by * 32 + (tid >> 5) + 8 * j;
+        r.ok[j] = m < C && col < cols;
+        r.e[j] = (img * C + min(m, C - 1)) * HW + pix;
+    }
+    return r;
+}
+
+template <int PART, bool FIN, bool FOUT>
+__device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, int tid, bool live) {
+    if (!live) return;
+    if (PART == PART_L1024) {                     // HW % 4 == 0: a float4 never straddles channels
+        const int e = (tile * kBlock + tid) * 4;
         if (e >= a.total) return;
         float s, t;
         bn_coeff(a, (e / a.HW) % a.C, s, t);
@@ -105,23 +134,38 @@ __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*) {
         v.x = fmaf(v.x, s, t), v.y = fmaf(v.y, s, t), v.z = fmaf(v.z, s, t), v.w = fmaf(v.w, s, t);
         if (a.relu) v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
         stg4(a.y, a.y + e, v, FOUT);
-    } else {
+    } else if (PART == PART_L256) {
+        const int i = tile * kBlock + tid;
         if (i >= a.total) return;
         float s, t;
         bn_coeff(a, (i / a.HW) % a.C, s, t);
         float v = fmaf(ldg(a.x, a.x + i, FIN), s, t);
         stg(a.y, a.y + i, a.relu ? fmaxf(v, 0.f) : v, FOUT);
+    } else {
+        const T32Index ix = t32_index(tile, tid, a.tiles_n, a.C, a.HW, a.cols);
+        float v[4], s[4], t[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            v[j] = ldg(a.x, a.x + ix.e[j], FIN);
+            bn_coeff(a, min((tile / a.tiles_n) * 32 + (tid >> 5) + 8 * j, a.C - 1), s[j], t[j]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float r = fmaf(v[j], s[j], t[j]);
+            if (ix.ok[j]) stg(a.y, a.y + ix.e[j], a.relu ? fmaxf(r, 0.f) : r, FOUT);
+        }
     }
 }
 
 // ------------------------------------------------------------------------------------
 // add_n: elementwise sum of k tensors, accumulated in argument order
 // ------------------------------------------------------------------------------------
-template <bool VEC4, bool FIN, bool FOUT>
-__device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*) {
-    const int i = tile * kBlock + threadIdx.x;
-    if (VEC4) {
-        const int e = i * 4;
+template <int PART, bool FIN, bool FOUT>
+__device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, int tid, bool live) {
+    if (!live) return;
+    if (PART == PART_L1024) {
+        const int e = (tile * kBlock + tid) * 4;
         if (e >= a.total) return;
         float4 acc = ldg4(a.x[0], a.x[0] + e, FIN);
 #pragma unroll
@@ -131,7 +175,8 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*) {
             acc.x += v.x, acc.y += v.y, acc.z += v.z, acc.w += v.w;
         }
         stg4(a.y, a.y + e, acc, FOUT);
-    } else {
+    } else if (PART == PART_L256) {
+        const int i = tile * kBlock + tid;
         if (i >= a.total) return;
         float acc = ldg(a.x[0], a.x[0] + i, FIN);
 #pragma unroll
@@ -140,6 +185,23 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*) {
             acc += ldg(a.x[j], a.x[j] + i, FIN);
         }
         stg(a.y, a.y + i, acc, FOUT);
+    } else {
+        const T32Index ix = t32_index(tile, tid, a.tiles_n, a.C, a.HW, a.cols);
+        float acc[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = ldg(a.x[0], a.x[0] + ix.e[q], FIN);
+#pragma unroll
+        for (int j = 1; j < NG_MAX_PREDS; ++j) {
+            if (j >= a.k) break;
+            float v[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = ldg(a.x[j], a.x[j] + ix.e[q], FIN);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] += v[q];
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (ix.ok[q]) stg(a.y, a.y + ix.e[q], acc[q], FOUT);
     }
 }
 
@@ -147,8 +209,9 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*) {
 // concat: output channel block j = channels [lo_j, lo_j + cnt_j) of input j
 // ------------------------------------------------------------------------------------
 template <bool VEC4, bool FIN, bool FOUT>
-__device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float*) {
-    const int i = tile * kBlock + threadIdx.x;
+__device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float*, int tid, bool live) {
+    if (!live) return;
+    const int i = tile * kBlock + tid;
     const int e = VEC4 ? i * 4 : i;
     if (e >= a.total) return;
     const int plane = e / a.HW, pix = e - plane * a.HW;
@@ -177,10 +240,10 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
 constexpr int kPoolPerThread = 1;
 
 template <bool FIN, bool FOUT>
-__device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*) {
+__device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*, int tid, bool live) {
     constexpr int P = kPoolPerThread;
-    const int base = (tile * kBlock + threadIdx.x) * P;
-    if (base >= a.total) return;
+    const int base = (tile * kBlock + tid) * P;
+    if (!live || base >= a.total) return;
     // all taps of all P outputs are loaded unconditionally from clamped coordinates, so the
     // loads are independent and in flight together; taps outside the image are masked afterwards
     float v[P][9];
@@ -223,10 +286,10 @@ __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*
 constexpr int dw_per_thread(int k) { return 1; }
 
 template <int K, int S, bool FIN, bool FOUT>
-__device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*) {
+__device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*, int tid, bool live) {
     constexpr int P = dw_per_thread(K);
-    const int base = (tile * kBlock + threadIdx.x) * P;
-    if (base >= a.total) return;
+    const int base = (tile * kBlock + tid) * P;
+    if (!live || base >= a.total) return;
     // unconditional loads from clamped coordinates (all in flight together), masked afterwards
     float v[P][K * K], w[P][K * K];
     int r0[P], c0[P];
@@ -272,10 +335,10 @@ __device__ __forceinline__ float wave_sum(float v) {
 }
 
 template <bool FIN, bool FOUT>
-__device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, float*) {
-    const int lane = threadIdx.x & 63;
-    const int plane = tile * (kBlock / 64) + (threadIdx.x >> 6);
-    if (plane >= a.planes) return;
+__device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, float*, int tid, bool live) {
+    const int lane = tid & 63;
+    const int plane = tile * (kBlock / 64) + (tid >> 6);
+    if (!live || plane >= a.planes) return;
     const float* src = a.x + (size_t)plane * a.HW;
     float acc = 0.f;
     for (int p = lane; p < a.HW; p += 64) acc += ldg(a.x, src + p, FIN);
@@ -287,10 +350,10 @@ __device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, 
 // fc (small batch): one wavefront per output feature; y[n][o] = <W[o], x[n]> + b[o]
 // ------------------------------------------------------------------------------------
 template <bool FIN, bool FOUT>
-__device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*) {
-    const int lane = threadIdx.x & 63;
-    const int o = tile * (kBlock / 64) + (threadIdx.x >> 6);
-    if (o >= a.Cout) return;
+__device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*, int tid, bool live) {
+    const int lane = tid & 63;
+    const int o = tile * (kBlock / 64) + (tid >> 6);
+    if (!live || o >= a.Cout) return;
     const float* wr = a.w + (size_t)o * a.Cin;
     for (int n = 0; n < a.N; ++n) {
         const float* xr = a.x + (size_t)n * a.Cin;
@@ -318,7 +381,7 @@ __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*) 
 // slices of KC staged through LDS (A transposed to [k][m] so both fragments read rows).
 // ------------------------------------------------------------------------------------
 template <int TM, int TN, int KC, bool FIN, bool FOUT>
-__device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, float* smem) {
+__device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, float* smem, int tid, bool live) {
     constexpr int WM = TM / 2, WN = TN / 2;           // per-wavefront sub-tile
     constexpr int FM = WM / 16, FN = WN / 16;         // 16 x 16 fragments per wavefront
     constexpr int LDA = TM + 1, LDB = TN + 1;
@@ -327,7 +390,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
     float* As = smem;                                 // [KC][LDA]
     float* Bs = smem + KC * LDA;                      // [KC][LDB]
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
     const int m0 = by * TM, n0 = bx * TN;
@@ -395,7 +458,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             const int col = n0 + wn * WN + j * 16 + (lane & 15);
-            if (col >= a.cols) continue;
+            if (col >= a.cols || !live) continue;
             const int img = col / a.HW, pix = col - img * a.HW;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -433,8 +496,8 @@ __global__ __launch_bounds__(kBlock) void pack_pw_weights_kernel(const float* w,
 }
 
 template <int CH, bool FIN, bool FOUT>                      // CH k steps per chunk: 4 * CH loads in flight per lane
-__device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, float* smem) {
-    const int tid = threadIdx.x, lane = tid & 63;
+__device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, float* smem, int tid, bool live) {
+    const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
     const int m0 = by * 32, n0 = bx * 32;
@@ -505,7 +568,7 @@ __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, f
 #pragma unroll
             for (int w2 = 1; w2 < 4; ++w2) sum += smem[((w2 * 4 + wave) * 4 + r) * 64 + lane];
             const int m = m0 + ti * 16 + 4 * (lane >> 4) + r;
-            if (m < a.Cout && col < a.cols) {
+            if (m < a.Cout && col < a.cols && live) {
                 const float b = a.bias ? a.bias[m] : 0.f;
                 stg(a.y, yb + (size_t)m * a.HW, sum + b, FOUT);
             }
@@ -523,7 +586,7 @@ __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, f
 // Tile index = (image * co_groups + channel group) * tiles_xy + pixel tile.
 // ------------------------------------------------------------------------------------
 template <int TP, int S, bool FIN, bool FOUT>
-__device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* smem) {
+__device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* smem, int tid, bool live) {
     constexpr int CIC = S == 2 && TP == 16 ? 2 : 4;    // input channels per LDS slice
     constexpr int IW = (TP - 1) * S + 3;               // input patch edge
     constexpr int LDP = IW + 1;
@@ -532,7 +595,6 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     static_assert(CIC * IW * LDP <= kSmemFloats, "LDS budget");
     float* patch = smem;                               // [CIC][IW][LDP]
 
-    const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int local = TP == 16 ? tid : (tid & 63);
     const int ty = local / TP, tx = local % TP;
@@ -594,7 +656,7 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
         }
         __syncthreads();
     }
-    if (oy < a.Ho && ox < a.Wo) {
+    if (oy < a.Ho && ox < a.Wo && live) {
 #pragma unroll
         for (int j = 0; j < CO; ++j)
             if (co0 + j < a.Cout) stg(a.y, a.y + (((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox, acc[j], FOUT);
@@ -612,14 +674,16 @@ template <int KID> struct KernelOf;
         using Args = ARGS;                                                                     \
         static constexpr const char* name = NAME;                                              \
         template <bool FIN, bool FOUT>                                                         \
-        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem) {       \
-            __VA_ARGS__, FIN, FOUT > (a, t, smem);                                             \
+        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live) { \
+            __VA_ARGS__, FIN, FOUT > (a, t, smem, tid, live);                                  \
         }                                                                                      \
     };
-NG_KERNEL(KID_BN, BnArgs, "bn_act", bn_act_tile < false)
-NG_KERNEL(KID_BN_V4, BnArgs, "bn_act_v4", bn_act_tile < true)
-NG_KERNEL(KID_ADD, AddArgs, "add_n", add_n_tile < false)
-NG_KERNEL(KID_ADD_V4, AddArgs, "add_n_v4", add_n_tile < true)
+NG_KERNEL(KID_BN, BnArgs, "bn_act", bn_act_tile < PART_L256)
+NG_KERNEL(KID_BN_V4, BnArgs, "bn_act_v4", bn_act_tile < PART_L1024)
+NG_KERNEL(KID_BN_T32, BnArgs, "bn_act_t32", bn_act_tile < PART_T32)
+NG_KERNEL(KID_ADD, AddArgs, "add_n", add_n_tile < PART_L256)
+NG_KERNEL(KID_ADD_V4, AddArgs, "add_n_v4", add_n_tile < PART_L1024)
+NG_KERNEL(KID_ADD_T32, AddArgs, "add_n_t32", add_n_tile < PART_T32)
 NG_KERNEL(KID_CONCAT, ConcatArgs, "concat", concat_tile < false)
 NG_KERNEL(KID_CONCAT_V4, ConcatArgs, "concat_v4", concat_tile < true)
 NG_KERNEL(KID_DW_K3S1, DwArgs, "dwconv_k3s1", dwconv_tile < 3, 1)
@@ -641,8 +705,8 @@ NG_KERNEL(KID_C3_T8S2, C3Args, "conv3x3_t8s2", conv3x3_tile < 8, 2)
         using Args = ARGS;                                                                     \
         static constexpr const char* name = NAME;                                              \
         template <bool FIN, bool FOUT>                                                         \
-        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem) {       \
-            FN<FIN, FOUT>(a, t, smem);                                                         \
+        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live) { \
+            FN<FIN, FOUT>(a, t, smem, tid, live);                                              \
         }                                                                                      \
     };
 NG_KERNEL0(KID_POOL, PoolArgs, "pool3x3", pool3x3_tile)
@@ -654,7 +718,7 @@ NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
 template <int KID>
 __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KID>::Args a) {
     __shared__ float smem[kSmemFloats];
-    KernelOf<KID>::template tile<false, false>(a, blockIdx.x, smem);
+    KernelOf<KID>::template tile<false, false>(a, blockIdx.x, smem, threadIdx.x, true);
 }
 
 // ------------------------------------------------------------------------------------
@@ -671,112 +735,116 @@ __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KI
 // stored and loaded with device-scope accesses, so no L2 is ever flushed or invalidated. Every wait is bounded: a workgroup that runs out of
 // spins raises the error flag and every workgroup leaves.
 // ------------------------------------------------------------------------------------
-typedef const __attribute__((address_space(4))) DevTask* ConstTaskPtr;
-typedef const __attribute__((address_space(4))) DevEntry* ConstEntryPtr;
-typedef const __attribute__((address_space(4))) int* ConstIntPtr;
-
-struct ArgWords {
-    unsigned w[kArgWords];
-};
-
+// One resident workgroup = kSubs sub-blocks of kBlock threads; sub-block `sub` takes tile
+// unit * kSubs + sub of every unit the workgroup owns. All sub-blocks walk the same number of
+// units (tile functions may contain workgroup barriers): a sub-block whose tile does not
+// exist runs tile 0 with `live` false (loads stay in bounds, nothing is stored) or returns.
+// `words` points at the record's argument block in LDS; it is the same for every lane, so
+// each word is moved into a scalar register.
 template <int KID>
-__device__ __forceinline__ void run_tiles(const ArgWords& blk, int tile, int step, int ntiles, float* smem, bool fin,
-                                          bool fout) {
+__device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int step, int ntiles, float* smem, int sub, int tid,
+                                          bool fin, bool fout) {
     using A = typename KernelOf<KID>::Args;
-    static_assert(sizeof(A) <= sizeof(ArgWords) && sizeof(A) % 4 == 0, "argument block does not fit the prefetch");
+    static_assert(sizeof(A) <= kArgWords * 4 && sizeof(A) % 4 == 0, "argument block does not fit the record");
+    unsigned w[sizeof(A) / 4];
+#pragma unroll
+    for (size_t i = 0; i < sizeof(A) / 4; ++i) w[i] = __builtin_amdgcn_readfirstlane(words[i]);
     A a;
-    __builtin_memcpy(&a, blk.w, sizeof(A));
-    if (!fin && !fout) {
-        for (; tile < ntiles; tile += step) KernelOf<KID>::template tile<false, false>(a, tile, smem);
-    } else if (!fin) {
-        for (; tile < ntiles; tile += step) KernelOf<KID>::template tile<false, true>(a, tile, smem);
-    } else if (!fout) {
-        for (; tile < ntiles; tile += step) KernelOf<KID>::template tile<true, false>(a, tile, smem);
-    } else {
-        for (; tile < ntiles; tile += step) KernelOf<KID>::template tile<true, true>(a, tile, smem);
+    __builtin_memcpy(&a, w, sizeof(A));
+    const int nunits = (ntiles + kSubs - 1) / kSubs;
+#define NG_LOOP(FI, FO)                                                              \
+    for (; unit < nunits; unit += step) {                                            \
+        const int tile = unit * kSubs + sub;                                         \
+        const bool live = tile < ntiles;                                             \
+        KernelOf<KID>::template tile<FI, FO>(a, live ? tile : 0, smem, tid, live);   \
     }
+    if (!fin && !fout) { NG_LOOP(false, false) }
+    else if (!fin) { NG_LOOP(false, true) }
+    else if (!fout) { NG_LOOP(true, false) }
+    else { NG_LOOP(true, true) }
+#undef NG_LOOP
 }
 
-__global__ __launch_bounds__(kBlock) void resident_kernel(DevPlan plan, unsigned epoch) {
-    __shared__ float smem[kSmemFloats];
+__global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned epoch) {
+    __shared__ float smem_all[kSubs * kSmemFloats];
+    __shared__ uint4 recs[kRecordsInLds * (kRecordWords / 4)];
     __shared__ int s_abort;
     const int lane = threadIdx.x;
+    const int sub = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kBlock), tid = (int)threadIdx.x % kBlock;
+    float* smem = smem_all + sub * kSmemFloats;
     if (lane == 0) s_abort = 0;
-    ConstTaskPtr tasks = (ConstTaskPtr)plan.tasks;
-    ConstEntryPtr entries = (ConstEntryPtr)plan.entries;
-    ConstIntPtr wg_first = (ConstIntPtr)plan.wg_first;
-    const int e_begin = wg_first[blockIdx.x], e_end = wg_first[blockIdx.x + 1];
-    __syncthreads();
+    const int e_begin = plan.wg_first[blockIdx.x], e_end = plan.wg_first[blockIdx.x + 1];
 
-    for (int e = e_begin; e < e_end; ++e) {
-        const int task = entries[e].task, tile0 = entries[e].tile_begin, step = entries[e].tile_step;
-        ConstTaskPtr t = tasks + task;
-        // Everything the task needs is fetched (uniform addresses, read-only space: scalar
-        // loads into SGPRs) before the wait, so the fetch overlaps with it.
-        const int kid = t->kid, ntiles = t->ntiles, np = t->n_parents;
-        const bool far_in = t->far_in != 0, far_out = t->release_far != 0;
-        ArgWords blk;
+    for (int chunk = e_begin; chunk < e_end; chunk += kRecordsInLds) {
+        // this workgroup's next records: global memory -> LDS, 16 bytes per lane and load
+        const int count = min(kRecordsInLds, e_end - chunk);
+        __syncthreads();                                        // the previous chunk is no longer read
         {
-            const __attribute__((address_space(4))) unsigned* src =
-                reinterpret_cast<const __attribute__((address_space(4))) unsigned*>(t->args);
-#pragma unroll
-            for (int i = 0; i < kArgWords; ++i) blk.w[i] = src[i];
+            const uint4* src = reinterpret_cast<const uint4*>(plan.records + chunk);
+            for (int i = lane; i < count * (kRecordWords / 4); i += kGroup) recs[i] = src[i];
         }
-        const bool tracer = plan.trace != nullptr && tile0 == 0 && lane == 0;
-        if (tracer) plan.trace[3 * task] = wall_clock64();
-        if (np > 0) {
-            if (lane < 64) {                                    // first wavefront: lane j watches parent j
-                bool ok = true;
-                if (lane < np) {
-                    const DevTask* tg = plan.tasks + task;      // per-lane index: ordinary loads
-                    const unsigned target = tg->need[lane] * epoch;
-                    const unsigned* counter = plan.done + (size_t)tg->parent[lane] * plan.done_stride;
-                    unsigned spins = 0;
-                    while ((int)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-                        if (++spins > plan.spin_limit ||
-                            ((spins & 63u) == 0 && __hip_atomic_load(plan.error_dev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                            ok = false;
-                            break;
+        __syncthreads();
+        for (int e = 0; e < count; ++e) {
+            const unsigned* rec = reinterpret_cast<const unsigned*>(recs + e * (kRecordWords / 4));
+            const int task = __builtin_amdgcn_readfirstlane(rec[0]), kid = __builtin_amdgcn_readfirstlane(rec[1]);
+            const int ntiles = __builtin_amdgcn_readfirstlane(rec[2]), np = __builtin_amdgcn_readfirstlane(rec[3]);
+            const int tile0 = __builtin_amdgcn_readfirstlane(rec[4]), step = __builtin_amdgcn_readfirstlane(rec[5]);
+            const bool far_in = __builtin_amdgcn_readfirstlane(rec[6]) != 0, far_out = __builtin_amdgcn_readfirstlane(rec[7]) != 0;
+            const bool tracer = plan.trace != nullptr && tile0 == 0 && lane == 0;
+            if (tracer) plan.trace[3 * task] = wall_clock64();
+            if (np > 0) {
+                if (lane < 64) {                                    // first wavefront: lane j watches parent j
+                    bool ok = true;
+                    if (lane < np) {
+                        const unsigned target = rec[16 + lane] * epoch;
+                        const unsigned* counter = plan.done + (size_t)rec[8 + lane] * plan.done_stride;
+                        unsigned spins = 0;
+                        while ((int)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+                            if (++spins > plan.spin_limit ||
+                                ((spins & 63u) == 0 && __hip_atomic_load(plan.error_dev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                                ok = false;
+                                break;
+                            }
+                            if (plan.poll_sleep == 0) __builtin_amdgcn_s_sleep(1);
+                            else if (plan.poll_sleep == 1) __builtin_amdgcn_s_sleep(4);
+                            else __builtin_amdgcn_s_sleep(16);
                         }
-                        if (plan.poll_sleep == 0) __builtin_amdgcn_s_sleep(1);
-                        else if (plan.poll_sleep == 1) __builtin_amdgcn_s_sleep(4);
-                        else __builtin_amdgcn_s_sleep(16);
+                        if (!ok && spins > plan.spin_limit) {
+                            atomicExch(plan.error_dev, task + 1);
+                            *plan.error_host = task + 1;
+                        }
                     }
-                    if (!ok && spins > plan.spin_limit) {
-                        atomicExch(plan.error_dev, task + 1);
-                        *plan.error_host = task + 1;
+                    if (__any(!ok)) {
+                        if (lane == 0) s_abort = 1;
                     }
+                    // Make the producers' stores visible to this compute unit. Producers on this
+                    // XCD have their results in the shared L2 already: dropping this CU's vector
+                    // L1 is enough (what a workgroup-scope acquire does when the waves of a
+                    // workgroup sit on different CUs). Tensors produced on another XCD are never
+                    // cached here at all: their loads are device-scope accesses (far_in).
+                    asm volatile("buffer_inv sc0" ::: "memory");
                 }
-                if (__any(!ok)) {
-                    if (lane == 0) s_abort = 1;
-                }
-                // Make the producers' stores visible to this compute unit. Producers on this
-                // XCD have their results in the shared L2 already: dropping this CU's vector
-                // L1 is enough (what a workgroup-scope acquire does when the waves of a
-                // workgroup sit on different CUs). Tensors produced on another XCD are never
-                // cached here at all: their loads are device-scope accesses (far_in mask).
-                asm volatile("buffer_inv sc0" ::: "memory");
+                __syncthreads();                                    // also waits for the invalidate to finish
+                if (s_abort) return;
             }
-            __syncthreads();                                    // also waits for the invalidate to finish
-            if (s_abort) return;
-        }
-        if (tracer) plan.trace[3 * task + 1] = wall_clock64();
-        switch (kid) {
-#define NG_CASE(KID) case KID: run_tiles<KID>(blk, tile0, step, ntiles, smem, far_in, far_out); break;
-            NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4) NG_CASE(KID_CONCAT)
-            NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
-            NG_CASE(KID_DW_K5S1) NG_CASE(KID_DW_K5S2) NG_CASE(KID_GAP) NG_CASE(KID_FC_GEMV)
-            NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_C3_T16S1) NG_CASE(KID_C3_T16S2)
-            NG_CASE(KID_C3_T8S1) NG_CASE(KID_C3_T8S2)
+            if (tracer) plan.trace[3 * task + 1] = wall_clock64();
+            switch (kid) {
+#define NG_CASE(KID) case KID: run_tiles<KID>(rec + 24, tile0, step, ntiles, smem, sub, tid, far_in, far_out); break;
+                NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_T32) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4) NG_CASE(KID_ADD_T32)
+                NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
+                NG_CASE(KID_DW_K5S1) NG_CASE(KID_DW_K5S2) NG_CASE(KID_GAP) NG_CASE(KID_FC_GEMV)
+                NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_C3_T16S1)
+                NG_CASE(KID_C3_T16S2) NG_CASE(KID_C3_T8S1) NG_CASE(KID_C3_T8S2)
 #undef NG_CASE
-            default: break;
-        }
-        __syncthreads();                 // every thread's stores have reached L2 (write-through L1, counted stores)
-        if (tracer) plan.trace[3 * task + 2] = wall_clock64();
-        if (lane == 0) {
-            // Publish completion. Readers on this XCD see the data in the shared L2; if there
-            // are readers elsewhere the tile functions have stored through to the memory side.
-            __hip_atomic_fetch_add(plan.done + (size_t)task * plan.done_stride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                default: break;
+            }
+            __syncthreads();             // every thread's stores have reached L2 (write-through L1, counted stores)
+            if (tracer) plan.trace[3 * task + 2] = wall_clock64();
+            if (lane == 0) {
+                // Publish completion. Readers on this XCD see the data in the shared L2; if there
+                // are readers elsewhere the tile functions have stored through to the memory side.
+                __hip_atomic_fetch_add(plan.done + (size_t)task * plan.done_stride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }
@@ -872,6 +940,7 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.relu = 1;
             }
             a.C = (int)o.c, a.HW = hw_out, a.total = total;
+            a.cols = (int)(o.n * hw_out), a.tiles_n = (int)ceil_div(a.cols, 32);
             if (hw_out % 4 == 0) set_kernel<KID_BN_V4>(t, a, ceil_div(total / 4, kBlock));
             else set_kernel<KID_BN>(t, a, ceil_div(total, kBlock));
             break;
@@ -882,6 +951,7 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             for (int j = 0; j < NG_MAX_PREDS; ++j) a.x[j] = buf(nd.preds[j < a.k ? j : 0]);
             a.y = buf(v);
             a.total = total;
+            a.C = (int)o.c, a.HW = hw_out, a.cols = (int)(o.n * hw_out), a.tiles_n = (int)ceil_div(a.cols, 32);
             if (total % 4 == 0) set_kernel<KID_ADD_V4>(t, a, ceil_div(total / 4, kBlock));
             else set_kernel<KID_ADD>(t, a, ceil_div(total, kBlock));
             break;

@@ -25,6 +25,7 @@
 //     *all* direct readers (edges of E): a reader on another XCD reads the tensor itself, even
 //     when it only waits for an intermediate task.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <numeric>
 
@@ -37,17 +38,18 @@ namespace {
 
 constexpr double kSyncNearUs = 1.1;   // completion counter -> dependent workgroup running, same XCD (measured)
 constexpr double kSyncFarUs = 1.5;    // extra cost when producer and consumer sit on different XCDs (measured)
+constexpr double kPublishUs = 0.3;    // stores drained and counter bumped: the workgroup moves on to its next entry
+constexpr double kLocalUs = 0.1;      // hand-over inside one workgroup: one barrier
 
-// Expected time of one round (one tile per workgroup) of a task, in microseconds. Rough
+// Expected time of one round (kSubs tiles per workgroup) of a task, in microseconds. Rough
 // figures from measurements of the tile functions inside the resident kernel; the planner
 // only needs them to be ordered sensibly.
-double tile_round_us(const ng_graph* g, int v) {
-    const Task& t = g->tasks[v];
+double tile_round_us(const ng_graph* g, int v, int kid) {
     const Node& nd = g->nodes[v];
     const double cin = nd.preds.empty() ? 0.0 : (double)g->nodes[nd.preds[0]].out.c;
-    switch (t.kid) {
-        case KID_BN: case KID_BN_V4: return 0.8;
-        case KID_ADD: case KID_ADD_V4: return 0.5;
+    switch (kid) {
+        case KID_BN: case KID_BN_V4: case KID_BN_T32: return 0.8;
+        case KID_ADD: case KID_ADD_V4: case KID_ADD_T32: return 0.5;
         case KID_CONCAT: case KID_CONCAT_V4: return 0.8;
         case KID_POOL: case KID_DW_K3S1: case KID_DW_K3S2: return 1.5;
         case KID_DW_K5S1: case KID_DW_K5S2: return 1.9;
@@ -60,10 +62,32 @@ double tile_round_us(const ng_graph* g, int v) {
     }
 }
 
+// The kernel variant of an elementwise task that uses partition `part` (KID_NONE if there is
+// none), and the number of tiles that partition has.
+int variant_for(const ng_graph* g, int v, int part, long* ntiles) {
+    const Node& nd = g->nodes[v];
+    const Shape& o = nd.out;
+    const long total = o.elems(), hw = o.h * o.w, cols = o.n * hw;
+    const bool bn = nd.op == NG_OP_BN_ACT || nd.op == NG_OP_RELU, add = nd.op == NG_OP_ADD_N;
+    if (!bn && !add) return KID_NONE;
+    switch (part) {
+        case PART_L256: *ntiles = (total + kBlock - 1) / kBlock; return bn ? KID_BN : KID_ADD;
+        case PART_L1024:
+            if ((bn && hw % 4 != 0) || (add && total % 4 != 0)) return KID_NONE;
+            *ntiles = (total / 4 + kBlock - 1) / kBlock;
+            return bn ? KID_BN_V4 : KID_ADD_V4;
+        case PART_T32: *ntiles = ((cols + 31) / 32) * ((o.c + 31) / 32); return bn ? KID_BN_T32 : KID_ADD_T32;
+        default: return KID_NONE;
+    }
+}
+
 struct Sim {
     std::vector<std::vector<DevEntry>> lists;
     std::vector<unsigned> parts;
     std::vector<int> xcd;
+    std::vector<int> kid;            // kernel variant chosen for the resident replay
+    std::vector<long> ntiles;        // its tile count
+    std::vector<int> local_parent;   // E' parent whose completion this task does not wait for (same workgroups, same tiles), or -1
     double makespan = 0;
 };
 
@@ -71,9 +95,13 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     const Schedule& sc = g->sched;
     const int n = (int)g->nodes.size();
     const int per_xcd = n_wg / 8;
+    const bool debug = getenv("NG_PLAN_DEBUG") != nullptr;
+    const bool allow_local = getenv("NG_NO_LOCAL") == nullptr;
 
+    // the planner counts work in units of kSubs tiles: what one workgroup does in one round
+    auto units_for = [&](long ntiles) { return (ntiles + kSubs - 1) / kSubs; };
     std::vector<long> stream_work(sc.n_streams, 0);
-    for (int v = 0; v < n; ++v) stream_work[sc.stream_of[v]] += g->tasks[v].ntiles;
+    for (int v = 0; v < n; ++v) stream_work[sc.stream_of[v]] += units_for(g->tasks[v].ntiles);
     std::vector<int> by_work(sc.n_streams);
     std::iota(by_work.begin(), by_work.end(), 0);
     std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return stream_work[a] > stream_work[b]; });
@@ -91,8 +119,11 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     out.lists.assign(n_wg, {});
     out.parts.assign(n, 0);
     out.xcd.assign(n, -1);
+    out.kid.assign(n, KID_NONE);
+    out.ntiles.assign(n, 0);
+    out.local_parent.assign(n, -1);
     std::vector<double> free_at(n_wg, 0.0), finish(n, 0.0);
-    std::vector<std::vector<int>> parents(n);
+    std::vector<std::vector<int>> parents(n), wgs(n);
     for (auto& e : sc.meg) parents[e.second].push_back(e.first);
 
     std::vector<int> cand;
@@ -100,7 +131,10 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         const Task& t = g->tasks[v];
         if (!t.fn) continue;
         const int home = stream_xcd[sc.stream_of[v]];
-        const bool wide = nx > 1 && sc.solo[v] && t.ntiles > per_xcd;
+        out.kid[v] = t.kid;
+        out.ntiles[v] = t.ntiles;
+        const long units = units_for(t.ntiles);
+        const bool wide = nx > 1 && sc.solo[v] && units > per_xcd;
         out.xcd[v] = nx == 1 ? 0 : (wide ? -1 : home);
         cand.clear();
         for (int w = 0; w < n_wg; ++w) {
@@ -108,33 +142,76 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             if (x >= nx) continue;
             if (wide || x == home) cand.push_back(w);
         }
-        double ready = 0;
-        for (int u : parents[v]) {
-            if (!g->tasks[u].fn) continue;
-            const bool far = out.xcd[u] < 0 || out.xcd[v] < 0 || out.xcd[u] != out.xcd[v] || g->resident_all_far;
-            ready = std::max(ready, finish[u] + (far ? kSyncFarUs : 0.0));
-        }
+        auto ready_without = [&](int skip) {
+            double ready = 0;
+            for (int u : parents[v]) {
+                if (!g->tasks[u].fn || u == skip) continue;
+                const bool far = out.xcd[u] < 0 || out.xcd[v] < 0 || out.xcd[u] != out.xcd[v] || g->resident_all_far;
+                ready = std::max(ready, finish[u] + (far ? kSyncFarUs : 0.0));
+            }
+            return ready;
+        };
+        const double ready = ready_without(-1);
         // workgroups in the order they become available for this task
         std::stable_sort(cand.begin(), cand.end(), [&](int a, int b) { return free_at[a] < free_at[b]; });
-        const double cost = tile_round_us(g, v);
+        const double cost = tile_round_us(g, v, t.kid);
         int best_p = 1;
         double best_finish = 1e300;
         for (int rounds = 1; rounds <= 4; ++rounds) {
-            const int p = (int)std::min<long>((t.ntiles + rounds - 1) / rounds, (long)cand.size());
-            const long r = (t.ntiles + p - 1) / p;
+            const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)cand.size());
+            const long r = (units + p - 1) / p;
             const double f = std::max(ready, free_at[cand[p - 1]]) + r * cost + kSyncNearUs;
             if (f < best_finish - 1e-9) best_finish = f, best_p = p;
         }
-        const int p = best_p;
-        const long r = (t.ntiles + p - 1) / p;
+        // Alternative for an elementwise task: take over the partition and the workgroups of
+        // an E' parent with the same output shape on the same XCD. Tile i then depends only on
+        // what the same workgroup wrote a moment ago, and the wait for that parent is dropped.
+        int follow = -1, follow_kid = KID_NONE;
+        long follow_ntiles = 0;
+        double follow_finish = 1e300;
+        if (allow_local && !wide && !g->resident_all_far) {
+            for (int u : parents[v]) {
+                if (!g->tasks[u].fn || out.xcd[u] != out.xcd[v] || !(g->nodes[u].out == g->nodes[v].out)) continue;
+                if (std::find(g->nodes[v].preds.begin(), g->nodes[v].preds.end(), u) == g->nodes[v].preds.end()) continue;
+                long nt = 0;
+                const int kid = variant_for(g, v, partition_of(out.kid[u]), &nt);
+                if (kid == KID_NONE || nt != out.ntiles[u]) continue;
+                if (kid != t.kid && !getenv("NG_LOCAL_ANY")) continue;
+                double start = ready_without(u);
+                for (int w : wgs[u]) start = std::max(start, free_at[w]);
+                const long r = (units_for(nt) + (long)wgs[u].size() - 1) / (long)wgs[u].size();
+                const double f = start + kLocalUs + r * tile_round_us(g, v, kid) + kSyncNearUs;
+                if (f < follow_finish) follow_finish = f, follow = u, follow_kid = kid, follow_ntiles = nt;
+            }
+        }
+        long r;
+        double begin;
+        if (follow >= 0 && follow_finish <= best_finish + 1e-9) {
+            out.local_parent[v] = follow;
+            out.kid[v] = follow_kid;
+            out.ntiles[v] = follow_ntiles;
+            wgs[v] = wgs[follow];
+            best_finish = follow_finish;
+            r = (units_for(follow_ntiles) + (long)wgs[v].size() - 1) / (long)wgs[v].size();
+            begin = follow_finish - kSyncNearUs - r * tile_round_us(g, v, follow_kid);
+        } else {
+            wgs[v].assign(cand.begin(), cand.begin() + best_p);
+            r = (units + best_p - 1) / best_p;
+            begin = -1;
+        }
+        const int p = (int)wgs[v].size();
+        const double run = r * tile_round_us(g, v, out.kid[v]);
         out.parts[v] = (unsigned)p;
         for (int j = 0; j < p; ++j) {
-            const int w = cand[j];
+            const int w = wgs[v][j];
             out.lists[w].push_back(DevEntry{v, j, p, 0});
-            free_at[w] = std::max(ready, free_at[w]) + r * cost + kSyncNearUs;
+            free_at[w] = (begin >= 0 ? begin : std::max(ready, free_at[w])) + run + kPublishUs;
         }
         finish[v] = best_finish;
         out.makespan = std::max(out.makespan, best_finish);
+        if (debug)
+            fprintf(stderr, "PLAN nx=%d v=%d kid=%d ntiles=%ld p=%d r=%ld xcd=%d ready=%.2f cost=%.2f finish=%.2f stream=%d local=%d\n",
+                    nx, v, out.kid[v], out.ntiles[v], p, r, out.xcd[v], ready, run / r, best_finish, sc.stream_of[v], out.local_parent[v]);
     }
 }
 
@@ -161,8 +238,8 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
         std::memset(&d, 0, sizeof d);
         const Task& t = g->tasks[v];
         if (!t.fn) continue;
-        d.kid = t.kid;
-        d.ntiles = (int)t.ntiles;
+        d.kid = best.kid[v];
+        d.ntiles = (int)best.ntiles[v];
         std::memcpy(d.args, t.args, sizeof t.args);
     }
     // A tensor crosses XCDs when a direct reader (any edge of E, not only E') runs elsewhere.
@@ -182,6 +259,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     }
     for (auto& e : sc.meg) {
         if (!g->tasks[e.first].fn || !g->tasks[e.second].fn) continue;
+        if (best.local_parent[e.second] == e.first) continue;   // handed over inside the workgroups
         DevTask& d = plan.tasks[e.second];
         if (d.n_parents >= NG_MAX_PREDS) return NG_EINVAL;
         d.parent[d.n_parents] = e.first;
@@ -224,10 +302,14 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
         for (auto& t : plan.tasks) far += __builtin_popcount(t.far_in);
         if (n_far_edges) *n_far_edges = far;
         // invariants: every tile of every task is covered exactly once, lists ascend in task id,
-        // the completions a consumer expects equal the workgroups its producer was split over
+        // the completions a consumer expects equal the workgroups its producer was split over,
+        // and an E' parent that is not waited for has the same tiles on the same workgroups
         bool ok = true;
-        std::vector<std::vector<int>> hits(g->nodes.size());
-        std::vector<unsigned> parts(g->nodes.size(), 0);
+        const size_t n = g->nodes.size();
+        std::vector<std::vector<int>> hits(n);
+        std::vector<unsigned> parts(n, 0);
+        std::vector<std::vector<long>> where(n);              // (workgroup, first unit, step) triples per task
+        auto units_of = [&](int v) { return ((long)plan.tasks[v].ntiles + kSubs - 1) / kSubs; };
         for (int w = 0; w < plan.n_wg; ++w) {
             int last = -1;
             for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
@@ -235,17 +317,30 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
                 ok = ok && en.task > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step;
                 last = en.task;
                 ++parts[en.task];
-                if (hits[en.task].empty()) hits[en.task].assign((size_t)g->tasks[en.task].ntiles, 0);
-                for (long t = en.tile_begin; t < g->tasks[en.task].ntiles; t += en.tile_step) ++hits[en.task][(size_t)t];
+                where[en.task].insert(where[en.task].end(), {(long)w, (long)en.tile_begin, (long)en.tile_step});
+                if (hits[en.task].empty()) hits[en.task].assign((size_t)units_of(en.task), 0);
+                for (long t = en.tile_begin; t < units_of(en.task); t += en.tile_step) ++hits[en.task][(size_t)t];
             }
         }
-        for (size_t v = 0; v < g->nodes.size(); ++v) {
+        int n_local = 0;
+        for (size_t v = 0; v < n; ++v) {
             if (!g->tasks[v].fn) continue;
-            ok = ok && hits[v].size() == (size_t)g->tasks[v].ntiles;
+            ok = ok && plan.tasks[v].ntiles > 0 && hits[v].size() == (size_t)units_of((int)v);
             for (int h : hits[v]) ok = ok && h == 1;
             const DevTask& d = plan.tasks[v];
             for (int j = 0; j < d.n_parents; ++j) ok = ok && d.parent[j] < (int)v && d.need[j] == parts[d.parent[j]] && parts[d.parent[j]] > 0;
         }
+        for (auto& e : g->sched.meg) {
+            const int u = e.first, v = e.second;
+            if (!g->tasks[u].fn || !g->tasks[v].fn) continue;
+            const DevTask& d = plan.tasks[v];
+            if (std::find(d.parent, d.parent + d.n_parents, u) != d.parent + d.n_parents) continue;
+            ++n_local;
+            const int part = partition_of(plan.tasks[u].kid);
+            ok = ok && part != PART_NONE && part == partition_of(d.kid) && plan.tasks[u].ntiles == d.ntiles &&
+                 g->nodes[u].out == g->nodes[v].out && where[u] == where[v];
+        }
+        if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d\n", n_local);
         if (coverage_ok) *coverage_ok = ok;
     }
     g->dry_run = false;

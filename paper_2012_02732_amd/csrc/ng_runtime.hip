@@ -33,8 +33,7 @@ struct Runtime {
     float empty_chain_us = 0.f;            // per-node time of a chain of empty kernels (measured on demand)
     // device-resident replay
     DevPlan plan{};
-    void* d_tasks = nullptr;
-    void* d_entries = nullptr;
+    void* d_records = nullptr;
     void* d_wg_first = nullptr;
     int* h_error = nullptr;                // pinned host memory
     int n_wg = 0, n_entries = 0;
@@ -158,7 +157,7 @@ int build_resident(ng_graph* g) {
     int dev = 0, cus = 0, per_cu = 0;
     NG_HIP(hipGetDevice(&dev));
     NG_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    NG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel_handle(), kBlock, 0));
+    NG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel_handle(), kGroup, 0));
     if (per_cu < 1 || cus < 8) return g->fail(NG_EHIP, "device-resident replay: kernel does not fit (%d per CU, %d CUs)", per_cu, cus);
     per_cu = std::min(per_cu, g->resident_wg_per_cu > 0 ? g->resident_wg_per_cu : 1);   // one per CU: two slow each other's hand-overs down
     const int n_wg = cus * per_cu / 8 * 8;
@@ -170,7 +169,19 @@ int build_resident(ng_graph* g) {
     std::vector<int>& wg_first = hp.wg_first;
     rt.xcds = hp.xcds;
     rt.est_us = hp.est_us;
-    if (entries.empty()) entries.push_back(DevEntry{0, 0, 1, 0});   // keeps the allocation non-empty; never read
+    // one self-contained record per entry: the kernel never touches the task table itself
+    std::vector<DevRecord> records(std::max<size_t>(entries.size(), 1));
+    std::memset(records.data(), 0, records.size() * sizeof(DevRecord));
+    for (size_t e = 0; e < entries.size(); ++e) {
+        const DevTask& t = tasks[entries[e].task];
+        DevRecord& r = records[e];
+        r.task = entries[e].task, r.kid = t.kid, r.ntiles = t.ntiles, r.n_parents = t.n_parents;
+        r.tile_begin = entries[e].tile_begin, r.tile_step = entries[e].tile_step;
+        r.far_in = t.far_in != 0, r.far_out = t.release_far != 0;
+        std::memcpy(r.parent, t.parent, sizeof r.parent);
+        std::memcpy(r.need, t.need, sizeof r.need);
+        std::memcpy(r.args, t.args, sizeof r.args);
+    }
 
     unsigned* d_done = nullptr;
     int* d_error = nullptr;
@@ -179,20 +190,17 @@ int build_resident(ng_graph* g) {
     rt.plan.done_stride = env_stride ? atoi(env_stride) : 64;    // one counter per 256 bytes
     rt.plan.poll_sleep = env_sleep ? atoi(env_sleep) : 1;
     rt.done_words = (size_t)n * rt.plan.done_stride;
-    NG_HIP(hipMalloc(&rt.d_tasks, tasks.size() * sizeof(DevTask)));
-    NG_HIP(hipMalloc(&rt.d_entries, entries.size() * sizeof(DevEntry)));
+    NG_HIP(hipMalloc(&rt.d_records, records.size() * sizeof(DevRecord)));
     NG_HIP(hipMalloc(&rt.d_wg_first, wg_first.size() * sizeof(int)));
     NG_HIP(hipMalloc(&d_done, rt.done_words * sizeof(unsigned)));
     NG_HIP(hipMalloc(&d_error, sizeof(int)));
     NG_HIP(hipHostMalloc(reinterpret_cast<void**>(&rt.h_error), sizeof(int), hipHostMallocDefault));
     *rt.h_error = 0;
-    NG_HIP(hipMemcpy(rt.d_tasks, tasks.data(), tasks.size() * sizeof(DevTask), hipMemcpyHostToDevice));
-    NG_HIP(hipMemcpy(rt.d_entries, entries.data(), entries.size() * sizeof(DevEntry), hipMemcpyHostToDevice));
+    NG_HIP(hipMemcpy(rt.d_records, records.data(), records.size() * sizeof(DevRecord), hipMemcpyHostToDevice));
     NG_HIP(hipMemcpy(rt.d_wg_first, wg_first.data(), wg_first.size() * sizeof(int), hipMemcpyHostToDevice));
     NG_HIP(hipMemset(d_done, 0, rt.done_words * sizeof(unsigned)));
     NG_HIP(hipMemset(d_error, 0, sizeof(int)));
-    rt.plan.tasks = static_cast<const DevTask*>(rt.d_tasks);
-    rt.plan.entries = static_cast<const DevEntry*>(rt.d_entries);
+    rt.plan.records = static_cast<const DevRecord*>(rt.d_records);
     rt.plan.wg_first = static_cast<const int*>(rt.d_wg_first);
     rt.plan.done = d_done;
     rt.plan.error_dev = d_error;
@@ -207,7 +215,7 @@ int build_resident(ng_graph* g) {
 
 int launch_resident(ng_graph* g) {
     Runtime& rt = *g->rt;
-    if (!rt.d_tasks) return g->fail(NG_ESTATE, "device-resident replay was not prepared");
+    if (!rt.d_records) return g->fail(NG_ESTATE, "device-resident replay was not prepared");
     hipStream_t origin = rt.streams[0];
     if (rt.counters_dirty) {                                   // a timed-out replay left partial counts behind
         NG_HIP(hipStreamSynchronize(origin));
@@ -220,7 +228,7 @@ int launch_resident(ng_graph* g) {
     rt.plan.spin_limit = g->resident_spin_limit;
     unsigned epoch = ++rt.epoch;
     void* args[2] = {&rt.plan, &epoch};
-    NG_HIP(hipLaunchKernel(resident_kernel_handle(), dim3(rt.n_wg), dim3(kBlock), args, 0, origin));
+    NG_HIP(hipLaunchKernel(resident_kernel_handle(), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
     return NG_OK;
 }
 
@@ -240,8 +248,7 @@ void destroy_runtime(ng_graph* g) {
     if (rt->t_start) (void)hipEventDestroy(rt->t_start);
     if (rt->t_stop) (void)hipEventDestroy(rt->t_stop);
     if (rt->constants) (void)hipFree(rt->constants);
-    if (rt->d_tasks) (void)hipFree(rt->d_tasks);
-    if (rt->d_entries) (void)hipFree(rt->d_entries);
+    if (rt->d_records) (void)hipFree(rt->d_records);
     if (rt->d_wg_first) (void)hipFree(rt->d_wg_first);
     if (rt->plan.done) (void)hipFree(rt->plan.done);
     if (rt->plan.error_dev) (void)hipFree(rt->plan.error_dev);
@@ -316,7 +323,7 @@ int ng_capture(ng_graph* g) {
     }
     if (int rc = record_multi(g, 0)) return rc;
     if (int rc = capture_single(g, 1)) return rc;
-    if (!rt.d_tasks)
+    if (!rt.d_records)
         if (int rc = build_resident(g)) return rc;
     // the pre-run itself: execute the recorded schedule once so that every kernel is loaded
     NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
@@ -378,7 +385,7 @@ int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned sp
 
 int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks) {
     if (!g) return NG_EINVAL;
-    if (g->phase < CAPTURED || !g->rt->d_tasks) return g->fail(NG_ESTATE, "ng_resident_trace: call ng_capture first");
+    if (g->phase < CAPTURED || !g->rt->d_records) return g->fail(NG_ESTATE, "ng_resident_trace: call ng_capture first");
     Runtime& rt = *g->rt;
     const size_t bytes = g->nodes.size() * 3 * sizeof(unsigned long long);
     NG_HIP(hipStreamSynchronize(rt.streams[0]));
