@@ -14,22 +14,22 @@ enum Kid : int {
     KID_BN, KID_BN_V4, KID_ADD, KID_ADD_V4, KID_CONCAT, KID_CONCAT_V4, KID_POOL,
     KID_DW_K3S1, KID_DW_K3S2, KID_DW_K5S1, KID_DW_K5S2, KID_GAP, KID_FC_GEMV,
     KID_PW_D4, KID_PW_D8, KID_PW_D16, KID_PW_64, KID_C3_T16S1, KID_C3_T16S2, KID_C3_T8S1, KID_C3_T8S2,
-    KID_BN_T32, KID_ADD_T32,         // elementwise tasks on the tile grid of the direct conv1x1 (resident replay only)
+    // conv1x1 for small problems, K split over the wavefronts in groups of 4 k-steps, 1..4 groups in flight:
+    KID_PW_V1, KID_PW_V2, KID_PW_V3, KID_PW_V4,   // 16 x 64 output tile, 128-bit activation loads (HW % 4 == 0)
+    KID_PW_S1, KID_PW_S2, KID_PW_S3, KID_PW_S4,   // 16 x 16 output tile, 32-bit activation loads
     KID_COUNT
 };
 
 // How a kernel splits its output into tiles (see the elementwise tile functions): only tasks
 // with the same partition of same-shaped outputs have matching tiles.
-enum { PART_NONE = -1, PART_L256 = 0, PART_L1024 = 1, PART_T32 = 2 };
+enum { PART_NONE = -1, PART_L256 = 0, PART_L1024 = 1 };
 constexpr int partition_of(int kid) {
     return (kid == KID_BN || kid == KID_ADD || kid == KID_CONCAT || kid == KID_POOL || kid == KID_DW_K3S1 ||
             kid == KID_DW_K3S2 || kid == KID_DW_K5S1 || kid == KID_DW_K5S2)
                ? PART_L256
                : (kid == KID_BN_V4 || kid == KID_ADD_V4 || kid == KID_CONCAT_V4)
                      ? PART_L1024
-                     : (kid == KID_PW_D4 || kid == KID_PW_D8 || kid == KID_PW_D16 || kid == KID_BN_T32 || kid == KID_ADD_T32)
-                           ? PART_T32
-                           : PART_NONE;
+                     : PART_NONE;
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
@@ -49,7 +49,6 @@ struct BnArgs {
     int relu;
     int C, HW;
     int total;            // elements
-    int cols, tiles_n;    // 32 x 32 partition: columns (N * HW) and tiles along them
 };
 
 struct AddArgs {
@@ -57,7 +56,6 @@ struct AddArgs {
     float* y;
     int k;
     int total;
-    int C, HW, cols, tiles_n;  // 32 x 32 partition: channels, pixels per plane, columns (N * HW), tiles along them
 };
 
 struct ConcatArgs {
@@ -108,8 +106,9 @@ struct PwArgs {
     float* y;                  // [N][Cout][HW]
     int Cin, Cout, HW, cols;   // cols = N * HW
     int tiles_n;               // tiles along the column (pixel) axis
-    const float* wp;           // KID_PW_DIRECT: weights repacked into MFMA operand order
-    int ksteps;                // direct kernels: k steps of 4 in the packed copy (padded, multiple of 4 * chunk)
+    const float* wp;           // direct kernels: weights repacked into MFMA operand order
+    int ksteps;                // 32 x 32 kernels: k-steps of 4 in the packed copy (padded, a multiple of 4 * chunk);
+                               // 16-row kernels: groups of 4 k-steps in the packed copy (a multiple of 4 * groups in flight)
     int mtiles;                // direct kernels: ceil(Cout / 16)
 };
 
@@ -144,11 +143,11 @@ struct DevTask {
     alignas(16) unsigned char args[kArgBytes];
 };
 
-struct DevEntry {                    // one task in one workgroup's list; tiles are counted in units of kSubs
+struct DevEntry {                    // one task in one workgroup's list; tiles are counted in units of `subs`
     int task;
     int tile_begin;
     int tile_step;
-    int pad_;
+    int subs;                        // sub-blocks of the workgroup that take a tile each per round (1..kSubs)
 };
 
 // What the resident kernel reads: one self-contained record per (workgroup, task) entry, the
@@ -158,8 +157,9 @@ constexpr int kRecordWords = 24 + kArgWords;     // 288 bytes, a multiple of 16
 constexpr int kRecordsInLds = 128;               // records a workgroup holds in LDS at a time (then it reloads)
 struct DevRecord {
     int task, kid, ntiles, n_parents;
-    int tile_begin, tile_step;                   // in units of kSubs tiles
-    int far_in, far_out;                         // != 0: device-scope loads of activations / stores of the result
+    int tile_begin, tile_step;                   // in units of `subs` tiles
+    int flags;                                   // bit 0: device-scope loads of activations, bit 1: device-scope stores of the result
+    int subs;                                    // sub-blocks that take a tile each per round (the others idle), 1..kSubs
     int parent[NG_MAX_PREDS];
     unsigned need[NG_MAX_PREDS];
     unsigned args[kArgWords];

@@ -93,35 +93,12 @@ __device__ __forceinline__ void bn_coeff(const BnArgs& a, int c, float& s, float
     }
 }
 
-// Elementwise operators come in three partitions of the output into tiles, so that an
+// Elementwise operators come in two partitions of the output into tiles, so that an
 // elementwise task can take over the partition of the task that feeds it (then tile i of
 // the consumer reads only what tile i of the producer wrote, and a workgroup that ran the
 // one can run the other without waiting for anybody else):
 //   PART_L256  tile t = elements [256 t, 256 t + 256), one per thread (pool, dwconv order)
 //   PART_L1024 tile t = elements [1024 t, 1024 t + 1024), one float4 per thread
-//   PART_T32   tile t = 32 channels x 32 columns (column = image * HW + pixel), the output
-//              tile of the direct conv1x1; thread = (row tid / 32 + 8 j, column tid % 32), j < 4
-
-// element offsets (and validity) of the up to 4 elements a thread owns in a PART_T32 tile
-struct T32Index {
-    int e[4];
-    bool ok[4];
-};
-__device__ __forceinline__ T32Index t32_index(int tile, int tid, int tiles_n, int C, int HW, int cols) {
-    const int by = tile / tiles_n, bx = tile - by * tiles_n;
-    const int col = bx * 32 + (tid & 31);
-    const int ccol = min(col, cols - 1);
-    const int img = ccol / HW, pix = ccol - img * HW;
-    T32Index r;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int m = by * 32 + (tid >> 5) + 8 * j;
-        r.ok[j] = m < C && col < cols;
-        r.e[j] = (img * C + min(m, C - 1)) * HW + pix;
-    }
-    return r;
-}
-
 template <int PART, bool FIN, bool FOUT>
 __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, int tid, bool live) {
     if (!live) return;
@@ -134,27 +111,13 @@ __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, i
         v.x = fmaf(v.x, s, t), v.y = fmaf(v.y, s, t), v.z = fmaf(v.z, s, t), v.w = fmaf(v.w, s, t);
         if (a.relu) v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
         stg4(a.y, a.y + e, v, FOUT);
-    } else if (PART == PART_L256) {
+    } else {
         const int i = tile * kBlock + tid;
         if (i >= a.total) return;
         float s, t;
         bn_coeff(a, (i / a.HW) % a.C, s, t);
         float v = fmaf(ldg(a.x, a.x + i, FIN), s, t);
         stg(a.y, a.y + i, a.relu ? fmaxf(v, 0.f) : v, FOUT);
-    } else {
-        const T32Index ix = t32_index(tile, tid, a.tiles_n, a.C, a.HW, a.cols);
-        float v[4], s[4], t[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            v[j] = ldg(a.x, a.x + ix.e[j], FIN);
-            bn_coeff(a, min((tile / a.tiles_n) * 32 + (tid >> 5) + 8 * j, a.C - 1), s[j], t[j]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const float r = fmaf(v[j], s[j], t[j]);
-            if (ix.ok[j]) stg(a.y, a.y + ix.e[j], a.relu ? fmaxf(r, 0.f) : r, FOUT);
-        }
     }
 }
 
@@ -175,7 +138,7 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, i
             acc.x += v.x, acc.y += v.y, acc.z += v.z, acc.w += v.w;
         }
         stg4(a.y, a.y + e, acc, FOUT);
-    } else if (PART == PART_L256) {
+    } else {
         const int i = tile * kBlock + tid;
         if (i >= a.total) return;
         float acc = ldg(a.x[0], a.x[0] + i, FIN);
@@ -185,23 +148,6 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, i
             acc += ldg(a.x[j], a.x[j] + i, FIN);
         }
         stg(a.y, a.y + i, acc, FOUT);
-    } else {
-        const T32Index ix = t32_index(tile, tid, a.tiles_n, a.C, a.HW, a.cols);
-        float acc[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) acc[q] = ldg(a.x[0], a.x[0] + ix.e[q], FIN);
-#pragma unroll
-        for (int j = 1; j < NG_MAX_PREDS; ++j) {
-            if (j >= a.k) break;
-            float v[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) v[q] = ldg(a.x[j], a.x[j] + ix.e[q], FIN);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) acc[q] += v[q];
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            if (ix.ok[q]) stg(a.y, a.y + ix.e[q], acc[q], FOUT);
     }
 }
 
@@ -404,7 +350,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
     for (int k0 = 0; k0 < a.Cin; k0 += KC) {
         // A slice: W[m0 + m][k0 + k] -> As[k][m]; consecutive threads walk k (contiguous in W).
         // Loads are unconditional from clamped indices (independent, all in flight), zeroed afterwards.
-        {
+        if (live) {
             constexpr int RM = kBlock / KC;                       // rows covered per pass
             const int k = tid % KC, gk = k0 + k;
             float v[TM / RM];
@@ -421,7 +367,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
             }
         }
         // B slice: X[k0 + k][n0 + n] -> Bs[k][n]; consecutive threads walk pixels
-        {
+        if (live) {
             constexpr int RK = kBlock / TN;                       // k rows covered per pass
             const int n = tid % TN, col = n0 + n;
             const int ccol = min(col, a.cols - 1);
@@ -437,6 +383,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
             }
         }
         __syncthreads();
+        if (live)
 #pragma unroll
         for (int kk = 0; kk < KC; kk += 4) {
             float af[FM], bf[FN];
@@ -525,7 +472,7 @@ __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, f
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int s0 = 0; s0 < steps; s0 += CH) {
+    for (int s0 = 0; s0 < (live ? steps : 0); s0 += CH) {
         float av[2][CH], bv[2][CH];
 #pragma unroll
         for (int q = 0; q < CH; ++q) {
@@ -578,6 +525,112 @@ __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, f
 }
 
 // ------------------------------------------------------------------------------------
+// conv1x1 for the smallest problems (one image, a few thousand pixels at most), where the
+// time goes into issuing loads and into waiting, not into arithmetic. Differences from the
+// 32 x 32 kernel above:
+//   * the output tile is 16 channels wide only, so a problem spreads over as many compute
+//     units as possible (an fp32 MFMA occupies its SIMD for 32 cycles: few tiles means
+//     few SIMDs working);
+//   * the packed weights hold 4 k-steps per lane (block (row tile, group g), lane l, word q
+//     = W[16 rt + l % 16][16 g + 4 q + l / 16]): one 128-bit load feeds 4 MFMAs;
+//   * VEC (pixels per plane a multiple of 4): activations are read 128 bits at a time. Lane l
+//     loads X[k][n0 + 4 (l % 16) .. + 3]; word j of that load is the B operand of MFMA tile j,
+//     whose columns are n0 + 4 i + j, i = 0..15 - four interleaved 16-column tiles, 64 columns
+//     per workgroup, and the four results of a lane are again 4 consecutive pixels: one
+//     128-bit store;
+//   * otherwise the tile is 16 x 16 and activations are read word by word.
+// K is split over the four wavefronts in groups of 4 k-steps, G groups in flight at a time;
+// partial sums are added through LDS in a fixed order.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void pack_pw_weights_k4_kernel(const float* w, float* wp, int Cout, int Cin,
+                                                                     int groups, int total) {
+    const int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i >= total) return;
+    const int q = i & 3, l = (i >> 2) & 63, blk = i >> 8;
+    const int gi = blk % groups, rt = blk / groups;
+    const int m = rt * 16 + (l & 15), k = 16 * gi + 4 * q + (l >> 4);
+    wp[i] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
+}
+
+template <int G, bool VEC, bool FIN, bool FOUT>
+__device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float* smem, int tid, bool live) {
+    constexpr int NJ = VEC ? 4 : 1;                          // MFMA tiles per wavefront
+    constexpr int TN = VEC ? 64 : 16;                        // columns per workgroup tile
+    static_assert(4 * NJ * 4 * 64 <= kSmemFloats, "LDS budget");
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
+    const int colv = bx * TN + (VEC ? 4 : 1) * (lane & 15);  // first column this lane owns
+    if (live) {
+        const int groups = a.ksteps;                         // groups of 4 k-steps in the packed copy, a multiple of 4 G
+        const int gw = groups >> 2;                          // groups per wavefront
+        const f32x4* ap = reinterpret_cast<const f32x4*>(a.wp) + ((size_t)by * groups + (size_t)wave * gw) * 64 + lane;
+        const int col = min(colv, a.cols - (VEC ? 4 : 1));   // columns past the end repeat the last ones; never stored
+        const int img = col / a.HW, pix = col - img * a.HW;
+        const float* xb = a.x + (size_t)img * a.Cin * a.HW + pix;
+        const unsigned k_last = (unsigned)(a.Cin - 1) * (unsigned)a.HW;   // rows past Cin (zero weights) repeat the last row
+        const unsigned k_step = 4u * (unsigned)a.HW;
+        unsigned koff = (unsigned)(16 * wave * gw + (lane >> 4)) * (unsigned)a.HW;
+        f32x4 acc[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int g0 = 0; g0 < gw; g0 += G) {
+            f32x4 av[G];
+            float bv[G][4][NJ];
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) {
+                av[gi] = ap[gi * 64];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const unsigned off = min(koff + (unsigned)(4 * gi + q) * k_step, k_last);
+                    if (VEC) {
+                        const float4 v = ldg4(a.x, xb + off, FIN);
+                        __builtin_memcpy(bv[gi][q], &v, sizeof v);
+                    } else {
+                        bv[gi][q][0] = ldg(a.x, xb + off, FIN);
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);               // every load of the chunk is issued before the first use
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j)
+                        acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[gi][q], bv[gi][q][j], acc[j], 0, 0, 0);
+            ap += G * 64;
+            koff += 4u * G * k_step;
+        }
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) smem[((wave * NJ + j) * 4 + r) * 64 + lane] = acc[j][r];
+    }
+    __syncthreads();
+    if (live) {
+        // wavefront w finishes accumulator register w of every MFMA tile: output row 4 (lane / 16) + w
+        const int m = by * 16 + 4 * (lane >> 4) + wave;
+        float out[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            float sum = smem[((0 * NJ + j) * 4 + wave) * 64 + lane];
+#pragma unroll
+            for (int w2 = 1; w2 < 4; ++w2) sum += smem[((w2 * NJ + j) * 4 + wave) * 64 + lane];
+            out[j] = sum;
+        }
+        if (m < a.Cout && colv < a.cols) {                   // VEC: cols is a multiple of 4, a lane's 4 columns are all in or all out
+            const float b = a.bias ? a.bias[m] : 0.f;
+            const int img = colv / a.HW, pix = colv - img * a.HW;
+            float* dst = a.y + ((size_t)img * a.Cout + m) * a.HW + pix;
+            if (VEC) stg4(a.y, dst, make_float4(out[0] + b, out[NJ > 1 ? 1 : 0] + b, out[NJ > 2 ? 2 : 0] + b, out[NJ > 3 ? 3 : 0] + b), FOUT);
+            else stg(a.y, dst, out[0] + b, FOUT);
+        }
+    }
+    __syncthreads();                                         // LDS is reused by the next tile
+}
+
+// ------------------------------------------------------------------------------------
 // conv3x3 dense on the vector ALUs: one thread = one output pixel x 8 output channels.
 // Input patches go through LDS (4 input channels per slice); the weights a wavefront
 // needs are the same for all of its lanes, so they are read through uniform addresses.
@@ -615,7 +668,7 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     for (int j = 0; j < CO; ++j) wrow[j] = a.w + (size_t)min(co0 + j, a.Cout - 1) * a.Cin * 9;
 
     for (int c0 = 0; c0 < a.Cin; c0 += CIC) {
-        {
+        if (live) {
             constexpr int NL = (CIC * IW * IW + kBlock - 1) / kBlock;   // loads per thread, all in flight
             float pv[NL];
 #pragma unroll
@@ -640,7 +693,7 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
             }
         }
         __syncthreads();
-        const int nci = min(CIC, a.Cin - c0);
+        const int nci = live ? min(CIC, a.Cin - c0) : 0;
         for (int ci = 0; ci < nci; ++ci) {
             float in[9];
 #pragma unroll
@@ -680,10 +733,8 @@ template <int KID> struct KernelOf;
     };
 NG_KERNEL(KID_BN, BnArgs, "bn_act", bn_act_tile < PART_L256)
 NG_KERNEL(KID_BN_V4, BnArgs, "bn_act_v4", bn_act_tile < PART_L1024)
-NG_KERNEL(KID_BN_T32, BnArgs, "bn_act_t32", bn_act_tile < PART_T32)
 NG_KERNEL(KID_ADD, AddArgs, "add_n", add_n_tile < PART_L256)
 NG_KERNEL(KID_ADD_V4, AddArgs, "add_n_v4", add_n_tile < PART_L1024)
-NG_KERNEL(KID_ADD_T32, AddArgs, "add_n_t32", add_n_tile < PART_T32)
 NG_KERNEL(KID_CONCAT, ConcatArgs, "concat", concat_tile < false)
 NG_KERNEL(KID_CONCAT_V4, ConcatArgs, "concat_v4", concat_tile < true)
 NG_KERNEL(KID_DW_K3S1, DwArgs, "dwconv_k3s1", dwconv_tile < 3, 1)
@@ -694,6 +745,14 @@ NG_KERNEL(KID_PW_D4, PwArgs, "conv1x1_mfma_d4", conv1x1_direct_tile < 4)
 NG_KERNEL(KID_PW_D8, PwArgs, "conv1x1_mfma_d8", conv1x1_direct_tile < 8)
 NG_KERNEL(KID_PW_D16, PwArgs, "conv1x1_mfma_d16", conv1x1_direct_tile < 16)
 NG_KERNEL(KID_PW_64, PwArgs, "conv1x1_mfma_64x64", conv1x1_mfma_tile < 64, 64, 16)
+NG_KERNEL(KID_PW_V1, PwArgs, "conv1x1_v1", conv1x1_k4_tile < 1, true)
+NG_KERNEL(KID_PW_V2, PwArgs, "conv1x1_v2", conv1x1_k4_tile < 2, true)
+NG_KERNEL(KID_PW_V3, PwArgs, "conv1x1_v3", conv1x1_k4_tile < 3, true)
+NG_KERNEL(KID_PW_V4, PwArgs, "conv1x1_v4", conv1x1_k4_tile < 4, true)
+NG_KERNEL(KID_PW_S1, PwArgs, "conv1x1_s1", conv1x1_k4_tile < 1, false)
+NG_KERNEL(KID_PW_S2, PwArgs, "conv1x1_s2", conv1x1_k4_tile < 2, false)
+NG_KERNEL(KID_PW_S3, PwArgs, "conv1x1_s3", conv1x1_k4_tile < 3, false)
+NG_KERNEL(KID_PW_S4, PwArgs, "conv1x1_s4", conv1x1_k4_tile < 4, false)
 NG_KERNEL(KID_C3_T16S1, C3Args, "conv3x3_t16s1", conv3x3_tile < 16, 1)
 NG_KERNEL(KID_C3_T16S2, C3Args, "conv3x3_t16s2", conv3x3_tile < 16, 2)
 NG_KERNEL(KID_C3_T8S1, C3Args, "conv3x3_t8s1", conv3x3_tile < 8, 1)
@@ -735,15 +794,17 @@ __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KI
 // stored and loaded with device-scope accesses, so no L2 is ever flushed or invalidated. Every wait is bounded: a workgroup that runs out of
 // spins raises the error flag and every workgroup leaves.
 // ------------------------------------------------------------------------------------
-// One resident workgroup = kSubs sub-blocks of kBlock threads; sub-block `sub` takes tile
-// unit * kSubs + sub of every unit the workgroup owns. All sub-blocks walk the same number of
-// units (tile functions may contain workgroup barriers): a sub-block whose tile does not
-// exist runs tile 0 with `live` false (loads stay in bounds, nothing is stored) or returns.
+// One resident workgroup = kSubs sub-blocks of kBlock threads; the first `subs` of them take
+// tile unit * subs + sub of every unit the workgroup owns (a task whose tiles keep the memory
+// pipeline of a compute unit busy is better spread over more compute units: subs = 1). All
+// sub-blocks walk the same number of units (tile functions may contain workgroup barriers):
+// a sub-block without a tile calls the tile function with `live` false, which only takes
+// part in the barriers.
 // `words` points at the record's argument block in LDS; it is the same for every lane, so
 // each word is moved into a scalar register.
 template <int KID>
-__device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int step, int ntiles, float* smem, int sub, int tid,
-                                          bool fin, bool fout) {
+__device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int step, int ntiles, int subs, float* smem, int sub,
+                                          int tid, bool fin, bool fout) {
     using A = typename KernelOf<KID>::Args;
     static_assert(sizeof(A) <= kArgWords * 4 && sizeof(A) % 4 == 0, "argument block does not fit the record");
     unsigned w[sizeof(A) / 4];
@@ -751,11 +812,11 @@ __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int s
     for (size_t i = 0; i < sizeof(A) / 4; ++i) w[i] = __builtin_amdgcn_readfirstlane(words[i]);
     A a;
     __builtin_memcpy(&a, w, sizeof(A));
-    const int nunits = (ntiles + kSubs - 1) / kSubs;
+    const int nunits = (ntiles + subs - 1) / subs;
 #define NG_LOOP(FI, FO)                                                              \
     for (; unit < nunits; unit += step) {                                            \
-        const int tile = unit * kSubs + sub;                                         \
-        const bool live = tile < ntiles;                                             \
+        const int tile = unit * subs + sub;                                          \
+        const bool live = sub < subs && tile < ntiles;                               \
         KernelOf<KID>::template tile<FI, FO>(a, live ? tile : 0, smem, tid, live);   \
     }
     if (!fin && !fout) { NG_LOOP(false, false) }
@@ -789,7 +850,8 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             const int task = __builtin_amdgcn_readfirstlane(rec[0]), kid = __builtin_amdgcn_readfirstlane(rec[1]);
             const int ntiles = __builtin_amdgcn_readfirstlane(rec[2]), np = __builtin_amdgcn_readfirstlane(rec[3]);
             const int tile0 = __builtin_amdgcn_readfirstlane(rec[4]), step = __builtin_amdgcn_readfirstlane(rec[5]);
-            const bool far_in = __builtin_amdgcn_readfirstlane(rec[6]) != 0, far_out = __builtin_amdgcn_readfirstlane(rec[7]) != 0;
+            const int flags = __builtin_amdgcn_readfirstlane(rec[6]), subs = __builtin_amdgcn_readfirstlane(rec[7]);
+            const bool far_in = (flags & 1) != 0, far_out = (flags & 2) != 0;
             const bool tracer = plan.trace != nullptr && tile0 == 0 && lane == 0;
             if (tracer) plan.trace[3 * task] = wall_clock64();
             if (np > 0) {
@@ -829,11 +891,12 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             }
             if (tracer) plan.trace[3 * task + 1] = wall_clock64();
             switch (kid) {
-#define NG_CASE(KID) case KID: run_tiles<KID>(rec + 24, tile0, step, ntiles, smem, sub, tid, far_in, far_out); break;
-                NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_T32) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4) NG_CASE(KID_ADD_T32)
+#define NG_CASE(KID) case KID: run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out); break;
+                NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
                 NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
                 NG_CASE(KID_DW_K5S1) NG_CASE(KID_DW_K5S2) NG_CASE(KID_GAP) NG_CASE(KID_FC_GEMV)
-                NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_C3_T16S1)
+                NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_PW_V1) NG_CASE(KID_PW_V2)
+                NG_CASE(KID_PW_V3) NG_CASE(KID_PW_V4) NG_CASE(KID_PW_S1) NG_CASE(KID_PW_S2) NG_CASE(KID_PW_S3) NG_CASE(KID_PW_S4) NG_CASE(KID_C3_T16S1)
                 NG_CASE(KID_C3_T16S2) NG_CASE(KID_C3_T8S1) NG_CASE(KID_C3_T8S2)
 #undef NG_CASE
                 default: break;
@@ -884,30 +947,70 @@ __global__ void empty_kernel() {}
 }  // namespace
 const void* empty_kernel_handle() { return reinterpret_cast<const void*>(&empty_kernel); }
 
-// Floats of library-owned constant memory node v needs (repacked conv1x1 weights), 0 if none.
-// Large pointwise problems (many 64 x 64 tiles) keep the LDS-tiled throughput kernel.
-size_t packed_floats(const ng_graph* g, int v) {
+namespace {
+// Which conv1x1 kernel a node gets. Decided from shapes alone, so that the size of the
+// repacked weights is known before any memory is bound.
+struct PwChoice {
+    enum Kind { NONE, GEMV, LDS64, DIRECT32, K4_VEC, K4_WORD } kind = NONE;
+    int in_flight = 0;        // K4: groups of 4 k-steps in flight (1..4); DIRECT32: k-steps per chunk
+    int groups = 0;           // K4: groups in the packed copy (a multiple of 4 * in_flight); DIRECT32: padded k-steps
+    size_t packed = 0;        // floats of repacked weights
+};
+PwChoice choose_pw(const ng_graph* g, int v) {
+    PwChoice c;
     const Node& nd = g->nodes[v];
-    if (nd.op != NG_OP_CONV1X1 && nd.op != NG_OP_FC) return 0;
+    if (nd.op != NG_OP_CONV1X1 && nd.op != NG_OP_FC) return c;
     const Shape& o = nd.out;
     const long cin = g->nodes[nd.preds[0]].out.c;
-    if (nd.op == NG_OP_FC && o.n <= 8) return 0;
-    const long cols = o.n * o.h * o.w;
-    if (((o.c + 63) / 64) * ((cols + 63) / 64) >= 256) return 0;
-    return (size_t)((o.c + 15) / 16) * 64 * pw_padded_steps(cin);
+    const long hw = o.h * o.w, cols = o.n * hw;
+    if (nd.op == NG_OP_FC && o.n <= 8) { c.kind = PwChoice::GEMV; return c; }
+    // large problems (many 64 x 64 tiles) keep the LDS-tiled throughput kernel
+    if (((o.c + 63) / 64) * ((cols + 63) / 64) >= 256) { c.kind = PwChoice::LDS64; return c; }
+    const bool vec = hw % 4 == 0;
+    const long tiles16 = ((o.c + 15) / 16) * ((cols + 15) / 16);
+    if (!vec && tiles16 > 128) {                             // enough tiles anyway: 32 x 32 tiles read less
+        c.kind = PwChoice::DIRECT32;
+        c.in_flight = pw_chunk(cin);
+        c.groups = pw_padded_steps(cin);
+        c.packed = (size_t)((o.c + 15) / 16) * 64 * c.groups;
+        return c;
+    }
+    c.kind = vec ? PwChoice::K4_VEC : PwChoice::K4_WORD;
+    const long groups = ceil_div(ceil_div(cin, 4), 4);
+    long gw = ceil_div(groups, 4);                           // groups per wavefront
+    if (gw <= 4) {
+        c.in_flight = (int)gw;
+    } else {
+        const long pad3 = ceil_div(gw, 3) * 3, pad4 = ceil_div(gw, 4) * 4;
+        c.in_flight = pad3 < pad4 ? 3 : 4;
+        gw = std::min(pad3, pad4);
+    }
+    c.groups = (int)(4 * gw);
+    c.packed = (size_t)((o.c + 15) / 16) * c.groups * 256;
+    return c;
 }
+
+}  // namespace
+
+// Floats of library-owned constant memory node v needs (repacked conv1x1 weights), 0 if none.
+size_t packed_floats(const ng_graph* g, int v) { return choose_pw(g, v).packed; }
 
 // Fill node v's constant memory: one pass over the weights, at bind time.
 int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
-    const size_t n = packed_floats(g, v);
-    if (n == 0) return NG_OK;
+    const PwChoice c = choose_pw(g, v);
+    if (c.packed == 0) return NG_OK;
     const Node& nd = g->nodes[v];
     const int cin = (int)g->nodes[nd.preds[0]].out.c, cout = (int)nd.out.c;
     if (!nd.weights[0]) return g->fail(NG_EINVAL, "node %d: weight 0 is a null device pointer", v);
-    pack_pw_weights_kernel<<<dim3((unsigned)((n + kBlock - 1) / kBlock)), dim3(kBlock), 0, static_cast<hipStream_t>(stream)>>>(
-        static_cast<const float*>(nd.weights[0]), packed, cout, cin, pw_padded_steps(cin), (int)n);
+    const dim3 grid((unsigned)((c.packed + kBlock - 1) / kBlock)), block(kBlock);
+    if (c.kind == PwChoice::DIRECT32)
+        pack_pw_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const float*>(nd.weights[0]), packed, cout, cin, c.groups, (int)c.packed);
+    else
+        pack_pw_weights_k4_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const float*>(nd.weights[0]), packed, cout, cin, c.groups, (int)c.packed);
     const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return g->fail(NG_EHIP, "pack_pw_weights_kernel: %s", hipGetErrorString(e));
+    if (e != hipSuccess) return g->fail(NG_EHIP, "repacking conv1x1 weights: %s", hipGetErrorString(e));
     return NG_OK;
 }
 
@@ -940,7 +1043,6 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.relu = 1;
             }
             a.C = (int)o.c, a.HW = hw_out, a.total = total;
-            a.cols = (int)(o.n * hw_out), a.tiles_n = (int)ceil_div(a.cols, 32);
             if (hw_out % 4 == 0) set_kernel<KID_BN_V4>(t, a, ceil_div(total / 4, kBlock));
             else set_kernel<KID_BN>(t, a, ceil_div(total, kBlock));
             break;
@@ -951,7 +1053,6 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             for (int j = 0; j < NG_MAX_PREDS; ++j) a.x[j] = buf(nd.preds[j < a.k ? j : 0]);
             a.y = buf(v);
             a.total = total;
-            a.C = (int)o.c, a.HW = hw_out, a.cols = (int)(o.n * hw_out), a.tiles_n = (int)ceil_div(a.cols, 32);
             if (total % 4 == 0) set_kernel<KID_ADD_V4>(t, a, ceil_div(total / 4, kBlock));
             else set_kernel<KID_ADD>(t, a, ceil_div(total, kBlock));
             break;
@@ -997,7 +1098,8 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
         case NG_OP_FC:
         case NG_OP_CONV1X1: {
             const bool fc = nd.op == NG_OP_FC;
-            if (fc && o.n <= 8) {
+            const PwChoice c = choose_pw(g, v);
+            if (c.kind == PwChoice::GEMV) {
                 FcArgs a{buf(nd.preds[0]), wf(0), wf(1), buf(v), (int)o.n, (int)i0.c, (int)o.c};
                 set_kernel<KID_FC_GEMV>(t, a, ceil_div(a.Cout, kBlock / 64));
                 break;
@@ -1005,20 +1107,35 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             PwArgs a{};
             a.x = buf(nd.preds[0]), a.w = wf(0), a.bias = fc ? wf(1) : nullptr, a.y = buf(v);
             a.Cin = (int)i0.c, a.Cout = (int)o.c, a.HW = hw_out, a.cols = (int)(o.n * hw_out);
-            if (packed_floats(g, v) == 0) {
+            if (c.kind == PwChoice::LDS64) {
                 a.tiles_n = (int)ceil_div(a.cols, 64);
                 set_kernel<KID_PW_64>(t, a, (long)a.tiles_n * ceil_div(a.Cout, 64));
-            } else {
-                if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
-                a.wp = packed;
-                const int chunk = pw_chunk(a.Cin);
-                a.ksteps = pw_padded_steps(a.Cin);
-                a.mtiles = (int)ceil_div(a.Cout, 16);
+                break;
+            }
+            if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
+            a.wp = packed;
+            a.ksteps = c.groups;
+            a.mtiles = (int)ceil_div(a.Cout, 16);
+            if (c.kind == PwChoice::DIRECT32) {
                 a.tiles_n = (int)ceil_div(a.cols, 32);
                 const long n = (long)a.tiles_n * ceil_div(a.Cout, 32);
-                if (chunk == 4) set_kernel<KID_PW_D4>(t, a, n);
-                else if (chunk == 8) set_kernel<KID_PW_D8>(t, a, n);
+                if (c.in_flight == 4) set_kernel<KID_PW_D4>(t, a, n);
+                else if (c.in_flight == 8) set_kernel<KID_PW_D8>(t, a, n);
                 else set_kernel<KID_PW_D16>(t, a, n);
+            } else if (c.kind == PwChoice::K4_VEC) {
+                a.tiles_n = (int)ceil_div(a.cols, 64);
+                const long n = (long)a.tiles_n * a.mtiles;
+                if (c.in_flight == 1) set_kernel<KID_PW_V1>(t, a, n);
+                else if (c.in_flight == 2) set_kernel<KID_PW_V2>(t, a, n);
+                else if (c.in_flight == 3) set_kernel<KID_PW_V3>(t, a, n);
+                else set_kernel<KID_PW_V4>(t, a, n);
+            } else {
+                a.tiles_n = (int)ceil_div(a.cols, 16);
+                const long n = (long)a.tiles_n * a.mtiles;
+                if (c.in_flight == 1) set_kernel<KID_PW_S1>(t, a, n);
+                else if (c.in_flight == 2) set_kernel<KID_PW_S2>(t, a, n);
+                else if (c.in_flight == 3) set_kernel<KID_PW_S3>(t, a, n);
+                else set_kernel<KID_PW_S4>(t, a, n);
             }
             break;
         }

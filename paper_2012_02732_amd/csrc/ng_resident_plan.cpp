@@ -41,25 +41,41 @@ constexpr double kSyncFarUs = 1.5;    // extra cost when producer and consumer s
 constexpr double kPublishUs = 0.3;    // stores drained and counter bumped: the workgroup moves on to its next entry
 constexpr double kLocalUs = 0.1;      // hand-over inside one workgroup: one barrier
 
-// Expected time of one round (kSubs tiles per workgroup) of a task, in microseconds. Rough
-// figures from measurements of the tile functions inside the resident kernel; the planner
-// only needs them to be ordered sensibly.
-double tile_round_us(const ng_graph* g, int v, int kid) {
+// Expected time of one round of a task, in microseconds, when `subs` sub-blocks of a
+// workgroup take a tile each: a latency part that does not depend on how many tiles share
+// the compute unit (address set-up, one trip to memory and back for the loads, one for the
+// stores) plus a throughput part per tile (load issue and data return of the compute
+// unit's one memory pipeline, matrix-core time of wavefronts that share a SIMD). Figures
+// from traces of the resident kernel; the planner only needs them to be ordered sensibly.
+double tile_round_us(const ng_graph* g, int v, int kid, int subs) {
     const Node& nd = g->nodes[v];
     const double cin = nd.preds.empty() ? 0.0 : (double)g->nodes[nd.preds[0]].out.c;
+    double base = 1.0, per_tile = 0.1;
     switch (kid) {
-        case KID_BN: case KID_BN_V4: case KID_BN_T32: return 0.8;
-        case KID_ADD: case KID_ADD_V4: case KID_ADD_T32: return 0.5;
-        case KID_CONCAT: case KID_CONCAT_V4: return 0.8;
-        case KID_POOL: case KID_DW_K3S1: case KID_DW_K3S2: return 1.5;
-        case KID_DW_K5S1: case KID_DW_K5S2: return 1.9;
-        case KID_GAP: return 1.0;
-        case KID_FC_GEMV: return 1.0 + 0.001 * cin * (double)nd.out.n;
-        case KID_PW_D4: case KID_PW_D8: case KID_PW_D16: return 1.6 + 0.004 * cin;
-        case KID_PW_64: return 1.5 + 0.05 * cin;
-        case KID_C3_T16S1: case KID_C3_T16S2: case KID_C3_T8S1: case KID_C3_T8S2: return 1.0 + 0.75 * cin;
-        default: return 1.0;
+        case KID_BN: case KID_BN_V4: base = 1.2, per_tile = 0.15; break;
+        case KID_ADD: case KID_ADD_V4: base = 0.9, per_tile = 0.1; break;
+        case KID_CONCAT: case KID_CONCAT_V4: base = 1.6, per_tile = 0.2; break;
+        case KID_POOL: base = 1.6, per_tile = 0.25; break;
+        case KID_DW_K3S1: case KID_DW_K3S2: base = 1.5, per_tile = 0.25; break;
+        case KID_DW_K5S1: case KID_DW_K5S2: base = 2.0, per_tile = 0.7; break;
+        case KID_GAP: base = 1.0, per_tile = 0.1; break;
+        case KID_FC_GEMV: base = 1.0 + 0.001 * cin * (double)nd.out.n, per_tile = 0.2; break;
+        case KID_PW_D4: case KID_PW_D8: case KID_PW_D16: base = 1.3, per_tile = 0.4 + 0.008 * cin; break;
+        case KID_PW_64: base = 1.5, per_tile = 0.025 * cin; break;
+        case KID_PW_V1: case KID_PW_V2: case KID_PW_V3: case KID_PW_V4: {
+            const PwArgs* a = reinterpret_cast<const PwArgs*>(g->tasks[v].args);
+            base = 1.3, per_tile = 0.3 * (a->ksteps / 4);           // per group of 4 k-steps and wavefront: 5 128-bit loads, 16 MFMAs
+            break;
+        }
+        case KID_PW_S1: case KID_PW_S2: case KID_PW_S3: case KID_PW_S4: {
+            const PwArgs* a = reinterpret_cast<const PwArgs*>(g->tasks[v].args);
+            base = 1.6, per_tile = 0.12 * (a->ksteps / 4);
+            break;
+        }
+        case KID_C3_T16S1: case KID_C3_T16S2: case KID_C3_T8S1: case KID_C3_T8S2: base = 1.0, per_tile = 0.375 * cin; break;
+        default: break;
     }
+    return base + per_tile * subs;
 }
 
 // The kernel variant of an elementwise task that uses partition `part` (KID_NONE if there is
@@ -67,7 +83,7 @@ double tile_round_us(const ng_graph* g, int v, int kid) {
 int variant_for(const ng_graph* g, int v, int part, long* ntiles) {
     const Node& nd = g->nodes[v];
     const Shape& o = nd.out;
-    const long total = o.elems(), hw = o.h * o.w, cols = o.n * hw;
+    const long total = o.elems(), hw = o.h * o.w;
     const bool bn = nd.op == NG_OP_BN_ACT || nd.op == NG_OP_RELU, add = nd.op == NG_OP_ADD_N;
     if (!bn && !add) return KID_NONE;
     switch (part) {
@@ -76,7 +92,6 @@ int variant_for(const ng_graph* g, int v, int part, long* ntiles) {
             if ((bn && hw % 4 != 0) || (add && total % 4 != 0)) return KID_NONE;
             *ntiles = (total / 4 + kBlock - 1) / kBlock;
             return bn ? KID_BN_V4 : KID_ADD_V4;
-        case PART_T32: *ntiles = ((cols + 31) / 32) * ((o.c + 31) / 32); return bn ? KID_BN_T32 : KID_ADD_T32;
         default: return KID_NONE;
     }
 }
@@ -87,6 +102,7 @@ struct Sim {
     std::vector<int> xcd;
     std::vector<int> kid;            // kernel variant chosen for the resident replay
     std::vector<long> ntiles;        // its tile count
+    std::vector<int> subs;           // sub-blocks per workgroup that take a tile each
     std::vector<int> local_parent;   // E' parent whose completion this task does not wait for (same workgroups, same tiles), or -1
     double makespan = 0;
 };
@@ -98,10 +114,10 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     const bool debug = getenv("NG_PLAN_DEBUG") != nullptr;
     const bool allow_local = getenv("NG_NO_LOCAL") == nullptr;
 
-    // the planner counts work in units of kSubs tiles: what one workgroup does in one round
-    auto units_for = [&](long ntiles) { return (ntiles + kSubs - 1) / kSubs; };
+    // the planner counts work in units of `subs` tiles: what one workgroup does in one round
+    auto units_for = [&](long ntiles, int subs) { return (ntiles + subs - 1) / subs; };
     std::vector<long> stream_work(sc.n_streams, 0);
-    for (int v = 0; v < n; ++v) stream_work[sc.stream_of[v]] += units_for(g->tasks[v].ntiles);
+    for (int v = 0; v < n; ++v) stream_work[sc.stream_of[v]] += units_for(g->tasks[v].ntiles, kSubs);
     std::vector<int> by_work(sc.n_streams);
     std::iota(by_work.begin(), by_work.end(), 0);
     std::stable_sort(by_work.begin(), by_work.end(), [&](int a, int b) { return stream_work[a] > stream_work[b]; });
@@ -121,6 +137,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     out.xcd.assign(n, -1);
     out.kid.assign(n, KID_NONE);
     out.ntiles.assign(n, 0);
+    out.subs.assign(n, kSubs);
     out.local_parent.assign(n, -1);
     std::vector<double> free_at(n_wg, 0.0), finish(n, 0.0);
     std::vector<std::vector<int>> parents(n), wgs(n);
@@ -133,8 +150,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         const int home = stream_xcd[sc.stream_of[v]];
         out.kid[v] = t.kid;
         out.ntiles[v] = t.ntiles;
-        const long units = units_for(t.ntiles);
-        const bool wide = nx > 1 && sc.solo[v] && units > per_xcd;
+        const bool wide = nx > 1 && sc.solo[v] && units_for(t.ntiles, kSubs) > per_xcd;
         out.xcd[v] = nx == 1 ? 0 : (wide ? -1 : home);
         cand.clear();
         for (int w = 0; w < n_wg; ++w) {
@@ -154,14 +170,21 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         const double ready = ready_without(-1);
         // workgroups in the order they become available for this task
         std::stable_sort(cand.begin(), cand.end(), [&](int a, int b) { return free_at[a] < free_at[b]; });
-        const double cost = tile_round_us(g, v, t.kid);
-        int best_p = 1;
+        int best_p = 1, best_subs = kSubs;
         double best_finish = 1e300;
-        for (int rounds = 1; rounds <= 4; ++rounds) {
-            const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)cand.size());
-            const long r = (units + p - 1) / p;
-            const double f = std::max(ready, free_at[cand[p - 1]]) + r * cost + kSyncNearUs;
-            if (f < best_finish - 1e-9) best_finish = f, best_p = p;
+        // only the matrix kernels keep a compute unit's memory pipeline busy enough to be worth
+        // spreading one tile per workgroup; for the others fewer participants is what counts
+        const bool heavy = t.kid >= KID_PW_D4 && t.kid != KID_BN && t.kid != KID_ADD && partition_of(t.kid) == PART_NONE &&
+                           t.kid != KID_GAP && t.kid != KID_FC_GEMV;
+        for (int subs = kSubs; subs >= (heavy ? 1 : kSubs); --subs) {
+            const long units = units_for(t.ntiles, subs);
+            const double cost = tile_round_us(g, v, t.kid, subs);
+            for (int rounds = 1; rounds <= 4; ++rounds) {
+                const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)cand.size());
+                const long r = (units + p - 1) / p;
+                const double f = std::max(ready, free_at[cand[p - 1]]) + r * cost + kSyncNearUs;
+                if (f < best_finish - 1e-9) best_finish = f, best_p = p, best_subs = subs;
+            }
         }
         // Alternative for an elementwise task: take over the partition and the workgroups of
         // an E' parent with the same output shape on the same XCD. Tile i then depends only on
@@ -179,8 +202,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
                 if (kid != t.kid && !getenv("NG_LOCAL_ANY")) continue;
                 double start = ready_without(u);
                 for (int w : wgs[u]) start = std::max(start, free_at[w]);
-                const long r = (units_for(nt) + (long)wgs[u].size() - 1) / (long)wgs[u].size();
-                const double f = start + kLocalUs + r * tile_round_us(g, v, kid) + kSyncNearUs;
+                const long r = (units_for(nt, out.subs[u]) + (long)wgs[u].size() - 1) / (long)wgs[u].size();
+                const double f = start + kLocalUs + r * tile_round_us(g, v, kid, out.subs[u]) + kSyncNearUs;
                 if (f < follow_finish) follow_finish = f, follow = u, follow_kid = kid, follow_ntiles = nt;
             }
         }
@@ -190,28 +213,30 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             out.local_parent[v] = follow;
             out.kid[v] = follow_kid;
             out.ntiles[v] = follow_ntiles;
+            out.subs[v] = out.subs[follow];
             wgs[v] = wgs[follow];
             best_finish = follow_finish;
-            r = (units_for(follow_ntiles) + (long)wgs[v].size() - 1) / (long)wgs[v].size();
-            begin = follow_finish - kSyncNearUs - r * tile_round_us(g, v, follow_kid);
+            r = (units_for(follow_ntiles, out.subs[v]) + (long)wgs[v].size() - 1) / (long)wgs[v].size();
+            begin = follow_finish - kSyncNearUs - r * tile_round_us(g, v, follow_kid, out.subs[v]);
         } else {
+            out.subs[v] = best_subs;
             wgs[v].assign(cand.begin(), cand.begin() + best_p);
-            r = (units + best_p - 1) / best_p;
+            r = (units_for(t.ntiles, best_subs) + best_p - 1) / best_p;
             begin = -1;
         }
         const int p = (int)wgs[v].size();
-        const double run = r * tile_round_us(g, v, out.kid[v]);
+        const double run = r * tile_round_us(g, v, out.kid[v], out.subs[v]);
         out.parts[v] = (unsigned)p;
         for (int j = 0; j < p; ++j) {
             const int w = wgs[v][j];
-            out.lists[w].push_back(DevEntry{v, j, p, 0});
+            out.lists[w].push_back(DevEntry{v, j, p, out.subs[v]});
             free_at[w] = (begin >= 0 ? begin : std::max(ready, free_at[w])) + run + kPublishUs;
         }
         finish[v] = best_finish;
         out.makespan = std::max(out.makespan, best_finish);
         if (debug)
-            fprintf(stderr, "PLAN nx=%d v=%d kid=%d ntiles=%ld p=%d r=%ld xcd=%d ready=%.2f cost=%.2f finish=%.2f stream=%d local=%d\n",
-                    nx, v, out.kid[v], out.ntiles[v], p, r, out.xcd[v], ready, run / r, best_finish, sc.stream_of[v], out.local_parent[v]);
+            fprintf(stderr, "PLAN nx=%d v=%d kid=%d ntiles=%ld p=%d r=%ld xcd=%d ready=%.2f cost=%.2f finish=%.2f stream=%d local=%d subs=%d\n",
+                    nx, v, out.kid[v], out.ntiles[v], p, r, out.xcd[v], ready, run / r, best_finish, sc.stream_of[v], out.local_parent[v], out.subs[v]);
     }
 }
 
@@ -308,8 +333,13 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
         const size_t n = g->nodes.size();
         std::vector<std::vector<int>> hits(n);
         std::vector<unsigned> parts(n, 0);
-        std::vector<std::vector<long>> where(n);              // (workgroup, first unit, step) triples per task
-        auto units_of = [&](int v) { return ((long)plan.tasks[v].ntiles + kSubs - 1) / kSubs; };
+        std::vector<std::vector<long>> where(n);              // (workgroup, first unit, step, subs) per task
+        std::vector<int> subs_of(n, 0);
+        for (const DevEntry& en : plan.entries) {
+            ok = ok && en.subs >= 1 && en.subs <= kSubs && (subs_of[en.task] == 0 || subs_of[en.task] == en.subs);
+            subs_of[en.task] = std::min(std::max(en.subs, 1), kSubs);
+        }
+        auto units_of = [&](int v) { return ((long)plan.tasks[v].ntiles + subs_of[v] - 1) / std::max(subs_of[v], 1); };
         for (int w = 0; w < plan.n_wg; ++w) {
             int last = -1;
             for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
@@ -317,7 +347,7 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
                 ok = ok && en.task > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step;
                 last = en.task;
                 ++parts[en.task];
-                where[en.task].insert(where[en.task].end(), {(long)w, (long)en.tile_begin, (long)en.tile_step});
+                where[en.task].insert(where[en.task].end(), {(long)w, (long)en.tile_begin, (long)en.tile_step, (long)en.subs});
                 if (hits[en.task].empty()) hits[en.task].assign((size_t)units_of(en.task), 0);
                 for (long t = en.tile_begin; t < units_of(en.task); t += en.tile_step) ++hits[en.task][(size_t)t];
             }

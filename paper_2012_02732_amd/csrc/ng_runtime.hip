@@ -177,7 +177,8 @@ int build_resident(ng_graph* g) {
         DevRecord& r = records[e];
         r.task = entries[e].task, r.kid = t.kid, r.ntiles = t.ntiles, r.n_parents = t.n_parents;
         r.tile_begin = entries[e].tile_begin, r.tile_step = entries[e].tile_step;
-        r.far_in = t.far_in != 0, r.far_out = t.release_far != 0;
+        r.flags = (t.far_in != 0 ? 1 : 0) | (t.release_far != 0 ? 2 : 0);
+        r.subs = entries[e].subs;
         std::memcpy(r.parent, t.parent, sizeof r.parent);
         std::memcpy(r.need, t.need, sizeof r.need);
         std::memcpy(r.args, t.args, sizeof r.args);
