@@ -200,11 +200,13 @@ int ng_sync(ng_graph* g);
  * XCD of its stream is handed over through that XCD's L2 and only the others pay for an L2
  * write-back and invalidate. */
 int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned spin_limit, int device_scope_everywhere);
-/* Per-task timeline of device-resident replays. enable != 0 switches recording on (off for 0).
- * If ticks is not NULL it first receives, for the last replay recorded, three device clock
- * readings per node (HOST array of 3 * n_nodes values, 100 MHz clock, 0 for input nodes):
- * wait for producers begins, inputs ready, all tiles of the first workgroup done. Waits for
- * the origin stream to go idle. */
+/* Per-task timeline of device-resident replays. enable != 0 switches recording on and clears
+ * the record (off for 0). If ticks is not NULL it first receives what was recorded since the
+ * last call: four device clock readings per node (HOST array of 4 * n_nodes values, 100 MHz
+ * clock; a task that did not run keeps ~0, 0, ~0, 0): the first workgroup starts to wait for
+ * the producers, the last workgroup has its inputs ready, the first and the last workgroup
+ * have stored their tiles. Record ONE replay between two calls for a timeline of that
+ * replay. Waits for the origin stream to go idle. */
 int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks);
 /* Host-only rehearsal of the device-resident plan (needs ng_plan_memory, no GPU): plans for
  * n_workgroups persistent workgroups (a multiple of 8) over xcds XCDs (0 = let the cost

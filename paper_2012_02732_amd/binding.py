@@ -229,17 +229,19 @@ def ng_resident_sizes(g):
 
 
 def ng_resident_trace(g, enable, fetch=False):
-    """Switch the per-task timeline on/off; with fetch=True return [(wait, ready, done)] in microseconds
-    relative to the earliest reading."""
+    """Switch the per-task timeline on/off (switching on clears it); with fetch=True return
+    [(first wait, last ready, first done, last done)] in microseconds relative to the earliest
+    reading, None for nodes that did not run."""
     if not fetch:
         check(g, lib.ng_resident_trace(g, int(enable), None))
         return None
     n = ng_num_nodes(g)
-    buf = (C.c_ulonglong * (3 * n))()
+    buf = (C.c_ulonglong * (4 * n))()
     check(g, lib.ng_resident_trace(g, int(enable), buf))
-    vals = [v for v in buf if v]
-    base = min(vals) if vals else 0
-    return [tuple((buf[3 * i + j] - base) / 100.0 if buf[3 * i + j] else None for j in range(3)) for i in range(n)]
+    top = 2 ** 64 - 1
+    ran = {i for i in range(n) if buf[4 * i + 3] != 0 and buf[4 * i] != top}
+    base = min((buf[4 * i] for i in ran), default=0)
+    return [tuple((buf[4 * i + j] - base) / 100.0 for j in range(4)) if i in ran else None for i in range(n)]
 
 
 def ng_time_replay(g, reps) -> float:

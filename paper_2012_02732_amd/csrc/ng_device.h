@@ -17,19 +17,25 @@ enum Kid : int {
     // conv1x1 for small problems, K split over the wavefronts in groups of 4 k-steps, 1..4 groups in flight:
     KID_PW_V1, KID_PW_V2, KID_PW_V3, KID_PW_V4,   // 16 x 64 output tile, 128-bit activation loads (HW % 4 == 0)
     KID_PW_S1, KID_PW_S2, KID_PW_S3, KID_PW_S4,   // 16 x 16 output tile, 32-bit activation loads
+    KID_BN_R64, KID_BN_R16, KID_ADD_R64, KID_ADD_R16,   // elementwise tasks on the tile grids of those two (resident replay)
     KID_COUNT
 };
 
 // How a kernel splits its output into tiles (see the elementwise tile functions): only tasks
 // with the same partition of same-shaped outputs have matching tiles.
-enum { PART_NONE = -1, PART_L256 = 0, PART_L1024 = 1 };
+enum { PART_NONE = -1, PART_L256 = 0, PART_L1024 = 1, PART_R64 = 2, PART_R16 = 3 };
 constexpr int partition_of(int kid) {
     return (kid == KID_BN || kid == KID_ADD || kid == KID_CONCAT || kid == KID_POOL || kid == KID_DW_K3S1 ||
             kid == KID_DW_K3S2 || kid == KID_DW_K5S1 || kid == KID_DW_K5S2)
                ? PART_L256
                : (kid == KID_BN_V4 || kid == KID_ADD_V4 || kid == KID_CONCAT_V4)
                      ? PART_L1024
-                     : PART_NONE;
+                     : (kid == KID_PW_V1 || kid == KID_PW_V2 || kid == KID_PW_V3 || kid == KID_PW_V4 || kid == KID_BN_R64 || kid == KID_ADD_R64)
+                           ? PART_R64
+                           : (kid == KID_PW_S1 || kid == KID_PW_S2 || kid == KID_PW_S3 || kid == KID_PW_S4 || kid == KID_BN_R16 ||
+                              kid == KID_ADD_R16)
+                                 ? PART_R16
+                                 : PART_NONE;
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
@@ -41,14 +47,12 @@ constexpr int kArgBytes = 256;       // size of the per-task argument block
 struct BnArgs {
     const float* x;
     float* y;
-    const float* gamma;   // nullptr => plain ReLU
-    const float* beta;
-    const float* mean;
-    const float* var;
-    float eps;
+    const float* scale;   // [C] gamma / sqrt(var + eps), folded once at bind time; nullptr => plain ReLU
+    const float* shift;   // [C] beta - mean * scale
     int relu;
     int C, HW;
     int total;            // elements
+    int cols;             // 2-D partitions: columns (N * HW)
 };
 
 struct AddArgs {
@@ -56,6 +60,7 @@ struct AddArgs {
     float* y;
     int k;
     int total;
+    int C, HW, cols;      // 2-D partitions: channels, pixels per plane, columns (N * HW)
 };
 
 struct ConcatArgs {
@@ -175,7 +180,7 @@ struct DevPlan {
     unsigned spin_limit;
     int done_stride;                 // words between two tasks' counters (spreads them over memory channels)
     int poll_sleep;                  // 0, 1, 2: back-off between two polls (1, 4, 16 sleep units)
-    unsigned long long* trace;       // optional [n_nodes][3]: wait begins, inputs ready, tiles done (100 MHz clock)
+    unsigned long long* trace;       // optional [n_nodes][4]: first wait begins, last workgroup ready, first and last workgroup done (100 MHz clock)
 };
 
 }  // namespace ng

@@ -68,6 +68,7 @@ struct ResidentPlan {
     std::vector<DevTask> tasks;                // [n_nodes]
     std::vector<DevEntry> entries;             // per-workgroup lists, concatenated
     std::vector<int> wg_first;                 // [n_wg + 1]
+    std::vector<int> order;                    // tasks in list order: every workgroup's list is a subsequence of it
 };
 
 struct Runtime;  // HIP-side state, defined in ng_runtime.hip

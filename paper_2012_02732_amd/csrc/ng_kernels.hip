@@ -84,40 +84,74 @@ constexpr int kSmemFloats = 4 * 33 * 34;
 // bn_act / relu: y = x * s[c] + t[c] (s, t folded from gamma, beta, mean, var), optional ReLU
 // ------------------------------------------------------------------------------------
 __device__ __forceinline__ void bn_coeff(const BnArgs& a, int c, float& s, float& t) {
-    if (a.gamma) {
-        s = a.gamma[c] / sqrtf(a.var[c] + a.eps);
-        t = a.beta[c] - a.mean[c] * s;
+    if (a.scale) {
+        s = a.scale[c];
+        t = a.shift[c];
     } else {
         s = 1.f;
         t = 0.f;
     }
 }
 
-// Elementwise operators come in two partitions of the output into tiles, so that an
+// Batch-norm parameters -> one multiplier and one offset per channel, once, at bind time.
+__global__ __launch_bounds__(kBlock) void fold_bn_kernel(const float* gamma, const float* beta, const float* mean,
+                                                         const float* var, float eps, float* scale, float* shift, int C) {
+    const int c = blockIdx.x * kBlock + threadIdx.x;
+    if (c >= C) return;
+    const float s = gamma[c] / sqrtf(var[c] + eps);
+    scale[c] = s;
+    shift[c] = beta[c] - mean[c] * s;
+}
+
+// Elementwise operators come in four partitions of the output into tiles, so that an
 // elementwise task can take over the partition of the task that feeds it (then tile i of
 // the consumer reads only what tile i of the producer wrote, and a workgroup that ran the
 // one can run the other without waiting for anybody else):
 //   PART_L256  tile t = elements [256 t, 256 t + 256), one per thread (pool, dwconv order)
 //   PART_L1024 tile t = elements [1024 t, 1024 t + 1024), one float4 per thread
+//   PART_R64   tile t = 16 channels x 64 columns (column = image * HW + pixel), the tile of
+//              the 128-bit conv1x1; thread = (channel tid / 16, 4 columns from 4 (tid % 16))
+//   PART_R16   tile t = 16 channels x 16 columns, the tile of the 32-bit conv1x1
+// ElemIndex: first element a thread owns (VEC of them, consecutive), its channel, validity.
+struct ElemIndex {
+    int e, c;
+    bool ok;
+};
+template <int PART>
+__device__ __forceinline__ ElemIndex elem_index(int tile, int tid, int C, int HW, int total, int cols) {
+    ElemIndex r;
+    if (PART == PART_L1024 || PART == PART_L256) {
+        r.e = (tile * kBlock + tid) * (PART == PART_L1024 ? 4 : 1);
+        r.ok = r.e < total;
+        r.c = (r.e / HW) % C;
+    } else {
+        constexpr int TN = PART == PART_R64 ? 64 : 16, V = PART == PART_R64 ? 4 : 1;
+        const int tiles_n = (cols + TN - 1) / TN;
+        const int by = tile / tiles_n, bx = tile - by * tiles_n;
+        const int col = bx * TN + V * (tid & 15);
+        r.c = by * 16 + (tid >> 4);
+        r.ok = r.c < C && col < cols;
+        const int img = col / HW, pix = col - img * HW;
+        r.e = (img * C + r.c) * HW + pix;
+    }
+    return r;
+}
+
 template <int PART, bool FIN, bool FOUT>
 __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, int tid, bool live) {
     if (!live) return;
-    if (PART == PART_L1024) {                     // HW % 4 == 0: a float4 never straddles channels
-        const int e = (tile * kBlock + tid) * 4;
-        if (e >= a.total) return;
-        float s, t;
-        bn_coeff(a, (e / a.HW) % a.C, s, t);
-        float4 v = ldg4(a.x, a.x + e, FIN);
+    const ElemIndex ix = elem_index<PART>(tile, tid, a.C, a.HW, a.total, a.cols);
+    if (!ix.ok) return;
+    float s, t;
+    bn_coeff(a, ix.c, s, t);
+    if (PART == PART_L1024 || PART == PART_R64) {          // HW % 4 == 0: a float4 never straddles channels
+        float4 v = ldg4(a.x, a.x + ix.e, FIN);
         v.x = fmaf(v.x, s, t), v.y = fmaf(v.y, s, t), v.z = fmaf(v.z, s, t), v.w = fmaf(v.w, s, t);
         if (a.relu) v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
-        stg4(a.y, a.y + e, v, FOUT);
+        stg4(a.y, a.y + ix.e, v, FOUT);
     } else {
-        const int i = tile * kBlock + tid;
-        if (i >= a.total) return;
-        float s, t;
-        bn_coeff(a, (i / a.HW) % a.C, s, t);
-        float v = fmaf(ldg(a.x, a.x + i, FIN), s, t);
-        stg(a.y, a.y + i, a.relu ? fmaxf(v, 0.f) : v, FOUT);
+        const float v = fmaf(ldg(a.x, a.x + ix.e, FIN), s, t);
+        stg(a.y, a.y + ix.e, a.relu ? fmaxf(v, 0.f) : v, FOUT);
     }
 }
 
@@ -127,9 +161,10 @@ __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, i
 template <int PART, bool FIN, bool FOUT>
 __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, int tid, bool live) {
     if (!live) return;
-    if (PART == PART_L1024) {
-        const int e = (tile * kBlock + tid) * 4;
-        if (e >= a.total) return;
+    const ElemIndex ix = elem_index<PART>(tile, tid, a.C, a.HW, a.total, a.cols);
+    if (!ix.ok) return;
+    const int e = ix.e;
+    if (PART == PART_L1024 || PART == PART_R64) {
         float4 acc = ldg4(a.x[0], a.x[0] + e, FIN);
 #pragma unroll
         for (int j = 1; j < NG_MAX_PREDS; ++j) {
@@ -139,15 +174,13 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, i
         }
         stg4(a.y, a.y + e, acc, FOUT);
     } else {
-        const int i = tile * kBlock + tid;
-        if (i >= a.total) return;
-        float acc = ldg(a.x[0], a.x[0] + i, FIN);
+        float acc = ldg(a.x[0], a.x[0] + e, FIN);
 #pragma unroll
         for (int j = 1; j < NG_MAX_PREDS; ++j) {
             if (j >= a.k) break;
-            acc += ldg(a.x[j], a.x[j] + i, FIN);
+            acc += ldg(a.x[j], a.x[j] + e, FIN);
         }
-        stg(a.y, a.y + i, acc, FOUT);
+        stg(a.y, a.y + e, acc, FOUT);
     }
 }
 
@@ -733,6 +766,10 @@ template <int KID> struct KernelOf;
     };
 NG_KERNEL(KID_BN, BnArgs, "bn_act", bn_act_tile < PART_L256)
 NG_KERNEL(KID_BN_V4, BnArgs, "bn_act_v4", bn_act_tile < PART_L1024)
+NG_KERNEL(KID_BN_R64, BnArgs, "bn_act_r64", bn_act_tile < PART_R64)
+NG_KERNEL(KID_BN_R16, BnArgs, "bn_act_r16", bn_act_tile < PART_R16)
+NG_KERNEL(KID_ADD_R64, AddArgs, "add_n_r64", add_n_tile < PART_R64)
+NG_KERNEL(KID_ADD_R16, AddArgs, "add_n_r16", add_n_tile < PART_R16)
 NG_KERNEL(KID_ADD, AddArgs, "add_n", add_n_tile < PART_L256)
 NG_KERNEL(KID_ADD_V4, AddArgs, "add_n_v4", add_n_tile < PART_L1024)
 NG_KERNEL(KID_CONCAT, ConcatArgs, "concat", concat_tile < false)
@@ -852,8 +889,8 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             const int tile0 = __builtin_amdgcn_readfirstlane(rec[4]), step = __builtin_amdgcn_readfirstlane(rec[5]);
             const int flags = __builtin_amdgcn_readfirstlane(rec[6]), subs = __builtin_amdgcn_readfirstlane(rec[7]);
             const bool far_in = (flags & 1) != 0, far_out = (flags & 2) != 0;
-            const bool tracer = plan.trace != nullptr && tile0 == 0 && lane == 0;
-            if (tracer) plan.trace[3 * task] = wall_clock64();
+            const bool tracer = plan.trace != nullptr && lane == 0;
+            if (tracer) atomicMin(plan.trace + 4 * task, wall_clock64());
             if (np > 0) {
                 if (lane < 64) {                                    // first wavefront: lane j watches parent j
                     bool ok = true;
@@ -889,10 +926,11 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                 __syncthreads();                                    // also waits for the invalidate to finish
                 if (s_abort) return;
             }
-            if (tracer) plan.trace[3 * task + 1] = wall_clock64();
+            if (tracer) atomicMax(plan.trace + 4 * task + 1, wall_clock64());
             switch (kid) {
 #define NG_CASE(KID) case KID: run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out); break;
-                NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
+                NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_R64) NG_CASE(KID_BN_R16) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
+                NG_CASE(KID_ADD_R64) NG_CASE(KID_ADD_R16)
                 NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
                 NG_CASE(KID_DW_K5S1) NG_CASE(KID_DW_K5S2) NG_CASE(KID_GAP) NG_CASE(KID_FC_GEMV)
                 NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_PW_V1) NG_CASE(KID_PW_V2)
@@ -902,7 +940,11 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                 default: break;
             }
             __syncthreads();             // every thread's stores have reached L2 (write-through L1, counted stores)
-            if (tracer) plan.trace[3 * task + 2] = wall_clock64();
+            if (tracer) {
+                const unsigned long long now = wall_clock64();
+                atomicMin(plan.trace + 4 * task + 2, now);
+                atomicMax(plan.trace + 4 * task + 3, now);
+            }
             if (lane == 0) {
                 // Publish completion. Readers on this XCD see the data in the shared L2; if there
                 // are readers elsewhere the tile functions have stored through to the memory side.
@@ -993,13 +1035,29 @@ PwChoice choose_pw(const ng_graph* g, int v) {
 }  // namespace
 
 // Floats of library-owned constant memory node v needs (repacked conv1x1 weights), 0 if none.
-size_t packed_floats(const ng_graph* g, int v) { return choose_pw(g, v).packed; }
+size_t packed_floats(const ng_graph* g, int v) {
+    const Node& nd = g->nodes[v];
+    if (nd.op == NG_OP_BN_ACT) return 2 * (size_t)((nd.out.c + 3) & ~3L);   // folded scale, shift
+    return choose_pw(g, v).packed;
+}
 
 // Fill node v's constant memory: one pass over the weights, at bind time.
 int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
+    const Node& nd = g->nodes[v];
+    if (nd.op == NG_OP_BN_ACT) {
+        for (int j = 0; j < 4; ++j)
+            if (!nd.weights[j]) return g->fail(NG_EINVAL, "node %d: weight %d is a null device pointer", v, j);
+        const int C = (int)nd.out.c;
+        fold_bn_kernel<<<dim3((unsigned)((C + kBlock - 1) / kBlock)), dim3(kBlock), 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const float*>(nd.weights[0]), static_cast<const float*>(nd.weights[1]),
+            static_cast<const float*>(nd.weights[2]), static_cast<const float*>(nd.weights[3]), nd.p.eps, packed,
+            packed + ((C + 3) & ~3), C);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return g->fail(NG_EHIP, "folding batch-norm parameters: %s", hipGetErrorString(e));
+        return NG_OK;
+    }
     const PwChoice c = choose_pw(g, v);
     if (c.packed == 0) return NG_OK;
-    const Node& nd = g->nodes[v];
     const int cin = (int)g->nodes[nd.preds[0]].out.c, cout = (int)nd.out.c;
     if (!nd.weights[0]) return g->fail(NG_EINVAL, "node %d: weight 0 is a null device pointer", v);
     const dim3 grid((unsigned)((c.packed + kBlock - 1) / kBlock)), block(kBlock);
@@ -1036,13 +1094,14 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.x = buf(nd.preds[0]);
             a.y = buf(v);
             if (nd.op == NG_OP_BN_ACT) {
-                a.gamma = wf(0), a.beta = wf(1), a.mean = wf(2), a.var = wf(3);
-                a.eps = nd.p.eps;
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for folded batch-norm parameters", v);
+                a.scale = packed, a.shift = packed + ((o.c + 3) & ~3L);
                 a.relu = nd.p.relu != 0;
             } else {
                 a.relu = 1;
             }
             a.C = (int)o.c, a.HW = hw_out, a.total = total;
+            a.cols = (int)(o.n * hw_out);
             if (hw_out % 4 == 0) set_kernel<KID_BN_V4>(t, a, ceil_div(total / 4, kBlock));
             else set_kernel<KID_BN>(t, a, ceil_div(total, kBlock));
             break;
@@ -1053,6 +1112,7 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             for (int j = 0; j < NG_MAX_PREDS; ++j) a.x[j] = buf(nd.preds[j < a.k ? j : 0]);
             a.y = buf(v);
             a.total = total;
+            a.C = (int)o.c, a.HW = hw_out, a.cols = (int)(o.n * hw_out);
             if (total % 4 == 0) set_kernel<KID_ADD_V4>(t, a, ceil_div(total / 4, kBlock));
             else set_kernel<KID_ADD>(t, a, ceil_div(total, kBlock));
             break;

@@ -11,15 +11,16 @@
 //     tensors that flow along a stream stay in that XCD's L2. Streams are placed heaviest
 //     first on the XCD with the least work so far.
 //   * The workgroups of an XCD are shared by the streams placed on it. Tasks are taken in
-//     ascending id (the submission order of the schedule) and each is given the workgroups
+//     the order in which their inputs are expected to be ready and each is given the workgroups
 //     of its XCD that a simple cost model expects to be free first - classic list
 //     scheduling - trying 1..4 rounds of tiles per workgroup and keeping the earliest
 //     expected finish. Independent tasks therefore land on different workgroups and overlap;
 //     dependent ones reuse the workgroups that just finished their producer.
 //   * A task no other task can run beside, with more tiles than one XCD has workgroups, is
 //     spread over every participating XCD.
-//   * Every workgroup's list is a subsequence of one topological order and a task waits only
-//     for earlier tasks, so with all workgroups resident no wait can depend on itself.
+//   * Every workgroup's list is a subsequence of one topological order (the order in which the
+//     planner placed the tasks) and a task waits only for earlier tasks, so with all
+//     workgroups resident no wait can depend on itself.
 //   * A task waits for all of its E' parents (FIFO order inside a stream does not order two
 //     workgroups). Whether a hand-over needs a device-scope fence is decided per tensor from
 //     *all* direct readers (edges of E): a reader on another XCD reads the tensor itself, even
@@ -28,6 +29,8 @@
 #include <cstdlib>
 #include <cstring>
 #include <numeric>
+#include <queue>
+#include <tuple>
 
 #include "ng_device.h"
 #include "ng_internal.h"
@@ -52,8 +55,8 @@ double tile_round_us(const ng_graph* g, int v, int kid, int subs) {
     const double cin = nd.preds.empty() ? 0.0 : (double)g->nodes[nd.preds[0]].out.c;
     double base = 1.0, per_tile = 0.1;
     switch (kid) {
-        case KID_BN: case KID_BN_V4: base = 1.2, per_tile = 0.15; break;
-        case KID_ADD: case KID_ADD_V4: base = 0.9, per_tile = 0.1; break;
+        case KID_BN: case KID_BN_V4: case KID_BN_R64: case KID_BN_R16: base = 1.2, per_tile = 0.15; break;
+        case KID_ADD: case KID_ADD_V4: case KID_ADD_R64: case KID_ADD_R16: base = 0.9, per_tile = 0.1; break;
         case KID_CONCAT: case KID_CONCAT_V4: base = 1.6, per_tile = 0.2; break;
         case KID_POOL: base = 1.6, per_tile = 0.25; break;
         case KID_DW_K3S1: case KID_DW_K3S2: base = 1.5, per_tile = 0.25; break;
@@ -83,7 +86,7 @@ double tile_round_us(const ng_graph* g, int v, int kid, int subs) {
 int variant_for(const ng_graph* g, int v, int part, long* ntiles) {
     const Node& nd = g->nodes[v];
     const Shape& o = nd.out;
-    const long total = o.elems(), hw = o.h * o.w;
+    const long total = o.elems(), hw = o.h * o.w, cols = o.n * hw;
     const bool bn = nd.op == NG_OP_BN_ACT || nd.op == NG_OP_RELU, add = nd.op == NG_OP_ADD_N;
     if (!bn && !add) return KID_NONE;
     switch (part) {
@@ -92,6 +95,11 @@ int variant_for(const ng_graph* g, int v, int part, long* ntiles) {
             if ((bn && hw % 4 != 0) || (add && total % 4 != 0)) return KID_NONE;
             *ntiles = (total / 4 + kBlock - 1) / kBlock;
             return bn ? KID_BN_V4 : KID_ADD_V4;
+        case PART_R64:
+            if (hw % 4 != 0) return KID_NONE;
+            *ntiles = ((o.c + 15) / 16) * ((cols + 63) / 64);
+            return bn ? KID_BN_R64 : KID_ADD_R64;
+        case PART_R16: *ntiles = ((o.c + 15) / 16) * ((cols + 15) / 16); return bn ? KID_BN_R16 : KID_ADD_R16;
         default: return KID_NONE;
     }
 }
@@ -103,6 +111,7 @@ struct Sim {
     std::vector<int> kid;            // kernel variant chosen for the resident replay
     std::vector<long> ntiles;        // its tile count
     std::vector<int> subs;           // sub-blocks per workgroup that take a tile each
+    std::vector<int> order;          // tasks in the order they were placed: every workgroup's list follows it
     std::vector<int> local_parent;   // E' parent whose completion this task does not wait for (same workgroups, same tiles), or -1
     double makespan = 0;
 };
@@ -143,10 +152,43 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     std::vector<std::vector<int>> parents(n), wgs(n);
     for (auto& e : sc.meg) parents[e.second].push_back(e.first);
 
+    // Tasks are taken in the order in which the model expects their inputs to be ready (ties:
+    // the longer remaining path first) - a topological order like ascending id, but one that
+    // does not make a workgroup sit in front of a task of a slow branch while a task of
+    // another stream further down its list could already run.
+    std::vector<std::vector<int>> children(n);
+    std::vector<int> waiting(n, 0);
+    for (auto& e : sc.meg)
+        if (g->tasks[e.first].fn && g->tasks[e.second].fn) children[e.first].push_back(e.second), ++waiting[e.second];
+    std::vector<double> tail(n, 0.0);
+    for (int v = n - 1; v >= 0; --v) {
+        if (!g->tasks[v].fn) continue;
+        double longest = 0;
+        for (int c : children[v]) longest = std::max(longest, tail[c]);
+        tail[v] = longest + tile_round_us(g, v, g->tasks[v].kid, kSubs) + kSyncNearUs;
+    }
+    auto ready_time = [&](int v) {                              // all parents placed: when the last of them is visible
+        const int home = stream_xcd[sc.stream_of[v]];
+        double ready = 0;
+        for (int u : parents[v]) {
+            if (!g->tasks[u].fn) continue;
+            const bool far = nx > 1 && (out.xcd[u] < 0 || out.xcd[u] != home);
+            ready = std::max(ready, finish[u] + (far ? kSyncFarUs : 0.0));
+        }
+        return ready;
+    };
+    typedef std::tuple<double, double, int> Key;                // (ready time, -tail, id): smallest first
+    std::priority_queue<Key, std::vector<Key>, std::greater<Key>> open;
+    for (int v = 0; v < n; ++v)
+        if (g->tasks[v].fn && waiting[v] == 0) open.push(Key(0.0, -tail[v], v));
+    out.order.clear();
+
     std::vector<int> cand;
-    for (int v = 0; v < n; ++v) {
+    while (!open.empty()) {
+        const int v = std::get<2>(open.top());
+        open.pop();
+        out.order.push_back(v);
         const Task& t = g->tasks[v];
-        if (!t.fn) continue;
         const int home = stream_xcd[sc.stream_of[v]];
         out.kid[v] = t.kid;
         out.ntiles[v] = t.ntiles;
@@ -174,8 +216,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         double best_finish = 1e300;
         // only the matrix kernels keep a compute unit's memory pipeline busy enough to be worth
         // spreading one tile per workgroup; for the others fewer participants is what counts
-        const bool heavy = t.kid >= KID_PW_D4 && t.kid != KID_BN && t.kid != KID_ADD && partition_of(t.kid) == PART_NONE &&
-                           t.kid != KID_GAP && t.kid != KID_FC_GEMV;
+        const bool heavy = (t.kid >= KID_PW_D4 && t.kid <= KID_C3_T8S2) || (t.kid >= KID_PW_V1 && t.kid <= KID_PW_S4);
         for (int subs = kSubs; subs >= (heavy ? 1 : kSubs); --subs) {
             const long units = units_for(t.ntiles, subs);
             const double cost = tile_round_us(g, v, t.kid, subs);
@@ -199,7 +240,6 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
                 long nt = 0;
                 const int kid = variant_for(g, v, partition_of(out.kid[u]), &nt);
                 if (kid == KID_NONE || nt != out.ntiles[u]) continue;
-                if (kid != t.kid && !getenv("NG_LOCAL_ANY")) continue;
                 double start = ready_without(u);
                 for (int w : wgs[u]) start = std::max(start, free_at[w]);
                 const long r = (units_for(nt, out.subs[u]) + (long)wgs[u].size() - 1) / (long)wgs[u].size();
@@ -237,6 +277,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         if (debug)
             fprintf(stderr, "PLAN nx=%d v=%d kid=%d ntiles=%ld p=%d r=%ld xcd=%d ready=%.2f cost=%.2f finish=%.2f stream=%d local=%d subs=%d\n",
                     nx, v, out.kid[v], out.ntiles[v], p, r, out.xcd[v], ready, run / r, best_finish, sc.stream_of[v], out.local_parent[v], out.subs[v]);
+        for (int c : children[v])
+            if (--waiting[c] == 0) open.push(Key(ready_time(c), -tail[c], c));
     }
 }
 
@@ -256,6 +298,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     plan.n_wg = n_wg;
     plan.xcds = best_nx;
     plan.est_us = best.makespan;
+    plan.order = best.order;
 
     plan.tasks.assign(n, DevTask());
     for (int v = 0; v < n; ++v) {
@@ -340,12 +383,22 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
             subs_of[en.task] = std::min(std::max(en.subs, 1), kSubs);
         }
         auto units_of = [&](int v) { return ((long)plan.tasks[v].ntiles + subs_of[v] - 1) / std::max(subs_of[v], 1); };
-        for (int w = 0; w < plan.n_wg; ++w) {
+        // every list follows one common order of the tasks in which parents come first
+        std::vector<int> pos(n, -1);
+        for (size_t i = 0; i < plan.order.size(); ++i) {
+            const int v = plan.order[i];
+            ok = ok && v >= 0 && v < (int)n && g->tasks[v].fn && pos[v] < 0;
+            if (v >= 0 && v < (int)n) pos[v] = (int)i;
+        }
+        for (size_t v = 0; v < n; ++v) ok = ok && ((pos[v] >= 0) == (g->tasks[v].fn != nullptr));
+        for (auto& e : g->sched.meg)
+            if (g->tasks[e.first].fn && g->tasks[e.second].fn) ok = ok && pos[e.first] < pos[e.second];
+        for (int w = 0; w < plan.n_wg && ok; ++w) {
             int last = -1;
             for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
                 const DevEntry& en = plan.entries[e];
-                ok = ok && en.task > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step;
-                last = en.task;
+                ok = ok && pos[en.task] > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step;
+                last = pos[en.task];
                 ++parts[en.task];
                 where[en.task].insert(where[en.task].end(), {(long)w, (long)en.tile_begin, (long)en.tile_step, (long)en.subs});
                 if (hits[en.task].empty()) hits[en.task].assign((size_t)units_of(en.task), 0);
@@ -358,7 +411,7 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
             ok = ok && plan.tasks[v].ntiles > 0 && hits[v].size() == (size_t)units_of((int)v);
             for (int h : hits[v]) ok = ok && h == 1;
             const DevTask& d = plan.tasks[v];
-            for (int j = 0; j < d.n_parents; ++j) ok = ok && d.parent[j] < (int)v && d.need[j] == parts[d.parent[j]] && parts[d.parent[j]] > 0;
+            for (int j = 0; j < d.n_parents; ++j) ok = ok && pos[d.parent[j]] < pos[v] && d.need[j] == parts[d.parent[j]] && parts[d.parent[j]] > 0;
         }
         for (auto& e : g->sched.meg) {
             const int u = e.first, v = e.second;

@@ -388,16 +388,18 @@ int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks) {
     if (!g) return NG_EINVAL;
     if (g->phase < CAPTURED || !g->rt->d_records) return g->fail(NG_ESTATE, "ng_resident_trace: call ng_capture first");
     Runtime& rt = *g->rt;
-    const size_t bytes = g->nodes.size() * 3 * sizeof(unsigned long long);
+    const size_t n = g->nodes.size(), bytes = n * 4 * sizeof(unsigned long long);
     NG_HIP(hipStreamSynchronize(rt.streams[0]));
     if (ticks) {
         if (!rt.plan.trace) return g->fail(NG_ESTATE, "ng_resident_trace: tracing is off");
         NG_HIP(hipMemcpy(ticks, rt.plan.trace, bytes, hipMemcpyDeviceToHost));
     }
-    if (enable && !rt.plan.trace) {
-        NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.plan.trace), bytes));
-        NG_HIP(hipMemset(rt.plan.trace, 0, bytes));
-    } else if (!enable && rt.plan.trace) {
+    if (enable) {
+        if (!rt.plan.trace) NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.plan.trace), bytes));
+        std::vector<unsigned long long> init(n * 4);                 // minima start at the top, maxima at 0
+        for (size_t v = 0; v < n; ++v) init[4 * v] = init[4 * v + 2] = ~0ull, init[4 * v + 1] = init[4 * v + 3] = 0;
+        NG_HIP(hipMemcpy(rt.plan.trace, init.data(), bytes, hipMemcpyHostToDevice));
+    } else if (rt.plan.trace) {
         NG_HIP(hipFree(rt.plan.trace));
         rt.plan.trace = nullptr;
     }
