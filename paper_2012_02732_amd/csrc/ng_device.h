@@ -18,6 +18,7 @@ enum Kid : int {
     KID_PW_V1, KID_PW_V2, KID_PW_V3, KID_PW_V4,   // 16 x 64 output tile, 128-bit activation loads (HW % 4 == 0)
     KID_PW_S1, KID_PW_S2, KID_PW_S3, KID_PW_S4,   // 16 x 16 output tile, 32-bit activation loads
     KID_BN_R64, KID_BN_R16, KID_ADD_R64, KID_ADD_R16,   // elementwise tasks on the tile grids of those two (resident replay)
+    KID_C3_M1, KID_C3_M2, KID_C3_M3, KID_C3_M4,   // conv3x3 as an implicit GEMM on the matrix cores, 16 x 16 output tile
     KID_COUNT
 };
 
@@ -36,6 +37,11 @@ constexpr int partition_of(int kid) {
                               kid == KID_ADD_R16)
                                  ? PART_R16
                                  : PART_NONE;
+}
+
+// kernels whose tiles keep a compute unit's memory pipeline or matrix cores busy for a while
+constexpr bool is_matrix_kernel(int kid) {
+    return (kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || (kid >= KID_PW_V1 && kid <= KID_PW_S4) || (kid >= KID_C3_M1 && kid <= KID_C3_M4);
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
@@ -126,6 +132,12 @@ struct C3Args {
     int tiles_x;               // pixel tiles along W
     int tiles_xy;              // pixel tiles per image
     int co_groups;             // channel groups (workgroups along Cout)
+    // implicit-GEMM kernels: Y[Cout][cols] = W[Cout][9 Cin] * patches[9 Cin][cols]
+    const float* wp;           // weights repacked into MFMA operand order, 4 k-steps per lane
+    int groups;                // groups of 4 k-steps in the packed copy (a multiple of 4 * groups in flight)
+    int stride;
+    int cols;                  // N * Ho * Wo
+    int tiles_n;               // ceil(cols / 16)
 };
 
 // ---- device-resident replay: the task schedule as data in device memory -------------------

@@ -750,6 +750,79 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
 }
 
 // ------------------------------------------------------------------------------------
+// conv3x3 as an implicit GEMM on the matrix cores: Y[Cout x cols] = W[Cout x 9 Cin] * P[9 Cin x cols]
+// with cols = N * Ho * Wo and P[(ci, dr, dc)][(n, oy, ox)] = x[n][ci][oy S - pad + dr][ox S - pad + dc]
+// (zero outside the image), gathered straight from global memory: the weight tensor
+// [Cout][Cin][3][3] already is that W, row-major, so it is repacked exactly like a 1x1
+// weight matrix with 9 Cin input channels. Same structure as the 16 x 16 conv1x1 above: K split
+// over the four wavefronts in groups of 4 k-steps, G groups in flight, fixed-order reduction.
+// A lane walks k in steps of 4, so (ci, tap) is updated incrementally: tap += 4, carry into ci.
+// ------------------------------------------------------------------------------------
+template <int G, bool FIN, bool FOUT>
+__device__ __forceinline__ void conv3x3_k4_tile(const C3Args& a, int tile, float* smem, int tid, bool live) {
+    static_assert(4 * 4 * 64 <= kSmemFloats, "LDS budget");
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
+    const int colv = bx * 16 + (lane & 15);
+    const int HWo = a.Ho * a.Wo;
+    if (live) {
+        const int groups = a.groups, gw = groups >> 2;
+        const f32x4* ap = reinterpret_cast<const f32x4*>(a.wp) + ((size_t)by * groups + (size_t)wave * gw) * 64 + lane;
+        const int col = min(colv, a.cols - 1);               // columns past the end repeat the last one; never stored
+        const int img = col / HWo, pix = col - img * HWo;
+        const int oy = pix / a.Wo, ox = pix - oy * a.Wo;
+        const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
+        const int HW = a.H * a.W;
+        const float* xb = a.x + (size_t)img * a.Cin * HW;
+        const int k0 = 16 * wave * gw + (lane >> 4);         // this lane's first k; then + 4 per k-step
+        int ci = k0 / 9, tap = k0 - 9 * ci;
+        f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int g0 = 0; g0 < gw; g0 += G) {
+            f32x4 av[G];
+            float bv[G][4];
+            unsigned inside = 0;
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi) {
+                av[gi] = ap[gi * 64];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int dr = (tap * 11) >> 5, dc = tap - 3 * dr;       // tap / 3, tap % 3 for tap < 9
+                    const int iy = iy0 + dr, ix = ix0 + dc;
+                    const bool in = ci < a.Cin && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+                    inside |= (in ? 1u : 0u) << (gi * 4 + q);
+                    const int off = min(ci, a.Cin - 1) * HW + min(max(iy, 0), a.H - 1) * a.W + min(max(ix, 0), a.W - 1);
+                    bv[gi][q] = ldg(a.x, xb + off, FIN);
+                    tap += 4;
+                    if (tap >= 9) tap -= 9, ++ci;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);               // every load of the chunk is issued before the first use
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[gi][q], ((inside >> (gi * 4 + q)) & 1u) ? bv[gi][q] : 0.f, acc, 0, 0, 0);
+            ap += G * 64;
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) smem[(wave * 4 + r) * 64 + lane] = acc[r];
+    }
+    __syncthreads();
+    if (live) {
+        const int m = by * 16 + 4 * (lane >> 4) + wave;      // wavefront w finishes accumulator register w
+        float sum = smem[(0 * 4 + wave) * 64 + lane];
+#pragma unroll
+        for (int w2 = 1; w2 < 4; ++w2) sum += smem[(w2 * 4 + wave) * 64 + lane];
+        if (m < a.Cout && colv < a.cols) {
+            const int img = colv / HWo, pix = colv - img * HWo;
+            stg(a.y, a.y + ((size_t)img * a.Cout + m) * HWo + pix, sum, FOUT);
+        }
+    }
+    __syncthreads();                                         // LDS is reused by the next tile
+}
+
+// ------------------------------------------------------------------------------------
 // kernel table: id -> argument type, tile function, name
 // ------------------------------------------------------------------------------------
 // FIN: activations are read with device-scope loads (some operand was produced on another
@@ -794,6 +867,10 @@ NG_KERNEL(KID_C3_T16S1, C3Args, "conv3x3_t16s1", conv3x3_tile < 16, 1)
 NG_KERNEL(KID_C3_T16S2, C3Args, "conv3x3_t16s2", conv3x3_tile < 16, 2)
 NG_KERNEL(KID_C3_T8S1, C3Args, "conv3x3_t8s1", conv3x3_tile < 8, 1)
 NG_KERNEL(KID_C3_T8S2, C3Args, "conv3x3_t8s2", conv3x3_tile < 8, 2)
+NG_KERNEL(KID_C3_M1, C3Args, "conv3x3_mfma_1", conv3x3_k4_tile < 1)
+NG_KERNEL(KID_C3_M2, C3Args, "conv3x3_mfma_2", conv3x3_k4_tile < 2)
+NG_KERNEL(KID_C3_M3, C3Args, "conv3x3_mfma_3", conv3x3_k4_tile < 3)
+NG_KERNEL(KID_C3_M4, C3Args, "conv3x3_mfma_4", conv3x3_k4_tile < 4)
 #undef NG_KERNEL
 // kernels without further template arguments
 #define NG_KERNEL0(KID, ARGS, NAME, FN)                                                        \
@@ -935,7 +1012,8 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                 NG_CASE(KID_DW_K5S1) NG_CASE(KID_DW_K5S2) NG_CASE(KID_GAP) NG_CASE(KID_FC_GEMV)
                 NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_PW_V1) NG_CASE(KID_PW_V2)
                 NG_CASE(KID_PW_V3) NG_CASE(KID_PW_V4) NG_CASE(KID_PW_S1) NG_CASE(KID_PW_S2) NG_CASE(KID_PW_S3) NG_CASE(KID_PW_S4) NG_CASE(KID_C3_T16S1)
-                NG_CASE(KID_C3_T16S2) NG_CASE(KID_C3_T8S1) NG_CASE(KID_C3_T8S2)
+                NG_CASE(KID_C3_T16S2) NG_CASE(KID_C3_T8S1) NG_CASE(KID_C3_T8S2) NG_CASE(KID_C3_M1) NG_CASE(KID_C3_M2)
+                NG_CASE(KID_C3_M3) NG_CASE(KID_C3_M4)
 #undef NG_CASE
                 default: break;
             }
@@ -998,6 +1076,21 @@ struct PwChoice {
     int groups = 0;           // K4: groups in the packed copy (a multiple of 4 * in_flight); DIRECT32: padded k-steps
     size_t packed = 0;        // floats of repacked weights
 };
+// K split of the 16-row kernels: groups of 4 k-steps, padded so that every wavefront gets
+// the same whole number of chunks of `in_flight` groups.
+void k4_split(long k_total, long cout, PwChoice& c) {
+    const long groups = ceil_div(ceil_div(k_total, 4), 4);
+    long gw = ceil_div(groups, 4);                           // groups per wavefront
+    if (gw <= 4) {
+        c.in_flight = (int)gw;
+    } else {
+        const long pad3 = ceil_div(gw, 3) * 3, pad4 = ceil_div(gw, 4) * 4;
+        c.in_flight = pad3 < pad4 ? 3 : 4;
+        gw = std::min(pad3, pad4);
+    }
+    c.groups = (int)(4 * gw);
+    c.packed = (size_t)((cout + 15) / 16) * c.groups * 256;
+}
 PwChoice choose_pw(const ng_graph* g, int v) {
     PwChoice c;
     const Node& nd = g->nodes[v];
@@ -1018,17 +1111,18 @@ PwChoice choose_pw(const ng_graph* g, int v) {
         return c;
     }
     c.kind = vec ? PwChoice::K4_VEC : PwChoice::K4_WORD;
-    const long groups = ceil_div(ceil_div(cin, 4), 4);
-    long gw = ceil_div(groups, 4);                           // groups per wavefront
-    if (gw <= 4) {
-        c.in_flight = (int)gw;
-    } else {
-        const long pad3 = ceil_div(gw, 3) * 3, pad4 = ceil_div(gw, 4) * 4;
-        c.in_flight = pad3 < pad4 ? 3 : 4;
-        gw = std::min(pad3, pad4);
-    }
-    c.groups = (int)(4 * gw);
-    c.packed = (size_t)((o.c + 15) / 16) * c.groups * 256;
+    k4_split(cin, o.c, c);
+    return c;
+}
+// conv3x3 with at least 8 input channels runs as an implicit GEMM with K = 9 Cin
+PwChoice choose_c3(const ng_graph* g, int v) {
+    PwChoice c;
+    const Node& nd = g->nodes[v];
+    if (nd.op != NG_OP_CONV3X3) return c;
+    const long cin = g->nodes[nd.preds[0]].out.c;
+    if (cin < 8) return c;
+    c.kind = PwChoice::K4_WORD;
+    k4_split(9 * cin, nd.out.c, c);
     return c;
 }
 
@@ -1038,6 +1132,7 @@ PwChoice choose_pw(const ng_graph* g, int v) {
 size_t packed_floats(const ng_graph* g, int v) {
     const Node& nd = g->nodes[v];
     if (nd.op == NG_OP_BN_ACT) return 2 * (size_t)((nd.out.c + 3) & ~3L);   // folded scale, shift
+    if (nd.op == NG_OP_CONV3X3) return choose_c3(g, v).packed;
     return choose_pw(g, v).packed;
 }
 
@@ -1056,9 +1151,10 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
         if (e != hipSuccess) return g->fail(NG_EHIP, "folding batch-norm parameters: %s", hipGetErrorString(e));
         return NG_OK;
     }
-    const PwChoice c = choose_pw(g, v);
+    const bool c3 = nd.op == NG_OP_CONV3X3;
+    const PwChoice c = c3 ? choose_c3(g, v) : choose_pw(g, v);
     if (c.packed == 0) return NG_OK;
-    const int cin = (int)g->nodes[nd.preds[0]].out.c, cout = (int)nd.out.c;
+    const int cin = (int)g->nodes[nd.preds[0]].out.c * (c3 ? 9 : 1), cout = (int)nd.out.c;
     if (!nd.weights[0]) return g->fail(NG_EINVAL, "node %d: weight 0 is a null device pointer", v);
     const dim3 grid((unsigned)((c.packed + kBlock - 1) / kBlock)), block(kBlock);
     if (c.kind == PwChoice::DIRECT32)
@@ -1200,8 +1296,22 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             break;
         }
         case NG_OP_CONV3X3: {
-            C3Args a{buf(nd.preds[0]), wf(0), buf(v), (int)i0.c, (int)o.c, (int)i0.h, (int)i0.w,
-                     (int)o.h, (int)o.w, nd.p.pad, 0, 0, 0};
+            C3Args a{};
+            a.x = buf(nd.preds[0]), a.w = wf(0), a.y = buf(v);
+            a.Cin = (int)i0.c, a.Cout = (int)o.c, a.H = (int)i0.h, a.W = (int)i0.w, a.Ho = (int)o.h, a.Wo = (int)o.w;
+            a.pad = nd.p.pad, a.stride = nd.p.stride;
+            const PwChoice c = choose_c3(g, v);
+            if (c.packed != 0) {
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
+                a.wp = packed, a.groups = c.groups;
+                a.cols = (int)(o.n * o.h * o.w), a.tiles_n = (int)ceil_div(a.cols, 16);
+                const long n = (long)a.tiles_n * ceil_div(a.Cout, 16);
+                if (c.in_flight == 1) set_kernel<KID_C3_M1>(t, a, n);
+                else if (c.in_flight == 2) set_kernel<KID_C3_M2>(t, a, n);
+                else if (c.in_flight == 3) set_kernel<KID_C3_M3>(t, a, n);
+                else set_kernel<KID_C3_M4>(t, a, n);
+                break;
+            }
             const bool small = o.h * o.w <= 24 * 24;       // small maps: 8 x 8 tiles waste fewer lanes
             const int tp = small ? 8 : 16;
             a.tiles_x = (int)ceil_div(o.w, tp);

@@ -43,6 +43,8 @@ constexpr double kSyncNearUs = 1.1;   // completion counter -> dependent workgro
 constexpr double kSyncFarUs = 1.5;    // extra cost when producer and consumer sit on different XCDs (measured)
 constexpr double kPublishUs = 0.3;    // stores drained and counter bumped: the workgroup moves on to its next entry
 constexpr double kLocalUs = 0.1;      // hand-over inside one workgroup: one barrier
+constexpr double kSpreadPenaltyUs = 5.0; // what spreading a task over all XCDs must gain before it is preferred (its readers go the long way too)
+constexpr double kFarRunFactor = 1.2; // a tile whose loads and stores all go through the memory side takes longer
 
 // Expected time of one round of a task, in microseconds, when `subs` sub-blocks of a
 // workgroup take a tile each: a latency part that does not depend on how many tiles share
@@ -76,6 +78,11 @@ double tile_round_us(const ng_graph* g, int v, int kid, int subs) {
             break;
         }
         case KID_C3_T16S1: case KID_C3_T16S2: case KID_C3_T8S1: case KID_C3_T8S2: base = 1.0, per_tile = 0.375 * cin; break;
+        case KID_C3_M1: case KID_C3_M2: case KID_C3_M3: case KID_C3_M4: {
+            const C3Args* a = reinterpret_cast<const C3Args*>(g->tasks[v].args);
+            base = 1.8, per_tile = 0.2 * (a->groups / 4);
+            break;
+        }
         default: break;
     }
     return base + per_tile * subs;
@@ -183,7 +190,6 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         if (g->tasks[v].fn && waiting[v] == 0) open.push(Key(0.0, -tail[v], v));
     out.order.clear();
 
-    std::vector<int> cand;
     while (!open.empty()) {
         const int v = std::get<2>(open.top());
         open.pop();
@@ -192,41 +198,61 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         const int home = stream_xcd[sc.stream_of[v]];
         out.kid[v] = t.kid;
         out.ntiles[v] = t.ntiles;
-        const bool wide = nx > 1 && sc.solo[v] && units_for(t.ntiles, kSubs) > per_xcd;
-        out.xcd[v] = nx == 1 ? 0 : (wide ? -1 : home);
-        cand.clear();
-        for (int w = 0; w < n_wg; ++w) {
-            const int x = w % 8;
-            if (x >= nx) continue;
-            if (wide || x == home) cand.push_back(w);
-        }
-        auto ready_without = [&](int skip) {
+        // Two placements are compared: on the XCD of the task's stream (inputs and outputs
+        // stay in that L2 when the neighbours are there too), or spread over every
+        // participating XCD (more workgroups, but everything the task touches goes through
+        // the memory side, and so does whatever reads its result).
+        auto ready_at = [&](int xcd_v, int skip) {
             double ready = 0;
             for (int u : parents[v]) {
                 if (!g->tasks[u].fn || u == skip) continue;
-                const bool far = out.xcd[u] < 0 || out.xcd[v] < 0 || out.xcd[u] != out.xcd[v] || g->resident_all_far;
+                const bool far = out.xcd[u] < 0 || xcd_v < 0 || out.xcd[u] != xcd_v || g->resident_all_far;
                 ready = std::max(ready, finish[u] + (far ? kSyncFarUs : 0.0));
             }
             return ready;
         };
-        const double ready = ready_without(-1);
-        // workgroups in the order they become available for this task
-        std::stable_sort(cand.begin(), cand.end(), [&](int a, int b) { return free_at[a] < free_at[b]; });
-        int best_p = 1, best_subs = kSubs;
-        double best_finish = 1e300;
         // only the matrix kernels keep a compute unit's memory pipeline busy enough to be worth
         // spreading one tile per workgroup; for the others fewer participants is what counts
-        const bool heavy = (t.kid >= KID_PW_D4 && t.kid <= KID_C3_T8S2) || (t.kid >= KID_PW_V1 && t.kid <= KID_PW_S4);
-        for (int subs = kSubs; subs >= (heavy ? 1 : kSubs); --subs) {
-            const long units = units_for(t.ntiles, subs);
-            const double cost = tile_round_us(g, v, t.kid, subs);
-            for (int rounds = 1; rounds <= 4; ++rounds) {
-                const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)cand.size());
-                const long r = (units + p - 1) / p;
-                const double f = std::max(ready, free_at[cand[p - 1]]) + r * cost + kSyncNearUs;
-                if (f < best_finish - 1e-9) best_finish = f, best_p = p, best_subs = subs;
+        const bool heavy = is_matrix_kernel(t.kid);
+        struct Placement {
+            double finish = 1e300, ready = 0;
+            int p = 1, subs = kSubs;
+            std::vector<int> cand;
+        };
+        auto place = [&](bool spread) {
+            Placement pl;
+            for (int w = 0; w < n_wg; ++w) {
+                const int x = w % 8;
+                if (x < nx && (spread || x == home)) pl.cand.push_back(w);
             }
+            pl.ready = ready_at(nx == 1 ? 0 : (spread ? -1 : home), -1);
+            // workgroups in the order they become available for this task
+            std::stable_sort(pl.cand.begin(), pl.cand.end(), [&](int a, int b) { return free_at[a] < free_at[b]; });
+            for (int subs = kSubs; subs >= (heavy ? 1 : kSubs); --subs) {
+                const long units = units_for(t.ntiles, subs);
+                const double cost = tile_round_us(g, v, t.kid, subs) * (spread ? kFarRunFactor : 1.0);
+                for (int rounds = 1; rounds <= 4; ++rounds) {
+                    const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)pl.cand.size());
+                    const long r = (units + p - 1) / p;
+                    const double f = std::max(pl.ready, free_at[pl.cand[p - 1]]) + r * cost + kSyncNearUs;
+                    if (f < pl.finish - 1e-9) pl.finish = f, pl.p = p, pl.subs = subs;
+                }
+            }
+            return pl;
+        };
+        Placement chosen = place(false);
+        bool wide = false;
+        if (nx > 1 && units_for(t.ntiles, kSubs) > per_xcd) {
+            Placement spread = place(true);
+            // what reads the result pays for the longer way too, unless nothing can run beside this task anyway
+            if (spread.finish + (sc.solo[v] ? 0.0 : kSpreadPenaltyUs) < chosen.finish) chosen = std::move(spread), wide = true;
         }
+        out.xcd[v] = nx == 1 ? 0 : (wide ? -1 : home);
+        const std::vector<int>& cand = chosen.cand;
+        const double ready = chosen.ready;
+        int best_p = chosen.p, best_subs = chosen.subs;
+        double best_finish = chosen.finish;
+        auto ready_without = [&](int skip) { return ready_at(out.xcd[v], skip); };
         // Alternative for an elementwise task: take over the partition and the workgroups of
         // an E' parent with the same output shape on the same XCD. Tile i then depends only on
         // what the same workgroup wrote a moment ago, and the wait for that parent is dropped.
