@@ -177,13 +177,20 @@ enum {
     NG_MODE_GRAPH_SINGLE = 1, /* captured single-stream graph */
     NG_MODE_EAGER_SINGLE = 2, /* task table launched kernel by kernel on the origin stream */
     NG_MODE_EAGER_MULTI = 3,  /* task table launched on the assigned streams with real events */
-    NG_MODE_DEVICE_RESIDENT = 4 /* one launch; persistent workgroups walk the recorded schedule themselves:
+    NG_MODE_DEVICE_RESIDENT = 4, /* one launch; persistent workgroups walk the recorded schedule themselves:
                                    a stream = a gang of workgroups serving its tasks in FIFO order, an event =
                                    a completion counter in device memory (record = release add, wait = poll +
                                    acquire). Raw submission of the task schedule (Section 4.1) without the
                                    command processor between dependent tasks. */
+    NG_MODE_AUTO = 5          /* whichever of modes 0, 1 and 4 was fastest in a short trial at ng_capture (an
+                                   ahead-of-time choice like the rest of the schedule: DAGs of many tiny tasks
+                                   gain most from mode 4, plain chains and large tasks from a HIP graph) */
 };
 int ng_replay_mode(ng_graph* g, int mode);
+/* The mode NG_MODE_AUTO stands for (0, 1 or 4) and the median replay + wait times, in
+ * microseconds, the trial at ng_capture measured for modes 0, 1 and 4 (HOST array of 3;
+ * either pointer may be NULL). */
+int ng_auto_mode(const ng_graph* g, int* mode, float* trial_us);
 /* Asynchronous: enqueue one inference on the origin stream (hip_streams[0]). */
 int ng_replay(ng_graph* g);
 /* Wait until the origin stream is idle. */

@@ -15,7 +15,7 @@ NG_MAX_PREDS = 8
 NG_OK, NG_EINVAL, NG_ESHAPE, NG_ESTATE, NG_ENOMEM, NG_EHIP = 0, -1, -2, -3, -4, -5
 (NG_OP_INPUT, NG_OP_CONV1X1, NG_OP_DWCONV, NG_OP_CONV3X3, NG_OP_BN_ACT, NG_OP_RELU, NG_OP_ADD_N,
  NG_OP_CONCAT, NG_OP_POOL, NG_OP_GLOBAL_AVGPOOL, NG_OP_FC) = range(11)
-NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_EAGER_SINGLE, NG_MODE_EAGER_MULTI, NG_MODE_DEVICE_RESIDENT = range(5)
+NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_EAGER_SINGLE, NG_MODE_EAGER_MULTI, NG_MODE_DEVICE_RESIDENT, NG_MODE_AUTO = range(6)
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnimble_graph.so")
 
@@ -24,7 +24,7 @@ SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_ou
            "ng_node_shape", "ng_schedule", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
            "ng_plan_memory", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
-           "ng_resident_dry_plan", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
+           "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
 
 
@@ -62,6 +62,7 @@ _sig = {
     "ng_replay": (_I, [_P]),
     "ng_sync": (_I, [_P]),
     "ng_resident_config": (_I, [_P, _I, _I, C.c_uint, _I]),
+    "ng_auto_mode": (_I, [_P, _IP, C.POINTER(C.c_float)]),
     "ng_resident_dry_plan": (_I, [_P, _I, _I, _DP, _IP, _IP, _IP]),
     "ng_resident_sizes": (_I, [_P, _IP, _IP, _IP, _DP]),
     "ng_resident_trace": (_I, [_P, _I, C.POINTER(C.c_ulonglong)]),
@@ -214,6 +215,13 @@ def ng_sync(g):
 
 def ng_resident_config(g, workgroups_per_cu=0, xcds=0, spin_limit=0, device_scope_everywhere=0):
     check(g, lib.ng_resident_config(g, workgroups_per_cu, xcds, spin_limit, device_scope_everywhere))
+
+
+def ng_auto_mode(g):
+    """(mode NG_MODE_AUTO resolves to, {mode: trial median in microseconds})"""
+    m, t = C.c_int(), (C.c_float * 3)()
+    check(g, lib.ng_auto_mode(g, C.byref(m), t))
+    return m.value, {NG_MODE_GRAPH_MULTI: t[0], NG_MODE_GRAPH_SINGLE: t[1], NG_MODE_DEVICE_RESIDENT: t[2]}
 
 
 def ng_resident_dry_plan(g, n_workgroups=256, xcds=0) -> dict:

@@ -84,6 +84,8 @@ struct ng_graph {
     std::vector<ng::Task> tasks;
     ng::Runtime* rt = nullptr;
     int mode = NG_MODE_GRAPH_MULTI;
+    int auto_mode = NG_MODE_GRAPH_MULTI;                 // what NG_MODE_AUTO resolves to (set by ng_capture)
+    float auto_trial_us[3] = {0, 0, 0};                  // trial medians of modes 0, 1, 4
     int resident_wg_per_cu = 0;                          // 0 = pick automatically
     int resident_xcds = 0;                               // XCDs the resident kernel spreads over, 0 = all 8
     unsigned resident_spin_limit = ng::kDefaultSpinLimit; // polls before a wait gives up

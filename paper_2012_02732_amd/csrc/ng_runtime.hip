@@ -11,6 +11,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <chrono>
 #include <cstdlib>
 #include <cstring>
 
@@ -330,6 +331,39 @@ int ng_capture(ng_graph* g) {
     NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
     NG_HIP(hipStreamSynchronize(rt.streams[0]));
     g->phase = CAPTURED;
+    // short trial: which way of replaying this schedule is fastest on this DAG
+    {
+        const int candidates[3] = {NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_DEVICE_RESIDENT};
+        const int saved = g->mode;
+        float best = 0;
+        for (int i = 0; i < 3; ++i) {
+            g->mode = candidates[i];
+            std::vector<float> us;
+            for (int rep = 0; rep < 2 + 9; ++rep) {
+                const auto t0 = std::chrono::steady_clock::now();
+                int rc = ng_replay(g);
+                if (rc == NG_OK) rc = ng_sync(g);
+                if (rc != NG_OK) {
+                    g->mode = saved;
+                    return rc;
+                }
+                if (rep >= 2) us.push_back(std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count());
+            }
+            std::sort(us.begin(), us.end());
+            g->auto_trial_us[i] = us[us.size() / 2];
+            if (i == 0 || g->auto_trial_us[i] < best) best = g->auto_trial_us[i], g->auto_mode = candidates[i];
+        }
+        g->mode = saved;
+    }
+    return NG_OK;
+}
+
+int ng_auto_mode(const ng_graph* g, int* mode, float* trial_us) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_auto_mode: call ng_capture first");
+    if (mode) *mode = g->auto_mode;
+    if (trial_us)
+        for (int i = 0; i < 3; ++i) trial_us[i] = g->auto_trial_us[i];
     return NG_OK;
 }
 
@@ -340,7 +374,7 @@ void* ng_tensor_ptr(const ng_graph* g, int id) {
 
 int ng_replay_mode(ng_graph* g, int mode) {
     if (!g) return NG_EINVAL;
-    if (mode < NG_MODE_GRAPH_MULTI || mode > NG_MODE_DEVICE_RESIDENT) return g->fail(NG_EINVAL, "ng_replay_mode: unknown mode %d", mode);
+    if (mode < NG_MODE_GRAPH_MULTI || mode > NG_MODE_AUTO) return g->fail(NG_EINVAL, "ng_replay_mode: unknown mode %d", mode);
     g->mode = mode;
     return NG_OK;
 }
@@ -349,7 +383,7 @@ int ng_replay(ng_graph* g) {
     if (!g) return NG_EINVAL;
     if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_replay: call ng_capture first");
     Runtime& rt = *g->rt;
-    switch (g->mode) {
+    switch (g->mode == NG_MODE_AUTO ? g->auto_mode : g->mode) {
         case NG_MODE_GRAPH_MULTI: NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0])); return NG_OK;
         case NG_MODE_GRAPH_SINGLE: NG_HIP(hipGraphLaunch(rt.exec[1], rt.streams[0])); return NG_OK;
         case NG_MODE_EAGER_SINGLE: return issue_all(g, false);

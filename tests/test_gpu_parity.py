@@ -91,7 +91,14 @@ def test_pool_and_depthwise(shape):
 @pytest.mark.parametrize("shape,couts", [((1, 16, 8, 8), (16, 1, 33)), ((1, 44, 28, 28), (44, 88)),
                                          ((2, 37, 7, 7), (50, 5)), ((1, 264, 14, 14), (88,)),
                                          ((4, 64, 17, 17), (192,)), ((1, 3, 5, 3), (7,)),
-                                         ((3, 130, 33, 31), (70,))])
+                                         ((3, 130, 33, 31), (70,)),
+                                         # one case per depth class of the 16-row kernels (1..4 groups of 4 k-steps
+                                         # in flight, one or several chunks), 128-bit and 32-bit activation loads
+                                         ((1, 88, 14, 14), (88,)), ((1, 512, 8, 8), (40,)), ((2, 176, 4, 4), (30,)),
+                                         ((1, 528, 7, 7), (176,)), ((1, 176, 7, 7), (176,)), ((1, 256, 7, 7), (17,)),
+                                         ((1, 100, 5, 5), (33,)), ((1, 20, 3, 5), (16,)),
+                                         # enough 64 x 64 tiles for the LDS-tiled throughput kernel
+                                         ((8, 64, 56, 56), (64,))])
 def test_conv1x1_mfma(shape, couts):
     def build(b):
         x = b.input(*shape)
@@ -249,5 +256,48 @@ def test_device_resident_wait_gives_up_and_recovers():
         again = r.run(mode=B.NG_MODE_DEVICE_RESIDENT)
         for k in good:
             assert np.array_equal(good[k], again[k])
+    finally:
+        r.close()
+
+
+def test_auto_mode_picks_the_fastest_trial_and_replays_correctly():
+    w = workloads.make("random200")
+    ref = forward(w)
+    r = GraphRunner(w, DEV)
+    r.prepare()
+    try:
+        mode, trial = B.ng_auto_mode(r.g)
+        assert mode in (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT)
+        assert all(t > 0 for t in trial.values()) and trial[mode] == min(trial.values())
+        out = r.run(mode=B.NG_MODE_AUTO)
+        for v in w.outputs:
+            assert rel_err(out[v], ref[v]) <= TOL
+    finally:
+        r.close()
+
+
+def test_device_resident_timeline_respects_the_dag():
+    """One traced replay: every task ran, a task's inputs are never ready before the last
+    workgroup of each E' parent has stored its tiles (the completion protocol at work), and
+    the trace is cleared when switched on again."""
+    w = workloads.make("random200")
+    r = GraphRunner(w, DEV)
+    sched = r.prepare()
+    try:
+        B.ng_replay_mode(r.g, B.NG_MODE_DEVICE_RESIDENT)
+        B.ng_replay(r.g); B.ng_sync(r.g)
+        B.ng_resident_trace(r.g, 1)
+        B.ng_replay(r.g); B.ng_sync(r.g)
+        tr = B.ng_resident_trace(r.g, 1, fetch=True)
+        tasks = [v for v, nd in enumerate(w.nodes) if nd.op != "input"]
+        assert all(tr[v] is not None for v in tasks)
+        for v in tasks:
+            first_wait, last_ready, first_done, last_done = tr[v]
+            assert first_wait <= last_ready <= last_done and first_done <= last_done
+        for u, v in sched["meg"]:
+            if tr[u] is not None:
+                assert tr[u][3] <= tr[v][1], (u, v, tr[u], tr[v])
+        again = B.ng_resident_trace(r.g, 0, fetch=True)       # switched on again above: nothing recorded since
+        assert all(t is None for t in again)
     finally:
         r.close()
