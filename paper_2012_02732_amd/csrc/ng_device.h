@@ -19,6 +19,7 @@ enum Kid : int {
     KID_PW_S1, KID_PW_S2, KID_PW_S3, KID_PW_S4,   // 16 x 16 output tile, 32-bit activation loads
     KID_BN_R64, KID_BN_R16, KID_ADD_R64, KID_ADD_R16,   // elementwise tasks on the tile grids of those two (resident replay)
     KID_C3_M1, KID_C3_M2, KID_C3_M3, KID_C3_M4,   // conv3x3 as an implicit GEMM on the matrix cores, 16 x 16 output tile
+    KID_POOL_P4, KID_DW_K3S1_P4,     // windowed kernels with 4 outputs per thread (resident replay)
     KID_COUNT
 };
 
@@ -29,7 +30,7 @@ constexpr int partition_of(int kid) {
     return (kid == KID_BN || kid == KID_ADD || kid == KID_CONCAT || kid == KID_POOL || kid == KID_DW_K3S1 ||
             kid == KID_DW_K3S2 || kid == KID_DW_K5S1 || kid == KID_DW_K5S2)
                ? PART_L256
-               : (kid == KID_BN_V4 || kid == KID_ADD_V4 || kid == KID_CONCAT_V4)
+               : (kid == KID_BN_V4 || kid == KID_ADD_V4 || kid == KID_CONCAT_V4 || kid == KID_POOL_P4 || kid == KID_DW_K3S1_P4)
                      ? PART_L1024
                      : (kid == KID_PW_V1 || kid == KID_PW_V2 || kid == KID_PW_V3 || kid == KID_PW_V4 || kid == KID_BN_R64 || kid == KID_ADD_R64)
                            ? PART_R64

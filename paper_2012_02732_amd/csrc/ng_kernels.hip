@@ -214,14 +214,14 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
 // ------------------------------------------------------------------------------------
 // pool3x3: max (out-of-bounds taps ignored) or average over the in-bounds taps
 // ------------------------------------------------------------------------------------
-// Outputs per thread of the windowed kernels: a task should fit its stream's gang in one
-// round, and one round costs one memory round trip however many loads are in flight.
-constexpr int kPoolPerThread = 1;
-
-template <bool FIN, bool FOUT>
+// Windowed kernels: a tile is 256 P consecutive outputs, thread t owns outputs t, t + 256, ...
+// of it (P = 1 for stand-alone launches; P = 4 when a task would otherwise need several
+// rounds on the workgroups of its stream - one round costs one trip to memory however many
+// loads are in flight, and 1024 consecutive outputs are also the tile of the float4
+// elementwise kernels, which can then take over the partition).
+template <int P, bool FIN, bool FOUT>
 __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*, int tid, bool live) {
-    constexpr int P = kPoolPerThread;
-    const int base = (tile * kBlock + tid) * P;
+    const int base = tile * kBlock * P + tid;
     if (!live || base >= a.total) return;
     // all taps of all P outputs are loaded unconditionally from clamped coordinates, so the
     // loads are independent and in flight together; taps outside the image are masked afterwards
@@ -229,7 +229,7 @@ __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*
     int r0[P], c0[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-        const int i = min(base + p, a.total - 1);
+        const int i = min(base + p * kBlock, a.total - 1);
         const int ow = i % a.Wo, t = i / a.Wo;
         const int oh = t % a.Ho, plane = t / a.Ho;
         const float* src = a.x + (size_t)plane * a.H * a.W;
@@ -255,26 +255,23 @@ __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*
                 else acc += in ? v[p][dr * 3 + dc] : 0.f;
                 cnt += in;
             }
-        if (base + p < a.total) stg(a.y, a.y + base + p, a.mode == 0 ? acc : acc / (float)cnt, FOUT);
+        if (base + p * kBlock < a.total) stg(a.y, a.y + base + p * kBlock, a.mode == 0 ? acc : acc / (float)cnt, FOUT);
     }
 }
 
 // ------------------------------------------------------------------------------------
 // dwconv: depthwise K x K, pad K/2, stride S; P outputs per thread
 // ------------------------------------------------------------------------------------
-constexpr int dw_per_thread(int k) { return 1; }
-
-template <int K, int S, bool FIN, bool FOUT>
+template <int K, int S, int P, bool FIN, bool FOUT>
 __device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*, int tid, bool live) {
-    constexpr int P = dw_per_thread(K);
-    const int base = (tile * kBlock + tid) * P;
+    const int base = tile * kBlock * P + tid;
     if (!live || base >= a.total) return;
     // unconditional loads from clamped coordinates (all in flight together), masked afterwards
     float v[P][K * K], w[P][K * K];
     int r0[P], c0[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
-        const int i = min(base + p, a.total - 1);
+        const int i = min(base + p * kBlock, a.total - 1);
         const int ow = i % a.Wo, t = i / a.Wo;
         const int oh = t % a.Ho, plane = t / a.Ho;
         const float* src = a.x + (size_t)plane * a.H * a.W;
@@ -300,7 +297,7 @@ __device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*, i
                 const bool in = r >= 0 && r < a.H && cc >= 0 && cc < a.W;
                 acc = fmaf(w[p][dr * K + dc], in ? v[p][dr * K + dc] : 0.f, acc);
             }
-        if (base + p < a.total) stg(a.y, a.y + base + p, acc, FOUT);
+        if (base + p * kBlock < a.total) stg(a.y, a.y + base + p * kBlock, acc, FOUT);
     }
 }
 
@@ -847,10 +844,13 @@ NG_KERNEL(KID_ADD, AddArgs, "add_n", add_n_tile < PART_L256)
 NG_KERNEL(KID_ADD_V4, AddArgs, "add_n_v4", add_n_tile < PART_L1024)
 NG_KERNEL(KID_CONCAT, ConcatArgs, "concat", concat_tile < false)
 NG_KERNEL(KID_CONCAT_V4, ConcatArgs, "concat_v4", concat_tile < true)
-NG_KERNEL(KID_DW_K3S1, DwArgs, "dwconv_k3s1", dwconv_tile < 3, 1)
-NG_KERNEL(KID_DW_K3S2, DwArgs, "dwconv_k3s2", dwconv_tile < 3, 2)
-NG_KERNEL(KID_DW_K5S1, DwArgs, "dwconv_k5s1", dwconv_tile < 5, 1)
-NG_KERNEL(KID_DW_K5S2, DwArgs, "dwconv_k5s2", dwconv_tile < 5, 2)
+NG_KERNEL(KID_DW_K3S1, DwArgs, "dwconv_k3s1", dwconv_tile < 3, 1, 1)
+NG_KERNEL(KID_DW_K3S2, DwArgs, "dwconv_k3s2", dwconv_tile < 3, 2, 1)
+NG_KERNEL(KID_DW_K5S1, DwArgs, "dwconv_k5s1", dwconv_tile < 5, 1, 1)
+NG_KERNEL(KID_DW_K5S2, DwArgs, "dwconv_k5s2", dwconv_tile < 5, 2, 1)
+NG_KERNEL(KID_DW_K3S1_P4, DwArgs, "dwconv_k3s1_p4", dwconv_tile < 3, 1, 4)
+NG_KERNEL(KID_POOL, PoolArgs, "pool3x3", pool3x3_tile < 1)
+NG_KERNEL(KID_POOL_P4, PoolArgs, "pool3x3_p4", pool3x3_tile < 4)
 NG_KERNEL(KID_PW_D4, PwArgs, "conv1x1_mfma_d4", conv1x1_direct_tile < 4)
 NG_KERNEL(KID_PW_D8, PwArgs, "conv1x1_mfma_d8", conv1x1_direct_tile < 8)
 NG_KERNEL(KID_PW_D16, PwArgs, "conv1x1_mfma_d16", conv1x1_direct_tile < 16)
@@ -882,7 +882,6 @@ NG_KERNEL(KID_C3_M4, C3Args, "conv3x3_mfma_4", conv3x3_k4_tile < 4)
             FN<FIN, FOUT>(a, t, smem, tid, live);                                              \
         }                                                                                      \
     };
-NG_KERNEL0(KID_POOL, PoolArgs, "pool3x3", pool3x3_tile)
 NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
 NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
 #undef NG_KERNEL0
@@ -1008,7 +1007,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
 #define NG_CASE(KID) case KID: run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out); break;
                 NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_R64) NG_CASE(KID_BN_R16) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
                 NG_CASE(KID_ADD_R64) NG_CASE(KID_ADD_R16)
-                NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
+                NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_POOL_P4) NG_CASE(KID_DW_K3S1_P4) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
                 NG_CASE(KID_DW_K5S1) NG_CASE(KID_DW_K5S2) NG_CASE(KID_GAP) NG_CASE(KID_FC_GEMV)
                 NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_PW_V1) NG_CASE(KID_PW_V2)
                 NG_CASE(KID_PW_V3) NG_CASE(KID_PW_V4) NG_CASE(KID_PW_S1) NG_CASE(KID_PW_S2) NG_CASE(KID_PW_S3) NG_CASE(KID_PW_S4) NG_CASE(KID_C3_T16S1)
@@ -1234,12 +1233,12 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
         case NG_OP_POOL: {
             PoolArgs a{buf(nd.preds[0]), buf(v), (int)i0.h, (int)i0.w, (int)o.h, (int)o.w,
                        nd.p.stride, nd.p.pad, nd.p.pool_mode, total};
-            set_kernel<KID_POOL>(t, a, ceil_div(total, kBlock * kPoolPerThread));
+            set_kernel<KID_POOL>(t, a, ceil_div(total, kBlock));
             break;
         }
         case NG_OP_DWCONV: {
             DwArgs a{buf(nd.preds[0]), wf(0), buf(v), (int)o.c, (int)i0.h, (int)i0.w, (int)o.h, (int)o.w, total};
-            const long n = ceil_div(total, kBlock * dw_per_thread(nd.p.k));
+            const long n = ceil_div(total, kBlock);
             if (nd.p.k == 3 && nd.p.stride == 1) set_kernel<KID_DW_K3S1>(t, a, n);
             else if (nd.p.k == 3) set_kernel<KID_DW_K3S2>(t, a, n);
             else if (nd.p.stride == 1) set_kernel<KID_DW_K5S1>(t, a, n);

@@ -61,6 +61,7 @@ double tile_round_us(const ng_graph* g, int v, int kid, int subs) {
         case KID_ADD: case KID_ADD_V4: case KID_ADD_R64: case KID_ADD_R16: base = 0.9, per_tile = 0.1; break;
         case KID_CONCAT: case KID_CONCAT_V4: base = 1.6, per_tile = 0.2; break;
         case KID_POOL: base = 1.6, per_tile = 0.25; break;
+        case KID_POOL_P4: case KID_DW_K3S1_P4: base = 1.9, per_tile = 0.6; break;
         case KID_DW_K3S1: case KID_DW_K3S2: base = 1.5, per_tile = 0.25; break;
         case KID_DW_K5S1: case KID_DW_K5S2: base = 2.0, per_tile = 0.7; break;
         case KID_GAP: base = 1.0, per_tile = 0.1; break;
@@ -198,6 +199,15 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         const int home = stream_xcd[sc.stream_of[v]];
         out.kid[v] = t.kid;
         out.ntiles[v] = t.ntiles;
+        // a windowed task that would need four or more rounds on its stream's workgroups gets 4 outputs
+        // per thread (4 x the index arithmetic in one round: pays off only from there)
+        if (units_for(t.ntiles, kSubs) > 3 * per_xcd && (t.kid == KID_POOL || t.kid == KID_DW_K3S1) &&
+            !getenv("NG_NO_P4")) {
+            out.kid[v] = t.kid == KID_POOL ? KID_POOL_P4 : KID_DW_K3S1_P4;
+            out.ntiles[v] = (g->nodes[v].out.elems() + 4 * kBlock - 1) / (4 * kBlock);
+        }
+        const int kid0 = out.kid[v];                        // before a possible change of partition below
+        const long ntiles0 = out.ntiles[v];
         // Two placements are compared: on the XCD of the task's stream (inputs and outputs
         // stay in that L2 when the neighbours are there too), or spread over every
         // participating XCD (more workgroups, but everything the task touches goes through
@@ -213,7 +223,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         };
         // only the matrix kernels keep a compute unit's memory pipeline busy enough to be worth
         // spreading one tile per workgroup; for the others fewer participants is what counts
-        const bool heavy = is_matrix_kernel(t.kid);
+        const bool heavy = is_matrix_kernel(kid0);
         struct Placement {
             double finish = 1e300, ready = 0;
             int p = 1, subs = kSubs;
@@ -229,8 +239,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             // workgroups in the order they become available for this task
             std::stable_sort(pl.cand.begin(), pl.cand.end(), [&](int a, int b) { return free_at[a] < free_at[b]; });
             for (int subs = kSubs; subs >= (heavy ? 1 : kSubs); --subs) {
-                const long units = units_for(t.ntiles, subs);
-                const double cost = tile_round_us(g, v, t.kid, subs) * (spread ? kFarRunFactor : 1.0);
+                const long units = units_for(ntiles0, subs);
+                const double cost = tile_round_us(g, v, kid0, subs) * (spread ? kFarRunFactor : 1.0);
                 for (int rounds = 1; rounds <= 4; ++rounds) {
                     const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)pl.cand.size());
                     const long r = (units + p - 1) / p;
@@ -242,7 +252,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         };
         Placement chosen = place(false);
         bool wide = false;
-        if (nx > 1 && units_for(t.ntiles, kSubs) > per_xcd) {
+        if (nx > 1 && units_for(ntiles0, kSubs) > per_xcd) {
             Placement spread = place(true);
             // what reads the result pays for the longer way too, unless nothing can run beside this task anyway
             if (spread.finish + (sc.solo[v] ? 0.0 : kSpreadPenaltyUs) < chosen.finish) chosen = std::move(spread), wide = true;
@@ -287,7 +297,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         } else {
             out.subs[v] = best_subs;
             wgs[v].assign(cand.begin(), cand.begin() + best_p);
-            r = (units_for(t.ntiles, best_subs) + best_p - 1) / best_p;
+            r = (units_for(ntiles0, best_subs) + best_p - 1) / best_p;
             begin = -1;
         }
         const int p = (int)wgs[v].size();
