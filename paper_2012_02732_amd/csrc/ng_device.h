@@ -45,6 +45,10 @@ constexpr bool is_matrix_kernel(int kid) {
     return (kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || (kid >= KID_PW_V1 && kid <= KID_PW_S4) || (kid >= KID_C3_M1 && kid <= KID_C3_M4);
 }
 
+// kernels of the lean build of the resident kernel: everything except the 32 x 32 and LDS-tiled
+// conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
+constexpr bool is_lean_kernel(int kid) { return !(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2; }
+
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
 constexpr int kSubs = 2;             // tiles a workgroup of the resident kernel works on at a time
 constexpr int kGroup = kBlock * kSubs;  // threads per workgroup of the resident kernel

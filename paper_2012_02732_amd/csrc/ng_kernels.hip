@@ -939,6 +939,9 @@ __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int s
 #undef NG_LOOP
 }
 
+// FULL = false leaves out the kernels that only large problems use (see is_lean_kernel): their
+// register needs would otherwise shape the allocation of the whole replay kernel.
+template <bool FULL>
 __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned epoch) {
     __shared__ float smem_all[kSubs * kSmemFloats];
     __shared__ uint4 recs[kRecordsInLds * (kRecordWords / 4)];
@@ -1004,7 +1007,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             }
             if (tracer) atomicMax(plan.trace + 4 * task + 1, wall_clock64());
             switch (kid) {
-#define NG_CASE(KID) case KID: run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out); break;
+#define NG_CASE(KID) case KID: if (FULL || is_lean_kernel(KID)) run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out); break;
                 NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_R64) NG_CASE(KID_BN_R16) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
                 NG_CASE(KID_ADD_R64) NG_CASE(KID_ADD_R16)
                 NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_POOL_P4) NG_CASE(KID_DW_K3S1_P4) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
@@ -1059,7 +1062,9 @@ int pw_padded_steps(long cin) {
 
 }  // namespace
 
-const void* resident_kernel_handle() { return reinterpret_cast<const void*>(&resident_kernel); }
+const void* resident_kernel_handle(bool full) {
+    return full ? reinterpret_cast<const void*>(&resident_kernel<true>) : reinterpret_cast<const void*>(&resident_kernel<false>);
+}
 
 namespace {
 __global__ void empty_kernel() {}

@@ -38,6 +38,7 @@ struct Runtime {
     void* d_wg_first = nullptr;
     int* h_error = nullptr;                // pinned host memory
     int n_wg = 0, n_entries = 0;
+    bool resident_full = true;             // the DAG uses kernels the lean build of the resident kernel leaves out
     unsigned epoch = 0;
     size_t done_words = 0;
     int xcds = 0;
@@ -158,7 +159,10 @@ int build_resident(ng_graph* g) {
     int dev = 0, cus = 0, per_cu = 0;
     NG_HIP(hipGetDevice(&dev));
     NG_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    NG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel_handle(), kGroup, 0));
+    rt.resident_full = false;
+    for (const Task& t : g->tasks)
+        if (t.fn && !is_lean_kernel(t.kid)) rt.resident_full = true;
+    NG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel_handle(rt.resident_full), kGroup, 0));
     if (per_cu < 1 || cus < 8) return g->fail(NG_EHIP, "device-resident replay: kernel does not fit (%d per CU, %d CUs)", per_cu, cus);
     per_cu = std::min(per_cu, g->resident_wg_per_cu > 0 ? g->resident_wg_per_cu : 1);   // one per CU: two slow each other's hand-overs down
     const int n_wg = cus * per_cu / 8 * 8;
@@ -230,7 +234,7 @@ int launch_resident(ng_graph* g) {
     rt.plan.spin_limit = g->resident_spin_limit;
     unsigned epoch = ++rt.epoch;
     void* args[2] = {&rt.plan, &epoch};
-    NG_HIP(hipLaunchKernel(resident_kernel_handle(), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
+    NG_HIP(hipLaunchKernel(resident_kernel_handle(rt.resident_full), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
     return NG_OK;
 }
 
