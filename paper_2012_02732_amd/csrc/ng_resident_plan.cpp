@@ -229,18 +229,24 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             int p = 1, subs = kSubs;
             std::vector<int> cand;
         };
-        auto place = [&](bool spread) {
+        // where = -1: every participating XCD; otherwise that XCD
+        auto place = [&](int where) {
             Placement pl;
+            const bool spread = where < 0;
             for (int w = 0; w < n_wg; ++w) {
                 const int x = w % 8;
-                if (x < nx && (spread || x == home)) pl.cand.push_back(w);
+                if (x < nx && (spread || x == where)) pl.cand.push_back(w);
             }
-            pl.ready = ready_at(nx == 1 ? 0 : (spread ? -1 : home), -1);
+            pl.ready = ready_at(nx == 1 ? 0 : where, -1);
+            // do this task's loads go through the memory side? (some direct input lives elsewhere)
+            bool far_loads = spread;
+            for (int u : g->nodes[v].preds)
+                if (g->tasks[u].fn && nx > 1 && (out.xcd[u] < 0 || out.xcd[u] != where)) far_loads = true;
             // workgroups in the order they become available for this task
             std::stable_sort(pl.cand.begin(), pl.cand.end(), [&](int a, int b) { return free_at[a] < free_at[b]; });
             for (int subs = kSubs; subs >= (heavy ? 1 : kSubs); --subs) {
                 const long units = units_for(ntiles0, subs);
-                const double cost = tile_round_us(g, v, kid0, subs) * (spread ? kFarRunFactor : 1.0);
+                const double cost = tile_round_us(g, v, kid0, subs) * (far_loads ? kFarRunFactor : 1.0);
                 for (int rounds = 1; rounds <= 4; ++rounds) {
                     const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)pl.cand.size());
                     const long r = (units + p - 1) / p;
@@ -250,14 +256,15 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             }
             return pl;
         };
-        Placement chosen = place(false);
+        const int where = nx == 1 ? 0 : home;
+        Placement chosen = place(where);
         bool wide = false;
         if (nx > 1 && units_for(ntiles0, kSubs) > per_xcd) {
-            Placement spread = place(true);
+            Placement spread = place(-1);
             // what reads the result pays for the longer way too, unless nothing can run beside this task anyway
             if (spread.finish + (sc.solo[v] ? 0.0 : kSpreadPenaltyUs) < chosen.finish) chosen = std::move(spread), wide = true;
         }
-        out.xcd[v] = nx == 1 ? 0 : (wide ? -1 : home);
+        out.xcd[v] = nx == 1 ? 0 : (wide ? -1 : where);
         const std::vector<int>& cand = chosen.cand;
         const double ready = chosen.ready;
         int best_p = chosen.p, best_subs = chosen.subs;
