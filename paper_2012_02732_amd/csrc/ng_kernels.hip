@@ -76,6 +76,13 @@ __device__ __forceinline__ void stg4(float* base, float* p, float4 v, bool far) 
 __device__ __forceinline__ float ldg_any(const float* p, bool far) {
     return far ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
 }
+// 128-bit device-scope load from a per-lane address (16-byte aligned). The compiler does not
+// know about loads issued from inline assembly, so the wait for the data is part of it.
+__device__ __forceinline__ float4 ldg4_any_far(const float* p) {
+    f32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off sc1\n\ts_waitcnt vmcnt(0)" : "=v"(v) : "v"(p) : "memory");
+    return make_float4(v[0], v[1], v[2], v[3]);
+}
 
 // LDS floats every workgroup owns: the largest user is the conv3x3 input patch (4 x 33 x 34).
 constexpr int kSmemFloats = 4 * 33 * 34;
@@ -203,7 +210,7 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
     const float* src = base + ((size_t)(n * cin + lo + c - first)) * a.HW + pix;
     if (VEC4) {
         float4 v;
-        if (FIN) v = make_float4(ldg_any(src, true), ldg_any(src + 1, true), ldg_any(src + 2, true), ldg_any(src + 3, true));
+        if (FIN) v = ldg4_any_far(src);
         else v = *reinterpret_cast<const float4*>(src);
         stg4(a.y, a.y + e, v, FOUT);
     } else {

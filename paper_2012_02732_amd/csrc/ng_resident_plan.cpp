@@ -251,7 +251,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
                     const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)pl.cand.size());
                     const long r = (units + p - 1) / p;
                     const double f = std::max(pl.ready, free_at[pl.cand[p - 1]]) + r * cost + kSyncNearUs;
-                    if (f < pl.finish - 1e-9) pl.finish = f, pl.p = p, pl.subs = subs;
+                    // same finish: fewer participants (fewer completions to collect, less skew)
+                    if (f < pl.finish - 1e-9 || (f < pl.finish + 1e-9 && p < pl.p)) pl.finish = f, pl.p = p, pl.subs = subs;
                 }
             }
             return pl;
