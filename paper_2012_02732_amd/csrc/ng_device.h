@@ -161,7 +161,12 @@ struct DevTask {
     // read with device-scope (memory-side) loads, and every producer of an operand stores
     // with device-scope stores (so no operand has dirty lines in an XCD-private L2)
     unsigned far_in;
-    unsigned pad_[3];
+    // which completion counters the task bumps: bit 0 the one in its XCD's L2 (waiters on the
+    // same XCD), bit 1 the device-scope one (waiters elsewhere, or the task runs on several XCDs),
+    // bit 2 with bit 1: in two levels (per XCD, then device scope)
+    unsigned publish;
+    unsigned parent_far;             // bit j: parent j is awaited through its device-scope counter
+    unsigned pad_[1];
     alignas(16) unsigned char args[kArgBytes];
 };
 
@@ -170,6 +175,7 @@ struct DevEntry {                    // one task in one workgroup's list; tiles 
     int tile_begin;
     int tile_step;
     int subs;                        // sub-blocks of the workgroup that take a tile each per round (1..kSubs)
+    int xcd_peers;                   // two-level completion: workgroups of this task on this workgroup's XCD, else 0
 };
 
 // What the resident kernel reads: one self-contained record per (workgroup, task) entry, the
@@ -180,9 +186,13 @@ constexpr int kRecordsInLds = 128;               // records a workgroup holds in
 struct DevRecord {
     int task, kid, ntiles, n_parents;
     int tile_begin, tile_step;                   // in units of `subs` tiles
-    int flags;                                   // bit 0: device-scope loads of activations, bit 1: device-scope stores of the result
-    int subs;                                    // sub-blocks that take a tile each per round (the others idle), 1..kSubs
-    int parent[NG_MAX_PREDS];
+    int flags;                                   // bit 0: device-scope loads of activations, bit 1: device-scope stores of the result,
+                                                 // bit 2 / 3: bump the XCD-local / the device-scope completion counter,
+                                                 // bit 4: two-level completion - bump a per-XCD counter, the last one of the
+                                                 // XCD bumps the device-scope counter (tasks spread over several XCDs)
+    int subs;                                    // bits 0-7: sub-blocks that take a tile each per round (the others idle), 1..kSubs;
+                                                 // bits 8-31: two-level completion (flags bit 4): workgroups of the task on this XCD
+    int parent[NG_MAX_PREDS];                    // bit 31: wait on the parent's device-scope counter
     unsigned need[NG_MAX_PREDS];
     unsigned args[kArgWords];
 };
@@ -191,7 +201,9 @@ static_assert(sizeof(DevRecord) == kRecordWords * 4 && sizeof(DevRecord) % 16 ==
 struct DevPlan {
     const DevRecord* records;        // concatenated per-workgroup lists, each in ascending task id
     const int* wg_first;             // [n_wg + 1] offsets into records
-    unsigned* done;                  // [n_nodes] completion counters, never reset between replays
+    unsigned* done;                  // [n_nodes] device-scope completion counters, never reset between replays
+    unsigned* done_near;             // [n_nodes] completion counters that live in the L2 of the task's XCD
+    unsigned* done_xcd;              // [n_nodes][8] first level of the two-level completion, one counter per XCD
     int* error_dev;                  // != 0 once any wait ran out of spins
     int* error_host;                 // same value in pinned host memory, for the host to read
     unsigned spin_limit;

@@ -973,7 +973,8 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             const int task = __builtin_amdgcn_readfirstlane(rec[0]), kid = __builtin_amdgcn_readfirstlane(rec[1]);
             const int ntiles = __builtin_amdgcn_readfirstlane(rec[2]), np = __builtin_amdgcn_readfirstlane(rec[3]);
             const int tile0 = __builtin_amdgcn_readfirstlane(rec[4]), step = __builtin_amdgcn_readfirstlane(rec[5]);
-            const int flags = __builtin_amdgcn_readfirstlane(rec[6]), subs = __builtin_amdgcn_readfirstlane(rec[7]);
+            const int flags = __builtin_amdgcn_readfirstlane(rec[6]), subs_word = __builtin_amdgcn_readfirstlane(rec[7]);
+            const int subs = subs_word & 0xff, xcd_peers = subs_word >> 8;
             const bool far_in = (flags & 1) != 0, far_out = (flags & 2) != 0;
             const bool tracer = plan.trace != nullptr && lane == 0;
             if (tracer) atomicMin(plan.trace + 4 * task, wall_clock64());
@@ -982,9 +983,23 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                     bool ok = true;
                     if (lane < np) {
                         const unsigned target = rec[16 + lane] * epoch;
-                        const unsigned* counter = plan.done + (size_t)rec[8 + lane] * plan.done_stride;
+                        const unsigned pw = rec[8 + lane];
+                        const bool far = (pw >> 31) != 0;
+                        unsigned* counter = (far ? plan.done : plan.done_near) + (size_t)(pw & 0x7fffffffu) * plan.done_stride;
                         unsigned spins = 0;
-                        while ((int)(__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+                        for (;;) {
+                            unsigned seen;
+                            if (far) {
+                                seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            } else {
+                                // read the counter where it lives, in this XCD's L2: a compare-and-swap that can
+                                // never match returns the current value (a plain load could be served by a stale
+                                // L1 line, and an atomic add of 0 is folded into such a load by the compiler)
+                                seen = 0xFFFFFFFFu;
+                                __hip_atomic_compare_exchange_strong(counter, &seen, 0xFFFFFFFFu, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                                     __HIP_MEMORY_SCOPE_WORKGROUP);
+                            }
+                            if ((int)(seen - target) >= 0) break;
                             if (++spins > plan.spin_limit ||
                                 ((spins & 63u) == 0 && __hip_atomic_load(plan.error_dev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
                                 ok = false;
@@ -1033,9 +1048,21 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                 atomicMax(plan.trace + 4 * task + 3, now);
             }
             if (lane == 0) {
-                // Publish completion. Readers on this XCD see the data in the shared L2; if there
-                // are readers elsewhere the tile functions have stored through to the memory side.
-                __hip_atomic_fetch_add(plan.done + (size_t)task * plan.done_stride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                // Publish completion. Readers on this XCD see the data in the shared L2 and are told through
+                // a counter in that same L2 (an atomic without device scope is carried out there); if there
+                // are readers elsewhere the tile functions have stored through to the memory side and the
+                // device-scope counter is bumped as well.
+                if (flags & 4)
+                    __hip_atomic_fetch_add(plan.done_near + (size_t)task * plan.done_stride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                bool tell_device = (flags & 8) != 0;
+                if (flags & 16) {
+                    // two levels: count the workgroups of this XCD in its L2; only the last one goes on
+                    const unsigned before = __hip_atomic_fetch_add(plan.done_xcd + ((size_t)task * 8 + (blockIdx.x & 7)) * plan.done_stride, 1u,
+                                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    tell_device = before + 1u == epoch * (unsigned)xcd_peers;
+                }
+                if (tell_device)
+                    __hip_atomic_fetch_add(plan.done + (size_t)task * plan.done_stride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
     }

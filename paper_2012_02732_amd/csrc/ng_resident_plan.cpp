@@ -115,6 +115,7 @@ int variant_for(const ng_graph* g, int v, int part, long* ntiles) {
 struct Sim {
     std::vector<std::vector<DevEntry>> lists;
     std::vector<unsigned> parts;
+    std::vector<unsigned> signals;   // increments of the device-scope counter per replay: participants, or XCDs used (two-level)
     std::vector<int> xcd;
     std::vector<int> kid;            // kernel variant chosen for the resident replay
     std::vector<long> ntiles;        // its tile count
@@ -151,6 +152,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
 
     out.lists.assign(n_wg, {});
     out.parts.assign(n, 0);
+    out.signals.assign(n, 0);
     out.xcd.assign(n, -1);
     out.kid.assign(n, KID_NONE);
     out.ntiles.assign(n, 0);
@@ -311,9 +313,15 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         const int p = (int)wgs[v].size();
         const double run = r * tile_round_us(g, v, out.kid[v], out.subs[v]);
         out.parts[v] = (unsigned)p;
+        // a task spread over several XCDs collects its completions per XCD first
+        int peers[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xcds_used = 0;
+        for (int j = 0; j < p; ++j) ++peers[wgs[v][j] % 8];
+        for (int x = 0; x < 8; ++x) xcds_used += peers[x] > 0;
+        const bool two_level = xcds_used > 1 && !getenv("NG_NO_TWO_LEVEL");
+        out.signals[v] = two_level ? (unsigned)xcds_used : (unsigned)p;
         for (int j = 0; j < p; ++j) {
             const int w = wgs[v][j];
-            out.lists[w].push_back(DevEntry{v, j, p, out.subs[v]});
+            out.lists[w].push_back(DevEntry{v, j, p, out.subs[v], two_level ? peers[w % 8] : 0});
             free_at[w] = (begin >= 0 ? begin : std::max(ready, free_at[w])) + run + kPublishUs;
         }
         finish[v] = best_finish;
@@ -375,7 +383,13 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
         DevTask& d = plan.tasks[e.second];
         if (d.n_parents >= NG_MAX_PREDS) return NG_EINVAL;
         d.parent[d.n_parents] = e.first;
-        d.need[d.n_parents] = best.parts[e.first];
+        d.need[d.n_parents] = best.signals[e.first];
+        // producer and consumer on the same single XCD: the completion is signalled through that XCD's L2
+        const bool near = best.xcd[e.first] >= 0 && best.xcd[e.first] == best.xcd[e.second] && !g->resident_all_far &&
+                          !getenv("NG_NO_NEAR_COUNTERS");
+        if (near) plan.tasks[e.first].publish |= 1u;
+        else plan.tasks[e.first].publish |= 2u, d.parent_far |= 1u << d.n_parents;
+        if (!near && best.signals[e.first] != best.parts[e.first]) plan.tasks[e.first].publish |= 4u;
         ++d.n_parents;
     }
     plan.entries.clear();
@@ -449,13 +463,32 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
                 for (long t = en.tile_begin; t < units_of(en.task); t += en.tile_step) ++hits[en.task][(size_t)t];
             }
         }
+        // increments of the device-scope counter a waiter may expect: one per participant, or with
+        // two-level completion one per XCD on which the task has participants
+        std::vector<unsigned> signals(n, 0);
+        {
+            std::vector<std::vector<int>> on_xcd(n, std::vector<int>(8, 0));
+            for (int w = 0; w < plan.n_wg; ++w)
+                for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) ++on_xcd[plan.entries[e].task][w % 8];
+            for (int w = 0; w < plan.n_wg; ++w)
+                for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
+                    const DevEntry& en = plan.entries[e];
+                    const bool two_level = (plan.tasks[en.task].publish & 4u) != 0;
+                    ok = ok && (en.xcd_peers == 0 || en.xcd_peers == on_xcd[en.task][w % 8]) && (!two_level || en.xcd_peers > 0);
+                }
+            for (size_t v = 0; v < n; ++v) {
+                int used = 0;
+                for (int x = 0; x < 8; ++x) used += on_xcd[v][x] > 0;
+                signals[v] = (plan.tasks[v].publish & 4u) ? (unsigned)used : parts[v];
+            }
+        }
         int n_local = 0;
         for (size_t v = 0; v < n; ++v) {
             if (!g->tasks[v].fn) continue;
             ok = ok && plan.tasks[v].ntiles > 0 && hits[v].size() == (size_t)units_of((int)v);
             for (int h : hits[v]) ok = ok && h == 1;
             const DevTask& d = plan.tasks[v];
-            for (int j = 0; j < d.n_parents; ++j) ok = ok && pos[d.parent[j]] < pos[v] && d.need[j] == parts[d.parent[j]] && parts[d.parent[j]] > 0;
+            for (int j = 0; j < d.n_parents; ++j) ok = ok && pos[d.parent[j]] < pos[v] && d.need[j] == signals[d.parent[j]] && parts[d.parent[j]] > 0;
         }
         for (auto& e : g->sched.meg) {
             const int u = e.first, v = e.second;

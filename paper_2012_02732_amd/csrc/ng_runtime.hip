@@ -182,9 +182,9 @@ int build_resident(ng_graph* g) {
         DevRecord& r = records[e];
         r.task = entries[e].task, r.kid = t.kid, r.ntiles = t.ntiles, r.n_parents = t.n_parents;
         r.tile_begin = entries[e].tile_begin, r.tile_step = entries[e].tile_step;
-        r.flags = (t.far_in != 0 ? 1 : 0) | (t.release_far != 0 ? 2 : 0);
-        r.subs = entries[e].subs;
-        std::memcpy(r.parent, t.parent, sizeof r.parent);
+        r.flags = (t.far_in != 0 ? 1 : 0) | (t.release_far != 0 ? 2 : 0) | ((t.publish & 1u) ? 4 : 0) | ((t.publish & 2u) ? 8 : 0) | ((t.publish & 4u) ? 16 : 0);
+        r.subs = entries[e].subs | (entries[e].xcd_peers << 8);
+        for (int j = 0; j < NG_MAX_PREDS; ++j) r.parent[j] = t.parent[j] | (((t.parent_far >> j) & 1u) ? (int)0x80000000u : 0);
         std::memcpy(r.need, t.need, sizeof r.need);
         std::memcpy(r.args, t.args, sizeof r.args);
     }
@@ -198,17 +198,19 @@ int build_resident(ng_graph* g) {
     rt.done_words = (size_t)n * rt.plan.done_stride;
     NG_HIP(hipMalloc(&rt.d_records, records.size() * sizeof(DevRecord)));
     NG_HIP(hipMalloc(&rt.d_wg_first, wg_first.size() * sizeof(int)));
-    NG_HIP(hipMalloc(&d_done, rt.done_words * sizeof(unsigned)));
+    NG_HIP(hipMalloc(&d_done, 10 * rt.done_words * sizeof(unsigned)));         // device-scope counters, the XCD-local ones, 8 per-XCD first-level ones
     NG_HIP(hipMalloc(&d_error, sizeof(int)));
     NG_HIP(hipHostMalloc(reinterpret_cast<void**>(&rt.h_error), sizeof(int), hipHostMallocDefault));
     *rt.h_error = 0;
     NG_HIP(hipMemcpy(rt.d_records, records.data(), records.size() * sizeof(DevRecord), hipMemcpyHostToDevice));
     NG_HIP(hipMemcpy(rt.d_wg_first, wg_first.data(), wg_first.size() * sizeof(int), hipMemcpyHostToDevice));
-    NG_HIP(hipMemset(d_done, 0, rt.done_words * sizeof(unsigned)));
+    NG_HIP(hipMemset(d_done, 0, 10 * rt.done_words * sizeof(unsigned)));
     NG_HIP(hipMemset(d_error, 0, sizeof(int)));
     rt.plan.records = static_cast<const DevRecord*>(rt.d_records);
     rt.plan.wg_first = static_cast<const int*>(rt.d_wg_first);
     rt.plan.done = d_done;
+    rt.plan.done_near = d_done + rt.done_words;
+    rt.plan.done_xcd = d_done + 2 * rt.done_words;
     rt.plan.error_dev = d_error;
     rt.plan.error_host = rt.h_error;
     rt.plan.spin_limit = g->resident_spin_limit;
@@ -225,7 +227,7 @@ int launch_resident(ng_graph* g) {
     hipStream_t origin = rt.streams[0];
     if (rt.counters_dirty) {                                   // a timed-out replay left partial counts behind
         NG_HIP(hipStreamSynchronize(origin));
-        NG_HIP(hipMemset(rt.plan.done, 0, rt.done_words * sizeof(unsigned)));
+        NG_HIP(hipMemset(rt.plan.done, 0, 10 * rt.done_words * sizeof(unsigned)));
         NG_HIP(hipMemset(rt.plan.error_dev, 0, sizeof(int)));
         *rt.h_error = 0;
         rt.epoch = 0;
