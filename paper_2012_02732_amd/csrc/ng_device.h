@@ -35,7 +35,7 @@ constexpr int partition_of(int kid) {
                      : (kid == KID_PW_V1 || kid == KID_PW_V2 || kid == KID_PW_V3 || kid == KID_PW_V4 || kid == KID_BN_R64 || kid == KID_ADD_R64)
                            ? PART_R64
                            : (kid == KID_PW_S1 || kid == KID_PW_S2 || kid == KID_PW_S3 || kid == KID_PW_S4 || kid == KID_BN_R16 ||
-                              kid == KID_ADD_R16)
+                              kid == KID_ADD_R16 || kid == KID_C3_M1 || kid == KID_C3_M2 || kid == KID_C3_M3 || kid == KID_C3_M4)
                                  ? PART_R16
                                  : PART_NONE;
 }

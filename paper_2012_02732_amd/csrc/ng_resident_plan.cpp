@@ -39,8 +39,8 @@ namespace ng {
 
 namespace {
 
-constexpr double kSyncNearUs = 1.1;   // completion counter -> dependent workgroup running, same XCD (measured)
-constexpr double kSyncFarUs = 1.5;    // extra cost when producer and consumer sit on different XCDs (measured)
+constexpr double kSyncNearUs = 0.7;   // completion counter -> dependent workgroup running, same XCD (measured)
+constexpr double kSyncFarUs = 2.0;    // extra cost when producer and consumer sit on different XCDs (measured)
 constexpr double kPublishUs = 0.3;    // stores drained and counter bumped: the workgroup moves on to its next entry
 constexpr double kLocalUs = 0.1;      // hand-over inside one workgroup: one barrier
 constexpr double kSpreadPenaltyUs = 5.0; // what spreading a task over all XCDs must gain before it is preferred (its readers go the long way too)
