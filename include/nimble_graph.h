@@ -197,7 +197,7 @@ int ng_replay(ng_graph* g);
 int ng_sync(ng_graph* g);
 
 /* Device-resident replay settings. workgroups_per_cu: resident workgroups per compute unit
- * (0 = automatic; only before ng_capture). xcds: number of XCDs (1, 2, 4 or 8; 0 = automatic;
+ * (0 = automatic; only before ng_capture). xcds: number of XCDs (1..8; 0 = automatic;
  * only before ng_capture) the streams are spread over; with 1 the whole DAG runs out of one
  * XCD's L2 and no completion needs a device-scope fence. spin_limit: polls after which a waiting workgroup
  * gives up (0 = default, a few seconds); every wait in the resident kernel is bounded by it.

@@ -341,7 +341,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     const int n = (int)g->nodes.size();
     Sim best;
     int best_nx = 0;
-    for (int nx : {1, 2, 4, 8}) {
+    for (int nx : {1, 2, 3, 4, 5, 6, 7, 8}) {
         if (xcds > 0 && nx != xcds) continue;
         Sim s;
         simulate(g, n_wg, nx, s);
@@ -409,8 +409,8 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
     using namespace ng;
     if (!g) return NG_EINVAL;
     if (g->phase < PLANNED) return g->fail(NG_ESTATE, "ng_resident_dry_plan: call ng_plan_memory first");
-    if (n_workgroups < 8 || n_workgroups % 8 != 0 || (xcds != 0 && xcds != 1 && xcds != 2 && xcds != 4 && xcds != 8))
-        return g->fail(NG_EINVAL, "ng_resident_dry_plan: workgroups must be a positive multiple of 8, xcds one of 0, 1, 2, 4, 8");
+    if (n_workgroups < 8 || n_workgroups % 8 != 0 || xcds < 0 || xcds > 8)
+        return g->fail(NG_EINVAL, "ng_resident_dry_plan: workgroups must be a positive multiple of 8, xcds 0..8");
     std::vector<Task> saved;
     saved.swap(g->tasks);
     g->dry_run = true;

@@ -413,7 +413,7 @@ int ng_sync(ng_graph* g) {
 int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned spin_limit, int device_scope_everywhere) {
     if (!g) return NG_EINVAL;
     if (workgroups_per_cu < 0 || workgroups_per_cu > 8) return g->fail(NG_EINVAL, "ng_resident_config: workgroups_per_cu must be 0..8");
-    if (xcds != 0 && xcds != 1 && xcds != 2 && xcds != 4 && xcds != 8) return g->fail(NG_EINVAL, "ng_resident_config: xcds must be 0, 1, 2, 4 or 8");
+    if (xcds < 0 || xcds > 8) return g->fail(NG_EINVAL, "ng_resident_config: xcds must be 0..8");
     if (workgroups_per_cu > 0 || xcds > 0 || (device_scope_everywhere != 0) != g->resident_all_far) {
         if (g->phase >= CAPTURED) return g->fail(NG_ESTATE, "ng_resident_config: the gang layout is fixed at ng_capture");
         if (workgroups_per_cu > 0) g->resident_wg_per_cu = workgroups_per_cu;

@@ -224,7 +224,7 @@ def test_bind_rejects_duplicate_stream_handles():
 
 
 @pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
-@pytest.mark.parametrize("n_wg,xcds", [(256, 0), (256, 1), (64, 4), (8, 8), (512, 2)])
+@pytest.mark.parametrize("n_wg,xcds", [(256, 0), (256, 1), (64, 4), (8, 8), (512, 2), (256, 5)])
 def test_device_resident_plan_covers_every_tile_once(name, n_wg, xcds):
     """The per-workgroup task lists of the device-resident replay, rehearsed on the host:
     every tile of every task is assigned exactly once, lists ascend in task id (so waits
@@ -249,7 +249,7 @@ def test_device_resident_plan_argument_checks():
     assert e.value.code == B.NG_ESTATE
     r.schedule()
     r.plan()
-    for bad in [(0, 0), (12, 0), (256, 3), (-8, 8)]:
+    for bad in [(0, 0), (12, 0), (256, 9), (256, -1), (-8, 8)]:
         with pytest.raises(B.NgError) as e:
             B.ng_resident_dry_plan(r.g, *bad)
         assert e.value.code == B.NG_EINVAL
