@@ -201,6 +201,32 @@ def main():
             print(f"{name:24s} launches {k['launches']:4d}  isolated total {k['us']:9.1f} us  avg {k['us'] / k['launches']:7.2f} us"
                   f"  {k['bytes'] / k['us'] * 1e-3:8.1f} GB/s  {k['flops'] / k['us'] * 1e-6:8.3f} TFLOP/s", file=sys.stderr)
 
+    # ---- where the time of one device-resident replay goes (its own trace) -----------------------
+    timeline = None
+    if args.mode == "device_resident":
+        B.ng_resident_trace(runner.g, 1)
+        B.ng_replay(runner.g)
+        B.ng_sync(runner.g)
+        tr = B.ng_resident_trace(runner.g, 0, fetch=True)
+        ran = [v for v in range(n_nodes) if tr[v] is not None]
+        if ran:
+            v = max(ran, key=lambda u: tr[u][3])
+            span = tr[v][3]
+            run_us = wait_us = 0.0
+            hops = 0
+            while v is not None:                 # walk back along the producer that finished last
+                ps = [u for u in w.nodes[v].preds if tr[u] is not None]
+                u = max(ps, key=lambda q: tr[q][3]) if ps else None
+                run_us += tr[v][3] - tr[v][1]
+                wait_us += tr[v][1] - (tr[u][3] if u is not None else 0.0)
+                hops += 1
+                v = u
+            timeline = {"traced_replay_us": span, "tasks_on_realised_chain": hops, "tile_execution_us": run_us,
+                        "hand_over_us": wait_us,
+                        "note": "one replay with per-task clock readings (tracing itself costs a few percent): last "
+                                "workgroup ready -> last workgroup stored, and the gaps between a producer's last store "
+                                "and the consumer's start"}
+
     n_wg, n_entries, xcds, est_us = B.ng_resident_sizes(runner.g)
     out = {
         "metric": "DAG latency at batch 1 (replay + wait, input resident in HBM)",
@@ -222,6 +248,7 @@ def main():
                           "t_cp_if_only_time_above_an_empty_kernel_counts_us": t_cp_lo,
                           "empty_kernel_chain_us_per_node": c_empty,
                           "planner_expected_us": est_us},
+        "resident_timeline": timeline,
         "modes_median_us": modes,
         "auto_mode": {"chosen": MODE_NAMES[auto_mode], "trial_us": {MODE_NAMES[k]: v for k, v in auto_trial.items()}},
         "roofline": roofline,
