@@ -110,6 +110,16 @@ __global__ __launch_bounds__(kBlock) void fold_bn_kernel(const float* gamma, con
     shift[c] = beta[c] - mean[c] * s;
 }
 
+// Every tile function takes a `wait` object and calls it exactly once, on every path and by
+// every thread of the workgroup (it may contain a workgroup barrier), before the first access
+// to data another task produced. Whatever does not depend on such data - index arithmetic,
+// reading weights and coefficients - goes before the call, so that it overlaps with waiting
+// for the producers. Stand-alone kernels pass NoWait; the resident kernel passes the wait
+// for the task's completion counters, which does its work on the first call only.
+struct NoWait {
+    __device__ __forceinline__ void operator()() const {}
+};
+
 // Elementwise operators come in four partitions of the output into tiles, so that an
 // elementwise task can take over the partition of the task that feeds it (then tile i of
 // the consumer reads only what tile i of the producer wrote, and a workgroup that ran the
@@ -144,13 +154,14 @@ __device__ __forceinline__ ElemIndex elem_index(int tile, int tid, int C, int HW
     return r;
 }
 
-template <int PART, bool FIN, bool FOUT>
-__device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, int tid, bool live) {
-    if (!live) return;
+template <int PART, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
     const ElemIndex ix = elem_index<PART>(tile, tid, a.C, a.HW, a.total, a.cols);
-    if (!ix.ok) return;
-    float s, t;
-    bn_coeff(a, ix.c, s, t);
+    const bool active = live && ix.ok;
+    float s = 1.f, t = 0.f;
+    if (active) bn_coeff(a, ix.c, s, t);
+    wait();
+    if (!active) return;
     if (PART == PART_L1024 || PART == PART_R64) {          // HW % 4 == 0: a float4 never straddles channels
         float4 v = ldg4(a.x, a.x + ix.e, FIN);
         v.x = fmaf(v.x, s, t), v.y = fmaf(v.y, s, t), v.z = fmaf(v.z, s, t), v.w = fmaf(v.w, s, t);
@@ -165,11 +176,11 @@ __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, i
 // ------------------------------------------------------------------------------------
 // add_n: elementwise sum of k tensors, accumulated in argument order
 // ------------------------------------------------------------------------------------
-template <int PART, bool FIN, bool FOUT>
-__device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, int tid, bool live) {
-    if (!live) return;
+template <int PART, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
     const ElemIndex ix = elem_index<PART>(tile, tid, a.C, a.HW, a.total, a.cols);
-    if (!ix.ok) return;
+    wait();
+    if (!live || !ix.ok) return;
     const int e = ix.e;
     if (PART == PART_L1024 || PART == PART_R64) {
         float4 acc = ldg4(a.x[0], a.x[0] + e, FIN);
@@ -194,12 +205,11 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, i
 // ------------------------------------------------------------------------------------
 // concat: output channel block j = channels [lo_j, lo_j + cnt_j) of input j
 // ------------------------------------------------------------------------------------
-template <bool VEC4, bool FIN, bool FOUT>
-__device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float*, int tid, bool live) {
-    if (!live) return;
+template <bool VEC4, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
     const int i = tile * kBlock + tid;
     const int e = VEC4 ? i * 4 : i;
-    if (e >= a.total) return;
+    const bool active = live && e < a.total;
     const int plane = e / a.HW, pix = e - plane * a.HW;
     const int n = plane / a.C, c = plane - n * a.C;
     const float* base = a.x[0];
@@ -208,6 +218,8 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
     for (int q = 1; q < NG_MAX_PREDS; ++q)
         if (q < a.k && c >= a.first[q]) base = a.x[q], cin = a.cin[q], lo = a.lo[q], first = a.first[q];
     const float* src = base + ((size_t)(n * cin + lo + c - first)) * a.HW + pix;
+    wait();
+    if (!active) return;
     if (VEC4) {
         float4 v;
         if (FIN) v = ldg4_any_far(src);
@@ -226,26 +238,32 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
 // rounds on the workgroups of its stream - one round costs one trip to memory however many
 // loads are in flight, and 1024 consecutive outputs are also the tile of the float4
 // elementwise kernels, which can then take over the partition).
-template <int P, bool FIN, bool FOUT>
-__device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*, int tid, bool live) {
+template <int P, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
     const int base = tile * kBlock * P + tid;
-    if (!live || base >= a.total) return;
+    const bool active = live && base < a.total;
     // all taps of all P outputs are loaded unconditionally from clamped coordinates, so the
     // loads are independent and in flight together; taps outside the image are masked afterwards
     float v[P][9];
     int r0[P], c0[P];
+    const float* src[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const int i = min(base + p * kBlock, a.total - 1);
         const int ow = i % a.Wo, t = i / a.Wo;
         const int oh = t % a.Ho, plane = t / a.Ho;
-        const float* src = a.x + (size_t)plane * a.H * a.W;
+        src[p] = a.x + (size_t)plane * a.H * a.W;
         r0[p] = oh * a.stride - a.pad, c0[p] = ow * a.stride - a.pad;
+    }
+    wait();
+    if (!active) return;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
 #pragma unroll
         for (int dr = 0; dr < 3; ++dr)
 #pragma unroll
             for (int dc = 0; dc < 3; ++dc)
-                v[p][dr * 3 + dc] = ldg(a.x, src + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
+                v[p][dr * 3 + dc] = ldg(a.x, src[p] + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
     }
     __builtin_amdgcn_sched_barrier(0);                       // all loads are issued before the first use
 #pragma unroll
@@ -269,28 +287,34 @@ __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*
 // ------------------------------------------------------------------------------------
 // dwconv: depthwise K x K, pad K/2, stride S; P outputs per thread
 // ------------------------------------------------------------------------------------
-template <int K, int S, int P, bool FIN, bool FOUT>
-__device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*, int tid, bool live) {
+template <int K, int S, int P, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
     const int base = tile * kBlock * P + tid;
-    if (!live || base >= a.total) return;
+    const bool active = live && base < a.total;
     // unconditional loads from clamped coordinates (all in flight together), masked afterwards
     float v[P][K * K], w[P][K * K];
     int r0[P], c0[P];
+    const float* src[P];
 #pragma unroll
     for (int p = 0; p < P; ++p) {
         const int i = min(base + p * kBlock, a.total - 1);
         const int ow = i % a.Wo, t = i / a.Wo;
         const int oh = t % a.Ho, plane = t / a.Ho;
-        const float* src = a.x + (size_t)plane * a.H * a.W;
+        src[p] = a.x + (size_t)plane * a.H * a.W;
         const float* wt = a.w + (plane % a.C) * K * K;
         r0[p] = oh * S - K / 2, c0[p] = ow * S - K / 2;
 #pragma unroll
-        for (int q = 0; q < K * K; ++q) w[p][q] = wt[q];
+        for (int q = 0; q < K * K; ++q) w[p][q] = wt[q];       // filter taps: not produced by any task
+    }
+    wait();
+    if (!active) return;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
 #pragma unroll
         for (int dr = 0; dr < K; ++dr)
 #pragma unroll
             for (int dc = 0; dc < K; ++dc)
-                v[p][dr * K + dc] = ldg(a.x, src + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
+                v[p][dr * K + dc] = ldg(a.x, src[p] + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
     }
     __builtin_amdgcn_sched_barrier(0);                       // all loads are issued before the first use
 #pragma unroll
@@ -317,8 +341,9 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-template <bool FIN, bool FOUT>
-__device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, float*, int tid, bool live) {
+template <bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    wait();
     const int lane = tid & 63;
     const int plane = tile * (kBlock / 64) + (tid >> 6);
     if (!live || plane >= a.planes) return;
@@ -332,8 +357,9 @@ __device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, 
 // ------------------------------------------------------------------------------------
 // fc (small batch): one wavefront per output feature; y[n][o] = <W[o], x[n]> + b[o]
 // ------------------------------------------------------------------------------------
-template <bool FIN, bool FOUT>
-__device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*, int tid, bool live) {
+template <bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    wait();
     const int lane = tid & 63;
     const int o = tile * (kBlock / 64) + (tid >> 6);
     if (!live || o >= a.Cout) return;
@@ -363,8 +389,9 @@ __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*, 
 // A workgroup of four wavefronts (2 x 2) owns a TM x TN output tile; K is walked in
 // slices of KC staged through LDS (A transposed to [k][m] so both fragments read rows).
 // ------------------------------------------------------------------------------------
-template <int TM, int TN, int KC, bool FIN, bool FOUT>
-__device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, float* smem, int tid, bool live) {
+template <int TM, int TN, int KC, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    wait();
     constexpr int WM = TM / 2, WN = TN / 2;           // per-wavefront sub-tile
     constexpr int FM = WM / 16, FN = WN / 16;         // 16 x 16 fragments per wavefront
     constexpr int LDA = TM + 1, LDB = TN + 1;
@@ -479,8 +506,9 @@ __global__ __launch_bounds__(kBlock) void pack_pw_weights_kernel(const float* w,
     wp[i] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
 }
 
-template <int CH, bool FIN, bool FOUT>                      // CH k steps per chunk: 4 * CH loads in flight per lane
-__device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, float* smem, int tid, bool live) {
+template <int CH, bool FIN, bool FOUT, class Wait>          // CH k steps per chunk: 4 * CH loads in flight per lane
+__device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    wait();
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
@@ -589,8 +617,8 @@ __global__ __launch_bounds__(kBlock) void pack_pw_weights_k4_kernel(const float*
     wp[i] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
 }
 
-template <int G, bool VEC, bool FIN, bool FOUT>
-__device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float* smem, int tid, bool live) {
+template <int G, bool VEC, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
     constexpr int NJ = VEC ? 4 : 1;                          // MFMA tiles per wavefront
     constexpr int TN = VEC ? 64 : 16;                        // columns per workgroup tile
     static_assert(4 * NJ * 4 * 64 <= kSmemFloats, "LDS budget");
@@ -598,16 +626,18 @@ __device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
     const int colv = bx * TN + (VEC ? 4 : 1) * (lane & 15);  // first column this lane owns
+    // addresses first (nothing is read yet), then the wait for the producers
+    const int groups = a.ksteps;                             // groups of 4 k-steps in the packed copy, a multiple of 4 G
+    const int gw = groups >> 2;                              // groups per wavefront
+    const f32x4* ap = reinterpret_cast<const f32x4*>(a.wp) + ((size_t)by * groups + (size_t)wave * gw) * 64 + lane;
+    const int col = min(colv, a.cols - (VEC ? 4 : 1));       // columns past the end repeat the last ones; never stored
+    const int img = col / a.HW, pix = col - img * a.HW;
+    const float* xb = a.x + (size_t)img * a.Cin * a.HW + pix;
+    const unsigned k_last = (unsigned)(a.Cin - 1) * (unsigned)a.HW;       // rows past Cin (zero weights) repeat the last row
+    const unsigned k_step = 4u * (unsigned)a.HW;
+    unsigned koff = (unsigned)(16 * wave * gw + (lane >> 4)) * (unsigned)a.HW;
+    wait();
     if (live) {
-        const int groups = a.ksteps;                         // groups of 4 k-steps in the packed copy, a multiple of 4 G
-        const int gw = groups >> 2;                          // groups per wavefront
-        const f32x4* ap = reinterpret_cast<const f32x4*>(a.wp) + ((size_t)by * groups + (size_t)wave * gw) * 64 + lane;
-        const int col = min(colv, a.cols - (VEC ? 4 : 1));   // columns past the end repeat the last ones; never stored
-        const int img = col / a.HW, pix = col - img * a.HW;
-        const float* xb = a.x + (size_t)img * a.Cin * a.HW + pix;
-        const unsigned k_last = (unsigned)(a.Cin - 1) * (unsigned)a.HW;   // rows past Cin (zero weights) repeat the last row
-        const unsigned k_step = 4u * (unsigned)a.HW;
-        unsigned koff = (unsigned)(16 * wave * gw + (lane >> 4)) * (unsigned)a.HW;
         f32x4 acc[NJ];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) acc[j] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -675,8 +705,9 @@ __device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float
 // TP = 8 : each wavefront owns the same 8 x 8 pixel tile and its own group of 8 channels.
 // Tile index = (image * co_groups + channel group) * tiles_xy + pixel tile.
 // ------------------------------------------------------------------------------------
-template <int TP, int S, bool FIN, bool FOUT>
-__device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* smem, int tid, bool live) {
+template <int TP, int S, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    wait();
     constexpr int CIC = S == 2 && TP == 16 ? 2 : 4;    // input channels per LDS slice
     constexpr int IW = (TP - 1) * S + 3;               // input patch edge
     constexpr int LDP = IW + 1;
@@ -762,25 +793,27 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
 // over the four wavefronts in groups of 4 k-steps, G groups in flight, fixed-order reduction.
 // A lane walks k in steps of 4, so (ci, tap) is updated incrementally: tap += 4, carry into ci.
 // ------------------------------------------------------------------------------------
-template <int G, bool FIN, bool FOUT>
-__device__ __forceinline__ void conv3x3_k4_tile(const C3Args& a, int tile, float* smem, int tid, bool live) {
+template <int G, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void conv3x3_k4_tile(const C3Args& a, int tile, float* smem, int tid, bool live, Wait& wait) {
     static_assert(4 * 4 * 64 <= kSmemFloats, "LDS budget");
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
     const int colv = bx * 16 + (lane & 15);
     const int HWo = a.Ho * a.Wo;
+    // addresses first (nothing is read yet), then the wait for the producers
+    const int groups = a.groups, gw = groups >> 2;
+    const f32x4* ap = reinterpret_cast<const f32x4*>(a.wp) + ((size_t)by * groups + (size_t)wave * gw) * 64 + lane;
+    const int col = min(colv, a.cols - 1);                   // columns past the end repeat the last one; never stored
+    const int img = col / HWo, pix = col - img * HWo;
+    const int oy = pix / a.Wo, ox = pix - oy * a.Wo;
+    const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
+    const int HW = a.H * a.W;
+    const float* xb = a.x + (size_t)img * a.Cin * HW;
+    const int k0 = 16 * wave * gw + (lane >> 4);             // this lane's first k; then + 4 per k-step
+    int ci = k0 / 9, tap = k0 - 9 * ci;
+    wait();
     if (live) {
-        const int groups = a.groups, gw = groups >> 2;
-        const f32x4* ap = reinterpret_cast<const f32x4*>(a.wp) + ((size_t)by * groups + (size_t)wave * gw) * 64 + lane;
-        const int col = min(colv, a.cols - 1);               // columns past the end repeat the last one; never stored
-        const int img = col / HWo, pix = col - img * HWo;
-        const int oy = pix / a.Wo, ox = pix - oy * a.Wo;
-        const int iy0 = oy * a.stride - a.pad, ix0 = ox * a.stride - a.pad;
-        const int HW = a.H * a.W;
-        const float* xb = a.x + (size_t)img * a.Cin * HW;
-        const int k0 = 16 * wave * gw + (lane >> 4);         // this lane's first k; then + 4 per k-step
-        int ci = k0 / 9, tap = k0 - 9 * ci;
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
         for (int g0 = 0; g0 < gw; g0 += G) {
             f32x4 av[G];
@@ -836,9 +869,9 @@ template <int KID> struct KernelOf;
     template <> struct KernelOf<KID> {                                                         \
         using Args = ARGS;                                                                     \
         static constexpr const char* name = NAME;                                              \
-        template <bool FIN, bool FOUT>                                                         \
-        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live) { \
-            __VA_ARGS__, FIN, FOUT > (a, t, smem, tid, live);                                  \
+        template <bool FIN, bool FOUT, class Wait>                                             \
+        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live, Wait& wait) { \
+            __VA_ARGS__, FIN, FOUT > (a, t, smem, tid, live, wait);                            \
         }                                                                                      \
     };
 NG_KERNEL(KID_BN, BnArgs, "bn_act", bn_act_tile < PART_L256)
@@ -884,9 +917,9 @@ NG_KERNEL(KID_C3_M4, C3Args, "conv3x3_mfma_4", conv3x3_k4_tile < 4)
     template <> struct KernelOf<KID> {                                                         \
         using Args = ARGS;                                                                     \
         static constexpr const char* name = NAME;                                              \
-        template <bool FIN, bool FOUT>                                                         \
-        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live) { \
-            FN<FIN, FOUT>(a, t, smem, tid, live);                                              \
+        template <bool FIN, bool FOUT, class Wait>                                             \
+        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live, Wait& wait) { \
+            FN<FIN, FOUT>(a, t, smem, tid, live, wait);                                        \
         }                                                                                      \
     };
 NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
@@ -897,7 +930,8 @@ NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
 template <int KID>
 __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KID>::Args a) {
     __shared__ float smem[kSmemFloats];
-    KernelOf<KID>::template tile<false, false>(a, blockIdx.x, smem, threadIdx.x, true);
+    NoWait wait;
+    KernelOf<KID>::template tile<false, false>(a, blockIdx.x, smem, threadIdx.x, true, wait);
 }
 
 // ------------------------------------------------------------------------------------
@@ -922,9 +956,9 @@ __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KI
 // part in the barriers.
 // `words` points at the record's argument block in LDS; it is the same for every lane, so
 // each word is moved into a scalar register.
-template <int KID>
+template <int KID, class Wait>
 __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int step, int ntiles, int subs, float* smem, int sub,
-                                          int tid, bool fin, bool fout) {
+                                          int tid, bool fin, bool fout, Wait& wait) {
     using A = typename KernelOf<KID>::Args;
     static_assert(sizeof(A) <= kArgWords * 4 && sizeof(A) % 4 == 0, "argument block does not fit the record");
     unsigned w[sizeof(A) / 4];
@@ -937,7 +971,7 @@ __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int s
     for (; unit < nunits; unit += step) {                                            \
         const int tile = unit * subs + sub;                                          \
         const bool live = sub < subs && tile < ntiles;                               \
-        KernelOf<KID>::template tile<FI, FO>(a, live ? tile : 0, smem, tid, live);   \
+        KernelOf<KID>::template tile<FI, FO>(a, live ? tile : 0, smem, tid, live, wait); \
     }
     if (!fin && !fout) { NG_LOOP(false, false) }
     else if (!fin) { NG_LOOP(false, true) }
@@ -945,6 +979,73 @@ __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int s
     else { NG_LOOP(true, true) }
 #undef NG_LOOP
 }
+
+// The wait of one list entry for the completion counters of its parents; see NoWait for the
+// contract. The first call does the work: lane j of the first wavefront polls parent j, then
+// the compute unit's L1 is dropped and the workgroup meets at a barrier. Later calls (further
+// tiles of the same entry) return at once.
+struct CounterWait {
+    const DevPlan& plan;
+    const unsigned* rec;             // the entry's record in LDS
+    int* s_abort;
+    unsigned epoch;
+    int task, np, lane;
+    bool tracer, pending;
+
+    __device__ __forceinline__ void operator()() {
+        if (!pending) return;
+        pending = false;
+        if (np > 0) {
+            if (lane < 64) {                                    // first wavefront: lane j watches parent j
+                bool ok = true;
+                if (lane < np) {
+                    const unsigned target = rec[16 + lane] * epoch;
+                    const unsigned pw = rec[8 + lane];
+                    const bool far = (pw >> 31) != 0;
+                    unsigned* counter = (far ? plan.done : plan.done_near) + (size_t)(pw & 0x7fffffffu) * plan.done_stride;
+                    unsigned spins = 0;
+                    for (;;) {
+                        unsigned seen;
+                        if (far) {
+                            seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        } else {
+                            // read the counter where it lives, in this XCD's L2: a compare-and-swap that can
+                            // never match returns the current value (a plain load could be served by a stale
+                            // L1 line, and an atomic add of 0 is folded into such a load by the compiler)
+                            seen = 0xFFFFFFFFu;
+                            __hip_atomic_compare_exchange_strong(counter, &seen, 0xFFFFFFFFu, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+                        }
+                        if ((int)(seen - target) >= 0) break;
+                        if (++spins > plan.spin_limit ||
+                            ((spins & 63u) == 0 && __hip_atomic_load(plan.error_dev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                            ok = false;
+                            break;
+                        }
+                        if (plan.poll_sleep == 0) __builtin_amdgcn_s_sleep(1);
+                        else if (plan.poll_sleep == 1) __builtin_amdgcn_s_sleep(4);
+                        else __builtin_amdgcn_s_sleep(16);
+                    }
+                    if (!ok && spins > plan.spin_limit) {
+                        atomicExch(plan.error_dev, task + 1);
+                        *plan.error_host = task + 1;
+                    }
+                }
+                if (__any(!ok)) {
+                    if (lane == 0) *s_abort = 1;
+                }
+                // Make the producers' stores visible to this compute unit. Producers on this
+                // XCD have their results in the shared L2 already: dropping this CU's vector
+                // L1 is enough (what a workgroup-scope acquire does when the waves of a
+                // workgroup sit on different CUs). Tensors produced on another XCD are never
+                // cached here at all: their loads are device-scope accesses (far_in).
+                asm volatile("buffer_inv sc0" ::: "memory");
+            }
+            __syncthreads();                                    // also waits for the invalidate to finish
+        }
+        if (tracer) atomicMax(plan.trace + 4 * task + 1, wall_clock64());
+    }
+};
 
 // FULL = false leaves out the kernels that only large problems use (see is_lean_kernel): their
 // register needs would otherwise shape the allocation of the whole replay kernel.
@@ -978,58 +1079,12 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             const bool far_in = (flags & 1) != 0, far_out = (flags & 2) != 0;
             const bool tracer = plan.trace != nullptr && lane == 0;
             if (tracer) atomicMin(plan.trace + 4 * task, wall_clock64());
-            if (np > 0) {
-                if (lane < 64) {                                    // first wavefront: lane j watches parent j
-                    bool ok = true;
-                    if (lane < np) {
-                        const unsigned target = rec[16 + lane] * epoch;
-                        const unsigned pw = rec[8 + lane];
-                        const bool far = (pw >> 31) != 0;
-                        unsigned* counter = (far ? plan.done : plan.done_near) + (size_t)(pw & 0x7fffffffu) * plan.done_stride;
-                        unsigned spins = 0;
-                        for (;;) {
-                            unsigned seen;
-                            if (far) {
-                                seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            } else {
-                                // read the counter where it lives, in this XCD's L2: a compare-and-swap that can
-                                // never match returns the current value (a plain load could be served by a stale
-                                // L1 line, and an atomic add of 0 is folded into such a load by the compiler)
-                                seen = 0xFFFFFFFFu;
-                                __hip_atomic_compare_exchange_strong(counter, &seen, 0xFFFFFFFFu, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                                     __HIP_MEMORY_SCOPE_WORKGROUP);
-                            }
-                            if ((int)(seen - target) >= 0) break;
-                            if (++spins > plan.spin_limit ||
-                                ((spins & 63u) == 0 && __hip_atomic_load(plan.error_dev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                                ok = false;
-                                break;
-                            }
-                            if (plan.poll_sleep == 0) __builtin_amdgcn_s_sleep(1);
-                            else if (plan.poll_sleep == 1) __builtin_amdgcn_s_sleep(4);
-                            else __builtin_amdgcn_s_sleep(16);
-                        }
-                        if (!ok && spins > plan.spin_limit) {
-                            atomicExch(plan.error_dev, task + 1);
-                            *plan.error_host = task + 1;
-                        }
-                    }
-                    if (__any(!ok)) {
-                        if (lane == 0) s_abort = 1;
-                    }
-                    // Make the producers' stores visible to this compute unit. Producers on this
-                    // XCD have their results in the shared L2 already: dropping this CU's vector
-                    // L1 is enough (what a workgroup-scope acquire does when the waves of a
-                    // workgroup sit on different CUs). Tensors produced on another XCD are never
-                    // cached here at all: their loads are device-scope accesses (far_in).
-                    asm volatile("buffer_inv sc0" ::: "memory");
-                }
-                __syncthreads();                                    // also waits for the invalidate to finish
-                if (s_abort) return;
-            }
-            if (tracer) atomicMax(plan.trace + 4 * task + 1, wall_clock64());
+            // What the task can do without its inputs (addresses, weights) happens inside the tile
+            // function before it calls `wait`; an entry that fails to wait in time still runs its
+            // tiles (all accesses stay in bounds) and the workgroup leaves right after.
+            CounterWait wait{plan, rec, &s_abort, epoch, task, np, lane, tracer, true};
             switch (kid) {
-#define NG_CASE(KID) case KID: if (FULL || is_lean_kernel(KID)) run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out); break;
+#define NG_CASE(KID) case KID: if (FULL || is_lean_kernel(KID)) run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out, wait); break;
                 NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_R64) NG_CASE(KID_BN_R16) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
                 NG_CASE(KID_ADD_R64) NG_CASE(KID_ADD_R16)
                 NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_POOL_P4) NG_CASE(KID_DW_K3S1_P4) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
@@ -1041,7 +1096,9 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
 #undef NG_CASE
                 default: break;
             }
+            wait();                      // an entry without tiles for this workgroup has not waited yet
             __syncthreads();             // every thread's stores have reached L2 (write-through L1, counted stores)
+            if (s_abort) return;
             if (tracer) {
                 const unsigned long long now = wall_clock64();
                 atomicMin(plan.trace + 4 * task + 2, now);
