@@ -301,3 +301,32 @@ def test_device_resident_timeline_respects_the_dag():
         assert all(t is None for t in again)
     finally:
         r.close()
+
+
+def test_device_resident_long_lists_reload_records():
+    """300 tiny dependent tasks: with one XCD and one-tile tasks, single workgroups get lists of
+    more records than they hold in LDS at a time, so the reload between chunks of a list is
+    exercised (and 300 same-stream hand-overs in a row)."""
+    def build(b):
+        x = b.input(1, 8, 4, 4)
+        y = x
+        for i in range(100):                      # affine maps and ReLU only: values stay O(1)
+            a = b.bn_act(y, relu=False)
+            c = b.relu(a)
+            y = b.bn_act(c, relu=False)
+    w = single_op(build)
+    ref = forward(w, keep=range(len(w.nodes)))
+    r = GraphRunner(w, DEV)
+    r.prepare(resident_xcds=1)
+    try:
+        n_wg, n_entries, xcds, _ = B.ng_resident_sizes(r.g)
+        assert xcds == 1 and n_entries >= 300
+        for _ in range(3):
+            r.arena.zero_()
+            r.set_input(w.input)
+            r.replay(B.NG_MODE_DEVICE_RESIDENT)
+            r.sync()
+            for v in (1, 150, 299, 300):
+                assert rel_err(r.output(v), ref[v]) <= TOL, v
+    finally:
+        r.close()
