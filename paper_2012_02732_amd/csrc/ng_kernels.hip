@@ -4,13 +4,14 @@
 // framework's operators unchanged (Section 5, "Experimental Setup"). These are the
 // operators of its benchmark networks, written for CDNA4.
 //
-// Every operator is written once as a *tile function*: the share of one 256-thread
-// workgroup, addressed by a linear tile index. Two kinds of kernels are built from them:
-//   * one stand-alone kernel per tile function (grid = number of tiles), taking ONE
-//     by-value argument struct so that the task table can hold a ready-made argument
-//     block per task (Section 4.1: kernel arguments are prepared once, ahead of time);
+// Every operator is written once as a *tile function*: the share of 256 threads,
+// addressed by a linear tile index. Two kinds of kernels are built from them:
+//   * one stand-alone kernel per tile function (grid = number of tiles, 256 threads),
+//     taking ONE by-value argument struct so that the task table can hold a ready-made
+//     argument block per task (Section 4.1: kernel arguments are prepared once, ahead of time);
 //   * the device-resident replay kernel at the end of this file, in which persistent
-//     workgroups walk the recorded task schedule themselves.
+//     workgroups of 512 threads (two tiles at a time) walk the recorded task schedule
+//     themselves.
 //
 // Sizing rule that differs from usual throughput tuning: tasks are small (tens of
 // thousands of elements) and are meant to run next to sibling tasks of other streams

@@ -16,15 +16,18 @@
 //     scheduling - trying 1..4 rounds of tiles per workgroup and keeping the earliest
 //     expected finish. Independent tasks therefore land on different workgroups and overlap;
 //     dependent ones reuse the workgroups that just finished their producer.
-//   * A task no other task can run beside, with more tiles than one XCD has workgroups, is
-//     spread over every participating XCD.
+//   * A task with more tiles than one XCD has workgroups may be spread over every participating
+//     XCD when that is expected to pay for the longer way its data then takes.
+//   * An elementwise task can take over the tile partition and the workgroups of the E' parent
+//     on its stream; that wait is then dropped (tile i needs only what the same workgroup wrote).
 //   * Every workgroup's list is a subsequence of one topological order (the order in which the
 //     planner placed the tasks) and a task waits only for earlier tasks, so with all
 //     workgroups resident no wait can depend on itself.
-//   * A task waits for all of its E' parents (FIFO order inside a stream does not order two
-//     workgroups). Whether a hand-over needs a device-scope fence is decided per tensor from
-//     *all* direct readers (edges of E): a reader on another XCD reads the tensor itself, even
-//     when it only waits for an intermediate task.
+//   * Otherwise a task waits for all of its E' parents (FIFO order inside a stream does not
+//     order two workgroups): through a counter in the XCD's L2 when producer and consumer share
+//     the XCD, through a device-scope counter when not. Whether a tensor is stored and loaded
+//     with device-scope accesses is decided from *all* direct readers (edges of E): a reader on
+//     another XCD reads the tensor itself, even when it only waits for an intermediate task.
 #include <algorithm>
 #include <cstdlib>
 #include <cstring>
