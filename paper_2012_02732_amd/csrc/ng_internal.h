@@ -114,6 +114,7 @@ size_t packed_floats(const ng_graph* g, int v);
 int pack_constants(ng_graph* g, int v, float* packed, void* stream);
 const void* resident_kernel_handle(bool full);
 const void* empty_kernel_handle();
+const void* xcd_probe_kernel_handle();
 // ng_resident_plan.cpp: xcds = 0 lets the cost model choose among 1, 2, 4, 8.
 int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan);
 // ng_runtime.hip

@@ -1154,6 +1154,15 @@ int pw_padded_steps(long cin) {
 
 }  // namespace
 
+// Which XCD runs workgroup i? The planner relies on i mod 8 (that is how a 1-D grid is dealt
+// out on this GPU); the runtime checks it with this probe before it trusts XCD-local L2s.
+namespace {
+__global__ __launch_bounds__(kGroup) void xcd_probe_kernel(int* xcd_of_workgroup) {
+    if (threadIdx.x == 0) xcd_of_workgroup[blockIdx.x] = (int)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));   // XCC_ID, bits 3:0
+}
+}  // namespace
+const void* xcd_probe_kernel_handle() { return reinterpret_cast<const void*>(&xcd_probe_kernel); }
+
 const void* resident_kernel_handle(bool full) {
     return full ? reinterpret_cast<const void*>(&resident_kernel<true>) : reinterpret_cast<const void*>(&resident_kernel<false>);
 }

@@ -38,6 +38,7 @@ struct Runtime {
     void* d_wg_first = nullptr;
     int* h_error = nullptr;                // pinned host memory
     int n_wg = 0, n_entries = 0;
+    bool xcd_mapping_ok = false;           // workgroup i of the resident grid runs on XCD i mod 8 (probed)
     bool resident_full = true;             // the DAG uses kernels the lean build of the resident kernel leaves out
     unsigned epoch = 0;
     size_t done_words = 0;
@@ -166,6 +167,23 @@ int build_resident(ng_graph* g) {
     if (per_cu < 1 || cus < 8) return g->fail(NG_EHIP, "device-resident replay: kernel does not fit (%d per CU, %d CUs)", per_cu, cus);
     per_cu = std::min(per_cu, g->resident_wg_per_cu > 0 ? g->resident_wg_per_cu : 1);   // one per CU: two slow each other's hand-overs down
     const int n_wg = cus * per_cu / 8 * 8;
+    // The plan keeps a stream's tensors and completion counters in the L2 of "its" XCD, taken to be
+    // workgroup index mod 8. Check that on this device with this grid; if it does not hold, every
+    // hand-over goes through device scope instead (correct whatever the mapping, only slower).
+    {
+        int* d_xcd = nullptr;
+        NG_HIP(hipMalloc(reinterpret_cast<void**>(&d_xcd), (size_t)n_wg * sizeof(int)));
+        void* probe_args[1] = {&d_xcd};
+        hipError_t pe = hipLaunchKernel(xcd_probe_kernel_handle(), dim3(n_wg), dim3(kGroup), probe_args, 0, rt.streams[0]);
+        std::vector<int> xcd_of((size_t)n_wg, -1);
+        if (pe == hipSuccess) pe = hipMemcpyAsync(xcd_of.data(), d_xcd, (size_t)n_wg * sizeof(int), hipMemcpyDeviceToHost, rt.streams[0]);
+        if (pe == hipSuccess) pe = hipStreamSynchronize(rt.streams[0]);
+        (void)hipFree(d_xcd);
+        if (pe != hipSuccess) return g->fail(NG_EHIP, "device-resident replay: XCD probe: %s", hipGetErrorString(pe));
+        rt.xcd_mapping_ok = true;
+        for (int w = 0; w < n_wg; ++w) rt.xcd_mapping_ok = rt.xcd_mapping_ok && xcd_of[w] == w % 8;
+        if (!rt.xcd_mapping_ok) g->resident_all_far = true;
+    }
     ResidentPlan hp;
     if (plan_resident(g, n_wg, g->resident_xcds, hp) != NG_OK)
         return g->fail(NG_EINVAL, "device-resident replay: a node has more than %d E' parents", NG_MAX_PREDS);
@@ -443,6 +461,13 @@ int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks) {
         NG_HIP(hipFree(rt.plan.trace));
         rt.plan.trace = nullptr;
     }
+    return NG_OK;
+}
+
+int ng_resident_xcd_mapping(const ng_graph* g, int* verified) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_resident_xcd_mapping: call ng_capture first");
+    if (verified) *verified = g->rt->xcd_mapping_ok ? 1 : 0;
     return NG_OK;
 }
 
