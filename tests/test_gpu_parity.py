@@ -357,3 +357,23 @@ def test_device_resident_on_random_dags(seed, shape, xcds):
             assert np.array_equal(outs[B.NG_MODE_GRAPH_SINGLE][v], outs[B.NG_MODE_DEVICE_RESIDENT][v]), (v, w.nodes[v].op)
     finally:
         r.close()
+
+
+def test_device_resident_device_scope_fallback():
+    """The fallback the runtime takes when workgroups are not dealt out to XCDs as expected:
+    every hand-over through device scope. Same results, bit for bit."""
+    w = workloads.make("random200")
+    r = GraphRunner(w, DEV)
+    r.prepare(resident_device_scope=1)
+    r2 = GraphRunner(w, DEV)
+    r2.prepare()
+    try:
+        a = r.run(w.input, mode=B.NG_MODE_DEVICE_RESIDENT)
+        b = r2.run(w.input, mode=B.NG_MODE_DEVICE_RESIDENT)
+        ref = forward(w)
+        for v in w.outputs:
+            assert np.array_equal(a[v], b[v])
+            assert rel_err(a[v], ref[v]) <= TOL
+    finally:
+        r.close()
+        r2.close()
