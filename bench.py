@@ -230,7 +230,9 @@ def main():
 
     n_wg, n_entries, xcds, est_us = B.ng_resident_sizes(runner.g)
     out = {
-        "metric": "DAG latency at batch 1 (replay + wait, input resident in HBM)",
+        "metric": "DAG latency (µs) at batch 1; % of critical-path bound; µs overhead/task",
+        "metric_note": "value = wall time of the K timed steps (each: replay + wait) / K, input resident in HBM; "
+                       "the other two parts of the metric are critical_path.fraction_of_bound and .overhead_us_per_task",
         "value": ms_per_step * 1e3, "unit": "us",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
