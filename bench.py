@@ -106,6 +106,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-modes", action="store_true")
     ap.add_argument("--per-task", action="store_true", help="also print a per-kernel table to stderr")
+    ap.add_argument("--timeline", action="store_true",
+                    help="device-resident mode: print how many tasks execute at the same time during one traced replay (stderr)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy (scale reference for HBM traffic counters)")
     args = ap.parse_args()
@@ -221,6 +223,25 @@ def main():
                 wait_us += tr[v][1] - (tr[u][3] if u is not None else 0.0)
                 hops += 1
                 v = u
+            if args.timeline:
+                # tasks executing at the same time: a task counts from the moment its last workgroup is past
+                # the wait until its last workgroup has stored its tiles
+                events = []
+                for u in ran:
+                    events.append((tr[u][1], 1))
+                    events.append((tr[u][3], -1))
+                events.sort()
+                hist, level, last_t = {}, 0, 0.0
+                for t_ev, d in events:
+                    hist[level] = hist.get(level, 0.0) + (t_ev - last_t)
+                    level += d
+                    last_t = t_ev
+                print(f"traced replay: {span:.1f} us, {len(ran)} tasks; time with k tasks executing:", file=sys.stderr)
+                for k in sorted(hist):
+                    print(f"  k = {k:2d}: {hist[k]:7.1f} us  {100 * hist[k] / span:5.1f} %", file=sys.stderr)
+                busy = sum(tr[u][3] - tr[u][1] for u in ran)
+                print(f"  sum of task execution intervals {busy:.1f} us = {busy / span:.2f} tasks executing on average; "
+                      f"no task executing (hand-overs only) {hist.get(0, 0.0):.1f} us", file=sys.stderr)
             timeline = {"traced_replay_us": span, "tasks_on_realised_chain": hops, "tile_execution_us": run_us,
                         "hand_over_us": wait_us,
                         "note": "one replay with per-task clock readings (they slow this one replay down by 15-20 %): "
