@@ -215,8 +215,8 @@ int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned sp
  * have stored their tiles. Record ONE replay between two calls for a timeline of that
  * replay. Waits for the origin stream to go idle. */
 int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks);
-/* *verified = 1 if the probe at ng_capture found workgroup i of the resident grid on XCD i mod 8,
- * which is what the plan's use of XCD-local L2s rests on; 0 if not, in which case every hand-over
+/* *verified = 1 if the probe at ng_capture found that workgroups of the resident grid with equal
+ * index mod 8 share an XCD, which is what the plan's use of XCD-local L2s rests on; 0 if not, in which case every hand-over
  * of the device-resident replay goes through device scope (correct on any mapping, slower). */
 int ng_resident_xcd_mapping(const ng_graph* g, int* verified);
 /* Host-only rehearsal of the device-resident plan (needs ng_plan_memory, no GPU): plans for

@@ -209,7 +209,7 @@ struct DevPlan {
     unsigned spin_limit;
     int done_stride;                 // words between two tasks' counters (spreads them over memory channels)
     int poll_sleep;                  // 0, 1, 2: back-off between two polls (1, 4, 16 sleep units)
-    unsigned long long* trace;       // optional [n_nodes][4]: first wait begins, last workgroup ready, first and last workgroup done (100 MHz clock)
+    unsigned long long* trace;       // optional [n_entries][3]: the entry starts to wait, is past the wait, has stored its tiles (100 MHz clock)
 };
 
 }  // namespace ng

@@ -991,7 +991,8 @@ struct CounterWait {
     int* s_abort;
     unsigned epoch;
     int task, np, lane;
-    bool tracer, pending;
+    unsigned long long* stamp;       // this entry's three clock readings when tracing, else nullptr (same for all lanes)
+    bool pending;
 
     __device__ __forceinline__ void operator()() {
         if (!pending) return;
@@ -1044,7 +1045,7 @@ struct CounterWait {
             }
             __syncthreads();                                    // also waits for the invalidate to finish
         }
-        if (tracer) atomicMax(plan.trace + 4 * task + 1, wall_clock64());
+        if (stamp != nullptr && lane == 0) stamp[1] = wall_clock64();
     }
 };
 
@@ -1078,12 +1079,13 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             const int flags = __builtin_amdgcn_readfirstlane(rec[6]), subs_word = __builtin_amdgcn_readfirstlane(rec[7]);
             const int subs = subs_word & 0xff, xcd_peers = subs_word >> 8;
             const bool far_in = (flags & 1) != 0, far_out = (flags & 2) != 0;
-            const bool tracer = plan.trace != nullptr && lane == 0;
-            if (tracer) atomicMin(plan.trace + 4 * task, wall_clock64());
+            // tracing: thread 0 stamps the clock into this entry's own slot (plain stores, nothing waits for them)
+            unsigned long long* stamp = plan.trace != nullptr ? plan.trace + 3 * (size_t)(chunk + e) : nullptr;
+            if (stamp != nullptr && lane == 0) stamp[0] = wall_clock64();
             // What the task can do without its inputs (addresses, weights) happens inside the tile
             // function before it calls `wait`; an entry that fails to wait in time still runs its
             // tiles (all accesses stay in bounds) and the workgroup leaves right after.
-            CounterWait wait{plan, rec, &s_abort, epoch, task, np, lane, tracer, true};
+            CounterWait wait{plan, rec, &s_abort, epoch, task, np, lane, stamp, true};
             switch (kid) {
 #define NG_CASE(KID) case KID: if (FULL || is_lean_kernel(KID)) run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out, wait); break;
                 NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_R64) NG_CASE(KID_BN_R16) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
@@ -1100,11 +1102,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             wait();                      // an entry without tiles for this workgroup has not waited yet
             __syncthreads();             // every thread's stores have reached L2 (write-through L1, counted stores)
             if (s_abort) return;
-            if (tracer) {
-                const unsigned long long now = wall_clock64();
-                atomicMin(plan.trace + 4 * task + 2, now);
-                atomicMax(plan.trace + 4 * task + 3, now);
-            }
+            if (stamp != nullptr && lane == 0) stamp[2] = wall_clock64();
             if (lane == 0) {
                 // Publish completion. Readers on this XCD see the data in the shared L2 and are told through
                 // a counter in that same L2 (an atomic without device scope is carried out there); if there
@@ -1154,8 +1152,9 @@ int pw_padded_steps(long cin) {
 
 }  // namespace
 
-// Which XCD runs workgroup i? The planner relies on i mod 8 (that is how a 1-D grid is dealt
-// out on this GPU); the runtime checks it with this probe before it trusts XCD-local L2s.
+// Which XCD runs workgroup i? The planner relies on workgroups with equal i mod 8 sharing one
+// (a 1-D grid is dealt out round-robin on this GPU); the runtime checks it with this probe
+// before it trusts XCD-local L2s.
 namespace {
 __global__ __launch_bounds__(kGroup) void xcd_probe_kernel(int* xcd_of_workgroup) {
     if (threadIdx.x == 0) xcd_of_workgroup[blockIdx.x] = (int)__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11));   // XCC_ID, bits 3:0

@@ -38,7 +38,8 @@ struct Runtime {
     void* d_wg_first = nullptr;
     int* h_error = nullptr;                // pinned host memory
     int n_wg = 0, n_entries = 0;
-    bool xcd_mapping_ok = false;           // workgroup i of the resident grid runs on XCD i mod 8 (probed)
+    std::vector<int> entry_task;           // node of every list entry, in record order (for the timeline)
+    bool xcd_mapping_ok = false;           // workgroups of the resident grid with equal index mod 8 share an XCD (probed)
     bool resident_full = true;             // the DAG uses kernels the lean build of the resident kernel leaves out
     unsigned epoch = 0;
     size_t done_words = 0;
@@ -167,9 +168,10 @@ int build_resident(ng_graph* g) {
     if (per_cu < 1 || cus < 8) return g->fail(NG_EHIP, "device-resident replay: kernel does not fit (%d per CU, %d CUs)", per_cu, cus);
     per_cu = std::min(per_cu, g->resident_wg_per_cu > 0 ? g->resident_wg_per_cu : 1);   // one per CU: two slow each other's hand-overs down
     const int n_wg = cus * per_cu / 8 * 8;
-    // The plan keeps a stream's tensors and completion counters in the L2 of "its" XCD, taken to be
-    // workgroup index mod 8. Check that on this device with this grid; if it does not hold, every
-    // hand-over goes through device scope instead (correct whatever the mapping, only slower).
+    // The plan keeps a stream's tensors and completion counters in the L2 of "its" XCD and takes
+    // workgroups with the same index mod 8 to share one. Check that on this device with this grid; if
+    // it does not hold, every hand-over goes through device scope instead (correct whatever the
+    // mapping, only slower).
     {
         int* d_xcd = nullptr;
         NG_HIP(hipMalloc(reinterpret_cast<void**>(&d_xcd), (size_t)n_wg * sizeof(int)));
@@ -180,8 +182,15 @@ int build_resident(ng_graph* g) {
         if (pe == hipSuccess) pe = hipStreamSynchronize(rt.streams[0]);
         (void)hipFree(d_xcd);
         if (pe != hipSuccess) return g->fail(NG_EHIP, "device-resident replay: XCD probe: %s", hipGetErrorString(pe));
+        // the dispatcher deals workgroups out round-robin, starting at an XCD that depends on what ran
+        // before: which XCD a class gets does not matter, only that a class stays together
         rt.xcd_mapping_ok = true;
-        for (int w = 0; w < n_wg; ++w) rt.xcd_mapping_ok = rt.xcd_mapping_ok && xcd_of[w] == w % 8;
+        for (int w = 0; w < n_wg; ++w) rt.xcd_mapping_ok = rt.xcd_mapping_ok && xcd_of[w] >= 0 && xcd_of[w] == xcd_of[w % 8];
+        if (!rt.xcd_mapping_ok && getenv("NG_PLAN_DEBUG")) {
+            fprintf(stderr, "XCD probe mismatch:");
+            for (int w = 0; w < std::min(n_wg, 48); ++w) fprintf(stderr, " %d", xcd_of[w]);
+            fprintf(stderr, "\n");
+        }
         if (!rt.xcd_mapping_ok) g->resident_all_far = true;
     }
     ResidentPlan hp;
@@ -195,7 +204,9 @@ int build_resident(ng_graph* g) {
     // one self-contained record per entry: the kernel never touches the task table itself
     std::vector<DevRecord> records(std::max<size_t>(entries.size(), 1));
     std::memset(records.data(), 0, records.size() * sizeof(DevRecord));
+    rt.entry_task.assign(entries.size(), 0);
     for (size_t e = 0; e < entries.size(); ++e) {
+        rt.entry_task[e] = entries[e].task;
         const DevTask& t = tasks[entries[e].task];
         DevRecord& r = records[e];
         r.task = entries[e].task, r.kid = t.kid, r.ntiles = t.ntiles, r.n_parents = t.n_parents;
@@ -446,17 +457,27 @@ int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks) {
     if (!g) return NG_EINVAL;
     if (g->phase < CAPTURED || !g->rt->d_records) return g->fail(NG_ESTATE, "ng_resident_trace: call ng_capture first");
     Runtime& rt = *g->rt;
-    const size_t n = g->nodes.size(), bytes = n * 4 * sizeof(unsigned long long);
+    // the kernel keeps three readings per list entry; a node's figures are the extremes over its entries
+    const size_t n = g->nodes.size(), entries = rt.entry_task.size(), bytes = std::max<size_t>(entries, 1) * 3 * sizeof(unsigned long long);
     NG_HIP(hipStreamSynchronize(rt.streams[0]));
     if (ticks) {
         if (!rt.plan.trace) return g->fail(NG_ESTATE, "ng_resident_trace: tracing is off");
-        NG_HIP(hipMemcpy(ticks, rt.plan.trace, bytes, hipMemcpyDeviceToHost));
+        std::vector<unsigned long long> raw(std::max<size_t>(entries, 1) * 3);
+        NG_HIP(hipMemcpy(raw.data(), rt.plan.trace, bytes, hipMemcpyDeviceToHost));
+        for (size_t v = 0; v < n; ++v) ticks[4 * v] = ticks[4 * v + 2] = ~0ull, ticks[4 * v + 1] = ticks[4 * v + 3] = 0;
+        for (size_t e = 0; e < entries; ++e) {
+            const unsigned long long* r = &raw[3 * e];
+            if (r[2] == 0) continue;                             // entry did not run since tracing was switched on
+            const size_t v = (size_t)rt.entry_task[e];
+            ticks[4 * v] = std::min(ticks[4 * v], r[0]);
+            ticks[4 * v + 1] = std::max(ticks[4 * v + 1], r[1]);
+            ticks[4 * v + 2] = std::min(ticks[4 * v + 2], r[2]);
+            ticks[4 * v + 3] = std::max(ticks[4 * v + 3], r[2]);
+        }
     }
     if (enable) {
         if (!rt.plan.trace) NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.plan.trace), bytes));
-        std::vector<unsigned long long> init(n * 4);                 // minima start at the top, maxima at 0
-        for (size_t v = 0; v < n; ++v) init[4 * v] = init[4 * v + 2] = ~0ull, init[4 * v + 1] = init[4 * v + 3] = 0;
-        NG_HIP(hipMemcpy(rt.plan.trace, init.data(), bytes, hipMemcpyHostToDevice));
+        NG_HIP(hipMemset(rt.plan.trace, 0, bytes));
     } else if (rt.plan.trace) {
         NG_HIP(hipFree(rt.plan.trace));
         rt.plan.trace = nullptr;

@@ -268,7 +268,7 @@ def test_auto_mode_picks_the_fastest_trial_and_replays_correctly():
     try:
         mode, trial = B.ng_auto_mode(r.g)
         assert mode in (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT)
-        assert B.ng_resident_xcd_mapping(r.g)        # workgroup i on XCD i mod 8: what the XCD-local hand-overs rest on
+        assert B.ng_resident_xcd_mapping(r.g)        # equal index mod 8 -> same XCD: what the XCD-local hand-overs rest on
         assert all(t > 0 for t in trial.values()) and trial[mode] == min(trial.values())
         out = r.run(mode=B.NG_MODE_AUTO)
         for v in w.outputs:
