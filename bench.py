@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes of one device-resident replay, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # scaled by what the same counters read for a plain 256 MiB copy (2.00 and 1.00): the
 # summary with the commands is profiles/resident_kernel_nasnet_style.md.
-MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (35268.6 * 2.00 + 47537.9 * 1.00) * 1024}
+MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (35263.6 * 2.00 + 47577.4 * 1.00) * 1024}
 
 MODES = {"graph_multi": 0, "graph_single": 1, "eager_single": 2, "eager_multi": 3, "device_resident": 4}
 MODE_NAMES = {v: k for k, v in MODES.items()}
@@ -244,7 +244,7 @@ def main():
                       f"no task executing (hand-overs only) {hist.get(0, 0.0):.1f} us", file=sys.stderr)
             timeline = {"traced_replay_us": span, "tasks_on_realised_chain": hops, "tile_execution_us": run_us,
                         "hand_over_us": wait_us,
-                        "note": "one replay with per-task clock readings (they slow this one replay down by 15-20 %): "
+                        "note": "one replay with per-entry clock readings (three plain stores per list entry, about 1 % slower): "
                                 "tile execution = last workgroup past its wait -> last workgroup stored; hand-over = "
                                 "the rest, i.e. a producer's last store -> the consumer past its wait, which includes "
                                 "the consumer's input-independent prologue"}

@@ -213,7 +213,9 @@ int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned sp
  * clock; a task that did not run keeps ~0, 0, ~0, 0): the first workgroup starts to wait for
  * the producers, the last workgroup has its inputs ready, the first and the last workgroup
  * have stored their tiles. Record ONE replay between two calls for a timeline of that
- * replay. Waits for the origin stream to go idle. */
+ * replay. A batch-norm / ReLU node that the plan fused into the convolution feeding it has
+ * no workgroups of its own: it reports the convolution's first / last store for both pairs
+ * (an interval of length zero). Waits for the origin stream to go idle. */
 int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks);
 /* *verified = 1 if the probe at ng_capture found that workgroups of the resident grid with equal
  * index mod 8 share an XCD, which is what the plan's use of XCD-local L2s rests on; 0 if not, in which case every hand-over
@@ -223,8 +225,9 @@ int ng_resident_xcd_mapping(const ng_graph* g, int* verified);
  * n_workgroups persistent workgroups (a multiple of 8) over xcds XCDs (0 = let the cost
  * model choose) and reports the expected makespan in microseconds, the number of
  * (workgroup, task) entries, the number of operands that cross XCDs, and whether the plan
- * passed its self-check (every tile of every task assigned exactly once, every list in
- * ascending task id, expected completion counts consistent). Any pointer may be NULL. */
+ * passed its self-check (every tile of every task assigned exactly once - a batch-norm / ReLU
+ * node fused into its convolution counts through that convolution's tiles -, every list in one
+ * common topological order, expected completion counts consistent). Any pointer may be NULL. */
 int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, double* expected_us, int* n_entries,
                          int* n_far_edges, int* coverage_ok);
 /* Layout chosen at ng_capture: resident workgroups, total (workgroup, task) entries, XCDs in

@@ -115,6 +115,17 @@ struct FcArgs {
     int N, Cin, Cout;
 };
 
+// Optional second result of a convolution tile (device-resident replay only): the batch-norm /
+// ReLU task that takes over the tile partition of the convolution is applied to the values
+// while they are still in registers, z = act(y * scale[c] + shift[c]) - the same arithmetic on
+// the same values as the stand-alone elementwise kernel. y == nullptr: none.
+struct Epilogue {
+    const float* scale;        // [Cout] or nullptr (plain ReLU: scale 1, shift 0)
+    const float* shift;
+    float* y;                  // same shape as the convolution's result
+    int relu;
+};
+
 struct PwArgs {
     const float* x;            // [N][Cin][HW]
     const float* w;            // [Cout][Cin]
@@ -126,6 +137,7 @@ struct PwArgs {
     int ksteps;                // 32 x 32 kernels: k-steps of 4 in the packed copy (padded, a multiple of 4 * chunk);
                                // 16-row kernels: groups of 4 k-steps in the packed copy (a multiple of 4 * groups in flight)
     int mtiles;                // direct kernels: ceil(Cout / 16)
+    Epilogue ep;               // 16-row kernels only
 };
 
 struct C3Args {
@@ -143,7 +155,9 @@ struct C3Args {
     int stride;
     int cols;                  // N * Ho * Wo
     int tiles_n;               // ceil(cols / 16)
+    Epilogue ep;               // implicit-GEMM kernels only
 };
+static_assert(sizeof(PwArgs) <= 48 * 4 && sizeof(C3Args) <= 48 * 4, "argument block the resident kernel prefetches");
 
 // ---- device-resident replay: the task schedule as data in device memory -------------------
 constexpr int kArgWords = 48;        // words of the argument block the resident kernel prefetches

@@ -69,6 +69,7 @@ struct ResidentPlan {
     std::vector<DevEntry> entries;             // per-workgroup lists, concatenated
     std::vector<int> wg_first;                 // [n_wg + 1]
     std::vector<int> order;                    // tasks in list order: every workgroup's list is a subsequence of it
+    std::vector<int> fused_into;               // [n_nodes] convolution whose tiles also produce this task's result (no entries of its own), or -1
 };
 
 struct Runtime;  // HIP-side state, defined in ng_runtime.hip

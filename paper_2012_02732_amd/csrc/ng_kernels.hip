@@ -637,6 +637,10 @@ __device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float
     const unsigned k_last = (unsigned)(a.Cin - 1) * (unsigned)a.HW;       // rows past Cin (zero weights) repeat the last row
     const unsigned k_step = 4u * (unsigned)a.HW;
     unsigned koff = (unsigned)(16 * wave * gw + (lane >> 4)) * (unsigned)a.HW;
+    // wavefront w finishes accumulator register w of every MFMA tile: output row 4 (lane / 16) + w
+    const int m = by * 16 + 4 * (lane >> 4) + wave;
+    float es = 1.f, et = 0.f;
+    if (a.ep.y != nullptr && a.ep.scale != nullptr) es = a.ep.scale[min(m, a.Cout - 1)], et = a.ep.shift[min(m, a.Cout - 1)];
     wait();
     if (live) {
         f32x4 acc[NJ];
@@ -677,8 +681,6 @@ __device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float
     }
     __syncthreads();
     if (live) {
-        // wavefront w finishes accumulator register w of every MFMA tile: output row 4 (lane / 16) + w
-        const int m = by * 16 + 4 * (lane >> 4) + wave;
         float out[NJ];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
@@ -690,9 +692,16 @@ __device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float
         if (m < a.Cout && colv < a.cols) {                   // VEC: cols is a multiple of 4, a lane's 4 columns are all in or all out
             const float b = a.bias ? a.bias[m] : 0.f;
             const int img = colv / a.HW, pix = colv - img * a.HW;
-            float* dst = a.y + ((size_t)img * a.Cout + m) * a.HW + pix;
-            if (VEC) stg4(a.y, dst, make_float4(out[0] + b, out[NJ > 1 ? 1 : 0] + b, out[NJ > 2 ? 2 : 0] + b, out[NJ > 3 ? 3 : 0] + b), FOUT);
-            else stg(a.y, dst, out[0] + b, FOUT);
+            const size_t at = ((size_t)img * a.Cout + m) * a.HW + pix;
+            float4 v = make_float4(out[0] + b, out[NJ > 1 ? 1 : 0] + b, out[NJ > 2 ? 2 : 0] + b, out[NJ > 3 ? 3 : 0] + b);
+            if (VEC) stg4(a.y, a.y + at, v, FOUT);
+            else stg(a.y, a.y + at, v.x, FOUT);
+            if (a.ep.y != nullptr) {
+                v.x = fmaf(v.x, es, et), v.y = fmaf(v.y, es, et), v.z = fmaf(v.z, es, et), v.w = fmaf(v.w, es, et);
+                if (a.ep.relu) v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
+                if (VEC) stg4(a.ep.y, a.ep.y + at, v, FOUT);
+                else stg(a.ep.y, a.ep.y + at, v.x, FOUT);
+            }
         }
     }
     __syncthreads();                                         // LDS is reused by the next tile
@@ -813,6 +822,9 @@ __device__ __forceinline__ void conv3x3_k4_tile(const C3Args& a, int tile, float
     const float* xb = a.x + (size_t)img * a.Cin * HW;
     const int k0 = 16 * wave * gw + (lane >> 4);             // this lane's first k; then + 4 per k-step
     int ci = k0 / 9, tap = k0 - 9 * ci;
+    const int m = by * 16 + 4 * (lane >> 4) + wave;          // wavefront w finishes accumulator register w
+    float es = 1.f, et = 0.f;
+    if (a.ep.y != nullptr && a.ep.scale != nullptr) es = a.ep.scale[min(m, a.Cout - 1)], et = a.ep.shift[min(m, a.Cout - 1)];
     wait();
     if (live) {
         f32x4 acc = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -848,13 +860,17 @@ __device__ __forceinline__ void conv3x3_k4_tile(const C3Args& a, int tile, float
     }
     __syncthreads();
     if (live) {
-        const int m = by * 16 + 4 * (lane >> 4) + wave;      // wavefront w finishes accumulator register w
         float sum = smem[(0 * 4 + wave) * 64 + lane];
 #pragma unroll
         for (int w2 = 1; w2 < 4; ++w2) sum += smem[(w2 * 4 + wave) * 64 + lane];
         if (m < a.Cout && colv < a.cols) {
             const int img = colv / HWo, pix = colv - img * HWo;
-            stg(a.y, a.y + ((size_t)img * a.Cout + m) * HWo + pix, sum, FOUT);
+            const size_t at = ((size_t)img * a.Cout + m) * HWo + pix;
+            stg(a.y, a.y + at, sum, FOUT);
+            if (a.ep.y != nullptr) {
+                const float z = fmaf(sum, es, et);
+                stg(a.ep.y, a.ep.y + at, a.ep.relu ? fmaxf(z, 0.f) : z, FOUT);
+            }
         }
     }
     __syncthreads();                                         // LDS is reused by the next tile

@@ -46,6 +46,7 @@ constexpr double kSyncNearUs = 0.7;   // completion counter -> dependent workgro
 constexpr double kSyncFarUs = 2.0;    // extra cost when producer and consumer sit on different XCDs (measured)
 constexpr double kPublishUs = 0.3;    // stores drained and counter bumped: the workgroup moves on to its next entry
 constexpr double kLocalUs = 0.1;      // hand-over inside one workgroup: one barrier
+constexpr double kFusedUs = 0.05;     // a batch-norm applied in the convolution's registers: a few instructions, one more store
 constexpr double kSpreadPenaltyUs = 5.0; // what spreading a task over all XCDs must gain before it is preferred (its readers go the long way too)
 constexpr double kFarRunFactor = 1.2; // a tile whose loads and stores all go through the memory side takes longer
 
@@ -125,6 +126,7 @@ struct Sim {
     std::vector<int> subs;           // sub-blocks per workgroup that take a tile each
     std::vector<int> order;          // tasks in the order they were placed: every workgroup's list follows it
     std::vector<int> local_parent;   // E' parent whose completion this task does not wait for (same workgroups, same tiles), or -1
+    std::vector<int> fused_into;     // convolution whose tiles also produce this (batch-norm / ReLU) task's result, or -1
     double makespan = 0;
 };
 
@@ -161,6 +163,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     out.ntiles.assign(n, 0);
     out.subs.assign(n, kSubs);
     out.local_parent.assign(n, -1);
+    out.fused_into.assign(n, -1);
+    const bool allow_fuse = getenv("NG_NO_FUSE") == nullptr;
     std::vector<double> free_at(n_wg, 0.0), finish(n, 0.0);
     std::vector<std::vector<int>> parents(n), wgs(n);
     for (auto& e : sc.meg) parents[e.second].push_back(e.first);
@@ -195,6 +199,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     for (int v = 0; v < n; ++v)
         if (g->tasks[v].fn && waiting[v] == 0) open.push(Key(0.0, -tail[v], v));
     out.order.clear();
+    std::vector<char> fused_child(n, 0);                        // the convolution already carries an epilogue
 
     while (!open.empty()) {
         const int v = std::get<2>(open.top());
@@ -210,6 +215,35 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             !getenv("NG_NO_P4")) {
             out.kid[v] = t.kid == KID_POOL ? KID_POOL_P4 : KID_DW_K3S1_P4;
             out.ntiles[v] = (g->nodes[v].out.elems() + 4 * kBlock - 1) / (4 * kBlock);
+        }
+        // A batch-norm / ReLU task whose only producer is a 16-row convolution is not run at all:
+        // the convolution's tiles apply it to their results before they store them (same tile
+        // grid, same arithmetic), and whoever waits for this task waits for the convolution.
+        if (allow_fuse && allow_local && (g->nodes[v].op == NG_OP_BN_ACT || g->nodes[v].op == NG_OP_RELU) &&
+            parents[v].size() == 1 && g->nodes[v].preds.size() == 1 && parents[v][0] == g->nodes[v].preds[0]) {
+            const int u = parents[v][0];
+            long nt = 0;
+            const bool conv16 = g->tasks[u].fn && ((out.kid[u] >= KID_PW_V1 && out.kid[u] <= KID_PW_S4) ||
+                                                   (out.kid[u] >= KID_C3_M1 && out.kid[u] <= KID_C3_M4));
+            if (conv16 && !fused_child[u] && g->nodes[u].out == g->nodes[v].out &&
+                variant_for(g, v, partition_of(out.kid[u]), &nt) != KID_NONE && nt == out.ntiles[u]) {
+                fused_child[u] = 1;
+                out.fused_into[v] = u;
+                out.local_parent[v] = u;
+                out.kid[v] = variant_for(g, v, partition_of(out.kid[u]), &nt);
+                out.ntiles[v] = nt;
+                out.subs[v] = out.subs[u];
+                out.xcd[v] = out.xcd[u];
+                wgs[v] = wgs[u];
+                out.parts[v] = out.parts[u];
+                out.signals[v] = out.signals[u];
+                finish[v] = finish[u] + kFusedUs;
+                out.makespan = std::max(out.makespan, finish[v]);
+                if (debug) fprintf(stderr, "PLAN nx=%d v=%d fused into %d finish=%.2f\n", nx, v, u, finish[v]);
+                for (int c : children[v])
+                    if (--waiting[c] == 0) open.push(Key(ready_time(c), -tail[c], c));
+                continue;
+            }
         }
         const int kid0 = out.kid[v];                        // before a possible change of partition below
         const long ntiles0 = out.ntiles[v];
@@ -354,6 +388,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     plan.xcds = best_nx;
     plan.est_us = best.makespan;
     plan.order = best.order;
+    plan.fused_into = best.fused_into;
 
     plan.tasks.assign(n, DevTask());
     for (int v = 0; v < n; ++v) {
@@ -380,19 +415,31 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
                 if (g->tasks[u].fn) plan.tasks[u].release_far = 1;
         if (g->resident_all_far) plan.tasks[v].release_far = 1;
     }
+    // fused pairs: the convolution's argument block gets the batch-norm's coefficients and output
+    for (int v = 0; v < n; ++v) {
+        const int u = best.fused_into[v];
+        if (u < 0) continue;
+        const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
+        Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};
+        const bool c3 = best.kid[u] >= KID_C3_M1 && best.kid[u] <= KID_C3_M4;
+        if (c3) reinterpret_cast<C3Args*>(plan.tasks[u].args)->ep = ep;
+        else reinterpret_cast<PwArgs*>(plan.tasks[u].args)->ep = ep;
+        plan.tasks[u].release_far |= plan.tasks[v].release_far;   // both results are stored the same way
+    }
     for (auto& e : sc.meg) {
         if (!g->tasks[e.first].fn || !g->tasks[e.second].fn) continue;
         if (best.local_parent[e.second] == e.first) continue;   // handed over inside the workgroups
+        const int src = best.fused_into[e.first] >= 0 ? best.fused_into[e.first] : e.first;   // who really produces it
         DevTask& d = plan.tasks[e.second];
         if (d.n_parents >= NG_MAX_PREDS) return NG_EINVAL;
-        d.parent[d.n_parents] = e.first;
-        d.need[d.n_parents] = best.signals[e.first];
+        d.parent[d.n_parents] = src;
+        d.need[d.n_parents] = best.signals[src];
         // producer and consumer on the same single XCD: the completion is signalled through that XCD's L2
-        const bool near = best.xcd[e.first] >= 0 && best.xcd[e.first] == best.xcd[e.second] && !g->resident_all_far &&
+        const bool near = best.xcd[src] >= 0 && best.xcd[src] == best.xcd[e.second] && !g->resident_all_far &&
                           !getenv("NG_NO_NEAR_COUNTERS");
-        if (near) plan.tasks[e.first].publish |= 1u;
-        else plan.tasks[e.first].publish |= 2u, d.parent_far |= 1u << d.n_parents;
-        if (!near && best.signals[e.first] != best.parts[e.first]) plan.tasks[e.first].publish |= 4u;
+        if (near) plan.tasks[src].publish |= 1u;
+        else plan.tasks[src].publish |= 2u, d.parent_far |= 1u << d.n_parents;
+        if (!near && best.signals[src] != best.parts[src]) plan.tasks[src].publish |= 4u;
         ++d.n_parents;
     }
     plan.entries.clear();
@@ -485,9 +532,27 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
                 signals[v] = (plan.tasks[v].publish & 4u) ? (unsigned)used : parts[v];
             }
         }
-        int n_local = 0;
+        int n_local = 0, n_fused = 0;
         for (size_t v = 0; v < n; ++v) {
             if (!g->tasks[v].fn) continue;
+            const int host = plan.fused_into[v];
+            if (host >= 0) {
+                // a fused batch-norm has no entries and no waits of its own; its convolution covers the same
+                // tile grid, comes earlier in the order and carries its coefficients and output address
+                ++n_fused;
+                const int hk = plan.tasks[host].kid;
+                const bool c3 = hk >= KID_C3_M1 && hk <= KID_C3_M4, pw = hk >= KID_PW_V1 && hk <= KID_PW_S4;
+                const Epilogue* ep = c3 ? &reinterpret_cast<const C3Args*>(plan.tasks[host].args)->ep
+                                        : &reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->ep;
+                const BnArgs* bn = reinterpret_cast<const BnArgs*>(plan.tasks[v].args);
+                ok = ok && (c3 || pw) && hits[v].empty() && plan.tasks[v].n_parents == 0 && plan.fused_into[host] < 0 &&
+                     pos[host] < pos[v] && g->nodes[v].preds.size() == 1 && g->nodes[v].preds[0] == host &&
+                     g->nodes[host].out == g->nodes[v].out && partition_of(hk) == partition_of(plan.tasks[v].kid) &&
+                     plan.tasks[host].ntiles == plan.tasks[v].ntiles && ep->y == bn->y && ep->scale == bn->scale &&
+                     ep->shift == bn->shift && ep->relu == bn->relu &&
+                     (plan.tasks[host].release_far || !plan.tasks[v].release_far);
+                continue;
+            }
             ok = ok && plan.tasks[v].ntiles > 0 && hits[v].size() == (size_t)units_of((int)v);
             for (int h : hits[v]) ok = ok && h == 1;
             const DevTask& d = plan.tasks[v];
@@ -497,13 +562,25 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
             const int u = e.first, v = e.second;
             if (!g->tasks[u].fn || !g->tasks[v].fn) continue;
             const DevTask& d = plan.tasks[v];
-            if (std::find(d.parent, d.parent + d.n_parents, u) != d.parent + d.n_parents) continue;
+            if (plan.fused_into[v] == u) continue;                                    // checked above
+            const int src = plan.fused_into[u] >= 0 ? plan.fused_into[u] : u;         // whose workgroups store u's result
+            if (std::find(d.parent, d.parent + d.n_parents, src) != d.parent + d.n_parents) continue;
             ++n_local;
             const int part = partition_of(plan.tasks[u].kid);
-            ok = ok && part != PART_NONE && part == partition_of(d.kid) && plan.tasks[u].ntiles == d.ntiles &&
-                 g->nodes[u].out == g->nodes[v].out && where[u] == where[v];
+            ok = ok && plan.fused_into[v] < 0 && part != PART_NONE && part == partition_of(d.kid) && plan.tasks[u].ntiles == d.ntiles &&
+                 g->nodes[u].out == g->nodes[v].out && where[src] == where[v];
         }
-        if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d\n", n_local);
+        // a convolution without a fused follower has no epilogue
+        std::vector<char> has_child(n, 0);
+        for (size_t v = 0; v < n; ++v)
+            if (plan.fused_into[v] >= 0) ok = ok && !has_child[plan.fused_into[v]], has_child[plan.fused_into[v]] = 1;
+        for (size_t u = 0; u < n; ++u) {
+            const int k = plan.tasks[u].kid;
+            if (!g->tasks[u].fn || has_child[u]) continue;
+            if (k >= KID_C3_M1 && k <= KID_C3_M4) ok = ok && reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y == nullptr;
+            if (k >= KID_PW_V1 && k <= KID_PW_S4) ok = ok && reinterpret_cast<const PwArgs*>(plan.tasks[u].args)->ep.y == nullptr;
+        }
+        if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d, fused: %d\n", n_local, n_fused);
         if (coverage_ok) *coverage_ok = ok;
     }
     g->dry_run = false;

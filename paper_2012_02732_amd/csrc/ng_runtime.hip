@@ -39,6 +39,7 @@ struct Runtime {
     int* h_error = nullptr;                // pinned host memory
     int n_wg = 0, n_entries = 0;
     std::vector<int> entry_task;           // node of every list entry, in record order (for the timeline)
+    std::vector<int> fused_into;           // per node: the convolution that also produces its result, or -1
     bool xcd_mapping_ok = false;           // workgroups of the resident grid with equal index mod 8 share an XCD (probed)
     bool resident_full = true;             // the DAG uses kernels the lean build of the resident kernel leaves out
     unsigned epoch = 0;
@@ -205,6 +206,7 @@ int build_resident(ng_graph* g) {
     std::vector<DevRecord> records(std::max<size_t>(entries.size(), 1));
     std::memset(records.data(), 0, records.size() * sizeof(DevRecord));
     rt.entry_task.assign(entries.size(), 0);
+    rt.fused_into = hp.fused_into;
     for (size_t e = 0; e < entries.size(); ++e) {
         rt.entry_task[e] = entries[e].task;
         const DevTask& t = tasks[entries[e].task];
@@ -474,6 +476,12 @@ int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks) {
             ticks[4 * v + 2] = std::min(ticks[4 * v + 2], r[2]);
             ticks[4 * v + 3] = std::max(ticks[4 * v + 3], r[2]);
         }
+        // a fused task ran inside its convolution's tiles: it takes no time of its own, at the moment the tiles are stored
+        for (size_t v = 0; v < n && v < rt.fused_into.size(); ++v)
+            if (rt.fused_into[v] >= 0) {
+                const unsigned long long* c = &ticks[4 * rt.fused_into[v]];
+                ticks[4 * v] = ticks[4 * v + 2] = c[2], ticks[4 * v + 1] = ticks[4 * v + 3] = c[3];
+            }
     }
     if (enable) {
         if (!rt.plan.trace) NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.plan.trace), bytes));
