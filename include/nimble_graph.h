@@ -221,6 +221,11 @@ int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks);
  * index mod 8 share an XCD, which is what the plan's use of XCD-local L2s rests on; 0 if not, in which case every hand-over
  * of the device-resident replay goes through device scope (correct on any mapping, slower). */
 int ng_resident_xcd_mapping(const ng_graph* g, int* verified);
+/* Which nodes the device-resident plan runs inside another node's tiles: host_of[v] (n_nodes entries,
+ * caller-owned host memory) = the convolution whose tiles also apply node v (a batch-norm / ReLU
+ * directly behind it, or an add_n that takes its - possibly batch-normed - result as one operand),
+ * or -1 for a node with workgroups of its own. Needs ng_capture. */
+int ng_resident_fusion(const ng_graph* g, int* host_of);
 /* Host-only rehearsal of the device-resident plan (needs ng_plan_memory, no GPU): plans for
  * n_workgroups persistent workgroups (a multiple of 8) over xcds XCDs (0 = let the cost
  * model choose) and reports the expected makespan in microseconds, the number of

@@ -20,13 +20,30 @@ enum Kid : int {
     KID_BN_R64, KID_BN_R16, KID_ADD_R64, KID_ADD_R16,   // elementwise tasks on the tile grids of those two (resident replay)
     KID_C3_M1, KID_C3_M2, KID_C3_M3, KID_C3_M4,   // conv3x3 as an implicit GEMM on the matrix cores, 16 x 16 output tile
     KID_POOL_P4, KID_DW_K3S1_P4,     // windowed kernels with 4 outputs per thread (resident replay)
+    // the 16-row convolutions with an add_n applied to their result before it is stored (resident replay)
+    KID_PW_V1A, KID_PW_V2A, KID_PW_V3A, KID_PW_V4A, KID_PW_S1A, KID_PW_S2A, KID_PW_S3A, KID_PW_S4A,
+    KID_C3_M1A, KID_C3_M2A, KID_C3_M3A, KID_C3_M4A,
     KID_COUNT
 };
+
+// the variant without / with a fused add_n of a 16-row convolution kernel (other ids map to themselves / KID_NONE)
+constexpr int plain_variant(int kid) {
+    return (kid >= KID_PW_V1A && kid <= KID_PW_S4A) ? kid - KID_PW_V1A + KID_PW_V1
+                                                    : (kid >= KID_C3_M1A && kid <= KID_C3_M4A) ? kid - KID_C3_M1A + KID_C3_M1 : kid;
+}
+constexpr int add_variant(int kid) {
+    return (kid >= KID_PW_V1 && kid <= KID_PW_S4) ? kid - KID_PW_V1 + KID_PW_V1A
+                                                  : (kid >= KID_C3_M1 && kid <= KID_C3_M4) ? kid - KID_C3_M1 + KID_C3_M1A : KID_NONE;
+}
+constexpr bool is_pw16(int kid) { return plain_variant(kid) >= KID_PW_V1 && plain_variant(kid) <= KID_PW_S4; }
+constexpr bool is_c3m(int kid) { return plain_variant(kid) >= KID_C3_M1 && plain_variant(kid) <= KID_C3_M4; }
+constexpr bool has_add_epilogue(int kid) { return plain_variant(kid) != kid; }
 
 // How a kernel splits its output into tiles (see the elementwise tile functions): only tasks
 // with the same partition of same-shaped outputs have matching tiles.
 enum { PART_NONE = -1, PART_L256 = 0, PART_L1024 = 1, PART_R64 = 2, PART_R16 = 3 };
-constexpr int partition_of(int kid) {
+constexpr int partition_of(int kid_any) {
+    const int kid = plain_variant(kid_any);
     return (kid == KID_BN || kid == KID_ADD || kid == KID_CONCAT || kid == KID_POOL || kid == KID_DW_K3S1 ||
             kid == KID_DW_K3S2 || kid == KID_DW_K5S1 || kid == KID_DW_K5S2)
                ? PART_L256
@@ -41,7 +58,8 @@ constexpr int partition_of(int kid) {
 }
 
 // kernels whose tiles keep a compute unit's memory pipeline or matrix cores busy for a while
-constexpr bool is_matrix_kernel(int kid) {
+constexpr bool is_matrix_kernel(int kid_any) {
+    const int kid = plain_variant(kid_any);
     return (kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || (kid >= KID_PW_V1 && kid <= KID_PW_S4) || (kid >= KID_C3_M1 && kid <= KID_C3_M4);
 }
 
@@ -126,6 +144,19 @@ struct Epilogue {
     int relu;
 };
 
+// Optional third result: the add_n task that takes the (batch-normed) convolution result as one
+// operand. The other operands come from other tasks; the tile waits for them only now (the
+// entry's late parents), adds in argument order and stores. y == nullptr: none.
+constexpr int kEpilogueAddMax = 4;           // operands of an add_n that can be fused
+struct AddEpilogue {
+    const float* x[kEpilogueAddMax - 1];     // the operands that are read, in argument order
+    float* y;
+    int k;                                   // operands in all, 2..kEpilogueAddMax
+    int zpos;                                // argument position of the value held in registers
+    int far;                                 // != 0: read the operands with device-scope loads
+    int pad_;
+};
+
 struct PwArgs {
     const float* x;            // [N][Cin][HW]
     const float* w;            // [Cout][Cin]
@@ -138,6 +169,9 @@ struct PwArgs {
                                // 16-row kernels: groups of 4 k-steps in the packed copy (a multiple of 4 * groups in flight)
     int mtiles;                // direct kernels: ceil(Cout / 16)
     Epilogue ep;               // 16-row kernels only
+};
+struct PwAddArgs : PwArgs {
+    AddEpilogue ea;            // applied to the batch-normed value when ep.y is set, else to the convolution result
 };
 
 struct C3Args {
@@ -157,7 +191,10 @@ struct C3Args {
     int tiles_n;               // ceil(cols / 16)
     Epilogue ep;               // implicit-GEMM kernels only
 };
-static_assert(sizeof(PwArgs) <= 48 * 4 && sizeof(C3Args) <= 48 * 4, "argument block the resident kernel prefetches");
+struct C3AddArgs : C3Args {
+    AddEpilogue ea;
+};
+static_assert(sizeof(PwAddArgs) <= 48 * 4 && sizeof(C3AddArgs) <= 48 * 4, "argument block the resident kernel prefetches");
 
 // ---- device-resident replay: the task schedule as data in device memory -------------------
 constexpr int kArgWords = 48;        // words of the argument block the resident kernel prefetches
@@ -180,7 +217,7 @@ struct DevTask {
     // bit 2 with bit 1: in two levels (per XCD, then device scope)
     unsigned publish;
     unsigned parent_far;             // bit j: parent j is awaited through its device-scope counter
-    unsigned pad_[1];
+    unsigned n_late;                 // the last n_late parents are awaited inside the tile function (operands of a fused add_n)
     alignas(16) unsigned char args[kArgBytes];
 };
 
@@ -203,7 +240,8 @@ struct DevRecord {
     int flags;                                   // bit 0: device-scope loads of activations, bit 1: device-scope stores of the result,
                                                  // bit 2 / 3: bump the XCD-local / the device-scope completion counter,
                                                  // bit 4: two-level completion - bump a per-XCD counter, the last one of the
-                                                 // XCD bumps the device-scope counter (tasks spread over several XCDs)
+                                                 // XCD bumps the device-scope counter (tasks spread over several XCDs),
+                                                 // bits 8-15: how many of the parents (the last ones) are awaited late
     int subs;                                    // bits 0-7: sub-blocks that take a tile each per round (the others idle), 1..kSubs;
                                                  // bits 8-31: two-level completion (flags bit 4): workgroups of the task on this XCD
     int parent[NG_MAX_PREDS];                    // bit 31: wait on the parent's device-scope counter

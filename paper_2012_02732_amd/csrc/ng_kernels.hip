@@ -117,9 +117,33 @@ __global__ __launch_bounds__(kBlock) void fold_bn_kernel(const float* gamma, con
 // reading weights and coefficients - goes before the call, so that it overlaps with waiting
 // for the producers. Stand-alone kernels pass NoWait; the resident kernel passes the wait
 // for the task's completion counters, which does its work on the first call only.
+// A convolution tile with a fused add_n calls `late` the same way, once, before it reads the
+// other operands of the sum.
 struct NoWait {
     __device__ __forceinline__ void operator()() const {}
+    __device__ __forceinline__ void late() const {}
 };
+
+// The add_n epilogue of a convolution tile: v holds this lane's values (4 consecutive pixels if
+// VEC, else one), `at` their position in the tensors; the sum runs in argument order.
+template <bool VEC, bool FOUT>
+__device__ __forceinline__ void add_epilogue(const AddEpilogue& ea, float4 v, size_t at) {
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int j = 0; j < kEpilogueAddMax; ++j) {               // constant indices only: the argument block stays in scalar registers
+        if (j >= ea.k) break;
+        float4 t = v;
+        if (j != ea.zpos) {
+            const float* x = j > ea.zpos ? ea.x[j > 0 ? j - 1 : 0] : ea.x[j < kEpilogueAddMax - 1 ? j : kEpilogueAddMax - 2];
+            if (VEC) t = ldg4(x, x + at, ea.far != 0);
+            else t.x = ldg(x, x + at, ea.far != 0);
+        }
+        if (j == 0) acc = t;
+        else acc.x += t.x, acc.y += t.y, acc.z += t.z, acc.w += t.w;
+    }
+    if (VEC) stg4(ea.y, ea.y + at, acc, FOUT);
+    else stg(ea.y, ea.y + at, acc.x, FOUT);
+}
 
 // Elementwise operators come in four partitions of the output into tiles, so that an
 // elementwise task can take over the partition of the task that feeds it (then tile i of
@@ -618,8 +642,9 @@ __global__ __launch_bounds__(kBlock) void pack_pw_weights_k4_kernel(const float*
     wp[i] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
 }
 
-template <int G, bool VEC, bool FIN, bool FOUT, class Wait>
-__device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+template <int G, bool VEC, bool EA, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void conv1x1_k4_tile(const typename std::conditional<EA, PwAddArgs, PwArgs>::type& a, int tile, float* smem,
+                                                int tid, bool live, Wait& wait) {
     constexpr int NJ = VEC ? 4 : 1;                          // MFMA tiles per wavefront
     constexpr int TN = VEC ? 64 : 16;                        // columns per workgroup tile
     static_assert(4 * NJ * 4 * 64 <= kSmemFloats, "LDS budget");
@@ -680,6 +705,9 @@ __device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float
             for (int r = 0; r < 4; ++r) smem[((wave * NJ + j) * 4 + r) * 64 + lane] = acc[j][r];
     }
     __syncthreads();
+    bool valid = false;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    size_t at = 0;
     if (live) {
         float out[NJ];
 #pragma unroll
@@ -689,11 +717,12 @@ __device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float
             for (int w2 = 1; w2 < 4; ++w2) sum += smem[((w2 * NJ + j) * 4 + wave) * 64 + lane];
             out[j] = sum;
         }
-        if (m < a.Cout && colv < a.cols) {                   // VEC: cols is a multiple of 4, a lane's 4 columns are all in or all out
+        valid = m < a.Cout && colv < a.cols;                 // VEC: cols is a multiple of 4, a lane's 4 columns are all in or all out
+        if (valid) {
             const float b = a.bias ? a.bias[m] : 0.f;
             const int img = colv / a.HW, pix = colv - img * a.HW;
-            const size_t at = ((size_t)img * a.Cout + m) * a.HW + pix;
-            float4 v = make_float4(out[0] + b, out[NJ > 1 ? 1 : 0] + b, out[NJ > 2 ? 2 : 0] + b, out[NJ > 3 ? 3 : 0] + b);
+            at = ((size_t)img * a.Cout + m) * a.HW + pix;
+            v = make_float4(out[0] + b, out[NJ > 1 ? 1 : 0] + b, out[NJ > 2 ? 2 : 0] + b, out[NJ > 3 ? 3 : 0] + b);
             if (VEC) stg4(a.y, a.y + at, v, FOUT);
             else stg(a.y, a.y + at, v.x, FOUT);
             if (a.ep.y != nullptr) {
@@ -703,6 +732,10 @@ __device__ __forceinline__ void conv1x1_k4_tile(const PwArgs& a, int tile, float
                 else stg(a.ep.y, a.ep.y + at, v.x, FOUT);
             }
         }
+    }
+    if constexpr (EA) {
+        wait.late();
+        if (valid) add_epilogue<VEC, FOUT>(a.ea, v, at);
     }
     __syncthreads();                                         // LDS is reused by the next tile
 }
@@ -803,8 +836,9 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
 // over the four wavefronts in groups of 4 k-steps, G groups in flight, fixed-order reduction.
 // A lane walks k in steps of 4, so (ci, tap) is updated incrementally: tap += 4, carry into ci.
 // ------------------------------------------------------------------------------------
-template <int G, bool FIN, bool FOUT, class Wait>
-__device__ __forceinline__ void conv3x3_k4_tile(const C3Args& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+template <int G, bool EA, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void conv3x3_k4_tile(const typename std::conditional<EA, C3AddArgs, C3Args>::type& a, int tile, float* smem,
+                                                int tid, bool live, Wait& wait) {
     static_assert(4 * 4 * 64 <= kSmemFloats, "LDS budget");
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -859,19 +893,29 @@ __device__ __forceinline__ void conv3x3_k4_tile(const C3Args& a, int tile, float
         for (int r = 0; r < 4; ++r) smem[(wave * 4 + r) * 64 + lane] = acc[r];
     }
     __syncthreads();
+    bool valid = false;
+    float z = 0.f;
+    size_t at = 0;
     if (live) {
         float sum = smem[(0 * 4 + wave) * 64 + lane];
 #pragma unroll
         for (int w2 = 1; w2 < 4; ++w2) sum += smem[(w2 * 4 + wave) * 64 + lane];
-        if (m < a.Cout && colv < a.cols) {
+        valid = m < a.Cout && colv < a.cols;
+        if (valid) {
             const int img = colv / HWo, pix = colv - img * HWo;
-            const size_t at = ((size_t)img * a.Cout + m) * HWo + pix;
+            at = ((size_t)img * a.Cout + m) * HWo + pix;
             stg(a.y, a.y + at, sum, FOUT);
+            z = sum;
             if (a.ep.y != nullptr) {
-                const float z = fmaf(sum, es, et);
-                stg(a.ep.y, a.ep.y + at, a.ep.relu ? fmaxf(z, 0.f) : z, FOUT);
+                z = fmaf(sum, es, et);
+                if (a.ep.relu) z = fmaxf(z, 0.f);
+                stg(a.ep.y, a.ep.y + at, z, FOUT);
             }
         }
+    }
+    if constexpr (EA) {
+        wait.late();
+        if (valid) add_epilogue<false, FOUT>(a.ea, make_float4(z, 0.f, 0.f, 0.f), at);
     }
     __syncthreads();                                         // LDS is reused by the next tile
 }
@@ -912,22 +956,34 @@ NG_KERNEL(KID_PW_D4, PwArgs, "conv1x1_mfma_d4", conv1x1_direct_tile < 4)
 NG_KERNEL(KID_PW_D8, PwArgs, "conv1x1_mfma_d8", conv1x1_direct_tile < 8)
 NG_KERNEL(KID_PW_D16, PwArgs, "conv1x1_mfma_d16", conv1x1_direct_tile < 16)
 NG_KERNEL(KID_PW_64, PwArgs, "conv1x1_mfma_64x64", conv1x1_mfma_tile < 64, 64, 16)
-NG_KERNEL(KID_PW_V1, PwArgs, "conv1x1_v1", conv1x1_k4_tile < 1, true)
-NG_KERNEL(KID_PW_V2, PwArgs, "conv1x1_v2", conv1x1_k4_tile < 2, true)
-NG_KERNEL(KID_PW_V3, PwArgs, "conv1x1_v3", conv1x1_k4_tile < 3, true)
-NG_KERNEL(KID_PW_V4, PwArgs, "conv1x1_v4", conv1x1_k4_tile < 4, true)
-NG_KERNEL(KID_PW_S1, PwArgs, "conv1x1_s1", conv1x1_k4_tile < 1, false)
-NG_KERNEL(KID_PW_S2, PwArgs, "conv1x1_s2", conv1x1_k4_tile < 2, false)
-NG_KERNEL(KID_PW_S3, PwArgs, "conv1x1_s3", conv1x1_k4_tile < 3, false)
-NG_KERNEL(KID_PW_S4, PwArgs, "conv1x1_s4", conv1x1_k4_tile < 4, false)
+NG_KERNEL(KID_PW_V1, PwArgs, "conv1x1_v1", conv1x1_k4_tile < 1, true, false)
+NG_KERNEL(KID_PW_V2, PwArgs, "conv1x1_v2", conv1x1_k4_tile < 2, true, false)
+NG_KERNEL(KID_PW_V3, PwArgs, "conv1x1_v3", conv1x1_k4_tile < 3, true, false)
+NG_KERNEL(KID_PW_V4, PwArgs, "conv1x1_v4", conv1x1_k4_tile < 4, true, false)
+NG_KERNEL(KID_PW_S1, PwArgs, "conv1x1_s1", conv1x1_k4_tile < 1, false, false)
+NG_KERNEL(KID_PW_S2, PwArgs, "conv1x1_s2", conv1x1_k4_tile < 2, false, false)
+NG_KERNEL(KID_PW_S3, PwArgs, "conv1x1_s3", conv1x1_k4_tile < 3, false, false)
+NG_KERNEL(KID_PW_S4, PwArgs, "conv1x1_s4", conv1x1_k4_tile < 4, false, false)
 NG_KERNEL(KID_C3_T16S1, C3Args, "conv3x3_t16s1", conv3x3_tile < 16, 1)
 NG_KERNEL(KID_C3_T16S2, C3Args, "conv3x3_t16s2", conv3x3_tile < 16, 2)
 NG_KERNEL(KID_C3_T8S1, C3Args, "conv3x3_t8s1", conv3x3_tile < 8, 1)
 NG_KERNEL(KID_C3_T8S2, C3Args, "conv3x3_t8s2", conv3x3_tile < 8, 2)
-NG_KERNEL(KID_C3_M1, C3Args, "conv3x3_mfma_1", conv3x3_k4_tile < 1)
-NG_KERNEL(KID_C3_M2, C3Args, "conv3x3_mfma_2", conv3x3_k4_tile < 2)
-NG_KERNEL(KID_C3_M3, C3Args, "conv3x3_mfma_3", conv3x3_k4_tile < 3)
-NG_KERNEL(KID_C3_M4, C3Args, "conv3x3_mfma_4", conv3x3_k4_tile < 4)
+NG_KERNEL(KID_C3_M1, C3Args, "conv3x3_mfma_1", conv3x3_k4_tile < 1, false)
+NG_KERNEL(KID_C3_M2, C3Args, "conv3x3_mfma_2", conv3x3_k4_tile < 2, false)
+NG_KERNEL(KID_C3_M3, C3Args, "conv3x3_mfma_3", conv3x3_k4_tile < 3, false)
+NG_KERNEL(KID_C3_M4, C3Args, "conv3x3_mfma_4", conv3x3_k4_tile < 4, false)
+NG_KERNEL(KID_PW_V1A, PwAddArgs, "conv1x1_v1_add", conv1x1_k4_tile < 1, true, true)
+NG_KERNEL(KID_PW_V2A, PwAddArgs, "conv1x1_v2_add", conv1x1_k4_tile < 2, true, true)
+NG_KERNEL(KID_PW_V3A, PwAddArgs, "conv1x1_v3_add", conv1x1_k4_tile < 3, true, true)
+NG_KERNEL(KID_PW_V4A, PwAddArgs, "conv1x1_v4_add", conv1x1_k4_tile < 4, true, true)
+NG_KERNEL(KID_PW_S1A, PwAddArgs, "conv1x1_s1_add", conv1x1_k4_tile < 1, false, true)
+NG_KERNEL(KID_PW_S2A, PwAddArgs, "conv1x1_s2_add", conv1x1_k4_tile < 2, false, true)
+NG_KERNEL(KID_PW_S3A, PwAddArgs, "conv1x1_s3_add", conv1x1_k4_tile < 3, false, true)
+NG_KERNEL(KID_PW_S4A, PwAddArgs, "conv1x1_s4_add", conv1x1_k4_tile < 4, false, true)
+NG_KERNEL(KID_C3_M1A, C3AddArgs, "conv3x3_mfma_1_add", conv3x3_k4_tile < 1, true)
+NG_KERNEL(KID_C3_M2A, C3AddArgs, "conv3x3_mfma_2_add", conv3x3_k4_tile < 2, true)
+NG_KERNEL(KID_C3_M3A, C3AddArgs, "conv3x3_mfma_3_add", conv3x3_k4_tile < 3, true)
+NG_KERNEL(KID_C3_M4A, C3AddArgs, "conv3x3_mfma_4_add", conv3x3_k4_tile < 4, true)
 #undef NG_KERNEL
 // kernels without further template arguments
 #define NG_KERNEL0(KID, ARGS, NAME, FN)                                                        \
@@ -1001,56 +1057,80 @@ __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int s
 // contract. The first call does the work: lane j of the first wavefront polls parent j, then
 // the compute unit's L1 is dropped and the workgroup meets at a barrier. Later calls (further
 // tiles of the same entry) return at once.
+// The polling loop of one lane.
+// 0: the counter has reached the target; 1: it has not (`once`: after a single look, otherwise because
+// another wait in the grid gave up); 2: ran out of spins.
+#ifndef NG_SPIN_INLINE
+#define NG_SPIN_INLINE __forceinline__
+#endif
+__device__ NG_SPIN_INLINE int spin_until(unsigned* counter, unsigned target, bool far, bool once, unsigned spin_limit,
+                                                    int* error_dev, int poll_sleep) {
+    unsigned spins = 0;
+    for (;;) {
+        unsigned seen;
+        if (far) {
+            seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            // read the counter where it lives, in this XCD's L2: a compare-and-swap that can
+            // never match returns the current value (a plain load could be served by a stale
+            // L1 line, and an atomic add of 0 is folded into such a load by the compiler)
+            seen = 0xFFFFFFFFu;
+            __hip_atomic_compare_exchange_strong(counter, &seen, 0xFFFFFFFFu, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
+        }
+        if ((int)(seen - target) >= 0) return 0;
+        if (once) return 1;
+        if (++spins > spin_limit) return 2;
+        if ((spins & 63u) == 0 && __hip_atomic_load(error_dev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) return 1;
+        if (poll_sleep == 0) __builtin_amdgcn_s_sleep(1);
+        else if (poll_sleep == 1) __builtin_amdgcn_s_sleep(4);
+        else __builtin_amdgcn_s_sleep(16);
+    }
+}
+
+template <bool LATE>                 // LATE: the entry may have late parents (kernels with a fused add_n)
 struct CounterWait {
     const DevPlan& plan;
     const unsigned* rec;             // the entry's record in LDS
     int* s_abort;
+    int* s_late;                     // LDS flag: the late parents were already complete at the first wait
     unsigned epoch;
-    int task, np, lane;
+    int task, np, n_late, lane;      // np parents in all, the last n_late of them awaited by `late`
     unsigned long long* stamp;       // this entry's three clock readings when tracing, else nullptr (same for all lanes)
-    bool pending;
+    bool pending, late_pending;
+
+    // Lane j of the first wavefront (first <= j < last) polls parent j until its counter has reached this
+    // replay's target (`once`: looks a single time); true if it has. Other lanes return true.
+    __device__ __forceinline__ bool poll(int first, int last, bool once) {
+        bool ok = true;
+        if (lane >= first && lane < last) {
+            const unsigned target = rec[16 + lane] * epoch;
+            const unsigned pw = rec[8 + lane];
+            const bool far = (pw >> 31) != 0;
+            unsigned* counter = (far ? plan.done : plan.done_near) + (size_t)(pw & 0x7fffffffu) * plan.done_stride;
+            const int status = spin_until(counter, target, far, once, plan.spin_limit, plan.error_dev, plan.poll_sleep);
+            ok = status == 0;
+            if (status == 2) {
+                atomicExch(plan.error_dev, task + 1);
+                *plan.error_host = task + 1;
+            }
+        }
+        return ok;
+    }
 
     __device__ __forceinline__ void operator()() {
         if (!pending) return;
         pending = false;
         if (np > 0) {
             if (lane < 64) {                                    // first wavefront: lane j watches parent j
-                bool ok = true;
-                if (lane < np) {
-                    const unsigned target = rec[16 + lane] * epoch;
-                    const unsigned pw = rec[8 + lane];
-                    const bool far = (pw >> 31) != 0;
-                    unsigned* counter = (far ? plan.done : plan.done_near) + (size_t)(pw & 0x7fffffffu) * plan.done_stride;
-                    unsigned spins = 0;
-                    for (;;) {
-                        unsigned seen;
-                        if (far) {
-                            seen = __hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        } else {
-                            // read the counter where it lives, in this XCD's L2: a compare-and-swap that can
-                            // never match returns the current value (a plain load could be served by a stale
-                            // L1 line, and an atomic add of 0 is folded into such a load by the compiler)
-                            seen = 0xFFFFFFFFu;
-                            __hip_atomic_compare_exchange_strong(counter, &seen, 0xFFFFFFFFu, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
-                                                                 __HIP_MEMORY_SCOPE_WORKGROUP);
-                        }
-                        if ((int)(seen - target) >= 0) break;
-                        if (++spins > plan.spin_limit ||
-                            ((spins & 63u) == 0 && __hip_atomic_load(plan.error_dev, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
-                            ok = false;
-                            break;
-                        }
-                        if (plan.poll_sleep == 0) __builtin_amdgcn_s_sleep(1);
-                        else if (plan.poll_sleep == 1) __builtin_amdgcn_s_sleep(4);
-                        else __builtin_amdgcn_s_sleep(16);
-                    }
-                    if (!ok && spins > plan.spin_limit) {
-                        atomicExch(plan.error_dev, task + 1);
-                        *plan.error_host = task + 1;
-                    }
-                }
+                const bool ok = poll(0, np - n_late, false);
                 if (__any(!ok)) {
                     if (lane == 0) *s_abort = 1;
+                }
+                if (LATE && n_late > 0) {                       // usually the late parents are done as well by now
+                    const bool there = poll(np - n_late, np, true);
+                    const bool all_there = !__any(!there);
+                    if (lane == 0) *s_late = all_there ? 1 : 0;
                 }
                 // Make the producers' stores visible to this compute unit. Producers on this
                 // XCD have their results in the shared L2 already: dropping this CU's vector
@@ -1063,6 +1143,21 @@ struct CounterWait {
         }
         if (stamp != nullptr && lane == 0) stamp[1] = wall_clock64();
     }
+
+    // Second wait of an entry whose tiles have a fused add_n: for the producers of the other operands.
+    __device__ __forceinline__ void late() {
+        if (!late_pending) return;
+        late_pending = false;
+        if (!LATE || n_late == 0 || *s_late != 0) return;       // same decision in every thread
+        if (lane < 64) {
+            const bool ok = poll(np - n_late, np, false);
+            if (__any(!ok)) {
+                if (lane == 0) *s_abort = 1;
+            }
+            asm volatile("buffer_inv sc0" ::: "memory");
+        }
+        __syncthreads();
+    }
 };
 
 // FULL = false leaves out the kernels that only large problems use (see is_lean_kernel): their
@@ -1071,7 +1166,7 @@ template <bool FULL>
 __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned epoch) {
     __shared__ float smem_all[kSubs * kSmemFloats];
     __shared__ uint4 recs[kRecordsInLds * (kRecordWords / 4)];
-    __shared__ int s_abort;
+    __shared__ int s_abort, s_late;
     const int lane = threadIdx.x;
     const int sub = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kBlock), tid = (int)threadIdx.x % kBlock;
     float* smem = smem_all + sub * kSmemFloats;
@@ -1095,15 +1190,22 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             const int flags = __builtin_amdgcn_readfirstlane(rec[6]), subs_word = __builtin_amdgcn_readfirstlane(rec[7]);
             const int subs = subs_word & 0xff, xcd_peers = subs_word >> 8;
             const bool far_in = (flags & 1) != 0, far_out = (flags & 2) != 0;
+            const int n_late = (flags >> 8) & 0xff;
             // tracing: thread 0 stamps the clock into this entry's own slot (plain stores, nothing waits for them)
             unsigned long long* stamp = plan.trace != nullptr ? plan.trace + 3 * (size_t)(chunk + e) : nullptr;
             if (stamp != nullptr && lane == 0) stamp[0] = wall_clock64();
             // What the task can do without its inputs (addresses, weights) happens inside the tile
             // function before it calls `wait`; an entry that fails to wait in time still runs its
             // tiles (all accesses stay in bounds) and the workgroup leaves right after.
-            CounterWait wait{plan, rec, &s_abort, epoch, task, np, lane, stamp, true};
+            // (every entry has at least one round of tiles, so the tile function always gets to call the wait)
             switch (kid) {
-#define NG_CASE(KID) case KID: if (FULL || is_lean_kernel(KID)) run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out, wait); break;
+#define NG_CASE(KID)                                                                                                         \
+    case KID:                                                                                                                \
+        if (FULL || is_lean_kernel(KID)) {                                                                                   \
+            CounterWait<has_add_epilogue(KID)> wait{plan, rec, &s_abort, &s_late, epoch, task, np, n_late, lane, stamp, true, true}; \
+            run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out, wait);                      \
+        }                                                                                                                    \
+        break;
                 NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_R64) NG_CASE(KID_BN_R16) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
                 NG_CASE(KID_ADD_R64) NG_CASE(KID_ADD_R16)
                 NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_POOL_P4) NG_CASE(KID_DW_K3S1_P4) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
@@ -1112,10 +1214,11 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                 NG_CASE(KID_PW_V3) NG_CASE(KID_PW_V4) NG_CASE(KID_PW_S1) NG_CASE(KID_PW_S2) NG_CASE(KID_PW_S3) NG_CASE(KID_PW_S4) NG_CASE(KID_C3_T16S1)
                 NG_CASE(KID_C3_T16S2) NG_CASE(KID_C3_T8S1) NG_CASE(KID_C3_T8S2) NG_CASE(KID_C3_M1) NG_CASE(KID_C3_M2)
                 NG_CASE(KID_C3_M3) NG_CASE(KID_C3_M4)
+                NG_CASE(KID_PW_V1A) NG_CASE(KID_PW_V2A) NG_CASE(KID_PW_V3A) NG_CASE(KID_PW_V4A) NG_CASE(KID_PW_S1A) NG_CASE(KID_PW_S2A)
+                NG_CASE(KID_PW_S3A) NG_CASE(KID_PW_S4A) NG_CASE(KID_C3_M1A) NG_CASE(KID_C3_M2A) NG_CASE(KID_C3_M3A) NG_CASE(KID_C3_M4A)
 #undef NG_CASE
                 default: break;
             }
-            wait();                      // an entry without tiles for this workgroup has not waited yet
             __syncthreads();             // every thread's stores have reached L2 (write-through L1, counted stores)
             if (s_abort) return;
             if (stamp != nullptr && lane == 0) stamp[2] = wall_clock64();

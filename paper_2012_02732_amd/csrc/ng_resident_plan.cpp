@@ -56,7 +56,8 @@ constexpr double kFarRunFactor = 1.2; // a tile whose loads and stores all go th
 // stores) plus a throughput part per tile (load issue and data return of the compute
 // unit's one memory pipeline, matrix-core time of wavefronts that share a SIMD). Figures
 // from traces of the resident kernel; the planner only needs them to be ordered sensibly.
-double tile_round_us(const ng_graph* g, int v, int kid, int subs) {
+double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
+    const int kid = plain_variant(kid_any);
     const Node& nd = g->nodes[v];
     const double cin = nd.preds.empty() ? 0.0 : (double)g->nodes[nd.preds[0]].out.c;
     double base = 1.0, per_tile = 0.1;
@@ -126,7 +127,7 @@ struct Sim {
     std::vector<int> subs;           // sub-blocks per workgroup that take a tile each
     std::vector<int> order;          // tasks in the order they were placed: every workgroup's list follows it
     std::vector<int> local_parent;   // E' parent whose completion this task does not wait for (same workgroups, same tiles), or -1
-    std::vector<int> fused_into;     // convolution whose tiles also produce this (batch-norm / ReLU) task's result, or -1
+    std::vector<int> fused_into;     // convolution whose tiles also produce this (batch-norm / ReLU / add_n) task's result, or -1
     double makespan = 0;
 };
 
@@ -199,11 +200,15 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     for (int v = 0; v < n; ++v)
         if (g->tasks[v].fn && waiting[v] == 0) open.push(Key(0.0, -tail[v], v));
     out.order.clear();
-    std::vector<char> fused_child(n, 0);                        // the convolution already carries an epilogue
+    std::vector<char> fused_child(n, 0);                        // the convolution already carries a batch-norm epilogue
+    std::vector<char> add_child(n, 0);                          // ... an add_n epilogue
+    std::vector<int> placed_at(n, -1);                          // position in out.order
+    const bool allow_fuse_add = allow_fuse && getenv("NG_NO_FUSE_ADD") == nullptr;
 
     while (!open.empty()) {
         const int v = std::get<2>(open.top());
         open.pop();
+        placed_at[v] = (int)out.order.size();
         out.order.push_back(v);
         const Task& t = g->tasks[v];
         const int home = stream_xcd[sc.stream_of[v]];
@@ -223,8 +228,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             parents[v].size() == 1 && g->nodes[v].preds.size() == 1 && parents[v][0] == g->nodes[v].preds[0]) {
             const int u = parents[v][0];
             long nt = 0;
-            const bool conv16 = g->tasks[u].fn && ((out.kid[u] >= KID_PW_V1 && out.kid[u] <= KID_PW_S4) ||
-                                                   (out.kid[u] >= KID_C3_M1 && out.kid[u] <= KID_C3_M4));
+            const bool conv16 = g->tasks[u].fn && (is_pw16(out.kid[u]) || is_c3m(out.kid[u]));
             if (conv16 && !fused_child[u] && g->nodes[u].out == g->nodes[v].out &&
                 variant_for(g, v, partition_of(out.kid[u]), &nt) != KID_NONE && nt == out.ntiles[u]) {
                 fused_child[u] = 1;
@@ -240,6 +244,63 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
                 finish[v] = finish[u] + kFusedUs;
                 out.makespan = std::max(out.makespan, finish[v]);
                 if (debug) fprintf(stderr, "PLAN nx=%d v=%d fused into %d finish=%.2f\n", nx, v, u, finish[v]);
+                for (int c : children[v])
+                    if (--waiting[c] == 0) open.push(Key(ready_time(c), -tail[c], c));
+                continue;
+            }
+        }
+        // An add_n with one operand that is such a convolution result (raw or batch-normed) and is
+        // read by nobody else goes the same way: the convolution's tiles wait for the producers
+        // of the other operands once their own sums are done, add and store. Those producers
+        // must come before the convolution in the common order of the lists (waits only point
+        // backwards), which is the case when the convolution is the later branch - the case
+        // in which the fused add_n saves a hand-over on the critical path.
+        if (allow_fuse_add && allow_local && g->nodes[v].op == NG_OP_ADD_N && g->nodes[v].preds.size() >= 2 &&
+            g->nodes[v].preds.size() <= (size_t)kEpilogueAddMax) {
+            const std::vector<int>& preds = g->nodes[v].preds;
+            int host = -1, via = -1;
+            for (int w : parents[v]) {
+                const int u = out.fused_into[w] >= 0 ? out.fused_into[w] : w;
+                if (!g->tasks[u].fn || add_child[u]) continue;
+                if (g->nodes[w].op == NG_OP_ADD_N) continue;                               // w must be the convolution or its batch-norm
+                const bool conv16 = is_pw16(out.kid[u]) || is_c3m(out.kid[u]);
+                if (!conv16 || (w == u && fused_child[u])) continue;
+                // nobody else reads the convolution or its batch-norm, and the value is one operand exactly once
+                if (children[u].size() != 1 || children[w].size() != 1 || children[w][0] != v) continue;
+                if (std::count(preds.begin(), preds.end(), w) != 1 || (w != u && std::count(preds.begin(), preds.end(), u) != 0)) continue;
+                long nt = 0;
+                if (!(g->nodes[u].out == g->nodes[v].out) || variant_for(g, v, partition_of(out.kid[u]), &nt) == KID_NONE || nt != out.ntiles[u]) continue;
+                bool before = true;
+                for (int p : parents[v])
+                    if (p != w && g->tasks[p].fn) before = before && placed_at[p] >= 0 && placed_at[p] < placed_at[u];
+                if (!before || parents[u].size() + parents[v].size() - 1 > (size_t)NG_MAX_PREDS) continue;
+                host = u, via = w;
+                break;
+            }
+            if (host >= 0) {
+                long nt = 0;
+                add_child[host] = 1;
+                out.kid[host] = add_variant(out.kid[host]);          // the kernel variant that has the add_n at its end
+                out.fused_into[v] = host;
+                out.local_parent[v] = via;
+                out.kid[v] = variant_for(g, v, partition_of(out.kid[host]), &nt);
+                out.ntiles[v] = nt;
+                out.subs[v] = out.subs[host];
+                out.xcd[v] = out.xcd[host];
+                wgs[v] = wgs[host];
+                out.parts[v] = out.parts[host];
+                out.signals[v] = out.signals[host];
+                double ready = finish[host];
+                for (int p : parents[v]) {
+                    if (p == via || !g->tasks[p].fn) continue;
+                    const bool far = out.xcd[p] < 0 || out.xcd[host] < 0 || out.xcd[p] != out.xcd[host] || g->resident_all_far;
+                    ready = std::max(ready, finish[p] + kSyncNearUs + (far ? kSyncFarUs : 0.0));
+                }
+                finish[v] = ready + kFusedUs;
+                if (finish[v] > finish[host] + kFusedUs)                 // the convolution's workgroups sit in the late wait
+                    for (int w : wgs[host]) free_at[w] = std::max(free_at[w], finish[v] + kPublishUs);
+                out.makespan = std::max(out.makespan, finish[v]);
+                if (debug) fprintf(stderr, "PLAN nx=%d v=%d add fused into %d via %d finish=%.2f\n", nx, v, host, via, finish[v]);
                 for (int c : children[v])
                     if (--waiting[c] == 0) open.push(Key(ready_time(c), -tail[c], c));
                 continue;
@@ -419,29 +480,50 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     for (int v = 0; v < n; ++v) {
         const int u = best.fused_into[v];
         if (u < 0) continue;
-        const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
-        Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};
-        const bool c3 = best.kid[u] >= KID_C3_M1 && best.kid[u] <= KID_C3_M4;
-        if (c3) reinterpret_cast<C3Args*>(plan.tasks[u].args)->ep = ep;
-        else reinterpret_cast<PwArgs*>(plan.tasks[u].args)->ep = ep;
-        plan.tasks[u].release_far |= plan.tasks[v].release_far;   // both results are stored the same way
+        const bool c3 = is_c3m(best.kid[u]);
+        if (g->nodes[v].op == NG_OP_ADD_N) {
+            const AddArgs* add = reinterpret_cast<const AddArgs*>(g->tasks[v].args);
+            AddEpilogue ea{};
+            ea.y = add->y, ea.k = add->k, ea.zpos = -1, ea.far = plan.tasks[v].far_in != 0 ? 1 : 0;
+            int q = 0;
+            for (int j = 0; j < add->k; ++j) {
+                if (g->nodes[v].preds[j] == best.local_parent[v]) ea.zpos = j;
+                else if (q < kEpilogueAddMax - 1) ea.x[q++] = add->x[j];
+            }
+            if (ea.zpos < 0 || q != add->k - 1) return NG_EINVAL;
+            if (!has_add_epilogue(best.kid[u])) return NG_EINVAL;
+            if (c3) reinterpret_cast<C3AddArgs*>(plan.tasks[u].args)->ea = ea;
+            else reinterpret_cast<PwAddArgs*>(plan.tasks[u].args)->ea = ea;
+        } else {
+            const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
+            Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};
+            if (c3) reinterpret_cast<C3Args*>(plan.tasks[u].args)->ep = ep;
+            else reinterpret_cast<PwArgs*>(plan.tasks[u].args)->ep = ep;
+        }
+        plan.tasks[u].release_far |= plan.tasks[v].release_far;   // all results of a tile are stored the same way
     }
-    for (auto& e : sc.meg) {
-        if (!g->tasks[e.first].fn || !g->tasks[e.second].fn) continue;
-        if (best.local_parent[e.second] == e.first) continue;   // handed over inside the workgroups
-        const int src = best.fused_into[e.first] >= 0 ? best.fused_into[e.first] : e.first;   // who really produces it
-        DevTask& d = plan.tasks[e.second];
-        if (d.n_parents >= NG_MAX_PREDS) return NG_EINVAL;
-        d.parent[d.n_parents] = src;
-        d.need[d.n_parents] = best.signals[src];
-        // producer and consumer on the same single XCD: the completion is signalled through that XCD's L2
-        const bool near = best.xcd[src] >= 0 && best.xcd[src] == best.xcd[e.second] && !g->resident_all_far &&
-                          !getenv("NG_NO_NEAR_COUNTERS");
-        if (near) plan.tasks[src].publish |= 1u;
-        else plan.tasks[src].publish |= 2u, d.parent_far |= 1u << d.n_parents;
-        if (!near && best.signals[src] != best.parts[src]) plan.tasks[src].publish |= 4u;
-        ++d.n_parents;
-    }
+    // who waits for whom: first what every entry awaits before it starts, then (pass 1) the producers of
+    // the other operands of a fused add_n, which its convolution awaits late
+    for (int pass = 0; pass < 2; ++pass)
+        for (auto& e : sc.meg) {
+            if (!g->tasks[e.first].fn || !g->tasks[e.second].fn) continue;
+            if (best.local_parent[e.second] == e.first) continue;   // handed over inside the workgroups
+            const int src = best.fused_into[e.first] >= 0 ? best.fused_into[e.first] : e.first;   // who really produces it
+            const int dst = best.fused_into[e.second] >= 0 ? best.fused_into[e.second] : e.second; // whose entries wait for it
+            if ((dst != e.second) != (pass == 1)) continue;
+            DevTask& d = plan.tasks[dst];
+            if (d.n_parents >= NG_MAX_PREDS) return NG_EINVAL;
+            d.parent[d.n_parents] = src;
+            d.need[d.n_parents] = best.signals[src];
+            // producer and consumer on the same single XCD: the completion is signalled through that XCD's L2
+            const bool near = best.xcd[src] >= 0 && best.xcd[src] == best.xcd[dst] && !g->resident_all_far &&
+                              !getenv("NG_NO_NEAR_COUNTERS");
+            if (near) plan.tasks[src].publish |= 1u;
+            else plan.tasks[src].publish |= 2u, d.parent_far |= 1u << d.n_parents;
+            if (!near && best.signals[src] != best.parts[src]) plan.tasks[src].publish |= 4u;
+            ++d.n_parents;
+            if (pass == 1) ++d.n_late;
+        }
     plan.entries.clear();
     plan.wg_first.assign(n_wg + 1, 0);
     for (int w = 0; w < n_wg; ++w) {
@@ -505,7 +587,8 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
             int last = -1;
             for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
                 const DevEntry& en = plan.entries[e];
-                ok = ok && pos[en.task] > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step;
+                ok = ok && pos[en.task] > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step &&
+                     en.tile_begin < units_of(en.task);       // at least one round of tiles: the entry's wait is inside its tile function
                 last = pos[en.task];
                 ++parts[en.task];
                 where[en.task].insert(where[en.task].end(), {(long)w, (long)en.tile_begin, (long)en.tile_step, (long)en.subs});
@@ -533,24 +616,53 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
             }
         }
         int n_local = 0, n_fused = 0;
+        std::vector<int> fused_bns(n, 0), fused_adds(n, 0);
         for (size_t v = 0; v < n; ++v) {
             if (!g->tasks[v].fn) continue;
             const int host = plan.fused_into[v];
             if (host >= 0) {
-                // a fused batch-norm has no entries and no waits of its own; its convolution covers the same
-                // tile grid, comes earlier in the order and carries its coefficients and output address
+                // a fused task has no entries and no waits of its own; its convolution covers the same tile
+                // grid, comes earlier in the order and carries its coefficients / operands and output address
                 ++n_fused;
                 const int hk = plan.tasks[host].kid;
-                const bool c3 = hk >= KID_C3_M1 && hk <= KID_C3_M4, pw = hk >= KID_PW_V1 && hk <= KID_PW_S4;
+                const bool c3 = is_c3m(hk), pw = is_pw16(hk);
                 const Epilogue* ep = c3 ? &reinterpret_cast<const C3Args*>(plan.tasks[host].args)->ep
                                         : &reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->ep;
-                const BnArgs* bn = reinterpret_cast<const BnArgs*>(plan.tasks[v].args);
+                const AddEpilogue* ea = c3 ? &reinterpret_cast<const C3AddArgs*>(plan.tasks[host].args)->ea
+                                           : &reinterpret_cast<const PwAddArgs*>(plan.tasks[host].args)->ea;
                 ok = ok && (c3 || pw) && hits[v].empty() && plan.tasks[v].n_parents == 0 && plan.fused_into[host] < 0 &&
-                     pos[host] < pos[v] && g->nodes[v].preds.size() == 1 && g->nodes[v].preds[0] == host &&
-                     g->nodes[host].out == g->nodes[v].out && partition_of(hk) == partition_of(plan.tasks[v].kid) &&
-                     plan.tasks[host].ntiles == plan.tasks[v].ntiles && ep->y == bn->y && ep->scale == bn->scale &&
-                     ep->shift == bn->shift && ep->relu == bn->relu &&
+                     pos[host] < pos[v] && g->nodes[host].out == g->nodes[v].out &&
+                     partition_of(hk) == partition_of(plan.tasks[v].kid) && plan.tasks[host].ntiles == plan.tasks[v].ntiles &&
                      (plan.tasks[host].release_far || !plan.tasks[v].release_far);
+                if (g->nodes[v].op == NG_OP_ADD_N) {
+                    ok = ok && has_add_epilogue(hk);
+                    const AddArgs* add = reinterpret_cast<const AddArgs*>(plan.tasks[v].args);
+                    const float* held = ep->y != nullptr ? ep->y : (c3 ? reinterpret_cast<const C3Args*>(plan.tasks[host].args)->y
+                                                                       : reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->y);
+                    ok = ok && ea->y == add->y && ea->k == add->k && add->k >= 2 && add->k <= kEpilogueAddMax && ea->zpos >= 0 &&
+                         ea->zpos < add->k && (ea->far != 0) == (plan.tasks[v].far_in != 0);
+                    int q = 0, late = 0;
+                    for (int j = 0; j < add->k && ok; ++j) {
+                        if (j == ea->zpos) ok = add->x[j] == held;
+                        else ok = ea->x[q++] == add->x[j];
+                    }
+                    // every E' parent of the add_n other than the fused operand is awaited late by the convolution
+                    for (auto& e : g->sched.meg)
+                        if (e.second == (int)v && g->tasks[e.first].fn) {
+                            const int src = plan.fused_into[e.first] >= 0 ? plan.fused_into[e.first] : e.first;
+                            if (src == host) continue;
+                            ++late;
+                            const DevTask& h = plan.tasks[host];
+                            ok = ok && std::find(h.parent + h.n_parents - h.n_late, h.parent + h.n_parents, src) != h.parent + h.n_parents;
+                        }
+                    ok = ok && late == (int)plan.tasks[host].n_late;
+                    ++fused_adds[host];
+                } else {
+                    const BnArgs* bn = reinterpret_cast<const BnArgs*>(plan.tasks[v].args);
+                    ok = ok && g->nodes[v].preds.size() == 1 && g->nodes[v].preds[0] == host && ep->y == bn->y &&
+                         ep->scale == bn->scale && ep->shift == bn->shift && ep->relu == bn->relu;
+                    ++fused_bns[host];
+                }
                 continue;
             }
             ok = ok && plan.tasks[v].ntiles > 0 && hits[v].size() == (size_t)units_of((int)v);
@@ -561,24 +673,26 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
         for (auto& e : g->sched.meg) {
             const int u = e.first, v = e.second;
             if (!g->tasks[u].fn || !g->tasks[v].fn) continue;
-            const DevTask& d = plan.tasks[v];
-            if (plan.fused_into[v] == u) continue;                                    // checked above
             const int src = plan.fused_into[u] >= 0 ? plan.fused_into[u] : u;         // whose workgroups store u's result
+            const int dst = plan.fused_into[v] >= 0 ? plan.fused_into[v] : v;         // whose workgroups wait for it
+            if (src == dst) continue;                                                 // fused pair, checked above
+            const DevTask& d = plan.tasks[dst];
             if (std::find(d.parent, d.parent + d.n_parents, src) != d.parent + d.n_parents) continue;
             ++n_local;
             const int part = partition_of(plan.tasks[u].kid);
             ok = ok && plan.fused_into[v] < 0 && part != PART_NONE && part == partition_of(d.kid) && plan.tasks[u].ntiles == d.ntiles &&
                  g->nodes[u].out == g->nodes[v].out && where[src] == where[v];
         }
-        // a convolution without a fused follower has no epilogue
-        std::vector<char> has_child(n, 0);
-        for (size_t v = 0; v < n; ++v)
-            if (plan.fused_into[v] >= 0) ok = ok && !has_child[plan.fused_into[v]], has_child[plan.fused_into[v]] = 1;
+        // epilogues are there exactly where a task was fused; late parents only with a fused add_n
         for (size_t u = 0; u < n; ++u) {
             const int k = plan.tasks[u].kid;
-            if (!g->tasks[u].fn || has_child[u]) continue;
-            if (k >= KID_C3_M1 && k <= KID_C3_M4) ok = ok && reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y == nullptr;
-            if (k >= KID_PW_V1 && k <= KID_PW_S4) ok = ok && reinterpret_cast<const PwArgs*>(plan.tasks[u].args)->ep.y == nullptr;
+            if (!g->tasks[u].fn) continue;
+            const bool c3 = is_c3m(k), pw = is_pw16(k);
+            ok = ok && fused_bns[u] <= 1 && fused_adds[u] <= 1 && (c3 || pw || fused_bns[u] + fused_adds[u] == 0) &&
+                 (fused_adds[u] == 1 || plan.tasks[u].n_late == 0) && plan.tasks[u].n_late <= (unsigned)plan.tasks[u].n_parents;
+            ok = ok && has_add_epilogue(k) == (fused_adds[u] == 1);
+            if (c3) ok = ok && (reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
+            if (pw) ok = ok && (reinterpret_cast<const PwArgs*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
         }
         if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d, fused: %d\n", n_local, n_fused);
         if (coverage_ok) *coverage_ok = ok;

@@ -213,7 +213,7 @@ int build_resident(ng_graph* g) {
         DevRecord& r = records[e];
         r.task = entries[e].task, r.kid = t.kid, r.ntiles = t.ntiles, r.n_parents = t.n_parents;
         r.tile_begin = entries[e].tile_begin, r.tile_step = entries[e].tile_step;
-        r.flags = (t.far_in != 0 ? 1 : 0) | (t.release_far != 0 ? 2 : 0) | ((t.publish & 1u) ? 4 : 0) | ((t.publish & 2u) ? 8 : 0) | ((t.publish & 4u) ? 16 : 0);
+        r.flags = (t.far_in != 0 ? 1 : 0) | (t.release_far != 0 ? 2 : 0) | ((t.publish & 1u) ? 4 : 0) | ((t.publish & 2u) ? 8 : 0) | ((t.publish & 4u) ? 16 : 0) | ((int)t.n_late << 8);
         r.subs = entries[e].subs | (entries[e].xcd_peers << 8);
         for (int j = 0; j < NG_MAX_PREDS; ++j) r.parent[j] = t.parent[j] | (((t.parent_far >> j) & 1u) ? (int)0x80000000u : 0);
         std::memcpy(r.need, t.need, sizeof r.need);
@@ -497,6 +497,13 @@ int ng_resident_xcd_mapping(const ng_graph* g, int* verified) {
     if (!g) return NG_EINVAL;
     if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_resident_xcd_mapping: call ng_capture first");
     if (verified) *verified = g->rt->xcd_mapping_ok ? 1 : 0;
+    return NG_OK;
+}
+
+int ng_resident_fusion(const ng_graph* g, int* host_of) {
+    if (!g || !host_of) return NG_EINVAL;
+    if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_resident_fusion: call ng_capture first");
+    for (size_t v = 0; v < g->nodes.size(); ++v) host_of[v] = v < g->rt->fused_into.size() ? g->rt->fused_into[v] : -1;
     return NG_OK;
 }
 

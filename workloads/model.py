@@ -86,7 +86,7 @@ class Builder:
         return self._add("relu", [x], self.shape(x))
 
     def add_n(self, xs) -> int:
-        assert 2 <= len(xs) <= 3
+        assert 2 <= len(xs) <= 8          # the library takes up to 8 predecessors per node
         s = self.shape(xs[0])
         assert all(self.shape(x) == s for x in xs), [self.shape(x) for x in xs]
         return self._add("add_n", xs, s)
