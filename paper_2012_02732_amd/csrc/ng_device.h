@@ -20,21 +20,26 @@ enum Kid : int {
     KID_BN_R64, KID_BN_R16, KID_ADD_R64, KID_ADD_R16,   // elementwise tasks on the tile grids of those two (resident replay)
     KID_C3_M1, KID_C3_M2, KID_C3_M3, KID_C3_M4,   // conv3x3 as an implicit GEMM on the matrix cores, 16 x 16 output tile
     KID_POOL_P4, KID_DW_K3S1_P4,     // windowed kernels with 4 outputs per thread (resident replay)
-    // the 16-row convolutions with an add_n applied to their result before it is stored (resident replay)
+    // the 16-row convolutions and the pools with an add_n applied to their result before it is stored (resident replay)
     KID_PW_V1A, KID_PW_V2A, KID_PW_V3A, KID_PW_V4A, KID_PW_S1A, KID_PW_S2A, KID_PW_S3A, KID_PW_S4A,
-    KID_C3_M1A, KID_C3_M2A, KID_C3_M3A, KID_C3_M4A,
+    KID_C3_M1A, KID_C3_M2A, KID_C3_M3A, KID_C3_M4A, KID_POOL_A, KID_POOL_P4A,
     KID_COUNT
 };
 
-// the variant without / with a fused add_n of a 16-row convolution kernel (other ids map to themselves / KID_NONE)
+// the variant without / with a fused add_n of a kernel (ids without such a variant map to themselves / KID_NONE)
 constexpr int plain_variant(int kid) {
-    return (kid >= KID_PW_V1A && kid <= KID_PW_S4A) ? kid - KID_PW_V1A + KID_PW_V1
-                                                    : (kid >= KID_C3_M1A && kid <= KID_C3_M4A) ? kid - KID_C3_M1A + KID_C3_M1 : kid;
+    return (kid >= KID_PW_V1A && kid <= KID_PW_S4A)
+               ? kid - KID_PW_V1A + KID_PW_V1
+               : (kid >= KID_C3_M1A && kid <= KID_C3_M4A) ? kid - KID_C3_M1A + KID_C3_M1
+                                                          : kid == KID_POOL_A ? KID_POOL : kid == KID_POOL_P4A ? KID_POOL_P4 : kid;
 }
 constexpr int add_variant(int kid) {
-    return (kid >= KID_PW_V1 && kid <= KID_PW_S4) ? kid - KID_PW_V1 + KID_PW_V1A
-                                                  : (kid >= KID_C3_M1 && kid <= KID_C3_M4) ? kid - KID_C3_M1 + KID_C3_M1A : KID_NONE;
+    return (kid >= KID_PW_V1 && kid <= KID_PW_S4)
+               ? kid - KID_PW_V1 + KID_PW_V1A
+               : (kid >= KID_C3_M1 && kid <= KID_C3_M4) ? kid - KID_C3_M1 + KID_C3_M1A
+                                                        : kid == KID_POOL ? KID_POOL_A : kid == KID_POOL_P4 ? KID_POOL_P4A : KID_NONE;
 }
+constexpr bool is_pool(int kid) { return plain_variant(kid) == KID_POOL || plain_variant(kid) == KID_POOL_P4; }
 constexpr bool is_pw16(int kid) { return plain_variant(kid) >= KID_PW_V1 && plain_variant(kid) <= KID_PW_S4; }
 constexpr bool is_c3m(int kid) { return plain_variant(kid) >= KID_C3_M1 && plain_variant(kid) <= KID_C3_M4; }
 constexpr bool has_add_epilogue(int kid) { return plain_variant(kid) != kid; }
@@ -103,12 +108,29 @@ struct ConcatArgs {
     int total;
 };
 
+// Optional further result of a convolution or pool tile (device-resident replay only): the add_n
+// task that takes the (batch-normed) convolution result or the pooled value as one operand. The other operands come from other tasks; the tile waits for them only now (the
+// entry's late parents), adds in argument order and stores. y == nullptr: none.
+constexpr int kEpilogueAddMax = 4;           // operands of an add_n that can be fused
+struct AddEpilogue {
+    const float* x[kEpilogueAddMax - 1];     // the operands that are read, in argument order
+    float* y;
+    int k;                                   // operands in all, 2..kEpilogueAddMax
+    int zpos;                                // argument position of the value held in registers
+    int far;                                 // != 0: read the operands with device-scope loads
+    int pad_;
+};
+
 struct PoolArgs {
     const float* x;
     float* y;
     int H, W, Ho, Wo;
     int stride, pad, mode;     // mode 0 max, 1 avg
     int total;                 // output elements
+};
+
+struct PoolAddArgs : PoolArgs {
+    AddEpilogue ea;            // the pooled value is one operand of an add_n
 };
 
 struct DwArgs {
@@ -142,19 +164,6 @@ struct Epilogue {
     const float* shift;
     float* y;                  // same shape as the convolution's result
     int relu;
-};
-
-// Optional third result: the add_n task that takes the (batch-normed) convolution result as one
-// operand. The other operands come from other tasks; the tile waits for them only now (the
-// entry's late parents), adds in argument order and stores. y == nullptr: none.
-constexpr int kEpilogueAddMax = 4;           // operands of an add_n that can be fused
-struct AddEpilogue {
-    const float* x[kEpilogueAddMax - 1];     // the operands that are read, in argument order
-    float* y;
-    int k;                                   // operands in all, 2..kEpilogueAddMax
-    int zpos;                                // argument position of the value held in registers
-    int far;                                 // != 0: read the operands with device-scope loads
-    int pad_;
 };
 
 struct PwArgs {

@@ -263,8 +263,9 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
 // rounds on the workgroups of its stream - one round costs one trip to memory however many
 // loads are in flight, and 1024 consecutive outputs are also the tile of the float4
 // elementwise kernels, which can then take over the partition).
-template <int P, bool FIN, bool FOUT, class Wait>
-__device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+template <int P, bool EA, bool FIN, bool FOUT, class Wait>
+__device__ __forceinline__ void pool3x3_tile(const typename std::conditional<EA, PoolAddArgs, PoolArgs>::type& a, int tile, float*, int tid,
+                                             bool live, Wait& wait) {
     const int base = tile * kBlock * P + tid;
     const bool active = live && base < a.total;
     // all taps of all P outputs are loaded unconditionally from clamped coordinates, so the
@@ -281,31 +282,44 @@ __device__ __forceinline__ void pool3x3_tile(const PoolArgs& a, int tile, float*
         r0[p] = oh * a.stride - a.pad, c0[p] = ow * a.stride - a.pad;
     }
     wait();
-    if (!active) return;
+    if (!EA && !active) return;                              // with a fused add_n every thread goes on to the late wait
+    float res[P];
+    if (active) {
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
+        for (int p = 0; p < P; ++p) {
 #pragma unroll
-        for (int dr = 0; dr < 3; ++dr)
+            for (int dr = 0; dr < 3; ++dr)
 #pragma unroll
-            for (int dc = 0; dc < 3; ++dc)
-                v[p][dr * 3 + dc] = ldg(a.x, src[p] + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
+                for (int dc = 0; dc < 3; ++dc)
+                    v[p][dr * 3 + dc] = ldg(a.x, src[p] + min(max(r0[p] + dr, 0), a.H - 1) * a.W + min(max(c0[p] + dc, 0), a.W - 1), FIN);
+        }
+        __builtin_amdgcn_sched_barrier(0);                   // all loads are issued before the first use
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            float acc = a.mode == 0 ? -INFINITY : 0.f;
+            int cnt = 0;
+#pragma unroll
+            for (int dr = 0; dr < 3; ++dr)
+#pragma unroll
+                for (int dc = 0; dc < 3; ++dc) {
+                    const int r = r0[p] + dr, c = c0[p] + dc;
+                    const bool in = r >= 0 && r < a.H && c >= 0 && c < a.W;
+                    if (a.mode == 0) acc = in ? fmaxf(acc, v[p][dr * 3 + dc]) : acc;
+                    else acc += in ? v[p][dr * 3 + dc] : 0.f;
+                    cnt += in;
+                }
+            res[p] = a.mode == 0 ? acc : acc / (float)cnt;
+            if (base + p * kBlock < a.total) stg(a.y, a.y + base + p * kBlock, res[p], FOUT);
+        }
     }
-    __builtin_amdgcn_sched_barrier(0);                       // all loads are issued before the first use
+    if constexpr (EA) {
+        wait.late();
+        if (active) {
 #pragma unroll
-    for (int p = 0; p < P; ++p) {
-        float acc = a.mode == 0 ? -INFINITY : 0.f;
-        int cnt = 0;
-#pragma unroll
-        for (int dr = 0; dr < 3; ++dr)
-#pragma unroll
-            for (int dc = 0; dc < 3; ++dc) {
-                const int r = r0[p] + dr, c = c0[p] + dc;
-                const bool in = r >= 0 && r < a.H && c >= 0 && c < a.W;
-                if (a.mode == 0) acc = in ? fmaxf(acc, v[p][dr * 3 + dc]) : acc;
-                else acc += in ? v[p][dr * 3 + dc] : 0.f;
-                cnt += in;
-            }
-        if (base + p * kBlock < a.total) stg(a.y, a.y + base + p * kBlock, a.mode == 0 ? acc : acc / (float)cnt, FOUT);
+            for (int p = 0; p < P; ++p)
+                if (base + p * kBlock < a.total)
+                    add_epilogue<false, FOUT>(a.ea, make_float4(res[p], 0.f, 0.f, 0.f), (size_t)(base + p * kBlock));
+        }
     }
 }
 
@@ -950,8 +964,10 @@ NG_KERNEL(KID_DW_K3S2, DwArgs, "dwconv_k3s2", dwconv_tile < 3, 2, 1)
 NG_KERNEL(KID_DW_K5S1, DwArgs, "dwconv_k5s1", dwconv_tile < 5, 1, 1)
 NG_KERNEL(KID_DW_K5S2, DwArgs, "dwconv_k5s2", dwconv_tile < 5, 2, 1)
 NG_KERNEL(KID_DW_K3S1_P4, DwArgs, "dwconv_k3s1_p4", dwconv_tile < 3, 1, 4)
-NG_KERNEL(KID_POOL, PoolArgs, "pool3x3", pool3x3_tile < 1)
-NG_KERNEL(KID_POOL_P4, PoolArgs, "pool3x3_p4", pool3x3_tile < 4)
+NG_KERNEL(KID_POOL, PoolArgs, "pool3x3", pool3x3_tile < 1, false)
+NG_KERNEL(KID_POOL_P4, PoolArgs, "pool3x3_p4", pool3x3_tile < 4, false)
+NG_KERNEL(KID_POOL_A, PoolAddArgs, "pool3x3_add", pool3x3_tile < 1, true)
+NG_KERNEL(KID_POOL_P4A, PoolAddArgs, "pool3x3_p4_add", pool3x3_tile < 4, true)
 NG_KERNEL(KID_PW_D4, PwArgs, "conv1x1_mfma_d4", conv1x1_direct_tile < 4)
 NG_KERNEL(KID_PW_D8, PwArgs, "conv1x1_mfma_d8", conv1x1_direct_tile < 8)
 NG_KERNEL(KID_PW_D16, PwArgs, "conv1x1_mfma_d16", conv1x1_direct_tile < 16)
@@ -1060,10 +1076,7 @@ __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int s
 // The polling loop of one lane.
 // 0: the counter has reached the target; 1: it has not (`once`: after a single look, otherwise because
 // another wait in the grid gave up); 2: ran out of spins.
-#ifndef NG_SPIN_INLINE
-#define NG_SPIN_INLINE __forceinline__
-#endif
-__device__ NG_SPIN_INLINE int spin_until(unsigned* counter, unsigned target, bool far, bool once, unsigned spin_limit,
+__device__ __forceinline__ int spin_until(unsigned* counter, unsigned target, bool far, bool once, unsigned spin_limit,
                                                     int* error_dev, int poll_sleep) {
     unsigned spins = 0;
     for (;;) {
@@ -1216,6 +1229,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                 NG_CASE(KID_C3_M3) NG_CASE(KID_C3_M4)
                 NG_CASE(KID_PW_V1A) NG_CASE(KID_PW_V2A) NG_CASE(KID_PW_V3A) NG_CASE(KID_PW_V4A) NG_CASE(KID_PW_S1A) NG_CASE(KID_PW_S2A)
                 NG_CASE(KID_PW_S3A) NG_CASE(KID_PW_S4A) NG_CASE(KID_C3_M1A) NG_CASE(KID_C3_M2A) NG_CASE(KID_C3_M3A) NG_CASE(KID_C3_M4A)
+                NG_CASE(KID_POOL_A) NG_CASE(KID_POOL_P4A)
 #undef NG_CASE
                 default: break;
             }

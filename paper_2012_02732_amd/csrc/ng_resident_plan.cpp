@@ -259,20 +259,26 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             g->nodes[v].preds.size() <= (size_t)kEpilogueAddMax) {
             const std::vector<int>& preds = g->nodes[v].preds;
             int host = -1, via = -1;
+            // first choice: a host on the XCD of the add_n's own stream, where its readers most likely are
+            static const int far_host = getenv("NG_FUSE_ADD_FAR") ? atoi(getenv("NG_FUSE_ADD_FAR")) : 1;
+            for (int pass = 0; pass < 1 + far_host && host < 0; ++pass)
             for (int w : parents[v]) {
                 const int u = out.fused_into[w] >= 0 ? out.fused_into[w] : w;
                 if (!g->tasks[u].fn || add_child[u]) continue;
+                if ((out.xcd[u] == (nx == 1 ? 0 : home)) != (pass == 0)) continue;
                 if (g->nodes[w].op == NG_OP_ADD_N) continue;                               // w must be the convolution or its batch-norm
-                const bool conv16 = is_pw16(out.kid[u]) || is_c3m(out.kid[u]);
-                if (!conv16 || (w == u && fused_child[u])) continue;
+                if (add_variant(out.kid[u]) == KID_NONE || (w == u && fused_child[u])) continue;   // a 16-row convolution or a pool
                 // nobody else reads the convolution or its batch-norm, and the value is one operand exactly once
                 if (children[u].size() != 1 || children[w].size() != 1 || children[w][0] != v) continue;
                 if (std::count(preds.begin(), preds.end(), w) != 1 || (w != u && std::count(preds.begin(), preds.end(), u) != 0)) continue;
                 long nt = 0;
                 if (!(g->nodes[u].out == g->nodes[v].out) || variant_for(g, v, partition_of(out.kid[u]), &nt) == KID_NONE || nt != out.ntiles[u]) continue;
                 bool before = true;
-                for (int p : parents[v])
-                    if (p != w && g->tasks[p].fn) before = before && placed_at[p] >= 0 && placed_at[p] < placed_at[u];
+                for (int p : parents[v]) {
+                    if (p == w || !g->tasks[p].fn) continue;
+                    const int src = out.fused_into[p] >= 0 ? out.fused_into[p] : p;      // whose counter the late wait watches
+                    before = before && src != u && placed_at[src] >= 0 && placed_at[src] < placed_at[u];
+                }
                 if (!before || parents[u].size() + parents[v].size() - 1 > (size_t)NG_MAX_PREDS) continue;
                 host = u, via = w;
                 break;
@@ -493,6 +499,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
             if (ea.zpos < 0 || q != add->k - 1) return NG_EINVAL;
             if (!has_add_epilogue(best.kid[u])) return NG_EINVAL;
             if (c3) reinterpret_cast<C3AddArgs*>(plan.tasks[u].args)->ea = ea;
+            else if (is_pool(best.kid[u])) reinterpret_cast<PoolAddArgs*>(plan.tasks[u].args)->ea = ea;
             else reinterpret_cast<PwAddArgs*>(plan.tasks[u].args)->ea = ea;
         } else {
             const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
@@ -625,20 +632,24 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
                 // grid, comes earlier in the order and carries its coefficients / operands and output address
                 ++n_fused;
                 const int hk = plan.tasks[host].kid;
-                const bool c3 = is_c3m(hk), pw = is_pw16(hk);
+                const bool c3 = is_c3m(hk), pw = is_pw16(hk), pool = is_pool(hk);
+                static const Epilogue none{};
                 const Epilogue* ep = c3 ? &reinterpret_cast<const C3Args*>(plan.tasks[host].args)->ep
-                                        : &reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->ep;
+                                        : pw ? &reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->ep : &none;
                 const AddEpilogue* ea = c3 ? &reinterpret_cast<const C3AddArgs*>(plan.tasks[host].args)->ea
-                                           : &reinterpret_cast<const PwAddArgs*>(plan.tasks[host].args)->ea;
-                ok = ok && (c3 || pw) && hits[v].empty() && plan.tasks[v].n_parents == 0 && plan.fused_into[host] < 0 &&
+                                           : pool ? &reinterpret_cast<const PoolAddArgs*>(plan.tasks[host].args)->ea
+                                                  : &reinterpret_cast<const PwAddArgs*>(plan.tasks[host].args)->ea;
+                ok = ok && (c3 || pw || (pool && g->nodes[v].op == NG_OP_ADD_N)) && hits[v].empty() && plan.tasks[v].n_parents == 0 && plan.fused_into[host] < 0 &&
                      pos[host] < pos[v] && g->nodes[host].out == g->nodes[v].out &&
                      partition_of(hk) == partition_of(plan.tasks[v].kid) && plan.tasks[host].ntiles == plan.tasks[v].ntiles &&
                      (plan.tasks[host].release_far || !plan.tasks[v].release_far);
                 if (g->nodes[v].op == NG_OP_ADD_N) {
                     ok = ok && has_add_epilogue(hk);
                     const AddArgs* add = reinterpret_cast<const AddArgs*>(plan.tasks[v].args);
-                    const float* held = ep->y != nullptr ? ep->y : (c3 ? reinterpret_cast<const C3Args*>(plan.tasks[host].args)->y
-                                                                       : reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->y);
+                    const float* held = ep->y != nullptr ? ep->y
+                                        : c3 ? reinterpret_cast<const C3Args*>(plan.tasks[host].args)->y
+                                             : pool ? reinterpret_cast<const PoolArgs*>(plan.tasks[host].args)->y
+                                                    : reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->y;
                     ok = ok && ea->y == add->y && ea->k == add->k && add->k >= 2 && add->k <= kEpilogueAddMax && ea->zpos >= 0 &&
                          ea->zpos < add->k && (ea->far != 0) == (plan.tasks[v].far_in != 0);
                     int q = 0, late = 0;
@@ -688,7 +699,7 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
             const int k = plan.tasks[u].kid;
             if (!g->tasks[u].fn) continue;
             const bool c3 = is_c3m(k), pw = is_pw16(k);
-            ok = ok && fused_bns[u] <= 1 && fused_adds[u] <= 1 && (c3 || pw || fused_bns[u] + fused_adds[u] == 0) &&
+            ok = ok && fused_bns[u] <= 1 && fused_adds[u] <= 1 && (c3 || pw || fused_bns[u] == 0) && (c3 || pw || is_pool(k) || fused_adds[u] == 0) &&
                  (fused_adds[u] == 1 || plan.tasks[u].n_late == 0) && plan.tasks[u].n_late <= (unsigned)plan.tasks[u].n_parents;
             ok = ok && has_add_epilogue(k) == (fused_adds[u] == 1);
             if (c3) ok = ok && (reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);

@@ -383,12 +383,12 @@ def _resident_vs_single(w, xcds=0):
         r.close()
 
 
-@pytest.mark.parametrize("shape,cout", [((1, 32, 14, 14), 48), ((1, 24, 7, 7), 24), ((2, 16, 8, 8), 40)])
+@pytest.mark.parametrize("shape,cout", [((1, 32, 14, 14), 48), ((1, 24, 7, 7), 24), ((2, 16, 8, 8), 40), ((1, 64, 28, 28), 32)])
 def test_device_resident_fused_epilogues(shape, cout):
     """Batch-norm / ReLU and add_n tasks that the device-resident plan runs inside the tiles of
     the convolution that feeds them: 128-bit and 32-bit conv1x1 tile grids and the conv3x3
-    implicit GEMM; the fused value as first, middle and last operand of 2, 3 and 4; an add_n
-    straight behind a convolution; other operands that are ready long before the convolution
+    implicit GEMM, pools with one and with four outputs per thread; the fused value as first,
+    middle and last operand of 2, 3 and 4; an add_n straight behind a convolution; other operands that are ready long before the convolution
     (an early ReLU) and long after it (a chain of slow tasks, so the late wait really waits);
     and next to them the cases that must NOT be fused (a second reader of the convolution
     result, five operands). Every tensor, the raw convolution results included, is checked."""
@@ -405,17 +405,21 @@ def test_device_resident_fused_epilogues(shape, cout):
         a5 = b.add_n([b.bn_act(c5, relu=True), early])                            # bn has a second reader below: bn fused, add_n not
         a6 = b.add_n([early, slow, a1, a2, b.bn_act(b.conv1x1(t, cout), relu=True)])   # five operands: add_n not fused
         b.concat([a1, a2, a3, a4, a5, a6, b.relu(a5), b.pool(c5, "max", 1, 1)])
+        a7 = b.add_n([b.pool(x, "avg", 1, 1), b.pool(t, "max", 1, 1), x])         # pools: one of them carries the add_n
+        b.relu(b.add_n([b.pool(a7, "max", 1, 1), t]))
     w = single_op(build)
     for xcds in (0, 1):
         host_of = _resident_vs_single(w, xcds)
         ops = [nd.op for nd in w.nodes]
         fused_bn = [v for v, h in enumerate(host_of) if h >= 0 and ops[v] in ("bn_act", "relu")]
         fused_add = [v for v, h in enumerate(host_of) if h >= 0 and ops[v] == "add_n"]
-        assert all(ops[host_of[v]] in ("conv1x1", "conv3x3") for v in fused_bn + fused_add)
+        assert all(ops[host_of[v]] in ("conv1x1", "conv3x3") for v in fused_bn)
+        assert all(ops[host_of[v]] in ("conv1x1", "conv3x3", "pool") for v in fused_add)
         assert len(fused_bn) >= 4, (xcds, host_of)
-        # an add_n is only fused when its other producers come before the convolution in the lists' common
-        # order, which depends on the cost model: at least one of the four candidates must make it
-        assert 1 <= len(fused_add) <= 4, (xcds, host_of)
+        # an add_n is only fused when its other producers come before its host in the lists' common
+        # order, which depends on the cost model: at least one convolution and one pool must make it
+        assert 2 <= len(fused_add) <= 6, (xcds, host_of)
+        assert {"pool"} < {ops[host_of[v]] for v in fused_add}, (xcds, host_of)
         assert all(len(w.nodes[v].preds) <= 4 for v in fused_add)
 
 
