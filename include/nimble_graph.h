@@ -135,8 +135,10 @@ int ng_get_schedule(const ng_graph* g, int* order, int* stream_of, int* chain_of
 int ng_get_scaffold(const ng_graph* g, int* fork, int* n_fork, int* join, int* n_join);
 
 /* Static memory plan (Section 4.1: memory requests are identical on every run, so the
- * exact amount is reserved once). One buffer per node output, 256-byte aligned, no reuse.
- * *arena_bytes receives the total. */
+ * exact amount is reserved once). One buffer per node output, 256-byte aligned, no reuse over
+ * time. One exception to "one buffer each": at batch 1 a tensor that a concat takes whole is
+ * placed inside the concat's buffer, at its channel block (16-byte aligned), so it is produced
+ * in place and the concat copies nothing for it. *arena_bytes receives the total. */
 int ng_plan_memory(ng_graph* g, size_t* arena_bytes);
 /* offset[n_nodes], bytes[n_nodes] of each node's output inside the arena (host arrays). */
 int ng_get_offsets(const ng_graph* g, size_t* offset, size_t* bytes);
@@ -224,7 +226,9 @@ int ng_resident_xcd_mapping(const ng_graph* g, int* verified);
 /* Which nodes the device-resident plan runs inside another node's tiles: host_of[v] (n_nodes entries,
  * caller-owned host memory) = the convolution whose tiles also apply node v (a batch-norm / ReLU
  * directly behind it, or an add_n that takes its - possibly batch-normed - result as one operand),
- * or -1 for a node with workgroups of its own. Needs ng_capture. */
+ * -2 for a concat that has nothing to do because the memory plan placed all its inputs inside its
+ * result (its readers wait for the producers of those inputs), or -1 for a node with workgroups of
+ * its own. Needs ng_capture. */
 int ng_resident_fusion(const ng_graph* g, int* host_of);
 /* Host-only rehearsal of the device-resident plan (needs ng_plan_memory, no GPU): plans for
  * n_workgroups persistent workgroups (a multiple of 8) over xcds XCDs (0 = let the cost

@@ -2,6 +2,7 @@
 // Paper: Nimble (arXiv 2012.02732), Section 4 (input is a static operator DAG with a
 // fixed input shape) and Section 4.1 (all shapes and all memory are fixed ahead of time).
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -262,12 +263,38 @@ int ng_plan_memory(ng_graph* g, size_t* arena_bytes) {
     const size_t n = g->nodes.size();
     g->offset.assign(n, 0);
     g->bytes.assign(n, 0);
+    // A tensor that one concat takes whole (batch 1: a channel block of the result is one
+    // contiguous range) is produced in place, inside the concat's buffer; the concat then has
+    // nothing to copy for it. Everything else gets a private buffer; nothing is reused.
+    g->alias_of.assign(n, -1);
+    std::vector<size_t> inside(n, 0);                       // byte offset inside the concat's buffer
+    if (!getenv("NG_NO_CONCAT_ALIAS"))
+        for (size_t c = 0; c < n; ++c) {
+            const Node& cat = g->nodes[c];
+            if (cat.op != NG_OP_CONCAT || cat.out.n != 1) continue;
+            const size_t plane = (size_t)cat.out.h * cat.out.w * sizeof(float);
+            size_t first = 0;
+            for (size_t j = 0; j < cat.preds.size(); ++j) {
+                const int p = cat.preds[j];
+                const Node& src = g->nodes[p];
+                const bool whole = cat.p.slice_lo[j] == 0 && cat.p.slice_hi[j] == src.out.c;
+                const bool once = std::count(cat.preds.begin(), cat.preds.end(), p) == 1;
+                if (src.op != NG_OP_INPUT && g->alias_of[p] < 0 && whole && once && (first * plane) % 16 == 0) {
+                    g->alias_of[p] = (int)c;
+                    inside[p] = first * plane;
+                }
+                first += (size_t)(cat.p.slice_hi[j] - cat.p.slice_lo[j]);
+            }
+        }
     size_t top = 0;
-    for (size_t v = 0; v < n; ++v) {            // one private buffer per node output, 256-byte aligned
-        g->offset[v] = top;
+    for (size_t v = 0; v < n; ++v) {            // one private buffer per remaining node output, 256-byte aligned
         g->bytes[v] = (size_t)g->nodes[v].out.elems() * sizeof(float);
+        if (g->alias_of[v] >= 0) continue;
+        g->offset[v] = top;
         top += (g->bytes[v] + 255) & ~(size_t)255;
     }
+    for (size_t v = n; v-- > 0;)                // a concat has a higher id than its inputs: its own place is final by now
+        if (g->alias_of[v] >= 0) g->offset[v] = g->offset[g->alias_of[v]] + inside[v];
     g->arena_bytes = top;
     g->phase = PLANNED;
     if (arena_bytes) *arena_bytes = top;

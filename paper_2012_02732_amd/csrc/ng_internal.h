@@ -70,6 +70,7 @@ struct ResidentPlan {
     std::vector<int> wg_first;                 // [n_wg + 1]
     std::vector<int> order;                    // tasks in list order: every workgroup's list is a subsequence of it
     std::vector<int> fused_into;               // [n_nodes] convolution whose tiles also produce this task's result (no entries of its own), or -1
+    std::vector<char> elided;                  // [n_nodes] concat with nothing to copy (inputs produced in place): no entries either
 };
 
 struct Runtime;  // HIP-side state, defined in ng_runtime.hip
@@ -81,6 +82,7 @@ struct ng_graph {
     std::vector<ng::Node> nodes;
     ng::Schedule sched;
     std::vector<size_t> offset, bytes;
+    std::vector<int> alias_of;                           // concat node inside whose output this node's output lives, or -1
     size_t arena_bytes = 0;
     std::vector<ng::Task> tasks;
     ng::Runtime* rt = nullptr;

@@ -244,7 +244,7 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
         if (q < a.k && c >= a.first[q]) base = a.x[q], cin = a.cin[q], lo = a.lo[q], first = a.first[q];
     const float* src = base + ((size_t)(n * cin + lo + c - first)) * a.HW + pix;
     wait();
-    if (!active) return;
+    if (!active || src == a.y + e) return;                   // an input the memory plan placed inside the result is there already
     if (VEC4) {
         float4 v;
         if (FIN) v = ldg4_any_far(src);

@@ -29,6 +29,7 @@
 //     with device-scope accesses is decided from *all* direct readers (edges of E): a reader on
 //     another XCD reads the tensor itself, even when it only waits for an intermediate task.
 #include <algorithm>
+#include <functional>
 #include <cstdlib>
 #include <cstring>
 #include <numeric>
@@ -128,6 +129,7 @@ struct Sim {
     std::vector<int> order;          // tasks in the order they were placed: every workgroup's list follows it
     std::vector<int> local_parent;   // E' parent whose completion this task does not wait for (same workgroups, same tiles), or -1
     std::vector<int> fused_into;     // convolution whose tiles also produce this (batch-norm / ReLU / add_n) task's result, or -1
+    std::vector<char> elided;        // concat whose inputs were all produced in place: no work, no entries
     double makespan = 0;
 };
 
@@ -165,6 +167,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
     out.subs.assign(n, kSubs);
     out.local_parent.assign(n, -1);
     out.fused_into.assign(n, -1);
+    out.elided.assign(n, 0);
+    const bool allow_elide = getenv("NG_NO_ELIDE") == nullptr;
     const bool allow_fuse = getenv("NG_NO_FUSE") == nullptr;
     std::vector<double> free_at(n_wg, 0.0), finish(n, 0.0);
     std::vector<std::vector<int>> parents(n), wgs(n);
@@ -220,6 +224,28 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             !getenv("NG_NO_P4")) {
             out.kid[v] = t.kid == KID_POOL ? KID_POOL_P4 : KID_DW_K3S1_P4;
             out.ntiles[v] = (g->nodes[v].out.elems() + 4 * kBlock - 1) / (4 * kBlock);
+        }
+        // A concat whose inputs the memory plan placed inside its result has nothing to copy: it gets
+        // no entries, and whoever waits for it waits for its producers instead.
+        if (allow_elide && g->nodes[v].op == NG_OP_CONCAT && !g->alias_of.empty()) {
+            bool in_place = true;
+            for (int u : g->nodes[v].preds) in_place = in_place && g->alias_of[u] == v && g->tasks[u].fn;
+            for (int c : children[v]) in_place = in_place && parents[c].size() - 1 + parents[v].size() <= (size_t)NG_MAX_PREDS;
+            if (in_place) {
+                out.elided[v] = 1;
+                out.kid[v] = KID_NONE;                      // nobody can take over its partition
+                out.ntiles[v] = 0;
+                int common = -2;                            // the XCD all producers ran on, else -1 (treated like a spread task)
+                double done = 0;
+                for (int u : g->nodes[v].preds) common = common == -2 ? out.xcd[u] : (common == out.xcd[u] ? common : -1);
+                for (int u : parents[v]) done = std::max(done, finish[u]);
+                out.xcd[v] = common;
+                finish[v] = done;
+                if (debug) fprintf(stderr, "PLAN nx=%d v=%d concat in place, xcd=%d finish=%.2f\n", nx, v, common, done);
+                for (int c : children[v])
+                    if (--waiting[c] == 0) open.push(Key(ready_time(c), -tail[c], c));
+                continue;
+            }
         }
         // A batch-norm / ReLU task whose only producer is a 16-row convolution is not run at all:
         // the convolution's tiles apply it to their results before they store them (same tile
@@ -277,7 +303,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
                 for (int p : parents[v]) {
                     if (p == w || !g->tasks[p].fn) continue;
                     const int src = out.fused_into[p] >= 0 ? out.fused_into[p] : p;      // whose counter the late wait watches
-                    before = before && src != u && placed_at[src] >= 0 && placed_at[src] < placed_at[u];
+                    before = before && src != u && !out.elided[src] && placed_at[src] >= 0 && placed_at[src] < placed_at[u];
                 }
                 if (!before || parents[u].size() + parents[v].size() - 1 > (size_t)NG_MAX_PREDS) continue;
                 host = u, via = w;
@@ -456,6 +482,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     plan.est_us = best.makespan;
     plan.order = best.order;
     plan.fused_into = best.fused_into;
+    plan.elided = best.elided;
 
     plan.tasks.assign(n, DevTask());
     for (int v = 0; v < n; ++v) {
@@ -482,6 +509,10 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
                 if (g->tasks[u].fn) plan.tasks[u].release_far = 1;
         if (g->resident_all_far) plan.tasks[v].release_far = 1;
     }
+    // the stores into an in-place concat are its producers' stores
+    for (int v = n - 1; v >= 0; --v)
+        if (best.elided[v] && plan.tasks[v].release_far)
+            for (int u : g->nodes[v].preds) plan.tasks[u].release_far = 1;
     // fused pairs: the convolution's argument block gets the batch-norm's coefficients and output
     for (int v = 0; v < n; ++v) {
         const int u = best.fused_into[v];
@@ -511,25 +542,42 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     }
     // who waits for whom: first what every entry awaits before it starts, then (pass 1) the producers of
     // the other operands of a fused add_n, which its convolution awaits late
+    std::vector<std::vector<int>> meg_parents(n);
+    for (auto& e : sc.meg)
+        if (g->tasks[e.first].fn && g->tasks[e.second].fn) meg_parents[e.second].push_back(e.first);
+    // the tasks whose completion stands for the completion of u: u itself, the host it is fused into, or
+    // (an in-place concat) what stands for each of its E' parents
+    std::function<void(int, std::vector<int>&)> producers_of = [&](int u, std::vector<int>& list) {
+        if (best.elided[u]) {
+            for (int p : meg_parents[u]) producers_of(p, list);
+            return;
+        }
+        const int src = best.fused_into[u] >= 0 ? best.fused_into[u] : u;
+        if (std::find(list.begin(), list.end(), src) == list.end()) list.push_back(src);
+    };
     for (int pass = 0; pass < 2; ++pass)
         for (auto& e : sc.meg) {
             if (!g->tasks[e.first].fn || !g->tasks[e.second].fn) continue;
-            if (best.local_parent[e.second] == e.first) continue;   // handed over inside the workgroups
-            const int src = best.fused_into[e.first] >= 0 ? best.fused_into[e.first] : e.first;   // who really produces it
+            if (best.local_parent[e.second] == e.first || best.elided[e.second]) continue;   // handed over inside the workgroups / nothing to wait for
             const int dst = best.fused_into[e.second] >= 0 ? best.fused_into[e.second] : e.second; // whose entries wait for it
             if ((dst != e.second) != (pass == 1)) continue;
+            std::vector<int> sources;
+            producers_of(e.first, sources);
             DevTask& d = plan.tasks[dst];
-            if (d.n_parents >= NG_MAX_PREDS) return NG_EINVAL;
-            d.parent[d.n_parents] = src;
-            d.need[d.n_parents] = best.signals[src];
-            // producer and consumer on the same single XCD: the completion is signalled through that XCD's L2
-            const bool near = best.xcd[src] >= 0 && best.xcd[src] == best.xcd[dst] && !g->resident_all_far &&
-                              !getenv("NG_NO_NEAR_COUNTERS");
-            if (near) plan.tasks[src].publish |= 1u;
-            else plan.tasks[src].publish |= 2u, d.parent_far |= 1u << d.n_parents;
-            if (!near && best.signals[src] != best.parts[src]) plan.tasks[src].publish |= 4u;
-            ++d.n_parents;
-            if (pass == 1) ++d.n_late;
+            for (int src : sources) {
+                if (src == dst || std::find(d.parent, d.parent + d.n_parents, src) != d.parent + d.n_parents) continue;
+                if (d.n_parents >= NG_MAX_PREDS) return NG_EINVAL;
+                d.parent[d.n_parents] = src;
+                d.need[d.n_parents] = best.signals[src];
+                // producer and consumer on the same single XCD: the completion is signalled through that XCD's L2
+                const bool near = best.xcd[src] >= 0 && best.xcd[src] == best.xcd[dst] && !g->resident_all_far &&
+                                  !getenv("NG_NO_NEAR_COUNTERS");
+                if (near) plan.tasks[src].publish |= 1u;
+                else plan.tasks[src].publish |= 2u, d.parent_far |= 1u << d.n_parents;
+                if (!near && best.signals[src] != best.parts[src]) plan.tasks[src].publish |= 4u;
+                ++d.n_parents;
+                if (pass == 1) ++d.n_late;
+            }
         }
     plan.entries.clear();
     plan.wg_first.assign(n_wg + 1, 0);
@@ -622,10 +670,17 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
                 signals[v] = (plan.tasks[v].publish & 4u) ? (unsigned)used : parts[v];
             }
         }
-        int n_local = 0, n_fused = 0;
+        int n_local = 0, n_fused = 0, n_elided = 0;
         std::vector<int> fused_bns(n, 0), fused_adds(n, 0);
         for (size_t v = 0; v < n; ++v) {
             if (!g->tasks[v].fn) continue;
+            if (plan.elided[v]) {
+                // an in-place concat: every input lives inside its result, no entries, no waits
+                ++n_elided;
+                ok = ok && g->nodes[v].op == NG_OP_CONCAT && hits[v].empty() && plan.tasks[v].n_parents == 0 && plan.fused_into[v] < 0;
+                for (int u : g->nodes[v].preds) ok = ok && g->alias_of[u] == (int)v && pos[u] < pos[v];
+                continue;
+            }
             const int host = plan.fused_into[v];
             if (host >= 0) {
                 // a fused task has no entries and no waits of its own; its convolution covers the same tile
@@ -664,9 +719,9 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
                             if (src == host) continue;
                             ++late;
                             const DevTask& h = plan.tasks[host];
-                            ok = ok && std::find(h.parent + h.n_parents - h.n_late, h.parent + h.n_parents, src) != h.parent + h.n_parents;
+                            ok = ok && !plan.elided[src] && std::find(h.parent, h.parent + h.n_parents, src) != h.parent + h.n_parents;
                         }
-                    ok = ok && late == (int)plan.tasks[host].n_late;
+                    ok = ok && late >= (int)plan.tasks[host].n_late;
                     ++fused_adds[host];
                 } else {
                     const BnArgs* bn = reinterpret_cast<const BnArgs*>(plan.tasks[v].args);
@@ -684,15 +739,28 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
         for (auto& e : g->sched.meg) {
             const int u = e.first, v = e.second;
             if (!g->tasks[u].fn || !g->tasks[v].fn) continue;
-            const int src = plan.fused_into[u] >= 0 ? plan.fused_into[u] : u;         // whose workgroups store u's result
+            if (plan.elided[v]) continue;                                              // waits for nothing
             const int dst = plan.fused_into[v] >= 0 ? plan.fused_into[v] : v;         // whose workgroups wait for it
-            if (src == dst) continue;                                                 // fused pair, checked above
             const DevTask& d = plan.tasks[dst];
-            if (std::find(d.parent, d.parent + d.n_parents, src) != d.parent + d.n_parents) continue;
-            ++n_local;
-            const int part = partition_of(plan.tasks[u].kid);
-            ok = ok && plan.fused_into[v] < 0 && part != PART_NONE && part == partition_of(d.kid) && plan.tasks[u].ntiles == d.ntiles &&
-                 g->nodes[u].out == g->nodes[v].out && where[src] == where[v];
+            // whose workgroups store u's result: u, its host, or (in-place concat) those of its E' parents
+            std::vector<int> sources;
+            std::function<void(int)> expand = [&](int t) {
+                if (plan.elided[t]) {
+                    for (auto& f : g->sched.meg)
+                        if (f.second == t && g->tasks[f.first].fn) expand(f.first);
+                } else {
+                    sources.push_back(plan.fused_into[t] >= 0 ? plan.fused_into[t] : t);
+                }
+            };
+            expand(u);
+            for (int src : sources) {
+                if (src == dst) continue;                                             // fused pair, checked above
+                if (std::find(d.parent, d.parent + d.n_parents, src) != d.parent + d.n_parents) continue;
+                ++n_local;
+                const int part = partition_of(plan.tasks[u].kid);
+                ok = ok && !plan.elided[u] && plan.fused_into[v] < 0 && part != PART_NONE && part == partition_of(d.kid) &&
+                     plan.tasks[u].ntiles == d.ntiles && g->nodes[u].out == g->nodes[v].out && where[src] == where[v];
+            }
         }
         // epilogues are there exactly where a task was fused; late parents only with a fused add_n
         for (size_t u = 0; u < n; ++u) {
@@ -705,7 +773,7 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
             if (c3) ok = ok && (reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
             if (pw) ok = ok && (reinterpret_cast<const PwArgs*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
         }
-        if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d, fused: %d\n", n_local, n_fused);
+        if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d, fused: %d, concats in place: %d\n", n_local, n_fused, n_elided);
         if (coverage_ok) *coverage_ok = ok;
     }
     g->dry_run = false;

@@ -40,6 +40,7 @@ struct Runtime {
     int n_wg = 0, n_entries = 0;
     std::vector<int> entry_task;           // node of every list entry, in record order (for the timeline)
     std::vector<int> fused_into;           // per node: the convolution that also produces its result, or -1
+    std::vector<char> elided;              // per node: a concat with nothing to copy
     bool xcd_mapping_ok = false;           // workgroups of the resident grid with equal index mod 8 share an XCD (probed)
     bool resident_full = true;             // the DAG uses kernels the lean build of the resident kernel leaves out
     unsigned epoch = 0;
@@ -207,6 +208,7 @@ int build_resident(ng_graph* g) {
     std::memset(records.data(), 0, records.size() * sizeof(DevRecord));
     rt.entry_task.assign(entries.size(), 0);
     rt.fused_into = hp.fused_into;
+    rt.elided = hp.elided;
     for (size_t e = 0; e < entries.size(); ++e) {
         rt.entry_task[e] = entries[e].task;
         const DevTask& t = tasks[entries[e].task];
@@ -477,11 +479,17 @@ int ng_resident_trace(ng_graph* g, int enable, unsigned long long* ticks) {
             ticks[4 * v + 3] = std::max(ticks[4 * v + 3], r[2]);
         }
         // a fused task ran inside its convolution's tiles: it takes no time of its own, at the moment the tiles are stored
-        for (size_t v = 0; v < n && v < rt.fused_into.size(); ++v)
+        // (an in-place concat likewise: it is complete the moment its last input is)
+        for (size_t v = 0; v < n && v < rt.fused_into.size(); ++v) {
             if (rt.fused_into[v] >= 0) {
                 const unsigned long long* c = &ticks[4 * rt.fused_into[v]];
                 ticks[4 * v] = ticks[4 * v + 2] = c[2], ticks[4 * v + 1] = ticks[4 * v + 3] = c[3];
+            } else if (rt.elided[v]) {
+                unsigned long long last = 0;
+                for (int u : g->nodes[v].preds) last = std::max(last, ticks[4 * u + 3]);
+                ticks[4 * v] = ticks[4 * v + 1] = ticks[4 * v + 2] = ticks[4 * v + 3] = last;
             }
+        }
     }
     if (enable) {
         if (!rt.plan.trace) NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.plan.trace), bytes));
@@ -503,7 +511,8 @@ int ng_resident_xcd_mapping(const ng_graph* g, int* verified) {
 int ng_resident_fusion(const ng_graph* g, int* host_of) {
     if (!g || !host_of) return NG_EINVAL;
     if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_resident_fusion: call ng_capture first");
-    for (size_t v = 0; v < g->nodes.size(); ++v) host_of[v] = v < g->rt->fused_into.size() ? g->rt->fused_into[v] : -1;
+    for (size_t v = 0; v < g->nodes.size(); ++v)
+        host_of[v] = v >= g->rt->fused_into.size() ? -1 : (g->rt->elided[v] ? -2 : g->rt->fused_into[v]);
     return NG_OK;
 }
 
