@@ -454,6 +454,48 @@ def test_device_resident_fused_add_waits_for_a_late_operand():
         r.close()
 
 
+@pytest.mark.parametrize("shape", [(1, 16, 14, 14), (1, 12, 7, 7), (2, 16, 8, 8)])
+def test_concat_inputs_produced_in_place(shape):
+    """At batch 1 the memory plan places a tensor that one concat takes whole inside the concat's
+    buffer; the concat kernel skips it, and the device-resident replay drops a concat with nothing
+    left to copy (its readers wait for the producers). Covered: a fully in-place concat, one nested
+    inside another, one with a sliced and a repeated input next to an in-place one, the network
+    input as a concat input, readers of the in-place tensors themselves, 7 x 7 planes (block offsets
+    that are multiples of 16 but not of 256 bytes), and batch 2, where nothing may be placed in place.
+    Every tensor in every mode against the oracle; resident and single-stream replays bit for bit."""
+    def build(b):
+        x = b.input(*shape)
+        a, bb, c = b.relu(x), b.bn_act(x, relu=False), b.pool(x, "max", 1, 1)
+        cat1 = b.concat([a, bb, c])                           # all three in place
+        d = b.dwconv(x, 3, 1)
+        cat2 = b.concat([cat1, d])                            # nested: cat1 (with a, bb, c inside) and d in place
+        e = b.relu(d)                                         # d has another reader
+        f = b.conv1x1(cat2, 20)
+        g_ = b.bn_act(f, relu=True)
+        lo = shape[1] // 4
+        cat3 = b.concat([g_, e, e, x], slices=[(0, 20), (lo, 3 * lo), (0, shape[1]), (0, shape[1])])   # g_ in place only
+        h = b.conv1x1(cat3, 24)
+        b.add_n([b.pool(cat1, "avg", 1, 1), cat1])            # readers of the dropped concat on other streams
+        b.concat([b.relu(h), b.bn_act(h, relu=False)])        # a concat nobody reads
+    w = single_op(build)
+    check_all_nodes(w, (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_EAGER_MULTI))
+    ops = [nd.op for nd in w.nodes]
+    cats = [v for v, o in enumerate(ops) if o == "concat"]
+    for xcds in (0, 1, 8):
+        host_of = _resident_vs_single(w, xcds)
+        dropped = [v for v in cats if host_of[v] == -2]
+        if shape[0] == 1:
+            assert cats[0] in dropped and cats[1] in dropped and cats[3] in dropped and cats[2] not in dropped, (xcds, host_of)
+        else:
+            assert not dropped
+    r = GraphRunner(w)
+    r.schedule(); r.plan()
+    off, nbytes = B.ng_get_offsets(r.g)
+    r.close()
+    inside = [v for v in range(len(w.nodes)) if any(off[c] <= off[v] and off[v] + nbytes[v] <= off[c] + nbytes[c] for c in cats if c != v)]
+    assert len(inside) == (8 if shape[0] == 1 else 0), inside
+
+
 def test_device_resident_device_scope_fallback():
     """The fallback the runtime takes when workgroups are not dealt out to XCDs as expected:
     every hand-over through device scope. Same results, bit for bit."""
