@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes of one device-resident replay, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # scaled by what the same counters read for a plain 256 MiB copy (2.00 and 1.00): the
 # summary with the commands is profiles/resident_kernel_nasnet_style.md.
-MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (35263.6 * 2.00 + 47577.4 * 1.00) * 1024}
+MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (28438.2 * 2.00 + 44857.6 * 1.00) * 1024}
 
 MODES = {"graph_multi": 0, "graph_single": 1, "eager_single": 2, "eager_multi": 3, "device_resident": 4}
 MODE_NAMES = {v: k for k, v in MODES.items()}
@@ -210,6 +210,7 @@ def main():
         B.ng_replay(runner.g)
         B.ng_sync(runner.g)
         tr = B.ng_resident_trace(runner.g, 0, fetch=True)
+        host_of = B.ng_resident_fusion(runner.g)
         ran = [v for v in range(n_nodes) if tr[v] is not None]
         if ran:
             v = max(ran, key=lambda u: tr[u][3])
@@ -227,7 +228,8 @@ def main():
                 # tasks executing at the same time: a task counts from the moment its last workgroup is past
                 # the wait until its last workgroup has stored its tiles
                 events = []
-                for u in ran:
+                own = [u for u in ran if host_of[u] == -1]        # the others ran inside a producer's tiles / had nothing to do
+                for u in own:
                     events.append((tr[u][1], 1))
                     events.append((tr[u][3], -1))
                 events.sort()
@@ -236,10 +238,11 @@ def main():
                     hist[level] = hist.get(level, 0.0) + (t_ev - last_t)
                     level += d
                     last_t = t_ev
-                print(f"traced replay: {span:.1f} us, {len(ran)} tasks; time with k tasks executing:", file=sys.stderr)
+                print(f"traced replay: {span:.1f} us, {len(ran)} tasks, {len(own)} of them with workgroups of their own; "
+                      f"time with k of those executing:", file=sys.stderr)
                 for k in sorted(hist):
                     print(f"  k = {k:2d}: {hist[k]:7.1f} us  {100 * hist[k] / span:5.1f} %", file=sys.stderr)
-                busy = sum(tr[u][3] - tr[u][1] for u in ran)
+                busy = sum(tr[u][3] - tr[u][1] for u in own)
                 print(f"  sum of task execution intervals {busy:.1f} us = {busy / span:.2f} tasks executing on average; "
                       f"no task executing (hand-overs only) {hist.get(0, 0.0):.1f} us", file=sys.stderr)
             timeline = {"traced_replay_us": span, "tasks_on_realised_chain": hops, "tile_execution_us": run_us,
@@ -250,6 +253,7 @@ def main():
                                 "the consumer's input-independent prologue"}
 
     n_wg, n_entries, xcds, est_us = B.ng_resident_sizes(runner.g)
+    fusion = B.ng_resident_fusion(runner.g)
     out = {
         "metric": "DAG latency (µs) at batch 1; % of critical-path bound; µs overhead/task",
         "metric_note": "value = wall time of the K timed steps (each: replay + wait) / K, input resident in HBM; "
@@ -261,7 +265,9 @@ def main():
         "config": {"workload": args.config + (f"_b{args.batch}" if args.config == "inception_style" else ""),
                    "input_shape": list(w.input.shape), "tasks": n_tasks, "streams": sched["n_streams"],
                    "sync_edges": sched["n_sync"], "events": sched["n_events"], "replay": args.mode,
-                   "resident_workgroups": n_wg, "resident_xcds": xcds},
+                   "resident_workgroups": n_wg, "resident_xcds": xcds,
+                   "resident_tasks_inside_their_producer": sum(h >= 0 for h in fusion),
+                   "resident_concats_in_place": sum(h == -2 for h in fusion)},
         "latency_us": {"median": t_e2e, "p10": percentile(lat, 0.10), "p90": percentile(lat, 0.90),
                        "device_side": dev_us},
         "throughput_replays_per_s": thr,

@@ -220,7 +220,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         out.ntiles[v] = t.ntiles;
         // a windowed task that would need four or more rounds on its stream's workgroups gets 4 outputs
         // per thread (4 x the index arithmetic in one round: pays off only from there)
-        if (units_for(t.ntiles, kSubs) > 3 * per_xcd && (t.kid == KID_POOL || t.kid == KID_DW_K3S1) &&
+        static const int p4_rounds = getenv("NG_P4_ROUNDS") ? atoi(getenv("NG_P4_ROUNDS")) : 2;
+        if (units_for(t.ntiles, kSubs) > p4_rounds * per_xcd && (t.kid == KID_POOL || t.kid == KID_DW_K3S1) &&
             !getenv("NG_NO_P4")) {
             out.kid[v] = t.kid == KID_POOL ? KID_POOL_P4 : KID_DW_K3S1_P4;
             out.ntiles[v] = (g->nodes[v].out.elems() + 4 * kBlock - 1) / (4 * kBlock);
