@@ -194,3 +194,90 @@ def schedule(n: int, edges: Sequence[Edge]) -> Schedule:
 
     return Schedule(n, reach, meg, matching, chain_of, n_chains, stream_of, n_streams, sync,
                     event_of, n_events, list(range(n)), waits, fork, join, phase3_changed)
+
+
+# ---------------------------------------------------------------------------------------
+# The jointly optimal assignment: fewest streams, and among those fewest synchronisations
+# ---------------------------------------------------------------------------------------
+# Definition (Section 4.2 states the two goals; Appendix A counts synchronisations): a stream
+# assignment with maximum logical concurrency puts two nodes on one stream only if one reaches
+# the other, so every stream is a chain of the closure; the number of streams is at least the
+# widest antichain; a safe plan must synchronise exactly the E' edges whose ends sit on
+# different streams (Lemma 1, Lemma 4). "Exact" = a partition of V into chains that has the
+# fewest chains and, among all such partitions, the fewest cross-chain E' edges.
+
+def _is_chain(nodes: Sequence[int], reach: List[int]) -> bool:
+    nodes = sorted(nodes)
+    return all((reach[a] >> b) & 1 for a, b in zip(nodes, nodes[1:]))
+
+
+def exact_optimum_by_enumeration(n: int, edges: Sequence[Edge]) -> Tuple[int, int]:
+    """(fewest streams, fewest synchronisations at that stream count) by trying every partition
+    of the nodes into sets (tiny n only: Bell(9) = 21147 partitions)."""
+    edges = sorted(set(edges))
+    reach = transitive_closure(n, edges)
+    meg = minimum_equivalent_graph(n, edges, reach)
+    best = None
+
+    def place(v: int, blocks: List[List[int]]):
+        nonlocal best
+        if v == n:
+            label = {}
+            for i, b in enumerate(blocks):
+                for x in b:
+                    label[x] = i
+            key = (len(blocks), sum(label[a] != label[b] for a, b in meg))
+            if best is None or key < best:
+                best = key
+            return
+        for b in blocks:                         # nodes arrive in ascending id: v joins a chain iff its last node reaches v
+            if (reach[b[-1]] >> v) & 1:
+                b.append(v)
+                place(v + 1, blocks)
+                b.pop()
+        blocks.append([v])
+        place(v + 1, blocks)
+        blocks.pop()
+
+    place(0, [])
+    return best
+
+
+def schedule_exact(n: int, edges: Sequence[Edge]) -> Schedule:
+    """Same record as `schedule`, with the streams of the jointly optimal assignment.
+
+    A partition into chains is a set of vertex-disjoint paths in the closure, i.e. a matching of
+    the bipartite graph whose pairs are the closure's (u, v); it has V - |matching| chains, and a
+    same-stream E' edge is always a matched pair (nothing lies between its ends). So the optimum
+    is a maximum matching with as many E' pairs as possible: an assignment problem in which a
+    closure pair is worth V + 1, an E' pair one more, anything else nothing (solved by the
+    library routine scipy.optimize.linear_sum_assignment)."""
+    import numpy as np
+    from scipy.optimize import linear_sum_assignment
+
+    base = schedule(n, edges)
+    reach, meg = base.reach, base.meg
+    worth = np.zeros((n, n), dtype=np.int64)
+    for u in range(n):
+        for v in _bits(reach[u]):
+            worth[u, v] = n + 1
+    for u, v in meg:
+        worth[u, v] += 1
+    rows, cols = linear_sum_assignment(worth, maximize=True)
+    nxt = {int(u): int(v) for u, v in zip(rows, cols) if worth[u, v] > 0}
+    stream_of = _label_chains(n, nxt)
+    n_streams = max(stream_of) + 1 if n else 0
+    sync = [(u, v) for u, v in meg if stream_of[u] != stream_of[v]]
+    event_of = [-1] * n
+    for i, u in enumerate(sorted({u for u, _ in sync})):
+        event_of[u] = i
+    waits = [[] for _ in range(n)]
+    for u, v in sync:
+        waits[v].append(u)
+    first = {}
+    for v in range(n):
+        first.setdefault(stream_of[v], v)
+    fork = sorted(s for s, v in first.items() if s != 0 and not waits[v])
+    join = sorted(s for s in first if s != 0)
+    return Schedule(n, reach, meg, base.matching, base.chain_of, base.n_chains, stream_of, n_streams, sync,
+                    event_of, sum(e >= 0 for e in event_of), list(range(n)), waits, fork, join, False)
