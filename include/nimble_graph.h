@@ -117,6 +117,19 @@ int ng_node_shape(const ng_graph* g, int id, int64_t nchw[4]);
  * Submission order is ascending node id; node 0 is on stream 0, the capture origin. */
 int ng_schedule(ng_graph* g);
 
+/* How ng_schedule forms the streams out of the chains (call before ng_schedule; NG_ESTATE after).
+ *   NG_ASSIGN_ALGORITHM1 (default): as described above - Algorithm 1, chains joined, then the
+ *     augmenting pass. Stream count = widest antichain always; |Lambda| = the minimum of
+ *     Theorem 3, |E'| - |M|, whenever the last pass finds nothing to do.
+ *   NG_ASSIGN_EXACT: the partition into the fewest chains of the closure that, among those,
+ *     keeps the most E' edges inside a stream - a maximum matching of the closure's bipartite
+ *     graph with as many E' edges as possible, found as a minimum-cost assignment (O(V^3)).
+ *     Stream count = widest antichain and |Lambda| = the least any such partition allows, always.
+ *     chain_of (Algorithm 1 verbatim) is the same in both. Which of several optimal partitions
+ *     comes out is unspecified. */
+enum { NG_ASSIGN_ALGORITHM1 = 0, NG_ASSIGN_EXACT = 1 };
+int ng_set_assignment(ng_graph* g, int assignment);
+
 /* Sizes of the arrays ng_get_schedule fills (any pointer may be NULL). */
 int ng_schedule_sizes(const ng_graph* g, int* n_nodes, int* n_streams, int* n_chains,
                       int* n_meg_edges, int* n_matching, int* n_sync, int* n_events);

@@ -16,12 +16,13 @@ NG_OK, NG_EINVAL, NG_ESHAPE, NG_ESTATE, NG_ENOMEM, NG_EHIP = 0, -1, -2, -3, -4, 
 (NG_OP_INPUT, NG_OP_CONV1X1, NG_OP_DWCONV, NG_OP_CONV3X3, NG_OP_BN_ACT, NG_OP_RELU, NG_OP_ADD_N,
  NG_OP_CONCAT, NG_OP_POOL, NG_OP_GLOBAL_AVGPOOL, NG_OP_FC) = range(11)
 NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_EAGER_SINGLE, NG_MODE_EAGER_MULTI, NG_MODE_DEVICE_RESIDENT, NG_MODE_AUTO = range(6)
+NG_ASSIGN_ALGORITHM1, NG_ASSIGN_EXACT = 0, 1
 
 LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnimble_graph.so")
 
 # every symbol include/nimble_graph.h declares
 SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_output", "ng_num_nodes",
-           "ng_node_shape", "ng_schedule", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
+           "ng_node_shape", "ng_schedule", "ng_set_assignment", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
            "ng_plan_memory", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
            "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
@@ -49,6 +50,7 @@ _sig = {
     "ng_num_nodes": (_I, [_P]),
     "ng_node_shape": (_I, [_P, _I, C.POINTER(C.c_int64)]),
     "ng_schedule": (_I, [_P]),
+    "ng_set_assignment": (_I, [_P, _I]),
     "ng_schedule_sizes": (_I, [_P, _IP, _IP, _IP, _IP, _IP, _IP, _IP]),
     "ng_get_schedule": (_I, [_P, _IP, _IP, _IP, _IP, _IP, _IP, _IP, _IP]),
     "ng_get_scaffold": (_I, [_P, _IP, _IP, _IP, _IP]),
@@ -144,6 +146,10 @@ def ng_node_shape(g, node_id):
 
 def ng_schedule(g):
     check(g, lib.ng_schedule(g))
+
+
+def ng_set_assignment(g, assignment: int):
+    check(g, lib.ng_set_assignment(g, assignment))
 
 
 def ng_schedule_sizes(g) -> dict:

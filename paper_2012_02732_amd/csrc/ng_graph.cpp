@@ -196,6 +196,15 @@ int ng_node_shape(const ng_graph* g, int id, int64_t nchw[4]) {
     return NG_OK;
 }
 
+int ng_set_assignment(ng_graph* g, int assignment) {
+    if (!g) return NG_EINVAL;
+    if (g->phase != BUILDING) return g->fail(NG_ESTATE, "ng_set_assignment: already scheduled");
+    if (assignment != NG_ASSIGN_ALGORITHM1 && assignment != NG_ASSIGN_EXACT)
+        return g->fail(NG_EINVAL, "ng_set_assignment: unknown assignment %d", assignment);
+    g->assignment = assignment;
+    return NG_OK;
+}
+
 int ng_schedule(ng_graph* g) {
     if (!g) return NG_EINVAL;
     if (g->phase != BUILDING) return g->fail(NG_ESTATE, "ng_schedule: already scheduled");
@@ -203,7 +212,7 @@ int ng_schedule(ng_graph* g) {
     std::vector<std::pair<int, int>> edges;
     for (int v = 0; v < (int)g->nodes.size(); ++v)
         for (int u : g->nodes[v].preds) edges.emplace_back(u, v);
-    compute_schedule((int)g->nodes.size(), edges, g->sched);
+    compute_schedule((int)g->nodes.size(), edges, g->sched, g->assignment == NG_ASSIGN_EXACT);
     g->phase = SCHEDULED;
     return NG_OK;
 }

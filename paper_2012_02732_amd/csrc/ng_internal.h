@@ -87,6 +87,7 @@ struct ng_graph {
     std::vector<ng::Task> tasks;
     ng::Runtime* rt = nullptr;
     int mode = NG_MODE_GRAPH_MULTI;
+    int assignment = NG_ASSIGN_ALGORITHM1;               // how ng_schedule forms the streams
     int auto_mode = NG_MODE_GRAPH_MULTI;                 // what NG_MODE_AUTO resolves to (set by ng_capture)
     float auto_trial_us[3] = {0, 0, 0};                  // trial medians of modes 0, 1, 4
     int resident_wg_per_cu = 0;                          // 0 = pick automatically
@@ -109,7 +110,7 @@ struct ng_graph {
 
 namespace ng {
 // ng_schedule.cpp
-void compute_schedule(int n, const std::vector<std::pair<int, int>>& edges, Schedule& out);
+void compute_schedule(int n, const std::vector<std::pair<int, int>>& edges, Schedule& out, bool exact);
 // ng_kernels.hip: fill the launch descriptor of node v (addresses resolved against `arena`;
 // `packed` = node v's share of the library-owned constant memory, see packed_floats).
 int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t);

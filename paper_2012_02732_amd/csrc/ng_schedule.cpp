@@ -22,6 +22,7 @@
 //     ascending id; a producer with cross-stream E' successors records one event, each such
 //     successor waits for it before launching.
 #include <algorithm>
+#include <limits>
 #include <cstdint>
 
 #include "ng_internal.h"
@@ -92,7 +93,51 @@ struct Matcher {
 
 }  // namespace
 
-void compute_schedule(int n, const std::vector<std::pair<int, int>>& raw_edges, Schedule& s) {
+namespace {
+
+// Minimum-cost perfect assignment of an n x n integer cost matrix (row-major), O(n^3): the
+// classic potential method - rows are added one at a time, each by a shortest augmenting path
+// over reduced costs. assigned_col[i] = column of row i.
+void assign_min_cost(int n, const std::vector<long>& cost, std::vector<int>& assigned_col) {
+    const long kInf = std::numeric_limits<long>::max() / 4;
+    std::vector<long> pot_row(n + 1, 0), pot_col(n + 1, 0), slack(n + 1);
+    std::vector<int> row_of_col(n + 1, 0), came_from(n + 1, 0);    // 1-based; column 0 is a virtual start
+    std::vector<char> used(n + 1);
+    for (int i = 1; i <= n; ++i) {
+        row_of_col[0] = i;
+        int col = 0;
+        std::fill(slack.begin(), slack.end(), kInf);
+        std::fill(used.begin(), used.end(), 0);
+        do {
+            used[col] = 1;
+            const int row = row_of_col[col];
+            long delta = kInf;
+            int next_col = 0;
+            for (int j = 1; j <= n; ++j) {
+                if (used[j]) continue;
+                const long reduced = cost[(size_t)(row - 1) * n + (j - 1)] - pot_row[row] - pot_col[j];
+                if (reduced < slack[j]) slack[j] = reduced, came_from[j] = col;
+                if (slack[j] < delta) delta = slack[j], next_col = j;
+            }
+            for (int j = 0; j <= n; ++j) {
+                if (used[j]) pot_row[row_of_col[j]] += delta, pot_col[j] -= delta;
+                else slack[j] -= delta;
+            }
+            col = next_col;
+        } while (row_of_col[col] != 0);
+        do {                                                   // flip the path back to the start
+            const int before = came_from[col];
+            row_of_col[col] = row_of_col[before];
+            col = before;
+        } while (col != 0);
+    }
+    assigned_col.assign(n, -1);
+    for (int j = 1; j <= n; ++j) assigned_col[row_of_col[j] - 1] = j - 1;
+}
+
+}  // namespace
+
+void compute_schedule(int n, const std::vector<std::pair<int, int>>& raw_edges, Schedule& s, bool exact) {
     s = Schedule();
     std::vector<std::pair<int, int>> edges = raw_edges;
     std::sort(edges.begin(), edges.end());
@@ -154,6 +199,25 @@ void compute_schedule(int n, const std::vector<std::pair<int, int>>& raw_edges, 
     // Steps 4-5: the merged sets are exactly the paths of the matching.
     s.n_chains = label_paths(s.chain_of);
 
+    if (exact) {
+        // Streams = a partition into the fewest chains of the closure (the widest antichain, Dilworth) that,
+        // among those, keeps the most E' edges inside a stream, i.e. needs the fewest synchronisations
+        // (a same-stream E' edge is always a pair of neighbours on its chain, so it is a matched pair):
+        // a maximum matching of the closure's bipartite graph with as many E' edges as possible. As an
+        // assignment problem: a closure pair costs -(n + 1), an E' pair one less, anything else 0, so one
+        // more matched pair always outweighs any number of E' pairs.
+        std::vector<long> cost((size_t)n * n, 0);
+        for (int u = 0; u < n; ++u)
+            for (int v = u + 1; v < n; ++v)
+                if (reach.get(u, v)) cost[(size_t)u * n + v] = -(long)(n + 1);
+        for (auto& e : s.meg) cost[(size_t)e.first * n + e.second] -= 1;
+        std::vector<int> col;
+        assign_min_cost(n, cost, col);
+        std::fill(next.begin(), next.end(), -1);
+        std::fill(prev.begin(), prev.end(), -1);
+        for (int u = 0; u < n; ++u)
+            if (col[u] > u && reach.get(u, col[u])) next[u] = col[u], prev[col[u]] = u;
+    } else {
     // Join chains: tails (no successor in the matching) to reachable heads (no predecessor).
     {
         std::vector<int> tails;
@@ -177,6 +241,7 @@ void compute_schedule(int n, const std::vector<std::pair<int, int>>& raw_edges, 
         }
         Matcher m(adj3, next, prev);
         m.run(all);
+    }
     }
     s.n_streams = label_paths(s.stream_of);
 

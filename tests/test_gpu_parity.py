@@ -496,6 +496,31 @@ def test_concat_inputs_produced_in_place(shape):
     assert len(inside) == (8 if shape[0] == 1 else 0), inside
 
 
+@pytest.mark.parametrize("seed", [11, 12])
+def test_replay_under_the_exact_stream_assignment(seed):
+    """The jointly optimal assignment (NG_ASSIGN_EXACT) is just another schedule of the same DAG:
+    same stream and synchronisation counts as the oracle's, every tensor right in the multi-stream
+    graph, the plain multi-stream launches and the device-resident replay."""
+    w = workloads.make("random200", seed=seed, n_nodes=80, n_layers=12, max_width=10, shape=(1, 16, 14, 14))
+    ref = forward(w, keep=range(len(w.nodes)))
+    from oracle.schedule import schedule_exact
+    o = schedule_exact(len(w.nodes), w.edges)
+    r = GraphRunner(w, DEV)
+    B.ng_set_assignment(r.g, B.NG_ASSIGN_EXACT)
+    sched = r.prepare()
+    try:
+        assert sched["n_streams"] == o.n_streams and len(sched["sync"]) == len(o.sync)
+        for mode in (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_EAGER_MULTI, B.NG_MODE_DEVICE_RESIDENT):
+            r.arena.zero_()
+            r.set_input(w.input)
+            r.replay(mode)
+            r.sync()
+            for v in range(1, len(w.nodes)):
+                assert rel_err(r.output(v), ref[v]) <= TOL, (mode, v, w.nodes[v].op)
+    finally:
+        r.close()
+
+
 def test_device_resident_device_scope_fallback():
     """The fallback the runtime takes when workgroups are not dealt out to XCDs as expected:
     every hand-over through device scope. Same results, bit for bit."""

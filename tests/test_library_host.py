@@ -9,7 +9,8 @@ import pytest
 
 import workloads
 from workloads.model import Node, Workload
-from oracle.schedule import schedule as oracle_schedule
+from oracle.schedule import schedule as oracle_schedule, schedule_exact as oracle_schedule_exact
+from oracle import checks
 from paper_2012_02732_amd import GraphRunner, binding as B
 from dag_util import random_dag, layered_dag
 
@@ -76,6 +77,67 @@ def test_schedule_parity_on_medium_dags():
         r = GraphRunner(abstract_workload(n, e))
         assert_same_schedule(r.schedule(), B.ng_get_scaffold(r.g), oracle_schedule(n, e))
         r.close()
+
+
+def check_exact_schedule(n, e, lib_sched, scaffold):
+    """The library's exact assignment against the oracle's: several partitions can be optimal, so
+    what is unique is compared (E', Algorithm 1's chains, stream and synchronisation counts) and
+    the rest is checked for validity (streams are chains of the closure, labelled in order of
+    their first node; Lambda = the cross-stream E' edges; events and scaffolding consistent)."""
+    o = oracle_schedule_exact(n, e)
+    assert lib_sched["meg"] == o.meg and lib_sched["n_matching"] == len(o.matching)
+    assert lib_sched["chain_of"] == o.chain_of and lib_sched["n_chains"] == o.n_chains
+    assert lib_sched["n_streams"] == o.n_streams and len(lib_sched["sync"]) == len(o.sync)
+    f = lib_sched["stream_of"]
+    assert checks.has_max_logical_concurrency(n, e, f)
+    firsts = [f.index(st) for st in range(lib_sched["n_streams"])]
+    assert firsts == sorted(firsts) and f[0] == 0 and sorted(set(f)) == list(range(lib_sched["n_streams"]))
+    assert lib_sched["sync"] == [(u, v) for u, v in o.meg if f[u] != f[v]]
+    producers = sorted({u for u, _ in lib_sched["sync"]})
+    assert [lib_sched["event_of"][u] for u in producers] == list(range(len(producers)))
+    assert lib_sched["n_events"] == len(producers) and all((ev >= 0) == (u in producers) for u, ev in enumerate(lib_sched["event_of"]))
+    if n <= 16:                                   # path enumeration: tiny DAGs only
+        assert checks.plan_is_safe(n, e, f, lib_sched["sync"])
+    waits = {v for _, v in lib_sched["sync"]}
+    first_of = {st: f.index(st) for st in range(lib_sched["n_streams"])}
+    assert scaffold == (sorted(st for st, v in first_of.items() if st != 0 and v not in waits),
+                        sorted(st for st in first_of if st != 0))
+
+
+def test_exact_assignment_on_random_tiny_dags_and_the_known_suboptimal_case():
+    rng = np.random.default_rng(321)
+    cases = [(12, [(0, 1), (0, 9), (1, 2), (1, 9), (2, 4), (3, 4), (3, 5), (3, 10), (3, 11), (4, 5), (5, 6),
+                   (5, 11), (7, 9), (7, 11), (8, 10)])]
+    for _ in range(1500):
+        n = int(rng.integers(1, 17))
+        cases.append((n, random_dag(rng, n, float(rng.uniform(0.1, 0.7)))))
+    for n, e in cases:
+        r = GraphRunner(abstract_workload(n, e))
+        B.ng_set_assignment(r.g, B.NG_ASSIGN_EXACT)
+        s = r.schedule()
+        check_exact_schedule(n, e, s, B.ng_get_scaffold(r.g))
+        r.close()
+    r = GraphRunner(abstract_workload(*cases[0]))           # the default procedure on the first case: one more
+    assert len(r.schedule()["sync"]) == 6
+    r.close()
+
+
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_exact_assignment_on_benchmark_configs(name):
+    w = workloads.make(name)
+    r = GraphRunner(w)
+    B.ng_set_assignment(r.g, B.NG_ASSIGN_EXACT)
+    s = r.schedule()
+    check_exact_schedule(len(w.nodes), w.edges, s, B.ng_get_scaffold(r.g))
+    with pytest.raises(B.NgError) as err:
+        B.ng_set_assignment(r.g, B.NG_ASSIGN_ALGORITHM1)    # too late
+    assert err.value.code == B.NG_ESTATE
+    r.close()
+    r = GraphRunner(w)
+    with pytest.raises(B.NgError) as err:
+        B.ng_set_assignment(r.g, 7)
+    assert err.value.code == B.NG_EINVAL
+    r.close()
 
 
 @pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
