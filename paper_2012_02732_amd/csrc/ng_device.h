@@ -43,6 +43,10 @@ constexpr bool is_pool(int kid) { return plain_variant(kid) == KID_POOL || plain
 constexpr bool is_pw16(int kid) { return plain_variant(kid) >= KID_PW_V1 && plain_variant(kid) <= KID_PW_S4; }
 constexpr bool is_c3m(int kid) { return plain_variant(kid) >= KID_C3_M1 && plain_variant(kid) <= KID_C3_M4; }
 constexpr bool has_add_epilogue(int kid) { return plain_variant(kid) != kid; }
+// convolutions whose argument block is a C3Args (the others with a batch-norm epilogue take a PwArgs)
+constexpr bool takes_c3_args(int kid) { return is_c3m(kid) || (kid >= KID_C3_T16S1 && kid <= KID_C3_T8S2); }
+// kernels whose tiles can apply a batch-norm / ReLU to their results before storing them: every convolution
+constexpr bool has_bn_epilogue(int kid) { return is_pw16(kid) || is_c3m(kid) || (kid >= KID_PW_D4 && kid <= KID_C3_T8S2); }
 
 // How a kernel splits its output into tiles (see the elementwise tile functions): only tasks
 // with the same partition of same-shaped outputs have matching tiles.
@@ -177,7 +181,7 @@ struct PwArgs {
     int ksteps;                // 32 x 32 kernels: k-steps of 4 in the packed copy (padded, a multiple of 4 * chunk);
                                // 16-row kernels: groups of 4 k-steps in the packed copy (a multiple of 4 * groups in flight)
     int mtiles;                // direct kernels: ceil(Cout / 16)
-    Epilogue ep;               // 16-row kernels only
+    Epilogue ep;
 };
 struct PwAddArgs : PwArgs {
     AddEpilogue ea;            // applied to the batch-normed value when ep.y is set, else to the convolution result
@@ -198,7 +202,7 @@ struct C3Args {
     int stride;
     int cols;                  // N * Ho * Wo
     int tiles_n;               // ceil(cols / 16)
-    Epilogue ep;               // implicit-GEMM kernels only
+    Epilogue ep;
 };
 struct C3AddArgs : C3Args {
     AddEpilogue ea;

@@ -124,6 +124,20 @@ struct NoWait {
     __device__ __forceinline__ void late() const {}
 };
 
+// Store one convolution result and, if a batch-norm / ReLU task was fused into the tile, that
+// task's result as well (the kernels for larger problems: coefficients are fetched here, per
+// value; the 16-row kernels fetch theirs before they wait for their inputs).
+template <bool FOUT>
+__device__ __forceinline__ void store_with_epilogue(float* y, const Epilogue& ep, size_t at, int channel, float v) {
+    stg(y, y + at, v, FOUT);
+    if (ep.y != nullptr) {
+        float s = 1.f, t = 0.f;
+        if (ep.scale != nullptr) s = ep.scale[channel], t = ep.shift[channel];
+        const float z = fmaf(v, s, t);
+        stg(ep.y, ep.y + at, ep.relu ? fmaxf(z, 0.f) : z, FOUT);
+    }
+}
+
 // The add_n epilogue of a convolution tile: v holds this lane's values (4 consecutive pixels if
 // VEC, else one), `at` their position in the tensors; the sum runs in argument order.
 template <bool VEC, bool FOUT>
@@ -515,7 +529,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
                 const int m = m0 + wm * WM + i * 16 + 4 * (lane >> 4) + r;
                 if (m < a.Cout) {
                     const float b = a.bias ? a.bias[m] : 0.f;
-                    stg(a.y, a.y + ((size_t)img * a.Cout + m) * a.HW + pix, acc[i][j][r] + b, FOUT);
+                    store_with_epilogue<FOUT>(a.y, a.ep, ((size_t)img * a.Cout + m) * a.HW + pix, m, acc[i][j][r] + b);
                 }
             }
         }
@@ -621,7 +635,7 @@ __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, f
             const int m = m0 + ti * 16 + 4 * (lane >> 4) + r;
             if (m < a.Cout && col < a.cols && live) {
                 const float b = a.bias ? a.bias[m] : 0.f;
-                stg(a.y, yb + (size_t)m * a.HW, sum + b, FOUT);
+                store_with_epilogue<FOUT>(a.y, a.ep, (size_t)(yb - a.y) + (size_t)m * a.HW, m, sum + b);
             }
         }
     }
@@ -837,7 +851,8 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     if (oy < a.Ho && ox < a.Wo && live) {
 #pragma unroll
         for (int j = 0; j < CO; ++j)
-            if (co0 + j < a.Cout) stg(a.y, a.y + (((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox, acc[j], FOUT);
+            if (co0 + j < a.Cout)
+                store_with_epilogue<FOUT>(a.y, a.ep, (((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox, co0 + j, acc[j]);
     }
 }
 

@@ -248,21 +248,21 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
                 continue;
             }
         }
-        // A batch-norm / ReLU task whose only producer is a 16-row convolution is not run at all:
-        // the convolution's tiles apply it to their results before they store them (same tile
-        // grid, same arithmetic), and whoever waits for this task waits for the convolution.
+        // A batch-norm / ReLU task whose only producer is a convolution is not run at all: the
+        // convolution's tiles apply it to their results before they store them (same values, same
+        // arithmetic), and whoever waits for this task waits for the convolution.
         if (allow_fuse && allow_local && (g->nodes[v].op == NG_OP_BN_ACT || g->nodes[v].op == NG_OP_RELU) &&
             parents[v].size() == 1 && g->nodes[v].preds.size() == 1 && parents[v][0] == g->nodes[v].preds[0]) {
             const int u = parents[v][0];
-            long nt = 0;
-            const bool conv16 = g->tasks[u].fn && (is_pw16(out.kid[u]) || is_c3m(out.kid[u]));
-            if (conv16 && !fused_child[u] && g->nodes[u].out == g->nodes[v].out &&
-                variant_for(g, v, partition_of(out.kid[u]), &nt) != KID_NONE && nt == out.ntiles[u]) {
+            if (g->tasks[u].fn && has_bn_epilogue(out.kid[u]) && !fused_child[u] && g->nodes[u].out == g->nodes[v].out) {
                 fused_child[u] = 1;
                 out.fused_into[v] = u;
                 out.local_parent[v] = u;
-                out.kid[v] = variant_for(g, v, partition_of(out.kid[u]), &nt);
-                out.ntiles[v] = nt;
+                // an elementwise task behind v may still take over the tile grid (16-row kernels only)
+                long nt = 0;
+                const int kid = variant_for(g, v, partition_of(out.kid[u]), &nt);
+                out.kid[v] = kid != KID_NONE && nt == out.ntiles[u] ? kid : KID_NONE;
+                out.ntiles[v] = out.kid[v] != KID_NONE ? nt : 0;
                 out.subs[v] = out.subs[u];
                 out.xcd[v] = out.xcd[u];
                 wgs[v] = wgs[u];
@@ -518,7 +518,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     for (int v = 0; v < n; ++v) {
         const int u = best.fused_into[v];
         if (u < 0) continue;
-        const bool c3 = is_c3m(best.kid[u]);
+        const bool c3 = takes_c3_args(best.kid[u]);
         if (g->nodes[v].op == NG_OP_ADD_N) {
             const AddArgs* add = reinterpret_cast<const AddArgs*>(g->tasks[v].args);
             AddEpilogue ea{};
@@ -688,17 +688,18 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
                 // grid, comes earlier in the order and carries its coefficients / operands and output address
                 ++n_fused;
                 const int hk = plan.tasks[host].kid;
-                const bool c3 = is_c3m(hk), pw = is_pw16(hk), pool = is_pool(hk);
+                const bool c3 = takes_c3_args(hk), pool = is_pool(hk), pw = !c3 && !pool && has_bn_epilogue(hk);
                 static const Epilogue none{};
                 const Epilogue* ep = c3 ? &reinterpret_cast<const C3Args*>(plan.tasks[host].args)->ep
                                         : pw ? &reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->ep : &none;
                 const AddEpilogue* ea = c3 ? &reinterpret_cast<const C3AddArgs*>(plan.tasks[host].args)->ea
                                            : pool ? &reinterpret_cast<const PoolAddArgs*>(plan.tasks[host].args)->ea
                                                   : &reinterpret_cast<const PwAddArgs*>(plan.tasks[host].args)->ea;
-                ok = ok && (c3 || pw || (pool && g->nodes[v].op == NG_OP_ADD_N)) && hits[v].empty() && plan.tasks[v].n_parents == 0 && plan.fused_into[host] < 0 &&
-                     pos[host] < pos[v] && g->nodes[host].out == g->nodes[v].out &&
-                     partition_of(hk) == partition_of(plan.tasks[v].kid) && plan.tasks[host].ntiles == plan.tasks[v].ntiles &&
-                     (plan.tasks[host].release_far || !plan.tasks[v].release_far);
+                const bool is_add = g->nodes[v].op == NG_OP_ADD_N;
+                ok = ok && (is_add ? add_variant(plain_variant(hk)) != KID_NONE : has_bn_epilogue(hk)) && hits[v].empty() &&
+                     plan.tasks[v].n_parents == 0 && plan.fused_into[host] < 0 && pos[host] < pos[v] &&
+                     g->nodes[host].out == g->nodes[v].out && (plan.tasks[host].release_far || !plan.tasks[v].release_far) &&
+                     (!is_add || (partition_of(hk) == partition_of(plan.tasks[v].kid) && plan.tasks[host].ntiles == plan.tasks[v].ntiles));
                 if (g->nodes[v].op == NG_OP_ADD_N) {
                     ok = ok && has_add_epilogue(hk);
                     const AddArgs* add = reinterpret_cast<const AddArgs*>(plan.tasks[v].args);
@@ -767,8 +768,8 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
         for (size_t u = 0; u < n; ++u) {
             const int k = plan.tasks[u].kid;
             if (!g->tasks[u].fn) continue;
-            const bool c3 = is_c3m(k), pw = is_pw16(k);
-            ok = ok && fused_bns[u] <= 1 && fused_adds[u] <= 1 && (c3 || pw || fused_bns[u] == 0) && (c3 || pw || is_pool(k) || fused_adds[u] == 0) &&
+            const bool c3 = takes_c3_args(k), pw = !c3 && has_bn_epilogue(k);
+            ok = ok && fused_bns[u] <= 1 && fused_adds[u] <= 1 && (c3 || pw || fused_bns[u] == 0) && (add_variant(plain_variant(k)) != KID_NONE || fused_adds[u] == 0) &&
                  (fused_adds[u] == 1 || plan.tasks[u].n_late == 0) && plan.tasks[u].n_late <= (unsigned)plan.tasks[u].n_parents;
             ok = ok && has_add_epilogue(k) == (fused_adds[u] == 1);
             if (c3) ok = ok && (reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
