@@ -153,6 +153,16 @@ int ng_get_scaffold(const ng_graph* g, int* fork, int* n_fork, int* join, int* n
  * placed inside the concat's buffer, at its channel block (16-byte aligned), so it is produced
  * in place and the concat copies nothing for it. *arena_bytes receives the total. */
 int ng_plan_memory(ng_graph* g, size_t* arena_bytes);
+/* Reuse over time, off by default (call before ng_plan_memory). When on, a tensor's buffer may be
+ * handed to a later node v once the tensor is dead FOR v: its producer and every one of its
+ * readers are ancestors of v in the DAG, so that any execution that respects the DAG - on any
+ * number of streams - is through with it before v writes. Best fit among such buffers, else new
+ * memory. Network inputs, outputs and the tensors of in-place concats keep private buffers.
+ * The device-resident replay keeps XCD-private L2 lines dirty across tasks and cannot run on such
+ * a plan: ng_capture then prepares the HIP-graph and plain-launch modes only, NG_MODE_AUTO
+ * chooses between the two graphs, and selecting NG_MODE_DEVICE_RESIDENT makes ng_replay fail
+ * with NG_ESTATE. */
+int ng_set_memory_reuse(ng_graph* g, int on);
 /* offset[n_nodes], bytes[n_nodes] of each node's output inside the arena (host arrays). */
 int ng_get_offsets(const ng_graph* g, size_t* offset, size_t* bytes);
 

@@ -23,7 +23,7 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnimble_g
 # every symbol include/nimble_graph.h declares
 SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_output", "ng_num_nodes",
            "ng_node_shape", "ng_schedule", "ng_set_assignment", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
-           "ng_plan_memory", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
+           "ng_plan_memory", "ng_set_memory_reuse", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
            "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
@@ -55,6 +55,7 @@ _sig = {
     "ng_get_schedule": (_I, [_P, _IP, _IP, _IP, _IP, _IP, _IP, _IP, _IP]),
     "ng_get_scaffold": (_I, [_P, _IP, _IP, _IP, _IP]),
     "ng_plan_memory": (_I, [_P, _SZP]),
+    "ng_set_memory_reuse": (_I, [_P, _I]),
     "ng_get_offsets": (_I, [_P, _SZP, _SZP]),
     "ng_critical_path": (_I, [_P, _FP, _FP, _IP, _IP]),
     "ng_bind": (_I, [_P, _P, C.c_size_t, C.POINTER(_P), _I]),
@@ -146,6 +147,10 @@ def ng_node_shape(g, node_id):
 
 def ng_schedule(g):
     check(g, lib.ng_schedule(g))
+
+
+def ng_set_memory_reuse(g, on: bool):
+    check(g, lib.ng_set_memory_reuse(g, int(bool(on))))
 
 
 def ng_set_assignment(g, assignment: int):

@@ -296,17 +296,64 @@ int ng_plan_memory(ng_graph* g, size_t* arena_bytes) {
             }
         }
     size_t top = 0;
-    for (size_t v = 0; v < n; ++v) {            // one private buffer per remaining node output, 256-byte aligned
+    // Reuse over time (optional): a buffer whose tensor is dead can hold a later tensor. With several
+    // streams "dead" cannot mean "earlier in the submission order": tensor z is dead for node v only if
+    // z's producer and every reader of z are ancestors of v, because only then does every execution
+    // that respects the DAG - whatever runs beside whatever - finish them before v starts to write.
+    // Network inputs and outputs and the tensors of in-place concats keep private buffers.
+    std::vector<std::vector<uint64_t>> anc;     // anc[v]: bit u set iff u is a strict ancestor of v
+    std::vector<std::vector<int>> readers(n);
+    std::vector<char> shares(n, 0);             // takes part in an in-place concat (as input or as the concat)
+    struct Block { size_t offset, bytes; int owner; };
+    std::vector<Block> blocks;                  // buffers that may be handed on, with their latest owner
+    if (g->memory_reuse) {
+        const size_t words = (n + 63) / 64;
+        anc.assign(n, std::vector<uint64_t>(words, 0));
+        for (size_t v = 0; v < n; ++v)
+            for (int u : g->nodes[v].preds) {
+                readers[u].push_back((int)v);
+                anc[v][u / 64] |= 1ull << (u % 64);
+                for (size_t w = 0; w < words; ++w) anc[v][w] |= anc[u][w];
+            }
+        for (size_t v = 0; v < n; ++v)
+            if (g->alias_of[v] >= 0) shares[v] = shares[g->alias_of[v]] = 1;
+    }
+    auto dead_for = [&](int z, size_t v) {
+        if (!((anc[v][z / 64] >> (z % 64)) & 1)) return false;
+        for (int r : readers[z])
+            if (!((anc[v][r / 64] >> (r % 64)) & 1)) return false;
+        return true;
+    };
+    for (size_t v = 0; v < n; ++v) {            // one buffer per remaining node output, 256-byte aligned
         g->bytes[v] = (size_t)g->nodes[v].out.elems() * sizeof(float);
         if (g->alias_of[v] >= 0) continue;
+        const size_t need = (g->bytes[v] + 255) & ~(size_t)255;
+        const bool own = !g->memory_reuse || g->nodes[v].op == NG_OP_INPUT || g->nodes[v].is_output || shares[v];
+        int pick = -1;
+        if (!own)                               // the smallest handed-on buffer that is large enough and dead for v
+            for (size_t b = 0; b < blocks.size(); ++b)
+                if (blocks[b].bytes >= need && (pick < 0 || blocks[b].bytes < blocks[pick].bytes) && dead_for(blocks[b].owner, v)) pick = (int)b;
+        if (pick >= 0) {
+            g->offset[v] = blocks[pick].offset;
+            blocks[pick].owner = (int)v;
+            continue;
+        }
         g->offset[v] = top;
-        top += (g->bytes[v] + 255) & ~(size_t)255;
+        top += need;
+        if (!own) blocks.push_back(Block{g->offset[v], need, (int)v});
     }
     for (size_t v = n; v-- > 0;)                // a concat has a higher id than its inputs: its own place is final by now
         if (g->alias_of[v] >= 0) g->offset[v] = g->offset[g->alias_of[v]] + inside[v];
     g->arena_bytes = top;
     g->phase = PLANNED;
     if (arena_bytes) *arena_bytes = top;
+    return NG_OK;
+}
+
+int ng_set_memory_reuse(ng_graph* g, int on) {
+    if (!g) return NG_EINVAL;
+    if (g->phase > SCHEDULED) return g->fail(NG_ESTATE, "ng_set_memory_reuse: the memory plan is already made");
+    g->memory_reuse = on != 0;
     return NG_OK;
 }
 

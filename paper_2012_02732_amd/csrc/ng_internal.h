@@ -88,6 +88,7 @@ struct ng_graph {
     ng::Runtime* rt = nullptr;
     int mode = NG_MODE_GRAPH_MULTI;
     int assignment = NG_ASSIGN_ALGORITHM1;               // how ng_schedule forms the streams
+    bool memory_reuse = false;                           // ng_plan_memory may give a dead tensor's buffer to a later one
     int auto_mode = NG_MODE_GRAPH_MULTI;                 // what NG_MODE_AUTO resolves to (set by ng_capture)
     float auto_trial_us[3] = {0, 0, 0};                  // trial medians of modes 0, 1, 4
     int resident_wg_per_cu = 0;                          // 0 = pick automatically

@@ -364,7 +364,8 @@ int ng_capture(ng_graph* g) {
     }
     if (int rc = record_multi(g, 0)) return rc;
     if (int rc = capture_single(g, 1)) return rc;
-    if (!rt.d_records)
+    // (a memory plan with reuse over time rules the device-resident replay out, see ng_set_memory_reuse)
+    if (!rt.d_records && !g->memory_reuse)
         if (int rc = build_resident(g)) return rc;
     // the pre-run itself: execute the recorded schedule once so that every kernel is loaded
     NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
@@ -375,7 +376,7 @@ int ng_capture(ng_graph* g) {
         const int candidates[3] = {NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_DEVICE_RESIDENT};
         const int saved = g->mode;
         float best = 0;
-        for (int i = 0; i < 3; ++i) {
+        for (int i = 0; i < (g->memory_reuse ? 2 : 3); ++i) {
             g->mode = candidates[i];
             std::vector<float> us;
             for (int rep = 0; rep < 2 + 9; ++rep) {

@@ -521,6 +521,39 @@ def test_replay_under_the_exact_stream_assignment(seed):
         r.close()
 
 
+@pytest.mark.parametrize("name", ["chain50", "random200", "nasnet_style", "inception_style"])
+def test_replay_on_a_memory_plan_with_reuse(name):
+    """Buffers handed on to later tensors (ng_set_memory_reuse): the network outputs must come out
+    right in both HIP-graph modes and both plain-launch modes, on fresh inputs and repeatedly -
+    10 streams (nasnet_style) or 75 (random200) run side by side on the shared buffers. The
+    device-resident replay is not available on such a plan and says so."""
+    w = workloads.make(name)
+    r = GraphRunner(w, DEV)
+    B.ng_set_memory_reuse(r.g, True)
+    r.prepare()
+    try:
+        rng = np.random.default_rng(5)
+        for trial in range(2):
+            x = w.input if trial == 0 else rng.standard_normal(w.input.shape).astype(np.float32)
+            ref = forward(w, x=x) if trial else forward(w)
+            for mode in (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_EAGER_MULTI, B.NG_MODE_EAGER_SINGLE, B.NG_MODE_AUTO):
+                r.arena.zero_()
+                r.set_input(x)
+                for _ in range(2):
+                    r.replay(mode)
+                    r.sync()
+                for v in w.outputs:
+                    assert rel_err(r.output(v), ref[v]) <= TOL, (name, trial, mode, v)
+        mode, _ = B.ng_auto_mode(r.g)
+        assert mode in (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_GRAPH_SINGLE)
+        B.ng_replay_mode(r.g, B.NG_MODE_DEVICE_RESIDENT)
+        with pytest.raises(B.NgError) as err:
+            B.ng_replay(r.g)
+        assert err.value.code == B.NG_ESTATE
+    finally:
+        r.close()
+
+
 def test_device_resident_device_scope_fallback():
     """The fallback the runtime takes when workgroups are not dealt out to XCDs as expected:
     every hand-over through device scope. Same results, bit for bit."""

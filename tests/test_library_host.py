@@ -11,6 +11,7 @@ import workloads
 from workloads.model import Node, Workload
 from oracle.schedule import schedule as oracle_schedule, schedule_exact as oracle_schedule_exact
 from oracle import checks
+from oracle.memory import plan_is_safe as memory_plan_is_safe
 from paper_2012_02732_amd import GraphRunner, binding as B
 from dag_util import random_dag, layered_dag
 
@@ -174,6 +175,74 @@ def test_configs_shapes_schedule_and_plan(name):
     if name == "inception_style" and w.nodes[0].shape[0] > 1:
         assert not inside
     r.close()
+
+
+def _in_place(w, off):
+    """Pairs (tensor, concat) the plan nests on purpose: the tensor sits at its channel block."""
+    pairs = set()
+    for c, nd in enumerate(w.nodes):
+        if nd.op != "concat":
+            continue
+        first = 0
+        for p, lo, hi in zip(nd.preds, nd.params["lo"], nd.params["hi"]):
+            if off[p] == off[c] + 4 * first * nd.shape[2] * nd.shape[3] and (lo, hi) == (0, w.nodes[p].shape[1]):
+                pairs.add((p, c))
+            first += hi - lo
+    return pairs
+
+
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_memory_reuse_plan_is_safe_on_any_number_of_streams(name):
+    """With reuse switched on the arena shrinks, and the oracle's reachability check passes: two
+    tensors share bytes only if everything that touches the one is an ancestor of the producer of
+    the other (or they are a concat and an input produced in place inside it)."""
+    w = workloads.make(name)
+    n = len(w.nodes)
+    r = GraphRunner(w); r.schedule(); private = r.plan(); r.close()
+    r = GraphRunner(w)
+    B.ng_set_memory_reuse(r.g, True)
+    r.schedule()
+    total = r.plan()
+    off, nbytes = B.ng_get_offsets(r.g)
+    assert nbytes == [4 * int(np.prod(nd.shape)) for nd in w.nodes]
+    assert all(o % 16 == 0 and o + b <= total for o, b in zip(off, nbytes))
+    nested = _in_place(w, off)
+    closure = set(nested)
+    for a, c in list(nested):                     # nesting is transitive (a concat inside a concat), and siblings never overlap
+        for c2, c3 in nested:
+            if c2 == c:
+                closure.add((a, c3))
+    keep = [0] + list(w.outputs)
+    ok = memory_plan_is_safe(n, w.edges, off, nbytes, keep,
+                             nested_ok=lambda a, b: (a, b) in closure or (b, a) in closure)
+    assert ok
+    assert total <= private
+    print(f"{name}: arena {private / 1e6:.2f} MB -> {total / 1e6:.2f} MB with reuse")
+    if name in ("chain50", "nasnet_style", "inception_style"):   # deep networks: most tensors die early (a 75-wide random DAG has few ancestors to inherit from)
+        assert total < 0.5 * private, (total, private)
+    with pytest.raises(B.NgError) as err:
+        B.ng_set_memory_reuse(r.g, False)         # too late
+    assert err.value.code == B.NG_ESTATE
+    r.close()
+
+
+def test_memory_reuse_on_random_dags():
+    rng = np.random.default_rng(99)
+    shrunk = 0
+    for _ in range(300):
+        n = int(rng.integers(2, 40))
+        e = random_dag(rng, n, float(rng.uniform(0.05, 0.5)))
+        w = abstract_workload(n, e)
+        r = GraphRunner(w)
+        B.ng_set_memory_reuse(r.g, True)
+        r.schedule()
+        total = r.plan()
+        off, nbytes = B.ng_get_offsets(r.g)
+        keep = [v for v in range(n) if not any(b == v for _, b in e)] + [n - 1]   # the inputs and the marked output
+        assert memory_plan_is_safe(n, e, off, nbytes, keep)
+        shrunk += total < 256 * n
+        r.close()
+    assert shrunk > 100
 
 
 def test_batch_changes_shapes_not_schedule():
