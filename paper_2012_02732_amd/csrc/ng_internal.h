@@ -122,6 +122,7 @@ const void* empty_kernel_handle();
 const void* xcd_probe_kernel_handle();
 // ng_resident_plan.cpp: xcds = 0 lets the cost model choose among 1, 2, 4, 8.
 int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan);
+bool resident_plan_is_consistent(const ng_graph* g, const ResidentPlan& plan);
 // ng_runtime.hip
 void destroy_runtime(ng_graph* g);
 }  // namespace ng

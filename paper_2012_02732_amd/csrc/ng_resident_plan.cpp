@@ -220,7 +220,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         out.ntiles[v] = t.ntiles;
         // a windowed task that would need four or more rounds on its stream's workgroups gets 4 outputs
         // per thread (4 x the index arithmetic in one round: pays off only from there)
-        static const int p4_rounds = getenv("NG_P4_ROUNDS") ? atoi(getenv("NG_P4_ROUNDS")) : 2;
+        const int p4_rounds = getenv("NG_P4_ROUNDS") ? atoi(getenv("NG_P4_ROUNDS")) : 2;
         if (units_for(t.ntiles, kSubs) > p4_rounds * per_xcd && (t.kid == KID_POOL || t.kid == KID_DW_K3S1) &&
             !getenv("NG_NO_P4")) {
             out.kid[v] = t.kid == KID_POOL ? KID_POOL_P4 : KID_DW_K3S1_P4;
@@ -287,7 +287,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
             const std::vector<int>& preds = g->nodes[v].preds;
             int host = -1, via = -1;
             // first choice: a host on the XCD of the add_n's own stream, where its readers most likely are
-            static const int far_host = getenv("NG_FUSE_ADD_FAR") ? atoi(getenv("NG_FUSE_ADD_FAR")) : 1;
+            const int far_host = getenv("NG_FUSE_ADD_FAR") ? atoi(getenv("NG_FUSE_ADD_FAR")) : 1;
             for (int pass = 0; pass < 1 + far_host && host < 0; ++pass)
             for (int w : parents[v]) {
                 const int u = out.fused_into[w] >= 0 ? out.fused_into[w] : w;
@@ -592,6 +592,176 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
 
 }  // namespace ng
 
+namespace ng {
+
+// Self-check of a device-resident plan against the graph it was made for; true if it holds.
+bool resident_plan_is_consistent(const ng_graph* g, const ResidentPlan& plan) {
+    // invariants: every tile of every task is covered exactly once, lists ascend in task id,
+    // the completions a consumer expects equal the workgroups its producer was split over,
+    // and an E' parent that is not waited for has the same tiles on the same workgroups
+    bool ok = true;
+    const size_t n = g->nodes.size();
+    std::vector<std::vector<int>> hits(n);
+    std::vector<unsigned> parts(n, 0);
+    std::vector<std::vector<long>> where(n);              // (workgroup, first unit, step, subs) per task
+    std::vector<int> subs_of(n, 0);
+    for (const DevEntry& en : plan.entries) {
+        ok = ok && en.subs >= 1 && en.subs <= kSubs && (subs_of[en.task] == 0 || subs_of[en.task] == en.subs);
+        subs_of[en.task] = std::min(std::max(en.subs, 1), kSubs);
+    }
+    auto units_of = [&](int v) { return ((long)plan.tasks[v].ntiles + subs_of[v] - 1) / std::max(subs_of[v], 1); };
+    // every list follows one common order of the tasks in which parents come first
+    std::vector<int> pos(n, -1);
+    for (size_t i = 0; i < plan.order.size(); ++i) {
+        const int v = plan.order[i];
+        ok = ok && v >= 0 && v < (int)n && g->tasks[v].fn && pos[v] < 0;
+        if (v >= 0 && v < (int)n) pos[v] = (int)i;
+    }
+    for (size_t v = 0; v < n; ++v) ok = ok && ((pos[v] >= 0) == (g->tasks[v].fn != nullptr));
+    for (auto& e : g->sched.meg)
+        if (g->tasks[e.first].fn && g->tasks[e.second].fn) ok = ok && pos[e.first] < pos[e.second];
+    for (int w = 0; w < plan.n_wg && ok; ++w) {
+        int last = -1;
+        for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
+            const DevEntry& en = plan.entries[e];
+            ok = ok && pos[en.task] > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step &&
+                 en.tile_begin < units_of(en.task);       // at least one round of tiles: the entry's wait is inside its tile function
+            last = pos[en.task];
+            ++parts[en.task];
+            where[en.task].insert(where[en.task].end(), {(long)w, (long)en.tile_begin, (long)en.tile_step, (long)en.subs});
+            if (hits[en.task].empty()) hits[en.task].assign((size_t)units_of(en.task), 0);
+            for (long t = en.tile_begin; t < units_of(en.task); t += en.tile_step) ++hits[en.task][(size_t)t];
+        }
+    }
+    // increments of the device-scope counter a waiter may expect: one per participant, or with
+    // two-level completion one per XCD on which the task has participants
+    std::vector<unsigned> signals(n, 0);
+    {
+        std::vector<std::vector<int>> on_xcd(n, std::vector<int>(8, 0));
+        for (int w = 0; w < plan.n_wg; ++w)
+            for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) ++on_xcd[plan.entries[e].task][w % 8];
+        for (int w = 0; w < plan.n_wg; ++w)
+            for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
+                const DevEntry& en = plan.entries[e];
+                const bool two_level = (plan.tasks[en.task].publish & 4u) != 0;
+                ok = ok && (en.xcd_peers == 0 || en.xcd_peers == on_xcd[en.task][w % 8]) && (!two_level || en.xcd_peers > 0);
+            }
+        for (size_t v = 0; v < n; ++v) {
+            int used = 0;
+            for (int x = 0; x < 8; ++x) used += on_xcd[v][x] > 0;
+            signals[v] = (plan.tasks[v].publish & 4u) ? (unsigned)used : parts[v];
+        }
+    }
+    int n_local = 0, n_fused = 0, n_elided = 0;
+    std::vector<int> fused_bns(n, 0), fused_adds(n, 0);
+    for (size_t v = 0; v < n; ++v) {
+        if (!g->tasks[v].fn) continue;
+        if (plan.elided[v]) {
+            // an in-place concat: every input lives inside its result, no entries, no waits
+            ++n_elided;
+            ok = ok && g->nodes[v].op == NG_OP_CONCAT && hits[v].empty() && plan.tasks[v].n_parents == 0 && plan.fused_into[v] < 0;
+            for (int u : g->nodes[v].preds) ok = ok && g->alias_of[u] == (int)v && pos[u] < pos[v];
+            continue;
+        }
+        const int host = plan.fused_into[v];
+        if (host >= 0) {
+            // a fused task has no entries and no waits of its own; its convolution covers the same tile
+            // grid, comes earlier in the order and carries its coefficients / operands and output address
+            ++n_fused;
+            const int hk = plan.tasks[host].kid;
+            const bool c3 = takes_c3_args(hk), pool = is_pool(hk), pw = !c3 && !pool && has_bn_epilogue(hk);
+            static const Epilogue none{};
+            const Epilogue* ep = c3 ? &reinterpret_cast<const C3Args*>(plan.tasks[host].args)->ep
+                                    : pw ? &reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->ep : &none;
+            const AddEpilogue* ea = c3 ? &reinterpret_cast<const C3AddArgs*>(plan.tasks[host].args)->ea
+                                       : pool ? &reinterpret_cast<const PoolAddArgs*>(plan.tasks[host].args)->ea
+                                              : &reinterpret_cast<const PwAddArgs*>(plan.tasks[host].args)->ea;
+            const bool is_add = g->nodes[v].op == NG_OP_ADD_N;
+            ok = ok && (is_add ? add_variant(plain_variant(hk)) != KID_NONE : has_bn_epilogue(hk)) && hits[v].empty() &&
+                 plan.tasks[v].n_parents == 0 && plan.fused_into[host] < 0 && pos[host] < pos[v] &&
+                 g->nodes[host].out == g->nodes[v].out && (plan.tasks[host].release_far || !plan.tasks[v].release_far) &&
+                 (!is_add || (partition_of(hk) == partition_of(plan.tasks[v].kid) && plan.tasks[host].ntiles == plan.tasks[v].ntiles));
+            if (g->nodes[v].op == NG_OP_ADD_N) {
+                ok = ok && has_add_epilogue(hk);
+                const AddArgs* add = reinterpret_cast<const AddArgs*>(plan.tasks[v].args);
+                const float* held = ep->y != nullptr ? ep->y
+                                    : c3 ? reinterpret_cast<const C3Args*>(plan.tasks[host].args)->y
+                                         : pool ? reinterpret_cast<const PoolArgs*>(plan.tasks[host].args)->y
+                                                : reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->y;
+                ok = ok && ea->y == add->y && ea->k == add->k && add->k >= 2 && add->k <= kEpilogueAddMax && ea->zpos >= 0 &&
+                     ea->zpos < add->k && (ea->far != 0) == (plan.tasks[v].far_in != 0);
+                int q = 0, late = 0;
+                for (int j = 0; j < add->k && ok; ++j) {
+                    if (j == ea->zpos) ok = add->x[j] == held;
+                    else ok = ea->x[q++] == add->x[j];
+                }
+                // every E' parent of the add_n other than the fused operand is awaited late by the convolution
+                for (auto& e : g->sched.meg)
+                    if (e.second == (int)v && g->tasks[e.first].fn) {
+                        const int src = plan.fused_into[e.first] >= 0 ? plan.fused_into[e.first] : e.first;
+                        if (src == host) continue;
+                        ++late;
+                        const DevTask& h = plan.tasks[host];
+                        ok = ok && !plan.elided[src] && std::find(h.parent, h.parent + h.n_parents, src) != h.parent + h.n_parents;
+                    }
+                ok = ok && late >= (int)plan.tasks[host].n_late;
+                ++fused_adds[host];
+            } else {
+                const BnArgs* bn = reinterpret_cast<const BnArgs*>(plan.tasks[v].args);
+                ok = ok && g->nodes[v].preds.size() == 1 && g->nodes[v].preds[0] == host && ep->y == bn->y &&
+                     ep->scale == bn->scale && ep->shift == bn->shift && ep->relu == bn->relu;
+                ++fused_bns[host];
+            }
+            continue;
+        }
+        ok = ok && plan.tasks[v].ntiles > 0 && hits[v].size() == (size_t)units_of((int)v);
+        for (int h : hits[v]) ok = ok && h == 1;
+        const DevTask& d = plan.tasks[v];
+        for (int j = 0; j < d.n_parents; ++j) ok = ok && pos[d.parent[j]] < pos[v] && d.need[j] == signals[d.parent[j]] && parts[d.parent[j]] > 0;
+    }
+    for (auto& e : g->sched.meg) {
+        const int u = e.first, v = e.second;
+        if (!g->tasks[u].fn || !g->tasks[v].fn) continue;
+        if (plan.elided[v]) continue;                                              // waits for nothing
+        const int dst = plan.fused_into[v] >= 0 ? plan.fused_into[v] : v;         // whose workgroups wait for it
+        const DevTask& d = plan.tasks[dst];
+        // whose workgroups store u's result: u, its host, or (in-place concat) those of its E' parents
+        std::vector<int> sources;
+        std::function<void(int)> expand = [&](int t) {
+            if (plan.elided[t]) {
+                for (auto& f : g->sched.meg)
+                    if (f.second == t && g->tasks[f.first].fn) expand(f.first);
+            } else {
+                sources.push_back(plan.fused_into[t] >= 0 ? plan.fused_into[t] : t);
+            }
+        };
+        expand(u);
+        for (int src : sources) {
+            if (src == dst) continue;                                             // fused pair, checked above
+            if (std::find(d.parent, d.parent + d.n_parents, src) != d.parent + d.n_parents) continue;
+            ++n_local;
+            const int part = partition_of(plan.tasks[u].kid);
+            ok = ok && !plan.elided[u] && plan.fused_into[v] < 0 && part != PART_NONE && part == partition_of(d.kid) &&
+                 plan.tasks[u].ntiles == d.ntiles && g->nodes[u].out == g->nodes[v].out && where[src] == where[v];
+        }
+    }
+    // epilogues are there exactly where a task was fused; late parents only with a fused add_n
+    for (size_t u = 0; u < n; ++u) {
+        const int k = plan.tasks[u].kid;
+        if (!g->tasks[u].fn) continue;
+        const bool c3 = takes_c3_args(k), pw = !c3 && has_bn_epilogue(k);
+        ok = ok && fused_bns[u] <= 1 && fused_adds[u] <= 1 && (c3 || pw || fused_bns[u] == 0) && (add_variant(plain_variant(k)) != KID_NONE || fused_adds[u] == 0) &&
+             (fused_adds[u] == 1 || plan.tasks[u].n_late == 0) && plan.tasks[u].n_late <= (unsigned)plan.tasks[u].n_parents;
+        ok = ok && has_add_epilogue(k) == (fused_adds[u] == 1);
+        if (c3) ok = ok && (reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
+        if (pw) ok = ok && (reinterpret_cast<const PwArgs*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
+    }
+    if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d, fused: %d, concats in place: %d, self-check %s\n", n_local, n_fused, n_elided, ok ? "passed" : "FAILED");
+    return ok;
+}
+
+}  // namespace ng
+
 extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, double* expected_us, int* n_entries,
                                     int* n_far_edges, int* coverage_ok) {
     using namespace ng;
@@ -615,167 +785,7 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
         int far = 0;
         for (auto& t : plan.tasks) far += __builtin_popcount(t.far_in);
         if (n_far_edges) *n_far_edges = far;
-        // invariants: every tile of every task is covered exactly once, lists ascend in task id,
-        // the completions a consumer expects equal the workgroups its producer was split over,
-        // and an E' parent that is not waited for has the same tiles on the same workgroups
-        bool ok = true;
-        const size_t n = g->nodes.size();
-        std::vector<std::vector<int>> hits(n);
-        std::vector<unsigned> parts(n, 0);
-        std::vector<std::vector<long>> where(n);              // (workgroup, first unit, step, subs) per task
-        std::vector<int> subs_of(n, 0);
-        for (const DevEntry& en : plan.entries) {
-            ok = ok && en.subs >= 1 && en.subs <= kSubs && (subs_of[en.task] == 0 || subs_of[en.task] == en.subs);
-            subs_of[en.task] = std::min(std::max(en.subs, 1), kSubs);
-        }
-        auto units_of = [&](int v) { return ((long)plan.tasks[v].ntiles + subs_of[v] - 1) / std::max(subs_of[v], 1); };
-        // every list follows one common order of the tasks in which parents come first
-        std::vector<int> pos(n, -1);
-        for (size_t i = 0; i < plan.order.size(); ++i) {
-            const int v = plan.order[i];
-            ok = ok && v >= 0 && v < (int)n && g->tasks[v].fn && pos[v] < 0;
-            if (v >= 0 && v < (int)n) pos[v] = (int)i;
-        }
-        for (size_t v = 0; v < n; ++v) ok = ok && ((pos[v] >= 0) == (g->tasks[v].fn != nullptr));
-        for (auto& e : g->sched.meg)
-            if (g->tasks[e.first].fn && g->tasks[e.second].fn) ok = ok && pos[e.first] < pos[e.second];
-        for (int w = 0; w < plan.n_wg && ok; ++w) {
-            int last = -1;
-            for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
-                const DevEntry& en = plan.entries[e];
-                ok = ok && pos[en.task] > last && en.tile_step > 0 && en.tile_begin >= 0 && en.tile_begin < en.tile_step &&
-                     en.tile_begin < units_of(en.task);       // at least one round of tiles: the entry's wait is inside its tile function
-                last = pos[en.task];
-                ++parts[en.task];
-                where[en.task].insert(where[en.task].end(), {(long)w, (long)en.tile_begin, (long)en.tile_step, (long)en.subs});
-                if (hits[en.task].empty()) hits[en.task].assign((size_t)units_of(en.task), 0);
-                for (long t = en.tile_begin; t < units_of(en.task); t += en.tile_step) ++hits[en.task][(size_t)t];
-            }
-        }
-        // increments of the device-scope counter a waiter may expect: one per participant, or with
-        // two-level completion one per XCD on which the task has participants
-        std::vector<unsigned> signals(n, 0);
-        {
-            std::vector<std::vector<int>> on_xcd(n, std::vector<int>(8, 0));
-            for (int w = 0; w < plan.n_wg; ++w)
-                for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) ++on_xcd[plan.entries[e].task][w % 8];
-            for (int w = 0; w < plan.n_wg; ++w)
-                for (int e = plan.wg_first[w]; e < plan.wg_first[w + 1]; ++e) {
-                    const DevEntry& en = plan.entries[e];
-                    const bool two_level = (plan.tasks[en.task].publish & 4u) != 0;
-                    ok = ok && (en.xcd_peers == 0 || en.xcd_peers == on_xcd[en.task][w % 8]) && (!two_level || en.xcd_peers > 0);
-                }
-            for (size_t v = 0; v < n; ++v) {
-                int used = 0;
-                for (int x = 0; x < 8; ++x) used += on_xcd[v][x] > 0;
-                signals[v] = (plan.tasks[v].publish & 4u) ? (unsigned)used : parts[v];
-            }
-        }
-        int n_local = 0, n_fused = 0, n_elided = 0;
-        std::vector<int> fused_bns(n, 0), fused_adds(n, 0);
-        for (size_t v = 0; v < n; ++v) {
-            if (!g->tasks[v].fn) continue;
-            if (plan.elided[v]) {
-                // an in-place concat: every input lives inside its result, no entries, no waits
-                ++n_elided;
-                ok = ok && g->nodes[v].op == NG_OP_CONCAT && hits[v].empty() && plan.tasks[v].n_parents == 0 && plan.fused_into[v] < 0;
-                for (int u : g->nodes[v].preds) ok = ok && g->alias_of[u] == (int)v && pos[u] < pos[v];
-                continue;
-            }
-            const int host = plan.fused_into[v];
-            if (host >= 0) {
-                // a fused task has no entries and no waits of its own; its convolution covers the same tile
-                // grid, comes earlier in the order and carries its coefficients / operands and output address
-                ++n_fused;
-                const int hk = plan.tasks[host].kid;
-                const bool c3 = takes_c3_args(hk), pool = is_pool(hk), pw = !c3 && !pool && has_bn_epilogue(hk);
-                static const Epilogue none{};
-                const Epilogue* ep = c3 ? &reinterpret_cast<const C3Args*>(plan.tasks[host].args)->ep
-                                        : pw ? &reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->ep : &none;
-                const AddEpilogue* ea = c3 ? &reinterpret_cast<const C3AddArgs*>(plan.tasks[host].args)->ea
-                                           : pool ? &reinterpret_cast<const PoolAddArgs*>(plan.tasks[host].args)->ea
-                                                  : &reinterpret_cast<const PwAddArgs*>(plan.tasks[host].args)->ea;
-                const bool is_add = g->nodes[v].op == NG_OP_ADD_N;
-                ok = ok && (is_add ? add_variant(plain_variant(hk)) != KID_NONE : has_bn_epilogue(hk)) && hits[v].empty() &&
-                     plan.tasks[v].n_parents == 0 && plan.fused_into[host] < 0 && pos[host] < pos[v] &&
-                     g->nodes[host].out == g->nodes[v].out && (plan.tasks[host].release_far || !plan.tasks[v].release_far) &&
-                     (!is_add || (partition_of(hk) == partition_of(plan.tasks[v].kid) && plan.tasks[host].ntiles == plan.tasks[v].ntiles));
-                if (g->nodes[v].op == NG_OP_ADD_N) {
-                    ok = ok && has_add_epilogue(hk);
-                    const AddArgs* add = reinterpret_cast<const AddArgs*>(plan.tasks[v].args);
-                    const float* held = ep->y != nullptr ? ep->y
-                                        : c3 ? reinterpret_cast<const C3Args*>(plan.tasks[host].args)->y
-                                             : pool ? reinterpret_cast<const PoolArgs*>(plan.tasks[host].args)->y
-                                                    : reinterpret_cast<const PwArgs*>(plan.tasks[host].args)->y;
-                    ok = ok && ea->y == add->y && ea->k == add->k && add->k >= 2 && add->k <= kEpilogueAddMax && ea->zpos >= 0 &&
-                         ea->zpos < add->k && (ea->far != 0) == (plan.tasks[v].far_in != 0);
-                    int q = 0, late = 0;
-                    for (int j = 0; j < add->k && ok; ++j) {
-                        if (j == ea->zpos) ok = add->x[j] == held;
-                        else ok = ea->x[q++] == add->x[j];
-                    }
-                    // every E' parent of the add_n other than the fused operand is awaited late by the convolution
-                    for (auto& e : g->sched.meg)
-                        if (e.second == (int)v && g->tasks[e.first].fn) {
-                            const int src = plan.fused_into[e.first] >= 0 ? plan.fused_into[e.first] : e.first;
-                            if (src == host) continue;
-                            ++late;
-                            const DevTask& h = plan.tasks[host];
-                            ok = ok && !plan.elided[src] && std::find(h.parent, h.parent + h.n_parents, src) != h.parent + h.n_parents;
-                        }
-                    ok = ok && late >= (int)plan.tasks[host].n_late;
-                    ++fused_adds[host];
-                } else {
-                    const BnArgs* bn = reinterpret_cast<const BnArgs*>(plan.tasks[v].args);
-                    ok = ok && g->nodes[v].preds.size() == 1 && g->nodes[v].preds[0] == host && ep->y == bn->y &&
-                         ep->scale == bn->scale && ep->shift == bn->shift && ep->relu == bn->relu;
-                    ++fused_bns[host];
-                }
-                continue;
-            }
-            ok = ok && plan.tasks[v].ntiles > 0 && hits[v].size() == (size_t)units_of((int)v);
-            for (int h : hits[v]) ok = ok && h == 1;
-            const DevTask& d = plan.tasks[v];
-            for (int j = 0; j < d.n_parents; ++j) ok = ok && pos[d.parent[j]] < pos[v] && d.need[j] == signals[d.parent[j]] && parts[d.parent[j]] > 0;
-        }
-        for (auto& e : g->sched.meg) {
-            const int u = e.first, v = e.second;
-            if (!g->tasks[u].fn || !g->tasks[v].fn) continue;
-            if (plan.elided[v]) continue;                                              // waits for nothing
-            const int dst = plan.fused_into[v] >= 0 ? plan.fused_into[v] : v;         // whose workgroups wait for it
-            const DevTask& d = plan.tasks[dst];
-            // whose workgroups store u's result: u, its host, or (in-place concat) those of its E' parents
-            std::vector<int> sources;
-            std::function<void(int)> expand = [&](int t) {
-                if (plan.elided[t]) {
-                    for (auto& f : g->sched.meg)
-                        if (f.second == t && g->tasks[f.first].fn) expand(f.first);
-                } else {
-                    sources.push_back(plan.fused_into[t] >= 0 ? plan.fused_into[t] : t);
-                }
-            };
-            expand(u);
-            for (int src : sources) {
-                if (src == dst) continue;                                             // fused pair, checked above
-                if (std::find(d.parent, d.parent + d.n_parents, src) != d.parent + d.n_parents) continue;
-                ++n_local;
-                const int part = partition_of(plan.tasks[u].kid);
-                ok = ok && !plan.elided[u] && plan.fused_into[v] < 0 && part != PART_NONE && part == partition_of(d.kid) &&
-                     plan.tasks[u].ntiles == d.ntiles && g->nodes[u].out == g->nodes[v].out && where[src] == where[v];
-            }
-        }
-        // epilogues are there exactly where a task was fused; late parents only with a fused add_n
-        for (size_t u = 0; u < n; ++u) {
-            const int k = plan.tasks[u].kid;
-            if (!g->tasks[u].fn) continue;
-            const bool c3 = takes_c3_args(k), pw = !c3 && has_bn_epilogue(k);
-            ok = ok && fused_bns[u] <= 1 && fused_adds[u] <= 1 && (c3 || pw || fused_bns[u] == 0) && (add_variant(plain_variant(k)) != KID_NONE || fused_adds[u] == 0) &&
-                 (fused_adds[u] == 1 || plan.tasks[u].n_late == 0) && plan.tasks[u].n_late <= (unsigned)plan.tasks[u].n_parents;
-            ok = ok && has_add_epilogue(k) == (fused_adds[u] == 1);
-            if (c3) ok = ok && (reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
-            if (pw) ok = ok && (reinterpret_cast<const PwArgs*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
-        }
-        if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d, fused: %d, concats in place: %d\n", n_local, n_fused, n_elided);
+        const bool ok = resident_plan_is_consistent(g, plan);
         if (coverage_ok) *coverage_ok = ok;
     }
     g->dry_run = false;

@@ -198,6 +198,9 @@ int build_resident(ng_graph* g) {
     ResidentPlan hp;
     if (plan_resident(g, n_wg, g->resident_xcds, hp) != NG_OK)
         return g->fail(NG_EINVAL, "device-resident replay: a node has more than %d E' parents", NG_MAX_PREDS);
+    // never launch a plan that does not pass its own check (coverage, one common order with parents first, counts):
+    // a wait that can never be satisfied would only end at the spin limit
+    if (!resident_plan_is_consistent(g, hp)) return g->fail(NG_EINVAL, "device-resident replay: the plan failed its self-check");
     std::vector<DevTask>& tasks = hp.tasks;
     std::vector<DevEntry>& entries = hp.entries;
     std::vector<int>& wg_first = hp.wg_first;
