@@ -123,26 +123,26 @@ __global__ __launch_bounds__(kBlock) void fold_bn_kernel(const float* gamma, con
 struct NoWait {
     __device__ __forceinline__ void operator()() const {}
     __device__ __forceinline__ void late() const {}
+    __device__ __forceinline__ constexpr bool far_out() const { return false; }
 };
 
 // Store one convolution result and, if a batch-norm / ReLU task was fused into the tile, that
 // task's result as well (the kernels for larger problems: coefficients are fetched here, per
 // value; the 16-row kernels fetch theirs before they wait for their inputs).
-template <bool FOUT>
-__device__ __forceinline__ void store_with_epilogue(float* y, const Epilogue& ep, size_t at, int channel, float v) {
-    stg(y, y + at, v, FOUT);
+__device__ __forceinline__ void store_with_epilogue(float* y, const Epilogue& ep, size_t at, int channel, float v, bool fout) {
+    stg(y, y + at, v, fout);
     if (ep.y != nullptr) {
         float s = 1.f, t = 0.f;
         if (ep.scale != nullptr) s = ep.scale[channel], t = ep.shift[channel];
         const float z = fmaf(v, s, t);
-        stg(ep.y, ep.y + at, ep.relu ? fmaxf(z, 0.f) : z, FOUT);
+        stg(ep.y, ep.y + at, ep.relu ? fmaxf(z, 0.f) : z, fout);
     }
 }
 
 // The add_n epilogue of a convolution tile: v holds this lane's values (4 consecutive pixels if
 // VEC, else one), `at` their position in the tensors; the sum runs in argument order.
-template <bool VEC, bool FOUT>
-__device__ __forceinline__ void add_epilogue(const AddEpilogue& ea, float4 v, size_t at) {
+template <bool VEC>
+__device__ __forceinline__ void add_epilogue(const AddEpilogue& ea, float4 v, size_t at, bool fout) {
     float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
     for (int j = 0; j < kEpilogueAddMax; ++j) {               // constant indices only: the argument block stays in scalar registers
@@ -156,8 +156,8 @@ __device__ __forceinline__ void add_epilogue(const AddEpilogue& ea, float4 v, si
         if (j == 0) acc = t;
         else acc.x += t.x, acc.y += t.y, acc.z += t.z, acc.w += t.w;
     }
-    if (VEC) stg4(ea.y, ea.y + at, acc, FOUT);
-    else stg(ea.y, ea.y + at, acc.x, FOUT);
+    if (VEC) stg4(ea.y, ea.y + at, acc, fout);
+    else stg(ea.y, ea.y + at, acc.x, fout);
 }
 
 // Elementwise operators come in four partitions of the output into tiles, so that an
@@ -194,8 +194,9 @@ __device__ __forceinline__ ElemIndex elem_index(int tile, int tid, int C, int HW
     return r;
 }
 
-template <int PART, bool FIN, bool FOUT, class Wait>
+template <int PART, bool FIN, class Wait>
 __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     const ElemIndex ix = elem_index<PART>(tile, tid, a.C, a.HW, a.total, a.cols);
     const bool active = live && ix.ok;
     float s = 1.f, t = 0.f;
@@ -206,18 +207,19 @@ __device__ __forceinline__ void bn_act_tile(const BnArgs& a, int tile, float*, i
         float4 v = ldg4(a.x, a.x + ix.e, FIN);
         v.x = fmaf(v.x, s, t), v.y = fmaf(v.y, s, t), v.z = fmaf(v.z, s, t), v.w = fmaf(v.w, s, t);
         if (a.relu) v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
-        stg4(a.y, a.y + ix.e, v, FOUT);
+        stg4(a.y, a.y + ix.e, v, fout);
     } else {
         const float v = fmaf(ldg(a.x, a.x + ix.e, FIN), s, t);
-        stg(a.y, a.y + ix.e, a.relu ? fmaxf(v, 0.f) : v, FOUT);
+        stg(a.y, a.y + ix.e, a.relu ? fmaxf(v, 0.f) : v, fout);
     }
 }
 
 // ------------------------------------------------------------------------------------
 // add_n: elementwise sum of k tensors, accumulated in argument order
 // ------------------------------------------------------------------------------------
-template <int PART, bool FIN, bool FOUT, class Wait>
+template <int PART, bool FIN, class Wait>
 __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     const ElemIndex ix = elem_index<PART>(tile, tid, a.C, a.HW, a.total, a.cols);
     wait();
     if (!live || !ix.ok) return;
@@ -230,7 +232,7 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, i
             const float4 v = ldg4(a.x[j], a.x[j] + e, FIN);
             acc.x += v.x, acc.y += v.y, acc.z += v.z, acc.w += v.w;
         }
-        stg4(a.y, a.y + e, acc, FOUT);
+        stg4(a.y, a.y + e, acc, fout);
     } else {
         float acc = ldg(a.x[0], a.x[0] + e, FIN);
 #pragma unroll
@@ -238,15 +240,16 @@ __device__ __forceinline__ void add_n_tile(const AddArgs& a, int tile, float*, i
             if (j >= a.k) break;
             acc += ldg(a.x[j], a.x[j] + e, FIN);
         }
-        stg(a.y, a.y + e, acc, FOUT);
+        stg(a.y, a.y + e, acc, fout);
     }
 }
 
 // ------------------------------------------------------------------------------------
 // concat: output channel block j = channels [lo_j, lo_j + cnt_j) of input j
 // ------------------------------------------------------------------------------------
-template <bool VEC4, bool FIN, bool FOUT, class Wait>
+template <bool VEC4, bool FIN, class Wait>
 __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     const int i = tile * kBlock + tid;
     const int e = VEC4 ? i * 4 : i;
     const bool active = live && e < a.total;
@@ -264,9 +267,9 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
         float4 v;
         if (FIN) v = ldg4_any_far(src);
         else v = *reinterpret_cast<const float4*>(src);
-        stg4(a.y, a.y + e, v, FOUT);
+        stg4(a.y, a.y + e, v, fout);
     } else {
-        stg(a.y, a.y + e, ldg_any(src, FIN), FOUT);
+        stg(a.y, a.y + e, ldg_any(src, FIN), fout);
     }
 }
 
@@ -278,9 +281,10 @@ __device__ __forceinline__ void concat_tile(const ConcatArgs& a, int tile, float
 // rounds on the workgroups of its stream - one round costs one trip to memory however many
 // loads are in flight, and 1024 consecutive outputs are also the tile of the float4
 // elementwise kernels, which can then take over the partition).
-template <int P, bool EA, bool FIN, bool FOUT, class Wait>
+template <int P, bool EA, bool FIN, class Wait>
 __device__ __forceinline__ void pool3x3_tile(const typename std::conditional<EA, PoolAddArgs, PoolArgs>::type& a, int tile, float*, int tid,
                                              bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     const int base = tile * kBlock * P + tid;
     const bool active = live && base < a.total;
     // all taps of all P outputs are loaded unconditionally from clamped coordinates, so the
@@ -324,7 +328,7 @@ __device__ __forceinline__ void pool3x3_tile(const typename std::conditional<EA,
                     cnt += in;
                 }
             res[p] = a.mode == 0 ? acc : acc / (float)cnt;
-            if (base + p * kBlock < a.total) stg(a.y, a.y + base + p * kBlock, res[p], FOUT);
+            if (base + p * kBlock < a.total) stg(a.y, a.y + base + p * kBlock, res[p], fout);
         }
     }
     if constexpr (EA) {
@@ -333,7 +337,7 @@ __device__ __forceinline__ void pool3x3_tile(const typename std::conditional<EA,
 #pragma unroll
             for (int p = 0; p < P; ++p)
                 if (base + p * kBlock < a.total)
-                    add_epilogue<false, FOUT>(a.ea, make_float4(res[p], 0.f, 0.f, 0.f), (size_t)(base + p * kBlock));
+                    add_epilogue<false>(a.ea, make_float4(res[p], 0.f, 0.f, 0.f), (size_t)(base + p * kBlock), fout);
         }
     }
 }
@@ -341,8 +345,9 @@ __device__ __forceinline__ void pool3x3_tile(const typename std::conditional<EA,
 // ------------------------------------------------------------------------------------
 // dwconv: depthwise K x K, pad K/2, stride S; P outputs per thread
 // ------------------------------------------------------------------------------------
-template <int K, int S, int P, bool FIN, bool FOUT, class Wait>
+template <int K, int S, int P, bool FIN, class Wait>
 __device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     const int base = tile * kBlock * P + tid;
     const bool active = live && base < a.total;
     // unconditional loads from clamped coordinates (all in flight together), masked afterwards
@@ -382,7 +387,7 @@ __device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*, i
                 const bool in = r >= 0 && r < a.H && cc >= 0 && cc < a.W;
                 acc = fmaf(w[p][dr * K + dc], in ? v[p][dr * K + dc] : 0.f, acc);
             }
-        if (base + p * kBlock < a.total) stg(a.y, a.y + base + p * kBlock, acc, FOUT);
+        if (base + p * kBlock < a.total) stg(a.y, a.y + base + p * kBlock, acc, fout);
     }
 }
 
@@ -395,8 +400,9 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-template <bool FIN, bool FOUT, class Wait>
+template <bool FIN, class Wait>
 __device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     wait();
     const int lane = tid & 63;
     const int plane = tile * (kBlock / 64) + (tid >> 6);
@@ -405,14 +411,15 @@ __device__ __forceinline__ void global_avgpool_tile(const GapArgs& a, int tile, 
     float acc = 0.f;
     for (int p = lane; p < a.HW; p += 64) acc += ldg(a.x, src + p, FIN);
     acc = wave_sum(acc);
-    if (lane == 0) stg(a.y, a.y + plane, acc / (float)a.HW, FOUT);
+    if (lane == 0) stg(a.y, a.y + plane, acc / (float)a.HW, fout);
 }
 
 // ------------------------------------------------------------------------------------
 // fc (small batch): one wavefront per output feature; y[n][o] = <W[o], x[n]> + b[o]
 // ------------------------------------------------------------------------------------
-template <bool FIN, bool FOUT, class Wait>
+template <bool FIN, class Wait>
 __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     wait();
     const int lane = tid & 63;
     const int o = tile * (kBlock / 64) + (tid >> 6);
@@ -432,7 +439,7 @@ __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*, 
             for (int k = lane; k < a.Cin; k += 64) acc = fmaf(wr[k], ldg(a.x, xr + k, FIN), acc);
         }
         acc = wave_sum(acc);
-        if (lane == 0) stg(a.y, a.y + (size_t)n * a.Cout + o, acc + a.b[o], FOUT);
+        if (lane == 0) stg(a.y, a.y + (size_t)n * a.Cout + o, acc + a.b[o], fout);
     }
 }
 
@@ -443,8 +450,9 @@ __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*, 
 // A workgroup of four wavefronts (2 x 2) owns a TM x TN output tile; K is walked in
 // slices of KC staged through LDS (A transposed to [k][m] so both fragments read rows).
 // ------------------------------------------------------------------------------------
-template <int TM, int TN, int KC, bool FIN, bool FOUT, class Wait>
+template <int TM, int TN, int KC, bool FIN, class Wait>
 __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     wait();
     constexpr int WM = TM / 2, WN = TN / 2;           // per-wavefront sub-tile
     constexpr int FM = WM / 16, FN = WN / 16;         // 16 x 16 fragments per wavefront
@@ -530,7 +538,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
                 const int m = m0 + wm * WM + i * 16 + 4 * (lane >> 4) + r;
                 if (m < a.Cout) {
                     const float b = a.bias ? a.bias[m] : 0.f;
-                    store_with_epilogue<FOUT>(a.y, a.ep, ((size_t)img * a.Cout + m) * a.HW + pix, m, acc[i][j][r] + b);
+                    store_with_epilogue(a.y, a.ep, ((size_t)img * a.Cout + m) * a.HW + pix, m, acc[i][j][r] + b, fout);
                 }
             }
         }
@@ -560,8 +568,9 @@ __global__ __launch_bounds__(kBlock) void pack_pw_weights_kernel(const float* w,
     wp[i] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
 }
 
-template <int CH, bool FIN, bool FOUT, class Wait>          // CH k steps per chunk: 4 * CH loads in flight per lane
+template <int CH, bool FIN, class Wait>          // CH k steps per chunk: 4 * CH loads in flight per lane
 __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     wait();
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -636,7 +645,7 @@ __device__ __forceinline__ void conv1x1_direct_tile(const PwArgs& a, int tile, f
             const int m = m0 + ti * 16 + 4 * (lane >> 4) + r;
             if (m < a.Cout && col < a.cols && live) {
                 const float b = a.bias ? a.bias[m] : 0.f;
-                store_with_epilogue<FOUT>(a.y, a.ep, (size_t)(yb - a.y) + (size_t)m * a.HW, m, sum + b);
+                store_with_epilogue(a.y, a.ep, (size_t)(yb - a.y) + (size_t)m * a.HW, m, sum + b, fout);
             }
         }
     }
@@ -671,9 +680,10 @@ __global__ __launch_bounds__(kBlock) void pack_pw_weights_k4_kernel(const float*
     wp[i] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
 }
 
-template <int G, bool VEC, bool EA, bool FIN, bool FOUT, class Wait>
+template <int G, bool VEC, bool EA, bool FIN, class Wait>
 __device__ __forceinline__ void conv1x1_k4_tile(const typename std::conditional<EA, PwAddArgs, PwArgs>::type& a, int tile, float* smem,
                                                 int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     constexpr int NJ = VEC ? 4 : 1;                          // MFMA tiles per wavefront
     constexpr int TN = VEC ? 64 : 16;                        // columns per workgroup tile
     static_assert(4 * NJ * 4 * 64 <= kSmemFloats, "LDS budget");
@@ -752,19 +762,19 @@ __device__ __forceinline__ void conv1x1_k4_tile(const typename std::conditional<
             const int img = colv / a.HW, pix = colv - img * a.HW;
             at = ((size_t)img * a.Cout + m) * a.HW + pix;
             v = make_float4(out[0] + b, out[NJ > 1 ? 1 : 0] + b, out[NJ > 2 ? 2 : 0] + b, out[NJ > 3 ? 3 : 0] + b);
-            if (VEC) stg4(a.y, a.y + at, v, FOUT);
-            else stg(a.y, a.y + at, v.x, FOUT);
+            if (VEC) stg4(a.y, a.y + at, v, fout);
+            else stg(a.y, a.y + at, v.x, fout);
             if (a.ep.y != nullptr) {
                 v.x = fmaf(v.x, es, et), v.y = fmaf(v.y, es, et), v.z = fmaf(v.z, es, et), v.w = fmaf(v.w, es, et);
                 if (a.ep.relu) v.x = fmaxf(v.x, 0.f), v.y = fmaxf(v.y, 0.f), v.z = fmaxf(v.z, 0.f), v.w = fmaxf(v.w, 0.f);
-                if (VEC) stg4(a.ep.y, a.ep.y + at, v, FOUT);
-                else stg(a.ep.y, a.ep.y + at, v.x, FOUT);
+                if (VEC) stg4(a.ep.y, a.ep.y + at, v, fout);
+                else stg(a.ep.y, a.ep.y + at, v.x, fout);
             }
         }
     }
     if constexpr (EA) {
         wait.late();
-        if (valid) add_epilogue<VEC, FOUT>(a.ea, v, at);
+        if (valid) add_epilogue<VEC>(a.ea, v, at, fout);
     }
     __syncthreads();                                         // LDS is reused by the next tile
 }
@@ -779,8 +789,9 @@ __device__ __forceinline__ void conv1x1_k4_tile(const typename std::conditional<
 // TP = 8 : each wavefront owns the same 8 x 8 pixel tile and its own group of 8 channels.
 // Tile index = (image * co_groups + channel group) * tiles_xy + pixel tile.
 // ------------------------------------------------------------------------------------
-template <int TP, int S, bool FIN, bool FOUT, class Wait>
+template <int TP, int S, bool FIN, class Wait>
 __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     constexpr int CIC = S == 2 && TP == 16 ? 2 : 4;    // input channels per LDS slice
     constexpr int IW = (TP - 1) * S + 3;               // input patch edge
     constexpr int LDP = IW + 1;
@@ -861,7 +872,7 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
 #pragma unroll
         for (int j = 0; j < CO; ++j)
             if (co0 + j < a.Cout)
-                store_with_epilogue<FOUT>(a.y, a.ep, (((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox, co0 + j, acc[j]);
+                store_with_epilogue(a.y, a.ep, (((size_t)img * a.Cout + co0 + j) * a.Ho + oy) * a.Wo + ox, co0 + j, acc[j], fout);
     }
 }
 
@@ -874,9 +885,10 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
 // over the four wavefronts in groups of 4 k-steps, G groups in flight, fixed-order reduction.
 // A lane walks k in steps of 4, so (ci, tap) is updated incrementally: tap += 4, carry into ci.
 // ------------------------------------------------------------------------------------
-template <int G, bool EA, bool FIN, bool FOUT, class Wait>
+template <int G, bool EA, bool FIN, class Wait>
 __device__ __forceinline__ void conv3x3_k4_tile(const typename std::conditional<EA, C3AddArgs, C3Args>::type& a, int tile, float* smem,
                                                 int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     static_assert(4 * 4 * 64 <= kSmemFloats, "LDS budget");
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -942,18 +954,18 @@ __device__ __forceinline__ void conv3x3_k4_tile(const typename std::conditional<
         if (valid) {
             const int img = colv / HWo, pix = colv - img * HWo;
             at = ((size_t)img * a.Cout + m) * HWo + pix;
-            stg(a.y, a.y + at, sum, FOUT);
+            stg(a.y, a.y + at, sum, fout);
             z = sum;
             if (a.ep.y != nullptr) {
                 z = fmaf(sum, es, et);
                 if (a.ep.relu) z = fmaxf(z, 0.f);
-                stg(a.ep.y, a.ep.y + at, z, FOUT);
+                stg(a.ep.y, a.ep.y + at, z, fout);
             }
         }
     }
     if constexpr (EA) {
         wait.late();
-        if (valid) add_epilogue<false, FOUT>(a.ea, make_float4(z, 0.f, 0.f, 0.f), at);
+        if (valid) add_epilogue<false>(a.ea, make_float4(z, 0.f, 0.f, 0.f), at, fout);
     }
     __syncthreads();                                         // LDS is reused by the next tile
 }
@@ -962,15 +974,17 @@ __device__ __forceinline__ void conv3x3_k4_tile(const typename std::conditional<
 // kernel table: id -> argument type, tile function, name
 // ------------------------------------------------------------------------------------
 // FIN: activations are read with device-scope loads (some operand was produced on another
-// XCD); FOUT: the result is stored with device-scope stores (some reader sits on another XCD).
+// XCD) - a template argument, because loads sit in the inner loops. Whether the result is stored
+// with device-scope stores (some reader sits on another XCD) is a run-time property of the
+// `wait` object: a kernel has a handful of stores, and one variant less per kernel halves the code.
 template <int KID> struct KernelOf;
 #define NG_KERNEL(KID, ARGS, NAME, ...)                                                        \
     template <> struct KernelOf<KID> {                                                         \
         using Args = ARGS;                                                                     \
         static constexpr const char* name = NAME;                                              \
-        template <bool FIN, bool FOUT, class Wait>                                             \
+        template <bool FIN, class Wait>                                                        \
         static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live, Wait& wait) { \
-            __VA_ARGS__, FIN, FOUT > (a, t, smem, tid, live, wait);                            \
+            __VA_ARGS__, FIN > (a, t, smem, tid, live, wait);                                  \
         }                                                                                      \
     };
 NG_KERNEL(KID_BN, BnArgs, "bn_act", bn_act_tile < PART_L256)
@@ -1030,9 +1044,9 @@ NG_KERNEL(KID_C3_M4A, C3AddArgs, "conv3x3_mfma_4_add", conv3x3_k4_tile < 4, true
     template <> struct KernelOf<KID> {                                                         \
         using Args = ARGS;                                                                     \
         static constexpr const char* name = NAME;                                              \
-        template <bool FIN, bool FOUT, class Wait>                                             \
+        template <bool FIN, class Wait>                                                        \
         static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live, Wait& wait) { \
-            FN<FIN, FOUT>(a, t, smem, tid, live, wait);                                        \
+            FN<FIN>(a, t, smem, tid, live, wait);                                              \
         }                                                                                      \
     };
 NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
@@ -1044,7 +1058,7 @@ template <int KID>
 __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KID>::Args a) {
     __shared__ float smem[kSmemFloats];
     NoWait wait;
-    KernelOf<KID>::template tile<false, false>(a, blockIdx.x, smem, threadIdx.x, true, wait);
+    KernelOf<KID>::template tile<false>(a, blockIdx.x, smem, threadIdx.x, true, wait);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1071,7 +1085,7 @@ __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KI
 // each word is moved into a scalar register.
 template <int KID, class Wait>
 __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int step, int ntiles, int subs, float* smem, int sub,
-                                          int tid, bool fin, bool fout, Wait& wait) {
+                                          int tid, bool fin, Wait& wait) {
     using A = typename KernelOf<KID>::Args;
     static_assert(sizeof(A) <= kArgWords * 4 && sizeof(A) % 4 == 0, "argument block does not fit the record");
     unsigned w[sizeof(A) / 4];
@@ -1080,16 +1094,14 @@ __device__ __forceinline__ void run_tiles(const unsigned* words, int unit, int s
     A a;
     __builtin_memcpy(&a, w, sizeof(A));
     const int nunits = (ntiles + subs - 1) / subs;
-#define NG_LOOP(FI, FO)                                                              \
+#define NG_LOOP(FI)                                                                  \
     for (; unit < nunits; unit += step) {                                            \
         const int tile = unit * subs + sub;                                          \
         const bool live = sub < subs && tile < ntiles;                               \
-        KernelOf<KID>::template tile<FI, FO>(a, live ? tile : 0, smem, tid, live, wait); \
+        KernelOf<KID>::template tile<FI>(a, live ? tile : 0, smem, tid, live, wait); \
     }
-    if (!fin && !fout) { NG_LOOP(false, false) }
-    else if (!fin) { NG_LOOP(false, true) }
-    else if (!fout) { NG_LOOP(true, false) }
-    else { NG_LOOP(true, true) }
+    if (!fin) { NG_LOOP(false) }
+    else { NG_LOOP(true) }
 #undef NG_LOOP
 }
 
@@ -1135,6 +1147,9 @@ struct CounterWait {
     int task, np, n_late, lane;      // np parents in all, the last n_late of them awaited by `late`
     unsigned long long* stamp;       // this entry's three clock readings when tracing, else nullptr (same for all lanes)
     bool pending, late_pending;
+    bool far_out_;                   // the entry's results are stored with device-scope stores
+
+    __device__ __forceinline__ bool far_out() const { return far_out_; }
 
     // Lane j of the first wavefront (first <= j < last) polls parent j until its counter has reached this
     // replay's target (`once`: looks a single time); true if it has. Other lanes return true.
@@ -1239,8 +1254,8 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
 #define NG_CASE(KID)                                                                                                         \
     case KID:                                                                                                                \
         if (FULL || is_lean_kernel(KID)) {                                                                                   \
-            CounterWait<has_add_epilogue(KID)> wait{plan, rec, &s_abort, &s_late, epoch, task, np, n_late, lane, stamp, true, true}; \
-            run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, far_out, wait);                      \
+            CounterWait<has_add_epilogue(KID)> wait{plan, rec, &s_abort, &s_late, epoch, task, np, n_late, lane, stamp, true, true, far_out}; \
+            run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, wait);                               \
         }                                                                                                                    \
         break;
                 NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_R64) NG_CASE(KID_BN_R16) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
