@@ -260,6 +260,38 @@ def test_device_resident_wait_gives_up_and_recovers():
         r.close()
 
 
+def test_device_resident_late_wait_gives_up_and_recovers():
+    """The same forced failure (spin limit 1, set from the host) on a DAG whose convolution tiles
+    carry a fused add_n and wait late for a slow operand: the late wait is bounded like the first
+    one, every workgroup leaves normally, ng_sync reports it, and the next replay is clean."""
+    def build(b):
+        x = b.input(1, 256, 14, 14)
+        slow = b.conv3x3(x, 32, 1, 1)
+        fast = b.bn_act(b.conv1x1(b.relu(x), 32), relu=True)
+        b.relu(b.add_n([slow, fast]))
+    w = single_op(build)
+    r = GraphRunner(w, DEV)
+    r.prepare(resident_xcds=8)
+    try:
+        host_of = B.ng_resident_fusion(r.g)
+        ops = [nd.op for nd in w.nodes]
+        assert host_of[ops.index("add_n")] == ops.index("conv1x1")
+        good = r.run(mode=B.NG_MODE_DEVICE_RESIDENT)
+        B.ng_resident_config(r.g, spin_limit=1)
+        B.ng_replay(r.g)
+        with pytest.raises(B.NgError) as ei:
+            B.ng_sync(r.g)
+        assert ei.value.code == B.NG_EHIP and "ran out of spins" in str(ei.value)
+        B.ng_resident_config(r.g, spin_limit=0)
+        r.arena.zero_()
+        r.set_input(w.input)
+        again = r.run(mode=B.NG_MODE_DEVICE_RESIDENT)
+        for k in good:
+            assert np.array_equal(good[k], again[k])
+    finally:
+        r.close()
+
+
 def test_auto_mode_picks_the_fastest_trial_and_replays_correctly():
     w = workloads.make("random200")
     ref = forward(w)
