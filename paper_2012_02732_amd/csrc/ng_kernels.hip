@@ -87,7 +87,6 @@ __device__ __forceinline__ float4 ldg4_any_far(const float* p) {
 
 // LDS floats every workgroup owns: the largest user is the conv3x3 input patch (4 x 33 x 34).
 constexpr int kSmemFloats = 4 * 33 * 34;
-constexpr int kStemMaxCin = 7;                  // input channels of the vector-ALU conv3x3 (deeper ones take the implicit GEMM)
 
 // ------------------------------------------------------------------------------------
 // bn_act / relu: y = x * s[c] + t[c] (s, t folded from gamma, beta, mean, var), optional ReLU
@@ -781,10 +780,8 @@ __device__ __forceinline__ void conv1x1_k4_tile(const typename std::conditional<
 
 // ------------------------------------------------------------------------------------
 // conv3x3 dense on the vector ALUs: one thread = one output pixel x 8 output channels.
-// Input patches go through LDS (4 input channels per slice). The weights a wavefront needs are
-// the same for all of its lanes: the workgroup copies them into LDS once per tile, before it
-// waits for its input, and every lane reads them from there (one address per wavefront: a
-// broadcast). Only used for fewer than 8 input channels (the stem of a network).
+// Input patches go through LDS (4 input channels per slice); the weights a wavefront
+// needs are the same for all of its lanes, so they are read through uniform addresses.
 // TP = 16: the workgroup owns a 16 x 16 pixel tile and one group of 8 output channels.
 // TP = 8 : each wavefront owns the same 8 x 8 pixel tile and its own group of 8 channels.
 // Tile index = (image * co_groups + channel group) * tiles_xy + pixel tile.
@@ -792,14 +789,14 @@ __device__ __forceinline__ void conv1x1_k4_tile(const typename std::conditional<
 template <int TP, int S, bool FIN, class Wait>
 __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* smem, int tid, bool live, Wait& wait) {
     const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
+    wait();
     constexpr int CIC = S == 2 && TP == 16 ? 2 : 4;    // input channels per LDS slice
     constexpr int IW = (TP - 1) * S + 3;               // input patch edge
     constexpr int LDP = IW + 1;
     constexpr int GROUPS = TP == 16 ? 1 : 4;           // channel groups per workgroup
     constexpr int CO = 8;
-    static_assert(CIC * IW * LDP + GROUPS * CO * kStemMaxCin * 9 <= kSmemFloats, "LDS budget");
+    static_assert(CIC * IW * LDP <= kSmemFloats, "LDS budget");
     float* patch = smem;                               // [CIC][IW][LDP]
-    float* wl = smem + CIC * IW * LDP;                 // [GROUPS][CO][Cin][9]
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int local = TP == 16 ? tid : (tid & 63);
@@ -815,16 +812,10 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     float acc[CO];
 #pragma unroll
     for (int j = 0; j < CO; ++j) acc[j] = 0.f;
-    // this tile's weights -> LDS (out-of-range channels repeat the last one and are masked at the store);
-    // the barrier after the first patch store below also orders these writes before the first read
-    const int per_channel = a.Cin * 9, per_group = CO * per_channel;
-    for (int i = tid; i < GROUPS * per_group; i += kBlock) {
-        const int grp = i / per_group, r = i - grp * per_group;
-        const int j = r / per_channel, rest = r - j * per_channel;
-        wl[i] = a.w[(size_t)min((cog * GROUPS + grp) * CO + j, a.Cout - 1) * per_channel + rest];
-    }
-    const float* wmine = wl + (TP == 16 ? 0 : wave) * per_group;
-    wait();
+    // clamped weight rows: out-of-range channels repeat the last one and are masked at the store
+    const float* wrow[CO];
+#pragma unroll
+    for (int j = 0; j < CO; ++j) wrow[j] = a.w + (size_t)min(co0 + j, a.Cout - 1) * a.Cin * 9;
 
     for (int c0 = 0; c0 < a.Cin; c0 += CIC) {
         if (live) {
@@ -861,7 +852,7 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
                 for (int dc = 0; dc < 3; ++dc) in[dr * 3 + dc] = patch[(ci * IW + ty * S + dr) * LDP + tx * S + dc];
 #pragma unroll
             for (int j = 0; j < CO; ++j) {
-                const float* wp = wmine + j * per_channel + (c0 + ci) * 9;
+                const float* wp = wrow[j] + (c0 + ci) * 9;
 #pragma unroll
                 for (int q = 0; q < 9; ++q) acc[j] = fmaf(wp[q], in[q], acc[j]);
             }
@@ -1396,7 +1387,7 @@ PwChoice choose_c3(const ng_graph* g, int v) {
     const Node& nd = g->nodes[v];
     if (nd.op != NG_OP_CONV3X3) return c;
     const long cin = g->nodes[nd.preds[0]].out.c;
-    if (cin <= kStemMaxCin) return c;
+    if (cin < 8) return c;
     c.kind = PwChoice::K4_WORD;
     k4_split(9 * cin, nd.out.c, c);
     return c;
