@@ -23,6 +23,7 @@ enum Kid : int {
     // the 16-row convolutions and the pools with an add_n applied to their result before it is stored (resident replay)
     KID_PW_V1A, KID_PW_V2A, KID_PW_V3A, KID_PW_V4A, KID_PW_S1A, KID_PW_S2A, KID_PW_S3A, KID_PW_S4A,
     KID_C3_M1A, KID_C3_M2A, KID_C3_M3A, KID_C3_M4A, KID_POOL_A, KID_POOL_P4A,
+    KID_C3_L32, KID_C3_L64,          // conv3x3 as an implicit GEMM staged through LDS, 32 x 128 / 64 x 64 output tiles (many columns)
     KID_COUNT
 };
 
@@ -43,10 +44,11 @@ constexpr bool is_pool(int kid) { return plain_variant(kid) == KID_POOL || plain
 constexpr bool is_pw16(int kid) { return plain_variant(kid) >= KID_PW_V1 && plain_variant(kid) <= KID_PW_S4; }
 constexpr bool is_c3m(int kid) { return plain_variant(kid) >= KID_C3_M1 && plain_variant(kid) <= KID_C3_M4; }
 constexpr bool has_add_epilogue(int kid) { return plain_variant(kid) != kid; }
+constexpr bool is_c3_lds(int kid) { return kid == KID_C3_L32 || kid == KID_C3_L64; }
 // convolutions whose argument block is a C3Args (the others with a batch-norm epilogue take a PwArgs)
-constexpr bool takes_c3_args(int kid) { return is_c3m(kid) || (kid >= KID_C3_T16S1 && kid <= KID_C3_T8S2); }
+constexpr bool takes_c3_args(int kid) { return is_c3m(kid) || is_c3_lds(kid) || (kid >= KID_C3_T16S1 && kid <= KID_C3_T8S2); }
 // kernels whose tiles can apply a batch-norm / ReLU to their results before storing them: every convolution
-constexpr bool has_bn_epilogue(int kid) { return is_pw16(kid) || is_c3m(kid) || (kid >= KID_PW_D4 && kid <= KID_C3_T8S2); }
+constexpr bool has_bn_epilogue(int kid) { return is_pw16(kid) || is_c3m(kid) || is_c3_lds(kid) || (kid >= KID_PW_D4 && kid <= KID_C3_T8S2); }
 
 // How a kernel splits its output into tiles (see the elementwise tile functions): only tasks
 // with the same partition of same-shaped outputs have matching tiles.
@@ -69,12 +71,15 @@ constexpr int partition_of(int kid_any) {
 // kernels whose tiles keep a compute unit's memory pipeline or matrix cores busy for a while
 constexpr bool is_matrix_kernel(int kid_any) {
     const int kid = plain_variant(kid_any);
-    return (kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || (kid >= KID_PW_V1 && kid <= KID_PW_S4) || (kid >= KID_C3_M1 && kid <= KID_C3_M4);
+    return (kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || (kid >= KID_PW_V1 && kid <= KID_PW_S4) || (kid >= KID_C3_M1 && kid <= KID_C3_M4) ||
+           kid == KID_C3_L32 || kid == KID_C3_L64;
 }
 
 // kernels of the lean build of the resident kernel: everything except the 32 x 32 and LDS-tiled
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
-constexpr bool is_lean_kernel(int kid) { return !(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2; }
+constexpr bool is_lean_kernel(int kid) {
+    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64;
+}
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
 constexpr int kSubs = 2;             // tiles a workgroup of the resident kernel works on at a time

@@ -544,6 +544,115 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
 }
 
 // ------------------------------------------------------------------------------------
+// conv3x3 with many output columns (large maps, batches): the same LDS-staged scheme as the
+// kernel above on the implicit GEMM Y[Cout x cols] = W[Cout x 9 Cin] * P[9 Cin x cols]. The
+// weight tensor [Cout][Cin][3][3] already is the row-major [Cout][9 Cin] matrix; the patch
+// matrix P[k = 9 ci + tap][col = (image, oy, ox)] is gathered while a K slice is filled
+// (clamped addresses, taps outside the image are zeroed). Every patch element is read from
+// global memory once per workgroup tile instead of once per 16 x 16 MFMA tile.
+// ------------------------------------------------------------------------------------
+template <int TM, int TN, int KC, bool FIN, class Wait>
+__device__ __forceinline__ void conv3x3_lds_tile(const C3Args& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
+    constexpr int WM = TM / 2, WN = TN / 2;           // per-wavefront sub-tile
+    constexpr int FM = WM / 16, FN = WN / 16;         // 16 x 16 fragments per wavefront
+    constexpr int LDA = TM + 1, LDB = TN + 1;
+    static_assert(KC * (LDA + LDB) <= kSmemFloats, "LDS budget");
+    static_assert(kBlock % KC == 0 && kBlock % TN == 0 && TM % (kBlock / KC) == 0 && KC % (kBlock / TN) == 0, "fill pattern");
+    float* As = smem;                                 // [KC][LDA]
+    float* Bs = smem + KC * LDA;                      // [KC][LDB]
+
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
+    const int m0 = by * TM, n0 = bx * TN;
+    const int K = 9 * a.Cin, HWo = a.Ho * a.Wo, HW = a.H * a.W;
+    // the column this thread fills in every B slice
+    const int fill_col = n0 + tid % TN;
+    const int ccol = min(fill_col, a.cols - 1);
+    const int fimg = ccol / HWo, fpix = ccol - fimg * HWo;
+    const int foy = fpix / a.Wo, fox = fpix - foy * a.Wo;
+    const int iy0 = foy * a.stride - a.pad, ix0 = fox * a.stride - a.pad;
+    const float* xin = a.x + (size_t)fimg * a.Cin * HW;
+
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    wait();
+
+    for (int k0 = 0; k0 < K; k0 += KC) {
+        if (live) {
+            // A slice: W[m0 + m][k0 + k] -> As[k][m]; consecutive threads walk k (contiguous in W)
+            constexpr int RM = kBlock / KC;
+            const int k = tid % KC, gk = k0 + k;
+            float v[TM / RM];
+#pragma unroll
+            for (int p = 0; p < TM / RM; ++p) {
+                const int gm = m0 + tid / KC + p * RM;
+                v[p] = a.w[(size_t)min(gm, a.Cout - 1) * K + min(gk, K - 1)];
+            }
+            // B slice: P[k0 + k][n0 + n] -> Bs[k][n]; consecutive threads walk columns
+            constexpr int RK = kBlock / TN;
+            float pv[KC / RK];
+            unsigned inside = 0;
+#pragma unroll
+            for (int p = 0; p < KC / RK; ++p) {
+                const int gk2 = min(k0 + tid / TN + p * RK, K - 1);
+                const int ci = gk2 / 9, tap = gk2 - 9 * ci;
+                const int dr = (tap * 11) >> 5, dc = tap - 3 * dr;   // tap / 3, tap % 3 for tap < 9
+                const int iy = iy0 + dr, ix = ix0 + dc;
+                const bool in = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+                inside |= (in ? 1u : 0u) << p;
+                pv[p] = ldg(a.x, xin + (size_t)ci * HW + min(max(iy, 0), a.H - 1) * a.W + min(max(ix, 0), a.W - 1), FIN);
+            }
+            __builtin_amdgcn_sched_barrier(0);                   // all loads of the slice are issued before the first use
+#pragma unroll
+            for (int p = 0; p < TM / RM; ++p) {
+                const int m = tid / KC + p * RM;
+                As[k * LDA + m] = (m0 + m < a.Cout && gk < K) ? v[p] : 0.f;
+            }
+#pragma unroll
+            for (int p = 0; p < KC / RK; ++p) {
+                const int kk = tid / TN + p * RK;
+                Bs[kk * LDB + tid % TN] = (fill_col < a.cols && k0 + kk < K && ((inside >> p) & 1u)) ? pv[p] : 0.f;
+            }
+        }
+        __syncthreads();
+        if (live)
+#pragma unroll
+        for (int kk = 0; kk < KC; kk += 4) {
+            float af[FM], bf[FN];
+#pragma unroll
+            for (int i = 0; i < FM; ++i) af[i] = As[(kk + (lane >> 4)) * LDA + wm * WM + i * 16 + (lane & 15)];
+#pragma unroll
+            for (int j = 0; j < FN; ++j) bf[j] = Bs[(kk + (lane >> 4)) * LDB + wn * WN + j * 16 + (lane & 15)];
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            const int col = n0 + wn * WN + j * 16 + (lane & 15);
+            if (col >= a.cols || !live) continue;
+            const int img = col / HWo, pix = col - img * HWo;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int m = m0 + wm * WM + i * 16 + 4 * (lane >> 4) + r;
+                if (m < a.Cout) store_with_epilogue(a.y, a.ep, ((size_t)img * a.Cout + m) * HWo + pix, m, acc[i][j][r], fout);
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------
 // conv1x1 for small problems (the batch-1 case): latency, not throughput, decides.
 // A workgroup owns a 32 x 32 output tile as 2 x 2 MFMA tiles; its four wavefronts split K
 // four ways, each accumulates all four MFMA tiles over its quarter of K with operands
@@ -1029,6 +1138,8 @@ NG_KERNEL(KID_C3_M1A, C3AddArgs, "conv3x3_mfma_1_add", conv3x3_k4_tile < 1, true
 NG_KERNEL(KID_C3_M2A, C3AddArgs, "conv3x3_mfma_2_add", conv3x3_k4_tile < 2, true)
 NG_KERNEL(KID_C3_M3A, C3AddArgs, "conv3x3_mfma_3_add", conv3x3_k4_tile < 3, true)
 NG_KERNEL(KID_C3_M4A, C3AddArgs, "conv3x3_mfma_4_add", conv3x3_k4_tile < 4, true)
+NG_KERNEL(KID_C3_L32, C3Args, "conv3x3_lds_32x128", conv3x3_lds_tile < 32, 128, 16)
+NG_KERNEL(KID_C3_L64, C3Args, "conv3x3_lds_64x64", conv3x3_lds_tile < 64, 64, 32)
 #undef NG_KERNEL
 // kernels without further template arguments
 #define NG_KERNEL0(KID, ARGS, NAME, FN)                                                        \
@@ -1259,7 +1370,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                 NG_CASE(KID_C3_M3) NG_CASE(KID_C3_M4)
                 NG_CASE(KID_PW_V1A) NG_CASE(KID_PW_V2A) NG_CASE(KID_PW_V3A) NG_CASE(KID_PW_V4A) NG_CASE(KID_PW_S1A) NG_CASE(KID_PW_S2A)
                 NG_CASE(KID_PW_S3A) NG_CASE(KID_PW_S4A) NG_CASE(KID_C3_M1A) NG_CASE(KID_C3_M2A) NG_CASE(KID_C3_M3A) NG_CASE(KID_C3_M4A)
-                NG_CASE(KID_POOL_A) NG_CASE(KID_POOL_P4A)
+                NG_CASE(KID_POOL_A) NG_CASE(KID_POOL_P4A) NG_CASE(KID_C3_L32) NG_CASE(KID_C3_L64)
 #undef NG_CASE
                 default: break;
             }
@@ -1338,7 +1449,7 @@ namespace {
 // Which conv1x1 kernel a node gets. Decided from shapes alone, so that the size of the
 // repacked weights is known before any memory is bound.
 struct PwChoice {
-    enum Kind { NONE, GEMV, LDS64, DIRECT32, K4_VEC, K4_WORD } kind = NONE;
+    enum Kind { NONE, GEMV, LDS64, DIRECT32, K4_VEC, K4_WORD, C3_LDS } kind = NONE;
     int in_flight = 0;        // K4: groups of 4 k-steps in flight (1..4); DIRECT32: k-steps per chunk
     int groups = 0;           // K4: groups in the packed copy (a multiple of 4 * in_flight); DIRECT32: padded k-steps
     size_t packed = 0;        // floats of repacked weights
@@ -1382,12 +1493,18 @@ PwChoice choose_pw(const ng_graph* g, int v) {
     return c;
 }
 // conv3x3 with at least 8 input channels runs as an implicit GEMM with K = 9 Cin
+constexpr long kC3LdsMinCols = 2048;      // measured: below this the 16 x 16 tiles (more workgroups, shorter K loops each) win
 PwChoice choose_c3(const ng_graph* g, int v) {
     PwChoice c;
     const Node& nd = g->nodes[v];
     if (nd.op != NG_OP_CONV3X3) return c;
     const long cin = g->nodes[nd.preds[0]].out.c;
     if (cin < 8) return c;
+    // many columns: the LDS-staged kernel reads each patch element once per 64- or 128-column tile (no repacked weights)
+    if (nd.out.n * nd.out.h * nd.out.w >= kC3LdsMinCols) {
+        c.kind = PwChoice::C3_LDS;
+        return c;
+    }
     c.kind = PwChoice::K4_WORD;
     k4_split(9 * cin, nd.out.c, c);
     return c;
@@ -1568,6 +1685,17 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.Cin = (int)i0.c, a.Cout = (int)o.c, a.H = (int)i0.h, a.W = (int)i0.w, a.Ho = (int)o.h, a.Wo = (int)o.w;
             a.pad = nd.p.pad, a.stride = nd.p.stride;
             const PwChoice c = choose_c3(g, v);
+            if (c.kind == PwChoice::C3_LDS) {
+                a.cols = (int)(o.n * o.h * o.w);
+                if (a.Cout <= 32) {
+                    a.tiles_n = (int)ceil_div(a.cols, 128);
+                    set_kernel<KID_C3_L32>(t, a, (long)a.tiles_n * ceil_div(a.Cout, 32));
+                } else {
+                    a.tiles_n = (int)ceil_div(a.cols, 64);
+                    set_kernel<KID_C3_L64>(t, a, (long)a.tiles_n * ceil_div(a.Cout, 64));
+                }
+                break;
+            }
             if (c.packed != 0) {
                 if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
                 a.wp = packed, a.groups = c.groups;

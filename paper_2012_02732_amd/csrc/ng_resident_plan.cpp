@@ -90,6 +90,8 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
             base = 1.8, per_tile = 0.2 * (a->groups / 4);
             break;
         }
+        case KID_C3_L32: base = 2.0, per_tile = 0.14 * cin; break;     // 9 Cin / 4 k-steps of 4 MFMAs per wavefront, plus the slice fills
+        case KID_C3_L64: base = 2.0, per_tile = 0.16 * cin; break;
         default: break;
     }
     return base + per_tile * subs;

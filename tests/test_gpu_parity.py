@@ -108,14 +108,17 @@ def test_conv1x1_mfma(shape, couts):
 
 
 @pytest.mark.parametrize("shape,cout", [((1, 32, 32, 32), 32), ((1, 3, 37, 41), 44), ((2, 5, 9, 9), 7),
-                                        ((1, 20, 17, 17), 24), ((1, 64, 8, 8), 40), ((1, 4, 3, 3), 9)])
+                                        ((1, 20, 17, 17), 24), ((1, 64, 8, 8), 40), ((1, 4, 3, 3), 9),
+                                        # 2048 columns and more: the LDS-staged implicit GEMM (32 x 128 tiles up to 32
+                                        # output channels, 64 x 64 above), ragged in every dimension, batch > 1
+                                        ((1, 16, 70, 70), 24), ((1, 8, 131, 135), 72), ((3, 9, 40, 41), 33), ((1, 32, 65, 64), 32)])
 def test_conv3x3(shape, cout):
     def build(b):
         x = b.input(*shape)
         for stride in (1, 2):
             for pad in (0, 1):
                 b.conv3x3(x, cout, stride, pad)
-    check_all_nodes(single_op(build))
+    check_all_nodes(single_op(build), (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
 
 
 @pytest.mark.parametrize("n,cin,cout", [(1, 2048, 1000), (3, 100, 10), (8, 33, 5), (32, 2048, 1000), (9, 64, 7)])
