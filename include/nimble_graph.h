@@ -206,7 +206,11 @@ enum {
                                    a stream = a gang of workgroups serving its tasks in FIFO order, an event =
                                    a completion counter in device memory (record = release add, wait = poll +
                                    acquire). Raw submission of the task schedule (Section 4.1) without the
-                                   command processor between dependent tasks. */
+                                   command processor between dependent tasks. A batch-norm / ReLU or add_n may run
+                                   inside the tiles of the task that produces its operand, and a concat whose
+                                   inputs were produced in place runs nothing (ng_resident_fusion reports which);
+                                   every node's tensor is written all the same and equals the other modes' bit
+                                   for bit. The plan passes a self-check at ng_capture or the capture fails. */
     NG_MODE_AUTO = 5          /* whichever of modes 0, 1 and 4 was fastest in a short trial at ng_capture (an
                                    ahead-of-time choice like the rest of the schedule: DAGs of many tiny tasks
                                    gain most from mode 4, plain chains and large tasks from a HIP graph) */
