@@ -404,4 +404,9 @@ def test_device_resident_plan_argument_checks():
         with pytest.raises(B.NgError) as e:
             B.ng_resident_dry_plan(r.g, *bad)
         assert e.value.code == B.NG_EINVAL
+    # queries about the captured replay are refused before ng_capture (no GPU needed to find that out)
+    for early in (B.ng_resident_fusion, B.ng_resident_sizes, B.ng_resident_xcd_mapping, B.ng_auto_mode):
+        with pytest.raises(B.NgError) as e:
+            early(r.g)
+        assert e.value.code == B.NG_ESTATE, early.__name__
     r.close()
