@@ -277,7 +277,11 @@ def main():
                           "t_cp_if_chain_time_counts_as_duration_us": t_cp_hi,
                           "t_cp_if_only_time_above_an_empty_kernel_counts_us": t_cp_lo,
                           "empty_kernel_chain_us_per_node": c_empty,
-                          "planner_expected_us": est_us},
+                          "planner_expected_us": est_us,
+                          "tasks_on_path_without_workgroups_of_their_own": sum(fusion[v] != -1 for v in path),
+                          "note": "t_cp = longest path of the DAG weighted with the isolated time of every task's "
+                                  "stand-alone kernel, every task counted; in the device-resident replay some of them "
+                                  "run inside their producer's tiles or have nothing to do (counted in the field above)"},
         "resident_timeline": timeline,
         "modes_median_us": modes,
         "auto_mode": {"chosen": MODE_NAMES[auto_mode], "trial_us": {MODE_NAMES[k]: v for k, v in auto_trial.items()}},
