@@ -44,11 +44,11 @@ namespace ng {
 namespace {
 
 constexpr double kSyncNearUs = 0.7;   // completion counter -> dependent workgroup running, same XCD (measured)
-constexpr double kSyncFarUs = 2.0;    // extra cost when producer and consumer sit on different XCDs (measured)
-constexpr double kPublishUs = 0.3;    // stores drained and counter bumped: the workgroup moves on to its next entry
+constexpr double kSyncFarUs = 1.0;    // extra cost when producer and consumer sit on different XCDs (measured 1-2 us; plans made with 1.0 replay fastest)
+constexpr double kPublishUs = 0.6;    // stores drained and counter bumped: the workgroup moves on to its next entry
 constexpr double kLocalUs = 0.1;      // hand-over inside one workgroup: one barrier
 constexpr double kFusedUs = 0.05;     // a batch-norm applied in the convolution's registers: a few instructions, one more store
-constexpr double kSpreadPenaltyUs = 5.0; // what spreading a task over all XCDs must gain before it is preferred (its readers go the long way too)
+constexpr double kSpreadPenaltyUs = 2.0; // what spreading a task over all XCDs must gain before it is preferred (its readers go the long way too)
 constexpr double kFarRunFactor = 1.2; // a tile whose loads and stores all go through the memory side takes longer
 
 // Expected time of one round of a task, in microseconds, when `subs` sub-blocks of a
