@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes of one device-resident replay, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # scaled by what the same counters read for a plain 256 MiB copy (2.00 and 1.00): the
 # summary with the commands is profiles/resident_kernel_nasnet_style.md.
-MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (27146.8 * 2.00 + 44834.2 * 1.00) * 1024}
+MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (28647.0 * 2.00 + 43908.4 * 1.00) * 1024}
 
 MODES = {"graph_multi": 0, "graph_single": 1, "eager_single": 2, "eager_multi": 3, "device_resident": 4}
 MODE_NAMES = {v: k for k, v in MODES.items()}
