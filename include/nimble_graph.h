@@ -236,6 +236,15 @@ int ng_sync(ng_graph* g);
  * XCD of its stream is handed over through that XCD's L2 and only the others pay for an L2
  * write-back and invalidate. */
 int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned spin_limit, int device_scope_everywhere);
+/* How many settings of the device-resident planner's cost model ng_capture tries (1..8; default 8;
+ * only before ng_capture). The planner decides between plans whose expected lengths differ by
+ * less than its model's error; ng_capture therefore builds the plans of `trials` settings (the
+ * first is the default one), replays each distinct plan a few times and keeps the fastest -
+ * the pre-run of Section 4.1 used for measuring as well as for recording. With 1 the default
+ * setting's plan is taken unmeasured (capture is shorter and the plan does not depend on timing). */
+int ng_resident_plan_trials(ng_graph* g, int trials);
+/* *setting = which of the tried settings ng_capture kept (0 = the default one). Needs ng_capture. */
+int ng_resident_plan_kept(const ng_graph* g, int* setting);
 /* Per-task timeline of device-resident replays. enable != 0 switches recording on and clears
  * the record (off for 0). If ticks is not NULL it first receives what was recorded since the
  * last call: four device clock readings per node (HOST array of 4 * n_nodes values, 100 MHz

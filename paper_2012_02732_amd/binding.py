@@ -25,7 +25,7 @@ SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_ou
            "ng_node_shape", "ng_schedule", "ng_set_assignment", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
            "ng_plan_memory", "ng_set_memory_reuse", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
-           "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
+           "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_plan_trials", "ng_resident_plan_kept", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
 
 
@@ -69,6 +69,8 @@ _sig = {
     "ng_resident_dry_plan": (_I, [_P, _I, _I, _DP, _IP, _IP, _IP]),
     "ng_resident_xcd_mapping": (_I, [_P, _IP]),
     "ng_resident_fusion": (_I, [_P, _IP]),
+    "ng_resident_plan_trials": (_I, [_P, _I]),
+    "ng_resident_plan_kept": (_I, [_P, _IP]),
     "ng_resident_sizes": (_I, [_P, _IP, _IP, _IP, _DP]),
     "ng_resident_trace": (_I, [_P, _I, C.POINTER(C.c_ulonglong)]),
     "ng_time_replay": (_I, [_P, _I, _FP]),
@@ -254,6 +256,16 @@ def ng_resident_fusion(g):
     host_of = _ints(lib.ng_num_nodes(g))
     check(g, lib.ng_resident_fusion(g, host_of))
     return list(host_of)[:lib.ng_num_nodes(g)]
+
+
+def ng_resident_plan_trials(g, trials: int):
+    check(g, lib.ng_resident_plan_trials(g, trials))
+
+
+def ng_resident_plan_kept(g) -> int:
+    v = C.c_int()
+    check(g, lib.ng_resident_plan_kept(g, C.byref(v)))
+    return v.value
 
 
 def ng_resident_sizes(g):

@@ -60,6 +60,19 @@ struct Task {
     unsigned args_bytes = 0;
 };
 
+// The settings of the device-resident planner's cost model that decide between plans of similar
+// expected length, where the model is least certain. The defaults replay fastest on the cell-style
+// workloads; ng_capture also builds the plans of a few other settings and keeps the one that
+// replays fastest on the device at hand (an ahead-of-time trial like the choice of the replay mode).
+struct PlanKnobs {
+    double sync_far_us = 1.0;        // extra cost of a hand-over when producer and consumer sit on different XCDs (measured 1-2 us)
+    double spread_penalty_us = 2.0;  // what spreading a task over all XCDs must gain before it is preferred (its readers go the long way too)
+    int p4_rounds = 3;               // rounds on the home XCD from which a windowed task takes 4 outputs per thread
+    double sync_near_us = 0.7;       // completion counter -> dependent workgroup running, same XCD (measured)
+    double publish_us = 1.2;         // stores drained and counter bumped: the workgroup moves on to its next entry
+    double far_run_factor = 1.2;     // a tile whose loads and stores all go through the memory side takes longer
+};
+
 // Output of the device-resident planner (ng_resident_plan.cpp).
 struct ResidentPlan {
     int n_wg = 0;                              // persistent workgroups (grid size)
@@ -94,6 +107,8 @@ struct ng_graph {
     int resident_wg_per_cu = 0;                          // 0 = pick automatically
     int resident_xcds = 0;                               // XCDs the resident kernel spreads over, 0 = all 8
     unsigned resident_spin_limit = ng::kDefaultSpinLimit; // polls before a wait gives up
+    int resident_plan_trials = 8;                        // planner settings ng_capture tries (1 = the default setting only)
+    int resident_plan_kept = 0;                          // which of them it kept
     bool dry_run = false;                                // task table built for planning only (host, fake addresses)
     bool resident_all_far = false;                       // treat every edge as crossing XCDs (device-scope fences everywhere)
     std::string err;
@@ -121,7 +136,7 @@ const void* resident_kernel_handle(bool full);
 const void* empty_kernel_handle();
 const void* xcd_probe_kernel_handle();
 // ng_resident_plan.cpp: xcds = 0 lets the cost model choose among 1, 2, 4, 8.
-int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan);
+int plan_resident(const ng_graph* g, int n_wg, int xcds, const PlanKnobs& knobs, ResidentPlan& plan);
 bool resident_plan_is_consistent(const ng_graph* g, const ResidentPlan& plan);
 // ng_runtime.hip
 void destroy_runtime(ng_graph* g);

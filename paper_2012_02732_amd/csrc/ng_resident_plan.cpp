@@ -43,13 +43,8 @@ namespace ng {
 
 namespace {
 
-constexpr double kSyncNearUs = 0.7;   // completion counter -> dependent workgroup running, same XCD (measured)
-constexpr double kSyncFarUs = 1.0;    // extra cost when producer and consumer sit on different XCDs (measured 1-2 us; plans made with 1.0 replay fastest)
-constexpr double kPublishUs = 0.6;    // stores drained and counter bumped: the workgroup moves on to its next entry
 constexpr double kLocalUs = 0.1;      // hand-over inside one workgroup: one barrier
 constexpr double kFusedUs = 0.05;     // a batch-norm applied in the convolution's registers: a few instructions, one more store
-constexpr double kSpreadPenaltyUs = 2.0; // what spreading a task over all XCDs must gain before it is preferred (its readers go the long way too)
-constexpr double kFarRunFactor = 1.2; // a tile whose loads and stores all go through the memory side takes longer
 
 // Expected time of one round of a task, in microseconds, when `subs` sub-blocks of a
 // workgroup take a tile each: a latency part that does not depend on how many tiles share
@@ -135,7 +130,9 @@ struct Sim {
     double makespan = 0;
 };
 
-void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
+void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& out) {
+    const double kSyncNearUs = knobs.sync_near_us, kSyncFarUs = knobs.sync_far_us, kSpreadPenaltyUs = knobs.spread_penalty_us;
+    const double kPublishUs = knobs.publish_us, kFarRunFactor = knobs.far_run_factor;
     const Schedule& sc = g->sched;
     const int n = (int)g->nodes.size();
     const int per_xcd = n_wg / 8;
@@ -220,9 +217,9 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
         const int home = stream_xcd[sc.stream_of[v]];
         out.kid[v] = t.kid;
         out.ntiles[v] = t.ntiles;
-        // a windowed task that would need four or more rounds on its stream's workgroups gets 4 outputs
-        // per thread (4 x the index arithmetic in one round: pays off only from there)
-        const int p4_rounds = getenv("NG_P4_ROUNDS") ? atoi(getenv("NG_P4_ROUNDS")) : 2;
+        // a windowed task that would need more than `p4_rounds` rounds on its stream's workgroups gets 4
+        // outputs per thread (4 x the index arithmetic in one round: pays off only from there)
+        const int p4_rounds = getenv("NG_P4_ROUNDS") ? atoi(getenv("NG_P4_ROUNDS")) : knobs.p4_rounds;
         if (units_for(t.ntiles, kSubs) > p4_rounds * per_xcd && (t.kid == KID_POOL || t.kid == KID_DW_K3S1) &&
             !getenv("NG_NO_P4")) {
             out.kid[v] = t.kid == KID_POOL ? KID_POOL_P4 : KID_DW_K3S1_P4;
@@ -469,7 +466,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, Sim& out) {
 
 }  // namespace
 
-int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
+int plan_resident(const ng_graph* g, int n_wg, int xcds, const PlanKnobs& knobs, ResidentPlan& plan) {
     const Schedule& sc = g->sched;
     const int n = (int)g->nodes.size();
     Sim best;
@@ -477,7 +474,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, ResidentPlan& plan) {
     for (int nx : {1, 2, 3, 4, 5, 6, 7, 8}) {
         if (xcds > 0 && nx != xcds) continue;
         Sim s;
-        simulate(g, n_wg, nx, s);
+        simulate(g, n_wg, nx, knobs, s);
         if (best_nx == 0 || s.makespan < best.makespan) best = std::move(s), best_nx = nx;
     }
     plan.n_wg = n_wg;
@@ -780,7 +777,7 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
     static float fake_constants;
     for (int v = 0; v < (int)g->nodes.size() && rc == NG_OK; ++v) rc = build_task(g, v, fake_arena, &fake_constants, g->tasks[v]);
     ResidentPlan plan;
-    if (rc == NG_OK && plan_resident(g, n_workgroups, xcds, plan) != NG_OK) rc = g->fail(NG_EINVAL, "too many E' parents");
+    if (rc == NG_OK && plan_resident(g, n_workgroups, xcds, PlanKnobs(), plan) != NG_OK) rc = g->fail(NG_EINVAL, "too many E' parents");
     if (rc == NG_OK) {
         if (expected_us) *expected_us = plan.est_us;
         if (n_entries) *n_entries = (int)plan.entries.size();

@@ -156,6 +156,10 @@ int record_multi(ng_graph* g, int slot) {
     return NG_OK;
 }
 
+int make_plan(ng_graph* g, const PlanKnobs& knobs, ResidentPlan& hp);
+int install_plan(ng_graph* g, const ResidentPlan& hp);
+int tune_resident(ng_graph* g);
+
 // Device-resident replay: plan on the host (ng_resident_plan.cpp), upload, keep the handles.
 int build_resident(ng_graph* g) {
     Runtime& rt = *g->rt;
@@ -195,15 +199,59 @@ int build_resident(ng_graph* g) {
         }
         if (!rt.xcd_mapping_ok) g->resident_all_far = true;
     }
+    unsigned* d_done = nullptr;
+    int* d_error = nullptr;
+    const char* env_stride = getenv("NG_DONE_STRIDE");
+    const char* env_sleep = getenv("NG_POLL_SLEEP");
+    rt.plan.done_stride = env_stride ? atoi(env_stride) : 64;    // one counter per 256 bytes
+    rt.plan.poll_sleep = env_sleep ? atoi(env_sleep) : 1;
+    rt.done_words = (size_t)n * rt.plan.done_stride;
+    NG_HIP(hipMalloc(&d_done, 10 * rt.done_words * sizeof(unsigned)));         // device-scope counters, the XCD-local ones, 8 per-XCD first-level ones
+    NG_HIP(hipMalloc(&d_error, sizeof(int)));
+    NG_HIP(hipHostMalloc(reinterpret_cast<void**>(&rt.h_error), sizeof(int), hipHostMallocDefault));
+    *rt.h_error = 0;
+    NG_HIP(hipMemset(d_done, 0, 10 * rt.done_words * sizeof(unsigned)));
+    NG_HIP(hipMemset(d_error, 0, sizeof(int)));
+    rt.plan.done = d_done;
+    rt.plan.done_near = d_done + rt.done_words;
+    rt.plan.done_xcd = d_done + 2 * rt.done_words;
+    rt.plan.error_dev = d_error;
+    rt.plan.error_host = rt.h_error;
+    rt.plan.spin_limit = g->resident_spin_limit;
+    rt.n_wg = n_wg;
+    rt.epoch = 0;
+    rt.counters_dirty = false;
     ResidentPlan hp;
-    if (plan_resident(g, n_wg, g->resident_xcds, hp) != NG_OK)
+    if (int rc = make_plan(g, PlanKnobs(), hp)) return rc;
+    return install_plan(g, hp);
+}
+
+// The planner's output for one setting of its cost model, self-checked.
+int make_plan(ng_graph* g, const PlanKnobs& knobs_in, ResidentPlan& hp) {
+    PlanKnobs knobs = knobs_in;
+    if (const char* e = getenv("NG_KNOBS"))                     // measurements only: "far,spread,p4,near,publish,farrun"
+        sscanf(e, "%lf,%lf,%d,%lf,%lf,%lf", &knobs.sync_far_us, &knobs.spread_penalty_us, &knobs.p4_rounds, &knobs.sync_near_us, &knobs.publish_us, &knobs.far_run_factor);
+    if (plan_resident(g, g->rt->n_wg, g->resident_xcds, knobs, hp) != NG_OK)
         return g->fail(NG_EINVAL, "device-resident replay: a node has more than %d E' parents", NG_MAX_PREDS);
     // never launch a plan that does not pass its own check (coverage, one common order with parents first, counts):
     // a wait that can never be satisfied would only end at the spin limit
     if (!resident_plan_is_consistent(g, hp)) return g->fail(NG_EINVAL, "device-resident replay: the plan failed its self-check");
-    std::vector<DevTask>& tasks = hp.tasks;
-    std::vector<DevEntry>& entries = hp.entries;
-    std::vector<int>& wg_first = hp.wg_first;
+    return NG_OK;
+}
+
+// Upload a plan: one record per list entry and the list heads. Replaces the plan that was there
+// (the caller has waited for its last replay). A task's counter grows per replay by the number
+// of workgroups the plan gave it, so the counters of another plan mean nothing to this one: the
+// next launch starts from zeroed counters and epoch 1 again.
+int install_plan(ng_graph* g, const ResidentPlan& hp) {
+    Runtime& rt = *g->rt;
+    const int n_wg = rt.n_wg;
+    const std::vector<DevTask>& tasks = hp.tasks;
+    const std::vector<DevEntry>& entries = hp.entries;
+    const std::vector<int>& wg_first = hp.wg_first;
+    if (rt.d_records) (void)hipFree(rt.d_records), rt.d_records = nullptr;
+    if (rt.d_wg_first) (void)hipFree(rt.d_wg_first), rt.d_wg_first = nullptr;
+    if (rt.plan.trace) (void)hipFree(rt.plan.trace), rt.plan.trace = nullptr;   // sized for the old lists: tracing is off again
     rt.xcds = hp.xcds;
     rt.est_us = hp.est_us;
     // one self-contained record per entry: the kernel never touches the task table itself
@@ -225,36 +273,83 @@ int build_resident(ng_graph* g) {
         std::memcpy(r.args, t.args, sizeof r.args);
     }
 
-    unsigned* d_done = nullptr;
-    int* d_error = nullptr;
-    const char* env_stride = getenv("NG_DONE_STRIDE");
-    const char* env_sleep = getenv("NG_POLL_SLEEP");
-    rt.plan.done_stride = env_stride ? atoi(env_stride) : 64;    // one counter per 256 bytes
-    rt.plan.poll_sleep = env_sleep ? atoi(env_sleep) : 1;
-    rt.done_words = (size_t)n * rt.plan.done_stride;
     NG_HIP(hipMalloc(&rt.d_records, records.size() * sizeof(DevRecord)));
     NG_HIP(hipMalloc(&rt.d_wg_first, wg_first.size() * sizeof(int)));
-    NG_HIP(hipMalloc(&d_done, 10 * rt.done_words * sizeof(unsigned)));         // device-scope counters, the XCD-local ones, 8 per-XCD first-level ones
-    NG_HIP(hipMalloc(&d_error, sizeof(int)));
-    NG_HIP(hipHostMalloc(reinterpret_cast<void**>(&rt.h_error), sizeof(int), hipHostMallocDefault));
-    *rt.h_error = 0;
     NG_HIP(hipMemcpy(rt.d_records, records.data(), records.size() * sizeof(DevRecord), hipMemcpyHostToDevice));
     NG_HIP(hipMemcpy(rt.d_wg_first, wg_first.data(), wg_first.size() * sizeof(int), hipMemcpyHostToDevice));
-    NG_HIP(hipMemset(d_done, 0, 10 * rt.done_words * sizeof(unsigned)));
-    NG_HIP(hipMemset(d_error, 0, sizeof(int)));
     rt.plan.records = static_cast<const DevRecord*>(rt.d_records);
     rt.plan.wg_first = static_cast<const int*>(rt.d_wg_first);
-    rt.plan.done = d_done;
-    rt.plan.done_near = d_done + rt.done_words;
-    rt.plan.done_xcd = d_done + 2 * rt.done_words;
-    rt.plan.error_dev = d_error;
-    rt.plan.error_host = rt.h_error;
-    rt.plan.spin_limit = g->resident_spin_limit;
-    rt.n_wg = n_wg;
     rt.n_entries = wg_first[n_wg];
-    rt.epoch = 0;
-    rt.counters_dirty = false;
+    if (rt.epoch != 0) rt.counters_dirty = true;
     return NG_OK;
+}
+
+int launch_resident(ng_graph* g);
+
+// The planner's cost model cannot tell plans of similar expected length apart (its figures are a
+// few tenths of a microsecond off per task, and which of them matter depends on the DAG). So a
+// few settings of the knobs it is least sure about are planned, each distinct plan is replayed
+// a few times, and the fastest one stays - measured ahead of time on the device at hand, like
+// everything else that is fixed before the first real replay.
+int tune_resident(ng_graph* g) {
+    // far hand-over, spread penalty, 4-outputs-per-thread threshold, near hand-over, publish, far-run factor
+    static const PlanKnobs kSettings[8] = {
+        PlanKnobs(),                        // the default
+        {1.0, 2.0, 3, 0.4, 1.5, 1.2},       // cheaper hand-overs, workgroups busy for longer after a task
+        {1.0, 2.0, 3, 0.7, 2.5, 1.2},       // ... much longer: tasks of one stream alternate between workgroups
+        {1.0, 2.0, 3, 0.7, 0.6, 1.2},       // ... shorter: a stream stays on few workgroups
+        {1.0, 1.0, 3, 0.7, 1.5, 1.2},       // spreads over all XCDs more readily
+        {1.0, 2.0, 3, 0.7, 1.5, 1.0},       // far operands cost a tile nothing
+        {1.0, 2.0, 2, 0.7, 1.2, 1.2},       // 4 outputs per thread from the third round on
+        {2.0, 2.0, 3, 0.7, 1.2, 1.2},       // a hand-over between XCDs costs twice as much: streams keep to themselves
+    };
+    const int trials = std::min(g->resident_plan_trials, 8);
+    g->resident_plan_kept = 0;
+    if (trials <= 1 || getenv("NG_NO_TUNE")) return NG_OK;
+    const int saved_mode = g->mode;
+    g->mode = NG_MODE_DEVICE_RESIDENT;
+    auto time_installed = [&](float* median_us) -> int {
+        std::vector<float> us;
+        int reps = 3 + 11;
+        for (int rep = 0; rep < reps; ++rep) {
+            const auto t0 = std::chrono::steady_clock::now();
+            int rc = launch_resident(g);
+            if (rc == NG_OK) rc = ng_sync(g);
+            if (rc != NG_OK) return rc;
+            const float t = std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count();
+            if (rep >= 3) us.push_back(t);
+            if (rep == 2 && t > 3000.f) reps = 3 + 3;             // a long replay: fewer looks
+        }
+        std::sort(us.begin(), us.end());
+        *median_us = us[us.size() / 2];
+        return NG_OK;
+    };
+    std::vector<ResidentPlan> plans;
+    std::vector<int> setting_of;
+    int best = -1, installed = -1, rc = NG_OK;
+    float best_us = 0;
+    for (int k = 0; k < trials && rc == NG_OK; ++k) {
+        ResidentPlan hp;
+        if ((rc = make_plan(g, kSettings[k], hp)) != NG_OK) break;
+        bool seen = false;
+        for (const ResidentPlan& q : plans)
+            seen = seen || (q.wg_first == hp.wg_first && q.entries.size() == hp.entries.size() &&
+                            std::memcmp(q.entries.data(), hp.entries.data(), hp.entries.size() * sizeof(DevEntry)) == 0 &&
+                            std::memcmp(q.tasks.data(), hp.tasks.data(), hp.tasks.size() * sizeof(DevTask)) == 0);
+        if (seen) continue;
+        if ((rc = install_plan(g, hp)) != NG_OK) break;
+        installed = (int)plans.size();
+        plans.push_back(std::move(hp));
+        setting_of.push_back(k);
+        float us = 0;
+        if ((rc = time_installed(&us)) != NG_OK) break;
+        if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN trial %d: expected %.1f us, replays in %.1f us\n", k, plans.back().est_us, us);
+        if (best < 0 || us < best_us) best = installed, best_us = us;
+    }
+    if (rc == NG_OK && best >= 0 && best != installed) rc = install_plan(g, plans[best]);
+    if (rc == NG_OK && best >= 0) g->resident_plan_kept = setting_of[best];
+    g->mode = saved_mode;
+    return rc;
 }
 
 int launch_resident(ng_graph* g) {
@@ -374,6 +469,8 @@ int ng_capture(ng_graph* g) {
     NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
     NG_HIP(hipStreamSynchronize(rt.streams[0]));
     g->phase = CAPTURED;
+    if (rt.d_records && !g->memory_reuse)
+        if (int rc = tune_resident(g)) return rc;
     // short trial: which way of replaying this schedule is fastest on this DAG
     {
         const int candidates[3] = {NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_DEVICE_RESIDENT};
@@ -458,6 +555,21 @@ int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned sp
         g->resident_all_far = device_scope_everywhere != 0;
     }
     g->resident_spin_limit = spin_limit ? spin_limit : kDefaultSpinLimit;
+    return NG_OK;
+}
+
+int ng_resident_plan_trials(ng_graph* g, int trials) {
+    if (!g) return NG_EINVAL;
+    if (trials < 1 || trials > 8) return g->fail(NG_EINVAL, "ng_resident_plan_trials: trials must be 1..8");
+    if (g->phase >= CAPTURED) return g->fail(NG_ESTATE, "ng_resident_plan_trials: the plan is fixed at ng_capture");
+    g->resident_plan_trials = trials;
+    return NG_OK;
+}
+
+int ng_resident_plan_kept(const ng_graph* g, int* setting) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_resident_plan_kept: call ng_capture first");
+    if (setting) *setting = g->resident_plan_kept;
     return NG_OK;
 }
 

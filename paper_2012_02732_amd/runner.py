@@ -107,9 +107,11 @@ class GraphRunner:
         return B.ng_plan_memory(self.g)
 
     # -- GPU part ----------------------------------------------------------------
-    def prepare(self, resident_wg_per_cu=0, resident_xcds=0, resident_device_scope=0):
+    def prepare(self, resident_wg_per_cu=0, resident_xcds=0, resident_device_scope=0, plan_trials=None):
         """schedule -> plan -> bind -> capture, allocating arena and streams with torch."""
         assert self.device is not None, "GraphRunner was created without a device"
+        if plan_trials is not None:
+            B.ng_resident_plan_trials(self.g, plan_trials)
         if resident_wg_per_cu or resident_xcds or resident_device_scope:
             B.ng_resident_config(self.g, resident_wg_per_cu, resident_xcds, 0, resident_device_scope)
         sched = self.schedule()

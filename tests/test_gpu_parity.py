@@ -274,7 +274,7 @@ def test_device_resident_late_wait_gives_up_and_recovers():
         b.relu(b.add_n([slow, fast]))
     w = single_op(build)
     r = GraphRunner(w, DEV)
-    r.prepare(resident_xcds=8)
+    r.prepare(resident_xcds=8, plan_trials=1)        # the default setting's plan: what it fuses is asserted below
     try:
         host_of = B.ng_resident_fusion(r.g)
         ops = [nd.op for nd in w.nodes]
@@ -394,12 +394,12 @@ def test_device_resident_on_random_dags(seed, shape, xcds):
         r.close()
 
 
-def _resident_vs_single(w, xcds=0):
+def _resident_vs_single(w, xcds=0, plan_trials=None):
     """Every tensor of both replays against the oracle, and the two bit for bit against each other;
-    returns the fusion map of the device-resident plan."""
+    returns the fusion map of the device-resident plan (plan_trials=1: of the default setting's plan)."""
     ref = forward(w, keep=range(len(w.nodes)))
     r = GraphRunner(w, DEV)
-    r.prepare(resident_xcds=xcds)
+    r.prepare(resident_xcds=xcds, plan_trials=plan_trials)
     try:
         outs = {}
         for mode in (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT):
@@ -444,7 +444,8 @@ def test_device_resident_fused_epilogues(shape, cout):
         b.relu(b.add_n([b.pool(a7, "max", 1, 1), t]))
     w = single_op(build)
     for xcds in (0, 1):
-        host_of = _resident_vs_single(w, xcds)
+        _resident_vs_single(w, xcds)                              # whichever plan the trials at capture keep
+        host_of = _resident_vs_single(w, xcds, plan_trials=1)     # the default setting's plan, examined below
         ops = [nd.op for nd in w.nodes]
         fused_bn = [v for v, h in enumerate(host_of) if h >= 0 and ops[v] in ("bn_act", "relu")]
         fused_add = [v for v, h in enumerate(host_of) if h >= 0 and ops[v] == "add_n"]
@@ -469,13 +470,13 @@ def test_device_resident_fused_add_waits_for_a_late_operand():
         fast = b.bn_act(b.conv1x1(b.relu(x), 32), relu=True)
         b.relu(b.add_n([slow, fast]))
     w = single_op(build)
-    host_of = _resident_vs_single(w, 8)          # 8 XCDs: the two branches get workgroups of their own
+    host_of = _resident_vs_single(w, 8, plan_trials=1)   # 8 XCDs: the two branches get workgroups of their own
     ops = [nd.op for nd in w.nodes]
     add = ops.index("add_n")
     slow = ops.index("conv3x3")
     assert host_of[add] == ops.index("conv1x1") and host_of[ops.index("bn_act")] == host_of[add], host_of
     r = GraphRunner(w, DEV)
-    r.prepare(resident_xcds=8)
+    r.prepare(resident_xcds=8, plan_trials=1)
     try:
         B.ng_replay_mode(r.g, B.NG_MODE_DEVICE_RESIDENT)
         for _ in range(3):
@@ -607,3 +608,35 @@ def test_device_resident_device_scope_fallback():
     finally:
         r.close()
         r2.close()
+
+
+@pytest.mark.parametrize("name", ["nasnet_style", "random200"])
+def test_plan_trials_at_capture_keep_a_correct_plan(name):
+    """ng_capture plans the device-resident replay under several settings of the planner's cost
+    model, replays each distinct plan and keeps the fastest. Whichever it keeps, the replay equals
+    the single-stream graph bit for bit on every output, also after the plan was swapped several
+    times during capture (the completion counters start over with every swap); with one trial the
+    default setting is kept; the number of trials is fixed at capture."""
+    w = workloads.make(name)
+    ref = forward(w)
+    outs = {}
+    for trials in (8, 1):
+        r = GraphRunner(w, DEV)
+        r.prepare(plan_trials=trials)
+        try:
+            kept = B.ng_resident_plan_kept(r.g)
+            assert 0 <= kept < trials
+            single = r.run(w.input, mode=B.NG_MODE_GRAPH_SINGLE)
+            for rep in range(3):
+                got = r.run(w.input, mode=B.NG_MODE_DEVICE_RESIDENT)
+                for v in w.outputs:
+                    assert np.array_equal(got[v], single[v]), (trials, rep, v)
+                    assert rel_err(got[v], ref[v]) <= TOL
+            outs[trials] = got
+            with pytest.raises(B.NgError) as ei:
+                B.ng_resident_plan_trials(r.g, 2)
+            assert ei.value.code == B.NG_ESTATE
+        finally:
+            r.close()
+    for v in w.outputs:
+        assert np.array_equal(outs[8][v], outs[1][v])

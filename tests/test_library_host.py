@@ -405,8 +405,15 @@ def test_device_resident_plan_argument_checks():
             B.ng_resident_dry_plan(r.g, *bad)
         assert e.value.code == B.NG_EINVAL
     # queries about the captured replay are refused before ng_capture (no GPU needed to find that out)
-    for early in (B.ng_resident_fusion, B.ng_resident_sizes, B.ng_resident_xcd_mapping, B.ng_auto_mode):
+    for early in (B.ng_resident_fusion, B.ng_resident_sizes, B.ng_resident_xcd_mapping, B.ng_auto_mode, B.ng_resident_plan_kept):
         with pytest.raises(B.NgError) as e:
             early(r.g)
         assert e.value.code == B.NG_ESTATE, early.__name__
+    # the number of planner settings ng_capture tries: 1..8
+    for bad in (0, 9, -1):
+        with pytest.raises(B.NgError) as e:
+            B.ng_resident_plan_trials(r.g, bad)
+        assert e.value.code == B.NG_EINVAL
+    B.ng_resident_plan_trials(r.g, 1)
+    B.ng_resident_plan_trials(r.g, 8)
     r.close()
