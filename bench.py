@@ -30,7 +30,7 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E
 # HBM bytes of one device-resident replay, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # scaled by what the same counters read for a plain 256 MiB copy (2.00 and 1.00): the
 # summary with the commands is profiles/resident_kernel_nasnet_style.md.
-MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (28647.0 * 2.00 + 43908.4 * 1.00) * 1024}
+MEASURED_TRAFFIC_BYTES = {("nasnet_style", "device_resident"): (29251.4 * 2.00 + 43548.7 * 1.00) * 1024}
 
 MODES = {"graph_multi": 0, "graph_single": 1, "eager_single": 2, "eager_multi": 3, "device_resident": 4}
 MODE_NAMES = {v: k for k, v in MODES.items()}
@@ -267,7 +267,8 @@ def main():
                    "sync_edges": sched["n_sync"], "events": sched["n_events"], "replay": args.mode,
                    "resident_workgroups": n_wg, "resident_xcds": xcds,
                    "resident_tasks_inside_their_producer": sum(h >= 0 for h in fusion),
-                   "resident_concats_in_place": sum(h == -2 for h in fusion)},
+                   "resident_concats_in_place": sum(h == -2 for h in fusion),
+                   "resident_plan_setting_kept": B.ng_resident_plan_kept(runner.g)},
         "latency_us": {"median": t_e2e, "p10": percentile(lat, 0.10), "p90": percentile(lat, 0.90),
                        "device_side": dev_us},
         "throughput_replays_per_s": thr,

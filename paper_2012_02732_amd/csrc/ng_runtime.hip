@@ -152,6 +152,7 @@ int record_multi(ng_graph* g, int slot) {
         NG_HIP(hipGraphAddKernelNode(&node[v], graph, deps.empty() ? nullptr : deps.data(), deps.size(), &kp));
         last_on_stream[st] = v;
     }
+    if (const char* dot = getenv("NG_GRAPH_DOT")) (void)hipGraphDebugDotPrint(graph, dot, 0);   // for inspection only
     NG_HIP(hipGraphInstantiate(&rt.exec[slot], graph, nullptr, nullptr, 0));
     return NG_OK;
 }
@@ -300,7 +301,7 @@ int tune_resident(ng_graph* g) {
         {1.0, 2.0, 3, 0.7, 0.6, 1.2},       // ... shorter: a stream stays on few workgroups
         {1.0, 1.0, 3, 0.7, 1.5, 1.2},       // spreads over all XCDs more readily
         {1.0, 2.0, 3, 0.7, 1.5, 1.0},       // far operands cost a tile nothing
-        {1.0, 2.0, 2, 0.7, 1.2, 1.2},       // 4 outputs per thread from the third round on
+        {1.0, 2.0, 1 << 20, 0.7, 1.2, 1.2}, // windowed tasks never take 4 outputs per thread
         {2.0, 2.0, 3, 0.7, 1.2, 1.2},       // a hand-over between XCDs costs twice as much: streams keep to themselves
     };
     const int trials = std::min(g->resident_plan_trials, 8);
@@ -358,8 +359,8 @@ int launch_resident(ng_graph* g) {
     hipStream_t origin = rt.streams[0];
     if (rt.counters_dirty) {                                   // a timed-out replay left partial counts behind
         NG_HIP(hipStreamSynchronize(origin));
-        NG_HIP(hipMemset(rt.plan.done, 0, 10 * rt.done_words * sizeof(unsigned)));
-        NG_HIP(hipMemset(rt.plan.error_dev, 0, sizeof(int)));
+        NG_HIP(hipMemsetAsync(rt.plan.done, 0, 10 * rt.done_words * sizeof(unsigned), origin));   // on the stream of the launch below
+        NG_HIP(hipMemsetAsync(rt.plan.error_dev, 0, sizeof(int), origin));
         *rt.h_error = 0;
         rt.epoch = 0;
         rt.counters_dirty = false;
