@@ -275,6 +275,10 @@ int ng_resident_fusion(const ng_graph* g, int* host_of);
  * common topological order, expected completion counts consistent). Any pointer may be NULL. */
 int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, double* expected_us, int* n_entries,
                          int* n_far_edges, int* coverage_ok);
+/* The same rehearsal for the setting-th (0..7) of the planner settings that ng_capture tries
+ * (ng_resident_plan_trials); setting 0 is what ng_resident_dry_plan plans with. */
+int ng_resident_dry_plan_setting(ng_graph* g, int setting, int n_workgroups, int xcds, double* expected_us,
+                                 int* n_entries, int* n_far_edges, int* coverage_ok);
 /* Layout chosen at ng_capture: resident workgroups, total (workgroup, task) entries, XCDs in
  * use, and the makespan in microseconds that the planner's cost model expects (any pointer
  * may be NULL). */

@@ -25,7 +25,7 @@ SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_ou
            "ng_node_shape", "ng_schedule", "ng_set_assignment", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
            "ng_plan_memory", "ng_set_memory_reuse", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
-           "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_plan_trials", "ng_resident_plan_kept", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
+           "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_dry_plan_setting", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_plan_trials", "ng_resident_plan_kept", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
 
 
@@ -67,6 +67,7 @@ _sig = {
     "ng_resident_config": (_I, [_P, _I, _I, C.c_uint, _I]),
     "ng_auto_mode": (_I, [_P, _IP, C.POINTER(C.c_float)]),
     "ng_resident_dry_plan": (_I, [_P, _I, _I, _DP, _IP, _IP, _IP]),
+    "ng_resident_dry_plan_setting": (_I, [_P, _I, _I, _I, _DP, _IP, _IP, _IP]),
     "ng_resident_xcd_mapping": (_I, [_P, _IP]),
     "ng_resident_fusion": (_I, [_P, _IP]),
     "ng_resident_plan_trials": (_I, [_P, _I]),
@@ -242,6 +243,12 @@ def ng_auto_mode(g):
 def ng_resident_dry_plan(g, n_workgroups=256, xcds=0) -> dict:
     e, n, f, ok = C.c_double(), C.c_int(), C.c_int(), C.c_int()
     check(g, lib.ng_resident_dry_plan(g, n_workgroups, xcds, C.byref(e), C.byref(n), C.byref(f), C.byref(ok)))
+    return {"expected_us": e.value, "n_entries": n.value, "n_far_edges": f.value, "ok": bool(ok.value)}
+
+
+def ng_resident_dry_plan_setting(g, setting, n_workgroups=256, xcds=0) -> dict:
+    e, n, f, ok = C.c_double(), C.c_int(), C.c_int(), C.c_int()
+    check(g, lib.ng_resident_dry_plan_setting(g, setting, n_workgroups, xcds, C.byref(e), C.byref(n), C.byref(f), C.byref(ok)))
     return {"expected_us": e.value, "n_entries": n.value, "n_far_edges": f.value, "ok": bool(ok.value)}
 
 

@@ -73,6 +73,9 @@ struct PlanKnobs {
     double far_run_factor = 1.2;     // a tile whose loads and stores all go through the memory side takes longer
 };
 
+constexpr int kPlanSettings = 8;
+const PlanKnobs& plan_setting(int k);   // the k-th setting ng_capture tries (0 = the default)
+
 // Output of the device-resident planner (ng_resident_plan.cpp).
 struct ResidentPlan {
     int n_wg = 0;                              // persistent workgroups (grid size)

@@ -466,6 +466,21 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
 
 }  // namespace
 
+const PlanKnobs& plan_setting(int k) {
+    // far hand-over, spread penalty, 4-outputs-per-thread threshold, near hand-over, publish, far-run factor
+    static const PlanKnobs kSettings[kPlanSettings] = {
+        PlanKnobs(),                        // the default
+        {1.0, 2.0, 3, 0.4, 1.5, 1.2},       // cheaper hand-overs, workgroups busy for longer after a task
+        {1.0, 2.0, 3, 0.7, 2.5, 1.2},       // ... much longer: tasks of one stream alternate between workgroups
+        {1.0, 2.0, 3, 0.7, 0.6, 1.2},       // ... shorter: a stream stays on few workgroups
+        {1.0, 1.0, 3, 0.7, 1.5, 1.2},       // spreads over all XCDs more readily
+        {1.0, 2.0, 3, 0.7, 1.5, 1.0},       // far operands cost a tile nothing
+        {1.0, 2.0, 1 << 20, 0.7, 1.2, 1.2}, // windowed tasks never take 4 outputs per thread
+        {2.0, 2.0, 3, 0.7, 1.2, 1.2},       // a hand-over between XCDs costs twice as much: streams keep to themselves
+    };
+    return kSettings[std::min(std::max(k, 0), kPlanSettings - 1)];
+}
+
 int plan_resident(const ng_graph* g, int n_wg, int xcds, const PlanKnobs& knobs, ResidentPlan& plan) {
     const Schedule& sc = g->sched;
     const int n = (int)g->nodes.size();
@@ -763,11 +778,18 @@ bool resident_plan_is_consistent(const ng_graph* g, const ResidentPlan& plan) {
 
 extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, double* expected_us, int* n_entries,
                                     int* n_far_edges, int* coverage_ok) {
+    return ng_resident_dry_plan_setting(g, 0, n_workgroups, xcds, expected_us, n_entries, n_far_edges, coverage_ok);
+}
+
+extern "C" int ng_resident_dry_plan_setting(ng_graph* g, int setting, int n_workgroups, int xcds, double* expected_us,
+                                            int* n_entries, int* n_far_edges, int* coverage_ok) {
     using namespace ng;
     if (!g) return NG_EINVAL;
     if (g->phase < PLANNED) return g->fail(NG_ESTATE, "ng_resident_dry_plan: call ng_plan_memory first");
     if (n_workgroups < 8 || n_workgroups % 8 != 0 || xcds < 0 || xcds > 8)
         return g->fail(NG_EINVAL, "ng_resident_dry_plan: workgroups must be a positive multiple of 8, xcds 0..8");
+    if (setting < 0 || setting >= kPlanSettings)
+        return g->fail(NG_EINVAL, "ng_resident_dry_plan_setting: setting must be 0..%d", kPlanSettings - 1);
     std::vector<Task> saved;
     saved.swap(g->tasks);
     g->dry_run = true;
@@ -777,7 +799,7 @@ extern "C" int ng_resident_dry_plan(ng_graph* g, int n_workgroups, int xcds, dou
     static float fake_constants;
     for (int v = 0; v < (int)g->nodes.size() && rc == NG_OK; ++v) rc = build_task(g, v, fake_arena, &fake_constants, g->tasks[v]);
     ResidentPlan plan;
-    if (rc == NG_OK && plan_resident(g, n_workgroups, xcds, PlanKnobs(), plan) != NG_OK) rc = g->fail(NG_EINVAL, "too many E' parents");
+    if (rc == NG_OK && plan_resident(g, n_workgroups, xcds, plan_setting(setting), plan) != NG_OK) rc = g->fail(NG_EINVAL, "too many E' parents");
     if (rc == NG_OK) {
         if (expected_us) *expected_us = plan.est_us;
         if (n_entries) *n_entries = (int)plan.entries.size();

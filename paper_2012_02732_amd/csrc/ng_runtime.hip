@@ -293,18 +293,7 @@ int launch_resident(ng_graph* g);
 // a few times, and the fastest one stays - measured ahead of time on the device at hand, like
 // everything else that is fixed before the first real replay.
 int tune_resident(ng_graph* g) {
-    // far hand-over, spread penalty, 4-outputs-per-thread threshold, near hand-over, publish, far-run factor
-    static const PlanKnobs kSettings[8] = {
-        PlanKnobs(),                        // the default
-        {1.0, 2.0, 3, 0.4, 1.5, 1.2},       // cheaper hand-overs, workgroups busy for longer after a task
-        {1.0, 2.0, 3, 0.7, 2.5, 1.2},       // ... much longer: tasks of one stream alternate between workgroups
-        {1.0, 2.0, 3, 0.7, 0.6, 1.2},       // ... shorter: a stream stays on few workgroups
-        {1.0, 1.0, 3, 0.7, 1.5, 1.2},       // spreads over all XCDs more readily
-        {1.0, 2.0, 3, 0.7, 1.5, 1.0},       // far operands cost a tile nothing
-        {1.0, 2.0, 1 << 20, 0.7, 1.2, 1.2}, // windowed tasks never take 4 outputs per thread
-        {2.0, 2.0, 3, 0.7, 1.2, 1.2},       // a hand-over between XCDs costs twice as much: streams keep to themselves
-    };
-    const int trials = std::min(g->resident_plan_trials, 8);
+    const int trials = std::min(g->resident_plan_trials, kPlanSettings);
     g->resident_plan_kept = 0;
     if (trials <= 1 || getenv("NG_NO_TUNE")) return NG_OK;
     const int saved_mode = g->mode;
@@ -331,7 +320,7 @@ int tune_resident(ng_graph* g) {
     float best_us = 0;
     for (int k = 0; k < trials && rc == NG_OK; ++k) {
         ResidentPlan hp;
-        if ((rc = make_plan(g, kSettings[k], hp)) != NG_OK) break;
+        if ((rc = make_plan(g, plan_setting(k), hp)) != NG_OK) break;
         bool seen = false;
         for (const ResidentPlan& q : plans)
             seen = seen || (q.wg_first == hp.wg_first && q.entries.size() == hp.entries.size() &&

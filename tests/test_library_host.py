@@ -393,6 +393,32 @@ def test_device_resident_plan_covers_every_tile_once(name, n_wg, xcds):
     r.close()
 
 
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_every_planner_setting_tried_at_capture_gives_a_consistent_plan(name):
+    """ng_capture plans the device-resident replay under 8 settings of the planner's cost model and
+    keeps the fastest plan; each of them, rehearsed on the host, covers every tile once, keeps one
+    common order with parents first and has consistent completion counts - on 8 XCDs and on fewer."""
+    r = GraphRunner(workloads.make(name))
+    r.schedule()
+    r.plan()
+    base = B.ng_resident_dry_plan(r.g, 256, 0)
+    assert B.ng_resident_dry_plan_setting(r.g, 0, 256, 0) == base
+    expected = set()
+    for setting in range(8):
+        for n_wg, xcds in ((256, 0), (256, 3), (64, 8)):
+            d = B.ng_resident_dry_plan_setting(r.g, setting, n_wg, xcds)
+            assert d["ok"] and d["n_entries"] > 0 and d["expected_us"] > 0, (setting, n_wg, xcds, d)
+            if (n_wg, xcds) == (256, 0):
+                expected.add(round(d["expected_us"], 3))
+    if name in ("nasnet_style", "inception_style", "random200"):
+        assert len(expected) >= 4          # the settings really lead to different plans on the branchy DAGs
+    for bad in (-1, 8):
+        with pytest.raises(B.NgError) as e:
+            B.ng_resident_dry_plan_setting(r.g, bad, 256, 0)
+        assert e.value.code == B.NG_EINVAL
+    r.close()
+
+
 def test_device_resident_plan_argument_checks():
     r = GraphRunner(workloads.make("tiny_cell"))
     with pytest.raises(B.NgError) as e:
