@@ -243,7 +243,10 @@ int ng_resident_config(ng_graph* g, int workgroups_per_cu, int xcds, unsigned sp
  * the pre-run of Section 4.1 used for measuring as well as for recording. With 1 the default
  * setting's plan is taken unmeasured (capture is shorter and the plan does not depend on timing). */
 int ng_resident_plan_trials(ng_graph* g, int trials);
-/* *setting = which of the tried settings ng_capture kept (0 = the default one). Needs ng_capture. */
+/* *setting = which of the tried settings ng_capture kept (0 = the default one). With all 8 settings
+ * tried, ng_capture also re-plans the kept setting once with every task's cost corrected by the
+ * task times a traced replay of the kept plan measured, and keeps that plan instead if it replays
+ * faster: *setting = 8 then. Needs ng_capture. */
 int ng_resident_plan_kept(const ng_graph* g, int* setting);
 /* Per-task timeline of device-resident replays. enable != 0 switches recording on and clears
  * the record (off for 0). If ticks is not NULL it first receives what was recorded since the

@@ -71,6 +71,7 @@ struct PlanKnobs {
     double sync_near_us = 0.7;       // completion counter -> dependent workgroup running, same XCD (measured)
     double publish_us = 1.2;         // stores drained and counter bumped: the workgroup moves on to its next entry
     double far_run_factor = 1.2;     // a tile whose loads and stores all go through the memory side takes longer
+    std::vector<double> task_scale;  // per node: measured / modelled tile time of an earlier plan (empty: the model as it is)
 };
 
 constexpr int kPlanSettings = 8;
@@ -87,6 +88,7 @@ struct ResidentPlan {
     std::vector<int> order;                    // tasks in list order: every workgroup's list is a subsequence of it
     std::vector<int> fused_into;               // [n_nodes] convolution whose tiles also produce this task's result (no entries of its own), or -1
     std::vector<char> elided;                  // [n_nodes] concat with nothing to copy (inputs produced in place): no entries either
+    std::vector<double> model_run_us;          // [n_nodes] modelled time from a task's last wait to its last store (0: no workgroups of its own)
 };
 
 struct Runtime;  // HIP-side state, defined in ng_runtime.hip

@@ -127,12 +127,17 @@ struct Sim {
     std::vector<int> local_parent;   // E' parent whose completion this task does not wait for (same workgroups, same tiles), or -1
     std::vector<int> fused_into;     // convolution whose tiles also produce this (batch-norm / ReLU / add_n) task's result, or -1
     std::vector<char> elided;        // concat whose inputs were all produced in place: no work, no entries
+    std::vector<double> model_run;   // what the model expects between a task's last wait and its last store
     double makespan = 0;
 };
 
 void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& out) {
     const double kSyncNearUs = knobs.sync_near_us, kSyncFarUs = knobs.sync_far_us, kSpreadPenaltyUs = knobs.spread_penalty_us;
     const double kPublishUs = knobs.publish_us, kFarRunFactor = knobs.far_run_factor;
+    // the model's round time, corrected by what a traced replay measured for this task (if anything)
+    auto round_us = [&](int v, int kid, int subs) {
+        return tile_round_us(g, v, kid, subs) * (knobs.task_scale.empty() ? 1.0 : knobs.task_scale[v]);
+    };
     const Schedule& sc = g->sched;
     const int n = (int)g->nodes.size();
     const int per_xcd = n_wg / 8;
@@ -167,6 +172,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
     out.local_parent.assign(n, -1);
     out.fused_into.assign(n, -1);
     out.elided.assign(n, 0);
+    out.model_run.assign(n, 0.0);
     const bool allow_elide = getenv("NG_NO_ELIDE") == nullptr;
     const bool allow_fuse = getenv("NG_NO_FUSE") == nullptr;
     std::vector<double> free_at(n_wg, 0.0), finish(n, 0.0);
@@ -186,7 +192,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
         if (!g->tasks[v].fn) continue;
         double longest = 0;
         for (int c : children[v]) longest = std::max(longest, tail[c]);
-        tail[v] = longest + tile_round_us(g, v, g->tasks[v].kid, kSubs) + kSyncNearUs;
+        tail[v] = longest + round_us(v, g->tasks[v].kid, kSubs) + kSyncNearUs;
     }
     auto ready_time = [&](int v) {                              // all parents placed: when the last of them is visible
         const int home = stream_xcd[sc.stream_of[v]];
@@ -378,7 +384,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
             std::stable_sort(pl.cand.begin(), pl.cand.end(), [&](int a, int b) { return free_at[a] < free_at[b]; });
             for (int subs = kSubs; subs >= (heavy ? 1 : kSubs); --subs) {
                 const long units = units_for(ntiles0, subs);
-                const double cost = tile_round_us(g, v, kid0, subs) * (far_loads ? kFarRunFactor : 1.0);
+                const double cost = round_us(v, kid0, subs) * (far_loads ? kFarRunFactor : 1.0);
                 for (int rounds = 1; rounds <= 4; ++rounds) {
                     const int p = (int)std::min<long>((units + rounds - 1) / rounds, (long)pl.cand.size());
                     const long r = (units + p - 1) / p;
@@ -419,7 +425,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
                 double start = ready_without(u);
                 for (int w : wgs[u]) start = std::max(start, free_at[w]);
                 const long r = (units_for(nt, out.subs[u]) + (long)wgs[u].size() - 1) / (long)wgs[u].size();
-                const double f = start + kLocalUs + r * tile_round_us(g, v, kid, out.subs[u]) + kSyncNearUs;
+                const double f = start + kLocalUs + r * round_us(v, kid, out.subs[u]) + kSyncNearUs;
                 if (f < follow_finish) follow_finish = f, follow = u, follow_kid = kid, follow_ntiles = nt;
             }
         }
@@ -433,7 +439,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
             wgs[v] = wgs[follow];
             best_finish = follow_finish;
             r = (units_for(follow_ntiles, out.subs[v]) + (long)wgs[v].size() - 1) / (long)wgs[v].size();
-            begin = follow_finish - kSyncNearUs - r * tile_round_us(g, v, follow_kid, out.subs[v]);
+            begin = follow_finish - kSyncNearUs - r * round_us(v, follow_kid, out.subs[v]);
         } else {
             out.subs[v] = best_subs;
             wgs[v].assign(cand.begin(), cand.begin() + best_p);
@@ -441,8 +447,9 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
             begin = -1;
         }
         const int p = (int)wgs[v].size();
-        const double run = r * tile_round_us(g, v, out.kid[v], out.subs[v]);
+        const double run = r * round_us(v, out.kid[v], out.subs[v]);
         out.parts[v] = (unsigned)p;
+        out.model_run[v] = run;
         // a task spread over several XCDs collects its completions per XCD first
         int peers[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xcds_used = 0;
         for (int j = 0; j < p; ++j) ++peers[wgs[v][j] % 8];
@@ -498,6 +505,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, const PlanKnobs& knobs,
     plan.order = best.order;
     plan.fused_into = best.fused_into;
     plan.elided = best.elided;
+    plan.model_run_us = best.model_run;
 
     plan.tasks.assign(n, DevTask());
     for (int v = 0; v < n; ++v) {
