@@ -80,7 +80,7 @@ int issue_all(ng_graph* g, bool multi) {
     hipStream_t origin = rt.streams[0];
     if (!multi) {
         for (int v : sc.order)
-            if (int rc = launch(g, g->tasks[v], origin)) return rc;
+            if (int rc = launch(g, g->launch_tasks[v], origin)) return rc;
         return NG_OK;
     }
     if (!sc.fork.empty()) {
@@ -90,7 +90,7 @@ int issue_all(ng_graph* g, bool multi) {
     for (int v : sc.order) {
         hipStream_t s = rt.streams[sc.stream_of[v]];
         for (int u : sc.waits[v]) NG_HIP(hipStreamWaitEvent(s, rt.events[sc.event_of[u]], 0));
-        if (int rc = launch(g, g->tasks[v], s)) return rc;
+        if (int rc = launch(g, g->launch_tasks[v], s)) return rc;
         if (sc.event_of[v] >= 0) NG_HIP(hipEventRecord(rt.events[sc.event_of[v]], s));
     }
     for (int s : sc.join) {
@@ -119,11 +119,12 @@ int capture_single(ng_graph* g, int slot) {
 }
 
 // Multi-stream record. The library already knows everything a capture of the pre-run
-// would discover, so the graph is written down directly: one kernel node per task, an
+// would discover, so the graph is written down directly: one kernel node per launch, an
 // edge from the previous task of the same stream (FIFO order within a stream) and an
 // edge for every planned event wait (Lambda). This is node for node and edge for edge
 // the graph that capturing issue_all(multi = true) describes; fork/join scaffolding has
-// no counterpart because it carries no dependency.
+// no counterpart because it carries no dependency, and a task without a launch of its own
+// passes its dependencies on to whatever depends on it.
 int record_multi(ng_graph* g, int slot) {
     Runtime& rt = *g->rt;
     const Schedule& sc = g->sched;
@@ -131,16 +132,26 @@ int record_multi(ng_graph* g, int slot) {
     hipGraph_t graph = nullptr;
     NG_HIP(hipGraphCreate(&graph, 0));
     rt.graph[slot] = graph;
-    std::vector<hipGraphNode_t> node(n, nullptr);
+    // what a dependency on task v amounts to in the graph: its kernel node - or, for a task without a launch
+    // of its own (a batch-norm applied by its convolution's kernel), everything that task would have waited for
+    std::vector<std::vector<hipGraphNode_t>> stands_for(n);
     std::vector<int> last_on_stream(sc.n_streams, -1);
     for (int v : sc.order) {
-        const Task& t = g->tasks[v];
+        const Task& t = g->launch_tasks[v];
         const int st = sc.stream_of[v];
-        if (!t.fn) continue;                                   // input: no task, nothing to order
+        if (!t.fn && g->launch_fused_into[v] < 0) continue;    // input: no task, nothing to order
         std::vector<hipGraphNode_t> deps;
-        if (last_on_stream[st] >= 0) deps.push_back(node[last_on_stream[st]]);
-        for (int u : sc.waits[v])
-            if (node[u]) deps.push_back(node[u]);
+        auto depend_on = [&](int u) {
+            for (hipGraphNode_t d : stands_for[u])
+                if (std::find(deps.begin(), deps.end(), d) == deps.end()) deps.push_back(d);
+        };
+        if (last_on_stream[st] >= 0) depend_on(last_on_stream[st]);
+        for (int u : sc.waits[v]) depend_on(u);
+        last_on_stream[st] = v;
+        if (!t.fn) {
+            stands_for[v] = deps;
+            continue;
+        }
         void* args[1] = {const_cast<unsigned char*>(t.args)};
         hipKernelNodeParams kp{};
         kp.func = const_cast<void*>(t.fn);
@@ -149,8 +160,9 @@ int record_multi(ng_graph* g, int slot) {
         kp.sharedMemBytes = t.lds_bytes;
         kp.kernelParams = args;
         kp.extra = nullptr;
-        NG_HIP(hipGraphAddKernelNode(&node[v], graph, deps.empty() ? nullptr : deps.data(), deps.size(), &kp));
-        last_on_stream[st] = v;
+        hipGraphNode_t node = nullptr;
+        NG_HIP(hipGraphAddKernelNode(&node, graph, deps.empty() ? nullptr : deps.data(), deps.size(), &kp));
+        stands_for[v].assign(1, node);
     }
     if (const char* dot = getenv("NG_GRAPH_DOT")) (void)hipGraphDebugDotPrint(graph, dot, 0);   // for inspection only
     NG_HIP(hipGraphInstantiate(&rt.exec[slot], graph, nullptr, nullptr, 0));
@@ -464,6 +476,29 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
     g->tasks.assign(g->nodes.size(), Task());
     for (int v = 0; v < (int)g->nodes.size(); ++v)
         if (int rc = build_task(g, v, rt.arena, rt.constants ? rt.constants + const_off[v] : nullptr, g->tasks[v])) return rc;
+    // Modes 0-3 run one kernel per task, with one exception: a batch-norm / ReLU whose only input is a
+    // convolution result is applied by the convolution's kernel while the sums are in registers (the
+    // same arithmetic on the same values; both tensors are stored), so it has no launch of its own and
+    // whatever waits for it waits for the convolution. Not under a memory plan with reuse over time:
+    // there the batch-norm's buffer may still hold the convolution's own input when the convolution runs.
+    g->launch_tasks = g->tasks;
+    g->launch_fused_into.assign(g->nodes.size(), -1);
+    if (!g->memory_reuse && !getenv("NG_NO_GRAPH_FUSE")) {
+        std::vector<char> has_epilogue(g->nodes.size(), 0);
+        for (int v = 0; v < (int)g->nodes.size(); ++v) {
+            const Node& nd = g->nodes[v];
+            if ((nd.op != NG_OP_BN_ACT && nd.op != NG_OP_RELU) || nd.preds.size() != 1) continue;
+            const int u = nd.preds[0];
+            if (!g->tasks[u].fn || !has_bn_epilogue(g->tasks[u].kid) || has_epilogue[u] || !(g->nodes[u].out == nd.out)) continue;
+            const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
+            const Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};
+            if (takes_c3_args(g->tasks[u].kid)) reinterpret_cast<C3Args*>(g->launch_tasks[u].args)->ep = ep;
+            else reinterpret_cast<PwArgs*>(g->launch_tasks[u].args)->ep = ep;
+            has_epilogue[u] = 1;
+            g->launch_fused_into[v] = u;
+            g->launch_tasks[v].fn = nullptr;
+        }
+    }
 
     rt.events.resize(g->sched.n_events);
     for (auto& e : rt.events) NG_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
