@@ -105,7 +105,7 @@ struct ng_graph {
     std::vector<ng::Task> tasks;                         // one stand-alone kernel per node (inputs: none)
     std::vector<ng::Task> launch_tasks;                  // what modes 0-3 launch: the same, except that a batch-norm / ReLU directly behind
                                                          // a convolution is applied by that convolution's kernel and has no launch of its own
-    std::vector<int> launch_fused_into;                  // [n_nodes] that convolution, or -1
+    std::vector<int> launch_fused_into;                  // [n_nodes] that convolution (the node itself: a concat with nothing to copy), or -1
     ng::Runtime* rt = nullptr;
     int mode = NG_MODE_GRAPH_MULTI;
     int assignment = NG_ASSIGN_ALGORITHM1;               // how ng_schedule forms the streams

@@ -498,6 +498,16 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
             g->launch_fused_into[v] = u;
             g->launch_tasks[v].fn = nullptr;
         }
+        // likewise a concat all of whose inputs the memory plan placed inside its result: nothing to copy, no launch
+        for (int v = 0; v < (int)g->nodes.size() && !g->alias_of.empty(); ++v) {
+            const Node& nd = g->nodes[v];
+            if (nd.op != NG_OP_CONCAT) continue;
+            bool in_place = true;
+            for (int u : nd.preds) in_place = in_place && g->alias_of[u] == v && g->tasks[u].fn;
+            if (!in_place) continue;
+            g->launch_fused_into[v] = v;                       // stands for its own dependencies
+            g->launch_tasks[v].fn = nullptr;
+        }
     }
 
     rt.events.resize(g->sched.n_events);
