@@ -198,6 +198,10 @@ void* ng_tensor_ptr(const ng_graph* g, int id);
 /* ---- 3. replay (Section 4.1: raw submission of the recorded tasks) ---- */
 
 enum {
+    /* Modes 0-3 run one stand-alone kernel per task, except that a batch-norm / ReLU whose only input is a
+     * convolution result is applied by the convolution's kernel (both tensors are stored) and a concat whose
+     * inputs were all produced in place is not launched; such a task keeps its place in the schedule (its
+     * waits and its event), and every tensor equals the one-kernel-per-task result bit for bit. */
     NG_MODE_GRAPH_MULTI = 0,  /* captured multi-stream graph, one hipGraphLaunch (default) */
     NG_MODE_GRAPH_SINGLE = 1, /* captured single-stream graph */
     NG_MODE_EAGER_SINGLE = 2, /* task table launched kernel by kernel on the origin stream */
