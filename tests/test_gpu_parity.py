@@ -651,3 +651,36 @@ def test_plan_trials_at_capture_keep_a_correct_plan(name):
             r.close()
     for v in w.outputs:
         assert np.array_equal(outs[8][v], outs[1][v])
+
+
+@pytest.mark.parametrize("name", ["chain50", "inception_style", "nasnet_style"])
+def test_launch_modes_with_and_without_epilogues_agree_bit_for_bit(name, monkeypatch):
+    """Modes 0-3 apply a batch-norm / ReLU directly behind a convolution in the convolution's kernel and
+    do not launch a concat whose inputs are already in place. With that switched off (one kernel per
+    task) every tensor of every node must come out the same, bit for bit, in each of the four modes -
+    the batch-norm outputs, the raw convolution results next to them, and the concat results."""
+    w = workloads.make(name)
+    modes = (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_EAGER_SINGLE, B.NG_MODE_EAGER_MULTI)
+
+    def run_all():
+        r = GraphRunner(w, DEV)
+        r.prepare(plan_trials=1)
+        try:
+            got = {}
+            for mode in modes:
+                r.arena.zero_()
+                r.set_input(w.input)
+                torch.cuda.synchronize()
+                r.replay(mode)
+                r.sync()
+                got[mode] = [r.output(v) for v in range(len(w.nodes))]
+            return got
+        finally:
+            r.close()
+
+    fused = run_all()
+    monkeypatch.setenv("NG_NO_GRAPH_FUSE", "1")         # read by ng_bind
+    plain = run_all()
+    for mode in modes:
+        for v in range(1, len(w.nodes)):
+            assert np.array_equal(fused[mode][v], plain[mode][v]), (mode, v, w.nodes[v].op)
