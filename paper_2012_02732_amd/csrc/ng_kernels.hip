@@ -472,42 +472,43 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int k0 = 0; k0 < a.Cin; k0 += KC) {
-        // A slice: W[m0 + m][k0 + k] -> As[k][m]; consecutive threads walk k (contiguous in W).
-        // Loads are unconditional from clamped indices (independent, all in flight), zeroed afterwards.
-        if (live) {
-            constexpr int RM = kBlock / KC;                       // rows covered per pass
-            const int k = tid % KC, gk = k0 + k;
-            float v[TM / RM];
+    // A slice: W[m0 + m][k0 + k] -> As[k][m]; consecutive threads walk k (contiguous in W).
+    // B slice: X[k0 + k][n0 + n] -> Bs[k][n]; consecutive threads walk pixels.
+    // Loads are unconditional from clamped indices (independent, all in flight), zeroed when they
+    // are stored. The loads of slice k0 + KC are issued before the matrix instructions of slice k0
+    // and stored after them, so their latency overlaps with the arithmetic.
+    constexpr int RM = kBlock / KC;                           // rows of A covered per pass
+    constexpr int RK = kBlock / TN;                           // k rows of B covered per pass
+    const int fk = tid % KC, fn = tid % TN, fcol = n0 + fn;
+    const int fccol = min(fcol, a.cols - 1);
+    const int fimg = fccol / a.HW, fpix = fccol - fimg * a.HW;
+    const float* xc = a.x + (size_t)fimg * a.Cin * a.HW + fpix;
+    float va[TM / RM], vb[KC / RK];
+    auto fetch = [&](int k0) {
 #pragma unroll
-            for (int p = 0; p < TM / RM; ++p) {
-                const int gm = m0 + tid / KC + p * RM;
-                v[p] = a.w[(size_t)min(gm, a.Cout - 1) * a.Cin + min(gk, a.Cin - 1)];
-            }
-            __builtin_amdgcn_sched_barrier(0);
+        for (int p = 0; p < TM / RM; ++p) {
+            const int gm = m0 + tid / KC + p * RM;
+            va[p] = a.w[(size_t)min(gm, a.Cout - 1) * a.Cin + min(k0 + fk, a.Cin - 1)];
+        }
+#pragma unroll
+        for (int p = 0; p < KC / RK; ++p) vb[p] = ldg(a.x, xc + (size_t)min(k0 + tid / TN + p * RK, a.Cin - 1) * a.HW, FIN);
+    };
+    if (live) fetch(0);
+    for (int k0 = 0; k0 < a.Cin; k0 += KC) {
+        if (live) {
 #pragma unroll
             for (int p = 0; p < TM / RM; ++p) {
                 const int m = tid / KC + p * RM;
-                As[k * LDA + m] = (m0 + m < a.Cout && gk < a.Cin) ? v[p] : 0.f;
+                As[fk * LDA + m] = (m0 + m < a.Cout && k0 + fk < a.Cin) ? va[p] : 0.f;
             }
-        }
-        // B slice: X[k0 + k][n0 + n] -> Bs[k][n]; consecutive threads walk pixels
-        if (live) {
-            constexpr int RK = kBlock / TN;                       // k rows covered per pass
-            const int n = tid % TN, col = n0 + n;
-            const int ccol = min(col, a.cols - 1);
-            const int img = ccol / a.HW, pix = ccol - img * a.HW;
-            const float* xc = a.x + (size_t)img * a.Cin * a.HW + pix;
-            float v[KC / RK];
-#pragma unroll
-            for (int p = 0; p < KC / RK; ++p) v[p] = ldg(a.x, xc + (size_t)min(k0 + tid / TN + p * RK, a.Cin - 1) * a.HW, FIN);
 #pragma unroll
             for (int p = 0; p < KC / RK; ++p) {
                 const int k = tid / TN + p * RK;
-                Bs[k * LDB + n] = (col < a.cols && k0 + k < a.Cin) ? v[p] : 0.f;
+                Bs[k * LDB + fn] = (fcol < a.cols && k0 + k < a.Cin) ? vb[p] : 0.f;
             }
         }
         __syncthreads();
+        if (live && k0 + KC < a.Cin) fetch(k0 + KC);
         if (live)
 #pragma unroll
         for (int kk = 0; kk < KC; kk += 4) {
