@@ -86,7 +86,7 @@ __device__ __forceinline__ float4 ldg4_any_far(const float* p) {
 }
 
 // LDS floats every workgroup owns: the largest user is the conv3x3 input patch (4 x 33 x 34).
-constexpr int kSmemFloats = 4 * 33 * 34;
+constexpr int kSmemFloats = 5120;
 
 // ------------------------------------------------------------------------------------
 // bn_act / relu: y = x * s[c] + t[c] (s, t folded from gamma, beta, mean, var), optional ReLU
@@ -545,21 +545,26 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
 }
 
 // ------------------------------------------------------------------------------------
-// conv3x3 with many output columns (large maps, batches): the same LDS-staged scheme as the
-// kernel above on the implicit GEMM Y[Cout x cols] = W[Cout x 9 Cin] * P[9 Cin x cols]. The
-// weight tensor [Cout][Cin][3][3] already is the row-major [Cout][9 Cin] matrix; the patch
-// matrix P[k = 9 ci + tap][col = (image, oy, ox)] is gathered while a K slice is filled
-// (clamped addresses, taps outside the image are zeroed). Every patch element is read from
-// global memory once per workgroup tile instead of once per 16 x 16 MFMA tile.
+// conv3x3 with many output columns (large maps, batches): the LDS-staged scheme of the kernel
+// above on the implicit GEMM Y[Cout x cols] = W'[Cout x K'] * P[K' x cols], with K ordered tap
+// first: k' = tap * CinP + ci, CinP = Cin rounded up to a multiple of KC. A K slice then has
+// ONE tap, so where the slice's patch rows lie relative to a column (and whether that is inside
+// the image) is worked out once per slice and thread, and the rows differ by a channel stride.
+// The weights are repacked at bind time into W'^T[k'][CoutP] (zero padded; CoutP a multiple of
+// TM), so a slice of them is read and stored to LDS along m without any mask. Rows of the LDS
+// slices are 16 (mod 32) floats apart: the four 16-lane groups of a wavefront, which read four
+// consecutive rows, then hit different banks. Every patch element is read from global memory
+// once per workgroup tile instead of once per 16 x 16 MFMA tile.
 // ------------------------------------------------------------------------------------
 template <int TM, int TN, int KC, bool FIN, class Wait>
 __device__ __forceinline__ void conv3x3_lds_tile(const C3Args& a, int tile, float* smem, int tid, bool live, Wait& wait) {
     const bool fout = wait.far_out();       // device-scope stores: some reader of the result sits on another XCD
     constexpr int WM = TM / 2, WN = TN / 2;           // per-wavefront sub-tile
     constexpr int FM = WM / 16, FN = WN / 16;         // 16 x 16 fragments per wavefront
-    constexpr int LDA = TM + 1, LDB = TN + 1;
+    constexpr int LDA = TM + 16, LDB = TN + 16;
+    static_assert(LDA % 32 == 16 && LDB % 32 == 16, "row pitch of the LDS slices");
     static_assert(KC * (LDA + LDB) <= kSmemFloats, "LDS budget");
-    static_assert(kBlock % KC == 0 && kBlock % TN == 0 && TM % (kBlock / KC) == 0 && KC % (kBlock / TN) == 0, "fill pattern");
+    static_assert(kBlock % TM == 0 && kBlock % TN == 0 && KC % (kBlock / TM) == 0 && KC % (kBlock / TN) == 0, "fill pattern");
     float* As = smem;                                 // [KC][LDA]
     float* Bs = smem + KC * LDA;                      // [KC][LDB]
 
@@ -567,7 +572,8 @@ __device__ __forceinline__ void conv3x3_lds_tile(const C3Args& a, int tile, floa
     const int wm = wave >> 1, wn = wave & 1;
     const int by = tile / a.tiles_n, bx = tile - by * a.tiles_n;
     const int m0 = by * TM, n0 = bx * TN;
-    const int K = 9 * a.Cin, HWo = a.Ho * a.Wo, HW = a.H * a.W;
+    const int CinP = a.groups, CoutP = (a.Cout + TM - 1) / TM * TM;
+    const int HWo = a.Ho * a.Wo, HW = a.H * a.W;
     // the column this thread fills in every B slice
     const int fill_col = n0 + tid % TN;
     const int ccol = min(fill_col, a.cols - 1);
@@ -575,6 +581,9 @@ __device__ __forceinline__ void conv3x3_lds_tile(const C3Args& a, int tile, floa
     const int foy = fpix / a.Wo, fox = fpix - foy * a.Wo;
     const int iy0 = foy * a.stride - a.pad, ix0 = fox * a.stride - a.pad;
     const float* xin = a.x + (size_t)fimg * a.Cin * HW;
+    // the weight column this thread fills in every A slice
+    constexpr int RA = kBlock / TM, RB = kBlock / TN;            // k rows covered per pass
+    const float* wcol = a.wp + m0 + tid % TM + (size_t)(tid / TM) * CoutP;
 
     f32x4 acc[FM][FN];
 #pragma unroll
@@ -583,59 +592,45 @@ __device__ __forceinline__ void conv3x3_lds_tile(const C3Args& a, int tile, floa
         for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
     wait();
 
-    for (int k0 = 0; k0 < K; k0 += KC) {
-        if (live) {
-            // A slice: W[m0 + m][k0 + k] -> As[k][m]; consecutive threads walk k (contiguous in W)
-            constexpr int RM = kBlock / KC;
-            const int k = tid % KC, gk = k0 + k;
-            float v[TM / RM];
+    for (int tap = 0; tap < 9; ++tap) {
+        const int dr = tap / 3, dc = tap - 3 * dr;
+        const int iy = iy0 + dr, ix = ix0 + dc;
+        const bool inside = fill_col < a.cols && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+        const float* xtap = xin + min(max(iy, 0), a.H - 1) * a.W + min(max(ix, 0), a.W - 1);
+        for (int c0 = 0; c0 < CinP; c0 += KC) {
+            if (live) {
+                float v[KC / RA], pv[KC / RB];
+                const float* wk = wcol + (size_t)(tap * CinP + c0) * CoutP;
 #pragma unroll
-            for (int p = 0; p < TM / RM; ++p) {
-                const int gm = m0 + tid / KC + p * RM;
-                v[p] = a.w[(size_t)min(gm, a.Cout - 1) * K + min(gk, K - 1)];
-            }
-            // B slice: P[k0 + k][n0 + n] -> Bs[k][n]; consecutive threads walk columns
-            constexpr int RK = kBlock / TN;
-            float pv[KC / RK];
-            unsigned inside = 0;
+                for (int p = 0; p < KC / RA; ++p) v[p] = wk[(size_t)p * RA * CoutP];
 #pragma unroll
-            for (int p = 0; p < KC / RK; ++p) {
-                const int gk2 = min(k0 + tid / TN + p * RK, K - 1);
-                const int ci = gk2 / 9, tap = gk2 - 9 * ci;
-                const int dr = (tap * 11) >> 5, dc = tap - 3 * dr;   // tap / 3, tap % 3 for tap < 9
-                const int iy = iy0 + dr, ix = ix0 + dc;
-                const bool in = (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
-                inside |= (in ? 1u : 0u) << p;
-                pv[p] = ldg(a.x, xin + (size_t)ci * HW + min(max(iy, 0), a.H - 1) * a.W + min(max(ix, 0), a.W - 1), FIN);
-            }
-            __builtin_amdgcn_sched_barrier(0);                   // all loads of the slice are issued before the first use
+                for (int p = 0; p < KC / RB; ++p) pv[p] = ldg(a.x, xtap + (size_t)min(c0 + tid / TN + p * RB, a.Cin - 1) * HW, FIN);
+                __builtin_amdgcn_sched_barrier(0);               // all loads of the slice are issued before the first use
 #pragma unroll
-            for (int p = 0; p < TM / RM; ++p) {
-                const int m = tid / KC + p * RM;
-                As[k * LDA + m] = (m0 + m < a.Cout && gk < K) ? v[p] : 0.f;
-            }
+                for (int p = 0; p < KC / RA; ++p) As[(tid / TM + p * RA) * LDA + tid % TM] = v[p];
 #pragma unroll
-            for (int p = 0; p < KC / RK; ++p) {
-                const int kk = tid / TN + p * RK;
-                Bs[kk * LDB + tid % TN] = (fill_col < a.cols && k0 + kk < K && ((inside >> p) & 1u)) ? pv[p] : 0.f;
+                for (int p = 0; p < KC / RB; ++p) {
+                    const int kk = tid / TN + p * RB;
+                    Bs[kk * LDB + tid % TN] = (inside && c0 + kk < a.Cin) ? pv[p] : 0.f;
+                }
             }
+            __syncthreads();
+            if (live)
+#pragma unroll
+            for (int kk = 0; kk < KC; kk += 4) {
+                float af[FM], bf[FN];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) af[i] = As[(kk + (lane >> 4)) * LDA + wm * WM + i * 16 + (lane & 15)];
+#pragma unroll
+                for (int j = 0; j < FN; ++j) bf[j] = Bs[(kk + (lane >> 4)) * LDB + wn * WN + j * 16 + (lane & 15)];
+#pragma unroll
+                for (int i = 0; i < FM; ++i)
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i], bf[j], acc[i][j], 0, 0, 0);
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        if (live)
-#pragma unroll
-        for (int kk = 0; kk < KC; kk += 4) {
-            float af[FM], bf[FN];
-#pragma unroll
-            for (int i = 0; i < FM; ++i) af[i] = As[(kk + (lane >> 4)) * LDA + wm * WM + i * 16 + (lane & 15)];
-#pragma unroll
-            for (int j = 0; j < FN; ++j) bf[j] = Bs[(kk + (lane >> 4)) * LDB + wn * WN + j * 16 + (lane & 15)];
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x4f32(af[i], bf[j], acc[i][j], 0, 0, 0);
-        }
-        __syncthreads();
     }
 
 #pragma unroll
@@ -651,6 +646,16 @@ __device__ __forceinline__ void conv3x3_lds_tile(const C3Args& a, int tile, floa
                 if (m < a.Cout) store_with_epilogue(a.y, a.ep, ((size_t)img * a.Cout + m) * HWo + pix, m, acc[i][j][r], fout);
             }
         }
+}
+
+// W[Cout][Cin][3][3] -> W'^T[tap * CinP + ci][CoutP], zero where ci >= Cin or m >= Cout
+__global__ __launch_bounds__(kBlock) void pack_c3_lds_weights_kernel(const float* w, float* wp, int Cout, int Cin, int CinP, int CoutP, long total) {
+    const long idx = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= total) return;
+    const int m = (int)(idx % CoutP);
+    const int k = (int)(idx / CoutP);
+    const int tap = k / CinP, ci = k - tap * CinP;
+    wp[idx] = (m < Cout && ci < Cin) ? w[((size_t)m * Cin + ci) * 9 + tap] : 0.f;
 }
 
 // ------------------------------------------------------------------------------------
@@ -1504,6 +1509,9 @@ PwChoice choose_c3(const ng_graph* g, int v) {
     // many columns: the LDS-staged kernel reads each patch element once per 64- or 128-column tile (no repacked weights)
     if (nd.out.n * nd.out.h * nd.out.w >= kC3LdsMinCols) {
         c.kind = PwChoice::C3_LDS;
+        const long kc = nd.out.c <= 32 ? 16 : 32, tm = nd.out.c <= 32 ? 32 : 64;     // K slice and rows per tile of the two kernels
+        c.groups = (int)((cin + kc - 1) / kc * kc);                                    // CinP
+        c.packed = (size_t)(9 * c.groups) * (size_t)((nd.out.c + tm - 1) / tm * tm);  // W'^T[9 CinP][CoutP]
         return c;
     }
     c.kind = PwChoice::K4_WORD;
@@ -1542,7 +1550,10 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
     const int cin = (int)g->nodes[nd.preds[0]].out.c * (c3 ? 9 : 1), cout = (int)nd.out.c;
     if (!nd.weights[0]) return g->fail(NG_EINVAL, "node %d: weight 0 is a null device pointer", v);
     const dim3 grid((unsigned)((c.packed + kBlock - 1) / kBlock)), block(kBlock);
-    if (c.kind == PwChoice::DIRECT32)
+    if (c.kind == PwChoice::C3_LDS)
+        pack_c3_lds_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const float*>(nd.weights[0]), packed, cout, cin / 9, c.groups, (int)(c.packed / (9 * (size_t)c.groups)), (long)c.packed);
+    else if (c.kind == PwChoice::DIRECT32)
         pack_pw_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
             static_cast<const float*>(nd.weights[0]), packed, cout, cin, c.groups, (int)c.packed);
     else
@@ -1687,6 +1698,8 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.pad = nd.p.pad, a.stride = nd.p.stride;
             const PwChoice c = choose_c3(g, v);
             if (c.kind == PwChoice::C3_LDS) {
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
+                a.wp = packed, a.groups = c.groups;
                 a.cols = (int)(o.n * o.h * o.w);
                 if (a.Cout <= 32) {
                     a.tiles_n = (int)ceil_div(a.cols, 128);
