@@ -447,7 +447,11 @@ __device__ __forceinline__ void fc_gemv_tile(const FcArgs& a, int tile, float*, 
 // with cols = N * HW. v_mfma_f32_16x16x4_f32: A fragment lane l -> A[l % 16][l / 16],
 // B fragment lane l -> B[l / 16][l % 16], accumulator register r of lane l -> D[4 * (l / 16) + r][l % 16].
 // A workgroup of four wavefronts (2 x 2) owns a TM x TN output tile; K is walked in
-// slices of KC staged through LDS (A transposed to [k][m] so both fragments read rows).
+// slices of KC staged through LDS, A as [k][m] so both fragments read rows. The weights are
+// repacked at bind time into that order, W^T[CinP][CoutP] (zero padded; CinP a multiple of
+// KC, CoutP of TM), so a slice of them is read and stored along m without any mask. Rows of
+// the LDS slices are 16 (mod 32) floats apart: the four 16-lane groups of a wavefront, which
+// read four consecutive rows, then hit different banks.
 // ------------------------------------------------------------------------------------
 template <int TM, int TN, int KC, bool FIN, class Wait>
 __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
@@ -455,9 +459,10 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
     wait();
     constexpr int WM = TM / 2, WN = TN / 2;           // per-wavefront sub-tile
     constexpr int FM = WM / 16, FN = WN / 16;         // 16 x 16 fragments per wavefront
-    constexpr int LDA = TM + 1, LDB = TN + 1;
+    constexpr int LDA = TM + 16, LDB = TN + 16;
+    static_assert(LDA % 32 == 16 && LDB % 32 == 16, "row pitch of the LDS slices");
     static_assert(KC * (LDA + LDB) <= kSmemFloats, "LDS budget");
-    static_assert(kBlock % KC == 0 && kBlock % TN == 0 && TM % (kBlock / KC) == 0 && KC % (kBlock / TN) == 0, "fill pattern");
+    static_assert(kBlock % TM == 0 && kBlock % TN == 0 && KC % (kBlock / TM) == 0 && KC % (kBlock / TN) == 0, "fill pattern");
     float* As = smem;                                 // [KC][LDA]
     float* Bs = smem + KC * LDA;                      // [KC][LDB]
 
@@ -472,24 +477,22 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
 #pragma unroll
         for (int j = 0; j < FN; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // A slice: W[m0 + m][k0 + k] -> As[k][m]; consecutive threads walk k (contiguous in W).
-    // B slice: X[k0 + k][n0 + n] -> Bs[k][n]; consecutive threads walk pixels.
-    // Loads are unconditional from clamped indices (independent, all in flight), zeroed when they
-    // are stored. The loads of slice k0 + KC are issued before the matrix instructions of slice k0
-    // and stored after them, so their latency overlaps with the arithmetic.
-    constexpr int RM = kBlock / KC;                           // rows of A covered per pass
+    // A slice: W^T[k0 + k][m0 + m] -> As[k][m]; B slice: X[k0 + k][n0 + n] -> Bs[k][n]; consecutive
+    // threads walk m and the pixels. Loads of X are unconditional from clamped indices (independent,
+    // all in flight), zeroed when they are stored. The loads of slice k0 + KC are issued before the
+    // matrix instructions of slice k0 and stored after them, so their latency overlaps with the arithmetic.
+    constexpr int RA = kBlock / TM;                           // k rows of A covered per pass
     constexpr int RK = kBlock / TN;                           // k rows of B covered per pass
-    const int fk = tid % KC, fn = tid % TN, fcol = n0 + fn;
+    const int CoutP = (a.Cout + TM - 1) / TM * TM;
+    const float* wcol = a.wp + m0 + tid % TM + (size_t)(tid / TM) * CoutP;
+    const int fn = tid % TN, fcol = n0 + fn;
     const int fccol = min(fcol, a.cols - 1);
     const int fimg = fccol / a.HW, fpix = fccol - fimg * a.HW;
     const float* xc = a.x + (size_t)fimg * a.Cin * a.HW + fpix;
-    float va[TM / RM], vb[KC / RK];
+    float va[KC / RA], vb[KC / RK];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int p = 0; p < TM / RM; ++p) {
-            const int gm = m0 + tid / KC + p * RM;
-            va[p] = a.w[(size_t)min(gm, a.Cout - 1) * a.Cin + min(k0 + fk, a.Cin - 1)];
-        }
+        for (int p = 0; p < KC / RA; ++p) va[p] = wcol[(size_t)(k0 + p * RA) * CoutP];
 #pragma unroll
         for (int p = 0; p < KC / RK; ++p) vb[p] = ldg(a.x, xc + (size_t)min(k0 + tid / TN + p * RK, a.Cin - 1) * a.HW, FIN);
     };
@@ -497,10 +500,7 @@ __device__ __forceinline__ void conv1x1_mfma_tile(const PwArgs& a, int tile, flo
     for (int k0 = 0; k0 < a.Cin; k0 += KC) {
         if (live) {
 #pragma unroll
-            for (int p = 0; p < TM / RM; ++p) {
-                const int m = tid / KC + p * RM;
-                As[fk * LDA + m] = (m0 + m < a.Cout && k0 + fk < a.Cin) ? va[p] : 0.f;
-            }
+            for (int p = 0; p < KC / RA; ++p) As[(tid / TM + p * RA) * LDA + tid % TM] = va[p];
 #pragma unroll
             for (int p = 0; p < KC / RK; ++p) {
                 const int k = tid / TN + p * RK;
@@ -646,6 +646,14 @@ __device__ __forceinline__ void conv3x3_lds_tile(const C3Args& a, int tile, floa
                 if (m < a.Cout) store_with_epilogue(a.y, a.ep, ((size_t)img * a.Cout + m) * HWo + pix, m, acc[i][j][r], fout);
             }
         }
+}
+
+// W[Cout][Cin] -> W^T[CinP][CoutP], zero where k >= Cin or m >= Cout
+__global__ __launch_bounds__(kBlock) void pack_pw_lds_weights_kernel(const float* w, float* wp, int Cout, int Cin, int CoutP, long total) {
+    const long idx = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= total) return;
+    const int m = (int)(idx % CoutP), k = (int)(idx / CoutP);
+    wp[idx] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
 }
 
 // W[Cout][Cin][3][3] -> W'^T[tap * CinP + ci][CoutP], zero where ci >= Cin or m >= Cout
@@ -1484,7 +1492,12 @@ PwChoice choose_pw(const ng_graph* g, int v) {
     const long hw = o.h * o.w, cols = o.n * hw;
     if (nd.op == NG_OP_FC && o.n <= 8) { c.kind = PwChoice::GEMV; return c; }
     // large problems (many 64 x 64 tiles) keep the LDS-tiled throughput kernel
-    if (((o.c + 63) / 64) * ((cols + 63) / 64) >= 256) { c.kind = PwChoice::LDS64; return c; }
+    if (((o.c + 63) / 64) * ((cols + 63) / 64) >= 256) {
+        c.kind = PwChoice::LDS64;
+        c.groups = (int)((cin + 15) / 16 * 16);                              // CinP: whole K slices of 16
+        c.packed = (size_t)c.groups * (size_t)((o.c + 63) / 64 * 64);       // W^T[CinP][CoutP]
+        return c;
+    }
     const bool vec = hw % 4 == 0;
     const long tiles16 = ((o.c + 15) / 16) * ((cols + 15) / 16);
     if (!vec && tiles16 > 128) {                             // enough tiles anyway: 32 x 32 tiles read less
@@ -1550,7 +1563,10 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
     const int cin = (int)g->nodes[nd.preds[0]].out.c * (c3 ? 9 : 1), cout = (int)nd.out.c;
     if (!nd.weights[0]) return g->fail(NG_EINVAL, "node %d: weight 0 is a null device pointer", v);
     const dim3 grid((unsigned)((c.packed + kBlock - 1) / kBlock)), block(kBlock);
-    if (c.kind == PwChoice::C3_LDS)
+    if (c.kind == PwChoice::LDS64)
+        pack_pw_lds_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const float*>(nd.weights[0]), packed, cout, cin, (int)(c.packed / (size_t)c.groups), (long)c.packed);
+    else if (c.kind == PwChoice::C3_LDS)
         pack_c3_lds_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
             static_cast<const float*>(nd.weights[0]), packed, cout, cin / 9, c.groups, (int)(c.packed / (9 * (size_t)c.groups)), (long)c.packed);
     else if (c.kind == PwChoice::DIRECT32)
@@ -1660,6 +1676,8 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.x = buf(nd.preds[0]), a.w = wf(0), a.bias = fc ? wf(1) : nullptr, a.y = buf(v);
             a.Cin = (int)i0.c, a.Cout = (int)o.c, a.HW = hw_out, a.cols = (int)(o.n * hw_out);
             if (c.kind == PwChoice::LDS64) {
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
+                a.wp = packed, a.ksteps = c.groups;
                 a.tiles_n = (int)ceil_div(a.cols, 64);
                 set_kernel<KID_PW_64>(t, a, (long)a.tiles_n * ceil_div(a.Cout, 64));
                 break;
