@@ -111,7 +111,9 @@ def test_conv1x1_mfma(shape, couts):
                                         ((1, 20, 17, 17), 24), ((1, 64, 8, 8), 40), ((1, 4, 3, 3), 9),
                                         # 2048 columns and more: the LDS-staged implicit GEMM (32 x 128 tiles up to 32
                                         # output channels, 64 x 64 above), ragged in every dimension, batch > 1
-                                        ((1, 16, 70, 70), 24), ((1, 8, 131, 135), 72), ((3, 9, 40, 41), 33), ((1, 32, 65, 64), 32)])
+                                        ((1, 16, 70, 70), 24), ((1, 8, 131, 135), 72), ((3, 9, 40, 41), 33), ((1, 32, 65, 64), 32),
+                                        # several K slices per tap with a ragged channel tail, in both kernels
+                                        ((1, 40, 46, 47), 70), ((2, 21, 33, 35), 20)])
 def test_conv3x3(shape, cout):
     def build(b):
         x = b.input(*shape)
