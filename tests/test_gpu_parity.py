@@ -98,7 +98,9 @@ def test_pool_and_depthwise(shape):
                                          ((1, 528, 7, 7), (176,)), ((1, 176, 7, 7), (176,)), ((1, 256, 7, 7), (17,)),
                                          ((1, 100, 5, 5), (33,)), ((1, 20, 3, 5), (16,)),
                                          # enough 64 x 64 tiles for the LDS-tiled throughput kernel
-                                         ((8, 64, 56, 56), (64,))])
+                                         ((8, 64, 56, 56), (64,)),
+                                         # ... ragged in every dimension (padded rows and columns of the repacked weights)
+                                         ((5, 37, 45, 47), (150,))])
 def test_conv1x1_mfma(shape, couts):
     def build(b):
         x = b.input(*shape)
