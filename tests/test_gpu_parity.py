@@ -125,7 +125,8 @@ def test_conv3x3(shape, cout):
     check_all_nodes(single_op(build), (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
 
 
-@pytest.mark.parametrize("n,cin,cout", [(1, 2048, 1000), (3, 100, 10), (8, 33, 5), (32, 2048, 1000), (9, 64, 7)])
+@pytest.mark.parametrize("n,cin,cout", [(1, 2048, 1000), (3, 100, 10), (8, 33, 5), (32, 2048, 1000), (9, 64, 7),
+                                        (1024, 70, 1000)])     # a batch large enough for the LDS-tiled kernel, with a bias
 def test_fc(n, cin, cout):
     def build(b):
         x = b.input(n, cin, 1, 1)
