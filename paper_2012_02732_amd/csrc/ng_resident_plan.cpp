@@ -28,6 +28,10 @@
 //     the XCD, through a device-scope counter when not. Whether a tensor is stored and loaded
 //     with device-scope accesses is decided from *all* direct readers (edges of E): a reader on
 //     another XCD reads the tensor itself, even when it only waits for an intermediate task.
+//   * The constants of the cost model that decide between plans of similar expected length
+//     (PlanKnobs) come with the call: the runtime plans under several settings of them
+//     (plan_setting) and keeps the plan that replays fastest, and can pass per-task correction
+//     factors measured in a traced replay.
 #include <algorithm>
 #include <functional>
 #include <cstdlib>
