@@ -5,7 +5,7 @@ tests, the smoke check and the benchmark's ``cpu_baseline`` leg do. It shares no
 code with the HIP library: both sides read the same workload descriptions
 (package ``workloads``) and nothing else.
 
-Two results are defined here, both written from the paper (Nimble,
+Three results are defined here, all written from the paper (Nimble,
 arXiv 2012.02732):
 
 * ``forward``  - the tensors a DAG computes. The method only changes *when*
@@ -14,6 +14,10 @@ arXiv 2012.02732):
   fp32 storage, fp64 arithmetic inside an operator.
 * ``schedule`` - Algorithm 1 (Section 4.2) followed step by step, plus the
   synchronisation plan of Appendix A, with every free choice fixed.
+
+* ``backward`` - (module ``backward``; no HIP counterpart yet) the gradients of a
+  DAG and a plain SGD update, the computation a recorded training iteration
+  (Section 5) would have to reproduce.
 
 Parity status: operator formulas are pinned against closed forms, pure-Python
 brute force and torch.nn.functional on CPU; the schedule is pinned by the
