@@ -14,10 +14,10 @@ arXiv 2012.02732):
   fp32 storage, fp64 arithmetic inside an operator.
 * ``schedule`` - Algorithm 1 (Section 4.2) followed step by step, plus the
   synchronisation plan of Appendix A, with every free choice fixed.
-
 * ``backward`` - (module ``backward``; no HIP counterpart yet) the gradients of a
   DAG and a plain SGD update, the computation a recorded training iteration
-  (Section 5) would have to reproduce.
+  (Section 5) would have to reproduce; pinned by central differences of an fp64
+  forward pass and by torch.autograd on CPU.
 
 Parity status: operator formulas are pinned against closed forms, pure-Python
 brute force and torch.nn.functional on CPU; the schedule is pinned by the
