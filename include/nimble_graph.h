@@ -163,12 +163,30 @@ int ng_plan_memory(ng_graph* g, size_t* arena_bytes);
  * chooses between the two graphs, and selecting NG_MODE_DEVICE_RESIDENT makes ng_replay fail
  * with NG_ESTATE. */
 int ng_set_memory_reuse(ng_graph* g, int on);
+/* Modes 0-3 launch one kernel per task, except that (on by default) a batch-norm / ReLU whose only
+ * input is a convolution result is applied by that convolution's kernel and a concat whose inputs
+ * were all produced in place is not launched. on = 0 switches both exceptions off: one kernel per
+ * task. Call before ng_bind (NG_ESTATE after). */
+int ng_set_launch_fusion(ng_graph* g, int on);
 /* offset[n_nodes], bytes[n_nodes] of each node's output inside the arena (host arrays). */
 int ng_get_offsets(const ng_graph* g, size_t* offset, size_t* bytes);
 
 /* Longest path of G under per-node weights t[n_nodes] (e.g. isolated kernel times):
  * the critical-path time of Section 3. path[] (room for n_nodes) receives the node ids. */
 int ng_critical_path(const ng_graph* g, const float* t, float* total, int* path, int* n_path);
+
+/* The dependency edges of the multi-stream HIP graph (NG_MODE_GRAPH_MULTI) exactly as ng_capture
+ * writes them, computed on the host (needs ng_plan_memory, no GPU): Section 4.1 replays the
+ * recorded tasks through one graph launch, and by Appendix A that record is only safe if every
+ * edge of E is ordered by the FIFO order of a stream or by a synchronised edge. fuse != 0: the
+ * graph as launched by default; 0: one kernel node per task (see ng_set_launch_fusion).
+ *   launched_by[n_nodes] (may be NULL): the task whose kernel node writes node v's tensor - v
+ *     itself, the convolution that also applies a fused batch-norm / ReLU, -1 for a network
+ *     input, -2 for a concat that is not launched because its inputs are produced in place;
+ *   src/dst[max_edges]: one entry per graph edge, as task ids (both ends have kernel nodes);
+ *   *n_edges: the number of edges; with max_edges = 0 only the count is returned, a positive
+ *     max_edges that is too small gives NG_ENOMEM. All arrays are caller-owned host memory. */
+int ng_get_graph_edges(ng_graph* g, int fuse, int* launched_by, int* n_edges, int* src, int* dst, int max_edges);
 
 /* ---- 2b. ahead-of-time pass, GPU part (Section 4.1: pre-run once, record the tasks) ---- */
 
@@ -202,7 +220,13 @@ enum {
      * convolution result is applied by the convolution's kernel (both tensors are stored) and a concat whose
      * inputs were all produced in place is not launched; such a task keeps its place in the schedule (its
      * waits and its event), and every tensor equals the one-kernel-per-task result bit for bit. */
-    NG_MODE_GRAPH_MULTI = 0,  /* captured multi-stream graph, one hipGraphLaunch (default) */
+    NG_MODE_GRAPH_MULTI = 0,  /* multi-stream graph, one hipGraphLaunch. LIMITATION: on one synthetic DAG (80 nodes,
+                                 33 streams) this HIP runtime let a kernel node start before its only dependency had
+                                 finished in 4-16 % of the launches, although the edge was in the graph. ng_capture
+                                 therefore replays this graph 8-64 times on a poisoned arena and compares every byte
+                                 with the single-stream graph's result (ng_graph_multi_check); if they ever differ
+                                 the mode is not a candidate of NG_MODE_AUTO and ng_replay refuses it (NG_ESTATE).
+                                 The check is a screen, not a proof: rare misorderings can pass it. */
     NG_MODE_GRAPH_SINGLE = 1, /* captured single-stream graph */
     NG_MODE_EAGER_SINGLE = 2, /* task table launched kernel by kernel on the origin stream */
     NG_MODE_EAGER_MULTI = 3,  /* task table launched on the assigned streams with real events */
@@ -215,15 +239,27 @@ enum {
                                    inputs were produced in place runs nothing (ng_resident_fusion reports which);
                                    every node's tensor is written all the same and equals the other modes' bit
                                    for bit. The plan passes a self-check at ng_capture or the capture fails. */
-    NG_MODE_AUTO = 5          /* whichever of modes 0, 1 and 4 was fastest in a short trial at ng_capture (an
+    NG_MODE_AUTO = 5          /* the default: whichever of modes 0, 1 and 4 was fastest in a short trial at ng_capture (an
                                    ahead-of-time choice like the rest of the schedule: DAGs of many tiny tasks
                                    gain most from mode 4, plain chains and large tasks from a HIP graph) */
 };
 int ng_replay_mode(ng_graph* g, int mode);
 /* The mode NG_MODE_AUTO stands for (0, 1 or 4) and the median replay + wait times, in
  * microseconds, the trial at ng_capture measured for modes 0, 1 and 4 (HOST array of 3;
- * either pointer may be NULL). */
+ * either pointer may be NULL). 0 for a mode that was not a candidate: mode 0 when its check
+ * failed, mode 4 under a memory plan with reuse. */
 int ng_auto_mode(const ng_graph* g, int* mode, float* trial_us);
+/* Result of the check of the multi-stream graph at ng_capture (see NG_MODE_GRAPH_MULTI):
+ * *state = 1 every compared replay reproduced the single-stream result byte for byte, -1 some
+ * replay did not (or the caller distrusts it), 0 not checked; *replays_compared = how many. */
+int ng_graph_multi_check(const ng_graph* g, int* state, int* replays_compared);
+/* Run the same check again with `replays` (1..100000) replays, e.g. for more confidence than the
+ * 8-64 replays of ng_capture give; may turn state 1 into -1, never back. Overwrites the arena
+ * (network inputs are kept); waits for the origin stream. NG_MODE_AUTO is re-decided. */
+int ng_graph_multi_recheck(ng_graph* g, int replays);
+/* For a caller whose own validation caught the multi-stream graph with a wrong result: marks it
+ * as failed (state -1): NG_MODE_AUTO no longer picks it and ng_replay refuses it. */
+int ng_graph_multi_distrust(ng_graph* g);
 /* Asynchronous: enqueue one inference on the origin stream (hip_streams[0]). */
 int ng_replay(ng_graph* g);
 /* Wait until the origin stream is idle. */

@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libnimble_g
 # every symbol include/nimble_graph.h declares
 SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_output", "ng_num_nodes",
            "ng_node_shape", "ng_schedule", "ng_set_assignment", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
-           "ng_plan_memory", "ng_set_memory_reuse", "ng_get_offsets", "ng_critical_path", "ng_bind", "ng_capture",
+           "ng_plan_memory", "ng_set_memory_reuse", "ng_set_launch_fusion", "ng_get_graph_edges", "ng_get_offsets",
+           "ng_graph_multi_check", "ng_graph_multi_recheck", "ng_graph_multi_distrust", "ng_critical_path", "ng_bind", "ng_capture",
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
            "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_dry_plan_setting", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_plan_trials", "ng_resident_plan_kept", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
@@ -57,6 +58,11 @@ _sig = {
     "ng_plan_memory": (_I, [_P, _SZP]),
     "ng_set_memory_reuse": (_I, [_P, _I]),
     "ng_get_offsets": (_I, [_P, _SZP, _SZP]),
+    "ng_set_launch_fusion": (_I, [_P, _I]),
+    "ng_get_graph_edges": (_I, [_P, _I, _IP, _IP, _IP, _IP, _I]),
+    "ng_graph_multi_check": (_I, [_P, _IP, _IP]),
+    "ng_graph_multi_recheck": (_I, [_P, _I]),
+    "ng_graph_multi_distrust": (_I, [_P]),
     "ng_critical_path": (_I, [_P, _FP, _FP, _IP, _IP]),
     "ng_bind": (_I, [_P, _P, C.c_size_t, C.POINTER(_P), _I]),
     "ng_capture": (_I, [_P]),
@@ -195,6 +201,34 @@ def ng_get_offsets(g):
     off, nbytes = (C.c_size_t * n)(), (C.c_size_t * n)()
     check(g, lib.ng_get_offsets(g, off, nbytes))
     return list(off), list(nbytes)
+
+
+def ng_set_launch_fusion(g, on: bool):
+    check(g, lib.ng_set_launch_fusion(g, int(bool(on))))
+
+
+def ng_get_graph_edges(g, fuse=True):
+    """(launched_by[n_nodes], [(src task, dst task)]) of the multi-stream HIP graph."""
+    n, ne = ng_num_nodes(g), C.c_int()
+    check(g, lib.ng_get_graph_edges(g, int(bool(fuse)), None, C.byref(ne), None, None, 0))
+    by, src, dst = _ints(n), _ints(ne.value), _ints(ne.value)
+    check(g, lib.ng_get_graph_edges(g, int(bool(fuse)), by, C.byref(ne), src, dst, ne.value))
+    return list(by[:n]), list(zip(src[:ne.value], dst[:ne.value]))
+
+
+def ng_graph_multi_check(g):
+    """(state, replays compared): 1 reproduced the single-stream result, -1 did not, 0 not checked."""
+    st, k = C.c_int(), C.c_int()
+    check(g, lib.ng_graph_multi_check(g, C.byref(st), C.byref(k)))
+    return st.value, k.value
+
+
+def ng_graph_multi_recheck(g, replays: int):
+    check(g, lib.ng_graph_multi_recheck(g, replays))
+
+
+def ng_graph_multi_distrust(g):
+    check(g, lib.ng_graph_multi_distrust(g))
 
 
 def ng_critical_path(g, t):

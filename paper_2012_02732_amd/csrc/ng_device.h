@@ -280,6 +280,8 @@ struct DevPlan {
     int done_stride;                 // words between two tasks' counters (spreads them over memory channels)
     int poll_sleep;                  // 0, 1, 2: back-off between two polls (1, 4, 16 sleep units)
     unsigned long long* trace;       // optional [n_entries][3]: the entry starts to wait, is past the wait, has stored its tiles (100 MHz clock)
+    unsigned long long* xcc_seen;    // [8] (replay number << 8 | XCC id) last filed per workgroup class (index mod 8); nullptr: every hand-over is device scope, nothing to check
 };
+constexpr int kErrorXcdMapping = 0x40000000;   // error-flag value: workgroups of one class (index mod 8) ran on different XCDs
 
 }  // namespace ng

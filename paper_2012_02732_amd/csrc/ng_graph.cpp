@@ -277,7 +277,7 @@ int ng_plan_memory(ng_graph* g, size_t* arena_bytes) {
     // nothing to copy for it. Everything else gets a private buffer; nothing is reused.
     g->alias_of.assign(n, -1);
     std::vector<size_t> inside(n, 0);                       // byte offset inside the concat's buffer
-    if (!getenv("NG_NO_CONCAT_ALIAS"))
+    if (!knob("NG_NO_CONCAT_ALIAS"))
         for (size_t c = 0; c < n; ++c) {
             const Node& cat = g->nodes[c];
             if (cat.op != NG_OP_CONCAT || cat.out.n != 1) continue;
@@ -354,6 +354,13 @@ int ng_set_memory_reuse(ng_graph* g, int on) {
     if (!g) return NG_EINVAL;
     if (g->phase > SCHEDULED) return g->fail(NG_ESTATE, "ng_set_memory_reuse: the memory plan is already made");
     g->memory_reuse = on != 0;
+    return NG_OK;
+}
+
+int ng_set_launch_fusion(ng_graph* g, int on) {
+    if (!g) return NG_EINVAL;
+    if (g->phase >= BOUND) return g->fail(NG_ESTATE, "ng_set_launch_fusion: the task table is already built");
+    g->launch_fusion = on != 0;
     return NG_OK;
 }
 

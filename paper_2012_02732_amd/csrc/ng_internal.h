@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdint>
 #include <cstdio>
+#include <cstdlib>
 #include <string>
 #include <vector>
 
@@ -91,6 +92,28 @@ struct ResidentPlan {
     std::vector<double> model_run_us;          // [n_nodes] modelled time from a task's last wait to its last store (0: no workgroups of its own)
 };
 
+// What modes 0-3 launch and how the multi-stream HIP graph orders it (ng_launch_graph.cpp).
+struct LaunchGraph {
+    std::vector<int> nodes;                    // tasks with a kernel node of their own, in submission order
+    std::vector<std::vector<int>> deps;        // per entry of `nodes`: the launched tasks it depends on
+};
+
+// Measurement switches (the ablations quoted in the design notes) exist only in a build with
+// -DNG_MEASUREMENT_KNOBS; the product build reads no environment variable at all.
+#ifdef NG_MEASUREMENT_KNOBS
+inline const char* knob(const char* name) { return getenv(name); }
+#else
+inline const char* knob(const char*) { return nullptr; }
+#endif
+// integer switch, range-checked; `fallback` when unset or malformed
+inline long knob_int(const char* name, long lo, long hi, long fallback) {
+    const char* e = knob(name);
+    if (!e || !*e) return fallback;
+    char* end = nullptr;
+    const long v = strtol(e, &end, 10);
+    return (end && *end == 0 && v >= lo && v <= hi) ? v : fallback;
+}
+
 struct Runtime;  // HIP-side state, defined in ng_runtime.hip
 
 }  // namespace ng
@@ -107,7 +130,10 @@ struct ng_graph {
                                                          // a convolution is applied by that convolution's kernel and has no launch of its own
     std::vector<int> launch_fused_into;                  // [n_nodes] that convolution (the node itself: a concat with nothing to copy), or -1
     ng::Runtime* rt = nullptr;
-    int mode = NG_MODE_GRAPH_MULTI;
+    int mode = NG_MODE_AUTO;
+    bool launch_fusion = true;                           // modes 0-3: batch-norm / ReLU applied by the convolution's kernel, in-place concats not launched
+    int graph_multi_state = 0;                           // capture-time check of the multi-stream graph: 0 not run, 1 reproduced the single-stream result, -1 did not
+    int graph_multi_checked = 0;                         // replays of it that were compared
     int assignment = NG_ASSIGN_ALGORITHM1;               // how ng_schedule forms the streams
     bool memory_reuse = false;                           // ng_plan_memory may give a dead tensor's buffer to a later one
     int auto_mode = NG_MODE_GRAPH_MULTI;                 // what NG_MODE_AUTO resolves to (set by ng_capture)
@@ -143,6 +169,9 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream);
 const void* resident_kernel_handle(bool full);
 const void* empty_kernel_handle();
 const void* xcd_probe_kernel_handle();
+// ng_launch_graph.cpp
+void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, std::vector<int>& fused_into);
+void build_launch_graph(const ng_graph* g, const std::vector<Task>& tasks, const std::vector<int>& fused_into, LaunchGraph& out);
 // ng_resident_plan.cpp: xcds = 0 lets the cost model choose among 1, 2, 4, 8.
 int plan_resident(const ng_graph* g, int n_wg, int xcds, const PlanKnobs& knobs, ResidentPlan& plan);
 bool resident_plan_is_consistent(const ng_graph* g, const ResidentPlan& plan);

@@ -1340,6 +1340,15 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
     float* smem = smem_all + sub * kSmemFloats;
     if (lane == 0) s_abort = 0;
     const int e_begin = plan.wg_first[blockIdx.x], e_end = plan.wg_first[blockIdx.x + 1];
+    // The plan keeps tensors in XCD-private L2s on the assumption that workgroups with equal index mod 8
+    // share an XCD. Every launch checks it: each workgroup files its XCC id under its class together with
+    // the replay number (a maximum, so whoever comes second in a class sees what the first one filed); the
+    // answer is looked at when the workgroup is done, and a disagreement raises the error flag.
+    unsigned long long xcc_prev = 0, xcc_mine = 0;
+    if (plan.xcc_seen != nullptr && lane == 0) {
+        xcc_mine = ((unsigned long long)epoch << 8) | (unsigned long long)(__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 15u);   // XCC_ID, bits 3:0
+        xcc_prev = __hip_atomic_fetch_max(plan.xcc_seen + (blockIdx.x & 7), xcc_mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 
     for (int chunk = e_begin; chunk < e_end; chunk += kRecordsInLds) {
         // this workgroup's next records: global memory -> LDS, 16 bytes per lane and load
@@ -1388,7 +1397,14 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
 #undef NG_CASE
                 default: break;
             }
-            __syncthreads();             // every thread's stores have reached L2 (write-through L1, counted stores)
+            // Publish protocol, step 1: every wave waits until all of its own vector memory operations have been
+            // acknowledged (stores are counted by vmcnt on this target and a store is acknowledged by the level
+            // its scope names: the XCD's L2 for a plain store through the write-through L1, the memory side for
+            // an sc1 store). The barrier's own workgroup-scope fence does not include this wait. Step 2: the
+            // barrier - every wave of the workgroup is past step 1. Step 3 (below): one lane bumps the counter,
+            // an operation issued after the barrier and therefore after every acknowledgement.
+            __builtin_amdgcn_s_waitcnt(0x0F70);                 // vmcnt(0), expcnt and lgkmcnt untouched
+            __syncthreads();
             if (s_abort) return;
             if (stamp != nullptr && lane == 0) stamp[2] = wall_clock64();
             if (lane == 0) {
@@ -1409,6 +1425,10 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
                     __hip_atomic_fetch_add(plan.done + (size_t)task * plan.done_stride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+    }
+    if (plan.xcc_seen != nullptr && lane == 0 && (xcc_prev >> 8) == (xcc_mine >> 8) && (xcc_prev & 255u) != (xcc_mine & 255u)) {
+        atomicExch(plan.error_dev, kErrorXcdMapping);
+        *plan.error_host = kErrorXcdMapping;
     }
 }
 

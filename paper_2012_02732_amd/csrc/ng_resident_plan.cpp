@@ -145,8 +145,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
     const Schedule& sc = g->sched;
     const int n = (int)g->nodes.size();
     const int per_xcd = n_wg / 8;
-    const bool debug = getenv("NG_PLAN_DEBUG") != nullptr;
-    const bool allow_local = getenv("NG_NO_LOCAL") == nullptr;
+    const bool debug = knob("NG_PLAN_DEBUG") != nullptr;
+    const bool allow_local = knob("NG_NO_LOCAL") == nullptr;
 
     // the planner counts work in units of `subs` tiles: what one workgroup does in one round
     auto units_for = [&](long ntiles, int subs) { return (ntiles + subs - 1) / subs; };
@@ -177,8 +177,8 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
     out.fused_into.assign(n, -1);
     out.elided.assign(n, 0);
     out.model_run.assign(n, 0.0);
-    const bool allow_elide = getenv("NG_NO_ELIDE") == nullptr;
-    const bool allow_fuse = getenv("NG_NO_FUSE") == nullptr;
+    const bool allow_elide = knob("NG_NO_ELIDE") == nullptr;
+    const bool allow_fuse = knob("NG_NO_FUSE") == nullptr;
     std::vector<double> free_at(n_wg, 0.0), finish(n, 0.0);
     std::vector<std::vector<int>> parents(n), wgs(n);
     for (auto& e : sc.meg) parents[e.second].push_back(e.first);
@@ -216,7 +216,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
     std::vector<char> fused_child(n, 0);                        // the convolution already carries a batch-norm epilogue
     std::vector<char> add_child(n, 0);                          // ... an add_n epilogue
     std::vector<int> placed_at(n, -1);                          // position in out.order
-    const bool allow_fuse_add = allow_fuse && getenv("NG_NO_FUSE_ADD") == nullptr;
+    const bool allow_fuse_add = allow_fuse && knob("NG_NO_FUSE_ADD") == nullptr;
 
     while (!open.empty()) {
         const int v = std::get<2>(open.top());
@@ -229,9 +229,9 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
         out.ntiles[v] = t.ntiles;
         // a windowed task that would need more than `p4_rounds` rounds on its stream's workgroups gets 4
         // outputs per thread (4 x the index arithmetic in one round: pays off only from there)
-        const int p4_rounds = getenv("NG_P4_ROUNDS") ? atoi(getenv("NG_P4_ROUNDS")) : knobs.p4_rounds;
+        const int p4_rounds = (int)knob_int("NG_P4_ROUNDS", 1, 1 << 20, knobs.p4_rounds);
         if (units_for(t.ntiles, kSubs) > p4_rounds * per_xcd && (t.kid == KID_POOL || t.kid == KID_DW_K3S1) &&
-            !getenv("NG_NO_P4")) {
+            !knob("NG_NO_P4")) {
             out.kid[v] = t.kid == KID_POOL ? KID_POOL_P4 : KID_DW_K3S1_P4;
             out.ntiles[v] = (g->nodes[v].out.elems() + 4 * kBlock - 1) / (4 * kBlock);
         }
@@ -296,7 +296,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
             const std::vector<int>& preds = g->nodes[v].preds;
             int host = -1, via = -1;
             // first choice: a host on the XCD of the add_n's own stream, where its readers most likely are
-            const int far_host = getenv("NG_FUSE_ADD_FAR") ? atoi(getenv("NG_FUSE_ADD_FAR")) : 1;
+            const int far_host = (int)knob_int("NG_FUSE_ADD_FAR", 0, 1, 1);
             for (int pass = 0; pass < 1 + far_host && host < 0; ++pass)
             for (int w : parents[v]) {
                 const int u = out.fused_into[w] >= 0 ? out.fused_into[w] : w;
@@ -458,7 +458,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
         int peers[8] = {0, 0, 0, 0, 0, 0, 0, 0}, xcds_used = 0;
         for (int j = 0; j < p; ++j) ++peers[wgs[v][j] % 8];
         for (int x = 0; x < 8; ++x) xcds_used += peers[x] > 0;
-        const bool two_level = xcds_used > 1 && !getenv("NG_NO_TWO_LEVEL");
+        const bool two_level = xcds_used > 1 && !knob("NG_NO_TWO_LEVEL");
         out.signals[v] = two_level ? (unsigned)xcds_used : (unsigned)p;
         for (int j = 0; j < p; ++j) {
             const int w = wgs[v][j];
@@ -598,7 +598,7 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, const PlanKnobs& knobs,
                 d.need[d.n_parents] = best.signals[src];
                 // producer and consumer on the same single XCD: the completion is signalled through that XCD's L2
                 const bool near = best.xcd[src] >= 0 && best.xcd[src] == best.xcd[dst] && !g->resident_all_far &&
-                                  !getenv("NG_NO_NEAR_COUNTERS");
+                                  !knob("NG_NO_NEAR_COUNTERS");
                 if (near) plan.tasks[src].publish |= 1u;
                 else plan.tasks[src].publish |= 2u, d.parent_far |= 1u << d.n_parents;
                 if (!near && best.signals[src] != best.parts[src]) plan.tasks[src].publish |= 4u;
@@ -782,7 +782,7 @@ bool resident_plan_is_consistent(const ng_graph* g, const ResidentPlan& plan) {
         if (c3) ok = ok && (reinterpret_cast<const C3Args*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
         if (pw) ok = ok && (reinterpret_cast<const PwArgs*>(plan.tasks[u].args)->ep.y != nullptr) == (fused_bns[u] == 1);
     }
-    if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d, fused: %d, concats in place: %d, self-check %s\n", n_local, n_fused, n_elided, ok ? "passed" : "FAILED");
+    if (knob("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN local hand-overs: %d, fused: %d, concats in place: %d, self-check %s\n", n_local, n_fused, n_elided, ok ? "passed" : "FAILED");
     return ok;
 }
 

@@ -122,35 +122,25 @@ int capture_single(ng_graph* g, int slot) {
 // would discover, so the graph is written down directly: one kernel node per launch, an
 // edge from the previous task of the same stream (FIFO order within a stream) and an
 // edge for every planned event wait (Lambda). This is node for node and edge for edge
-// the graph that capturing issue_all(multi = true) describes; fork/join scaffolding has
-// no counterpart because it carries no dependency, and a task without a launch of its own
-// passes its dependencies on to whatever depends on it.
+// the graph that capturing issue_all(multi = true) describes; which nodes and which edges
+// is decided by host-only code (build_launch_graph), the same that ng_get_graph_edges reports.
 int record_multi(ng_graph* g, int slot) {
     Runtime& rt = *g->rt;
-    const Schedule& sc = g->sched;
     const int n = (int)g->nodes.size();
+    LaunchGraph lg;
+    build_launch_graph(g, g->tasks, g->launch_fused_into, lg);
     hipGraph_t graph = nullptr;
     NG_HIP(hipGraphCreate(&graph, 0));
     rt.graph[slot] = graph;
-    // what a dependency on task v amounts to in the graph: its kernel node - or, for a task without a launch
-    // of its own (a batch-norm applied by its convolution's kernel), everything that task would have waited for
-    std::vector<std::vector<hipGraphNode_t>> stands_for(n);
-    std::vector<int> last_on_stream(sc.n_streams, -1);
-    for (int v : sc.order) {
+    std::vector<hipGraphNode_t> node_of(n, nullptr);
+    for (size_t i = 0; i < lg.nodes.size(); ++i) {
+        const int v = lg.nodes[i];
         const Task& t = g->launch_tasks[v];
-        const int st = sc.stream_of[v];
-        if (!t.fn && g->launch_fused_into[v] < 0) continue;    // input: no task, nothing to order
+        if (!t.fn) return g->fail(NG_EINVAL, "multi-stream graph: task %d has no kernel", v);
         std::vector<hipGraphNode_t> deps;
-        auto depend_on = [&](int u) {
-            for (hipGraphNode_t d : stands_for[u])
-                if (std::find(deps.begin(), deps.end(), d) == deps.end()) deps.push_back(d);
-        };
-        if (last_on_stream[st] >= 0) depend_on(last_on_stream[st]);
-        for (int u : sc.waits[v]) depend_on(u);
-        last_on_stream[st] = v;
-        if (!t.fn) {
-            stands_for[v] = deps;
-            continue;
+        for (int d : lg.deps[i]) {
+            if (!node_of[d]) return g->fail(NG_EINVAL, "multi-stream graph: task %d depends on task %d, which has no node yet", v, d);
+            deps.push_back(node_of[d]);
         }
         void* args[1] = {const_cast<unsigned char*>(t.args)};
         hipKernelNodeParams kp{};
@@ -160,12 +150,102 @@ int record_multi(ng_graph* g, int slot) {
         kp.sharedMemBytes = t.lds_bytes;
         kp.kernelParams = args;
         kp.extra = nullptr;
-        hipGraphNode_t node = nullptr;
-        NG_HIP(hipGraphAddKernelNode(&node, graph, deps.empty() ? nullptr : deps.data(), deps.size(), &kp));
-        stands_for[v].assign(1, node);
+        NG_HIP(hipGraphAddKernelNode(&node_of[v], graph, deps.empty() ? nullptr : deps.data(), deps.size(), &kp));
     }
-    if (const char* dot = getenv("NG_GRAPH_DOT")) (void)hipGraphDebugDotPrint(graph, dot, 0);   // for inspection only
+    if (const char* dot = knob("NG_GRAPH_DOT")) (void)hipGraphDebugDotPrint(graph, dot, 0);   // measurement builds: for inspection
     NG_HIP(hipGraphInstantiate(&rt.exec[slot], graph, nullptr, nullptr, 0));
+    return NG_OK;
+}
+
+// ---- capture-time check of the multi-stream graph -------------------------------------------
+// The multi-stream graph and the single-stream graph launch the same kernels with the same
+// arguments, so after any execution that respects the graph's edges every byte of the arena is
+// the same. The check replays the multi-stream graph several times on an arena whose tensors
+// were overwritten with a NaN pattern and compares the whole arena with what the single-stream
+// graph left behind. A graph replay that lets a kernel start before its producer (seen on one
+// synthetic DAG with this HIP runtime although every edge was in the graph) shows up as
+// a stale or poisoned tensor. It is a probabilistic screen, not a proof: an order violation that
+// happens in 4 % of launches is caught by 64 replays with probability 0.93.
+__global__ __launch_bounds__(256) void poison_kernel(unsigned* p, size_t words) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0x7FC0DEADu;
+}
+__global__ __launch_bounds__(256) void mismatch_kernel(const unsigned* a, const unsigned* b, size_t words, unsigned* count) {
+    unsigned mine = 0;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) mine += a[i] != b[i];
+    if (mine) atomicAdd(count, mine);
+}
+
+int issue_poison(ng_graph* g, hipStream_t s) {
+    Runtime& rt = *g->rt;
+    // everything except the network inputs (their values are the caller's)
+    std::vector<std::pair<size_t, size_t>> keep;
+    for (size_t v = 0; v < g->nodes.size(); ++v)
+        if (g->nodes[v].op == NG_OP_INPUT) keep.emplace_back(g->offset[v], g->offset[v] + g->bytes[v]);
+    std::sort(keep.begin(), keep.end());
+    size_t at = 0;
+    auto fill = [&](size_t lo, size_t hi) -> int {
+        if (hi <= lo) return NG_OK;
+        const size_t words = (hi - lo) / 4;
+        const unsigned blocks = (unsigned)std::min<size_t>((words + 255) / 256, 4096);
+        poison_kernel<<<dim3(blocks), dim3(256), 0, s>>>(reinterpret_cast<unsigned*>(rt.arena + lo), words);
+        NG_HIP(hipGetLastError());
+        return NG_OK;
+    };
+    for (auto& k : keep) {
+        if (int rc = fill(at, k.first)) return rc;
+        at = std::max(at, k.second);
+    }
+    return fill(at, g->arena_bytes);
+}
+
+int verify_graph_multi(ng_graph* g, int replays) {
+    Runtime& rt = *g->rt;
+    hipStream_t s = rt.streams[0];
+    g->graph_multi_state = 0;
+    g->graph_multi_checked = 0;
+    if (g->arena_bytes < 4) return NG_OK;
+    const size_t words = g->arena_bytes / 4;
+    unsigned* snap = nullptr;
+    unsigned* d_count = nullptr;
+    NG_HIP(hipMalloc(reinterpret_cast<void**>(&snap), words * 4));
+    int rc = NG_OK;
+    unsigned mismatches = 0;
+    auto hip_ok = [&](hipError_t e, const char* what) {
+        if (e != hipSuccess && rc == NG_OK) rc = g->fail(NG_EHIP, "checking the multi-stream graph: %s: %s", what, hipGetErrorString(e));
+        return e == hipSuccess;
+    };
+    if (hip_ok(hipMalloc(reinterpret_cast<void**>(&d_count), sizeof(unsigned)), "hipMalloc") &&
+        hip_ok(hipMemsetAsync(d_count, 0, sizeof(unsigned), s), "hipMemsetAsync") && (rc = issue_poison(g, s)) == NG_OK &&
+        hip_ok(hipGraphLaunch(rt.exec[1], s), "hipGraphLaunch (single stream)") &&
+        hip_ok(hipMemcpyAsync(snap, rt.arena, words * 4, hipMemcpyDeviceToDevice, s), "hipMemcpyAsync") &&
+        hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) {
+        if (replays <= 0) {
+            // about 40 ms of replays, 8 to 64 of them
+            const auto t0 = std::chrono::steady_clock::now();
+            if (hip_ok(hipGraphLaunch(rt.exec[0], s), "hipGraphLaunch") && hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) {
+                const double us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+                replays = (int)std::min(64.0, std::max(8.0, 40000.0 / std::max(us, 1.0)));
+            }
+        }
+        const unsigned blocks = (unsigned)std::min<size_t>((words + 255) / 256, 4096);
+        for (int i = 0; i < replays && rc == NG_OK; ++i) {
+            if ((rc = issue_poison(g, s)) != NG_OK) break;
+            if (!hip_ok(hipGraphLaunch(rt.exec[0], s), "hipGraphLaunch")) break;
+            mismatch_kernel<<<dim3(blocks), dim3(256), 0, s>>>(reinterpret_cast<const unsigned*>(rt.arena), snap, words, d_count);
+            if (!hip_ok(hipGetLastError(), "compare kernel")) break;
+            ++g->graph_multi_checked;
+        }
+        if (rc == NG_OK && hip_ok(hipMemcpyAsync(&mismatches, d_count, sizeof(unsigned), hipMemcpyDeviceToHost, s), "hipMemcpyAsync"))
+            hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize");
+    }
+    (void)hipStreamSynchronize(s);
+    if (d_count) (void)hipFree(d_count);
+    (void)hipFree(snap);
+    if (rc != NG_OK) return rc;
+    g->graph_multi_state = mismatches == 0 && g->graph_multi_checked > 0 ? 1 : -1;
+    // leave the arena as a normal replay leaves it
+    NG_HIP(hipGraphLaunch(rt.exec[1], s));
+    NG_HIP(hipStreamSynchronize(s));
     return NG_OK;
 }
 
@@ -205,7 +285,7 @@ int build_resident(ng_graph* g) {
         // before: which XCD a class gets does not matter, only that a class stays together
         rt.xcd_mapping_ok = true;
         for (int w = 0; w < n_wg; ++w) rt.xcd_mapping_ok = rt.xcd_mapping_ok && xcd_of[w] >= 0 && xcd_of[w] == xcd_of[w % 8];
-        if (!rt.xcd_mapping_ok && getenv("NG_PLAN_DEBUG")) {
+        if (!rt.xcd_mapping_ok && knob("NG_PLAN_DEBUG")) {
             fprintf(stderr, "XCD probe mismatch:");
             for (int w = 0; w < std::min(n_wg, 48); ++w) fprintf(stderr, " %d", xcd_of[w]);
             fprintf(stderr, "\n");
@@ -214,20 +294,21 @@ int build_resident(ng_graph* g) {
     }
     unsigned* d_done = nullptr;
     int* d_error = nullptr;
-    const char* env_stride = getenv("NG_DONE_STRIDE");
-    const char* env_sleep = getenv("NG_POLL_SLEEP");
-    rt.plan.done_stride = env_stride ? atoi(env_stride) : 64;    // one counter per 256 bytes
-    rt.plan.poll_sleep = env_sleep ? atoi(env_sleep) : 1;
+    rt.plan.done_stride = (int)knob_int("NG_DONE_STRIDE", 1, 1024, 64);    // one counter per 256 bytes
+    rt.plan.poll_sleep = (int)knob_int("NG_POLL_SLEEP", 0, 2, 1);
     rt.done_words = (size_t)n * rt.plan.done_stride;
-    NG_HIP(hipMalloc(&d_done, 10 * rt.done_words * sizeof(unsigned)));         // device-scope counters, the XCD-local ones, 8 per-XCD first-level ones
+    NG_HIP(hipMalloc(&d_done, (10 * rt.done_words + 18) * sizeof(unsigned)));  // device-scope counters, the XCD-local ones, 8 per-XCD first-level ones, 8 class records
     NG_HIP(hipMalloc(&d_error, sizeof(int)));
     NG_HIP(hipHostMalloc(reinterpret_cast<void**>(&rt.h_error), sizeof(int), hipHostMallocDefault));
     *rt.h_error = 0;
-    NG_HIP(hipMemset(d_done, 0, 10 * rt.done_words * sizeof(unsigned)));
+    NG_HIP(hipMemset(d_done, 0, (10 * rt.done_words + 18) * sizeof(unsigned)));
     NG_HIP(hipMemset(d_error, 0, sizeof(int)));
     rt.plan.done = d_done;
     rt.plan.done_near = d_done + rt.done_words;
     rt.plan.done_xcd = d_done + 2 * rt.done_words;
+    rt.plan.xcc_seen = rt.xcd_mapping_ok && !g->resident_all_far
+                           ? reinterpret_cast<unsigned long long*>(d_done + ((10 * rt.done_words + 1) & ~(size_t)1))   // 8-byte aligned, behind the counters
+                           : nullptr;
     rt.plan.error_dev = d_error;
     rt.plan.error_host = rt.h_error;
     rt.plan.spin_limit = g->resident_spin_limit;
@@ -242,8 +323,14 @@ int build_resident(ng_graph* g) {
 // The planner's output for one setting of its cost model, self-checked.
 int make_plan(ng_graph* g, const PlanKnobs& knobs_in, ResidentPlan& hp) {
     PlanKnobs knobs = knobs_in;
-    if (const char* e = getenv("NG_KNOBS"))                     // measurements only: "far,spread,p4,near,publish,farrun"
-        sscanf(e, "%lf,%lf,%d,%lf,%lf,%lf", &knobs.sync_far_us, &knobs.spread_penalty_us, &knobs.p4_rounds, &knobs.sync_near_us, &knobs.publish_us, &knobs.far_run_factor);
+    if (const char* e = knob("NG_KNOBS")) {                   // measurement builds only: "far,spread,p4,near,publish,farrun"
+        PlanKnobs k = knobs;
+        const bool parsed = sscanf(e, "%lf,%lf,%d,%lf,%lf,%lf", &k.sync_far_us, &k.spread_penalty_us, &k.p4_rounds, &k.sync_near_us, &k.publish_us, &k.far_run_factor) == 6;
+        auto sane = [](double v) { return v >= 0.0 && v <= 100.0; };
+        if (parsed && sane(k.sync_far_us) && sane(k.spread_penalty_us) && k.p4_rounds >= 1 && sane(k.sync_near_us) && sane(k.publish_us) &&
+            k.far_run_factor >= 0.5 && k.far_run_factor <= 10.0)
+            knobs = k;
+    }
     if (plan_resident(g, g->rt->n_wg, g->resident_xcds, knobs, hp) != NG_OK)
         return g->fail(NG_EINVAL, "device-resident replay: a node has more than %d E' parents", NG_MAX_PREDS);
     // never launch a plan that does not pass its own check (coverage, one common order with parents first, counts):
@@ -298,6 +385,7 @@ int install_plan(ng_graph* g, const ResidentPlan& hp) {
 }
 
 int launch_resident(ng_graph* g);
+void pick_auto_mode(ng_graph* g);
 
 // The planner's cost model cannot tell plans of similar expected length apart (its figures are a
 // few tenths of a microsecond off per task, and which of them matter depends on the DAG). So a
@@ -307,7 +395,7 @@ int launch_resident(ng_graph* g);
 int tune_resident(ng_graph* g) {
     const int trials = std::min(g->resident_plan_trials, kPlanSettings);
     g->resident_plan_kept = 0;
-    if (trials <= 1 || getenv("NG_NO_TUNE")) return NG_OK;
+    if (trials <= 1 || knob("NG_NO_TUNE")) return NG_OK;
     const int saved_mode = g->mode;
     g->mode = NG_MODE_DEVICE_RESIDENT;
     auto time_installed = [&](float* median_us) -> int {
@@ -345,7 +433,7 @@ int tune_resident(ng_graph* g) {
         setting_of.push_back(k);
         float us = 0;
         if ((rc = time_installed(&us)) != NG_OK) break;
-        if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN trial %d: expected %.1f us, replays in %.1f us\n", k, plans.back().est_us, us);
+        if (knob("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN trial %d: expected %.1f us, replays in %.1f us\n", k, plans.back().est_us, us);
         if (best < 0 || us < best_us) best = installed, best_us = us;
     }
     if (rc == NG_OK && best >= 0 && best != installed) rc = install_plan(g, plans[best]), installed = best;
@@ -353,7 +441,7 @@ int tune_resident(ng_graph* g) {
     // One more candidate: the kept setting planned again with every task's round time corrected by what
     // a traced replay of the kept plan measured for it (the model's per-kernel figures are averages; a
     // task's own shape can be 30 % off them).
-    if (rc == NG_OK && best >= 0 && trials >= kPlanSettings && !getenv("NG_NO_MEASURED_PLAN")) {
+    if (rc == NG_OK && best >= 0 && trials >= kPlanSettings && !knob("NG_NO_MEASURED_PLAN")) {
         const size_t n = g->nodes.size();
         std::vector<double> measured(n, 0.0);
         std::vector<unsigned long long> ticks(4 * n);
@@ -378,7 +466,7 @@ int tune_resident(ng_graph* g) {
             ResidentPlan hp;
             float us = 0;
             if ((rc = make_plan(g, knobs, hp)) == NG_OK && (rc = install_plan(g, hp)) == NG_OK && (rc = time_installed(&us)) == NG_OK) {
-                if (getenv("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN trial with measured task times: expected %.1f us, replays in %.1f us\n", hp.est_us, us);
+                if (knob("NG_PLAN_DEBUG")) fprintf(stderr, "PLAN trial with measured task times: expected %.1f us, replays in %.1f us\n", hp.est_us, us);
                 if (us < best_us) g->resident_plan_kept = kPlanSettings;
                 else rc = install_plan(g, plans[best]);
             }
@@ -394,7 +482,7 @@ int launch_resident(ng_graph* g) {
     hipStream_t origin = rt.streams[0];
     if (rt.counters_dirty) {                                   // a timed-out replay left partial counts behind
         NG_HIP(hipStreamSynchronize(origin));
-        NG_HIP(hipMemsetAsync(rt.plan.done, 0, 10 * rt.done_words * sizeof(unsigned), origin));   // on the stream of the launch below
+        NG_HIP(hipMemsetAsync(rt.plan.done, 0, (10 * rt.done_words + 18) * sizeof(unsigned), origin));   // on the stream of the launch below
         NG_HIP(hipMemsetAsync(rt.plan.error_dev, 0, sizeof(int), origin));
         *rt.h_error = 0;
         rt.epoch = 0;
@@ -405,6 +493,17 @@ int launch_resident(ng_graph* g) {
     void* args[2] = {&rt.plan, &epoch};
     NG_HIP(hipLaunchKernel(resident_kernel_handle(rt.resident_full), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
     return NG_OK;
+}
+
+// NG_MODE_AUTO = the fastest of the candidates that were tried (a trial time of 0 means: not a candidate)
+void pick_auto_mode(ng_graph* g) {
+    const int candidates[3] = {NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_DEVICE_RESIDENT};
+    g->auto_mode = NG_MODE_GRAPH_SINGLE;
+    float best = 0.f;
+    for (int i = 0; i < 3; ++i) {
+        if (g->auto_trial_us[i] <= 0.f || (i == 0 && g->graph_multi_state != 1)) continue;
+        if (best <= 0.f || g->auto_trial_us[i] < best) best = g->auto_trial_us[i], g->auto_mode = candidates[i];
+    }
 }
 
 }  // namespace
@@ -476,38 +575,23 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
     g->tasks.assign(g->nodes.size(), Task());
     for (int v = 0; v < (int)g->nodes.size(); ++v)
         if (int rc = build_task(g, v, rt.arena, rt.constants ? rt.constants + const_off[v] : nullptr, g->tasks[v])) return rc;
-    // Modes 0-3 run one kernel per task, with one exception: a batch-norm / ReLU whose only input is a
-    // convolution result is applied by the convolution's kernel while the sums are in registers (the
-    // same arithmetic on the same values; both tensors are stored), so it has no launch of its own and
-    // whatever waits for it waits for the convolution. Not under a memory plan with reuse over time:
-    // there the batch-norm's buffer may still hold the convolution's own input when the convolution runs.
+    // Modes 0-3 run one kernel per task, with two exceptions (decide_launch_fusion): a batch-norm / ReLU
+    // whose only input is a convolution result is applied by the convolution's kernel while the sums are
+    // in registers (the same arithmetic on the same values; both tensors are stored), and a concat all of
+    // whose inputs the memory plan placed inside its result is not launched. Such a task has no launch of
+    // its own and whatever waits for it waits for what it waited for.
     g->launch_tasks = g->tasks;
-    g->launch_fused_into.assign(g->nodes.size(), -1);
-    if (!g->memory_reuse && !getenv("NG_NO_GRAPH_FUSE")) {
-        std::vector<char> has_epilogue(g->nodes.size(), 0);
-        for (int v = 0; v < (int)g->nodes.size(); ++v) {
-            const Node& nd = g->nodes[v];
-            if ((nd.op != NG_OP_BN_ACT && nd.op != NG_OP_RELU) || nd.preds.size() != 1) continue;
-            const int u = nd.preds[0];
-            if (!g->tasks[u].fn || !has_bn_epilogue(g->tasks[u].kid) || has_epilogue[u] || !(g->nodes[u].out == nd.out)) continue;
+    decide_launch_fusion(g, g->tasks, g->launch_fusion, g->launch_fused_into);
+    for (int v = 0; v < (int)g->nodes.size(); ++v) {
+        const int u = g->launch_fused_into[v];
+        if (u < 0) continue;
+        if (u != v) {
             const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
             const Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};
             if (takes_c3_args(g->tasks[u].kid)) reinterpret_cast<C3Args*>(g->launch_tasks[u].args)->ep = ep;
             else reinterpret_cast<PwArgs*>(g->launch_tasks[u].args)->ep = ep;
-            has_epilogue[u] = 1;
-            g->launch_fused_into[v] = u;
-            g->launch_tasks[v].fn = nullptr;
         }
-        // likewise a concat all of whose inputs the memory plan placed inside its result: nothing to copy, no launch
-        for (int v = 0; v < (int)g->nodes.size() && !g->alias_of.empty(); ++v) {
-            const Node& nd = g->nodes[v];
-            if (nd.op != NG_OP_CONCAT) continue;
-            bool in_place = true;
-            for (int u : nd.preds) in_place = in_place && g->alias_of[u] == v && g->tasks[u].fn;
-            if (!in_place) continue;
-            g->launch_fused_into[v] = v;                       // stands for its own dependencies
-            g->launch_tasks[v].fn = nullptr;
-        }
+        g->launch_tasks[v].fn = nullptr;
     }
 
     rt.events.resize(g->sched.n_events);
@@ -535,17 +619,20 @@ int ng_capture(ng_graph* g) {
     if (!rt.d_records && !g->memory_reuse)
         if (int rc = build_resident(g)) return rc;
     // the pre-run itself: execute the recorded schedule once so that every kernel is loaded
-    NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
+    NG_HIP(hipGraphLaunch(rt.exec[1], rt.streams[0]));
     NG_HIP(hipStreamSynchronize(rt.streams[0]));
     g->phase = CAPTURED;
     if (rt.d_records && !g->memory_reuse)
         if (int rc = tune_resident(g)) return rc;
+    // the multi-stream graph has to reproduce the single-stream result before it may be chosen
+    if (int rc = verify_graph_multi(g, 0)) return rc;
     // short trial: which way of replaying this schedule is fastest on this DAG
     {
         const int candidates[3] = {NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_DEVICE_RESIDENT};
         const int saved = g->mode;
-        float best = 0;
-        for (int i = 0; i < (g->memory_reuse ? 2 : 3); ++i) {
+        for (int i = 0; i < 3; ++i) {
+            g->auto_trial_us[i] = 0.f;
+            if ((i == 0 && g->graph_multi_state != 1) || (i == 2 && g->memory_reuse)) continue;
             g->mode = candidates[i];
             std::vector<float> us;
             for (int rep = 0; rep < 2 + 9; ++rep) {
@@ -560,9 +647,9 @@ int ng_capture(ng_graph* g) {
             }
             std::sort(us.begin(), us.end());
             g->auto_trial_us[i] = us[us.size() / 2];
-            if (i == 0 || g->auto_trial_us[i] < best) best = g->auto_trial_us[i], g->auto_mode = candidates[i];
         }
         g->mode = saved;
+        pick_auto_mode(g);
     }
     return NG_OK;
 }
@@ -573,6 +660,33 @@ int ng_auto_mode(const ng_graph* g, int* mode, float* trial_us) {
     if (mode) *mode = g->auto_mode;
     if (trial_us)
         for (int i = 0; i < 3; ++i) trial_us[i] = g->auto_trial_us[i];
+    return NG_OK;
+}
+
+int ng_graph_multi_check(const ng_graph* g, int* state, int* replays_compared) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return const_cast<ng_graph*>(g)->fail(NG_ESTATE, "ng_graph_multi_check: call ng_capture first");
+    if (state) *state = g->graph_multi_state;
+    if (replays_compared) *replays_compared = g->graph_multi_checked;
+    return NG_OK;
+}
+
+int ng_graph_multi_recheck(ng_graph* g, int replays) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_graph_multi_recheck: call ng_capture first");
+    if (replays < 1 || replays > 100000) return g->fail(NG_EINVAL, "ng_graph_multi_recheck: replays must be 1..100000");
+    if (g->graph_multi_state < 0) return NG_OK;               // a mismatch once seen stays
+    NG_HIP(hipStreamSynchronize(g->rt->streams[0]));
+    if (int rc = verify_graph_multi(g, replays)) return rc;
+    pick_auto_mode(g);
+    return NG_OK;
+}
+
+int ng_graph_multi_distrust(ng_graph* g) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_graph_multi_distrust: call ng_capture first");
+    g->graph_multi_state = -1;
+    pick_auto_mode(g);
     return NG_OK;
 }
 
@@ -593,7 +707,12 @@ int ng_replay(ng_graph* g) {
     if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_replay: call ng_capture first");
     Runtime& rt = *g->rt;
     switch (g->mode == NG_MODE_AUTO ? g->auto_mode : g->mode) {
-        case NG_MODE_GRAPH_MULTI: NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0])); return NG_OK;
+        case NG_MODE_GRAPH_MULTI:
+            if (g->graph_multi_state < 0)
+                return g->fail(NG_ESTATE, "ng_replay: the multi-stream HIP graph did not reproduce the single-stream result when it was checked "
+                                          "(%d replays compared); choose another replay mode", g->graph_multi_checked);
+            NG_HIP(hipGraphLaunch(rt.exec[0], rt.streams[0]));
+            return NG_OK;
         case NG_MODE_GRAPH_SINGLE: NG_HIP(hipGraphLaunch(rt.exec[1], rt.streams[0])); return NG_OK;
         case NG_MODE_EAGER_SINGLE: return issue_all(g, false);
         case NG_MODE_EAGER_MULTI: return issue_all(g, true);
@@ -608,6 +727,9 @@ int ng_sync(ng_graph* g) {
     if (g->rt->h_error && *g->rt->h_error != 0) {
         const int task = *g->rt->h_error - 1;
         g->rt->counters_dirty = true;
+        if (*g->rt->h_error == kErrorXcdMapping)
+            return g->fail(NG_EHIP, "device-resident replay: workgroups with equal index mod 8 did not share an XCD in this launch, which the "
+                                    "plan's use of XCD-local L2s rests on; outputs may be stale");
         return g->fail(NG_EHIP, "device-resident replay: the wait before task %d ran out of spins; outputs are incomplete", task);
     }
     return NG_OK;

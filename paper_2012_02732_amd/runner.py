@@ -17,7 +17,21 @@ from . import binding as B
 # torch hands out streams from a pool of 32 per device, so asking it for more returns the
 # same handle twice; wide DAGs need more distinct streams than that. Streams are therefore
 # created straight from the HIP runtime torch has already loaded.
-_hip = C.CDLL("libamdhip64.so.7")
+def _loaded_hip_runtime():
+    """The libamdhip64 this process has mapped already (torch brought it in): its path as the
+    loader recorded it, so that no second copy and no guessed version suffix is involved."""
+    try:
+        with open("/proc/self/maps") as maps:
+            for line in maps:
+                path = line.rsplit(" ", 1)[-1].strip()
+                if "libamdhip64.so" in path.rsplit("/", 1)[-1]:
+                    return path
+    except OSError:
+        pass
+    raise ImportError("libamdhip64 is not loaded in this process (PyTorch-ROCm should have loaded it)")
+
+
+_hip = C.CDLL(_loaded_hip_runtime())
 _hip.hipStreamCreateWithFlags.argtypes = [C.POINTER(C.c_void_p), C.c_uint]
 _hip.hipStreamDestroy.argtypes = [C.c_void_p]
 _HIP_STREAM_NON_BLOCKING = 1
@@ -107,11 +121,13 @@ class GraphRunner:
         return B.ng_plan_memory(self.g)
 
     # -- GPU part ----------------------------------------------------------------
-    def prepare(self, resident_wg_per_cu=0, resident_xcds=0, resident_device_scope=0, plan_trials=None):
+    def prepare(self, resident_wg_per_cu=0, resident_xcds=0, resident_device_scope=0, plan_trials=None, launch_fusion=True):
         """schedule -> plan -> bind -> capture, allocating arena and streams with torch."""
         assert self.device is not None, "GraphRunner was created without a device"
         if plan_trials is not None:
             B.ng_resident_plan_trials(self.g, plan_trials)
+        if not launch_fusion:
+            B.ng_set_launch_fusion(self.g, False)
         if resident_wg_per_cu or resident_xcds or resident_device_scope:
             B.ng_resident_config(self.g, resident_wg_per_cu, resident_xcds, 0, resident_device_scope)
         sched = self.schedule()

@@ -540,18 +540,20 @@ def test_concat_inputs_produced_in_place(shape):
 _ALL_MULTI = (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_EAGER_MULTI, B.NG_MODE_DEVICE_RESIDENT)
 
 
-@pytest.mark.parametrize("seed,modes", [(11, _ALL_MULTI), (13, _ALL_MULTI),
-                                        (12, (B.NG_MODE_EAGER_MULTI, B.NG_MODE_DEVICE_RESIDENT))])
-def test_replay_under_the_exact_stream_assignment(seed, modes):
+_SEED12_REASON = ("multi-stream HIP graph of the seed-12 DAG: in 4-16 % of hipGraphLaunches the runtime started the kernel node of "
+                  "task 44 before the node of task 2, its only dependency, had finished, although that edge is in the graph the "
+                  "library builds (tests/test_library_host.py pins the edge list on the CPU). Cause inside the HIP runtime, not "
+                  "established; the case stays off the GPU in this mode. ng_capture's own check of the multi-stream graph is what "
+                  "keeps such a graph from being replayed (test_multi_stream_graph_check_*).")
+
+
+@pytest.mark.parametrize("seed,mode", [(s, m) for s in (11, 13) for m in _ALL_MULTI] +
+                         [pytest.param(12, B.NG_MODE_GRAPH_MULTI, marks=pytest.mark.skip(reason=_SEED12_REASON)),
+                          (12, B.NG_MODE_EAGER_MULTI), (12, B.NG_MODE_DEVICE_RESIDENT)])
+def test_replay_under_the_exact_stream_assignment(seed, mode):
     """The jointly optimal assignment (NG_ASSIGN_EXACT) is just another schedule of the same DAG:
     same stream and synchronisation counts as the oracle's, every tensor right in the multi-stream
-    graph, the plain multi-stream launches and the device-resident replay.
-
-    The DAG of seed 12 leaves the multi-stream HIP graph out: in about 1 of 25 launches of that graph
-    (under either assignment) the runtime starts the kernel node of task 44 before the node of task 2
-    has finished, although the edge between them is in the graph (hipGraphDebugDotPrint shows it;
-    the library adds exactly the edges of this schedule, which the host tests prove sufficient). The
-    same schedule issued with events on streams, and the device-resident replay, never showed it."""
+    graph, the plain multi-stream launches and the device-resident replay."""
     w = workloads.make("random200", seed=seed, n_nodes=80, n_layers=12, max_width=10, shape=(1, 16, 14, 14))
     ref = forward(w, keep=range(len(w.nodes)))
     from oracle.schedule import schedule_exact
@@ -561,16 +563,75 @@ def test_replay_under_the_exact_stream_assignment(seed, modes):
     sched = r.prepare()
     try:
         assert sched["n_streams"] == o.n_streams and len(sched["sync"]) == len(o.sync)
-        for mode in modes:
-            r.arena.zero_()
-            r.set_input(w.input)
-            torch.cuda.synchronize()
-            r.replay(mode)
-            r.sync()
-            for v in range(1, len(w.nodes)):
-                assert rel_err(r.output(v), ref[v]) <= TOL, (mode, v, w.nodes[v].op)
+        state, compared = B.ng_graph_multi_check(r.g)
+        print(f"seed {seed}: multi-stream graph check state {state} after {compared} replays", flush=True)
+        if mode == B.NG_MODE_GRAPH_MULTI and state != 1:
+            pytest.skip("the capture-time check refused the multi-stream graph of this DAG")
+        r.arena.zero_()
+        r.set_input(w.input)
+        torch.cuda.synchronize()
+        r.replay(mode)
+        r.sync()
+        for v in range(1, len(w.nodes)):
+            assert rel_err(r.output(v), ref[v]) <= TOL, (mode, v, w.nodes[v].op)
     finally:
         r.close()
+
+
+@pytest.mark.parametrize("name", ["tiny_cell", "chain50", "random200", "nasnet_style", "inception_style"])
+def test_multi_stream_graph_check_passes_on_the_configs(name):
+    """ng_capture replays the multi-stream graph 8-64 times on a poisoned arena and compares every
+    byte with the single-stream graph's result; on the five configurations it must come out clean,
+    the inputs must have survived the poisoning, and a longer re-check must agree."""
+    w = workloads.make(name)
+    r = GraphRunner(w, DEV)
+    r.prepare(plan_trials=1)
+    try:
+        state, compared = B.ng_graph_multi_check(r.g)
+        assert state == 1 and 8 <= compared <= 64, (state, compared)
+        assert np.array_equal(r.output(0), w.input)
+        B.ng_graph_multi_recheck(r.g, 20)
+        assert B.ng_graph_multi_check(r.g) == (1, 20)
+        ref = forward(w)
+        got = r.run(mode=B.NG_MODE_GRAPH_MULTI)
+        for v in w.outputs:
+            assert rel_err(got[v], ref[v]) <= TOL
+    finally:
+        r.close()
+
+
+def test_multi_stream_graph_distrusted_is_refused_and_auto_avoids_it():
+    """The failure path of that check, forced from the host: once the graph is marked as failed,
+    NG_MODE_AUTO picks among the other candidates and an explicit replay in that mode is refused."""
+    w = workloads.make("inception_style")
+    r = GraphRunner(w, DEV)
+    r.prepare(plan_trials=1)
+    try:
+        B.ng_graph_multi_distrust(r.g)
+        assert B.ng_graph_multi_check(r.g)[0] == -1
+        mode, trial = B.ng_auto_mode(r.g)
+        assert mode in (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT)
+        B.ng_replay_mode(r.g, B.NG_MODE_GRAPH_MULTI)
+        with pytest.raises(B.NgError) as ei:
+            B.ng_replay(r.g)
+        assert ei.value.code == B.NG_ESTATE and "multi-stream" in str(ei.value)
+        B.ng_graph_multi_recheck(r.g, 8)                      # a mismatch once recorded stays
+        assert B.ng_graph_multi_check(r.g)[0] == -1
+        ref = forward(w)
+        got = r.run(mode=B.NG_MODE_AUTO)
+        for v in w.outputs:
+            assert rel_err(got[v], ref[v]) <= TOL
+    finally:
+        r.close()
+
+
+@pytest.mark.skip(reason="switched-off path: recording the multi-stream schedule by hipStreamBeginCapture on the assigned streams ended in a "
+                         "host segmentation fault inside the HIP runtime (hipStreamEndCapture / graph construction) for every schedule in which "
+                         "two side streams wait for each other's events (nasnet_style, random200); fork-only schedules captured fine. The cause "
+                         "is not established, so the library writes that graph node by node instead (ng_capture) and nothing in it calls "
+                         "stream capture on more than one stream. Kept as a marker of the removed path; there is nothing to run.")
+def test_multi_stream_schedule_recorded_by_stream_capture():
+    raise AssertionError("not reachable: the capture path no longer exists in the library")
 
 
 @pytest.mark.parametrize("name", ["chain50", "random200", "nasnet_style", "inception_style"])
@@ -659,7 +720,7 @@ def test_plan_trials_at_capture_keep_a_correct_plan(name):
 
 
 @pytest.mark.parametrize("name", ["chain50", "inception_style", "nasnet_style"])
-def test_launch_modes_with_and_without_epilogues_agree_bit_for_bit(name, monkeypatch):
+def test_launch_modes_with_and_without_epilogues_agree_bit_for_bit(name):
     """Modes 0-3 apply a batch-norm / ReLU directly behind a convolution in the convolution's kernel and
     do not launch a concat whose inputs are already in place. With that switched off (one kernel per
     task) every tensor of every node must come out the same, bit for bit, in each of the four modes -
@@ -667,9 +728,9 @@ def test_launch_modes_with_and_without_epilogues_agree_bit_for_bit(name, monkeyp
     w = workloads.make(name)
     modes = (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_EAGER_SINGLE, B.NG_MODE_EAGER_MULTI)
 
-    def run_all():
+    def run_all(launch_fusion):
         r = GraphRunner(w, DEV)
-        r.prepare(plan_trials=1)
+        r.prepare(plan_trials=1, launch_fusion=launch_fusion)
         try:
             got = {}
             for mode in modes:
@@ -683,9 +744,8 @@ def test_launch_modes_with_and_without_epilogues_agree_bit_for_bit(name, monkeyp
         finally:
             r.close()
 
-    fused = run_all()
-    monkeypatch.setenv("NG_NO_GRAPH_FUSE", "1")         # read by ng_bind
-    plain = run_all()
+    fused = run_all(True)
+    plain = run_all(False)                              # ng_set_launch_fusion(g, 0): one kernel per task
     for mode in modes:
         for v in range(1, len(w.nodes)):
             assert np.array_equal(fused[mode][v], plain[mode][v]), (mode, v, w.nodes[v].op)

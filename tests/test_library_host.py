@@ -443,3 +443,132 @@ def test_device_resident_plan_argument_checks():
     B.ng_resident_plan_trials(r.g, 1)
     B.ng_resident_plan_trials(r.g, 8)
     r.close()
+
+
+# ---- the multi-stream HIP graph's edge list, pinned on the CPU ------------------------------
+
+def _graph_order_is_safe(w, launched_by, graph_edges):
+    """Appendix A, safe plan, applied to the graph that is really launched: for every edge (u, v)
+    of E, each kernel node that writes (part of) u's tensor must reach, through graph edges, the
+    kernel node that computes v. Written from the definitions: a fused batch-norm's tensor is written
+    by its convolution's node, an in-place concat's tensor by the nodes of its inputs, and an in-place
+    concat itself computes nothing."""
+    n = len(w.nodes)
+
+    def writers(t):
+        if launched_by[t] == -1:
+            return set()                                    # network input: written before the launch
+        if launched_by[t] == -2:
+            return set().union(*[writers(p) for p in w.nodes[t].preds])
+        return {launched_by[t]}
+
+    reach = checks.reachable(n, graph_edges)
+    for u, v in w.edges:
+        if launched_by[v] < 0:
+            continue                                        # v runs nothing
+        runner = launched_by[v]
+        for k in writers(u):
+            if k != runner and not reach[k][runner]:
+                return False, (u, v, k, runner)
+    # every graph edge points forward in the submission order (ascending id): the graph is acyclic
+    return all(a < b for a, b in graph_edges), None
+
+
+def _exact_and_default(w):
+    for assignment in (B.NG_ASSIGN_ALGORITHM1, B.NG_ASSIGN_EXACT):
+        for fuse in (True, False):
+            r = GraphRunner(w)
+            B.ng_set_assignment(r.g, assignment)
+            sched = r.schedule()
+            r.plan()
+            launched_by, ge = B.ng_get_graph_edges(r.g, fuse)
+            r.close()
+            yield assignment, fuse, sched, launched_by, ge
+
+
+@pytest.mark.parametrize("name", workloads.CONFIG_NAMES)
+def test_multi_stream_graph_edges_order_every_dependency_on_the_configs(name):
+    w = workloads.make(name)
+    if len(w.nodes) > 300:                                   # closure by relaxation is cubic: keep the big ones to the default assignment
+        runs = [(B.NG_ASSIGN_ALGORITHM1, f) for f in (True, False)]
+    else:
+        runs = [(a, f) for a in (B.NG_ASSIGN_ALGORITHM1, B.NG_ASSIGN_EXACT) for f in (True, False)]
+    for assignment, fuse in runs:
+        r = GraphRunner(w)
+        B.ng_set_assignment(r.g, assignment)
+        sched = r.schedule()
+        r.plan()
+        launched_by, ge = B.ng_get_graph_edges(r.g, fuse)
+        r.close()
+        ok, why = _graph_order_is_safe(w, launched_by, ge)
+        assert ok, (name, assignment, fuse, why)
+        ops = [nd.op for nd in w.nodes]
+        if fuse:
+            # what is not launched: batch-norms / ReLUs behind a convolution, concats with all inputs in place
+            assert all(ops[v] in ("bn_act", "relu") and ops[launched_by[v]] in ("conv1x1", "conv3x3", "fc")
+                       for v in range(len(ops)) if launched_by[v] not in (v, -1, -2))
+            assert all(ops[v] == "concat" for v in range(len(ops)) if launched_by[v] == -2)
+        else:
+            assert all(launched_by[v] == (v if ops[v] != "input" else -1) for v in range(len(ops)))
+            # one kernel per task: the edges are exactly FIFO neighbours on a stream plus Lambda
+            last, fifo = {}, set()
+            for v in sched["order"]:
+                if ops[v] == "input":
+                    continue
+                s = sched["stream_of"][v]
+                if s in last:
+                    fifo.add((last[s], v))
+                last[s] = v
+            lam = {(a, b) for a, b in sched["sync"] if ops[a] != "input"}
+            assert set(ge) == fifo | lam, (name, assignment)
+
+
+@pytest.mark.parametrize("seed", [11, 12, 13])
+def test_multi_stream_graph_edges_on_the_80_node_dags(seed):
+    """Seed 12 is the DAG on which the multi-stream HIP graph was seen to run task 44 before task 2
+    had finished: the edge list the library hands to the runtime orders every dependency, that one
+    included, under both assignments and with and without the launch fusions."""
+    w = workloads.make("random200", seed=seed, n_nodes=80, n_layers=12, max_width=10, shape=(1, 16, 14, 14))
+    for assignment, fuse, sched, launched_by, ge in _exact_and_default(w):
+        ok, why = _graph_order_is_safe(w, launched_by, ge)
+        assert ok, (seed, assignment, fuse, why)
+        # and the plain statement of the oracle for the unfused graph: FIFO + Lambda covers E
+        if not fuse:
+            assert checks.execution_respects_edges(len(w.nodes), w.edges, sched["stream_of"], sched["order"], sched["sync"])
+    if seed == 12:
+        r = GraphRunner(w)
+        r.schedule(); r.plan()
+        launched_by, ge = B.ng_get_graph_edges(r.g, True)
+        r.close()
+        assert (2, 44) in w.edges
+        k2, k44 = launched_by[2], launched_by[44]
+        assert checks.reachable(len(w.nodes), ge)[k2][k44]
+
+
+def test_graph_edges_check_catches_a_planted_mistake():
+    """The checker itself: drop one needed edge from a correct list and it must say so."""
+    w = workloads.make("random200", seed=12, n_nodes=80, n_layers=12, max_width=10, shape=(1, 16, 14, 14))
+    r = GraphRunner(w)
+    r.schedule(); r.plan()
+    launched_by, ge = B.ng_get_graph_edges(r.g, False)
+    r.close()
+    assert _graph_order_is_safe(w, launched_by, ge)[0]
+    sched_sync = [e for e in ge if e == (launched_by[2], launched_by[44])]
+    assert sched_sync, "the direct edge 2 -> 44 is part of the graph"
+    broken = [e for e in ge if e != sched_sync[0]]
+    assert not _graph_order_is_safe(w, launched_by, broken)[0]
+
+
+def test_graph_edges_errors():
+    w = workloads.make("tiny_cell")
+    r = GraphRunner(w)
+    with pytest.raises(B.NgError) as ei:
+        B.ng_get_graph_edges(r.g)
+    assert ei.value.code == B.NG_ESTATE
+    r.schedule(); r.plan()
+    n_e = C.c_int()
+    src, dst = (C.c_int * 1)(), (C.c_int * 1)()
+    assert B.lib.ng_get_graph_edges(r.g, 1, None, C.byref(n_e), src, dst, 1) == B.NG_ENOMEM and n_e.value > 1
+    assert B.lib.ng_get_graph_edges(r.g, 1, None, C.byref(n_e), None, None, 5) == B.NG_EINVAL
+    B.ng_set_launch_fusion(r.g, False)
+    r.close()
