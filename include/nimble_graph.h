@@ -334,12 +334,35 @@ int ng_time_replay(ng_graph* g, int reps, float* avg_us);
  * an empty kernel) is launched on the origin stream and timed with events; *us_per_node
  * receives elapsed / reps (best of three launches). Includes the dependent-dispatch gap. */
 int ng_time_chain(ng_graph* g, int id, int reps, float* us_per_node);
-/* Isolated duration of one task in microseconds, the weight used for the critical path
- * (Section 3: "GPU active time" of an operator): chain time of the task's kernel minus the
- * chain time of an empty kernel (that removes the dispatch gap) plus the duration of an
- * empty kernel as the device's dispatch timestamps report it on this GPU (1.0 us).
- * 0 for input nodes. */
+/* Cross-check of ng_time_task_device that needs no timestamps: chain time of the task's kernel minus
+ * the chain time of an empty kernel (that removes the dispatch gap); a lower estimate of the kernel's
+ * duration, since whatever an empty kernel itself takes is subtracted too. 0 for input nodes. */
 int ng_time_task(ng_graph* g, int id, int reps, float* isolated_us);
+/* Time the GPU is busy with one task's kernel when it runs alone (Section 3: the "GPU active
+ * time" of an operator, which the critical-path time sums along the longest path), by the device's
+ * own clock: a copy of the kernel that reads the 100 MHz clock at the first instruction of every
+ * workgroup and again once the workgroup's stores are acknowledged is launched `reps` times by
+ * itself; one launch's time = latest end - earliest start over its workgroups. *median_us and
+ * *min_us (may be NULL) receive median and minimum. What the command processor spends around a
+ * dispatch is not part of it (a kernel trace's begin-to-end time of the same kernel is 1-2 us longer).
+ * as_executed = 0: the task's stand-alone kernel, one kernel per task whatever the replay mode does.
+ * as_executed != 0 (needs ng_capture): the kernel the current replay mode really runs for the task -
+ * in modes 0-3 a convolution together with the batch-norm / ReLU fused into its kernel, in the
+ * device-resident mode the plan's kernel variant with its fused batch-norm and add_n - and 0 for a
+ * task that has no kernel of its own in that mode (it runs inside another task's kernel or has
+ * nothing to do) and for inputs. */
+int ng_time_task_device(ng_graph* g, int id, int as_executed, int reps, float* median_us, float* min_us);
+/* One launch of the same kernel (as_executed as above; id = -1: an empty kernel) on the origin
+ * stream, awaited before the call returns: a solo dispatch for a kernel trace taken from outside
+ * (rocprofv3 --kernel-trace), whose begin-to-end timestamps are the other definition of an isolated
+ * kernel time. Nothing is launched for a task without a kernel of its own. */
+int ng_launch_task_solo(ng_graph* g, int id, int as_executed);
+/* Name of the kernel the current replay mode runs for the node, as timed by ng_time_task_device with
+ * as_executed != 0; "" if it has none of its own. Needs ng_capture. Valid until ng_destroy. */
+const char* ng_task_kernel_executed(const ng_graph* g, int id);
+/* Median wall time, in microseconds, of launching one empty kernel on the origin stream and waiting
+ * for it: what a replay + wait costs before any task has run. */
+int ng_time_launch_floor(ng_graph* g, int reps, float* median_us);
 /* Name of the kernel bound to a node ("" for input nodes); valid until ng_destroy. */
 const char* ng_task_kernel(const ng_graph* g, int id);
 /* Algorithmic work of a node, from its shapes: bytes moved and flops (host doubles). */

@@ -27,6 +27,7 @@ SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_ou
            "ng_graph_multi_check", "ng_graph_multi_recheck", "ng_graph_multi_distrust", "ng_critical_path", "ng_bind", "ng_capture",
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
            "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_dry_plan_setting", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_plan_trials", "ng_resident_plan_kept", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
+           "ng_time_task_device", "ng_task_kernel_executed", "ng_time_launch_floor", "ng_launch_task_solo",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
 
 
@@ -83,6 +84,10 @@ _sig = {
     "ng_time_replay": (_I, [_P, _I, _FP]),
     "ng_time_chain": (_I, [_P, _I, _I, _FP]),
     "ng_time_task": (_I, [_P, _I, _I, _FP]),
+    "ng_time_task_device": (_I, [_P, _I, _I, _I, _FP, _FP]),
+    "ng_task_kernel_executed": (C.c_char_p, [_P, _I]),
+    "ng_launch_task_solo": (_I, [_P, _I, _I]),
+    "ng_time_launch_floor": (_I, [_P, _I, _FP]),
     "ng_task_kernel": (C.c_char_p, [_P, _I]),
     "ng_task_work": (_I, [_P, _I, _DP, _DP]),
     "ng_last_error": (C.c_char_p, [_P]),
@@ -346,6 +351,27 @@ def ng_time_chain(g, node_id, reps) -> float:
 def ng_time_task(g, node_id, reps) -> float:
     out = C.c_float()
     check(g, lib.ng_time_task(g, node_id, reps, C.byref(out)))
+    return out.value
+
+
+def ng_time_task_device(g, node_id, as_executed, reps):
+    """(median, minimum) of the kernel's begin-to-end time by device timestamps, microseconds."""
+    med, lo = C.c_float(), C.c_float()
+    check(g, lib.ng_time_task_device(g, node_id, int(bool(as_executed)), reps, C.byref(med), C.byref(lo)))
+    return med.value, lo.value
+
+
+def ng_launch_task_solo(g, node_id, as_executed=False):
+    check(g, lib.ng_launch_task_solo(g, node_id, int(bool(as_executed))))
+
+
+def ng_task_kernel_executed(g, node_id) -> str:
+    return lib.ng_task_kernel_executed(g, node_id).decode()
+
+
+def ng_time_launch_floor(g, reps) -> float:
+    out = C.c_float()
+    check(g, lib.ng_time_launch_floor(g, reps, C.byref(out)))
     return out.value
 
 

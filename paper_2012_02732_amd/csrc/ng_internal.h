@@ -168,6 +168,8 @@ size_t packed_floats(const ng_graph* g, int v);
 int pack_constants(ng_graph* g, int v, float* packed, void* stream);
 const void* resident_kernel_handle(bool full);
 const void* empty_kernel_handle();
+const void* standalone_kernel_handle(int kid, const char** name);
+const void* timed_kernel_handle(int kid);
 const void* xcd_probe_kernel_handle();
 // ng_launch_graph.cpp
 void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, std::vector<int>& fused_into);

@@ -1169,12 +1169,45 @@ NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
 NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
 #undef NG_KERNEL0
 
+// every kernel id that has a tile function
+#define NG_FOR_EACH_KID(X)                                                                                              \
+    X(KID_BN) X(KID_BN_V4) X(KID_BN_R64) X(KID_BN_R16) X(KID_ADD) X(KID_ADD_V4) X(KID_ADD_R64) X(KID_ADD_R16)           \
+    X(KID_CONCAT) X(KID_CONCAT_V4) X(KID_POOL) X(KID_POOL_P4) X(KID_DW_K3S1_P4) X(KID_DW_K3S1) X(KID_DW_K3S2)           \
+    X(KID_DW_K5S1) X(KID_DW_K5S2) X(KID_GAP) X(KID_FC_GEMV)                                                             \
+    X(KID_PW_D4) X(KID_PW_D8) X(KID_PW_D16) X(KID_PW_64) X(KID_PW_V1) X(KID_PW_V2)                                      \
+    X(KID_PW_V3) X(KID_PW_V4) X(KID_PW_S1) X(KID_PW_S2) X(KID_PW_S3) X(KID_PW_S4) X(KID_C3_T16S1)                       \
+    X(KID_C3_T16S2) X(KID_C3_T8S1) X(KID_C3_T8S2) X(KID_C3_M1) X(KID_C3_M2)                                             \
+    X(KID_C3_M3) X(KID_C3_M4)                                                                                           \
+    X(KID_PW_V1A) X(KID_PW_V2A) X(KID_PW_V3A) X(KID_PW_V4A) X(KID_PW_S1A) X(KID_PW_S2A)                                 \
+    X(KID_PW_S3A) X(KID_PW_S4A) X(KID_C3_M1A) X(KID_C3_M2A) X(KID_C3_M3A) X(KID_C3_M4A)                                 \
+    X(KID_POOL_A) X(KID_POOL_P4A) X(KID_C3_L32) X(KID_C3_L64)
+
 // Stand-alone kernel of one tile function: one workgroup per tile.
 template <int KID>
 __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KID>::Args a) {
     __shared__ float smem[kSmemFloats];
     NoWait wait;
     KernelOf<KID>::template tile<false>(a, blockIdx.x, smem, threadIdx.x, true, wait);
+}
+
+// The same, with the device's clock read around it: workgroup b leaves in stamps[2 b] the time of its
+// first instruction and in stamps[2 b + 1] the time at which all its stores were acknowledged (100 MHz
+// constant clock; plain stores, one pair per workgroup, so the readings do not disturb each other). The
+// latest end minus the earliest start is the time the GPU is busy with the task when it runs alone,
+// without what the command processor spends around a dispatch.
+template <int KID>
+__global__ __launch_bounds__(kBlock) void timed_kernel(typename KernelOf<KID>::Args a, unsigned long long* stamps) {
+    __shared__ float smem[kSmemFloats];
+    unsigned long long t0 = 0;
+    if (threadIdx.x == 0) t0 = wall_clock64();
+    NoWait wait;
+    KernelOf<KID>::template tile<false>(a, blockIdx.x, smem, threadIdx.x, true, wait);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                          // vmcnt(0): this wave's stores are acknowledged
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        stamps[2 * (size_t)blockIdx.x] = t0;
+        stamps[2 * (size_t)blockIdx.x + 1] = wall_clock64();
+    }
 }
 
 // ------------------------------------------------------------------------------------
@@ -1383,17 +1416,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, wait);                               \
         }                                                                                                                    \
         break;
-                NG_CASE(KID_BN) NG_CASE(KID_BN_V4) NG_CASE(KID_BN_R64) NG_CASE(KID_BN_R16) NG_CASE(KID_ADD) NG_CASE(KID_ADD_V4)
-                NG_CASE(KID_ADD_R64) NG_CASE(KID_ADD_R16)
-                NG_CASE(KID_CONCAT) NG_CASE(KID_CONCAT_V4) NG_CASE(KID_POOL) NG_CASE(KID_POOL_P4) NG_CASE(KID_DW_K3S1_P4) NG_CASE(KID_DW_K3S1) NG_CASE(KID_DW_K3S2)
-                NG_CASE(KID_DW_K5S1) NG_CASE(KID_DW_K5S2) NG_CASE(KID_GAP) NG_CASE(KID_FC_GEMV)
-                NG_CASE(KID_PW_D4) NG_CASE(KID_PW_D8) NG_CASE(KID_PW_D16) NG_CASE(KID_PW_64) NG_CASE(KID_PW_V1) NG_CASE(KID_PW_V2)
-                NG_CASE(KID_PW_V3) NG_CASE(KID_PW_V4) NG_CASE(KID_PW_S1) NG_CASE(KID_PW_S2) NG_CASE(KID_PW_S3) NG_CASE(KID_PW_S4) NG_CASE(KID_C3_T16S1)
-                NG_CASE(KID_C3_T16S2) NG_CASE(KID_C3_T8S1) NG_CASE(KID_C3_T8S2) NG_CASE(KID_C3_M1) NG_CASE(KID_C3_M2)
-                NG_CASE(KID_C3_M3) NG_CASE(KID_C3_M4)
-                NG_CASE(KID_PW_V1A) NG_CASE(KID_PW_V2A) NG_CASE(KID_PW_V3A) NG_CASE(KID_PW_V4A) NG_CASE(KID_PW_S1A) NG_CASE(KID_PW_S2A)
-                NG_CASE(KID_PW_S3A) NG_CASE(KID_PW_S4A) NG_CASE(KID_C3_M1A) NG_CASE(KID_C3_M2A) NG_CASE(KID_C3_M3A) NG_CASE(KID_C3_M4A)
-                NG_CASE(KID_POOL_A) NG_CASE(KID_POOL_P4A) NG_CASE(KID_C3_L32) NG_CASE(KID_C3_L64)
+                NG_FOR_EACH_KID(NG_CASE)
 #undef NG_CASE
                 default: break;
             }
@@ -1478,6 +1501,30 @@ namespace {
 __global__ void empty_kernel() {}
 }  // namespace
 const void* empty_kernel_handle() { return reinterpret_cast<const void*>(&empty_kernel); }
+
+// The stand-alone kernel of a kernel id (nullptr if the id has none) and its name: lets the runtime
+// launch a task in the variant a replay mode really executes (e.g. a convolution with its fused
+// batch-norm and add_n), by itself, for timing.
+const void* standalone_kernel_handle(int kid, const char** name) {
+    switch (kid) {
+#define NG_HANDLE(KID) \
+    case KID:          \
+        if (name) *name = KernelOf<KID>::name; \
+        return reinterpret_cast<const void*>(&standalone_kernel<KID>);
+        NG_FOR_EACH_KID(NG_HANDLE)
+#undef NG_HANDLE
+        default: return nullptr;
+    }
+}
+const void* timed_kernel_handle(int kid) {
+    switch (kid) {
+#define NG_HANDLE(KID) \
+    case KID: return reinterpret_cast<const void*>(&timed_kernel<KID>);
+        NG_FOR_EACH_KID(NG_HANDLE)
+#undef NG_HANDLE
+        default: return nullptr;
+    }
+}
 
 namespace {
 // Which conv1x1 kernel a node gets. Decided from shapes alone, so that the size of the

@@ -32,6 +32,8 @@ struct Runtime {
     hipEvent_t t_start = nullptr, t_stop = nullptr;
     float* constants = nullptr;            // library-owned: repacked weights
     float empty_chain_us = 0.f;            // per-node time of a chain of empty kernels (measured on demand)
+    unsigned long long* stamps = nullptr;  // device memory: the clock readings of a timed kernel, one pair per workgroup
+    size_t stamps_wgs = 0;
     // device-resident replay
     DevPlan plan{};
     void* d_records = nullptr;
@@ -41,6 +43,7 @@ struct Runtime {
     std::vector<int> entry_task;           // node of every list entry, in record order (for the timeline)
     std::vector<int> fused_into;           // per node: the convolution that also produces its result, or -1
     std::vector<char> elided;              // per node: a concat with nothing to copy
+    std::vector<DevTask> kept_tasks;       // per node: kernel id, tile count and argument block of the installed plan (host copy)
     bool xcd_mapping_ok = false;           // workgroups of the resident grid with equal index mod 8 share an XCD (probed)
     bool resident_full = true;             // the DAG uses kernels the lean build of the resident kernel leaves out
     unsigned epoch = 0;
@@ -49,10 +52,6 @@ struct Runtime {
     double est_us = 0;
     bool counters_dirty = false;
 };
-
-// Duration of an empty kernel by the device's own dispatch timestamps on this GPU (the
-// smallest kernels in a rocprofv3 kernel trace last 1.0 - 1.1 us).
-constexpr float kEmptyKernelUs = 1.0f;
 
 namespace {
 
@@ -360,6 +359,7 @@ int install_plan(ng_graph* g, const ResidentPlan& hp) {
     rt.entry_task.assign(entries.size(), 0);
     rt.fused_into = hp.fused_into;
     rt.elided = hp.elided;
+    rt.kept_tasks = hp.tasks;
     for (size_t e = 0; e < entries.size(); ++e) {
         rt.entry_task[e] = entries[e].task;
         const DevTask& t = tasks[entries[e].task];
@@ -528,6 +528,7 @@ void destroy_runtime(ng_graph* g) {
     if (rt->plan.error_dev) (void)hipFree(rt->plan.error_dev);
     if (rt->plan.trace) (void)hipFree(rt->plan.trace);
     if (rt->h_error) (void)hipHostFree(rt->h_error);
+    if (rt->stamps) (void)hipFree(rt->stamps);
     delete rt;
     g->rt = nullptr;
 }
@@ -923,7 +924,116 @@ int ng_time_task(ng_graph* g, int id, int reps, float* isolated_us) {
         if (int rc = ng_time_chain(g, -1, 200, &rt.empty_chain_us)) return rc;
     float c = 0.f;
     if (int rc = ng_time_chain(g, id, reps, &c)) return rc;
-    *isolated_us = std::max(c - rt.empty_chain_us, 0.f) + kEmptyKernelUs;
+    *isolated_us = std::max(c - rt.empty_chain_us, 0.f);
+    return NG_OK;
+}
+
+// The task as replay mode `mode` really runs it, as a stand-alone launch: the per-task kernel, or the
+// convolution with its fused batch-norm (modes 0-3), or the kernel variant of the device-resident plan
+// (partition, outputs per thread, fused batch-norm and add_n). false: the task has no kernel of its own
+// in that mode (it runs inside another task's kernel, or has nothing to do).
+static bool executed_task(const ng_graph* g, int id, int mode, Task& out, const char** name) {
+    if (mode == NG_MODE_AUTO) mode = g->auto_mode;
+    if (mode != NG_MODE_DEVICE_RESIDENT) {
+        out = g->launch_tasks[id];
+        if (name) *name = out.name;
+        return out.fn != nullptr;
+    }
+    const Runtime& rt = *g->rt;
+    if ((size_t)id >= rt.kept_tasks.size() || !g->tasks[id].fn || rt.fused_into[id] >= 0 || rt.elided[id]) return false;
+    const DevTask& d = rt.kept_tasks[id];
+    const char* nm = "";
+    const void* fn = standalone_kernel_handle(d.kid, &nm);
+    if (!fn || d.ntiles <= 0) return false;
+    out = Task();
+    out.fn = fn, out.name = nm, out.kid = d.kid, out.ntiles = d.ntiles;
+    out.grid[0] = (unsigned)d.ntiles, out.block[0] = kBlock;
+    static_assert(sizeof out.args == sizeof d.args, "argument blocks");
+    std::memcpy(out.args, d.args, sizeof out.args);
+    if (name) *name = nm;
+    return true;
+}
+
+int ng_time_task_device(ng_graph* g, int id, int as_executed, int reps, float* median_us, float* min_us) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < (as_executed ? CAPTURED : BOUND)) return g->fail(NG_ESTATE, "ng_time_task_device: call %s first", as_executed ? "ng_capture" : "ng_bind");
+    if (id < 0 || id >= (int)g->nodes.size() || reps <= 0 || reps > 100000 || !median_us) return g->fail(NG_EINVAL, "ng_time_task_device: bad argument");
+    *median_us = 0.f;
+    if (min_us) *min_us = 0.f;
+    Task t = g->tasks[id];
+    if (as_executed && !executed_task(g, id, g->mode, t, nullptr)) return NG_OK;
+    if (!t.fn) return NG_OK;
+    Runtime& rt = *g->rt;
+    hipStream_t s = rt.streams[0];
+    const void* fn = timed_kernel_handle(t.kid);
+    if (!fn) return g->fail(NG_EINVAL, "ng_time_task_device: kernel %d has no timed variant", t.kid);
+    const size_t wgs = (size_t)t.grid[0] * t.grid[1] * t.grid[2];
+    if (rt.stamps_wgs < wgs) {                                     // one pair of readings per workgroup
+        if (rt.stamps) (void)hipFree(rt.stamps), rt.stamps = nullptr, rt.stamps_wgs = 0;
+        NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.stamps), wgs * 2 * sizeof(unsigned long long)));
+        rt.stamps_wgs = wgs;
+    }
+    unsigned long long* stamps = rt.stamps;
+    void* args[2] = {t.args, &stamps};
+    std::vector<unsigned long long> h(2 * wgs);
+    std::vector<float> us;
+    NG_HIP(hipStreamSynchronize(s));
+    for (int rep = -2; rep < reps; ++rep) {                        // two untimed launches first
+        NG_HIP(hipLaunchKernel(fn, dim3(t.grid[0], t.grid[1], t.grid[2]), dim3(t.block[0], t.block[1], t.block[2]), args, t.lds_bytes, s));
+        NG_HIP(hipStreamSynchronize(s));                           // solo: nothing else is in flight when the next one starts
+        if (rep < 0) continue;
+        NG_HIP(hipMemcpy(h.data(), rt.stamps, h.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+        unsigned long long first = ~0ull, last = 0;
+        for (size_t b = 0; b < wgs; ++b) first = std::min(first, h[2 * b]), last = std::max(last, h[2 * b + 1]);
+        if (last >= first) us.push_back(0.01f * (float)(last - first));   // 100 MHz clock
+    }
+    if (us.empty()) return g->fail(NG_EHIP, "ng_time_task_device: the kernel left no clock readings");
+    std::sort(us.begin(), us.end());
+    *median_us = us[us.size() / 2];
+    if (min_us) *min_us = us.front();
+    return NG_OK;
+}
+
+int ng_launch_task_solo(ng_graph* g, int id, int as_executed) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < (as_executed ? CAPTURED : BOUND)) return g->fail(NG_ESTATE, "ng_launch_task_solo: call %s first", as_executed ? "ng_capture" : "ng_bind");
+    if (id < -1 || id >= (int)g->nodes.size()) return g->fail(NG_EINVAL, "ng_launch_task_solo: no node %d", id);
+    hipStream_t s = g->rt->streams[0];
+    if (id < 0) {
+        NG_HIP(hipLaunchKernel(empty_kernel_handle(), dim3(1), dim3(64), nullptr, 0, s));
+    } else {
+        Task t = g->tasks[id];
+        if (as_executed && !executed_task(g, id, g->mode, t, nullptr)) return NG_OK;
+        if (!t.fn) return NG_OK;
+        void* args[1] = {t.args};
+        NG_HIP(hipLaunchKernel(t.fn, dim3(t.grid[0], t.grid[1], t.grid[2]), dim3(t.block[0], t.block[1], t.block[2]), args, t.lds_bytes, s));
+    }
+    NG_HIP(hipStreamSynchronize(s));
+    return NG_OK;
+}
+
+const char* ng_task_kernel_executed(const ng_graph* g, int id) {
+    if (!g || g->phase < CAPTURED || id < 0 || id >= (int)g->tasks.size()) return "";
+    Task t;
+    const char* name = "";
+    return executed_task(g, id, g->mode, t, &name) ? name : "";
+}
+
+int ng_time_launch_floor(ng_graph* g, int reps, float* median_us) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < BOUND) return g->fail(NG_ESTATE, "ng_time_launch_floor: call ng_bind first");
+    if (reps <= 0 || reps > 100000 || !median_us) return g->fail(NG_EINVAL, "ng_time_launch_floor: bad argument");
+    hipStream_t s = g->rt->streams[0];
+    NG_HIP(hipStreamSynchronize(s));
+    std::vector<float> us;
+    for (int rep = -3; rep < reps; ++rep) {
+        const auto t0 = std::chrono::steady_clock::now();
+        NG_HIP(hipLaunchKernel(empty_kernel_handle(), dim3(1), dim3(64), nullptr, 0, s));
+        NG_HIP(hipStreamSynchronize(s));
+        if (rep >= 0) us.push_back(std::chrono::duration<float, std::micro>(std::chrono::steady_clock::now() - t0).count());
+    }
+    std::sort(us.begin(), us.end());
+    *median_us = us[us.size() / 2];
     return NG_OK;
 }
 

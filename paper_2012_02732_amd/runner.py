@@ -166,6 +166,12 @@ class GraphRunner:
         torch.cuda.synchronize(self.device)
         return self._view(node_id).cpu().numpy()
 
+    def output_images(self, node_id, lo, hi) -> np.ndarray:
+        """Images [lo, hi) of a node's tensor (only that slice crosses to the host)."""
+        self.sync()
+        torch.cuda.synchronize(self.device)
+        return self._view(node_id)[lo:hi].cpu().numpy()
+
     def run(self, x=None, mode=None) -> dict:
         if x is not None:
             self.set_input(x)

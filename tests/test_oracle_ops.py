@@ -183,3 +183,61 @@ def test_forward_shapes_and_finiteness(name):
     for i, nd in enumerate(w.nodes):
         assert out[i].shape == nd.shape and out[i].dtype == np.float32
         assert np.isfinite(out[i]).all()
+
+
+def test_forward_all_ten_ops_against_hand_composition_with_torch():
+    """A 17-node DAG that uses every operator kind, including the strided / padded / sliced /
+    multi-operand variants, composed a second time by hand from torch.nn.functional in fp64.
+    Pins forward.eval_node's plumbing: which weight goes where, stride and pad, pool mode,
+    concat slices in predecessor order, add_n over several operands, fc with its bias."""
+    from workloads.model import Builder
+    b = Builder("all_ops")
+    x = b.input(2, 6, 11, 9)
+    c3 = b.conv3x3(x, 8, stride=2, pad=1)           # 1  -> [2, 8, 6, 5]
+    bn = b.bn_act(c3, relu=True)                    # 2
+    c3b = b.conv3x3(x, 8, stride=2, pad=1)          # 3
+    bn2 = b.bn_act(c3b, relu=False, eps=1e-3)       # 4
+    dw = b.dwconv(bn, 5, 1)                         # 5
+    pw = b.conv1x1(dw, 8)                           # 6
+    mx = b.pool(bn2, "max", 1, 1)                   # 7
+    av = b.pool(bn2, "avg", 1, 1)                   # 8
+    s3 = b.add_n([pw, mx, av])                      # 9
+    r = b.relu(s3)                                  # 10
+    dw2 = b.dwconv(x, 3, 2)                         # 11 -> [2, 6, 6, 5]
+    cat = b.concat([r, dw2, bn2], slices=[(2, 7), (0, 6), (1, 4)])   # 12: 5 + 6 + 3 = 14 channels
+    p2 = b.pool(cat, "avg", 2, 0)                   # 13 -> [2, 14, 2, 2]
+    c3c = b.conv3x3(p2, 10, stride=1, pad=1)        # 14 -> [2, 10, 2, 2]
+    gap = b.global_avgpool(c3c)                     # 15
+    fc = b.fc(gap, 7)                               # 16
+    rng = np.random.default_rng(5)
+    b.draw_weights(rng, 0.3, "random")
+    w = b.finish(rng, outputs=[fc, cat, s3])
+    nd = w.nodes
+    assert {n.op for n in nd} == set(workloads.OPS)
+    out = forward(w, keep=range(len(nd)))
+
+    def bn_t(t, node):
+        g, be, m, v = (t64(a) for a in node.weights)
+        y = F.batch_norm(t, m, v, g, be, False, 0.0, node.params["eps"])
+        return F.relu(y) if node.params["relu"] else y
+
+    X = t64(w.input)
+    t1 = F.conv2d(X, t64(nd[1].weights[0]), stride=2, padding=1)
+    t2 = bn_t(t1, nd[2])
+    t3 = F.conv2d(X, t64(nd[3].weights[0]), stride=2, padding=1)
+    t4 = bn_t(t3, nd[4])
+    t5 = F.conv2d(t2, t64(nd[5].weights[0])[:, None], stride=1, padding=2, groups=8)
+    t6 = F.conv2d(t5, t64(nd[6].weights[0])[:, :, None, None])
+    t7 = F.max_pool2d(t4, 3, stride=1, padding=1)
+    t8 = F.avg_pool2d(t4, 3, stride=1, padding=1, count_include_pad=False)
+    t9 = t6 + t7 + t8
+    t10 = F.relu(t9)
+    t11 = F.conv2d(X, t64(nd[11].weights[0])[:, None], stride=2, padding=1, groups=6)
+    t12 = torch.cat([t10[:, 2:7], t11[:, 0:6], t4[:, 1:4]], dim=1)
+    t13 = F.avg_pool2d(t12, 3, stride=2, padding=0)
+    t14 = F.conv2d(t13, t64(nd[14].weights[0]), stride=1, padding=1)
+    t15 = t14.mean(dim=(2, 3), keepdim=True)
+    t16 = F.linear(t15[:, :, 0, 0], t64(nd[16].weights[0]), t64(nd[16].weights[1]))[:, :, None, None]
+    for v, t in {1: t1, 2: t2, 4: t4, 5: t5, 6: t6, 7: t7, 8: t8, 9: t9, 10: t10, 11: t11, 12: t12, 13: t13, 14: t14,
+                 15: t15, 16: t16}.items():
+        close(out[v], t.numpy(), 5e-6)       # fp32 storage of every intermediate tensor in the oracle
