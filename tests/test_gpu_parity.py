@@ -221,7 +221,6 @@ def test_isolated_task_times_and_critical_path():
         names = [B.ng_task_kernel_executed(r.g, v) for v in range(n)]
         for v in range(1, n):
             assert (te[v] > 0) == (host_of[v] == -1) == (names[v] != ""), (v, te[v], host_of[v], names[v])
-        assert any(nm.endswith("_add") for nm in names) or all(h == -1 for h in host_of[1:])
         B.ng_replay_mode(r.g, B.NG_MODE_GRAPH_SINGLE)      # modes 0-3: the batch-norm behind a convolution has no kernel of its own
         tg = [B.ng_time_task_device(r.g, v, True, 5)[0] for v in range(n)]
         assert tg[2] == 0.0 and tg[1] > 0 and B.ng_task_kernel_executed(r.g, 2) == ""
@@ -678,18 +677,18 @@ def test_replay_on_a_memory_plan_with_reuse(name):
     B.ng_set_memory_reuse(r.g, True)
     r.prepare()
     try:
-        # Tensors that are still whole when a replay ends: those whose bytes no later node took over. (A later
-        # node whose buffer contains the tensor is its in-place concat, or a concat around that one: no take-over.)
+        # Tensors that are still whole when a replay ends: those whose bytes no later node took over. (A concat
+        # whose buffer contains one of its own inputs produced that input in place: no take-over.)
         off, nbytes = B.ng_get_offsets(r.g)
         n = len(w.nodes)
 
+        def in_place(v, u):                  # v is produced inside concat u's buffer (directly or through a nested concat)
+            if w.nodes[u].op != "concat" or not (off[u] <= off[v] and off[v] + nbytes[v] <= off[u] + nbytes[u]):
+                return False
+            return v in w.nodes[u].preds or any(in_place(v, c) for c in w.nodes[u].preds if c > v)
+
         def taken_over(v):
-            for u in range(v + 1, n):
-                if off[u] < off[v] + nbytes[v] and off[v] < off[u] + nbytes[u]:
-                    inside = w.nodes[u].op == "concat" and off[u] <= off[v] and off[v] + nbytes[v] <= off[u] + nbytes[u]
-                    if not inside:
-                        return True
-            return False
+            return any(off[u] < off[v] + nbytes[v] and off[v] < off[u] + nbytes[u] and not in_place(v, u) for u in range(v + 1, n))
         live = [v for v in range(1, n) if not taken_over(v)]
         assert set(w.outputs) <= set(live) and len(live) < n - 1, (len(live), n)
         print(f"{name}: {len(live)} of {n - 1} tensors are still whole at the end of a replay on the reuse plan", flush=True)
