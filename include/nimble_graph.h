@@ -264,6 +264,19 @@ int ng_graph_multi_distrust(ng_graph* g);
 int ng_replay(ng_graph* g);
 /* Wait until the origin stream is idle. */
 int ng_sync(ng_graph* g);
+/* The device-resident replay (NG_MODE_DEVICE_RESIDENT, whatever mode is selected) for callers that
+ * cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc. Same kernel, same recorded plan and same results as ng_replay in that mode, but the
+ * completion counters, the per-launch XCD records and the error flag live in a file-scope device
+ * array of the library (2.5 MiB, held by every GPU the library runs on until the process ends)
+ * instead of memory from hipMalloc. The call allocates and frees nothing and records no memset: it
+ * enqueues a fill kernel that clears the part of the array it uses and then the replay kernel, both
+ * on the origin stream. Limits: graphs of at most 1024 nodes (NG_ENOMEM with the sizes otherwise);
+ * needs ng_capture and a device-resident plan (NG_ESTATE under a memory plan with reuse); the
+ * device the graph was bound on must be current (NG_EINVAL). All calls on one GPU - of this graph
+ * or of any other - share the array: calls that overlap on one GPU race; wait (ng_sync) for one
+ * before the next is enqueued. The per-task timeline (ng_resident_trace) is not recorded. */
+int ng_replay_static(ng_graph* g);
 
 /* Device-resident replay settings. workgroups_per_cu: resident workgroups per compute unit
  * (0 = automatic; only before ng_capture). xcds: number of XCDs (1..8; 0 = automatic;

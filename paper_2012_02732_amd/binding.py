@@ -25,7 +25,7 @@ SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_ou
            "ng_node_shape", "ng_schedule", "ng_set_assignment", "ng_schedule_sizes", "ng_get_schedule", "ng_get_scaffold",
            "ng_plan_memory", "ng_set_memory_reuse", "ng_set_launch_fusion", "ng_get_graph_edges", "ng_get_offsets",
            "ng_graph_multi_check", "ng_graph_multi_recheck", "ng_graph_multi_distrust", "ng_critical_path", "ng_bind", "ng_capture",
-           "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_sync", "ng_resident_config",
+           "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_replay_static", "ng_sync", "ng_resident_config",
            "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_dry_plan_setting", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_plan_trials", "ng_resident_plan_kept", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
            "ng_time_task_device", "ng_task_kernel_executed", "ng_time_launch_floor", "ng_launch_task_solo",
            "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
@@ -70,6 +70,7 @@ _sig = {
     "ng_tensor_ptr": (_P, [_P, _I]),
     "ng_replay_mode": (_I, [_P, _I]),
     "ng_replay": (_I, [_P]),
+    "ng_replay_static": (_I, [_P]),
     "ng_sync": (_I, [_P]),
     "ng_resident_config": (_I, [_P, _I, _I, C.c_uint, _I]),
     "ng_auto_mode": (_I, [_P, _IP, C.POINTER(C.c_float)]),
@@ -262,6 +263,10 @@ def ng_replay_mode(g, mode):
 
 def ng_replay(g):
     check(g, lib.ng_replay(g))
+
+
+def ng_replay_static(g):
+    check(g, lib.ng_replay_static(g))
 
 
 def ng_sync(g):

@@ -51,6 +51,7 @@ struct Runtime {
     int xcds = 0;
     double est_us = 0;
     bool counters_dirty = false;
+    int device = -1;                       // the device that was current at ng_bind
 };
 
 namespace {
@@ -562,6 +563,7 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
     Runtime& rt = *g->rt;
     rt.arena = static_cast<char*>(arena);
     rt.arena_bytes = arena_bytes;
+    NG_HIP(hipGetDevice(&rt.device));
     for (int s = 0; s < g->sched.n_streams; ++s) rt.streams.push_back(static_cast<hipStream_t>(hip_streams[s]));
 
     // constant memory: weights repacked once, ahead of time, into the order the kernels read them
@@ -719,6 +721,65 @@ int ng_replay(ng_graph* g) {
         case NG_MODE_EAGER_MULTI: return issue_all(g, true);
         default: return launch_resident(g);
     }
+}
+
+// ---- device-resident replay that allocates nothing -------------------------------------------
+// For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses that
+// forbid hipMalloc): the completion counters, the per-launch XCD records and the error flag of the
+// device-resident replay live in a file-scope device array instead of memory from hipMalloc. Each GPU
+// holds its own copy of the array (kept until the process ends); its address on a device is looked up
+// once, with that device current, and only that address - never the array's name - is used by host code.
+// Every call on a GPU shares that GPU's array, so every call first clears the part it uses (with a fill
+// kernel, not a memset node, so the call can be captured) and replays as replay number 1.
+// Calls that overlap on one GPU - from one graph or from several - race on the array.
+constexpr int kStaticMaxNodes = 1024;                                           // nodes of the largest graph this entry point takes
+constexpr size_t kStaticScratchWords = 10 * (size_t)kStaticMaxNodes * 64 + 64;  // counters at the default stride + records + flag: 2.5 MiB
+static __device__ __align__(256) unsigned scratch[kStaticScratchWords];
+constexpr int kMaxDevices = 64;
+static unsigned* scratch_on_device[kMaxDevices];                                 // nullptr: not looked up yet
+
+__global__ __launch_bounds__(256) void zero_words_kernel(unsigned* p, size_t words) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < words; i += (size_t)gridDim.x * 256) p[i] = 0u;
+}
+
+int ng_replay_static(ng_graph* g) {
+    if (!g) return NG_EINVAL;
+    if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_replay_static: call ng_capture first");
+    Runtime& rt = *g->rt;
+    if (!rt.d_records) return g->fail(NG_ESTATE, "ng_replay_static: this graph has no device-resident plan (memory plan with reuse)");
+    const size_t n = g->nodes.size();
+    const size_t done_words = n * (size_t)rt.plan.done_stride;
+    const size_t xcc_at = (10 * done_words + 1) & ~(size_t)1, error_at = xcc_at + 16, need = error_at + 2;
+    if (n > (size_t)kStaticMaxNodes || need > kStaticScratchWords)
+        return g->fail(NG_ENOMEM, "ng_replay_static: the graph has %zu nodes and needs %zu words of counters; the static scratch array "
+                                  "takes graphs of up to %d nodes (%zu words)", n, need, kStaticMaxNodes, kStaticScratchWords);
+    int dev = -1;
+    NG_HIP(hipGetDevice(&dev));
+    if (dev != rt.device || dev < 0 || dev >= kMaxDevices)
+        return g->fail(NG_EINVAL, "ng_replay_static: device %d is current, the graph was bound on device %d", dev, rt.device);
+    if (!scratch_on_device[dev]) {
+        void* p = nullptr;
+        NG_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        scratch_on_device[dev] = static_cast<unsigned*>(p);
+    }
+    unsigned* base = scratch_on_device[dev];
+    DevPlan plan = rt.plan;
+    plan.done = base;
+    plan.done_near = base + done_words;
+    plan.done_xcd = base + 2 * done_words;
+    plan.xcc_seen = rt.plan.xcc_seen ? reinterpret_cast<unsigned long long*>(base + xcc_at) : nullptr;
+    plan.error_dev = reinterpret_cast<int*>(base + error_at);
+    plan.trace = nullptr;
+    plan.spin_limit = g->resident_spin_limit;
+    hipStream_t origin = rt.streams[0];
+    if (*rt.h_error != 0) *rt.h_error = 0;                     // left by a replay that gave up (calls do not overlap, so it has ended)
+    const unsigned blocks = (unsigned)std::min<size_t>((need + 255) / 256, 1024);
+    zero_words_kernel<<<dim3(blocks), dim3(256), 0, origin>>>(base, need);
+    NG_HIP(hipGetLastError());
+    unsigned epoch = 1;
+    void* args[2] = {&plan, &epoch};
+    NG_HIP(hipLaunchKernel(resident_kernel_handle(rt.resident_full), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
+    return NG_OK;
 }
 
 int ng_sync(ng_graph* g) {
