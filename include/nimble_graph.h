@@ -59,11 +59,39 @@ enum {
     NG_OP_CONCAT = 7,         /* channel slices [slice_lo[j], slice_hi[j]) of pred j stacked along C */
     NG_OP_POOL = 8,           /* 3x3 window, pool_mode 0 = max, 1 = avg (divisor = in-bounds taps), stride {1,2}, pad {0,1} */
     NG_OP_GLOBAL_AVGPOOL = 9, /* mean over H x W -> [n][c][1][1] */
-    NG_OP_FC = 10             /* y = W x + b on [n][cin][1][1], weights {W[cout][cin], b[cout]} */
+    NG_OP_FC = 10,            /* y = W x + b on [n][cin][1][1], weights {W[cout][cin], b[cout]} */
+    /* Training (Section 5, the training results: one whole iteration - forward pass, backward pass and
+     * weight update - is recorded and replayed like an inference). The backward operators are tasks
+     * of the same DAG; "dy" is the gradient of the loss with respect to the forward operator's
+     * result, "x" the forward operator's input (listed where its values or only its shape are
+     * needed). Weight arguments are the FORWARD operator's own buffers. Batch norm keeps its
+     * statistics (mean, var) fixed. A graph with an NG_OP_SGD_UPDATE node is a graph that trains:
+     * its convolutions, fc and batch-norms read their parameters where the caller keeps them on
+     * every replay (nothing is repacked or folded at ng_bind). */
+    NG_OP_CONV1X1_DGRAD = 11, /* preds {dy}, weights {W[cout][cin]}, cout = channels of the result (the forward cin):
+                                 dx[n][ci] = sum_co W[co][ci] dy[n][co]; with h = w = 1 the fc's input gradient */
+    NG_OP_CONV1X1_WGRAD = 12, /* preds {dy, x} -> dW as [cout][cin][1][1]; with h = w = 1 the fc's */
+    NG_OP_CONV3X3_DGRAD = 13, /* preds {dy, x}, weights {W}, stride, pad of the forward conv -> dx, shape of x */
+    NG_OP_CONV3X3_WGRAD = 14, /* preds {dy, x}, stride, pad -> dW [cout][cin][3][3] */
+    NG_OP_DWCONV_DGRAD = 15,  /* preds {dy, x}, weights {W[c][k][k]}, k, stride -> dx */
+    NG_OP_DWCONV_WGRAD = 16,  /* preds {dy, x}, k, stride -> dW as [1][c][k][k] */
+    NG_OP_BN_ACT_DGRAD = 17,  /* preds {dy, x}, weights {gamma, beta, mean, var}, eps, relu -> dx */
+    NG_OP_BN_ACT_WGRAD = 18,  /* preds {dy, x}, same weights -> [2][c][1][1]: dgamma, then dbeta */
+    NG_OP_RELU_DGRAD = 19,    /* preds {dy, x} -> dy where x > 0, else 0 */
+    NG_OP_POOL_DGRAD = 20,    /* preds {dy, x}, pool_mode, stride, pad -> dx; max: to the first tap (row-major in the
+                                 window) that attains the maximum; avg: dy / in-bounds taps of the window */
+    NG_OP_GAP_DGRAD = 21,     /* preds {dy, x} -> dy[n][c] / (h w) at every pixel */
+    NG_OP_CHANNEL_SUM = 22,   /* preds {dy} -> [1][c][1][1], sum over n, h, w (the fc's bias gradient) */
+    NG_OP_SLICE_PAD = 23,     /* preds {dy}: gradient of one concat input. Result has cout channels; its channels
+                                 [slice_lo[1], slice_lo[1] + cnt) are dy's channels [slice_lo[0], slice_hi[0]),
+                                 cnt = slice_hi[0] - slice_lo[0]; every other channel is 0 */
+    NG_OP_SGD_UPDATE = 24     /* preds {grad, then any nodes that must have run first (readers of W)}, weights {W}:
+                                 W[i] -= lr * grad[slice_lo[0] + i] for i < cout, IN PLACE in the caller's buffer;
+                                 the node's own result is [1][1][1][1] */
 };
 
 typedef struct ng_op_params {
-    int32_t cout;      /* CONV1X1, CONV3X3, FC */
+    int32_t cout;      /* CONV1X1, CONV3X3, FC; CONV1X1_DGRAD, SLICE_PAD: channels of the result; SGD_UPDATE: elements of W */
     int32_t k;         /* DWCONV: 3 or 5 */
     int32_t stride;    /* DWCONV, CONV3X3, POOL: 1 or 2 */
     int32_t pad;       /* CONV3X3, POOL: 0 or 1 */
@@ -72,6 +100,7 @@ typedef struct ng_op_params {
     float eps;         /* BN_ACT */
     int32_t slice_lo[NG_MAX_PREDS]; /* CONCAT; slice_hi[j] == 0 means "all channels of pred j" */
     int32_t slice_hi[NG_MAX_PREDS];
+    float lr;          /* SGD_UPDATE */
 } ng_op_params;
 
 typedef struct ng_graph ng_graph; /* opaque */

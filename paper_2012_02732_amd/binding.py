@@ -14,7 +14,10 @@ import torch  # noqa: F401  (loads the process-wide HIP runtime before the libra
 NG_MAX_PREDS = 8
 NG_OK, NG_EINVAL, NG_ESHAPE, NG_ESTATE, NG_ENOMEM, NG_EHIP = 0, -1, -2, -3, -4, -5
 (NG_OP_INPUT, NG_OP_CONV1X1, NG_OP_DWCONV, NG_OP_CONV3X3, NG_OP_BN_ACT, NG_OP_RELU, NG_OP_ADD_N,
- NG_OP_CONCAT, NG_OP_POOL, NG_OP_GLOBAL_AVGPOOL, NG_OP_FC) = range(11)
+ NG_OP_CONCAT, NG_OP_POOL, NG_OP_GLOBAL_AVGPOOL, NG_OP_FC,
+ NG_OP_CONV1X1_DGRAD, NG_OP_CONV1X1_WGRAD, NG_OP_CONV3X3_DGRAD, NG_OP_CONV3X3_WGRAD, NG_OP_DWCONV_DGRAD, NG_OP_DWCONV_WGRAD,
+ NG_OP_BN_ACT_DGRAD, NG_OP_BN_ACT_WGRAD, NG_OP_RELU_DGRAD, NG_OP_POOL_DGRAD, NG_OP_GAP_DGRAD, NG_OP_CHANNEL_SUM,
+ NG_OP_SLICE_PAD, NG_OP_SGD_UPDATE) = range(25)
 NG_MODE_GRAPH_MULTI, NG_MODE_GRAPH_SINGLE, NG_MODE_EAGER_SINGLE, NG_MODE_EAGER_MULTI, NG_MODE_DEVICE_RESIDENT, NG_MODE_AUTO = range(6)
 NG_ASSIGN_ALGORITHM1, NG_ASSIGN_EXACT = 0, 1
 
@@ -34,7 +37,7 @@ SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_ou
 class ng_op_params(C.Structure):
     _fields_ = [("cout", C.c_int32), ("k", C.c_int32), ("stride", C.c_int32), ("pad", C.c_int32),
                 ("relu", C.c_int32), ("pool_mode", C.c_int32), ("eps", C.c_float),
-                ("slice_lo", C.c_int32 * NG_MAX_PREDS), ("slice_hi", C.c_int32 * NG_MAX_PREDS)]
+                ("slice_lo", C.c_int32 * NG_MAX_PREDS), ("slice_hi", C.c_int32 * NG_MAX_PREDS), ("lr", C.c_float)]
 
 
 if not os.path.exists(LIB_PATH):

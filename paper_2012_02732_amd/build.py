@@ -20,8 +20,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libnimble_graph.so")
-SOURCES = ["ng_graph.cpp", "ng_schedule.cpp", "ng_launch_graph.cpp", "ng_resident_plan.cpp", "ng_kernels.hip",
-           "ng_train_kernels.hip", "ng_runtime.hip", "ng_noalloc.hip"]
+SOURCES = ["ng_graph.cpp", "ng_schedule.cpp", "ng_launch_graph.cpp", "ng_resident_plan.cpp", "ng_kernels.hip", "ng_runtime.hip"]
 
 
 def hipcc() -> str:
@@ -44,8 +43,8 @@ def _flags(knobs: bool):
 
 def build(verbose: bool = True, incremental: bool = False, knobs: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    sources = [s for s in SOURCES if os.path.exists(os.path.join(CSRC, s))]
-    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    sources = list(SOURCES)
+    headers = glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(CSRC, "*.inc")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
     newest_header = max(os.path.getmtime(h) for h in headers)
     stamp = os.path.join(OBJ, "flags.txt")
     flag_text = " ".join(_flags(knobs))

@@ -24,8 +24,14 @@ enum Kid : int {
     KID_PW_V1A, KID_PW_V2A, KID_PW_V3A, KID_PW_V4A, KID_PW_S1A, KID_PW_S2A, KID_PW_S3A, KID_PW_S4A,
     KID_C3_M1A, KID_C3_M2A, KID_C3_M3A, KID_C3_M4A, KID_POOL_A, KID_POOL_P4A,
     KID_C3_L32, KID_C3_L64,          // conv3x3 as an implicit GEMM staged through LDS, 32 x 128 / 64 x 64 output tiles (many columns)
+    // graphs that train (weights change between replays, so nothing is repacked): convolutions and fc, forward and backward,
+    // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
+    KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
+    KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_GAP_DGRAD,
+    KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,
     KID_COUNT
 };
+constexpr bool is_train_kernel(int kid) { return kid >= KID_GEMM_PW_FWD && kid <= KID_SGD; }
 
 // the variant without / with a fused add_n of a kernel (ids without such a variant map to themselves / KID_NONE)
 constexpr int plain_variant(int kid) {
@@ -78,7 +84,14 @@ constexpr bool is_matrix_kernel(int kid_any) {
 // kernels of the lean build of the resident kernel: everything except the 32 x 32 and LDS-tiled
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
-    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64;
+    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_train_kernel(kid);
+}
+// Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean
+// kernels plus the training kernels: a graph that trains runs its convolutions through the GEMM kernels, never through
+// the repacked-weight kernels of the full build).
+enum { BUILD_LEAN = 0, BUILD_FULL = 1, BUILD_TRAIN = 2 };
+constexpr bool in_build(int build, int kid) {
+    return build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid));
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
@@ -213,6 +226,59 @@ struct C3AddArgs : C3Args {
     AddEpilogue ea;
 };
 static_assert(sizeof(PwAddArgs) <= 48 * 4 && sizeof(C3AddArgs) <= 48 * 4, "argument block the resident kernel prefetches");
+
+// ---- training kernels -------------------------------------------------------------------
+// C[M x N] = A[M x K] * B[K x N] where A, B and C are views of the convolution's natural tensors; which
+// view is the kernel id's business. Cin, Cout, H, W, Ho, Wo, stride, pad describe the FORWARD convolution.
+// Weight gradients have a long K (batch x pixels) and few output tiles, so K is split over `splits`
+// workgroups per tile; partial tiles go to `ws`, the workgroup that arrives last (counter `cnt`) adds them
+// up in split order - the result does not depend on the order of arrival.
+constexpr int kGemmTile = 64;        // output tile edge
+struct GemmArgs {
+    const float* a;            // forward / dgrad: the weights W; wgrad: dY
+    const float* b;            // forward: X; dgrad: dY; wgrad: X
+    float* c;                  // forward: Y; dgrad: dX; wgrad: dW
+    const float* bias;         // forward of an fc: [Cout], else nullptr
+    float* ws;                 // wgrad: partial tiles [tiles][splits][64 * 64]
+    unsigned* cnt;             // wgrad: arrivals per tile [tiles], zero between replays
+    int M, N, K;
+    int Cin, Cout, H, W, Ho, Wo, stride, pad;
+    int tiles_n;               // tiles along N
+    int splits, k_per_split;   // k_per_split a multiple of the K slice
+};
+struct BnRawArgs {             // batch-norm with its four parameter vectors as they are (they change when the graph trains)
+    const float* x;            // forward input
+    const float* dy;           // backward: upstream gradient (nullptr forward)
+    float* y;                  // forward: output; dgrad: dx; wgrad: [2][C] = dgamma, dbeta
+    const float* gamma; const float* beta; const float* mean; const float* var;
+    float eps;
+    int relu, C, HW, N, total;
+};
+struct EltGradArgs {           // relu / global-avgpool / slice-pad / channel-sum: small elementwise backward operators
+    const float* dy;
+    const float* x;            // relu: forward input
+    float* y;
+    int C, HW, N, total;       // of the output
+    int src_C, src_lo, dst_lo, cnt;   // slice-pad: dy has src_C channels; its channels [src_lo, src_lo + cnt) go to [dst_lo, dst_lo + cnt)
+    float scale;               // gap: 1 / (H W)
+};
+struct DwGradArgs {            // depthwise backward; C, H, W, Ho, Wo, K, S of the FORWARD operator
+    const float* dy; const float* x; const float* w;
+    float* y;                  // dgrad: dx [N][C][H][W]; wgrad: dW [C][K][K]
+    int N, C, H, W, Ho, Wo, K, S, total;
+};
+struct PoolGradArgs {          // pool backward; geometry of the FORWARD operator
+    const float* dy; const float* x;
+    float* y;                  // dx
+    int H, W, Ho, Wo, stride, pad, mode, total;
+};
+struct SgdArgs {
+    float* w;                  // updated in place
+    const float* g;            // gradient tensor; element i of w pairs with g[offset + i]
+    float* flag;               // the node's own (1-element) output
+    float lr;
+    int offset, total;
+};
 
 // ---- device-resident replay: the task schedule as data in device memory -------------------
 constexpr int kArgWords = 48;        // words of the argument block the resident kernel prefetches

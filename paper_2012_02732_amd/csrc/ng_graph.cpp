@@ -110,6 +110,107 @@ const char* infer_shape(const ng_graph* g, int op, ng_op_params& p, const int* p
             out = in(0);
             out.c = p.cout;
             return nullptr;
+        // ---- backward operators: in(0) = dy, in(1) = x, the forward operator's input ----
+        case NG_OP_CONV1X1_DGRAD:
+            if (!need(1, 1)) return "conv1x1_dgrad takes dy and the forward weights";
+            if (p.cout <= 0) return "conv1x1_dgrad: cout (channels of the result) must be positive";
+            out = in(0);
+            out.c = p.cout;
+            return nullptr;
+        case NG_OP_CONV1X1_WGRAD:
+            if (!need(2, 0)) return "conv1x1_wgrad takes dy and x";
+            if (in(0).n != in(1).n || in(0).h != in(1).h || in(0).w != in(1).w) {
+                code = NG_ESHAPE;
+                return "conv1x1_wgrad: dy and x differ in n, h or w";
+            }
+            out = Shape{in(0).c, in(1).c, 1, 1};
+            return nullptr;
+        case NG_OP_CONV3X3_DGRAD:
+        case NG_OP_CONV3X3_WGRAD: {
+            const bool dgrad = op == NG_OP_CONV3X3_DGRAD;
+            if (!need(2, dgrad ? 1 : 0)) return "conv3x3 backward takes dy and x (dgrad: and the forward weights)";
+            if (!in_set(p.stride, 1, 2) || !in_set(p.pad, 0, 1)) return "conv3x3 backward: stride in {1,2}, pad in {0,1}";
+            if (in(0).n != in(1).n || conv_out(in(1).h, 3, p.stride, p.pad) != in(0).h || conv_out(in(1).w, 3, p.stride, p.pad) != in(0).w) {
+                code = NG_ESHAPE;
+                return "conv3x3 backward: dy does not have the shape the forward convolution gives for x";
+            }
+            out = dgrad ? in(1) : Shape{in(0).c, in(1).c, 3, 3};
+            return nullptr;
+        }
+        case NG_OP_DWCONV_DGRAD:
+        case NG_OP_DWCONV_WGRAD: {
+            const bool dgrad = op == NG_OP_DWCONV_DGRAD;
+            if (!need(2, dgrad ? 1 : 0)) return "dwconv backward takes dy and x (dgrad: and the forward weights)";
+            if (!in_set(p.k, 3, 5) || !in_set(p.stride, 1, 2)) return "dwconv backward: k in {3,5}, stride in {1,2}";
+            if (in(0).n != in(1).n || in(0).c != in(1).c || conv_out(in(1).h, p.k, p.stride, p.k / 2) != in(0).h ||
+                conv_out(in(1).w, p.k, p.stride, p.k / 2) != in(0).w) {
+                code = NG_ESHAPE;
+                return "dwconv backward: dy does not have the shape the forward operator gives for x";
+            }
+            out = dgrad ? in(1) : Shape{1, in(1).c, p.k, p.k};
+            return nullptr;
+        }
+        case NG_OP_BN_ACT_DGRAD:
+        case NG_OP_BN_ACT_WGRAD:
+            if (!need(2, 4)) return "bn_act backward takes dy, x and the 4 forward weights";
+            if (!(p.eps >= 0.f)) return "bn_act backward: eps must be >= 0";
+            if (!(in(0) == in(1))) {
+                code = NG_ESHAPE;
+                return "bn_act backward: dy and x differ in shape";
+            }
+            out = op == NG_OP_BN_ACT_DGRAD ? in(1) : Shape{2, in(1).c, 1, 1};
+            return nullptr;
+        case NG_OP_RELU_DGRAD:
+            if (!need(2, 0)) return "relu_dgrad takes dy and x";
+            if (!(in(0) == in(1))) {
+                code = NG_ESHAPE;
+                return "relu_dgrad: dy and x differ in shape";
+            }
+            out = in(1);
+            return nullptr;
+        case NG_OP_POOL_DGRAD:
+            if (!need(2, 0)) return "pool_dgrad takes dy and x";
+            if (!in_set(p.pool_mode, 0, 1) || !in_set(p.stride, 1, 2) || !in_set(p.pad, 0, 1))
+                return "pool_dgrad: mode in {0,1}, stride in {1,2}, pad in {0,1}";
+            if (in(0).n != in(1).n || in(0).c != in(1).c || conv_out(in(1).h, 3, p.stride, p.pad) != in(0).h ||
+                conv_out(in(1).w, 3, p.stride, p.pad) != in(0).w) {
+                code = NG_ESHAPE;
+                return "pool_dgrad: dy does not have the shape the forward pool gives for x";
+            }
+            out = in(1);
+            return nullptr;
+        case NG_OP_GAP_DGRAD:
+            if (!need(2, 0)) return "global_avgpool_dgrad takes dy and x";
+            if (in(0).n != in(1).n || in(0).c != in(1).c || in(0).h != 1 || in(0).w != 1) {
+                code = NG_ESHAPE;
+                return "global_avgpool_dgrad: dy must be [n][c][1][1] for x [n][c][h][w]";
+            }
+            out = in(1);
+            return nullptr;
+        case NG_OP_CHANNEL_SUM:
+            if (!need(1, 0)) return "channel_sum takes 1 input";
+            out = Shape{1, in(0).c, 1, 1};
+            return nullptr;
+        case NG_OP_SLICE_PAD: {
+            if (!need(1, 0)) return "slice_pad takes 1 input";
+            const int cnt = p.slice_hi[0] - p.slice_lo[0];
+            if (p.cout <= 0 || p.slice_lo[0] < 0 || cnt <= 0 || p.slice_hi[0] > in(0).c || p.slice_lo[1] < 0 || p.slice_lo[1] + cnt > p.cout) {
+                code = NG_ESHAPE;
+                return "slice_pad: channel ranges out of range";
+            }
+            out = in(0);
+            out.c = p.cout;
+            return nullptr;
+        }
+        case NG_OP_SGD_UPDATE:
+            if (n_preds < 1 || n_weights != 1) return "sgd_update takes the gradient (and nodes to run after) and 1 weight buffer";
+            if (p.cout <= 0 || p.slice_lo[0] < 0 || (int64_t)p.slice_lo[0] + p.cout > in(0).elems()) {
+                code = NG_ESHAPE;
+                return "sgd_update: [offset, offset + elements) is not inside the gradient tensor";
+            }
+            if (!(p.lr == p.lr)) return "sgd_update: lr is not a number";
+            out = Shape{1, 1, 1, 1};
+            return nullptr;
         default:
             return "unknown operator kind";
     }
@@ -213,6 +314,8 @@ int ng_schedule(ng_graph* g) {
     for (int v = 0; v < (int)g->nodes.size(); ++v)
         for (int u : g->nodes[v].preds) edges.emplace_back(u, v);
     compute_schedule((int)g->nodes.size(), edges, g->sched, g->assignment == NG_ASSIGN_EXACT);
+    g->trainable = false;
+    for (const Node& nd : g->nodes) g->trainable = g->trainable || nd.op == NG_OP_SGD_UPDATE;
     g->phase = SCHEDULED;
     return NG_OK;
 }
@@ -415,6 +518,26 @@ int ng_task_work(const ng_graph* g, int id, double* bytes, double* flops) {
         case NG_OP_POOL: b = 4 * (in0 + out); f = 9 * out; break;
         case NG_OP_GLOBAL_AVGPOOL: b = 4 * (in0 + out); f = in0; break;
         case NG_OP_FC: b = 4 * (cin * nd.out.c + nd.out.c + in0 + out); f = 2 * cin * out; break;
+        // backward operators: in0 = elements of dy, in1 = elements of x
+        case NG_OP_CONV1X1_DGRAD: b = 4 * (in0 + cin * nd.out.c + out); f = 2 * cin * out; break;
+        case NG_OP_CONV3X3_DGRAD: b = 4 * (in0 + 9 * cin * nd.out.c + out); f = 18.0 * nd.out.c * in0; break;
+        case NG_OP_CONV1X1_WGRAD:
+        case NG_OP_CONV3X3_WGRAD: {
+            const double in1 = (double)g->nodes[nd.preds[1]].out.elems(), cx = (double)g->nodes[nd.preds[1]].out.c;
+            b = 4 * (in0 + in1 + out);
+            f = 2.0 * cx * in0 * (nd.op == NG_OP_CONV3X3_WGRAD ? 9 : 1);
+            break;
+        }
+        case NG_OP_DWCONV_DGRAD: b = 4 * (in0 + nd.out.c * nd.p.k * nd.p.k + out); f = 2.0 * nd.p.k * nd.p.k * in0; break;
+        case NG_OP_DWCONV_WGRAD: b = 4 * (in0 + (double)g->nodes[nd.preds[1]].out.elems() + out); f = 2.0 * nd.p.k * nd.p.k * in0; break;
+        case NG_OP_BN_ACT_DGRAD: b = 12 * out + 16.0 * nd.out.c; f = 4 * out; break;
+        case NG_OP_BN_ACT_WGRAD: b = 8 * in0 + 16.0 * cin; f = 6 * in0; break;
+        case NG_OP_RELU_DGRAD: b = 12 * out; f = out; break;
+        case NG_OP_POOL_DGRAD: b = 4 * (in0 + 2 * out); f = 9 * out; break;
+        case NG_OP_GAP_DGRAD: b = 4 * (in0 + out); f = out; break;
+        case NG_OP_CHANNEL_SUM: b = 4 * (in0 + out); f = in0; break;
+        case NG_OP_SLICE_PAD: b = 4 * (out + out); break;
+        case NG_OP_SGD_UPDATE: b = 12.0 * nd.p.cout; f = 2.0 * nd.p.cout; break;
         default: break;
     }
     if (bytes) *bytes = b;

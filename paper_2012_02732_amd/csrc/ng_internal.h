@@ -131,6 +131,7 @@ struct ng_graph {
     std::vector<int> launch_fused_into;                  // [n_nodes] that convolution (the node itself: a concat with nothing to copy), or -1
     ng::Runtime* rt = nullptr;
     int mode = NG_MODE_AUTO;
+    bool trainable = false;                              // some node updates weights: nothing derived from weight values may be kept across replays
     bool launch_fusion = true;                           // modes 0-3: batch-norm / ReLU applied by the convolution's kernel, in-place concats not launched
     int graph_multi_state = 0;                           // capture-time check of the multi-stream graph: 0 not run, 1 reproduced the single-stream result, -1 did not
     int graph_multi_checked = 0;                         // replays of it that were compared
@@ -166,7 +167,7 @@ void compute_schedule(int n, const std::vector<std::pair<int, int>>& edges, Sche
 int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t);
 size_t packed_floats(const ng_graph* g, int v);
 int pack_constants(ng_graph* g, int v, float* packed, void* stream);
-const void* resident_kernel_handle(bool full);
+const void* resident_kernel_handle(int build);
 const void* empty_kernel_handle();
 const void* standalone_kernel_handle(int kid, const char** name);
 const void* timed_kernel_handle(int kid);

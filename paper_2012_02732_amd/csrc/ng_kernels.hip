@@ -1084,6 +1084,8 @@ __device__ __forceinline__ void conv3x3_k4_tile(const typename std::conditional<
     __syncthreads();                                         // LDS is reused by the next tile
 }
 
+#include "ng_train_tiles.inc"
+
 // ------------------------------------------------------------------------------------
 // kernel table: id -> argument type, tile function, name
 // ------------------------------------------------------------------------------------
@@ -1154,6 +1156,17 @@ NG_KERNEL(KID_C3_M3A, C3AddArgs, "conv3x3_mfma_3_add", conv3x3_k4_tile < 3, true
 NG_KERNEL(KID_C3_M4A, C3AddArgs, "conv3x3_mfma_4_add", conv3x3_k4_tile < 4, true)
 NG_KERNEL(KID_C3_L32, C3Args, "conv3x3_lds_32x128", conv3x3_lds_tile < 32, 128, 16)
 NG_KERNEL(KID_C3_L64, C3Args, "conv3x3_lds_64x64", conv3x3_lds_tile < 64, 64, 32)
+NG_KERNEL(KID_GEMM_PW_FWD, GemmArgs, "gemm_conv1x1_fwd", gemm_tile < GEMM_PW_FWD)
+NG_KERNEL(KID_GEMM_PW_DGRAD, GemmArgs, "gemm_conv1x1_dgrad", gemm_tile < GEMM_PW_DGRAD)
+NG_KERNEL(KID_GEMM_PW_WGRAD, GemmArgs, "gemm_conv1x1_wgrad", gemm_tile < GEMM_PW_WGRAD)
+NG_KERNEL(KID_GEMM_C3_FWD, GemmArgs, "gemm_conv3x3_fwd", gemm_tile < GEMM_C3_FWD)
+NG_KERNEL(KID_GEMM_C3_DGRAD, GemmArgs, "gemm_conv3x3_dgrad", gemm_tile < GEMM_C3_DGRAD)
+NG_KERNEL(KID_GEMM_C3_WGRAD, GemmArgs, "gemm_conv3x3_wgrad", gemm_tile < GEMM_C3_WGRAD)
+NG_KERNEL(KID_BN_RAW, BnRawArgs, "bn_act_raw", bn_raw_tile < 0)
+NG_KERNEL(KID_BN_DGRAD, BnRawArgs, "bn_act_dgrad", bn_raw_tile < 1)
+NG_KERNEL(KID_RELU_DGRAD, EltGradArgs, "relu_dgrad", elt_grad_tile < 0)
+NG_KERNEL(KID_GAP_DGRAD, EltGradArgs, "global_avgpool_dgrad", elt_grad_tile < 1)
+NG_KERNEL(KID_SLICE_PAD, EltGradArgs, "slice_pad", elt_grad_tile < 2)
 #undef NG_KERNEL
 // kernels without further template arguments
 #define NG_KERNEL0(KID, ARGS, NAME, FN)                                                        \
@@ -1167,6 +1180,12 @@ NG_KERNEL(KID_C3_L64, C3Args, "conv3x3_lds_64x64", conv3x3_lds_tile < 64, 64, 32
     };
 NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
 NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
+NG_KERNEL0(KID_BN_WGRAD, BnRawArgs, "bn_act_wgrad", bn_wgrad_tile)
+NG_KERNEL0(KID_CHANNEL_SUM, EltGradArgs, "channel_sum", channel_sum_tile)
+NG_KERNEL0(KID_DW_DGRAD, DwGradArgs, "dwconv_dgrad", dw_dgrad_tile)
+NG_KERNEL0(KID_DW_WGRAD, DwGradArgs, "dwconv_wgrad", dw_wgrad_tile)
+NG_KERNEL0(KID_POOL_DGRAD, PoolGradArgs, "pool3x3_dgrad", pool_dgrad_tile)
+NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
 #undef NG_KERNEL0
 
 // every kernel id that has a tile function
@@ -1180,7 +1199,10 @@ NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
     X(KID_C3_M3) X(KID_C3_M4)                                                                                           \
     X(KID_PW_V1A) X(KID_PW_V2A) X(KID_PW_V3A) X(KID_PW_V4A) X(KID_PW_S1A) X(KID_PW_S2A)                                 \
     X(KID_PW_S3A) X(KID_PW_S4A) X(KID_C3_M1A) X(KID_C3_M2A) X(KID_C3_M3A) X(KID_C3_M4A)                                 \
-    X(KID_POOL_A) X(KID_POOL_P4A) X(KID_C3_L32) X(KID_C3_L64)
+    X(KID_POOL_A) X(KID_POOL_P4A) X(KID_C3_L32) X(KID_C3_L64)                                                          \
+    X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
+    X(KID_GEMM_C3_WGRAD) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
+    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD)
 
 // Stand-alone kernel of one tile function: one workgroup per tile.
 template <int KID>
@@ -1361,9 +1383,10 @@ struct CounterWait {
     }
 };
 
-// FULL = false leaves out the kernels that only large problems use (see is_lean_kernel): their
-// register needs would otherwise shape the allocation of the whole replay kernel.
-template <bool FULL>
+// BUILD selects which tile functions are compiled in (see in_build): the lean build leaves out the kernels
+// that only large problems use - their register needs would otherwise shape the allocation of the whole
+// replay kernel -, the train build has the lean kernels plus those of graphs that train.
+template <int BUILD>
 __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned epoch) {
     __shared__ float smem_all[kSubs * kSmemFloats];
     __shared__ uint4 recs[kRecordsInLds * (kRecordWords / 4)];
@@ -1411,7 +1434,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             switch (kid) {
 #define NG_CASE(KID)                                                                                                         \
     case KID:                                                                                                                \
-        if (FULL || is_lean_kernel(KID)) {                                                                                   \
+        if (in_build(BUILD, KID)) {                                                                                          \
             CounterWait<has_add_epilogue(KID)> wait{plan, rec, &s_abort, &s_late, epoch, task, np, n_late, lane, stamp, true, true, far_out}; \
             run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, wait);                               \
         }                                                                                                                    \
@@ -1493,8 +1516,10 @@ __global__ __launch_bounds__(kGroup) void xcd_probe_kernel(int* xcd_of_workgroup
 }  // namespace
 const void* xcd_probe_kernel_handle() { return reinterpret_cast<const void*>(&xcd_probe_kernel); }
 
-const void* resident_kernel_handle(bool full) {
-    return full ? reinterpret_cast<const void*>(&resident_kernel<true>) : reinterpret_cast<const void*>(&resident_kernel<false>);
+const void* resident_kernel_handle(int build) {
+    return build == BUILD_TRAIN ? reinterpret_cast<const void*>(&resident_kernel<BUILD_TRAIN>)
+                                : build == BUILD_FULL ? reinterpret_cast<const void*>(&resident_kernel<BUILD_FULL>)
+                                                      : reinterpret_cast<const void*>(&resident_kernel<BUILD_LEAN>);
 }
 
 namespace {
@@ -1602,8 +1627,36 @@ PwChoice choose_c3(const ng_graph* g, int v) {
 }  // namespace
 
 // Floats of library-owned constant memory node v needs (repacked conv1x1 weights), 0 if none.
+namespace {
+// K split of a weight-gradient GEMM: enough workgroups to occupy the GPU, splits of whole K slices
+void gemm_split(long m, long n, long k, int* splits, int* k_per_split) {
+    const long tiles = ceil_div(m, kGemmTile) * ceil_div(n, kGemmTile);
+    long want = std::max<long>(1, std::min<long>(ceil_div(768, tiles), ceil_div(k, 256)));
+    const long per = ceil_div(ceil_div(k, want), 16) * 16;
+    *k_per_split = (int)per;
+    *splits = (int)ceil_div(k, per);
+}
+// geometry of a weight-gradient node: (M, N, K) of dW[M x N] = dY[M x K] * P^T[K x N]
+bool wgrad_dims(const ng_graph* g, int v, long* m, long* n, long* k) {
+    const Node& nd = g->nodes[v];
+    if (nd.op != NG_OP_CONV1X1_WGRAD && nd.op != NG_OP_CONV3X3_WGRAD) return false;
+    const Shape& dy = g->nodes[nd.preds[0]].out;
+    const Shape& x = g->nodes[nd.preds[1]].out;
+    *m = dy.c, *n = x.c * (nd.op == NG_OP_CONV3X3_WGRAD ? 9 : 1), *k = dy.n * dy.h * dy.w;
+    return true;
+}
+}  // namespace
+
 size_t packed_floats(const ng_graph* g, int v) {
     const Node& nd = g->nodes[v];
+    long wm, wn, wk;
+    if (wgrad_dims(g, v, &wm, &wn, &wk)) {                     // split-K workspace: partial tiles, then one arrival counter per tile
+        int splits, per;
+        gemm_split(wm, wn, wk, &splits, &per);
+        const size_t tiles = (size_t)(ceil_div(wm, kGemmTile) * ceil_div(wn, kGemmTile));
+        return splits > 1 ? tiles * splits * kGemmTile * kGemmTile + ((tiles + 63) & ~(size_t)63) : 0;
+    }
+    if (g->trainable) return 0;                                // weights change between replays: nothing is folded or repacked
     if (nd.op == NG_OP_BN_ACT) return 2 * (size_t)((nd.out.c + 3) & ~3L);   // folded scale, shift
     if (nd.op == NG_OP_CONV3X3) return choose_c3(g, v).packed;
     return choose_pw(g, v).packed;
@@ -1612,6 +1665,16 @@ size_t packed_floats(const ng_graph* g, int v) {
 // Fill node v's constant memory: one pass over the weights, at bind time.
 int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
     const Node& nd = g->nodes[v];
+    long wm, wn, wk;
+    if (wgrad_dims(g, v, &wm, &wn, &wk)) {                     // the arrival counters start at zero
+        const size_t floats = packed_floats(g, v);
+        if (floats == 0) return NG_OK;
+        const size_t tiles = (size_t)(ceil_div(wm, kGemmTile) * ceil_div(wn, kGemmTile)), cnt = (tiles + 63) & ~(size_t)63;
+        const hipError_t e = hipMemsetAsync(packed + floats - cnt, 0, cnt * sizeof(float), static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return g->fail(NG_EHIP, "clearing split-K counters: %s", hipGetErrorString(e));
+        return NG_OK;
+    }
+    if (g->trainable) return NG_OK;
     if (nd.op == NG_OP_BN_ACT) {
         for (int j = 0; j < 4; ++j)
             if (!nd.weights[j]) return g->fail(NG_EINVAL, "node %d: weight %d is a null device pointer", v, j);
@@ -1664,6 +1727,16 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
 
     switch (nd.op) {
         case NG_OP_BN_ACT:
+            if (g->trainable) {                                   // gamma and beta change between replays: no folded copy
+                BnRawArgs a{};
+                a.x = buf(nd.preds[0]), a.y = buf(v);
+                a.gamma = wf(0), a.beta = wf(1), a.mean = wf(2), a.var = wf(3);
+                a.eps = nd.p.eps, a.relu = nd.p.relu != 0;
+                a.C = (int)o.c, a.HW = hw_out, a.N = (int)o.n, a.total = total;
+                set_kernel<KID_BN_RAW>(t, a, ceil_div(total, kBlock));
+                break;
+            }
+            [[fallthrough]];
         case NG_OP_RELU: {
             BnArgs a{};
             a.x = buf(nd.preds[0]);
@@ -1733,6 +1806,15 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
         case NG_OP_FC:
         case NG_OP_CONV1X1: {
             const bool fc = nd.op == NG_OP_FC;
+            if (g->trainable) {                                   // weights change between replays: read them where they are
+                GemmArgs a{};
+                a.a = wf(0), a.b = buf(nd.preds[0]), a.c = buf(v), a.bias = fc ? wf(1) : nullptr;
+                a.M = (int)o.c, a.K = (int)i0.c, a.N = (int)(o.n * hw_out);
+                a.Cin = (int)i0.c, a.Cout = (int)o.c, a.H = a.Ho = (int)o.h, a.W = a.Wo = (int)o.w, a.stride = 1;
+                a.tiles_n = (int)ceil_div(a.N, kGemmTile), a.splits = 1, a.k_per_split = a.K;
+                set_kernel<KID_GEMM_PW_FWD>(t, a, (long)a.tiles_n * ceil_div(a.M, kGemmTile));
+                break;
+            }
             const PwChoice c = choose_pw(g, v);
             if (c.kind == PwChoice::GEMV) {
                 FcArgs a{buf(nd.preds[0]), wf(0), wf(1), buf(v), (int)o.n, (int)i0.c, (int)o.c};
@@ -1781,6 +1863,16 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.x = buf(nd.preds[0]), a.w = wf(0), a.y = buf(v);
             a.Cin = (int)i0.c, a.Cout = (int)o.c, a.H = (int)i0.h, a.W = (int)i0.w, a.Ho = (int)o.h, a.Wo = (int)o.w;
             a.pad = nd.p.pad, a.stride = nd.p.stride;
+            if (g->trainable) {
+                GemmArgs ga{};
+                ga.a = wf(0), ga.b = buf(nd.preds[0]), ga.c = buf(v);
+                ga.M = (int)o.c, ga.K = (int)i0.c * 9, ga.N = (int)(o.n * o.h * o.w);
+                ga.Cin = (int)i0.c, ga.Cout = (int)o.c, ga.H = (int)i0.h, ga.W = (int)i0.w, ga.Ho = (int)o.h, ga.Wo = (int)o.w;
+                ga.stride = nd.p.stride, ga.pad = nd.p.pad;
+                ga.tiles_n = (int)ceil_div(ga.N, kGemmTile), ga.splits = 1, ga.k_per_split = ga.K;
+                set_kernel<KID_GEMM_C3_FWD>(t, ga, (long)ga.tiles_n * ceil_div(ga.M, kGemmTile));
+                break;
+            }
             const PwChoice c = choose_c3(g, v);
             if (c.kind == PwChoice::C3_LDS) {
                 if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
@@ -1817,6 +1909,107 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             } else {
                 if (nd.p.stride == 1) set_kernel<KID_C3_T16S1>(t, a, n); else set_kernel<KID_C3_T16S2>(t, a, n);
             }
+            break;
+        }
+        // ---- backward operators and the weight update (graphs that train) ----
+        case NG_OP_CONV1X1_DGRAD:
+        case NG_OP_CONV3X3_DGRAD: {
+            const bool c3 = nd.op == NG_OP_CONV3X3_DGRAD;
+            const Shape& dy = i0;                                 // [n][Cout][Ho][Wo]; the result has the shape of the forward input
+            GemmArgs a{};
+            a.a = wf(0), a.b = buf(nd.preds[0]), a.c = buf(v);
+            a.Cin = (int)o.c, a.Cout = (int)dy.c, a.H = (int)o.h, a.W = (int)o.w, a.Ho = (int)dy.h, a.Wo = (int)dy.w;
+            a.stride = c3 ? nd.p.stride : 1, a.pad = c3 ? nd.p.pad : 0;
+            a.M = a.Cin, a.K = a.Cout * (c3 ? 9 : 1), a.N = (int)(o.n * o.h * o.w);
+            a.tiles_n = (int)ceil_div(a.N, kGemmTile), a.splits = 1, a.k_per_split = a.K;
+            const long n = (long)a.tiles_n * ceil_div(a.M, kGemmTile);
+            if (c3) set_kernel<KID_GEMM_C3_DGRAD>(t, a, n); else set_kernel<KID_GEMM_PW_DGRAD>(t, a, n);
+            break;
+        }
+        case NG_OP_CONV1X1_WGRAD:
+        case NG_OP_CONV3X3_WGRAD: {
+            const bool c3 = nd.op == NG_OP_CONV3X3_WGRAD;
+            const Shape& dy = i0;
+            const Shape& x = g->nodes[nd.preds[1]].out;
+            GemmArgs a{};
+            a.a = buf(nd.preds[0]), a.b = buf(nd.preds[1]), a.c = buf(v);
+            a.Cin = (int)x.c, a.Cout = (int)dy.c, a.H = (int)x.h, a.W = (int)x.w, a.Ho = (int)dy.h, a.Wo = (int)dy.w;
+            a.stride = c3 ? nd.p.stride : 1, a.pad = c3 ? nd.p.pad : 0;
+            a.M = a.Cout, a.N = a.Cin * (c3 ? 9 : 1), a.K = (int)(dy.n * dy.h * dy.w);
+            a.tiles_n = (int)ceil_div(a.N, kGemmTile);
+            gemm_split(a.M, a.N, a.K, &a.splits, &a.k_per_split);
+            const long tiles = (long)a.tiles_n * ceil_div(a.M, kGemmTile);
+            if (a.splits > 1) {
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no workspace for the split-K partial tiles", v);
+                a.ws = packed;
+                a.cnt = reinterpret_cast<unsigned*>(packed + (size_t)tiles * a.splits * kGemmTile * kGemmTile);
+            }
+            if (c3) set_kernel<KID_GEMM_C3_WGRAD>(t, a, tiles * a.splits); else set_kernel<KID_GEMM_PW_WGRAD>(t, a, tiles * a.splits);
+            break;
+        }
+        case NG_OP_BN_ACT_DGRAD:
+        case NG_OP_BN_ACT_WGRAD: {
+            const Shape& x = g->nodes[nd.preds[1]].out;
+            BnRawArgs a{};
+            a.dy = buf(nd.preds[0]), a.x = buf(nd.preds[1]), a.y = buf(v);
+            a.gamma = wf(0), a.beta = wf(1), a.mean = wf(2), a.var = wf(3);
+            a.eps = nd.p.eps, a.relu = nd.p.relu != 0;
+            a.C = (int)x.c, a.HW = (int)(x.h * x.w), a.N = (int)x.n, a.total = (int)x.elems();
+            if (nd.op == NG_OP_BN_ACT_DGRAD) set_kernel<KID_BN_DGRAD>(t, a, ceil_div(a.total, kBlock));
+            else set_kernel<KID_BN_WGRAD>(t, a, a.C);
+            break;
+        }
+        case NG_OP_RELU_DGRAD:
+        case NG_OP_GAP_DGRAD:
+        case NG_OP_SLICE_PAD:
+        case NG_OP_CHANNEL_SUM: {
+            EltGradArgs a{};
+            a.dy = buf(nd.preds[0]), a.x = nd.preds.size() > 1 ? buf(nd.preds[1]) : nullptr, a.y = buf(v);
+            a.C = (int)o.c, a.HW = hw_out, a.N = (int)o.n, a.total = total;
+            if (nd.op == NG_OP_RELU_DGRAD) {
+                set_kernel<KID_RELU_DGRAD>(t, a, ceil_div(total, kBlock));
+            } else if (nd.op == NG_OP_GAP_DGRAD) {
+                a.scale = 1.f / (float)hw_out;
+                set_kernel<KID_GAP_DGRAD>(t, a, ceil_div(total, kBlock));
+            } else if (nd.op == NG_OP_SLICE_PAD) {
+                a.src_C = (int)i0.c, a.src_lo = nd.p.slice_lo[0], a.cnt = nd.p.slice_hi[0] - nd.p.slice_lo[0], a.dst_lo = nd.p.slice_lo[1];
+                set_kernel<KID_SLICE_PAD>(t, a, ceil_div(total, kBlock));
+            } else {                                              // sums run over the input's images and pixels
+                a.C = (int)i0.c, a.HW = (int)(i0.h * i0.w), a.N = (int)i0.n;
+                set_kernel<KID_CHANNEL_SUM>(t, a, a.C);
+            }
+            break;
+        }
+        case NG_OP_DWCONV_DGRAD:
+        case NG_OP_DWCONV_WGRAD: {
+            const Shape& dy = i0;
+            const Shape& x = g->nodes[nd.preds[1]].out;
+            DwGradArgs a{};
+            a.dy = buf(nd.preds[0]), a.x = buf(nd.preds[1]), a.y = buf(v);
+            a.N = (int)x.n, a.C = (int)x.c, a.H = (int)x.h, a.W = (int)x.w, a.Ho = (int)dy.h, a.Wo = (int)dy.w;
+            a.K = nd.p.k, a.S = nd.p.stride, a.total = (int)x.elems();
+            if (nd.op == NG_OP_DWCONV_DGRAD) {
+                a.w = wf(0);
+                set_kernel<KID_DW_DGRAD>(t, a, ceil_div(a.total, kBlock));
+            } else {
+                set_kernel<KID_DW_WGRAD>(t, a, a.C);
+            }
+            break;
+        }
+        case NG_OP_POOL_DGRAD: {
+            const Shape& dy = i0;
+            const Shape& x = g->nodes[nd.preds[1]].out;
+            PoolGradArgs a{buf(nd.preds[0]), buf(nd.preds[1]), buf(v), (int)x.h, (int)x.w, (int)dy.h, (int)dy.w,
+                           nd.p.stride, nd.p.pad, nd.p.pool_mode, (int)x.elems()};
+            set_kernel<KID_POOL_DGRAD>(t, a, ceil_div(a.total, kBlock));
+            break;
+        }
+        case NG_OP_SGD_UPDATE: {
+            SgdArgs a{};
+            a.w = const_cast<float*>(wf(0));                      // caller-owned, updated in place
+            a.g = buf(nd.preds[0]), a.flag = buf(v);
+            a.lr = nd.p.lr, a.offset = nd.p.slice_lo[0], a.total = nd.p.cout;
+            set_kernel<KID_SGD>(t, a, ceil_div(a.total, kBlock));
             break;
         }
         default:

@@ -91,6 +91,24 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
         }
         case KID_C3_L32: base = 2.0, per_tile = 0.14 * cin; break;     // 9 Cin / 4 k-steps of 4 MFMAs per wavefront, plus the slice fills
         case KID_C3_L64: base = 2.0, per_tile = 0.16 * cin; break;
+        case KID_GEMM_PW_FWD: case KID_GEMM_PW_DGRAD: case KID_GEMM_PW_WGRAD: case KID_GEMM_C3_FWD: case KID_GEMM_C3_DGRAD:
+        case KID_GEMM_C3_WGRAD: {
+            const GemmArgs* a = reinterpret_cast<const GemmArgs*>(g->tasks[v].args);
+            base = 2.0, per_tile = 0.04 * a->k_per_split;             // per K slice of 16: gathered loads, LDS fill, 16 MFMAs per wavefront
+            break;
+        }
+        case KID_BN_RAW: case KID_BN_DGRAD: case KID_RELU_DGRAD: case KID_GAP_DGRAD: case KID_SLICE_PAD: case KID_SGD: base = 1.2, per_tile = 0.15; break;
+        case KID_DW_DGRAD: case KID_POOL_DGRAD: base = 2.0, per_tile = 0.7; break;
+        case KID_BN_WGRAD: case KID_CHANNEL_SUM: {
+            const double count = (double)g->nodes[nd.preds[0]].out.elems() / std::max<double>(1.0, (double)g->nodes[nd.preds[0]].out.c);
+            base = 1.5 + 0.00002 * count * 256.0 / kBlock, per_tile = 0.00003 * count;   // one workgroup walks a whole channel
+            break;
+        }
+        case KID_DW_WGRAD: {
+            const double count = (double)g->nodes[nd.preds[0]].out.elems() / std::max<double>(1.0, (double)g->nodes[nd.preds[0]].out.c);
+            base = 2.0, per_tile = 0.0005 * count;
+            break;
+        }
         default: break;
     }
     return base + per_tile * subs;

@@ -45,13 +45,16 @@ struct Runtime {
     std::vector<char> elided;              // per node: a concat with nothing to copy
     std::vector<DevTask> kept_tasks;       // per node: kernel id, tile count and argument block of the installed plan (host copy)
     bool xcd_mapping_ok = false;           // workgroups of the resident grid with equal index mod 8 share an XCD (probed)
-    bool resident_full = true;             // the DAG uses kernels the lean build of the resident kernel leaves out
+    int resident_build = BUILD_FULL;       // which build of the resident kernel the DAG's kernels need
     unsigned epoch = 0;
     size_t done_words = 0;
     int xcds = 0;
     double est_us = 0;
     bool counters_dirty = false;
     int device = -1;                       // the device that was current at ng_bind
+    // a graph that trains: copies of the weights its update nodes write, taken when ng_capture starts
+    std::vector<std::pair<float*, size_t>> trained;   // (caller's buffer, elements)
+    float* trained_copy = nullptr;
 };
 
 namespace {
@@ -175,6 +178,41 @@ __global__ __launch_bounds__(256) void mismatch_kernel(const unsigned* a, const 
     if (mine) atomicAdd(count, mine);
 }
 
+// A replay of a graph that trains changes the caller's weights. ng_capture replays many times (pre-run,
+// trials, the check of the multi-stream graph): it keeps a copy of every weight buffer an update node
+// writes and puts the values back, so that capture leaves the weights as it found them and the check
+// compares replays that start from the same weights.
+int save_trained_weights(ng_graph* g) {
+    Runtime& rt = *g->rt;
+    rt.trained.clear();
+    if (rt.trained_copy) (void)hipFree(rt.trained_copy), rt.trained_copy = nullptr;
+    size_t total = 0;
+    for (const Node& nd : g->nodes)
+        if (nd.op == NG_OP_SGD_UPDATE) {
+            rt.trained.emplace_back(const_cast<float*>(static_cast<const float*>(nd.weights[0])), (size_t)nd.p.cout);
+            total += (size_t)nd.p.cout;
+        }
+    if (total == 0) return NG_OK;
+    NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.trained_copy), total * sizeof(float)));
+    size_t at = 0;
+    for (auto& w : rt.trained) {
+        NG_HIP(hipMemcpyAsync(rt.trained_copy + at, w.first, w.second * sizeof(float), hipMemcpyDeviceToDevice, rt.streams[0]));
+        at += w.second;
+    }
+    NG_HIP(hipStreamSynchronize(rt.streams[0]));
+    return NG_OK;
+}
+int restore_trained_weights(ng_graph* g) {
+    Runtime& rt = *g->rt;
+    if (!rt.trained_copy) return NG_OK;
+    size_t at = 0;
+    for (auto& w : rt.trained) {
+        NG_HIP(hipMemcpyAsync(w.first, rt.trained_copy + at, w.second * sizeof(float), hipMemcpyDeviceToDevice, rt.streams[0]));
+        at += w.second;
+    }
+    return NG_OK;
+}
+
 int issue_poison(ng_graph* g, hipStream_t s) {
     Runtime& rt = *g->rt;
     // everything except the network inputs (their values are the caller's)
@@ -215,21 +253,23 @@ int verify_graph_multi(ng_graph* g, int replays) {
         return e == hipSuccess;
     };
     if (hip_ok(hipMalloc(reinterpret_cast<void**>(&d_count), sizeof(unsigned)), "hipMalloc") &&
-        hip_ok(hipMemsetAsync(d_count, 0, sizeof(unsigned), s), "hipMemsetAsync") && (rc = issue_poison(g, s)) == NG_OK &&
+        hip_ok(hipMemsetAsync(d_count, 0, sizeof(unsigned), s), "hipMemsetAsync") && (rc = restore_trained_weights(g)) == NG_OK &&
+        (rc = issue_poison(g, s)) == NG_OK &&
         hip_ok(hipGraphLaunch(rt.exec[1], s), "hipGraphLaunch (single stream)") &&
         hip_ok(hipMemcpyAsync(snap, rt.arena, words * 4, hipMemcpyDeviceToDevice, s), "hipMemcpyAsync") &&
         hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) {
         if (replays <= 0) {
             // about 40 ms of replays, 8 to 64 of them
             const auto t0 = std::chrono::steady_clock::now();
-            if (hip_ok(hipGraphLaunch(rt.exec[0], s), "hipGraphLaunch") && hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) {
+            if ((rc = restore_trained_weights(g)) == NG_OK && hip_ok(hipGraphLaunch(rt.exec[0], s), "hipGraphLaunch") &&
+                hip_ok(hipStreamSynchronize(s), "hipStreamSynchronize")) {
                 const double us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
                 replays = (int)std::min(64.0, std::max(8.0, 40000.0 / std::max(us, 1.0)));
             }
         }
         const unsigned blocks = (unsigned)std::min<size_t>((words + 255) / 256, 4096);
         for (int i = 0; i < replays && rc == NG_OK; ++i) {
-            if ((rc = issue_poison(g, s)) != NG_OK) break;
+            if ((rc = issue_poison(g, s)) != NG_OK || (rc = restore_trained_weights(g)) != NG_OK) break;
             if (!hip_ok(hipGraphLaunch(rt.exec[0], s), "hipGraphLaunch")) break;
             mismatch_kernel<<<dim3(blocks), dim3(256), 0, s>>>(reinterpret_cast<const unsigned*>(rt.arena), snap, words, d_count);
             if (!hip_ok(hipGetLastError(), "compare kernel")) break;
@@ -244,6 +284,7 @@ int verify_graph_multi(ng_graph* g, int replays) {
     if (rc != NG_OK) return rc;
     g->graph_multi_state = mismatches == 0 && g->graph_multi_checked > 0 ? 1 : -1;
     // leave the arena as a normal replay leaves it
+    if (int rc2 = restore_trained_weights(g)) return rc2;
     NG_HIP(hipGraphLaunch(rt.exec[1], s));
     NG_HIP(hipStreamSynchronize(s));
     return NG_OK;
@@ -260,10 +301,15 @@ int build_resident(ng_graph* g) {
     int dev = 0, cus = 0, per_cu = 0;
     NG_HIP(hipGetDevice(&dev));
     NG_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    rt.resident_full = false;
+    rt.resident_build = BUILD_LEAN;
     for (const Task& t : g->tasks)
-        if (t.fn && !is_lean_kernel(t.kid)) rt.resident_full = true;
-    NG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel_handle(rt.resident_full), kGroup, 0));
+        if (t.fn && is_train_kernel(t.kid)) rt.resident_build = BUILD_TRAIN;
+    for (const Task& t : g->tasks)
+        if (t.fn && !is_lean_kernel(t.kid) && !is_train_kernel(t.kid)) {
+            if (rt.resident_build == BUILD_TRAIN) return g->fail(NG_EINVAL, "device-resident replay: kernel %s does not belong in a graph that trains", t.name);
+            rt.resident_build = BUILD_FULL;
+        }
+    NG_HIP(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, resident_kernel_handle(rt.resident_build), kGroup, 0));
     if (per_cu < 1 || cus < 8) return g->fail(NG_EHIP, "device-resident replay: kernel does not fit (%d per CU, %d CUs)", per_cu, cus);
     per_cu = std::min(per_cu, g->resident_wg_per_cu > 0 ? g->resident_wg_per_cu : 1);   // one per CU: two slow each other's hand-overs down
     const int n_wg = cus * per_cu / 8 * 8;
@@ -492,7 +538,7 @@ int launch_resident(ng_graph* g) {
     rt.plan.spin_limit = g->resident_spin_limit;
     unsigned epoch = ++rt.epoch;
     void* args[2] = {&rt.plan, &epoch};
-    NG_HIP(hipLaunchKernel(resident_kernel_handle(rt.resident_full), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
+    NG_HIP(hipLaunchKernel(resident_kernel_handle(rt.resident_build), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
     return NG_OK;
 }
 
@@ -530,6 +576,7 @@ void destroy_runtime(ng_graph* g) {
     if (rt->plan.trace) (void)hipFree(rt->plan.trace);
     if (rt->h_error) (void)hipHostFree(rt->h_error);
     if (rt->stamps) (void)hipFree(rt->stamps);
+    if (rt->trained_copy) (void)hipFree(rt->trained_copy);
     delete rt;
     g->rt = nullptr;
 }
@@ -616,6 +663,8 @@ int ng_capture(ng_graph* g) {
         if (rt.exec[i]) (void)hipGraphExecDestroy(rt.exec[i]), rt.exec[i] = nullptr;
         if (rt.graph[i]) (void)hipGraphDestroy(rt.graph[i]), rt.graph[i] = nullptr;
     }
+    if (g->trainable)
+        if (int rc = save_trained_weights(g)) return rc;
     if (int rc = record_multi(g, 0)) return rc;
     if (int rc = capture_single(g, 1)) return rc;
     // (a memory plan with reuse over time rules the device-resident replay out, see ng_set_memory_reuse)
@@ -654,6 +703,12 @@ int ng_capture(ng_graph* g) {
         g->mode = saved;
         pick_auto_mode(g);
     }
+    if (g->trainable) {                                        // the caller's weights as ng_capture found them
+        if (int rc = restore_trained_weights(g)) return rc;
+        NG_HIP(hipStreamSynchronize(rt.streams[0]));
+        if (rt.trained_copy) (void)hipFree(rt.trained_copy), rt.trained_copy = nullptr;
+        rt.trained.clear();
+    }
     return NG_OK;
 }
 
@@ -679,8 +734,18 @@ int ng_graph_multi_recheck(ng_graph* g, int replays) {
     if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_graph_multi_recheck: call ng_capture first");
     if (replays < 1 || replays > 100000) return g->fail(NG_EINVAL, "ng_graph_multi_recheck: replays must be 1..100000");
     if (g->graph_multi_state < 0) return NG_OK;               // a mismatch once seen stays
-    NG_HIP(hipStreamSynchronize(g->rt->streams[0]));
-    if (int rc = verify_graph_multi(g, replays)) return rc;
+    Runtime& rt = *g->rt;
+    NG_HIP(hipStreamSynchronize(rt.streams[0]));
+    if (g->trainable)
+        if (int rc = save_trained_weights(g)) return rc;
+    int rc = verify_graph_multi(g, replays);
+    if (g->trainable) {                                        // every compared replay started from the caller's weights, and they are back
+        if (rc == NG_OK) rc = restore_trained_weights(g);
+        (void)hipStreamSynchronize(rt.streams[0]);
+        if (rt.trained_copy) (void)hipFree(rt.trained_copy), rt.trained_copy = nullptr;
+        rt.trained.clear();
+    }
+    if (rc != NG_OK) return rc;
     pick_auto_mode(g);
     return NG_OK;
 }
@@ -778,7 +843,7 @@ int ng_replay_static(ng_graph* g) {
     NG_HIP(hipGetLastError());
     unsigned epoch = 1;
     void* args[2] = {&plan, &epoch};
-    NG_HIP(hipLaunchKernel(resident_kernel_handle(rt.resident_full), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
+    NG_HIP(hipLaunchKernel(resident_kernel_handle(rt.resident_build), dim3(rt.n_wg), dim3(kGroup), args, 0, origin));
     return NG_OK;
 }
 

@@ -50,7 +50,13 @@ def _new_streams(n):
 _OPS = {"conv1x1": B.NG_OP_CONV1X1, "dwconv": B.NG_OP_DWCONV, "conv3x3": B.NG_OP_CONV3X3,
         "bn_act": B.NG_OP_BN_ACT, "relu": B.NG_OP_RELU, "add_n": B.NG_OP_ADD_N,
         "concat": B.NG_OP_CONCAT, "pool": B.NG_OP_POOL, "global_avgpool": B.NG_OP_GLOBAL_AVGPOOL,
-        "fc": B.NG_OP_FC}
+        "fc": B.NG_OP_FC,
+        "conv1x1_dgrad": B.NG_OP_CONV1X1_DGRAD, "conv1x1_wgrad": B.NG_OP_CONV1X1_WGRAD,
+        "conv3x3_dgrad": B.NG_OP_CONV3X3_DGRAD, "conv3x3_wgrad": B.NG_OP_CONV3X3_WGRAD,
+        "dwconv_dgrad": B.NG_OP_DWCONV_DGRAD, "dwconv_wgrad": B.NG_OP_DWCONV_WGRAD,
+        "bn_act_dgrad": B.NG_OP_BN_ACT_DGRAD, "bn_act_wgrad": B.NG_OP_BN_ACT_WGRAD, "relu_dgrad": B.NG_OP_RELU_DGRAD,
+        "pool_dgrad": B.NG_OP_POOL_DGRAD, "global_avgpool_dgrad": B.NG_OP_GAP_DGRAD, "channel_sum": B.NG_OP_CHANNEL_SUM,
+        "slice_pad": B.NG_OP_SLICE_PAD, "sgd_update": B.NG_OP_SGD_UPDATE}
 
 
 def _params(nd) -> B.ng_op_params:
@@ -64,6 +70,10 @@ def _params(nd) -> B.ng_op_params:
     p.eps = float(q.get("eps", 0.0))
     for j, (lo, hi) in enumerate(zip(q.get("lo", []), q.get("hi", []))):
         p.slice_lo[j], p.slice_hi[j] = int(lo), int(hi)
+    if nd.op == "slice_pad":
+        p.slice_lo[0], p.slice_hi[0], p.slice_lo[1] = int(q["src_lo"]), int(q["src_hi"]), int(q["dst_lo"])
+    if nd.op == "sgd_update":
+        p.lr, p.slice_lo[0], p.cout = float(q["lr"]), int(q["offset"]), int(q["numel"])
     return p
 
 
@@ -75,7 +85,7 @@ class GraphRunner:
         self.workload = workload
         self.device = device
         self.g = B.ng_create()
-        self._weights = []                       # keeps device tensors alive
+        self._weights = {}                       # (node id, weight index) -> device tensor (kept alive; shared by backward nodes)
         self.arena = None
         self.streams = []
         for v, nd in enumerate(workload.nodes):
@@ -84,13 +94,15 @@ class GraphRunner:
                 vid = B.ng_add_input(self.g, (q["n"], q["c"], q["h"], q["w"]))
             else:
                 ptrs = []
-                for w in nd.weights:
+                for j, w in enumerate(nd.weights):
                     if device is None:
                         ptrs.append(0)
                     else:
                         t = torch.from_numpy(np.ascontiguousarray(w, dtype=np.float32)).to(device)
-                        self._weights.append(t)
+                        self._weights[(v, j)] = t
                         ptrs.append(t.data_ptr())
+                for ref in getattr(nd, "shared_weights", []):       # the same buffers as an earlier node's
+                    ptrs.append(0 if device is None else self._weights[tuple(ref)].data_ptr())
                 vid = B.ng_add_node(self.g, _OPS[nd.op], _params(nd), nd.preds, ptrs)
             assert vid == v
         for o in workload.outputs:
@@ -139,6 +151,8 @@ class GraphRunner:
         torch.cuda.synchronize(self.device)
         B.ng_bind(self.g, base, nbytes, self.streams)
         self.set_input(self.workload.input)
+        for node_id, value in getattr(self.workload, "inputs", {}).items():
+            self.set_input(value, node_id)
         B.ng_capture(self.g)
         return sched
 
@@ -151,6 +165,15 @@ class GraphRunner:
     def set_input(self, x: np.ndarray, node_id: int = 0):
         t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
         self._view(node_id).copy_(t.to(self.device))
+        torch.cuda.synchronize(self.device)
+
+    def weight(self, node_id, j) -> np.ndarray:
+        """Current value of weight j of a node (a training graph updates it in place)."""
+        torch.cuda.synchronize(self.device)
+        return self._weights[(node_id, j)].cpu().numpy()
+
+    def set_weight(self, node_id, j, value: np.ndarray):
+        self._weights[(node_id, j)].copy_(torch.from_numpy(np.ascontiguousarray(value, dtype=np.float32)).to(self.device))
         torch.cuda.synchronize(self.device)
 
     def replay(self, mode=None):

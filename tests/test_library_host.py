@@ -572,3 +572,82 @@ def test_graph_edges_errors():
     assert B.lib.ng_get_graph_edges(r.g, 1, None, C.byref(n_e), None, None, 5) == B.NG_EINVAL
     B.ng_set_launch_fusion(r.g, False)
     r.close()
+
+
+# ---- the DAG of a training iteration (forward + backward + update as tasks) -------------------
+
+def _training_workloads():
+    fw = workloads.make("tiny_cell")
+    out = fw.outputs[0]
+    yield workloads.training_graph(fw, 0.1, {out: np.ones(fw.nodes[out].shape, np.float32)})
+    fw = workloads.nas_cell_cifar(batch=2, c=8, image=8)
+    out = fw.outputs[0]
+    yield workloads.training_graph(fw, 0.1, {out: np.ones(fw.nodes[out].shape, np.float32)})
+
+
+def test_training_dag_registers_schedules_and_orders_every_weight_update():
+    for tw in _training_workloads():
+        n = len(tw.nodes)
+        r = GraphRunner(tw)
+        for v, nd in enumerate(tw.nodes):                        # the library's shape inference agrees with the recipe
+            assert B.ng_node_shape(r.g, v) == tuple(nd.shape), (v, nd.op)
+        sched = r.schedule()
+        o = oracle_schedule(n, tw.edges)
+        assert_same_schedule(sched, B.ng_get_scaffold(r.g), o)
+        assert checks.execution_respects_edges(n, tw.edges, sched["stream_of"], sched["order"], sched["sync"])
+        r.plan()
+        for fuse in (True, False):
+            launched_by, ge = B.ng_get_graph_edges(r.g, fuse)
+            ok, why = _graph_order_is_safe(tw, launched_by, ge)
+            assert ok, (tw.name, fuse, why)
+            assert all(launched_by[v] == v for v in range(n) if tw.nodes[v].op != "input")   # a graph that trains launches every task
+        plan = B.ng_resident_dry_plan(r.g)
+        assert plan["ok"]
+        r.close()
+        # an update writes its weight in place: every other node that reads that weight must be its ancestor,
+        # and nothing that reads the weight may come after it
+        reach = checks.reachable(n, tw.edges)
+        readers = {}
+        for v, nd in enumerate(tw.nodes):
+            keys = [(v, j) for j in range(len(nd.weights))] + [tuple(k) for k in nd.shared_weights]
+            for k in keys:
+                readers.setdefault(k, []).append(v)
+        assert tw.update_of
+        for key, upd in tw.update_of.items():
+            for v in readers[key]:
+                assert v == upd or reach[v][upd], (tw.name, key, v, upd)
+        # one gradient node per forward node that has one, one update per trainable weight (batch-norm statistics stay fixed)
+        for v, nd in enumerate(tw.forward.nodes):
+            want = {"conv1x1": 1, "conv3x3": 1, "dwconv": 1, "fc": 2, "bn_act": 2}.get(nd.op, 0)
+            assert sum(1 for (u, j) in tw.update_of if u == v) == want, (v, nd.op)
+
+
+def test_training_operator_errors():
+    g = B.ng_create()
+    x = B.ng_add_input(g, (2, 4, 6, 6))
+    dy = B.ng_add_input(g, (2, 4, 3, 3))
+    p = B.ng_op_params()
+    p.stride, p.pad, p.pool_mode = 1, 1, 0
+    with pytest.raises(B.NgError) as ei:                          # a 3x3 stride-1 pool of x is 6x6, not 3x3
+        B.ng_add_node(g, B.NG_OP_POOL_DGRAD, p, [dy, x], [])
+    assert ei.value.code == B.NG_ESHAPE
+    p.stride = 2
+    ok = B.ng_add_node(g, B.NG_OP_POOL_DGRAD, p, [dy, x], [])
+    assert B.ng_node_shape(g, ok) == (2, 4, 6, 6)
+    q = B.ng_op_params()
+    q.cout, q.lr = 1000, 0.1
+    with pytest.raises(B.NgError) as ei:                          # more elements than the gradient tensor has
+        B.ng_add_node(g, B.NG_OP_SGD_UPDATE, q, [ok], [0])
+    assert ei.value.code == B.NG_ESHAPE
+    q.cout = 10
+    with pytest.raises(B.NgError):                                # an update needs exactly one weight buffer
+        B.ng_add_node(g, B.NG_OP_SGD_UPDATE, q, [ok], [])
+    s = B.ng_op_params()
+    s.cout = 6
+    s.slice_lo[0], s.slice_hi[0], s.slice_lo[1] = 1, 4, 4          # 3 channels to [4, 7) of 6: out of range
+    with pytest.raises(B.NgError) as ei:
+        B.ng_add_node(g, B.NG_OP_SLICE_PAD, s, [dy], [])
+    assert ei.value.code == B.NG_ESHAPE
+    s.slice_lo[1] = 3
+    assert B.ng_node_shape(g, B.ng_add_node(g, B.NG_OP_SLICE_PAD, s, [dy], [])) == (2, 6, 3, 3)
+    B.ng_destroy(g)

@@ -28,5 +28,6 @@ Conventions shared by every consumer (an interface, not an implementation):
     fc              cout                    weights: W[cout, cin], b[cout];
                                             input must be [n, cin, 1, 1]
 """
-from .model import Node, Workload, OPS  # noqa: F401
+from .model import Node, Workload, OPS, TRAIN_OPS  # noqa: F401
 from .configs import make, CONFIG_NAMES  # noqa: F401
+from .training import training_graph, nas_cell_cifar, TrainingWorkload  # noqa: F401

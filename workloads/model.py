@@ -8,6 +8,10 @@ import numpy as np
 
 OPS = ("input", "conv1x1", "dwconv", "conv3x3", "bn_act", "relu", "add_n",
        "concat", "pool", "global_avgpool", "fc")
+# operators that only occur in the DAG of a training iteration (see workloads/training.py)
+TRAIN_OPS = ("conv1x1_dgrad", "conv1x1_wgrad", "conv3x3_dgrad", "conv3x3_wgrad", "dwconv_dgrad", "dwconv_wgrad",
+             "bn_act_dgrad", "bn_act_wgrad", "relu_dgrad", "pool_dgrad", "global_avgpool_dgrad", "channel_sum",
+             "slice_pad", "sgd_update")
 
 
 @dataclass
@@ -21,6 +25,9 @@ class Node:
     shape: Tuple[int, int, int, int] = (0, 0, 0, 0)
     # Multiplier on the std of this node's random weights (recipe-internal).
     init_gain: float = 1.0
+    # Weight buffers this node shares with earlier nodes, as (node id, weight index) pairs, in the order the
+    # operator takes them (a backward operator reads the forward operator's weights, the update writes them).
+    shared_weights: List[Tuple[int, int]] = field(default_factory=list)
 
 
 @dataclass
