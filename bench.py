@@ -51,12 +51,28 @@ MEASURED_TRAFFIC_BYTES = {}
 
 MODES = {"graph_multi": 0, "graph_single": 1, "eager_single": 2, "eager_multi": 3, "device_resident": 4}
 MODE_NAMES = {v: k for k, v in MODES.items()}
-ALL_CONFIGS = [("tiny_cell", 1), ("chain50", 1), ("random200", 1), ("nasnet_style", 1), ("inception_style", 1), ("inception_style", 32)]
+ALL_CONFIGS = [("tiny_cell", 1), ("chain50", 1), ("random200", 1), ("nasnet_style", 1), ("inception_style", 1), ("inception_style", 32),
+               ("nas_cell_cifar_training", 32)]
 HEADLINE = ("nasnet_style", 1)
 
 
 def label(name, batch):
-    return name + (f"_b{batch}" if name == "inception_style" else "")
+    return name + (f"_b{batch}" if name in ("inception_style", "nas_cell_cifar_training") else "")
+
+
+def make_workload(name, batch):
+    import numpy as np
+    import workloads
+    if name == "nas_cell_cifar_training":
+        # one training iteration (forward, backward, SGD) of the NAS-cell network on CIFAR-sized inputs, the paper's
+        # training setting (Section 5); dL/dlogits is a fixed random seed tensor, the step size is tiny so that
+        # thousands of timed steps do not drift the weights away
+        fwd = workloads.nas_cell_cifar(batch=batch)
+        out = fwd.outputs[0]
+        seed = (np.random.default_rng(0).standard_normal(fwd.nodes[out].shape) / batch).astype(np.float32)
+        return workloads.training_graph(fwd, 1e-6, {out: seed})
+    kw = {"batch": batch} if name == "inception_style" else {}
+    return workloads.make(name, **kw)
 
 
 def percentile(xs, q):
@@ -186,11 +202,9 @@ def resident_timeline(runner, B, w, n_nodes, verbose):
 def measure(name, batch, steps, warmup, args, headline):
     """All measurements of one configuration -> dict."""
     import torch
-    import workloads
     from paper_2012_02732_amd import GraphRunner, binding as B
 
-    kw = {"batch": batch} if name == "inception_style" else {}
-    w = workloads.make(name, **kw)
+    w = make_workload(name, batch)
     t_prep = time.perf_counter()
     runner = GraphRunner(w, "cuda:0")
     sched = runner.prepare()
@@ -346,11 +360,9 @@ def measure(name, batch, steps, warmup, args, headline):
 def solo_launches(args):
     """Every task's kernel `R` times by itself, then the kernels the chosen replay mode really runs, each
     after a marker of three empty kernels; writes what was launched, in order, to the sidecar file."""
-    import workloads
     from paper_2012_02732_amd import GraphRunner, binding as B
     name, batch = args.config, args.batch
-    kw = {"batch": batch} if name == "inception_style" else {}
-    w = workloads.make(name, **kw)
+    w = make_workload(name, batch)
     runner = GraphRunner(w, "cuda:0")
     runner.prepare()
     auto_mode, _ = B.ng_auto_mode(runner.g)
@@ -465,7 +477,7 @@ def main():
     if args.config == "all":
         todo, head = ALL_CONFIGS, HEADLINE
     else:
-        head = (args.config, args.batch if args.config == "inception_style" else 1)
+        head = (args.config, args.batch if args.config in ("inception_style", "nas_cell_cifar_training") else 1)
         todo = [head]
     results = {}
     for name, batch in todo:

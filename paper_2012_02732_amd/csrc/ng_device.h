@@ -266,6 +266,8 @@ struct DwGradArgs {            // depthwise backward; C, H, W, Ho, Wo, K, S of t
     const float* dy; const float* x; const float* w;
     float* y;                  // dgrad: dx [N][C][H][W]; wgrad: dW [C][K][K]
     int N, C, H, W, Ho, Wo, K, S, total;
+    float* ws;                 // wgrad, N > 1: per-image partial sums [C][N][K K]
+    unsigned* cnt;             // wgrad, N > 1: arrivals per channel, zero between replays
 };
 struct PoolGradArgs {          // pool backward; geometry of the FORWARD operator
     const float* dy; const float* x;

@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 #include <type_traits>
 
@@ -119,6 +120,9 @@ __global__ __launch_bounds__(kBlock) void fold_bn_kernel(const float* gamma, con
 // for the task's completion counters, which does its work on the first call only.
 // A convolution tile with a fused add_n calls `late` the same way, once, before it reads the
 // other operands of the sum.
+// A tile function meets the same number of workgroup barriers whatever its tile index and whether
+// or not it is `live`: in the resident kernel two sub-blocks of one workgroup run different tiles
+// of a task side by side and share every barrier.
 struct NoWait {
     __device__ __forceinline__ void operator()() const {}
     __device__ __forceinline__ void late() const {}
@@ -1631,7 +1635,11 @@ namespace {
 // K split of a weight-gradient GEMM: enough workgroups to occupy the GPU, splits of whole K slices
 void gemm_split(long m, long n, long k, int* splits, int* k_per_split) {
     const long tiles = ceil_div(m, kGemmTile) * ceil_div(n, kGemmTile);
-    long want = std::max<long>(1, std::min<long>(ceil_div(768, tiles), ceil_div(k, 256)));
+    // A split costs its share of the K slices (about 0.5 us each) and adds one partial tile to what the workgroup
+    // that arrives last has to add up (about 0.4 us each): the sum is smallest near sqrt(1.25 x slices) splits.
+    const double slices = (double)ceil_div(k, 16);
+    long want = (long)std::lround(std::sqrt(1.25 * slices));
+    want = std::max<long>(1, std::min<long>(want, std::max<long>(1, 768 / tiles)));
     const long per = ceil_div(ceil_div(k, want), 16) * 16;
     *k_per_split = (int)per;
     *splits = (int)ceil_div(k, per);
@@ -1656,6 +1664,10 @@ size_t packed_floats(const ng_graph* g, int v) {
         const size_t tiles = (size_t)(ceil_div(wm, kGemmTile) * ceil_div(wn, kGemmTile));
         return splits > 1 ? tiles * splits * kGemmTile * kGemmTile + ((tiles + 63) & ~(size_t)63) : 0;
     }
+    if (nd.op == NG_OP_DWCONV_WGRAD) {                         // per-image partial sums [C][N][K K], then one arrival counter per channel
+        const Shape& x = g->nodes[nd.preds[1]].out;
+        return x.n > 1 ? (size_t)x.c * x.n * nd.p.k * nd.p.k + (size_t)((x.c + 63) & ~63L) : 0;
+    }
     if (g->trainable) return 0;                                // weights change between replays: nothing is folded or repacked
     if (nd.op == NG_OP_BN_ACT) return 2 * (size_t)((nd.out.c + 3) & ~3L);   // folded scale, shift
     if (nd.op == NG_OP_CONV3X3) return choose_c3(g, v).packed;
@@ -1672,6 +1684,14 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
         const size_t tiles = (size_t)(ceil_div(wm, kGemmTile) * ceil_div(wn, kGemmTile)), cnt = (tiles + 63) & ~(size_t)63;
         const hipError_t e = hipMemsetAsync(packed + floats - cnt, 0, cnt * sizeof(float), static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return g->fail(NG_EHIP, "clearing split-K counters: %s", hipGetErrorString(e));
+        return NG_OK;
+    }
+    if (nd.op == NG_OP_DWCONV_WGRAD) {
+        const size_t floats = packed_floats(g, v);
+        if (floats == 0) return NG_OK;
+        const size_t cnt = (size_t)((g->nodes[nd.preds[1]].out.c + 63) & ~63L);
+        const hipError_t e = hipMemsetAsync(packed + floats - cnt, 0, cnt * sizeof(float), static_cast<hipStream_t>(stream));
+        if (e != hipSuccess) return g->fail(NG_EHIP, "clearing depthwise wgrad counters: %s", hipGetErrorString(e));
         return NG_OK;
     }
     if (g->trainable) return NG_OK;
@@ -1992,7 +2012,12 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.w = wf(0);
                 set_kernel<KID_DW_DGRAD>(t, a, ceil_div(a.total, kBlock));
             } else {
-                set_kernel<KID_DW_WGRAD>(t, a, a.C);
+                if (a.N > 1) {
+                    if (!packed) return g->fail(NG_EINVAL, "node %d: no workspace for the per-image partial sums", v);
+                    a.ws = packed;
+                    a.cnt = reinterpret_cast<unsigned*>(packed + (size_t)a.C * a.N * a.K * a.K);
+                }
+                set_kernel<KID_DW_WGRAD>(t, a, (long)a.C * a.N);
             }
             break;
         }

@@ -104,9 +104,9 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
             base = 1.5 + 0.00002 * count * 256.0 / kBlock, per_tile = 0.00003 * count;   // one workgroup walks a whole channel
             break;
         }
-        case KID_DW_WGRAD: {
-            const double count = (double)g->nodes[nd.preds[0]].out.elems() / std::max<double>(1.0, (double)g->nodes[nd.preds[0]].out.c);
-            base = 2.0, per_tile = 0.0005 * count;
+        case KID_DW_WGRAD: {                                           // one workgroup per (channel, image)
+            const double count = (double)g->nodes[nd.preds[0]].out.h * (double)g->nodes[nd.preds[0]].out.w;
+            base = 2.5, per_tile = 0.0005 * count;
             break;
         }
         default: break;
