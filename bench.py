@@ -25,6 +25,9 @@ Other uses:
         (to be run under `rocprofv3 --kernel-trace`), writes what it launched to F;
   bench.py --dispatch-trace kernel_trace.csv --sidecar F   no GPU: critical path from the trace's
         begin-to-end dispatch timestamps.
+  bench.py --config C --mode graph_multi --replay-only N   N replays between two markers (under
+        `rocprofv3 --kernel-trace`); bench.py --overlap-trace kernel_trace.csv --replay-only N   no GPU:
+        how many kernels execute at the same time and the idle gaps between them.
 """
 from __future__ import annotations
 
@@ -430,6 +433,68 @@ def dispatch_trace(args):
         print(f"{kn:28s} {'as executed' if executed else 'per task':12s} {len(v):5d} {statistics.median(v):10.2f} {min(v):7.2f} {max(v):7.2f}", file=sys.stderr)
 
 
+def replay_only(args):
+    """A few replays in one launch-based mode and nothing else after the marker: for a kernel trace from outside."""
+    from paper_2012_02732_amd import GraphRunner, binding as B
+    w = make_workload(args.config, args.batch)
+    runner = GraphRunner(w, "cuda:0")
+    runner.prepare(plan_trials=1)
+    mode = MODES[args.mode]
+    total, lat = time_mode(runner, B, mode, 20, 5)
+    for _ in range(3):
+        B.ng_launch_task_solo(runner.g, -1)
+    for _ in range(args.replay_only):
+        B.ng_replay(runner.g)
+        B.ng_sync(runner.g)
+    for _ in range(3):
+        B.ng_launch_task_solo(runner.g, -1)
+    runner.close()
+    print(json.dumps({"workload": label(args.config, args.batch), "replay": args.mode, "replays_after_marker": args.replay_only,
+                      "replay_median_us_under_the_profiler": statistics.median(lat)}))
+
+
+def overlap_trace(args):
+    """Kernel overlap and idle gaps of launch-based replays, from the begin / end timestamps of a kernel trace of
+    --replay-only (no GPU needed): between the two markers (three empty kernels each), per replay."""
+    rows = []
+    with open(args.overlap_trace, newline="") as f:
+        for r in csv.DictReader(f):
+            rows.append((int(r["Start_Timestamp"]), int(r["End_Timestamp"]), r["Kernel_Name"]))
+    rows.sort()
+    marks = [i for i in range(len(rows) - 2) if all("empty_kernel" in rows[i + j][2] for j in range(3))]
+    assert len(marks) >= 2, "markers not found in the trace"
+    body = rows[marks[-2] + 3:marks[-1]]
+    assert body and args.replay_only > 0 and len(body) % args.replay_only == 0, (len(body), args.replay_only)
+    per = len(body) // args.replay_only
+    hist, spans, busy_any, sum_dur, gaps = {}, [], [], [], []
+    for rep in range(args.replay_only):
+        ks = body[rep * per:(rep + 1) * per]
+        t0, t1 = min(k[0] for k in ks), max(k[1] for k in ks)
+        ev = sorted([(k[0], 1) for k in ks] + [(k[1], -1) for k in ks])
+        level, last = 0, t0
+        local = {}
+        for t, d in ev:
+            local[level] = local.get(level, 0) + (t - last)
+            if level == 0 and t > last:
+                gaps.append((t - last) / 1000.0)
+            level += d
+            last = t
+        for k, v in local.items():
+            hist[k] = hist.get(k, 0.0) + v / 1000.0
+        spans.append((t1 - t0) / 1000.0)
+        busy_any.append(((t1 - t0) - local.get(0, 0)) / 1000.0)
+        sum_dur.append(sum(k[1] - k[0] for k in ks) / 1000.0)
+    n = args.replay_only
+    out = {"kernels_per_replay": per, "replays": n, "first_start_to_last_end_us": statistics.median(spans),
+           "some_kernel_executing_us": statistics.median(busy_any), "no_kernel_executing_us": statistics.median(spans) - statistics.median(busy_any),
+           "sum_of_kernel_durations_us": statistics.median(sum_dur),
+           "kernels_executing_on_average_while_any_is": statistics.median(sum_dur) / statistics.median(busy_any),
+           "time_with_k_kernels_executing_us": {str(k): hist[k] / n for k in sorted(hist)},
+           "idle_gaps": {"count_per_replay": len(gaps) / n, "median_us": statistics.median(gaps) if gaps else 0.0,
+                         "p90_us": percentile(gaps, 0.9) if gaps else 0.0, "max_us": max(gaps) if gaps else 0.0}}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -451,20 +516,29 @@ def main():
     ap.add_argument("--solo-launches", type=int, default=0)
     ap.add_argument("--sidecar", default="solo_sidecar.json")
     ap.add_argument("--dispatch-trace", default=None)
+    ap.add_argument("--replay-only", type=int, default=0, help="with --config and --mode: that many replays between two markers, for a kernel trace")
+    ap.add_argument("--overlap-trace", default=None, help="kernel trace (csv) of a --replay-only run: overlap histogram and idle gaps (give the same --replay-only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no multi-GPU part); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     if args.dispatch_trace:
         return dispatch_trace(args)
+    if args.overlap_trace:
+        return overlap_trace(args)
 
     import torch
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
-    if args.solo_launches > 0:
+    if args.solo_launches > 0 or args.replay_only > 0:
         if args.config == "all":
             args.config = HEADLINE[0]
+        if args.replay_only > 0:
+            if args.mode in ("auto", "device_resident"):
+                print("bench.py: --replay-only is for the launch-based modes (give --mode)", file=sys.stderr)
+                sys.exit(2)
+            return replay_only(args)
         return solo_launches(args)
 
     if args.copy_probe:
