@@ -187,10 +187,10 @@ int ng_plan_memory(ng_graph* g, size_t* arena_bytes);
  * readers are ancestors of v in the DAG, so that any execution that respects the DAG - on any
  * number of streams - is through with it before v writes. Best fit among such buffers, else new
  * memory. Network inputs, outputs and the tensors of in-place concats keep private buffers.
- * The device-resident replay keeps XCD-private L2 lines dirty across tasks and cannot run on such
- * a plan: ng_capture then prepares the HIP-graph and plain-launch modes only, NG_MODE_AUTO
- * chooses between the two graphs, and selecting NG_MODE_DEVICE_RESIDENT makes ng_replay fail
- * with NG_ESTATE. */
+ * The device-resident replay normally keeps a stream's tensors in the L2 of one XCD; on such a plan
+ * an address holds several tensors in the course of a replay, so there every load and store of it
+ * goes through device scope instead (as with device_scope_everywhere of ng_resident_config) and no
+ * task runs inside another task's tiles: slower than on a plan without reuse, same results. */
 int ng_set_memory_reuse(ng_graph* g, int on);
 /* Modes 0-3 launch one kernel per task, except that (on by default) a batch-norm / ReLU whose only
  * input is a convolution result is applied by that convolution's kernel and a concat whose inputs
@@ -276,7 +276,7 @@ int ng_replay_mode(ng_graph* g, int mode);
 /* The mode NG_MODE_AUTO stands for (0, 1 or 4) and the median replay + wait times, in
  * microseconds, the trial at ng_capture measured for modes 0, 1 and 4 (HOST array of 3;
  * either pointer may be NULL). 0 for a mode that was not a candidate: mode 0 when its check
- * failed, mode 4 under a memory plan with reuse. */
+ * failed. */
 int ng_auto_mode(const ng_graph* g, int* mode, float* trial_us);
 /* Result of the check of the multi-stream graph at ng_capture (see NG_MODE_GRAPH_MULTI):
  * *state = 1 every compared replay reproduced the single-stream result byte for byte, -1 some
@@ -301,7 +301,7 @@ int ng_sync(ng_graph* g);
  * instead of memory from hipMalloc. The call allocates and frees nothing and records no memset: it
  * enqueues a fill kernel that clears the part of the array it uses and then the replay kernel, both
  * on the origin stream. Limits: graphs of at most 1024 nodes (NG_ENOMEM with the sizes otherwise);
- * needs ng_capture and a device-resident plan (NG_ESTATE under a memory plan with reuse); the
+ * needs ng_capture (NG_ESTATE before); the
  * device the graph was bound on must be current (NG_EINVAL). All calls on one GPU - of this graph
  * or of any other - share the array: calls that overlap on one GPU race; wait (ng_sync) for one
  * before the next is enqueued. The per-task timeline (ng_resident_trace) is not recorded. */

@@ -164,7 +164,9 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
     const int n = (int)g->nodes.size();
     const int per_xcd = n_wg / 8;
     const bool debug = knob("NG_PLAN_DEBUG") != nullptr;
-    const bool allow_local = knob("NG_NO_LOCAL") == nullptr;
+    // (under a memory plan with reuse over time a task's result may live where its producer's own input still is: every task
+    // then waits for the completion of all its producers, and no task runs inside another task's tiles)
+    const bool allow_local = knob("NG_NO_LOCAL") == nullptr && !g->memory_reuse;
 
     // the planner counts work in units of `subs` tiles: what one workgroup does in one round
     auto units_for = [&](long ntiles, int subs) { return (ntiles + subs - 1) / subs; };
@@ -196,7 +198,7 @@ void simulate(const ng_graph* g, int n_wg, int nx, const PlanKnobs& knobs, Sim& 
     out.elided.assign(n, 0);
     out.model_run.assign(n, 0.0);
     const bool allow_elide = knob("NG_NO_ELIDE") == nullptr;
-    const bool allow_fuse = knob("NG_NO_FUSE") == nullptr;
+    const bool allow_fuse = knob("NG_NO_FUSE") == nullptr && !g->memory_reuse;
     std::vector<double> free_at(n_wg, 0.0), finish(n, 0.0);
     std::vector<std::vector<int>> parents(n), wgs(n);
     for (auto& e : sc.meg) parents[e.second].push_back(e.first);

@@ -667,14 +667,19 @@ int ng_capture(ng_graph* g) {
         if (int rc = save_trained_weights(g)) return rc;
     if (int rc = record_multi(g, 0)) return rc;
     if (int rc = capture_single(g, 1)) return rc;
-    // (a memory plan with reuse over time rules the device-resident replay out, see ng_set_memory_reuse)
-    if (!rt.d_records && !g->memory_reuse)
+    // Under a memory plan with reuse over time an address holds several tensors in the course of one replay, produced
+    // and read on different XCDs: no XCD-private L2 may keep a line of it (a dirty line of an earlier tensor could be
+    // written back over a later one, a clean one could be read in its place). Every store and load of the
+    // device-resident replay then goes through device scope, as in the fallback for an unexpected XCD mapping, and the
+    // planner runs no task inside another task's tiles (a fused result may live where the host's own input still is).
+    if (g->memory_reuse) g->resident_all_far = true;
+    if (!rt.d_records)
         if (int rc = build_resident(g)) return rc;
     // the pre-run itself: execute the recorded schedule once so that every kernel is loaded
     NG_HIP(hipGraphLaunch(rt.exec[1], rt.streams[0]));
     NG_HIP(hipStreamSynchronize(rt.streams[0]));
     g->phase = CAPTURED;
-    if (rt.d_records && !g->memory_reuse)
+    if (rt.d_records)
         if (int rc = tune_resident(g)) return rc;
     // the multi-stream graph has to reproduce the single-stream result before it may be chosen
     if (int rc = verify_graph_multi(g, 0)) return rc;
@@ -684,7 +689,7 @@ int ng_capture(ng_graph* g) {
         const int saved = g->mode;
         for (int i = 0; i < 3; ++i) {
             g->auto_trial_us[i] = 0.f;
-            if ((i == 0 && g->graph_multi_state != 1) || (i == 2 && g->memory_reuse)) continue;
+            if (i == 0 && g->graph_multi_state != 1) continue;
             g->mode = candidates[i];
             std::vector<float> us;
             for (int rep = 0; rep < 2 + 9; ++rep) {
@@ -811,7 +816,7 @@ int ng_replay_static(ng_graph* g) {
     if (!g) return NG_EINVAL;
     if (g->phase < CAPTURED) return g->fail(NG_ESTATE, "ng_replay_static: call ng_capture first");
     Runtime& rt = *g->rt;
-    if (!rt.d_records) return g->fail(NG_ESTATE, "ng_replay_static: this graph has no device-resident plan (memory plan with reuse)");
+    if (!rt.d_records) return g->fail(NG_ESTATE, "ng_replay_static: this graph has no device-resident plan");
     const size_t n = g->nodes.size();
     const size_t done_words = n * (size_t)rt.plan.done_stride;
     const size_t xcc_at = (10 * done_words + 1) & ~(size_t)1, error_at = xcc_at + 16, need = error_at + 2;
