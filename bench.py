@@ -50,7 +50,7 @@ RIDGE_FLOP_PER_BYTE = PEAK_MFMA_F32_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
 # HBM bytes of one launch of the dominant kernel, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; KiB
 # per dispatch) scaled by what the same counters read for a plain 256 MiB copy (2.00 and 1.00). Key:
 # (workload, kernel). The summaries with the commands are under profiles/.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {("nasnet_style", "resident_kernel"): (29281.7 * 2.00 + 43689.1 * 1.00) * 1024}   # profiles/resident_kernel_nasnet_style.md
 
 MODES = {"graph_multi": 0, "graph_single": 1, "eager_single": 2, "eager_multi": 3, "device_resident": 4}
 MODE_NAMES = {v: k for k, v in MODES.items()}
