@@ -24,6 +24,10 @@ enum Kid : int {
     KID_PW_V1A, KID_PW_V2A, KID_PW_V3A, KID_PW_V4A, KID_PW_S1A, KID_PW_S2A, KID_PW_S3A, KID_PW_S4A,
     KID_C3_M1A, KID_C3_M2A, KID_C3_M3A, KID_C3_M4A, KID_POOL_A, KID_POOL_P4A,
     KID_C3_L32, KID_C3_L64,          // conv3x3 as an implicit GEMM staged through LDS, 32 x 128 / 64 x 64 output tiles (many columns)
+    // conv3x3 for many output pixels, patch-stationary: 16 input channels of the tile's input patch sit in LDS and the nine taps
+    // read it at shifted addresses; weights go from memory straight into matrix-instruction operands. Output tiles (rows x pixels)
+    // 64 x 64 and 96 x 64 with a patch of up to 256 pixels; 32 x 128, 64 x 64 and 64 x 128 with up to 640 (wide images, stride 2)
+    KID_C3_P64, KID_C3_P96, KID_C3_Q32, KID_C3_Q64, KID_C3_Q128,
     // graphs that train (weights change between replays, so nothing is repacked): convolutions and fc, forward and backward,
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
     KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
@@ -50,7 +54,8 @@ constexpr bool is_pool(int kid) { return plain_variant(kid) == KID_POOL || plain
 constexpr bool is_pw16(int kid) { return plain_variant(kid) >= KID_PW_V1 && plain_variant(kid) <= KID_PW_S4; }
 constexpr bool is_c3m(int kid) { return plain_variant(kid) >= KID_C3_M1 && plain_variant(kid) <= KID_C3_M4; }
 constexpr bool has_add_epilogue(int kid) { return plain_variant(kid) != kid; }
-constexpr bool is_c3_lds(int kid) { return kid == KID_C3_L32 || kid == KID_C3_L64; }
+constexpr bool is_c3_patch(int kid) { return kid >= KID_C3_P64 && kid <= KID_C3_Q128; }
+constexpr bool is_c3_lds(int kid) { return kid == KID_C3_L32 || kid == KID_C3_L64 || is_c3_patch(kid); }
 // convolutions whose argument block is a C3Args (the others with a batch-norm epilogue take a PwArgs)
 constexpr bool takes_c3_args(int kid) { return is_c3m(kid) || is_c3_lds(kid) || (kid >= KID_C3_T16S1 && kid <= KID_C3_T8S2); }
 // kernels whose tiles can apply a batch-norm / ReLU to their results before storing them: every convolution
@@ -78,13 +83,14 @@ constexpr int partition_of(int kid_any) {
 constexpr bool is_matrix_kernel(int kid_any) {
     const int kid = plain_variant(kid_any);
     return (kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || (kid >= KID_PW_V1 && kid <= KID_PW_S4) || (kid >= KID_C3_M1 && kid <= KID_C3_M4) ||
-           kid == KID_C3_L32 || kid == KID_C3_L64;
+           kid == KID_C3_L32 || kid == KID_C3_L64 || is_c3_patch(kid);
 }
 
 // kernels of the lean build of the resident kernel: everything except the 32 x 32 and LDS-tiled
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
-    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_train_kernel(kid);
+    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) &&
+           !is_train_kernel(kid);
 }
 // Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean
 // kernels plus the training kernels: a graph that trains runs its convolutions through the GEMM kernels, never through
@@ -212,14 +218,16 @@ struct C3Args {
     int Cin, Cout, H, W, Ho, Wo;
     int pad;
     int tiles_x;               // pixel tiles along W
-    int tiles_xy;              // pixel tiles per image
+    int tiles_xy;              // pixel tiles per image (patch-stationary kernels: runs of consecutive pixels per image)
     int co_groups;             // channel groups (workgroups along Cout)
     // implicit-GEMM kernels: Y[Cout][cols] = W[Cout][9 Cin] * patches[9 Cin][cols]
     const float* wp;           // weights repacked into MFMA operand order, 4 k-steps per lane
-    int groups;                // groups of 4 k-steps in the packed copy (a multiple of 4 * groups in flight)
+                               // (patch-stationary kernels: [tap * Cin / 16 + block][CoutP][16], see pack_c3_patch_weights_kernel)
+    int groups;                // groups of 4 k-steps in the packed copy (a multiple of 4 * groups in flight);
+                               // LDS-staged and patch-stationary kernels: input channels of the packed copy
     int stride;
     int cols;                  // N * Ho * Wo
-    int tiles_n;               // ceil(cols / 16)
+    int tiles_n;               // tiles along the pixel axis (patch-stationary kernels: N * tiles_xy)
     Epilogue ep;
 };
 struct C3AddArgs : C3Args {

@@ -86,8 +86,13 @@ __device__ __forceinline__ float4 ldg4_any_far(const float* p) {
     return make_float4(v[0], v[1], v[2], v[3]);
 }
 
-// LDS floats every workgroup owns: the largest user is the conv3x3 input patch (4 x 33 x 34).
+// LDS floats every workgroup owns: the largest users are the conv3x3 input patches (4 x 33 x 34; 256 pixels x 20).
 constexpr int kSmemFloats = 5120;
+// ... and what the conv3x3 kernels with a patch of up to 640 pixels get instead (stand-alone kernels: only they; the
+// resident kernel: every workgroup of the build that contains them)
+constexpr int kSmemFloatsWide = 12800;
+constexpr bool has_wide_patch(int kid) { return kid == KID_C3_Q32 || kid == KID_C3_Q64 || kid == KID_C3_Q128; }
+constexpr int smem_floats(int kid) { return has_wide_patch(kid) ? kSmemFloatsWide : kSmemFloats; }
 
 // ------------------------------------------------------------------------------------
 // bn_act / relu: y = x * s[c] + t[c] (s, t folded from gamma, beta, mean, var), optional ReLU
@@ -652,6 +657,176 @@ __device__ __forceinline__ void conv3x3_lds_tile(const C3Args& a, int tile, floa
         }
 }
 
+// ------------------------------------------------------------------------------------
+// conv3x3 for many output pixels (large maps, batches), patch-stationary: Y[Cout x pixels] = W[Cout x 9 Cin] * patches.
+// A tile is TM = 32 FM output channels by a run of TN = 32 FN consecutive output pixels of one image (row-major, so a run
+// may wrap over several rows). K is walked in blocks of 16 input channels, and within a block tap by tap:
+//   * B operand. The input pixels the run needs - its rows plus the halo, (W + 2 pad) wide with the padding stored as
+//     zeros - are kept in LDS for one block of 16 channels, pixel-major, 20 floats per pixel, the 16 channels of a
+//     pixel in the order p = 4 (k % 4) + k / 4: v_mfma_f32_16x16x4_f32 step s takes k = 4 s + g from lane group g, so
+//     one 128-bit LDS read gives a lane its operands of all four steps. A tap is an address shift
+//     ((dr (W + 2 pad) + dc) pixels), so the nine taps of a block run off ONE patch without a barrier between them: 9 x
+//     4 FM FN matrix instructions per wavefront per pair of barriers, and each input element is fetched once per
+//     tile and block instead of once per tap.
+//   * A operand. The weights were repacked at bind time into [tap * blocks + block][CoutP][16] with the same order of
+//     the 16 k: the 16 rows x 64 bytes a wavefront needs for one fragment are 1 KiB in a row, and every lane loads its
+//     four operands with one 128-bit load straight from memory (L2) into registers, three slices ahead. No LDS, no
+//     barrier and no vector ALU work for A.
+//   * Filling the patch: a thread owns up to 4 PM / 256 (pixel, group of 4 channels) items; their global offsets are
+//     worked out once per tile (out-of-image and padding positions get an offset beyond the buffer's size, for which
+//     a buffer load returns 0), so a fill is four 32-bit loads with a scalar channel offset and one 128-bit LDS write
+//     per item. The loads of block b + 1 are issued in the middle of block b's taps.
+// Four wavefronts as 2 x 2, each 16 FM x 16 FN. Needs Cin % 16 == 0 and a patch of at most PM pixels.
+// ------------------------------------------------------------------------------------
+template <int FM, int FN, int PM, bool FIN, class Wait>
+__device__ __forceinline__ void conv3x3_patch_tile(const C3Args& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();
+    constexpr int WM = 16 * FM, WN = 16 * FN, TM = 2 * WM, TN = 2 * WN, LD = 20;
+    constexpr int ITEMS = 4 * PM / kBlock;
+    constexpr unsigned kOutside = 0x80000000u;          // beyond any tensor (num_records < 2^31): the load returns 0
+    constexpr int kIn = FIN ? kPolicyDeviceScope : 0;
+    static_assert(PM * LD <= (PM > 256 ? kSmemFloatsWide : kSmemFloats) && PM % 64 == 0, "LDS budget");
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int r = lane & 15, g = lane >> 4;
+    const int by = tile % a.co_groups, bt = tile / a.co_groups;
+    const int img = bt / a.tiles_xy, seg = bt - img * a.tiles_xy;
+    const int m0 = by * TM;
+    const int HWo = a.Ho * a.Wo, HW = a.H * a.W;
+    const int p0 = seg * TN, npx = min(TN, HWo - p0);
+    const int oy_a = p0 / a.Wo, oy_b = (p0 + npx - 1) / a.Wo;
+    const int iy_a = oy_a * a.stride - a.pad, Wp = a.W + 2 * a.pad, P = ((oy_b - oy_a) * a.stride + 3) * Wp;
+    const int blocks = a.groups / 16, n_slices = 9 * blocks, CoutP = a.co_groups * TM;
+    const __amdgpu_buffer_rsrc_t xr =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x), 0, (a.tiles_n / a.tiles_xy) * a.Cin * HW * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.wp), 0, n_slices * CoutP * 64, 0x00020000);
+
+    // this thread's fill items: (pixel of the patch, channels j, j + 4, j + 8, j + 12 of the block)
+    unsigned goff[ITEMS];
+    int loff[ITEMS];
+#pragma unroll
+    for (int t = 0; t < ITEMS; ++t) {
+        const int idx = tid + kBlock * t;
+        const int j = idx / P, pixel = idx - j * P;
+        const int pr = pixel / Wp, pc = pixel - pr * Wp;
+        const int iy = iy_a + pr, ix = pc - a.pad;
+        const bool item = live && idx < 4 * P;
+        const bool inside = item && (unsigned)iy < (unsigned)a.H && (unsigned)ix < (unsigned)a.W;
+        goff[t] = inside ? (unsigned)(((img * a.Cin + j) * HW + iy * a.W + ix) * 4) : kOutside;
+        loff[t] = item ? pixel * (LD / 4) + j : -1;     // in units of 4 floats
+    }
+    // where this lane's B fragments start in the patch (tap 0), and its A rows in a slice of the packed weights
+    int lbase[FN];
+#pragma unroll
+    for (int jn = 0; jn < FN; ++jn) {
+        const int px = p0 + min(wn * WN + jn * 16 + r, npx - 1);
+        const int oy = px / a.Wo, ox = px - oy * a.Wo;
+        lbase[jn] = ((oy - oy_a) * a.stride * Wp + ox * a.stride) * LD + 4 * g;
+    }
+    const unsigned va_off = (unsigned)(((wm * WM + r) * 16 + 4 * g) * 4);
+
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < FN; ++jn) acc[i][jn] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 pv[ITEMS];
+    // Loads are issued unconditionally and in a fixed order (idle items read "outside"): the compiler then counts
+    // exactly how many younger loads may stay in flight at each wait.
+    auto fill_load = [&](int block) {
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t) {
+            u32x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = __builtin_amdgcn_raw_buffer_load_b32(xr, goff[t], (unsigned)((block * 16 + 4 * q) * HW * 4), kIn);
+            pv[t] = v;
+        }
+    };
+    auto fill_store = [&]() {
+#pragma unroll
+        for (int t = 0; t < ITEMS; ++t)
+            if (loff[t] >= 0) reinterpret_cast<u32x4*>(smem)[loff[t]] = pv[t];
+    };
+    u32x4 af[3][FM];
+    auto a_load = [&](int slice, int stage) {
+        const int block = slice / 9, tap = slice - 9 * block;
+        const unsigned so = (unsigned)(((tap * blocks + block) * CoutP + m0) * 64);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) af[stage][i] = __builtin_amdgcn_raw_buffer_load_b128(wr, va_off + i * 1024, so, 0);
+    };
+
+    wait();
+    if (live) {
+        fill_load(0);
+#pragma unroll
+        for (int d = 0; d < 3; ++d) a_load(d, d);
+        fill_store();
+    }
+    __syncthreads();
+    for (int block = 0; block < blocks; ++block) {
+        if (live) {
+            f32x4 bf[2][FN];
+#pragma unroll
+            for (int jn = 0; jn < FN; ++jn) bf[0][jn] = *reinterpret_cast<const f32x4*>(smem + lbase[jn]);
+#pragma unroll
+            for (int tap = 0; tap < 9; ++tap) {
+                const int slice = block * 9 + tap, stage = tap % 3;
+                if (tap < 8) {                          // next tap's B fragments, before this tap's matrix instructions
+                    const int shift = (((tap + 1) / 3) * Wp + (tap + 1) % 3) * LD;
+#pragma unroll
+                    for (int jn = 0; jn < FN; ++jn) bf[(tap + 1) & 1][jn] = *reinterpret_cast<const f32x4*>(smem + lbase[jn] + shift);
+                }
+                if (tap == 3) {
+                    fill_load(min(block + 1, blocks - 1));
+                    __builtin_amdgcn_sched_barrier(0);  // keep the loads here: the compiler would sink them to their use
+                }
+                f32x4 afr[FM];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) afr[i] = __builtin_bit_cast(f32x4, af[stage][i]);
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int jn = 0; jn < FN; ++jn)
+                            acc[i][jn] = __builtin_amdgcn_mfma_f32_16x16x4f32(afr[i][s4], bf[tap & 1][jn][s4], acc[i][jn], 0, 0, 0);
+                a_load(min(slice + 3, n_slices - 1), stage);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();                                // every wavefront is done with this block's patch
+        if (live && block + 1 < blocks) fill_store();
+        __syncthreads();
+    }
+    if (!live) return;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < FN; ++jn) {
+            const int cl = wn * WN + jn * 16 + r;
+            if (cl >= npx) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int m = m0 + wm * WM + i * 16 + 4 * g + q;
+                if (m < a.Cout) store_with_epilogue(a.y, a.ep, ((size_t)img * a.Cout + m) * HWo + p0 + cl, m, acc[i][jn][q], fout);
+            }
+        }
+}
+
+// W[Cout][Cin][3][3] -> [tap * (CinP / 16) + block][CoutP][16], the 16 channels of a block in the order
+// p = 4 (k % 4) + k / 4 (position p holds k = 4 (p % 4) + p / 4); zero where m >= Cout or the channel >= Cin
+__global__ __launch_bounds__(kBlock) void pack_c3_patch_weights_kernel(const float* w, float* wq, int Cout, int Cin, int CinP, int CoutP, long total) {
+    const long idx = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= total) return;
+    const int p = (int)(idx & 15);
+    const long row = idx >> 4;
+    const int m = (int)(row % CoutP), slice = (int)(row / CoutP);
+    const int kp = slice * 16 + 4 * (p & 3) + (p >> 2);
+    const int tap = kp / CinP, ci = kp - tap * CinP;
+    wq[idx] = (m < Cout && ci < Cin) ? w[((size_t)m * Cin + ci) * 9 + tap] : 0.f;
+}
+
 // W[Cout][Cin] -> W^T[CinP][CoutP], zero where k >= Cin or m >= Cout
 __global__ __launch_bounds__(kBlock) void pack_pw_lds_weights_kernel(const float* w, float* wp, int Cout, int Cin, int CoutP, long total) {
     const long idx = (long)blockIdx.x * kBlock + threadIdx.x;
@@ -1160,6 +1335,11 @@ NG_KERNEL(KID_C3_M3A, C3AddArgs, "conv3x3_mfma_3_add", conv3x3_k4_tile < 3, true
 NG_KERNEL(KID_C3_M4A, C3AddArgs, "conv3x3_mfma_4_add", conv3x3_k4_tile < 4, true)
 NG_KERNEL(KID_C3_L32, C3Args, "conv3x3_lds_32x128", conv3x3_lds_tile < 32, 128, 16)
 NG_KERNEL(KID_C3_L64, C3Args, "conv3x3_lds_64x64", conv3x3_lds_tile < 64, 64, 32)
+NG_KERNEL(KID_C3_P64, C3Args, "conv3x3_patch_64x64", conv3x3_patch_tile < 2, 2, 256)
+NG_KERNEL(KID_C3_P96, C3Args, "conv3x3_patch_96x64", conv3x3_patch_tile < 3, 2, 256)
+NG_KERNEL(KID_C3_Q32, C3Args, "conv3x3_patch_32x128_wide", conv3x3_patch_tile < 1, 4, 640)
+NG_KERNEL(KID_C3_Q64, C3Args, "conv3x3_patch_64x64_wide", conv3x3_patch_tile < 2, 2, 640)
+NG_KERNEL(KID_C3_Q128, C3Args, "conv3x3_patch_64x128_wide", conv3x3_patch_tile < 2, 4, 640)
 NG_KERNEL(KID_GEMM_PW_FWD, GemmArgs, "gemm_conv1x1_fwd", gemm_tile < GEMM_PW_FWD)
 NG_KERNEL(KID_GEMM_PW_DGRAD, GemmArgs, "gemm_conv1x1_dgrad", gemm_tile < GEMM_PW_DGRAD)
 NG_KERNEL(KID_GEMM_PW_WGRAD, GemmArgs, "gemm_conv1x1_wgrad", gemm_tile < GEMM_PW_WGRAD)
@@ -1204,6 +1384,7 @@ NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
     X(KID_PW_V1A) X(KID_PW_V2A) X(KID_PW_V3A) X(KID_PW_V4A) X(KID_PW_S1A) X(KID_PW_S2A)                                 \
     X(KID_PW_S3A) X(KID_PW_S4A) X(KID_C3_M1A) X(KID_C3_M2A) X(KID_C3_M3A) X(KID_C3_M4A)                                 \
     X(KID_POOL_A) X(KID_POOL_P4A) X(KID_C3_L32) X(KID_C3_L64)                                                          \
+    X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128)                                              \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
     X(KID_GEMM_C3_WGRAD) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD)
@@ -1211,7 +1392,7 @@ NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
 // Stand-alone kernel of one tile function: one workgroup per tile.
 template <int KID>
 __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KID>::Args a) {
-    __shared__ float smem[kSmemFloats];
+    __shared__ __align__(16) float smem[smem_floats(KID)];
     NoWait wait;
     KernelOf<KID>::template tile<false>(a, blockIdx.x, smem, threadIdx.x, true, wait);
 }
@@ -1223,7 +1404,7 @@ __global__ __launch_bounds__(kBlock) void standalone_kernel(typename KernelOf<KI
 // without what the command processor spends around a dispatch.
 template <int KID>
 __global__ __launch_bounds__(kBlock) void timed_kernel(typename KernelOf<KID>::Args a, unsigned long long* stamps) {
-    __shared__ float smem[kSmemFloats];
+    __shared__ __align__(16) float smem[smem_floats(KID)];
     unsigned long long t0 = 0;
     if (threadIdx.x == 0) t0 = wall_clock64();
     NoWait wait;
@@ -1392,12 +1573,13 @@ struct CounterWait {
 // replay kernel -, the train build has the lean kernels plus those of graphs that train.
 template <int BUILD>
 __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned epoch) {
-    __shared__ float smem_all[kSubs * kSmemFloats];
+    constexpr int kSmemPerSub = BUILD == BUILD_FULL ? kSmemFloatsWide : kSmemFloats;
+    __shared__ __align__(16) float smem_all[kSubs * kSmemPerSub];
     __shared__ uint4 recs[kRecordsInLds * (kRecordWords / 4)];
     __shared__ int s_abort, s_late;
     const int lane = threadIdx.x;
     const int sub = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kBlock), tid = (int)threadIdx.x % kBlock;
-    float* smem = smem_all + sub * kSmemFloats;
+    float* smem = smem_all + sub * kSmemPerSub;
     if (lane == 0) s_abort = 0;
     const int e_begin = plan.wg_first[blockIdx.x], e_end = plan.wg_first[blockIdx.x + 1];
     // The plan keeps tensors in XCD-private L2s on the assumption that workgroups with equal index mod 8
@@ -1559,7 +1741,8 @@ namespace {
 // Which conv1x1 kernel a node gets. Decided from shapes alone, so that the size of the
 // repacked weights is known before any memory is bound.
 struct PwChoice {
-    enum Kind { NONE, GEMV, LDS64, DIRECT32, K4_VEC, K4_WORD, C3_LDS } kind = NONE;
+    enum Kind { NONE, GEMV, LDS64, DIRECT32, K4_VEC, K4_WORD, C3_LDS, C3_PATCH } kind = NONE;
+    int kid = KID_NONE;       // C3_PATCH: which of the patch-stationary kernels
     int in_flight = 0;        // K4: groups of 4 k-steps in flight (1..4); DIRECT32: k-steps per chunk
     int groups = 0;           // K4: groups in the packed copy (a multiple of 4 * in_flight); DIRECT32: padded k-steps
     size_t packed = 0;        // floats of repacked weights
@@ -1609,13 +1792,52 @@ PwChoice choose_pw(const ng_graph* g, int v) {
 }
 // conv3x3 with at least 8 input channels runs as an implicit GEMM with K = 9 Cin
 constexpr long kC3LdsMinCols = 2048;      // measured: below this the 16 x 16 tiles (more workgroups, shorter K loops each) win
+// The patch-stationary kernels: rows and pixels of a tile, pixels the patch may have.
+struct PatchKernel { int kid, tm, tn, pm; };
+constexpr PatchKernel kPatchKernels[] = {{KID_C3_P64, 64, 64, 256}, {KID_C3_P96, 96, 64, 256}, {KID_C3_Q32, 32, 128, 640},
+                                         {KID_C3_Q64, 64, 64, 640}, {KID_C3_Q128, 64, 128, 640}};
+// Largest patch a run of tn consecutive output pixels can need: the rows it touches (a run can start at the end of a
+// row), stride apart, plus two, each W + 2 pad wide.
+long patch_pixels(long tn, long W, long Ho, long Wo, long stride, long pad) {
+    const long rows = std::min(Ho, (tn - 2) / Wo + 2);
+    return ((rows - 1) * stride + 3) * (W + 2 * pad);
+}
+// Which patch kernel a conv3x3 gets (KID_NONE: none fits). Decided from shapes: a workgroup's time goes with the rows of
+// its tile, a compute unit works its workgroups off side by side, so the estimate is (tiles per compute unit, rounded up)
+// x rows; one lone workgroup per compute unit cannot keep the matrix cores busy on its own (x 1.15).
+int choose_patch_kernel(const Shape& in, const Shape& out, long stride, long pad) {
+    if (in.c % 16 != 0 || in.n * in.c * in.h * in.w * 4 >= (1L << 31)) return KID_NONE;
+    int best = KID_NONE;
+    double best_cost = 0;
+    for (const PatchKernel& k : kPatchKernels) {
+        if (patch_pixels(k.tn, in.w, out.h, out.w, stride, pad) > k.pm) continue;
+        if ((k.tm == 32) != (out.c <= 32)) continue;                      // the 32-row kernel is for 32 output channels and fewer
+        const long tiles = out.n * ceil_div(out.h * out.w, k.tn) * ceil_div(out.c, k.tm);
+        const long rounds = ceil_div(tiles, 256);
+        double cost = (double)rounds * k.tm * (k.tn / 64) * (rounds == 1 ? 1.15 : 1.0) * (k.pm > 256 ? 1.08 : 1.0);
+        if (k.tn == 128) cost *= 0.92;                                    // the weights are fetched once for twice the pixels
+        if (best == KID_NONE || cost < best_cost) best = k.kid, best_cost = cost;
+    }
+    return best;
+}
 PwChoice choose_c3(const ng_graph* g, int v) {
     PwChoice c;
     const Node& nd = g->nodes[v];
     if (nd.op != NG_OP_CONV3X3) return c;
-    const long cin = g->nodes[nd.preds[0]].out.c;
+    const Shape& in = g->nodes[nd.preds[0]].out;
+    const long cin = in.c;
     if (cin < 8) return c;
-    // many columns: the LDS-staged kernel reads each patch element once per 64- or 128-column tile (no repacked weights)
+    // many output pixels: the patch-stationary kernels
+    if (nd.out.n * nd.out.h * nd.out.w >= kC3LdsMinCols) {
+        const int kid = choose_patch_kernel(in, nd.out, nd.p.stride, nd.p.pad);
+        for (const PatchKernel& k : kPatchKernels)
+            if (k.kid == kid) {
+                c.kind = PwChoice::C3_PATCH, c.kid = kid;
+                c.groups = (int)cin;                                                             // CinP = Cin (a multiple of 16)
+                c.packed = (size_t)(9 * cin) * (size_t)(ceil_div(nd.out.c, k.tm) * k.tm);        // [9 Cin / 16][CoutP][16]
+                return c;
+            }
+    }
     if (nd.out.n * nd.out.h * nd.out.w >= kC3LdsMinCols) {
         c.kind = PwChoice::C3_LDS;
         const long kc = nd.out.c <= 32 ? 16 : 32, tm = nd.out.c <= 32 ? 32 : 64;     // K slice and rows per tile of the two kernels
@@ -1713,7 +1935,10 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
     const int cin = (int)g->nodes[nd.preds[0]].out.c * (c3 ? 9 : 1), cout = (int)nd.out.c;
     if (!nd.weights[0]) return g->fail(NG_EINVAL, "node %d: weight 0 is a null device pointer", v);
     const dim3 grid((unsigned)((c.packed + kBlock - 1) / kBlock)), block(kBlock);
-    if (c.kind == PwChoice::LDS64)
+    if (c.kind == PwChoice::C3_PATCH)
+        pack_c3_patch_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const float*>(nd.weights[0]), packed, cout, cin / 9, c.groups, (int)(c.packed / (9 * (size_t)c.groups)), (long)c.packed);
+    else if (c.kind == PwChoice::LDS64)
         pack_pw_lds_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
             static_cast<const float*>(nd.weights[0]), packed, cout, cin, (int)(c.packed / (size_t)c.groups), (long)c.packed);
     else if (c.kind == PwChoice::C3_LDS)
@@ -1894,6 +2119,26 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 break;
             }
             const PwChoice c = choose_c3(g, v);
+            if (c.kind == PwChoice::C3_PATCH) {
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
+                a.wp = packed, a.groups = c.groups;
+                a.cols = (int)(o.n * o.h * o.w);
+                for (const PatchKernel& k : kPatchKernels) {
+                    if (k.kid != c.kid) continue;
+                    a.tiles_xy = (int)ceil_div(o.h * o.w, k.tn);          // runs of pixels per image
+                    a.tiles_n = (int)o.n * a.tiles_xy;
+                    a.co_groups = (int)ceil_div(a.Cout, k.tm);
+                }
+                const long n = (long)a.tiles_n * a.co_groups;
+                switch (c.kid) {
+                    case KID_C3_P64: set_kernel<KID_C3_P64>(t, a, n); break;
+                    case KID_C3_P96: set_kernel<KID_C3_P96>(t, a, n); break;
+                    case KID_C3_Q32: set_kernel<KID_C3_Q32>(t, a, n); break;
+                    case KID_C3_Q64: set_kernel<KID_C3_Q64>(t, a, n); break;
+                    default: set_kernel<KID_C3_Q128>(t, a, n); break;
+                }
+                break;
+            }
             if (c.kind == PwChoice::C3_LDS) {
                 if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
                 a.wp = packed, a.groups = c.groups;

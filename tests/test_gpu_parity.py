@@ -100,7 +100,10 @@ def test_pool_and_depthwise(shape):
                                          # enough 64 x 64 tiles for the LDS-tiled throughput kernel
                                          ((8, 64, 56, 56), (64,)),
                                          # ... ragged in every dimension (padded rows and columns of the repacked weights)
-                                         ((5, 37, 45, 47), (150,))])
+                                         ((5, 37, 45, 47), (150,)),
+                                         # both row-tile heights of the throughput kernel (64 up to 96 output channels, 128 above), K not a
+                                         # multiple of the slice, pixels per plane not a multiple of 4
+                                         ((6, 50, 53, 55), (96, 97)), ((32, 20, 35, 35), (300,))])
 def test_conv1x1_mfma(shape, couts):
     def build(b):
         x = b.input(*shape)
@@ -115,7 +118,9 @@ def test_conv1x1_mfma(shape, couts):
                                         # output channels, 64 x 64 above), ragged in every dimension, batch > 1
                                         ((1, 16, 70, 70), 24), ((1, 8, 131, 135), 72), ((3, 9, 40, 41), 33), ((1, 32, 65, 64), 32),
                                         # several K slices per tap with a ragged channel tail, in both kernels
-                                        ((1, 40, 46, 47), 70), ((2, 21, 33, 35), 20)])
+                                        ((1, 40, 46, 47), 70), ((2, 21, 33, 35), 20),
+                                        # the same kernels with many more tiles
+                                        ((2, 24, 97, 96), 40), ((1, 40, 130, 131), 130), ((9, 17, 61, 63), 97)])
 def test_conv3x3(shape, cout):
     def build(b):
         x = b.input(*shape)
@@ -123,6 +128,40 @@ def test_conv3x3(shape, cout):
             for pad in (0, 1):
                 b.conv3x3(x, cout, stride, pad)
     check_all_nodes(single_op(build), (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
+
+
+# The patch-stationary conv3x3 kernels (input channels a multiple of 16, 2048 output pixels and more). Each case names the
+# kernel its stride-1 / pad-1 convolution must get; with the other strides and paddings the same shapes reach further kernels
+# of the family (stride 2: patches with every second pixel used) and, below 2048 output pixels, the small-problem kernels.
+@pytest.mark.parametrize("shape,cout,kernel", [
+    # runs of 64 pixels that wrap over up to three rows, last run of an image partial, 70 of 128 rows used, 3 images
+    ((3, 16, 35, 37), 70, "conv3x3_patch_64x64"),
+    # three blocks of 16 channels, rows used up to 130 of 192
+    ((2, 48, 33, 35), 130, "conv3x3_patch_64x64"),
+    # 96-row tiles (two rounds of workgroups fewer than with 64-row tiles)
+    ((32, 16, 35, 35), 96, "conv3x3_patch_96x64"),
+    # patches of more than 256 pixels: wide rows, two blocks of channels; its stride-2 convolutions use them as well
+    ((4, 32, 49, 51), 100, "conv3x3_patch_64x64_wide"),
+    # 32 output channels and fewer: 32 x 128 tiles
+    ((2, 16, 70, 71), 24, "conv3x3_patch_32x128_wide"),
+    # many tiles: 64 x 128
+    ((4, 16, 150, 151), 64, "conv3x3_patch_64x128_wide"),
+    # 8 x 8 maps: a run of 64 pixels is a whole image
+    ((40, 32, 8, 8), 64, "conv3x3_patch_64x64")])
+def test_conv3x3_patch_kernels(shape, cout, kernel):
+    def build(b):
+        x = b.input(*shape)
+        b.conv3x3(x, cout, 1, 1)
+        for stride, pad in ((1, 0), (2, 0), (2, 1)):
+            b.conv3x3(x, cout, stride, pad)
+    w = single_op(build)
+    r = GraphRunner(w, DEV)
+    r.prepare()
+    try:
+        assert B.ng_task_kernel(r.g, 1) == kernel
+    finally:
+        r.close()
+    check_all_nodes(w, (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
 
 
 @pytest.mark.parametrize("n,cin,cout", [(1, 2048, 1000), (3, 100, 10), (8, 33, 5), (32, 2048, 1000), (9, 64, 7),
