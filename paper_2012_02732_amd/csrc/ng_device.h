@@ -28,6 +28,9 @@ enum Kid : int {
     // read it at shifted addresses; weights go from memory straight into matrix-instruction operands. Output tiles (rows x pixels)
     // 64 x 64 and 96 x 64 with a patch of up to 256 pixels; 32 x 128, 64 x 64 and 64 x 128 with up to 640 (wide images, stride 2)
     KID_C3_P64, KID_C3_P96, KID_C3_Q32, KID_C3_Q64, KID_C3_Q128,
+    // conv1x1 for many output pixels on the same plan (activations pixel-major in LDS, 32 or 64 channels at a time, weights
+    // straight from memory): 32 x 64 and 64 x 64 output tiles
+    KID_PW_P32, KID_PW_P64,
     // graphs that train (weights change between replays, so nothing is repacked): convolutions and fc, forward and backward,
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
     KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
@@ -55,11 +58,12 @@ constexpr bool is_pw16(int kid) { return plain_variant(kid) >= KID_PW_V1 && plai
 constexpr bool is_c3m(int kid) { return plain_variant(kid) >= KID_C3_M1 && plain_variant(kid) <= KID_C3_M4; }
 constexpr bool has_add_epilogue(int kid) { return plain_variant(kid) != kid; }
 constexpr bool is_c3_patch(int kid) { return kid >= KID_C3_P64 && kid <= KID_C3_Q128; }
+constexpr bool is_pw_patch(int kid) { return kid == KID_PW_P32 || kid == KID_PW_P64; }
 constexpr bool is_c3_lds(int kid) { return kid == KID_C3_L32 || kid == KID_C3_L64 || is_c3_patch(kid); }
 // convolutions whose argument block is a C3Args (the others with a batch-norm epilogue take a PwArgs)
 constexpr bool takes_c3_args(int kid) { return is_c3m(kid) || is_c3_lds(kid) || (kid >= KID_C3_T16S1 && kid <= KID_C3_T8S2); }
 // kernels whose tiles can apply a batch-norm / ReLU to their results before storing them: every convolution
-constexpr bool has_bn_epilogue(int kid) { return is_pw16(kid) || is_c3m(kid) || is_c3_lds(kid) || (kid >= KID_PW_D4 && kid <= KID_C3_T8S2); }
+constexpr bool has_bn_epilogue(int kid) { return is_pw16(kid) || is_c3m(kid) || is_c3_lds(kid) || is_pw_patch(kid) || (kid >= KID_PW_D4 && kid <= KID_C3_T8S2); }
 
 // How a kernel splits its output into tiles (see the elementwise tile functions): only tasks
 // with the same partition of same-shaped outputs have matching tiles.
@@ -83,13 +87,13 @@ constexpr int partition_of(int kid_any) {
 constexpr bool is_matrix_kernel(int kid_any) {
     const int kid = plain_variant(kid_any);
     return (kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || (kid >= KID_PW_V1 && kid <= KID_PW_S4) || (kid >= KID_C3_M1 && kid <= KID_C3_M4) ||
-           kid == KID_C3_L32 || kid == KID_C3_L64 || is_c3_patch(kid);
+           kid == KID_C3_L32 || kid == KID_C3_L64 || is_c3_patch(kid) || is_pw_patch(kid);
 }
 
 // kernels of the lean build of the resident kernel: everything except the 32 x 32 and LDS-tiled
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
-    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) &&
+    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) &&
            !is_train_kernel(kid);
 }
 // Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean
@@ -202,9 +206,10 @@ struct PwArgs {
     int Cin, Cout, HW, cols;   // cols = N * HW
     int tiles_n;               // tiles along the column (pixel) axis
     const float* wp;           // direct kernels: weights repacked into MFMA operand order
+                               // (kernels with the activations pixel-major in LDS: [Cin / 16][CoutP][16], see pack_pw_patch_weights_kernel)
     int ksteps;                // 32 x 32 kernels: k-steps of 4 in the packed copy (padded, a multiple of 4 * chunk);
                                // 16-row kernels: groups of 4 k-steps in the packed copy (a multiple of 4 * groups in flight)
-    int mtiles;                // direct kernels: ceil(Cout / 16)
+    int mtiles;                // direct kernels: ceil(Cout / 16); pixel-major kernels: tiles along Cout
     Epilogue ep;
 };
 struct PwAddArgs : PwArgs {

@@ -827,6 +827,144 @@ __global__ __launch_bounds__(kBlock) void pack_c3_patch_weights_kernel(const flo
     wq[idx] = (m < Cout && ci < Cin) ? w[((size_t)m * Cin + ci) * 9 + tap] : 0.f;
 }
 
+// ------------------------------------------------------------------------------------
+// conv1x1 / fc for many output pixels on the plan of the patch-stationary conv3x3: Y[Cout x cols] = W[Cout x Cin] X[Cin x cols],
+// tile = 32 FM output channels x 64 consecutive columns (a run may cross from one image into the next). KB blocks of 16
+// input channels of the tile's columns sit in LDS, pixel-major (16 KB + 4 floats per column, the 16 channels of a block in
+// the order the matrix instruction consumes them, so a lane's operands of four steps are one 128-bit read); the weights
+// ([Cin / 16][CoutP][16], same channel order) go from memory straight into operands, one chunk ahead. Per pair of barriers
+// a wavefront issues 8 KB FM matrix instructions. A thread fills one column's four-channel group per block: its global
+// offset is worked out once per tile (columns beyond the end: an offset for which the buffer load returns 0).
+// Four wavefronts as 2 x 2, each 16 FM x 32. Needs Cin % 16 == 0.
+// ------------------------------------------------------------------------------------
+template <int FM, int KB, bool FIN, class Wait>
+__device__ __forceinline__ void conv1x1_patch_tile(const PwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();
+    constexpr int FN = 2, WM = 16 * FM, WN = 16 * FN, TM = 2 * WM, TN = 2 * WN, LD = 16 * KB + 4;
+    constexpr unsigned kOutside = 0x80000000u;          // beyond any tensor (num_records < 2^31): the load returns 0
+    constexpr int kIn = FIN ? kPolicyDeviceScope : 0;
+    static_assert(TN * LD <= kSmemFloats && TN * 4 == kBlock, "LDS budget; one fill item per thread");
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1, r = lane & 15, g = lane >> 4;
+    const int by = tile % a.mtiles, bx = tile / a.mtiles;
+    const int m0 = by * TM, n0 = bx * TN;
+    const int blocks = a.ksteps / 16, chunks = (blocks + KB - 1) / KB, CoutP = a.mtiles * TM;
+    const __amdgpu_buffer_rsrc_t xr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.x), 0, a.cols * a.Cin * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wr = __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(a.wp), 0, blocks * CoutP * 64, 0x00020000);
+    // this thread's fill item: column c of the tile, channels j, j + 4, j + 8, j + 12 of every block
+    unsigned goff;
+    {
+        const int c = tid % TN, j = tid / TN;
+        const int col = n0 + c;
+        const int img = col / a.HW, pix = col - img * a.HW;
+        goff = (live && col < a.cols) ? (unsigned)(((img * a.Cin + j) * a.HW + pix) * 4) : kOutside;
+    }
+    const int loff = (tid % TN) * (LD / 4) + tid / TN;   // in units of 4 floats
+    int lbase[FN];
+#pragma unroll
+    for (int jn = 0; jn < FN; ++jn) lbase[jn] = (wn * WN + jn * 16 + r) * LD + 4 * g;
+    const unsigned va_off = (unsigned)(((wm * WM + r) * 16 + 4 * g) * 4);
+
+    f32x4 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < FN; ++jn) acc[i][jn] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    u32x4 pv[KB];
+    // loads are issued unconditionally and in a fixed order (blocks beyond Cin read "outside"): the compiler then counts
+    // exactly how many younger loads may stay in flight at each wait
+    auto fill_load = [&](int chunk) {
+#pragma unroll
+        for (int b = 0; b < KB; ++b) {
+            const int block = chunk * KB + b;
+            const unsigned off = block < blocks ? goff : kOutside;
+            u32x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) v[q] = __builtin_amdgcn_raw_buffer_load_b32(xr, off, (unsigned)((block * 16 + 4 * q) * a.HW * 4), kIn);
+            pv[b] = v;
+        }
+    };
+    auto fill_store = [&]() {
+#pragma unroll
+        for (int b = 0; b < KB; ++b) reinterpret_cast<u32x4*>(smem)[loff + 4 * b] = pv[b];
+    };
+    u32x4 af[KB][FM];
+    auto a_load = [&](int slice, int stage) {           // a slice beyond Cin re-reads the last one: its activations are zeros
+        const unsigned so = (unsigned)((min(slice, blocks - 1) * CoutP + m0) * 64);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) af[stage][i] = __builtin_amdgcn_raw_buffer_load_b128(wr, va_off + i * 1024, so, 0);
+    };
+
+    wait();
+    if (live) {
+        fill_load(0);
+#pragma unroll
+        for (int b = 0; b < KB; ++b) a_load(b, b);
+        fill_store();
+    }
+    __syncthreads();
+    for (int chunk = 0; chunk < chunks; ++chunk) {
+        if (live) {
+            f32x4 bf[2][FN];
+#pragma unroll
+            for (int jn = 0; jn < FN; ++jn) bf[0][jn] = *reinterpret_cast<const f32x4*>(smem + lbase[jn]);
+#pragma unroll
+            for (int b = 0; b < KB; ++b) {
+                if (b + 1 < KB) {
+#pragma unroll
+                    for (int jn = 0; jn < FN; ++jn) bf[(b + 1) & 1][jn] = *reinterpret_cast<const f32x4*>(smem + lbase[jn] + 16 * (b + 1));
+                }
+                if (b == 0) {
+                    fill_load(min(chunk + 1, chunks - 1));
+                    __builtin_amdgcn_sched_barrier(0);  // keep the loads here: the compiler would sink them to their use
+                }
+                f32x4 afr[FM];
+#pragma unroll
+                for (int i = 0; i < FM; ++i) afr[i] = __builtin_bit_cast(f32x4, af[b][i]);
+#pragma unroll
+                for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+                    for (int i = 0; i < FM; ++i)
+#pragma unroll
+                        for (int jn = 0; jn < FN; ++jn)
+                            acc[i][jn] = __builtin_amdgcn_mfma_f32_16x16x4f32(afr[i][s4], bf[b & 1][jn][s4], acc[i][jn], 0, 0, 0);
+                a_load((chunk + 1) * KB + b, b);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        __syncthreads();                                // every wavefront is done with this chunk
+        if (live && chunk + 1 < chunks) fill_store();
+        __syncthreads();
+    }
+    if (!live) return;
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int jn = 0; jn < FN; ++jn) {
+            const int col = n0 + wn * WN + jn * 16 + r;
+            if (col >= a.cols) continue;
+            const int img = col / a.HW, pix = col - img * a.HW;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int m = m0 + wm * WM + i * 16 + 4 * g + q;
+                if (m < a.Cout)
+                    store_with_epilogue(a.y, a.ep, ((size_t)img * a.Cout + m) * a.HW + pix, m, acc[i][jn][q] + (a.bias ? a.bias[m] : 0.f), fout);
+            }
+        }
+}
+
+// W[Cout][Cin] -> [Cin / 16][CoutP][16], the 16 channels of a block in the order p = 4 (k % 4) + k / 4; zero where m >= Cout
+__global__ __launch_bounds__(kBlock) void pack_pw_patch_weights_kernel(const float* w, float* wq, int Cout, int Cin, int CoutP, long total) {
+    const long idx = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= total) return;
+    const int p = (int)(idx & 15);
+    const long row = idx >> 4;
+    const int m = (int)(row % CoutP), block = (int)(row / CoutP);
+    const int k = block * 16 + 4 * (p & 3) + (p >> 2);
+    wq[idx] = (m < Cout && k < Cin) ? w[(size_t)m * Cin + k] : 0.f;
+}
+
 // W[Cout][Cin] -> W^T[CinP][CoutP], zero where k >= Cin or m >= Cout
 __global__ __launch_bounds__(kBlock) void pack_pw_lds_weights_kernel(const float* w, float* wp, int Cout, int Cin, int CoutP, long total) {
     const long idx = (long)blockIdx.x * kBlock + threadIdx.x;
@@ -1335,6 +1473,8 @@ NG_KERNEL(KID_C3_M3A, C3AddArgs, "conv3x3_mfma_3_add", conv3x3_k4_tile < 3, true
 NG_KERNEL(KID_C3_M4A, C3AddArgs, "conv3x3_mfma_4_add", conv3x3_k4_tile < 4, true)
 NG_KERNEL(KID_C3_L32, C3Args, "conv3x3_lds_32x128", conv3x3_lds_tile < 32, 128, 16)
 NG_KERNEL(KID_C3_L64, C3Args, "conv3x3_lds_64x64", conv3x3_lds_tile < 64, 64, 32)
+NG_KERNEL(KID_PW_P32, PwArgs, "conv1x1_patch_32x64", conv1x1_patch_tile < 1, 4)
+NG_KERNEL(KID_PW_P64, PwArgs, "conv1x1_patch_64x64", conv1x1_patch_tile < 2, 2)
 NG_KERNEL(KID_C3_P64, C3Args, "conv3x3_patch_64x64", conv3x3_patch_tile < 2, 2, 256)
 NG_KERNEL(KID_C3_P96, C3Args, "conv3x3_patch_96x64", conv3x3_patch_tile < 3, 2, 256)
 NG_KERNEL(KID_C3_Q32, C3Args, "conv3x3_patch_32x128_wide", conv3x3_patch_tile < 1, 4, 640)
@@ -1384,10 +1524,19 @@ NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
     X(KID_PW_V1A) X(KID_PW_V2A) X(KID_PW_V3A) X(KID_PW_V4A) X(KID_PW_S1A) X(KID_PW_S2A)                                 \
     X(KID_PW_S3A) X(KID_PW_S4A) X(KID_C3_M1A) X(KID_C3_M2A) X(KID_C3_M3A) X(KID_C3_M4A)                                 \
     X(KID_POOL_A) X(KID_POOL_P4A) X(KID_C3_L32) X(KID_C3_L64)                                                          \
-    X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128)                                              \
+    X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
     X(KID_GEMM_C3_WGRAD) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD)
+
+// A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
+// different offsets): the predicates that name the type must agree with the type the kernel takes.
+#define NG_CHECK_ARGS(KID)                                                                                              \
+    static_assert(!has_bn_epilogue(KID) || (takes_c3_args(KID) ? std::is_base_of<C3Args, KernelOf<KID>::Args>::value    \
+                                                               : std::is_base_of<PwArgs, KernelOf<KID>::Args>::value),  \
+                  "takes_c3_args / has_bn_epilogue disagree with the kernel's argument type");
+NG_FOR_EACH_KID(NG_CHECK_ARGS)
+#undef NG_CHECK_ARGS
 
 // Stand-alone kernel of one tile function: one workgroup per tile.
 template <int KID>
@@ -1741,8 +1890,8 @@ namespace {
 // Which conv1x1 kernel a node gets. Decided from shapes alone, so that the size of the
 // repacked weights is known before any memory is bound.
 struct PwChoice {
-    enum Kind { NONE, GEMV, LDS64, DIRECT32, K4_VEC, K4_WORD, C3_LDS, C3_PATCH } kind = NONE;
-    int kid = KID_NONE;       // C3_PATCH: which of the patch-stationary kernels
+    enum Kind { NONE, GEMV, LDS64, DIRECT32, K4_VEC, K4_WORD, C3_LDS, C3_PATCH, PW_PATCH } kind = NONE;
+    int kid = KID_NONE;       // C3_PATCH, PW_PATCH: which of the kernels
     int in_flight = 0;        // K4: groups of 4 k-steps in flight (1..4); DIRECT32: k-steps per chunk
     int groups = 0;           // K4: groups in the packed copy (a multiple of 4 * in_flight); DIRECT32: padded k-steps
     size_t packed = 0;        // floats of repacked weights
@@ -1762,6 +1911,7 @@ void k4_split(long k_total, long cout, PwChoice& c) {
     c.groups = (int)(4 * gw);
     c.packed = (size_t)((cout + 15) / 16) * c.groups * 256;
 }
+constexpr long kPwPatchMinCols = 2048;
 PwChoice choose_pw(const ng_graph* g, int v) {
     PwChoice c;
     const Node& nd = g->nodes[v];
@@ -1770,6 +1920,17 @@ PwChoice choose_pw(const ng_graph* g, int v) {
     const long cin = g->nodes[nd.preds[0]].out.c;
     const long hw = o.h * o.w, cols = o.n * hw;
     if (nd.op == NG_OP_FC && o.n <= 8) { c.kind = PwChoice::GEMV; return c; }
+    // many output pixels, whole blocks of 16 input channels: activations pixel-major in LDS, weights straight from memory;
+    // 64-row tiles unless that leaves most compute units without one
+    const long tiles64 = ((o.c + 63) / 64) * ((cols + 63) / 64);
+    if (cols >= kPwPatchMinCols && cin % 16 == 0 && cin >= 64 && tiles64 >= 64 && cols * cin * 4 < (1L << 31)) {
+        c.kind = PwChoice::PW_PATCH;
+        c.kid = tiles64 < 200 ? KID_PW_P32 : KID_PW_P64;
+        const long tm = c.kid == KID_PW_P32 ? 32 : 64;
+        c.groups = (int)cin;
+        c.packed = (size_t)cin * (size_t)((o.c + tm - 1) / tm * tm);       // [Cin / 16][CoutP][16]
+        return c;
+    }
     // large problems (many 64 x 64 tiles) keep the LDS-tiled throughput kernel
     if (((o.c + 63) / 64) * ((cols + 63) / 64) >= 256) {
         c.kind = PwChoice::LDS64;
@@ -1935,7 +2096,10 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
     const int cin = (int)g->nodes[nd.preds[0]].out.c * (c3 ? 9 : 1), cout = (int)nd.out.c;
     if (!nd.weights[0]) return g->fail(NG_EINVAL, "node %d: weight 0 is a null device pointer", v);
     const dim3 grid((unsigned)((c.packed + kBlock - 1) / kBlock)), block(kBlock);
-    if (c.kind == PwChoice::C3_PATCH)
+    if (c.kind == PwChoice::PW_PATCH)
+        pack_pw_patch_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
+            static_cast<const float*>(nd.weights[0]), packed, cout, cin, (int)(c.packed / (size_t)c.groups), (long)c.packed);
+    else if (c.kind == PwChoice::C3_PATCH)
         pack_c3_patch_weights_kernel<<<grid, block, 0, static_cast<hipStream_t>(stream)>>>(
             static_cast<const float*>(nd.weights[0]), packed, cout, cin / 9, c.groups, (int)(c.packed / (9 * (size_t)c.groups)), (long)c.packed);
     else if (c.kind == PwChoice::LDS64)
@@ -2069,6 +2233,15 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             PwArgs a{};
             a.x = buf(nd.preds[0]), a.w = wf(0), a.bias = fc ? wf(1) : nullptr, a.y = buf(v);
             a.Cin = (int)i0.c, a.Cout = (int)o.c, a.HW = hw_out, a.cols = (int)(o.n * hw_out);
+            if (c.kind == PwChoice::PW_PATCH) {
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
+                a.wp = packed, a.ksteps = c.groups;
+                a.tiles_n = (int)ceil_div(a.cols, 64);
+                a.mtiles = (int)ceil_div(a.Cout, c.kid == KID_PW_P32 ? 32 : 64);
+                if (c.kid == KID_PW_P32) set_kernel<KID_PW_P32>(t, a, (long)a.tiles_n * a.mtiles);
+                else set_kernel<KID_PW_P64>(t, a, (long)a.tiles_n * a.mtiles);
+                break;
+            }
             if (c.kind == PwChoice::LDS64) {
                 if (!packed) return g->fail(NG_EINVAL, "node %d: no buffer for repacked weights", v);
                 a.wp = packed, a.ksteps = c.groups;

@@ -73,6 +73,8 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
         case KID_FC_GEMV: base = 1.0 + 0.001 * cin * (double)nd.out.n, per_tile = 0.2; break;
         case KID_PW_D4: case KID_PW_D8: case KID_PW_D16: base = 1.3, per_tile = 0.4 + 0.008 * cin; break;
         case KID_PW_64: base = 1.5, per_tile = 0.025 * cin; break;
+        case KID_PW_P64: base = 1.5, per_tile = 0.02 * cin; break;
+        case KID_PW_P32: base = 1.5, per_tile = 0.012 * cin; break;
         case KID_PW_V1: case KID_PW_V2: case KID_PW_V3: case KID_PW_V4: {
             const PwArgs* a = reinterpret_cast<const PwArgs*>(g->tasks[v].args);
             base = 1.3, per_tile = 0.3 * (a->ksteps / 4);           // per group of 4 k-steps and wavefront: 5 128-bit loads, 16 MFMAs

@@ -97,19 +97,23 @@ def test_pool_and_depthwise(shape):
                                          ((1, 88, 14, 14), (88,)), ((1, 512, 8, 8), (40,)), ((2, 176, 4, 4), (30,)),
                                          ((1, 528, 7, 7), (176,)), ((1, 176, 7, 7), (176,)), ((1, 256, 7, 7), (17,)),
                                          ((1, 100, 5, 5), (33,)), ((1, 20, 3, 5), (16,)),
-                                         # enough 64 x 64 tiles for the LDS-tiled throughput kernel
+                                         # enough 64 x 64 tiles for the throughput kernels: input channels a multiple of 16 ...
                                          ((8, 64, 56, 56), (64,)),
-                                         # ... ragged in every dimension (padded rows and columns of the repacked weights)
+                                         # ... and not (the LDS-tiled kernel), ragged in every dimension (padded rows and columns of
+                                         # the repacked weights)
                                          ((5, 37, 45, 47), (150,)),
-                                         # both row-tile heights of the throughput kernel (64 up to 96 output channels, 128 above), K not a
-                                         # multiple of the slice, pixels per plane not a multiple of 4
-                                         ((6, 50, 53, 55), (96, 97)), ((32, 20, 35, 35), (300,))])
+                                         # 2048 columns and more, whole blocks of 16 input channels: the kernels with the activations
+                                         # pixel-major in LDS. 32-row tiles (few tiles), 5 and 6 blocks (last chunk of 4 partial), rows
+                                         # and columns ragged, runs that cross image boundaries
+                                         ((32, 64, 8, 8), (192, 100)), ((8, 80, 17, 19), (70,)), ((6, 96, 23, 25), (130,)),
+                                         # 64-row tiles (200 tiles and more), 5 blocks (last chunk of 2 partial)
+                                         ((4, 80, 56, 57), (64, 150))])
 def test_conv1x1_mfma(shape, couts):
     def build(b):
         x = b.input(*shape)
         for c in couts:
             b.conv1x1(x, c)
-    check_all_nodes(single_op(build))
+    check_all_nodes(single_op(build), (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
 
 
 @pytest.mark.parametrize("shape,cout", [((1, 32, 32, 32), 32), ((1, 3, 37, 41), 44), ((2, 5, 9, 9), 7),
@@ -165,7 +169,8 @@ def test_conv3x3_patch_kernels(shape, cout, kernel):
 
 
 @pytest.mark.parametrize("n,cin,cout", [(1, 2048, 1000), (3, 100, 10), (8, 33, 5), (32, 2048, 1000), (9, 64, 7),
-                                        (1024, 70, 1000)])     # a batch large enough for the LDS-tiled kernel, with a bias
+                                        (1024, 70, 1000),      # a batch large enough for the LDS-tiled kernel, with a bias
+                                        (2048, 64, 100)])      # ... and for the kernel with the activations pixel-major in LDS
 def test_fc(n, cin, cout):
     def build(b):
         x = b.input(n, cin, 1, 1)
