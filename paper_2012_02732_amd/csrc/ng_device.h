@@ -34,6 +34,7 @@ enum Kid : int {
     // graphs that train (weights change between replays, so nothing is repacked): convolutions and fc, forward and backward,
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
     KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
+    KID_PW_WGRAD_PX,                 // conv1x1 weight gradient with both operands read along the pixels, 128 bits at a time (HW % 16 == 0)
     KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_GAP_DGRAD,
     KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,
     KID_COUNT
@@ -258,6 +259,9 @@ struct GemmArgs {
     int Cin, Cout, H, W, Ho, Wo, stride, pad;
     int tiles_n;               // tiles along N
     int splits, k_per_split;   // k_per_split a multiple of the K slice
+    // conv1x1_wgrad_px: the partial tiles are added up in a tree with a fan-in of 4; ws = partial tiles
+    // [tiles][splits][64 * 64], then per level l >= 1 the sums [tiles][ceil(splits / 4^l)][64 * 64] down to two nodes;
+    // cnt = arrivals per node, per level from level 1 on, [tiles][ceil(splits / 4^l)]
 };
 struct BnRawArgs {             // batch-norm with its four parameter vectors as they are (they change when the graph trains)
     const float* x;            // forward input

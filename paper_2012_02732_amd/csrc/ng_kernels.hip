@@ -1510,6 +1510,7 @@ NG_KERNEL0(KID_DW_DGRAD, DwGradArgs, "dwconv_dgrad", dw_dgrad_tile)
 NG_KERNEL0(KID_DW_WGRAD, DwGradArgs, "dwconv_wgrad", dw_wgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD, PoolGradArgs, "pool3x3_dgrad", pool_dgrad_tile)
 NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
+NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
 #undef NG_KERNEL0
 
 // every kernel id that has a tile function
@@ -1526,7 +1527,7 @@ NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
     X(KID_POOL_A) X(KID_POOL_P4A) X(KID_C3_L32) X(KID_C3_L64)                                                          \
     X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
-    X(KID_GEMM_C3_WGRAD) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
+    X(KID_GEMM_C3_WGRAD) X(KID_PW_WGRAD_PX) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
@@ -1923,7 +1924,7 @@ PwChoice choose_pw(const ng_graph* g, int v) {
     // many output pixels, whole blocks of 16 input channels: activations pixel-major in LDS, weights straight from memory;
     // 64-row tiles unless that leaves most compute units without one
     const long tiles64 = ((o.c + 63) / 64) * ((cols + 63) / 64);
-    if (cols >= kPwPatchMinCols && cin % 16 == 0 && cin >= 64 && tiles64 >= 64 && cols * cin * 4 < (1L << 31)) {
+    if (cols >= kPwPatchMinCols && cin % 16 == 0 && cin >= 64 && tiles64 >= 64 && cols * cin * 4 < (1L << 31) && !knob("NG_NO_PATCH_KERNELS")) {
         c.kind = PwChoice::PW_PATCH;
         c.kid = tiles64 < 200 ? KID_PW_P32 : KID_PW_P64;
         const long tm = c.kid == KID_PW_P32 ? 32 : 64;
@@ -1989,7 +1990,7 @@ PwChoice choose_c3(const ng_graph* g, int v) {
     const long cin = in.c;
     if (cin < 8) return c;
     // many output pixels: the patch-stationary kernels
-    if (nd.out.n * nd.out.h * nd.out.w >= kC3LdsMinCols) {
+    if (nd.out.n * nd.out.h * nd.out.w >= kC3LdsMinCols && !knob("NG_NO_PATCH_KERNELS")) {
         const int kid = choose_patch_kernel(in, nd.out, nd.p.stride, nd.p.pad);
         for (const PatchKernel& k : kPatchKernels)
             if (k.kid == kid) {
@@ -2036,16 +2037,52 @@ bool wgrad_dims(const ng_graph* g, int v, long* m, long* n, long* k) {
     *m = dy.c, *n = x.c * (nd.op == NG_OP_CONV3X3_WGRAD ? 9 : 1), *k = dy.n * dy.h * dy.w;
     return true;
 }
+// How a weight-gradient node is computed: which kernel, how K is split, what workspace it needs.
+struct WgradPlan {
+    bool px = false;              // conv1x1_wgrad_px (both operands 128 bits along the pixels) instead of the gather GEMM
+    long tiles = 0;
+    int splits = 1, k_per_split = 0;
+    size_t ws_floats = 0;         // partial tiles (and group sums)
+    size_t cnt_words = 0;         // arrival counters behind them, a multiple of 64
+};
+WgradPlan wgrad_plan(const ng_graph* g, int v) {
+    WgradPlan p;
+    long m, n, k;
+    if (!wgrad_dims(g, v, &m, &n, &k)) return p;
+    const Node& nd = g->nodes[v];
+    const Shape& dy = g->nodes[nd.preds[0]].out;
+    const Shape& x = g->nodes[nd.preds[1]].out;
+    p.tiles = ceil_div(m, kGemmTile) * ceil_div(n, kGemmTile);
+    const size_t tile_floats = (size_t)kGemmTile * kGemmTile;
+    p.px = nd.op == NG_OP_CONV1X1_WGRAD && (dy.h * dy.w) % 16 == 0 && dy.elems() * 4 < (1L << 31) && x.elems() * 4 < (1L << 31);
+    if (p.px) {
+        // one workgroup per split, four wavefronts each, a wavefront wants two slices of 16 pixels at least; about one
+        // workgroup per compute unit over all tiles
+        const long want = std::max<long>(1, std::min<long>(ceil_div(k, 128), std::max<long>(1, 256 / p.tiles)));
+        p.k_per_split = (int)(ceil_div(ceil_div(k, want), 64) * 64);
+        p.splits = (int)ceil_div(k, p.k_per_split);
+        // the tree of sums (fan-in 4): tiles of every level but the root, one counter per node from level 1 on
+        size_t nodes = 0, counters = 0;
+        for (long width = p.splits; width > 1; width = ceil_div(width, 4)) nodes += (size_t)width, counters += (size_t)ceil_div(width, 4);
+        p.ws_floats = (size_t)p.tiles * nodes * tile_floats;
+        p.cnt_words = ((size_t)p.tiles * counters + 63) & ~(size_t)63;
+        return p;
+    }
+    gemm_split(m, n, k, &p.splits, &p.k_per_split);
+    if (p.splits > 1) {
+        p.ws_floats = (size_t)p.tiles * p.splits * tile_floats;
+        p.cnt_words = ((size_t)p.tiles + 63) & ~(size_t)63;
+    }
+    return p;
+}
 }  // namespace
 
 size_t packed_floats(const ng_graph* g, int v) {
     const Node& nd = g->nodes[v];
     long wm, wn, wk;
-    if (wgrad_dims(g, v, &wm, &wn, &wk)) {                     // split-K workspace: partial tiles, then one arrival counter per tile
-        int splits, per;
-        gemm_split(wm, wn, wk, &splits, &per);
-        const size_t tiles = (size_t)(ceil_div(wm, kGemmTile) * ceil_div(wn, kGemmTile));
-        return splits > 1 ? tiles * splits * kGemmTile * kGemmTile + ((tiles + 63) & ~(size_t)63) : 0;
+    if (wgrad_dims(g, v, &wm, &wn, &wk)) {                     // split-K workspace: partial tiles, then the arrival counters
+        const WgradPlan p = wgrad_plan(g, v);
+        return p.ws_floats + p.cnt_words;
     }
     if (nd.op == NG_OP_DWCONV_WGRAD) {                         // per-image partial sums [C][N][K K], then one arrival counter per channel
         const Shape& x = g->nodes[nd.preds[1]].out;
@@ -2062,10 +2099,9 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
     const Node& nd = g->nodes[v];
     long wm, wn, wk;
     if (wgrad_dims(g, v, &wm, &wn, &wk)) {                     // the arrival counters start at zero
-        const size_t floats = packed_floats(g, v);
-        if (floats == 0) return NG_OK;
-        const size_t tiles = (size_t)(ceil_div(wm, kGemmTile) * ceil_div(wn, kGemmTile)), cnt = (tiles + 63) & ~(size_t)63;
-        const hipError_t e = hipMemsetAsync(packed + floats - cnt, 0, cnt * sizeof(float), static_cast<hipStream_t>(stream));
+        const WgradPlan p = wgrad_plan(g, v);
+        if (p.cnt_words == 0) return NG_OK;
+        const hipError_t e = hipMemsetAsync(packed + p.ws_floats, 0, p.cnt_words * sizeof(float), static_cast<hipStream_t>(stream));
         if (e != hipSuccess) return g->fail(NG_EHIP, "clearing split-K counters: %s", hipGetErrorString(e));
         return NG_OK;
     }
@@ -2375,14 +2411,17 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.stride = c3 ? nd.p.stride : 1, a.pad = c3 ? nd.p.pad : 0;
             a.M = a.Cout, a.N = a.Cin * (c3 ? 9 : 1), a.K = (int)(dy.n * dy.h * dy.w);
             a.tiles_n = (int)ceil_div(a.N, kGemmTile);
-            gemm_split(a.M, a.N, a.K, &a.splits, &a.k_per_split);
-            const long tiles = (long)a.tiles_n * ceil_div(a.M, kGemmTile);
+            const WgradPlan p = wgrad_plan(g, v);
+            a.splits = p.splits, a.k_per_split = p.k_per_split;
+            const long tiles = p.tiles;
             if (a.splits > 1) {
                 if (!packed) return g->fail(NG_EINVAL, "node %d: no workspace for the split-K partial tiles", v);
                 a.ws = packed;
-                a.cnt = reinterpret_cast<unsigned*>(packed + (size_t)tiles * a.splits * kGemmTile * kGemmTile);
+                a.cnt = reinterpret_cast<unsigned*>(packed + p.ws_floats);
             }
-            if (c3) set_kernel<KID_GEMM_C3_WGRAD>(t, a, tiles * a.splits); else set_kernel<KID_GEMM_PW_WGRAD>(t, a, tiles * a.splits);
+            if (p.px) set_kernel<KID_PW_WGRAD_PX>(t, a, tiles * a.splits);
+            else if (c3) set_kernel<KID_GEMM_C3_WGRAD>(t, a, tiles * a.splits);
+            else set_kernel<KID_GEMM_PW_WGRAD>(t, a, tiles * a.splits);
             break;
         }
         case NG_OP_BN_ACT_DGRAD:
