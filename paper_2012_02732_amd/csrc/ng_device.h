@@ -270,6 +270,9 @@ struct BnRawArgs {             // batch-norm with its four parameter vectors as 
     const float* gamma; const float* beta; const float* mean; const float* var;
     float eps;
     int relu, C, HW, N, total;
+    float* ws;                 // wgrad, chunks > 1: per-chunk sums [C][chunks][2]
+    unsigned* cnt;             // wgrad, chunks > 1: arrivals per channel, zero between replays
+    int chunks;                // wgrad: workgroups a channel's images are split over
 };
 struct EltGradArgs {           // relu / global-avgpool / slice-pad / channel-sum: small elementwise backward operators
     const float* dy;
@@ -283,8 +286,9 @@ struct DwGradArgs {            // depthwise backward; C, H, W, Ho, Wo, K, S of t
     const float* dy; const float* x; const float* w;
     float* y;                  // dgrad: dx [N][C][H][W]; wgrad: dW [C][K][K]
     int N, C, H, W, Ho, Wo, K, S, total;
-    float* ws;                 // wgrad, N > 1: per-image partial sums [C][N][K K]
-    unsigned* cnt;             // wgrad, N > 1: arrivals per channel, zero between replays
+    float* ws;                 // wgrad, chunks > 1: per-chunk partial sums [C][chunks][K K]
+    unsigned* cnt;             // wgrad, chunks > 1: arrivals per channel, zero between replays
+    int chunks;                // wgrad: workgroups a channel's images are split over
 };
 struct PoolGradArgs {          // pool backward; geometry of the FORWARD operator
     const float* dy; const float* x;

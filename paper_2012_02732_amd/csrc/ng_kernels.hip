@@ -2037,6 +2037,11 @@ bool wgrad_dims(const ng_graph* g, int v, long* m, long* n, long* k) {
     *m = dy.c, *n = x.c * (nd.op == NG_OP_CONV3X3_WGRAD ? 9 : 1), *k = dy.n * dy.h * dy.w;
     return true;
 }
+// Workgroups a channel of a batch-norm or depthwise parameter gradient is split over (by images): about 512 workgroups in all
+long bn_wgrad_chunks(long channels, long images) {
+    const long want = std::max<long>(1, std::min<long>(images, ceil_div(512, channels)));
+    return ceil_div(images, ceil_div(images, want));            // no empty chunk
+}
 // How a weight-gradient node is computed: which kernel, how K is split, what workspace it needs.
 struct WgradPlan {
     bool px = false;              // conv1x1_wgrad_px (both operands 128 bits along the pixels) instead of the gather GEMM
@@ -2084,9 +2089,15 @@ size_t packed_floats(const ng_graph* g, int v) {
         const WgradPlan p = wgrad_plan(g, v);
         return p.ws_floats + p.cnt_words;
     }
-    if (nd.op == NG_OP_DWCONV_WGRAD) {                         // per-image partial sums [C][N][K K], then one arrival counter per channel
+    if (nd.op == NG_OP_DWCONV_WGRAD) {                         // per-chunk partial sums [C][chunks][K K] (padded), then one arrival counter per channel
         const Shape& x = g->nodes[nd.preds[1]].out;
-        return x.n > 1 ? (size_t)x.c * x.n * nd.p.k * nd.p.k + (size_t)((x.c + 63) & ~63L) : 0;
+        const long chunks = bn_wgrad_chunks(x.c, x.n);
+        return chunks > 1 ? (size_t)((x.c * chunks * nd.p.k * nd.p.k + 63) & ~63L) + (size_t)((x.c + 63) & ~63L) : 0;
+    }
+    if (nd.op == NG_OP_BN_ACT_WGRAD) {                         // per-chunk sums [C][chunks][2] (padded), then one arrival counter per channel
+        const Shape& x = g->nodes[nd.preds[1]].out;
+        const long chunks = bn_wgrad_chunks(x.c, x.n);
+        return chunks > 1 ? (size_t)((x.c * chunks * 2 + 63) & ~63L) + (size_t)((x.c + 63) & ~63L) : 0;
     }
     if (g->trainable) return 0;                                // weights change between replays: nothing is folded or repacked
     if (nd.op == NG_OP_BN_ACT) return 2 * (size_t)((nd.out.c + 3) & ~3L);   // folded scale, shift
@@ -2105,7 +2116,7 @@ int pack_constants(ng_graph* g, int v, float* packed, void* stream) {
         if (e != hipSuccess) return g->fail(NG_EHIP, "clearing split-K counters: %s", hipGetErrorString(e));
         return NG_OK;
     }
-    if (nd.op == NG_OP_DWCONV_WGRAD) {
+    if (nd.op == NG_OP_DWCONV_WGRAD || nd.op == NG_OP_BN_ACT_WGRAD) {
         const size_t floats = packed_floats(g, v);
         if (floats == 0) return NG_OK;
         const size_t cnt = (size_t)((g->nodes[nd.preds[1]].out.c + 63) & ~63L);
@@ -2432,8 +2443,17 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.gamma = wf(0), a.beta = wf(1), a.mean = wf(2), a.var = wf(3);
             a.eps = nd.p.eps, a.relu = nd.p.relu != 0;
             a.C = (int)x.c, a.HW = (int)(x.h * x.w), a.N = (int)x.n, a.total = (int)x.elems();
-            if (nd.op == NG_OP_BN_ACT_DGRAD) set_kernel<KID_BN_DGRAD>(t, a, ceil_div(a.total, kBlock));
-            else set_kernel<KID_BN_WGRAD>(t, a, a.C);
+            if (nd.op == NG_OP_BN_ACT_DGRAD) {
+                set_kernel<KID_BN_DGRAD>(t, a, ceil_div(a.total, kBlock));
+                break;
+            }
+            a.chunks = (int)bn_wgrad_chunks(a.C, a.N);
+            if (a.chunks > 1) {
+                if (!packed) return g->fail(NG_EINVAL, "node %d: no workspace for the per-chunk sums", v);
+                a.ws = packed;
+                a.cnt = reinterpret_cast<unsigned*>(packed + (((size_t)a.C * a.chunks * 2 + 63) & ~(size_t)63));
+            }
+            set_kernel<KID_BN_WGRAD>(t, a, (long)a.C * a.chunks);
             break;
         }
         case NG_OP_RELU_DGRAD:
@@ -2469,12 +2489,13 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.w = wf(0);
                 set_kernel<KID_DW_DGRAD>(t, a, ceil_div(a.total, kBlock));
             } else {
-                if (a.N > 1) {
-                    if (!packed) return g->fail(NG_EINVAL, "node %d: no workspace for the per-image partial sums", v);
+                a.chunks = (int)bn_wgrad_chunks(a.C, a.N);
+                if (a.chunks > 1) {
+                    if (!packed) return g->fail(NG_EINVAL, "node %d: no workspace for the per-chunk partial sums", v);
                     a.ws = packed;
-                    a.cnt = reinterpret_cast<unsigned*>(packed + (size_t)a.C * a.N * a.K * a.K);
+                    a.cnt = reinterpret_cast<unsigned*>(packed + (((size_t)a.C * a.chunks * a.K * a.K + 63) & ~(size_t)63));
                 }
-                set_kernel<KID_DW_WGRAD>(t, a, (long)a.C * a.N);
+                set_kernel<KID_DW_WGRAD>(t, a, (long)a.C * a.chunks);
             }
             break;
         }

@@ -110,12 +110,14 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
         case KID_BN_RAW: case KID_BN_DGRAD: case KID_RELU_DGRAD: case KID_GAP_DGRAD: case KID_SLICE_PAD: case KID_SGD: base = 1.2, per_tile = 0.15; break;
         case KID_DW_DGRAD: case KID_POOL_DGRAD: base = 2.0, per_tile = 0.7; break;
         case KID_BN_WGRAD: case KID_CHANNEL_SUM: {
-            const double count = (double)g->nodes[nd.preds[0]].out.elems() / std::max<double>(1.0, (double)g->nodes[nd.preds[0]].out.c);
+            double count = (double)g->nodes[nd.preds[0]].out.elems() / std::max<double>(1.0, (double)g->nodes[nd.preds[0]].out.c);
+            if (kid == KID_BN_WGRAD) count /= std::max(1, reinterpret_cast<const BnRawArgs*>(g->tasks[v].args)->chunks);   // a channel's images are split over workgroups
             base = 1.5 + 0.00002 * count * 256.0 / kBlock, per_tile = 0.00003 * count;   // one workgroup walks a whole channel
             break;
         }
-        case KID_DW_WGRAD: {                                           // one workgroup per (channel, image)
-            const double count = (double)g->nodes[nd.preds[0]].out.h * (double)g->nodes[nd.preds[0]].out.w;
+        case KID_DW_WGRAD: {                                           // one workgroup per (channel, chunk of images)
+            const DwGradArgs* a = reinterpret_cast<const DwGradArgs*>(g->tasks[v].args);
+            const double count = (double)g->nodes[nd.preds[0]].out.h * (double)g->nodes[nd.preds[0]].out.w * ((a->N + a->chunks - 1) / std::max(1, a->chunks));
             base = 2.5, per_tile = 0.0005 * count;
             break;
         }
