@@ -31,6 +31,7 @@ enum Kid : int {
     // conv1x1 for many output pixels on the same plan (activations pixel-major in LDS, 32 or 64 channels at a time, weights
     // straight from memory): 32 x 64 and 64 x 64 output tiles
     KID_PW_P32, KID_PW_P64,
+    KID_POOL_ROW_S1, KID_POOL_ROW_S2,   // pool3x3 for large tensors: a thread computes 4 outputs of a column, lanes run along the row (stride 1 / 2)
     // graphs that train (weights change between replays, so nothing is repacked): convolutions and fc, forward and backward,
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
     KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
@@ -60,6 +61,7 @@ constexpr bool is_c3m(int kid) { return plain_variant(kid) >= KID_C3_M1 && plain
 constexpr bool has_add_epilogue(int kid) { return plain_variant(kid) != kid; }
 constexpr bool is_c3_patch(int kid) { return kid >= KID_C3_P64 && kid <= KID_C3_Q128; }
 constexpr bool is_pw_patch(int kid) { return kid == KID_PW_P32 || kid == KID_PW_P64; }
+constexpr bool is_pool_row(int kid) { return kid == KID_POOL_ROW_S1 || kid == KID_POOL_ROW_S2; }
 constexpr bool is_c3_lds(int kid) { return kid == KID_C3_L32 || kid == KID_C3_L64 || is_c3_patch(kid); }
 // convolutions whose argument block is a C3Args (the others with a batch-norm epilogue take a PwArgs)
 constexpr bool takes_c3_args(int kid) { return is_c3m(kid) || is_c3_lds(kid) || (kid >= KID_C3_T16S1 && kid <= KID_C3_T8S2); }
@@ -94,7 +96,7 @@ constexpr bool is_matrix_kernel(int kid_any) {
 // kernels of the lean build of the resident kernel: everything except the 32 x 32 and LDS-tiled
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
-    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) &&
+    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) && !is_pool_row(kid) &&
            !is_train_kernel(kid);
 }
 // Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean

@@ -1401,6 +1401,71 @@ __device__ __forceinline__ void conv3x3_k4_tile(const typename std::conditional<
     __syncthreads();                                         // LDS is reused by the next tile
 }
 
+// ------------------------------------------------------------------------------------
+// pool3x3 for large tensors (batches): a thread computes 4 outputs of one output column, one below the other;
+// neighbouring lanes have neighbouring columns, so every load and store of a wavefront is a contiguous run. The 3 + 3 STRIDE
+// input rows x 3 columns the four windows cover are loaded once (4.5 loads per output at stride 1 instead of 9, each
+// touching 2-3 cache lines per wavefront), reduced along the rows first and then down the column; row / column validity
+// is worked out once per thread. Items = (plane, block of 4 output rows, output column) in that order.
+// (Four neighbouring outputs of a ROW per thread was measured first and is slower than one output per thread: lanes
+// 16 bytes apart make every load instruction touch eight cache lines.)
+// ------------------------------------------------------------------------------------
+template <int STRIDE, bool FIN, class Wait>
+__device__ __forceinline__ void pool3x3_col_tile(const PoolArgs& a, int tile, float*, int tid, bool live, Wait& wait) {
+    const bool fout = wait.far_out();
+    constexpr int NR = 3 + 3 * STRIDE;                       // input rows under four windows one below the other
+    const int blocks = (a.Ho + 3) >> 2;
+    const int items = (a.total / (a.Ho * a.Wo)) * blocks * a.Wo;
+    const int item = tile * kBlock + tid;
+    const bool active = live && item < items;
+    const int it = min(item, items - 1);
+    const int ow = it % a.Wo, t1 = it / a.Wo;
+    const int blk = t1 % blocks, plane = t1 / blocks;
+    const int oh0 = 4 * blk, r0 = oh0 * STRIDE - a.pad, c0 = ow * STRIDE - a.pad;
+    const float* src = a.x + (size_t)plane * a.H * a.W;
+    wait();
+    if (!active) return;
+    const bool max_mode = a.mode == 0;
+    const float neutral = max_mode ? -INFINITY : 0.f;
+    float v[NR][3];
+    bool row_in[NR], col_in[3];
+#pragma unroll
+    for (int dr = 0; dr < NR; ++dr) row_in[dr] = (unsigned)(r0 + dr) < (unsigned)a.H;
+#pragma unroll
+    for (int dc = 0; dc < 3; ++dc) col_in[dc] = (unsigned)(c0 + dc) < (unsigned)a.W;
+    int cc[3];
+#pragma unroll
+    for (int dc = 0; dc < 3; ++dc) cc[dc] = min(max(c0 + dc, 0), a.W - 1);
+#pragma unroll
+    for (int dr = 0; dr < NR; ++dr) {
+        const float* row = src + min(max(r0 + dr, 0), a.H - 1) * a.W;
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) v[dr][dc] = ldg(a.x, row + cc[dc], FIN);
+    }
+    __builtin_amdgcn_sched_barrier(0);                       // all loads are issued before the first use
+    float rowv[NR];                                          // along the rows: columns outside the image do not take part
+#pragma unroll
+    for (int dr = 0; dr < NR; ++dr) {
+        float acc = neutral;
+#pragma unroll
+        for (int dc = 0; dc < 3; ++dc) {
+            const float x = col_in[dc] ? v[dr][dc] : neutral;
+            acc = max_mode ? fmaxf(acc, x) : acc + x;
+        }
+        rowv[dr] = row_in[dr] ? acc : neutral;
+    }
+    const int cols = (int)col_in[0] + (int)col_in[1] + (int)col_in[2];
+    float* out = a.y + ((size_t)plane * a.Ho + oh0) * a.Wo + ow;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (oh0 + j >= a.Ho) break;
+        const int b = j * STRIDE;
+        float acc = max_mode ? fmaxf(fmaxf(rowv[b], rowv[b + 1]), rowv[b + 2]) : (rowv[b] + rowv[b + 1]) + rowv[b + 2];
+        if (!max_mode) acc = acc / (float)(cols * ((int)row_in[b] + (int)row_in[b + 1] + (int)row_in[b + 2]));
+        stg(a.y, out + (size_t)j * a.Wo, acc, fout);
+    }
+}
+
 #include "ng_train_tiles.inc"
 
 // ------------------------------------------------------------------------------------
@@ -1437,6 +1502,8 @@ NG_KERNEL(KID_DW_K5S2, DwArgs, "dwconv_k5s2", dwconv_tile < 5, 2, 1)
 NG_KERNEL(KID_DW_K3S1_P4, DwArgs, "dwconv_k3s1_p4", dwconv_tile < 3, 1, 4)
 NG_KERNEL(KID_POOL, PoolArgs, "pool3x3", pool3x3_tile < 1, false)
 NG_KERNEL(KID_POOL_P4, PoolArgs, "pool3x3_p4", pool3x3_tile < 4, false)
+NG_KERNEL(KID_POOL_ROW_S1, PoolArgs, "pool3x3_col4_s1", pool3x3_col_tile < 1)
+NG_KERNEL(KID_POOL_ROW_S2, PoolArgs, "pool3x3_col4_s2", pool3x3_col_tile < 2)
 NG_KERNEL(KID_POOL_A, PoolAddArgs, "pool3x3_add", pool3x3_tile < 1, true)
 NG_KERNEL(KID_POOL_P4A, PoolAddArgs, "pool3x3_p4_add", pool3x3_tile < 4, true)
 NG_KERNEL(KID_PW_D4, PwArgs, "conv1x1_mfma_d4", conv1x1_direct_tile < 4)
@@ -1526,6 +1593,7 @@ NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
     X(KID_PW_S3A) X(KID_PW_S4A) X(KID_C3_M1A) X(KID_C3_M2A) X(KID_C3_M3A) X(KID_C3_M4A)                                 \
     X(KID_POOL_A) X(KID_POOL_P4A) X(KID_C3_L32) X(KID_C3_L64)                                                          \
     X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
+    X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
     X(KID_GEMM_C3_WGRAD) X(KID_PW_WGRAD_PX) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD)
@@ -1913,6 +1981,7 @@ void k4_split(long k_total, long cout, PwChoice& c) {
     c.packed = (size_t)((cout + 15) / 16) * c.groups * 256;
 }
 constexpr long kPwPatchMinCols = 2048;
+constexpr long kPoolRowMinOutputs = 1 << 20;   // pool3x3: from here on the kernel with four outputs of a column per thread
 PwChoice choose_pw(const ng_graph* g, int v) {
     PwChoice c;
     const Node& nd = g->nodes[v];
@@ -2242,6 +2311,13 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
         case NG_OP_POOL: {
             PoolArgs a{buf(nd.preds[0]), buf(v), (int)i0.h, (int)i0.w, (int)o.h, (int)o.w,
                        nd.p.stride, nd.p.pad, nd.p.pool_mode, total};
+            // large tensors (batches): four outputs of a column per thread
+            if (total >= kPoolRowMinOutputs && !g->trainable && (nd.p.stride == 1 || nd.p.stride == 2)) {
+                const long items = (long)o.n * o.c * ceil_div(o.h, 4) * o.w;
+                if (nd.p.stride == 1) set_kernel<KID_POOL_ROW_S1>(t, a, ceil_div(items, kBlock));
+                else set_kernel<KID_POOL_ROW_S2>(t, a, ceil_div(items, kBlock));
+                break;
+            }
             set_kernel<KID_POOL>(t, a, ceil_div(total, kBlock));
             break;
         }

@@ -66,6 +66,7 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
         case KID_ADD: case KID_ADD_V4: case KID_ADD_R64: case KID_ADD_R16: base = 0.9, per_tile = 0.1; break;
         case KID_CONCAT: case KID_CONCAT_V4: base = 1.6, per_tile = 0.2; break;
         case KID_POOL: base = 1.6, per_tile = 0.25; break;
+        case KID_POOL_ROW_S1: case KID_POOL_ROW_S2: base = 1.8, per_tile = 0.5; break;
         case KID_POOL_P4: case KID_DW_K3S1_P4: base = 1.9, per_tile = 0.6; break;
         case KID_DW_K3S1: case KID_DW_K3S2: base = 1.5, per_tile = 0.25; break;
         case KID_DW_K5S1: case KID_DW_K5S2: base = 2.0, per_tile = 0.7; break;

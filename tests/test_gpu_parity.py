@@ -168,6 +168,27 @@ def test_conv3x3_patch_kernels(shape, cout, kernel):
     check_all_nodes(w, (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
 
 
+# pool3x3 on tensors of a million outputs and more: four outputs of a column per thread, both modes, strides and
+# paddings; heights that leave a partial block of 1, 2 and 3 output rows (and none)
+@pytest.mark.parametrize("shape", [(8, 64, 45, 47), (2, 48, 149, 147), (16, 32, 96, 101), (16, 32, 97, 96), (8, 64, 64, 88)])
+def test_pool_large_tensors(shape):
+    def build(b):
+        x = b.input(*shape)
+        for mode in ("max", "avg"):
+            for stride in (1, 2):
+                for pad in (0, 1):
+                    b.pool(x, mode, stride, pad)
+    w = single_op(build)
+    r = GraphRunner(w, DEV)
+    r.prepare()
+    try:
+        names = [B.ng_task_kernel(r.g, v) for v in range(1, len(w.nodes))]
+    finally:
+        r.close()
+    assert "pool3x3_col4_s1" in names and (shape[0] < 16 or "pool3x3_col4_s2" in names), names
+    check_all_nodes(w, (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
+
+
 @pytest.mark.parametrize("n,cin,cout", [(1, 2048, 1000), (3, 100, 10), (8, 33, 5), (32, 2048, 1000), (9, 64, 7),
                                         (1024, 70, 1000),      # a batch large enough for the LDS-tiled kernel, with a bias
                                         (2048, 64, 100)])      # ... and for the kernel with the activations pixel-major in LDS
