@@ -216,6 +216,12 @@ int ng_critical_path(const ng_graph* g, const float* t, float* total, int* path,
  *   *n_edges: the number of edges; with max_edges = 0 only the count is returned, a positive
  *     max_edges that is too small gives NG_ENOMEM. All arrays are caller-owned host memory. */
 int ng_get_graph_edges(ng_graph* g, int fuse, int* launched_by, int* n_edges, int* src, int* dst, int max_edges);
+/* Name of the kernel node `id` will be bound to, worked out on the host from the shapes alone (needs
+ * ng_plan_memory, no GPU; after ng_bind the same as ng_task_kernel): which of the hand-written kernels a
+ * task runs is decided by the library, per node, from its operator, shapes and the graph's being a
+ * training graph or not (Section 4.1: the pre-run records the kernel of every task once). "" for an input
+ * node, NULL on an error (ng_last_error). The string is a constant of the library. */
+const char* ng_planned_task_kernel(ng_graph* g, int id);
 
 /* ---- 2b. ahead-of-time pass, GPU part (Section 4.1: pre-run once, record the tasks) ---- */
 

@@ -31,7 +31,7 @@ SYMBOLS = ("ng_create", "ng_destroy", "ng_add_input", "ng_add_node", "ng_mark_ou
            "ng_tensor_ptr", "ng_replay_mode", "ng_replay", "ng_replay_static", "ng_sync", "ng_resident_config",
            "ng_auto_mode", "ng_resident_dry_plan", "ng_resident_dry_plan_setting", "ng_resident_xcd_mapping", "ng_resident_fusion", "ng_resident_plan_trials", "ng_resident_plan_kept", "ng_resident_sizes", "ng_resident_trace", "ng_time_replay", "ng_time_chain", "ng_time_task",
            "ng_time_task_device", "ng_task_kernel_executed", "ng_time_launch_floor", "ng_launch_task_solo",
-           "ng_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
+           "ng_task_kernel", "ng_planned_task_kernel", "ng_task_work", "ng_last_error", "ng_version")
 
 
 class ng_op_params(C.Structure):
@@ -93,6 +93,7 @@ _sig = {
     "ng_launch_task_solo": (_I, [_P, _I, _I]),
     "ng_time_launch_floor": (_I, [_P, _I, _FP]),
     "ng_task_kernel": (C.c_char_p, [_P, _I]),
+    "ng_planned_task_kernel": (C.c_char_p, [_P, _I]),
     "ng_task_work": (_I, [_P, _I, _DP, _DP]),
     "ng_last_error": (C.c_char_p, [_P]),
     "ng_version": (C.c_char_p, []),
@@ -385,6 +386,14 @@ def ng_time_launch_floor(g, reps) -> float:
 
 def ng_task_kernel(g, node_id) -> str:
     return lib.ng_task_kernel(g, node_id).decode()
+
+
+def ng_planned_task_kernel(g, node_id) -> str:
+    """The kernel the node will be bound to, from the shapes alone (no GPU)."""
+    name = lib.ng_planned_task_kernel(g, node_id)
+    if name is None:
+        raise NgError(NG_EINVAL, lib.ng_last_error(g).decode() if g else "null graph")
+    return name.decode()
 
 
 def ng_task_work(g, node_id):

@@ -133,3 +133,13 @@ extern "C" int ng_get_graph_edges(ng_graph* g, int fuse, int* launched_by, int* 
     if (count > max_edges && max_edges > 0) return g->fail(NG_ENOMEM, "ng_get_graph_edges: %d edges, room for %d", count, max_edges);
     return NG_OK;
 }
+
+extern "C" const char* ng_planned_task_kernel(ng_graph* g, int id) {
+    if (!g) return nullptr;
+    if (g->phase < PLANNED) return g->fail(NG_ESTATE, "ng_planned_task_kernel: call ng_plan_memory first"), nullptr;
+    if (id < 0 || id >= (int)g->nodes.size()) return g->fail(NG_EINVAL, "ng_planned_task_kernel: no node %d", id), nullptr;
+    TaskView view(g);
+    if (view.rc != NG_OK) return nullptr;
+    const char* name = g->tasks[id].name;
+    return name ? name : "";
+}

@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 import workloads
-from workloads.model import Node, Workload
+from workloads.model import Builder, Node, Workload
 from oracle.schedule import schedule as oracle_schedule, schedule_exact as oracle_schedule_exact
 from oracle import checks
 from oracle.memory import plan_is_safe as memory_plan_is_safe
@@ -651,3 +651,100 @@ def test_training_operator_errors():
     s.slice_lo[1] = 3
     assert B.ng_node_shape(g, B.ng_add_node(g, B.NG_OP_SLICE_PAD, s, [dy], [])) == (2, 6, 3, 3)
     B.ng_destroy(g)
+
+
+# ---- which hand-written kernel a node is bound to (decided on the host from shapes alone) --------------------------
+def _planned_kernels(w):
+    r = GraphRunner(w)
+    try:
+        r.schedule()
+        r.plan()
+        return [B.ng_planned_task_kernel(r.g, v) for v in range(len(w.nodes))]
+    finally:
+        r.close()
+
+
+def _single_ops(build):
+    b = Builder("single_op")
+    build(b)
+    rng = np.random.default_rng(0)
+    b.draw_weights(rng, 0.2, "random")
+    return b.finish(rng)
+
+
+def _kernels_on(shape, ops):
+    """Kernel names of `ops` (callables taking the builder and the input node) applied to one input of `shape`."""
+    def build(b):
+        x = b.input(*shape)
+        for op in ops:
+            op(b, x)
+    return _planned_kernels(_single_ops(build))[1:]
+
+
+def test_kernel_choice_of_the_patch_stationary_convolutions():
+    def c3(cout, stride=1, pad=1):
+        return lambda b, x: b.conv3x3(x, cout, stride, pad)
+    # 96 rows: 640 tiles (3 rounds) against 1280 of 64 rows (5 rounds); 64 rows; 32 output channels: 32 x 128 tiles, whose runs
+    # of 128 pixels need a patch of 259; stride 2: every second pixel of a patch of 385
+    assert _kernels_on((32, 96, 35, 35), [c3(96), c3(64), c3(32), c3(96, 2, 0)]) == [
+        "conv3x3_patch_96x64", "conv3x3_patch_64x64", "conv3x3_patch_32x128_wide", "conv3x3_patch_64x64_wide"]
+    # 480 tiles of 64 rows (2 rounds) against 320 of 96 (2 rounds of 1.5 x the work)
+    assert _kernels_on((32, 192, 17, 17), [c3(192)]) == ["conv3x3_patch_64x64"]
+    # 256 tiles of 96 rows: one per compute unit
+    assert _kernels_on((32, 384, 8, 8), [c3(768)]) == ["conv3x3_patch_96x64"]
+    # wide rows and thousands of tiles: 64 x 128
+    assert _kernels_on((32, 32, 147, 147), [c3(64)]) == ["conv3x3_patch_64x128_wide"]
+    # 24 input channels are not whole blocks of 16; a run of 64 pixels of a 299-wide image can need 4 x 301 pixels of patch
+    assert _kernels_on((2, 24, 97, 96), [c3(40)]) == ["conv3x3_lds_64x64"]
+    assert _kernels_on((1, 16, 299, 299), [c3(64)]) == ["conv3x3_lds_64x64"]
+    # 1225 output pixels: a small problem
+    assert _kernels_on((1, 96, 35, 35), [c3(96)])[0].startswith("conv3x3_mfma_")
+
+
+def test_kernel_choice_of_conv1x1_pool_and_the_networks():
+    def pw(cout):
+        return lambda b, x: b.conv1x1(x, cout)
+
+    def pool(mode, stride, pad):
+        return lambda b, x: b.pool(x, mode, stride, pad)
+    assert _kernels_on((32, 768, 17, 17), [pw(192)]) == ["conv1x1_patch_64x64"]          # 435 tiles of 64 x 64
+    assert _kernels_on((32, 1280, 8, 8), [pw(192)]) == ["conv1x1_patch_32x64"]           # 96 tiles of 64 x 64: 32-row tiles instead
+    assert _kernels_on((5, 37, 45, 47), [pw(150)]) == ["conv1x1_mfma_64x64"]             # 37 input channels: the LDS-tiled kernel
+    small = _kernels_on((1, 768, 17, 17), [pw(192), pool("max", 1, 1)])                  # 289 columns: small problems
+    assert not small[0].startswith("conv1x1_patch") and small[1] == "pool3x3"
+    assert _kernels_on((32, 288, 35, 35), [pool("max", 1, 1), pool("avg", 2, 0)]) == ["pool3x3_col4_s1", "pool3x3_col4_s2"]
+    # the Inception-style network at batch 32: every convolution but the 3-channel stem on the patch kernels
+    w = workloads.make("inception_style", batch=32)
+    k = _planned_kernels(w)
+    convs = [k[v] for v, nd in enumerate(w.nodes) if nd.op in ("conv1x1", "conv3x3")]
+    assert sorted(c for c in convs if not c.startswith(("conv1x1_patch", "conv3x3_patch"))) == ["conv3x3_t16s2"]
+    # at batch 1 only its wide stem layers have 2048 output pixels
+    w1 = workloads.make("inception_style")
+    k1 = _planned_kernels(w1)
+    assert sum(c.startswith(("conv1x1_patch", "conv3x3_patch")) for c in k1) == 4
+    # errors
+    r = GraphRunner(w)
+    try:
+        with pytest.raises(B.NgError):
+            B.ng_planned_task_kernel(r.g, 0)                                                    # not planned yet
+        r.schedule()
+        r.plan()
+        with pytest.raises(B.NgError):
+            B.ng_planned_task_kernel(r.g, len(w.nodes))
+    finally:
+        r.close()
+
+
+def test_kernel_choice_in_a_training_graph():
+    fwd = workloads.nas_cell_cifar(batch=32)
+    out = fwd.outputs[0]
+    w = workloads.training_graph(fwd, 1e-6, {out: np.zeros(fwd.nodes[out].shape, np.float32)})
+    k = _planned_kernels(w)
+    by_op = {}
+    for v, nd in enumerate(w.nodes):
+        by_op.setdefault(nd.op, set()).add(k[v])
+    # weights change between replays: convolutions run the gather GEMM on the weights as they are, never a repacked copy
+    assert by_op["conv1x1"] == {"gemm_conv1x1_fwd"} and by_op["conv3x3"] == {"gemm_conv3x3_fwd"} and by_op["pool"] == {"pool3x3"}
+    # 32 x 32 and 16 x 16 maps: the weight gradient reads both operands 128 bits along the pixels; the fc (1 x 1 maps) cannot
+    assert by_op["conv1x1_wgrad"] == {"conv1x1_wgrad_px", "gemm_conv1x1_wgrad"}
+    assert sum(name == "gemm_conv1x1_wgrad" for name in k) == 1
