@@ -193,9 +193,11 @@ int ng_plan_memory(ng_graph* g, size_t* arena_bytes);
  * task runs inside another task's tiles: slower than on a plan without reuse, same results. */
 int ng_set_memory_reuse(ng_graph* g, int on);
 /* Modes 0-3 launch one kernel per task, except that (on by default) a batch-norm / ReLU whose only
- * input is a convolution result is applied by that convolution's kernel and a concat whose inputs
- * were all produced in place is not launched. on = 0 switches both exceptions off: one kernel per
- * task. Call before ng_bind (NG_ESTATE after). */
+ * input is a convolution result is applied by that convolution's kernel, a concat whose inputs
+ * were all produced in place is not launched, and weight updates (NG_OP_SGD_UPDATE) whose output no
+ * node reads are carried out together by the launch of the last of them on their stream (modes 1 and
+ * 2: of the last of them in the submission order; same arithmetic per element). on = 0 switches the
+ * exceptions off: one kernel per task. Call before ng_bind (NG_ESTATE after). */
 int ng_set_launch_fusion(ng_graph* g, int on);
 /* offset[n_nodes], bytes[n_nodes] of each node's output inside the arena (host arrays). */
 int ng_get_offsets(const ng_graph* g, size_t* offset, size_t* bytes);
@@ -210,8 +212,9 @@ int ng_critical_path(const ng_graph* g, const float* t, float* total, int* path,
  * edge of E is ordered by the FIFO order of a stream or by a synchronised edge. fuse != 0: the
  * graph as launched by default; 0: one kernel node per task (see ng_set_launch_fusion).
  *   launched_by[n_nodes] (may be NULL): the task whose kernel node writes node v's tensor - v
- *     itself, the convolution that also applies a fused batch-norm / ReLU, -1 for a network
- *     input, -2 for a concat that is not launched because its inputs are produced in place;
+ *     itself, the convolution that also applies a fused batch-norm / ReLU, the later weight update
+ *     of the same stream whose launch also carries out this one, -1 for a network input, -2 for a
+ *     concat that is not launched because its inputs are produced in place;
  *   src/dst[max_edges]: one entry per graph edge, as task ids (both ends have kernel nodes);
  *   *n_edges: the number of edges; with max_edges = 0 only the count is returned, a positive
  *     max_edges that is too small gives NG_ENOMEM. All arrays are caller-owned host memory. */

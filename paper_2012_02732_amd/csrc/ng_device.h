@@ -38,6 +38,7 @@ enum Kid : int {
     KID_PW_WGRAD_PX,                 // conv1x1 weight gradient with both operands read along the pixels, 128 bits at a time (HW % 16 == 0)
     KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_GAP_DGRAD,
     KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,
+    KID_SGD_BATCH,                   // several update nodes in one launch (launch-based replay modes only, in no build of the resident kernel)
     KID_COUNT
 };
 constexpr bool is_train_kernel(int kid) { return kid >= KID_GEMM_PW_FWD && kid <= KID_SGD; }
@@ -97,14 +98,14 @@ constexpr bool is_matrix_kernel(int kid_any) {
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
     return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) && !is_pool_row(kid) &&
-           !is_train_kernel(kid);
+           !is_train_kernel(kid) && kid != KID_SGD_BATCH;
 }
 // Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean
 // kernels plus the training kernels: a graph that trains runs its convolutions through the GEMM kernels, never through
 // the repacked-weight kernels of the full build).
 enum { BUILD_LEAN = 0, BUILD_FULL = 1, BUILD_TRAIN = 2 };
 constexpr bool in_build(int build, int kid) {
-    return build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid));
+    return kid == KID_SGD_BATCH ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid));
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
@@ -303,6 +304,21 @@ struct SgdArgs {
     float* flag;               // the node's own (1-element) output
     float lr;
     int offset, total;
+};
+
+// One workgroup's share of a batched update: up to kSgdTileElems consecutive elements of one update node, with the
+// addresses already advanced to the share's first element. A table of these in device memory is the whole
+// description of the launch.
+constexpr int kSgdTileElems = 1024;
+struct SgdTile {
+    float* w;
+    const float* g;
+    float* flag;               // the node's (1-element) output if this is the node's first share, else nullptr
+    float lr;
+    int count;
+};
+struct SgdBatchArgs {
+    const SgdTile* tiles;      // [ntiles]
 };
 
 // ---- device-resident replay: the task schedule as data in device memory -------------------

@@ -128,6 +128,7 @@ struct ng_graph {
     std::vector<ng::Task> tasks;                         // one stand-alone kernel per node (inputs: none)
     std::vector<ng::Task> launch_tasks;                  // what modes 0-3 launch: the same, except that a batch-norm / ReLU directly behind
                                                          // a convolution is applied by that convolution's kernel and has no launch of its own
+    std::vector<ng::Task> single_tasks;                  // what the single-stream modes launch: the same, with the weight updates of all streams in one launch
     std::vector<int> launch_fused_into;                  // [n_nodes] that convolution (the node itself: a concat with nothing to copy), or -1
     ng::Runtime* rt = nullptr;
     int mode = NG_MODE_AUTO;
@@ -173,7 +174,9 @@ const void* standalone_kernel_handle(int kid, const char** name);
 const void* timed_kernel_handle(int kid);
 const void* xcd_probe_kernel_handle();
 // ng_launch_graph.cpp
-void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, std::vector<int>& fused_into);
+void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, bool one_stream, std::vector<int>& fused_into);
+void make_sgd_batch_task(const std::vector<Task>& tasks, const std::vector<int>& members, std::vector<SgdTile>& table,
+                         const SgdTile* table_dev, Task& t);
 void build_launch_graph(const ng_graph* g, const std::vector<Task>& tasks, const std::vector<int>& fused_into, LaunchGraph& out);
 // ng_resident_plan.cpp: xcds = 0 lets the cost model choose among 1, 2, 4, 8.
 int plan_resident(const ng_graph* g, int n_wg, int xcds, const PlanKnobs& knobs, ResidentPlan& plan);

@@ -1577,6 +1577,7 @@ NG_KERNEL0(KID_DW_DGRAD, DwGradArgs, "dwconv_dgrad", dw_dgrad_tile)
 NG_KERNEL0(KID_DW_WGRAD, DwGradArgs, "dwconv_wgrad", dw_wgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD, PoolGradArgs, "pool3x3_dgrad", pool_dgrad_tile)
 NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
+NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
 NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
 #undef NG_KERNEL0
 
@@ -1596,7 +1597,7 @@ NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
     X(KID_GEMM_C3_WGRAD) X(KID_PW_WGRAD_PX) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
-    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD)
+    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
 // different offsets): the predicates that name the type must agree with the type the kernel takes.
@@ -1919,6 +1920,23 @@ __global__ __launch_bounds__(kGroup) void xcd_probe_kernel(int* xcd_of_workgroup
 }
 }  // namespace
 const void* xcd_probe_kernel_handle() { return reinterpret_cast<const void*>(&xcd_probe_kernel); }
+
+// The launch that carries out the update nodes `members` (their stand-alone tasks in `tasks`) at once. The shares of
+// the members are appended to `table`, the host copy of the device table that will sit at `table_dev`: the task's
+// argument points at its first share there.
+void make_sgd_batch_task(const std::vector<Task>& tasks, const std::vector<int>& members, std::vector<SgdTile>& table,
+                         const SgdTile* table_dev, Task& t) {
+    const size_t first = table.size();
+    for (int v : members) {
+        SgdArgs a;
+        std::memcpy(&a, tasks[v].args, sizeof a);
+        for (int at = 0; at < a.total || at == 0; at += kSgdTileElems)
+            table.push_back(SgdTile{a.w + at, a.g + a.offset + at, at == 0 ? a.flag : nullptr, a.lr, std::min(a.total - at, kSgdTileElems)});
+    }
+    t = Task();
+    t.block[0] = kBlock;
+    set_kernel<KID_SGD_BATCH>(t, SgdBatchArgs{table_dev + first}, (long)(table.size() - first));
+}
 
 const void* resident_kernel_handle(int build) {
     return build == BUILD_TRAIN ? reinterpret_cast<const void*>(&resident_kernel<BUILD_TRAIN>)

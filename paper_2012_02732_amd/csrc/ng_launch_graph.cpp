@@ -18,9 +18,13 @@ namespace ng {
 //   * a batch-norm / ReLU whose only input is a convolution result is applied by that
 //     convolution's kernel (fused_into[v] = the convolution);
 //   * a concat all of whose inputs the memory plan placed inside its result has nothing to
-//     copy (fused_into[v] = v).
+//     copy (fused_into[v] = v);
+//   * weight updates that nothing depends on are carried out by the launch of the last such update of their stream
+//     (`one_stream`: of the whole submission order; fused_into[v] = that update). A later launch is always in order
+//     for an update: it already comes after every reader of its weights, and it keeps its place in the stream, so
+//     the last one's launch comes after everything the earlier ones waited for.
 // Everything else: -1. `tasks` needs the kernel ids only (a dry task table will do).
-void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, std::vector<int>& fused_into) {
+void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, bool one_stream, std::vector<int>& fused_into) {
     const int n = (int)g->nodes.size();
     fused_into.assign(n, -1);
     // not under a memory plan with reuse over time: there the batch-norm's buffer may still hold the
@@ -41,6 +45,18 @@ void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, boo
         bool in_place = true;
         for (int u : nd.preds) in_place = in_place && g->alias_of[u] == v && tasks[u].fn;
         if (in_place) fused_into[v] = v;
+    }
+    std::vector<char> is_read(n, 0);
+    for (int v = 0; v < n; ++v)
+        for (int u : g->nodes[v].preds) is_read[u] = 1;
+    const Schedule& sc = g->sched;
+    std::vector<int> last_update(one_stream ? 1 : sc.n_streams, -1);
+    for (auto it = sc.order.rbegin(); it != sc.order.rend(); ++it) {
+        const int v = *it;
+        if (g->nodes[v].op != NG_OP_SGD_UPDATE || tasks[v].kid != KID_SGD || is_read[v]) continue;
+        int& last = last_update[one_stream ? 0 : sc.stream_of[v]];
+        if (last < 0) last = v;
+        else fused_into[v] = last;
     }
 }
 
@@ -116,7 +132,7 @@ extern "C" int ng_get_graph_edges(ng_graph* g, int fuse, int* launched_by, int* 
     TaskView view(g);
     if (view.rc != NG_OK) return view.rc;
     std::vector<int> fused_into;
-    decide_launch_fusion(g, g->tasks, fuse != 0, fused_into);
+    decide_launch_fusion(g, g->tasks, fuse != 0, false, fused_into);
     LaunchGraph lg;
     build_launch_graph(g, g->tasks, fused_into, lg);
     const int n = (int)g->nodes.size();

@@ -31,6 +31,7 @@ struct Runtime {
     hipGraphExec_t exec[2] = {nullptr, nullptr};
     hipEvent_t t_start = nullptr, t_stop = nullptr;
     float* constants = nullptr;            // library-owned: repacked weights
+    SgdTile* sgd_tiles = nullptr;          // library-owned: the shares of the batched weight updates (modes 0-3)
     float empty_chain_us = 0.f;            // per-node time of a chain of empty kernels (measured on demand)
     unsigned long long* stamps = nullptr;  // device memory: the clock readings of a timed kernel, one pair per workgroup
     size_t stamps_wgs = 0;
@@ -83,7 +84,7 @@ int issue_all(ng_graph* g, bool multi) {
     hipStream_t origin = rt.streams[0];
     if (!multi) {
         for (int v : sc.order)
-            if (int rc = launch(g, g->launch_tasks[v], origin)) return rc;
+            if (int rc = launch(g, g->single_tasks[v], origin)) return rc;
         return NG_OK;
     }
     if (!sc.fork.empty()) {
@@ -569,6 +570,7 @@ void destroy_runtime(ng_graph* g) {
     if (rt->t_start) (void)hipEventDestroy(rt->t_start);
     if (rt->t_stop) (void)hipEventDestroy(rt->t_stop);
     if (rt->constants) (void)hipFree(rt->constants);
+    if (rt->sgd_tiles) (void)hipFree(rt->sgd_tiles);
     if (rt->d_records) (void)hipFree(rt->d_records);
     if (rt->d_wg_first) (void)hipFree(rt->d_wg_first);
     if (rt->plan.done) (void)hipFree(rt->plan.done);
@@ -630,19 +632,41 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
     // in registers (the same arithmetic on the same values; both tensors are stored), and a concat all of
     // whose inputs the memory plan placed inside its result is not launched. Such a task has no launch of
     // its own and whatever waits for it waits for what it waited for.
-    g->launch_tasks = g->tasks;
-    decide_launch_fusion(g, g->tasks, g->launch_fusion, g->launch_fused_into);
-    for (int v = 0; v < (int)g->nodes.size(); ++v) {
-        const int u = g->launch_fused_into[v];
-        if (u < 0) continue;
-        if (u != v) {
-            const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
-            const Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};
-            if (takes_c3_args(g->tasks[u].kid)) reinterpret_cast<C3Args*>(g->launch_tasks[u].args)->ep = ep;
-            else reinterpret_cast<PwArgs*>(g->launch_tasks[u].args)->ep = ep;
+    // Weight updates are gathered into one launch per stream, in the single-stream modes into one launch.
+    std::vector<int> single_fused_into;
+    decide_launch_fusion(g, g->tasks, g->launch_fusion, false, g->launch_fused_into);
+    decide_launch_fusion(g, g->tasks, g->launch_fusion, true, single_fused_into);
+    size_t sgd_shares = 0;
+    for (int v = 0; v < (int)g->nodes.size(); ++v)
+        if (g->tasks[v].kid == KID_SGD && g->tasks[v].fn) sgd_shares += 2 * (size_t)(1 + g->nodes[v].p.cout / kSgdTileElems);   // once per table, rounded up
+    if (sgd_shares > 0) NG_HIP(hipMalloc(reinterpret_cast<void**>(&rt.sgd_tiles), sgd_shares * sizeof(SgdTile)));
+    std::vector<SgdTile> sgd_table;
+    auto fuse_launches = [&](const std::vector<int>& fused_into, std::vector<Task>& out) {
+        out = g->tasks;
+        std::vector<std::vector<int>> batch(g->nodes.size());       // per last update: the updates its launch carries out, in submission order
+        for (int v : g->sched.order) {
+            const int u = fused_into[v];
+            if (u < 0) continue;
+            if (g->tasks[v].kid == KID_SGD && u != v) {
+                batch[u].push_back(v);
+            } else if (u != v) {
+                const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
+                const Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};
+                if (takes_c3_args(g->tasks[u].kid)) reinterpret_cast<C3Args*>(out[u].args)->ep = ep;
+                else reinterpret_cast<PwArgs*>(out[u].args)->ep = ep;
+            }
+            out[v].fn = nullptr;
         }
-        g->launch_tasks[v].fn = nullptr;
-    }
+        for (int u = 0; u < (int)g->nodes.size(); ++u) {
+            if (batch[u].empty()) continue;
+            batch[u].push_back(u);
+            make_sgd_batch_task(g->tasks, batch[u], sgd_table, rt.sgd_tiles, out[u]);
+        }
+    };
+    fuse_launches(g->launch_fused_into, g->launch_tasks);
+    fuse_launches(single_fused_into, g->single_tasks);
+    if (sgd_table.size() > sgd_shares) return g->fail(NG_EINVAL, "ng_bind: %zu shares of weight updates, room for %zu", sgd_table.size(), sgd_shares);
+    if (!sgd_table.empty()) NG_HIP(hipMemcpy(rt.sgd_tiles, sgd_table.data(), sgd_table.size() * sizeof(SgdTile), hipMemcpyHostToDevice));
 
     rt.events.resize(g->sched.n_events);
     for (auto& e : rt.events) NG_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
@@ -1066,7 +1090,7 @@ int ng_time_task(ng_graph* g, int id, int reps, float* isolated_us) {
 static bool executed_task(const ng_graph* g, int id, int mode, Task& out, const char** name) {
     if (mode == NG_MODE_AUTO) mode = g->auto_mode;
     if (mode != NG_MODE_DEVICE_RESIDENT) {
-        out = g->launch_tasks[id];
+        out = (mode == NG_MODE_GRAPH_SINGLE || mode == NG_MODE_EAGER_SINGLE) ? g->single_tasks[id] : g->launch_tasks[id];
         if (name) *name = out.name;
         return out.fn != nullptr;
     }

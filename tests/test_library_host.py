@@ -523,6 +523,39 @@ def test_multi_stream_graph_edges_order_every_dependency_on_the_configs(name):
             assert set(ge) == fifo | lam, (name, assignment)
 
 
+def test_multi_stream_graph_edges_of_a_training_graph_with_gathered_updates():
+    """Weight updates that nothing reads have no launch of their own: the last update of a stream
+    carries out those before it on that stream. The graph must still order every tensor an update
+    reads (gradient, and the readers of the weights it is told to run after) before the launch
+    that stands in for it."""
+    fwd = workloads.nas_cell_cifar(batch=2)
+    out = fwd.outputs[0]
+    w = workloads.training_graph(fwd, 1e-6, {out: np.zeros(fwd.nodes[out].shape, np.float32)})
+    ops = [nd.op for nd in w.nodes]
+    updates = [v for v in range(len(ops)) if ops[v] == "sgd_update"]
+    assert len(updates) > 10
+    for fuse in (True, False):
+        r = GraphRunner(w)
+        sched = r.schedule()
+        r.plan()
+        launched_by, ge = B.ng_get_graph_edges(r.g, fuse)
+        r.close()
+        ok, why = _graph_order_is_safe(w, launched_by, ge)
+        assert ok, (fuse, why)
+        if not fuse:
+            assert all(launched_by[v] == v for v in updates)
+            continue
+        pos = {v: i for i, v in enumerate(sched["order"])}
+        for s in set(sched["stream_of"][v] for v in updates):
+            mine = [v for v in updates if sched["stream_of"][v] == s]
+            last = max(mine, key=lambda v: pos[v])
+            assert all(launched_by[v] == last for v in mine), s
+        # planted mistake: without the edges into one of the standing-in launches the check fails
+        last = launched_by[updates[0]]
+        broken = [e for e in ge if e[1] != last]
+        assert len(broken) < len(ge) and not _graph_order_is_safe(w, launched_by, broken)[0]
+
+
 @pytest.mark.parametrize("seed", [11, 12, 13])
 def test_multi_stream_graph_edges_on_the_80_node_dags(seed):
     """Seed 12 is the DAG on which the multi-stream HIP graph was seen to run task 44 before task 2
