@@ -36,7 +36,7 @@ enum Kid : int {
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
     KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
     KID_PW_WGRAD_PX,                 // conv1x1 weight gradient with both operands read along the pixels, 128 bits at a time (HW % 16 == 0)
-    KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_GAP_DGRAD,
+    KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_POOL_DGRAD_LDS, KID_GAP_DGRAD,
     KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,
     KID_SGD_BATCH,                   // several update nodes in one launch (launch-based replay modes only, in no build of the resident kernel)
     KID_COUNT
@@ -297,7 +297,9 @@ struct PoolGradArgs {          // pool backward; geometry of the FORWARD operato
     const float* dy; const float* x;
     float* y;                  // dx
     int H, W, Ho, Wo, stride, pad, mode, total;
+    int planes_per_tile;       // pool3x3_dgrad_lds: whole (image, channel) planes a workgroup stages in LDS (planes_per_tile H W <= kPoolGradChunk)
 };
+constexpr int kPoolGradChunk = 1024;
 struct SgdArgs {
     float* w;                  // updated in place
     const float* g;            // gradient tensor; element i of w pairs with g[offset + i]

@@ -1576,6 +1576,7 @@ NG_KERNEL0(KID_CHANNEL_SUM, EltGradArgs, "channel_sum", channel_sum_tile)
 NG_KERNEL0(KID_DW_DGRAD, DwGradArgs, "dwconv_dgrad", dw_dgrad_tile)
 NG_KERNEL0(KID_DW_WGRAD, DwGradArgs, "dwconv_wgrad", dw_wgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD, PoolGradArgs, "pool3x3_dgrad", pool_dgrad_tile)
+NG_KERNEL0(KID_POOL_DGRAD_LDS, PoolGradArgs, "pool3x3_dgrad_lds", pool_dgrad_lds_tile)
 NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
 NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
 NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
@@ -1597,7 +1598,7 @@ NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
     X(KID_GEMM_C3_WGRAD) X(KID_PW_WGRAD_PX) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
-    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH)
+    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
 // different offsets): the predicates that name the type must agree with the type the kernel takes.
@@ -2598,7 +2599,13 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             const Shape& x = g->nodes[nd.preds[1]].out;
             PoolGradArgs a{buf(nd.preds[0]), buf(nd.preds[1]), buf(v), (int)x.h, (int)x.w, (int)dy.h, (int)dy.w,
                            nd.p.stride, nd.p.pad, nd.p.pool_mode, (int)x.elems()};
-            set_kernel<KID_POOL_DGRAD>(t, a, ceil_div(a.total, kBlock));
+            const long plane = (long)x.h * x.w;
+            if (plane <= kPoolGradChunk && dy.h * dy.w <= plane) {      // whole planes fit a workgroup's LDS
+                a.planes_per_tile = (int)(kPoolGradChunk / plane);
+                set_kernel<KID_POOL_DGRAD_LDS>(t, a, ceil_div(a.total / plane, a.planes_per_tile));
+            } else {
+                set_kernel<KID_POOL_DGRAD>(t, a, ceil_div(a.total, kBlock));
+            }
             break;
         }
         case NG_OP_SGD_UPDATE: {

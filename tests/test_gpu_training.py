@@ -164,6 +164,38 @@ def test_training_step_all_operators_small():
     check_training(fwd, seeds, 0.01, (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT), end_to_end=False)
 
 
+@pytest.mark.parametrize("shape,kernel", [((2, 5, 40, 36), "pool3x3_dgrad"), ((3, 7, 9, 10), "pool3x3_dgrad_lds"),
+                                          ((2, 3, 32, 32), "pool3x3_dgrad_lds"), ((5, 3, 16, 16), "pool3x3_dgrad_lds")])
+def test_training_pool_backward_plane_sizes(shape, kernel):
+    """Pool backward through both of its kernels: planes a workgroup stages whole in LDS (up to 1024 pixels; several
+    small planes per workgroup with a ragged last group) and larger ones; maximum and average, strides 1 and 2,
+    with and without padding. Ties are frequent: the inputs of the pools are rounded to a few values."""
+    from workloads.model import Builder
+    b = Builder("pool_backward")
+    x = b.input(*shape)
+    pw = b.conv1x1(x, shape[1])
+    outs = []
+    for mode, stride, pad in (("max", 1, 1), ("avg", 1, 1), ("max", 2, 0), ("avg", 2, 1), ("max", 2, 1)):
+        outs.append(b.global_avgpool(b.pool(pw, mode, stride, pad)))
+    f = b.fc(b.add_n(outs), 4)
+    rng = np.random.default_rng(5)
+    b.draw_weights(rng, 0.3, "random")
+    fwd = b.finish(rng, outputs=[f])
+    fwd.input = (np.round(fwd.input * 2.0) / 2.0).astype(np.float32)
+    for nd in fwd.nodes:                                             # conv1x1 of coarse values with coarse weights: many equal taps
+        if nd.op == "conv1x1":
+            nd.weights[0] = (np.round(nd.weights[0] * 4.0) / 4.0).astype(np.float32)
+    seeds = {f: rng.standard_normal(fwd.nodes[f].shape).astype(np.float32)}
+    tw = workloads.training_graph(fwd, 0.01, seeds)
+    r = GraphRunner(tw)
+    r.schedule()
+    r.plan()
+    names = {B.ng_planned_task_kernel(r.g, v) for v, nd in enumerate(tw.nodes) if nd.op == "pool_dgrad"}
+    r.close()
+    assert names == {kernel}, names
+    check_training(fwd, seeds, 0.01, (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT), end_to_end=False)
+
+
 def test_training_step_nas_cell_batch32_cifar():
     """The paper's training setting: batch 32, 32 x 32 inputs. One normal and one reduction cell of the
     NASNet-style recipe between a 3x3 stem and a 10-way classifier; 259 tasks in one DAG."""
