@@ -1550,6 +1550,8 @@ NG_KERNEL(KID_C3_Q128, C3Args, "conv3x3_patch_64x128_wide", conv3x3_patch_tile <
 NG_KERNEL(KID_GEMM_PW_FWD, GemmArgs, "gemm_conv1x1_fwd", gemm_tile < GEMM_PW_FWD)
 NG_KERNEL(KID_GEMM_PW_DGRAD, GemmArgs, "gemm_conv1x1_dgrad", gemm_tile < GEMM_PW_DGRAD)
 NG_KERNEL(KID_GEMM_PW_WGRAD, GemmArgs, "gemm_conv1x1_wgrad", gemm_tile < GEMM_PW_WGRAD)
+NG_KERNEL(KID_PW_PX_FWD, GemmArgs, "conv1x1_px_fwd", pw_px_tile < GEMM_PW_FWD)
+NG_KERNEL(KID_PW_PX_DGRAD, GemmArgs, "conv1x1_px_dgrad", pw_px_tile < GEMM_PW_DGRAD)
 NG_KERNEL(KID_GEMM_C3_FWD, GemmArgs, "gemm_conv3x3_fwd", gemm_tile < GEMM_C3_FWD)
 NG_KERNEL(KID_GEMM_C3_DGRAD, GemmArgs, "gemm_conv3x3_dgrad", gemm_tile < GEMM_C3_DGRAD)
 NG_KERNEL(KID_GEMM_C3_WGRAD, GemmArgs, "gemm_conv3x3_wgrad", gemm_tile < GEMM_C3_WGRAD)
@@ -1597,7 +1599,7 @@ NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
     X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
-    X(KID_GEMM_C3_WGRAD) X(KID_PW_WGRAD_PX) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
+    X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
@@ -1902,6 +1904,15 @@ void set_kernel(Task& t, const typename KernelOf<KID>::Args& a, long ntiles) {
 }
 
 long ceil_div(long a, long b) { return (a + b - 1) / b; }
+
+// conv1x1 forward / input gradient of a graph that trains: the kernel that reads pixels 128 bits at a time re-reads the
+// activations once per 16 rows, which pays while the rows are few (the 64 x 64 LDS-staged GEMM tile otherwise).
+bool pw_px_applies(const GemmArgs& a) {
+    const long hw = (long)a.Ho * a.Wo;
+    return hw % 4 == 0 && a.K % 4 == 0 && a.M <= 256 && a.bias == nullptr && (long)a.K * a.N * 4 < (1L << 31) &&
+           (long)a.M * a.N * 4 < (1L << 31);
+}
+long pw_px_tiles(const GemmArgs& a) { return ceil_div(ceil_div(a.N / 4, 16) * ceil_div(a.M, 16), 4); }
 
 // Direct conv1x1: k steps per chunk by problem depth, and the padded step count of the packed copy.
 int pw_chunk(long cin) { return cin <= 64 ? 4 : (cin <= 128 ? 8 : 16); }
@@ -2363,7 +2374,8 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.M = (int)o.c, a.K = (int)i0.c, a.N = (int)(o.n * hw_out);
                 a.Cin = (int)i0.c, a.Cout = (int)o.c, a.H = a.Ho = (int)o.h, a.W = a.Wo = (int)o.w, a.stride = 1;
                 a.tiles_n = (int)ceil_div(a.N, kGemmTile), a.splits = 1, a.k_per_split = a.K;
-                set_kernel<KID_GEMM_PW_FWD>(t, a, (long)a.tiles_n * ceil_div(a.M, kGemmTile));
+                if (!fc && pw_px_applies(a)) set_kernel<KID_PW_PX_FWD>(t, a, pw_px_tiles(a));
+                else set_kernel<KID_GEMM_PW_FWD>(t, a, (long)a.tiles_n * ceil_div(a.M, kGemmTile));
                 break;
             }
             const PwChoice c = choose_pw(g, v);
@@ -2503,7 +2515,9 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.M = a.Cin, a.K = a.Cout * (c3 ? 9 : 1), a.N = (int)(o.n * o.h * o.w);
             a.tiles_n = (int)ceil_div(a.N, kGemmTile), a.splits = 1, a.k_per_split = a.K;
             const long n = (long)a.tiles_n * ceil_div(a.M, kGemmTile);
-            if (c3) set_kernel<KID_GEMM_C3_DGRAD>(t, a, n); else set_kernel<KID_GEMM_PW_DGRAD>(t, a, n);
+            if (c3) set_kernel<KID_GEMM_C3_DGRAD>(t, a, n);
+            else if (pw_px_applies(a)) set_kernel<KID_PW_PX_DGRAD>(t, a, pw_px_tiles(a));
+            else set_kernel<KID_GEMM_PW_DGRAD>(t, a, n);
             break;
         }
         case NG_OP_CONV1X1_WGRAD:

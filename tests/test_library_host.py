@@ -776,8 +776,13 @@ def test_kernel_choice_in_a_training_graph():
     by_op = {}
     for v, nd in enumerate(w.nodes):
         by_op.setdefault(nd.op, set()).add(k[v])
-    # weights change between replays: convolutions run the gather GEMM on the weights as they are, never a repacked copy
-    assert by_op["conv1x1"] == {"gemm_conv1x1_fwd"} and by_op["conv3x3"] == {"gemm_conv3x3_fwd"} and by_op["pool"] == {"pool3x3"}
+    # weights change between replays: convolutions read the weights as they are, never a repacked copy; with 44 and 88
+    # channels the 1 x 1 convolutions stream the pixels 128 bits at a time, forward and input gradient
+    assert by_op["conv1x1"] == {"conv1x1_px_fwd"} and by_op["conv3x3"] == {"gemm_conv3x3_fwd"} and by_op["pool"] == {"pool3x3"}
+    # the classifier (1 x 1 maps, a bias) stays on the gather GEMM, forward and backward
+    assert by_op["conv1x1_dgrad"] == {"conv1x1_px_dgrad", "gemm_conv1x1_dgrad"} and by_op["fc"] == {"gemm_conv1x1_fwd"}
+    assert sum(name == "gemm_conv1x1_dgrad" for name in k) == 1
+    assert by_op["pool_dgrad"] == {"pool3x3_dgrad_lds"}
     # 32 x 32 and 16 x 16 maps: the weight gradient reads both operands 128 bits along the pixels; the fc (1 x 1 maps) cannot
     assert by_op["conv1x1_wgrad"] == {"conv1x1_wgrad_px", "gemm_conv1x1_wgrad"}
     assert sum(name == "gemm_conv1x1_wgrad" for name in k) == 1
