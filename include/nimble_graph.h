@@ -196,8 +196,11 @@ int ng_set_memory_reuse(ng_graph* g, int on);
  * input is a convolution result is applied by that convolution's kernel, a concat whose inputs
  * were all produced in place is not launched, and weight updates (NG_OP_SGD_UPDATE) whose output no
  * node reads are carried out together by the launch of the last of them on their stream (modes 1 and
- * 2: of the last of them in the submission order; same arithmetic per element). on = 0 switches the
- * exceptions off: one kernel per task. Call before ng_bind (NG_ESTATE after). */
+ * 2: of the last of them in the submission order; same arithmetic per element), and the input gradient
+ * and the parameter gradients of a batch-norm (NG_OP_BN_ACT_DGRAD, NG_OP_BN_ACT_WGRAD with the same dy
+ * and x) are computed in one walk over dy and x by the launch of whichever of the two comes first, if
+ * both are on one stream (always, in modes 1 and 2). on = 0 switches the exceptions off: one kernel
+ * per task. Call before ng_bind (NG_ESTATE after). */
 int ng_set_launch_fusion(ng_graph* g, int on);
 /* offset[n_nodes], bytes[n_nodes] of each node's output inside the arena (host arrays). */
 int ng_get_offsets(const ng_graph* g, size_t* offset, size_t* bytes);
@@ -210,10 +213,12 @@ int ng_critical_path(const ng_graph* g, const float* t, float* total, int* path,
  * writes them, computed on the host (needs ng_plan_memory, no GPU): Section 4.1 replays the
  * recorded tasks through one graph launch, and by Appendix A that record is only safe if every
  * edge of E is ordered by the FIFO order of a stream or by a synchronised edge. fuse != 0: the
- * graph as launched by default; 0: one kernel node per task (see ng_set_launch_fusion).
+ * graph as launched by default; 0: one kernel node per task (see ng_set_launch_fusion); 2: what the
+ * single-stream modes launch instead (the launches in submission order, each behind the one before).
  *   launched_by[n_nodes] (may be NULL): the task whose kernel node writes node v's tensor - v
  *     itself, the convolution that also applies a fused batch-norm / ReLU, the later weight update
- *     of the same stream whose launch also carries out this one, -1 for a network input, -2 for a
+ *     of the same stream whose launch also carries out this one, the other half of a batch-norm's
+ *     backward pass that comes earlier on the stream, -1 for a network input, -2 for a
  *     concat that is not launched because its inputs are produced in place;
  *   src/dst[max_edges]: one entry per graph edge, as task ids (both ends have kernel nodes);
  *   *n_edges: the number of edges; with max_edges = 0 only the count is returned, a positive

@@ -218,11 +218,12 @@ def ng_set_launch_fusion(g, on: bool):
 
 
 def ng_get_graph_edges(g, fuse=True):
-    """(launched_by[n_nodes], [(src task, dst task)]) of the multi-stream HIP graph."""
+    """(launched_by[n_nodes], [(src task, dst task)]) of the multi-stream HIP graph; fuse=2: of the single-stream modes."""
     n, ne = ng_num_nodes(g), C.c_int()
-    check(g, lib.ng_get_graph_edges(g, int(bool(fuse)), None, C.byref(ne), None, None, 0))
+    fuse = 2 if fuse == 2 else int(bool(fuse))
+    check(g, lib.ng_get_graph_edges(g, fuse, None, C.byref(ne), None, None, 0))
     by, src, dst = _ints(n), _ints(ne.value), _ints(ne.value)
-    check(g, lib.ng_get_graph_edges(g, int(bool(fuse)), by, C.byref(ne), src, dst, ne.value))
+    check(g, lib.ng_get_graph_edges(g, fuse, by, C.byref(ne), src, dst, ne.value))
     return list(by[:n]), list(zip(src[:ne.value], dst[:ne.value]))
 
 

@@ -40,6 +40,7 @@ enum Kid : int {
     KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_POOL_DGRAD_LDS, KID_GAP_DGRAD,
     KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,
     KID_SGD_BATCH,                   // several update nodes in one launch (launch-based replay modes only, in no build of the resident kernel)
+    KID_BN_BACKWARD,                 // batch-norm input gradient and parameter gradients of the same (dy, x) in one launch (likewise)
     KID_COUNT
 };
 constexpr bool is_train_kernel(int kid) { return kid >= KID_GEMM_PW_FWD && kid <= KID_SGD; }
@@ -99,14 +100,14 @@ constexpr bool is_matrix_kernel(int kid_any) {
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
     return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) && !is_pool_row(kid) &&
-           !is_train_kernel(kid) && kid != KID_SGD_BATCH;
+           !is_train_kernel(kid) && kid != KID_SGD_BATCH && kid != KID_BN_BACKWARD;
 }
 // Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean
 // kernels plus the training kernels: a graph that trains runs its convolutions through the GEMM kernels, never through
 // the repacked-weight kernels of the full build).
 enum { BUILD_LEAN = 0, BUILD_FULL = 1, BUILD_TRAIN = 2 };
 constexpr bool in_build(int build, int kid) {
-    return kid == KID_SGD_BATCH ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid));
+    return (kid == KID_SGD_BATCH || kid == KID_BN_BACKWARD) ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid));
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
@@ -277,6 +278,7 @@ struct BnRawArgs {             // batch-norm with its four parameter vectors as 
     float* ws;                 // wgrad, chunks > 1: per-chunk sums [C][chunks][2]
     unsigned* cnt;             // wgrad, chunks > 1: arrivals per channel, zero between replays
     int chunks;                // wgrad: workgroups a channel's images are split over
+    float* dx;                 // bn_act_backward: the input gradient, written by the kernel of the parameter gradients
 };
 struct EltGradArgs {           // relu / global-avgpool / slice-pad / channel-sum: small elementwise backward operators
     const float* dy;

@@ -175,6 +175,7 @@ const void* timed_kernel_handle(int kid);
 const void* xcd_probe_kernel_handle();
 // ng_launch_graph.cpp
 void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, bool one_stream, std::vector<int>& fused_into);
+void make_bn_backward_task(const Task& dgrad, const Task& wgrad, Task& t);
 void make_sgd_batch_task(const std::vector<Task>& tasks, const std::vector<int>& members, std::vector<SgdTile>& table,
                          const SgdTile* table_dev, Task& t);
 void build_launch_graph(const ng_graph* g, const std::vector<Task>& tasks, const std::vector<int>& fused_into, LaunchGraph& out);

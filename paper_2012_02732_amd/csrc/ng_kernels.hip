@@ -1557,6 +1557,8 @@ NG_KERNEL(KID_GEMM_C3_DGRAD, GemmArgs, "gemm_conv3x3_dgrad", gemm_tile < GEMM_C3
 NG_KERNEL(KID_GEMM_C3_WGRAD, GemmArgs, "gemm_conv3x3_wgrad", gemm_tile < GEMM_C3_WGRAD)
 NG_KERNEL(KID_BN_RAW, BnRawArgs, "bn_act_raw", bn_raw_tile < 0)
 NG_KERNEL(KID_BN_DGRAD, BnRawArgs, "bn_act_dgrad", bn_raw_tile < 1)
+NG_KERNEL(KID_BN_WGRAD, BnRawArgs, "bn_act_wgrad", bn_wgrad_tile < false)
+NG_KERNEL(KID_BN_BACKWARD, BnRawArgs, "bn_act_backward", bn_wgrad_tile < true)
 NG_KERNEL(KID_RELU_DGRAD, EltGradArgs, "relu_dgrad", elt_grad_tile < 0)
 NG_KERNEL(KID_GAP_DGRAD, EltGradArgs, "global_avgpool_dgrad", elt_grad_tile < 1)
 NG_KERNEL(KID_SLICE_PAD, EltGradArgs, "slice_pad", elt_grad_tile < 2)
@@ -1573,7 +1575,6 @@ NG_KERNEL(KID_SLICE_PAD, EltGradArgs, "slice_pad", elt_grad_tile < 2)
     };
 NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
 NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
-NG_KERNEL0(KID_BN_WGRAD, BnRawArgs, "bn_act_wgrad", bn_wgrad_tile)
 NG_KERNEL0(KID_CHANNEL_SUM, EltGradArgs, "channel_sum", channel_sum_tile)
 NG_KERNEL0(KID_DW_DGRAD, DwGradArgs, "dwconv_dgrad", dw_dgrad_tile)
 NG_KERNEL0(KID_DW_WGRAD, DwGradArgs, "dwconv_wgrad", dw_wgrad_tile)
@@ -1600,7 +1601,7 @@ NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
     X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
-    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH)
+    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
 // different offsets): the predicates that name the type must agree with the type the kernel takes.
@@ -1948,6 +1949,18 @@ void make_sgd_batch_task(const std::vector<Task>& tasks, const std::vector<int>&
     t = Task();
     t.block[0] = kBlock;
     set_kernel<KID_SGD_BATCH>(t, SgdBatchArgs{table_dev + first}, (long)(table.size() - first));
+}
+
+// The launch that computes a batch-norm's parameter gradients (task `wgrad`) and its input gradient (task `dgrad`, same
+// dy, x and parameters) in one walk over dy and x.
+void make_bn_backward_task(const Task& dgrad, const Task& wgrad, Task& t) {
+    BnRawArgs a, d;
+    std::memcpy(&a, wgrad.args, sizeof a);
+    std::memcpy(&d, dgrad.args, sizeof d);
+    a.dx = d.y;
+    t = Task();
+    t.block[0] = kBlock;
+    set_kernel<KID_BN_BACKWARD>(t, a, wgrad.ntiles);
 }
 
 const void* resident_kernel_handle(int build) {

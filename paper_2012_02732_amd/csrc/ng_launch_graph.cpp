@@ -22,7 +22,12 @@ namespace ng {
 //   * weight updates that nothing depends on are carried out by the launch of the last such update of their stream
 //     (`one_stream`: of the whole submission order; fused_into[v] = that update). A later launch is always in order
 //     for an update: it already comes after every reader of its weights, and it keeps its place in the stream, so
-//     the last one's launch comes after everything the earlier ones waited for.
+//     the last one's launch comes after everything the earlier ones waited for;
+//   * the input gradient and the parameter gradients of a batch-norm (same dy, same x) are computed by one launch, at
+//     the place of whichever of the two tasks comes first on their stream (fused_into[the later one] = the earlier
+//     one). Both are ready when the first one is (same inputs), each tensor has its buffer to itself, and the later
+//     task's place in the stream is behind the launch, so whatever follows it in the stream or waits for its event
+//     is ordered after the launch.
 // Everything else: -1. `tasks` needs the kernel ids only (a dry task table will do).
 void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, bool one_stream, std::vector<int>& fused_into) {
     const int n = (int)g->nodes.size();
@@ -46,10 +51,30 @@ void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, boo
         for (int u : nd.preds) in_place = in_place && g->alias_of[u] == v && tasks[u].fn;
         if (in_place) fused_into[v] = v;
     }
+    const Schedule& sc = g->sched;
+    // batch-norm backward: input gradient and parameter gradients of the same (dy, x) are two walks over the same data;
+    // whichever of the two comes first on their common stream computes both
+    std::vector<int> pos(n, 0);
+    for (int i = 0; i < (int)sc.order.size(); ++i) pos[sc.order[i]] = i;
+    for (int d = 0; d < n; ++d) {
+        const Node& nd = g->nodes[d];
+        if (nd.op != NG_OP_BN_ACT_DGRAD || tasks[d].kid != KID_BN_DGRAD) continue;
+        for (int w = 0; w < n; ++w) {
+            const Node& nw = g->nodes[w];
+            if (nw.op != NG_OP_BN_ACT_WGRAD || tasks[w].kid != KID_BN_WGRAD || fused_into[w] >= 0 || nw.preds != nd.preds ||
+                nw.weights != nd.weights || nw.p.relu != nd.p.relu || nw.p.eps != nd.p.eps)
+                continue;
+            if (!one_stream && sc.stream_of[w] != sc.stream_of[d]) continue;
+            bool taken = false;                                   // w already computes another node's input gradient
+            for (int v = 0; v < n; ++v) taken = taken || fused_into[v] == w;
+            if (taken) continue;
+            if (pos[d] < pos[w]) fused_into[w] = d; else fused_into[d] = w;
+            break;
+        }
+    }
     std::vector<char> is_read(n, 0);
     for (int v = 0; v < n; ++v)
         for (int u : g->nodes[v].preds) is_read[u] = 1;
-    const Schedule& sc = g->sched;
     std::vector<int> last_update(one_stream ? 1 : sc.n_streams, -1);
     for (auto it = sc.order.rbegin(); it != sc.order.rend(); ++it) {
         const int v = *it;
@@ -132,9 +157,17 @@ extern "C" int ng_get_graph_edges(ng_graph* g, int fuse, int* launched_by, int* 
     TaskView view(g);
     if (view.rc != NG_OK) return view.rc;
     std::vector<int> fused_into;
-    decide_launch_fusion(g, g->tasks, fuse != 0, false, fused_into);
+    decide_launch_fusion(g, g->tasks, fuse != 0, fuse == 2, fused_into);
     LaunchGraph lg;
-    build_launch_graph(g, g->tasks, fused_into, lg);
+    if (fuse == 2) {                                           // one stream: every launch follows the one before it
+        for (int v : g->sched.order) {
+            if (!g->tasks[v].fn || fused_into[v] >= 0) continue;
+            lg.deps.push_back(lg.nodes.empty() ? std::vector<int>() : std::vector<int>(1, lg.nodes.back()));
+            lg.nodes.push_back(v);
+        }
+    } else {
+        build_launch_graph(g, g->tasks, fused_into, lg);
+    }
     const int n = (int)g->nodes.size();
     if (launched_by)
         for (int v = 0; v < n; ++v)

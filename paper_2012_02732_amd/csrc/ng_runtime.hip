@@ -649,6 +649,10 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
             if (u < 0) continue;
             if (g->tasks[v].kid == KID_SGD && u != v) {
                 batch[u].push_back(v);
+            } else if (g->tasks[v].kid == KID_BN_DGRAD && g->tasks[u].kid == KID_BN_WGRAD) {
+                make_bn_backward_task(g->tasks[v], g->tasks[u], out[u]);
+            } else if (g->tasks[v].kid == KID_BN_WGRAD && g->tasks[u].kid == KID_BN_DGRAD) {
+                make_bn_backward_task(g->tasks[u], g->tasks[v], out[u]);
             } else if (u != v) {
                 const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
                 const Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};

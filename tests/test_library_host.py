@@ -554,6 +554,22 @@ def test_multi_stream_graph_edges_of_a_training_graph_with_gathered_updates():
         last = launched_by[updates[0]]
         broken = [e for e in ge if e[1] != last]
         assert len(broken) < len(ge) and not _graph_order_is_safe(w, launched_by, broken)[0]
+    # What the single-stream modes launch: one launch for all updates, and a batch-norm's input gradient and parameter
+    # gradients (same dy, same x) in one launch, that of whichever of the two comes first.
+    r = GraphRunner(w)
+    sched = r.schedule()
+    r.plan()
+    launched_by, ge = B.ng_get_graph_edges(r.g, 2)
+    r.close()
+    assert _graph_order_is_safe(w, launched_by, ge)[0]
+    pos = {v: i for i, v in enumerate(sched["order"])}
+    assert len({launched_by[v] for v in updates}) == 1 and launched_by[updates[0]] == max(updates, key=lambda v: pos[v])
+    halves = [v for v in range(len(ops)) if ops[v] in ("bn_act_dgrad", "bn_act_wgrad")]
+    absorbed = [v for v in halves if launched_by[v] != v]
+    assert 2 * len(absorbed) == len(halves)
+    for v in absorbed:
+        u = launched_by[v]
+        assert {ops[v], ops[u]} == {"bn_act_dgrad", "bn_act_wgrad"} and w.nodes[v].preds == w.nodes[u].preds and pos[u] < pos[v]
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
