@@ -267,6 +267,12 @@ struct GemmArgs {
     // conv1x1_wgrad_px: the partial tiles are added up in a tree with a fan-in of 4; ws = partial tiles
     // [tiles][splits][64 * 64], then per level l >= 1 the sums [tiles][ceil(splits / 4^l)][64 * 64] down to two nodes;
     // cnt = arrivals per node, per level from level 1 on, [tiles][ceil(splits / 4^l)]
+    // conv1x1_px_fwd in the launch-based modes: a batch-norm (+ ReLU) of the result, applied while the sums are in
+    // registers and stored to bn_y next to the convolution's own result (nullptr: none); parameters as they are
+    const float* bn_gamma; const float* bn_beta; const float* bn_mean; const float* bn_var;
+    float* bn_y;
+    float bn_eps;
+    int bn_relu;
 };
 struct BnRawArgs {             // batch-norm with its four parameter vectors as they are (they change when the graph trains)
     const float* x;            // forward input

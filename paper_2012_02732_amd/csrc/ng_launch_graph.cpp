@@ -40,7 +40,9 @@ void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, boo
         const Node& nd = g->nodes[v];
         if ((nd.op != NG_OP_BN_ACT && nd.op != NG_OP_RELU) || nd.preds.size() != 1) continue;
         const int u = nd.preds[0];
-        if (!tasks[u].fn || !has_bn_epilogue(tasks[u].kid) || has_epilogue[u] || !(g->nodes[u].out == nd.out)) continue;
+        // a graph that trains: the conv1x1 kernel that streams the pixels applies a batch-norm from its raw parameters
+        const bool raw = nd.op == NG_OP_BN_ACT && tasks[v].kid == KID_BN_RAW && tasks[u].kid == KID_PW_PX_FWD;
+        if (!tasks[u].fn || !(has_bn_epilogue(tasks[u].kid) || raw) || has_epilogue[u] || !(g->nodes[u].out == nd.out)) continue;
         has_epilogue[u] = 1;
         fused_into[v] = u;
     }

@@ -653,6 +653,11 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
                 make_bn_backward_task(g->tasks[v], g->tasks[u], out[u]);
             } else if (g->tasks[v].kid == KID_BN_WGRAD && g->tasks[u].kid == KID_BN_DGRAD) {
                 make_bn_backward_task(g->tasks[u], g->tasks[v], out[u]);
+            } else if (g->tasks[v].kid == KID_BN_RAW && g->tasks[u].kid == KID_PW_PX_FWD) {
+                const BnRawArgs* bn = reinterpret_cast<const BnRawArgs*>(g->tasks[v].args);
+                GemmArgs* conv = reinterpret_cast<GemmArgs*>(out[u].args);
+                conv->bn_gamma = bn->gamma, conv->bn_beta = bn->beta, conv->bn_mean = bn->mean, conv->bn_var = bn->var;
+                conv->bn_y = bn->y, conv->bn_eps = bn->eps, conv->bn_relu = bn->relu;
             } else if (u != v) {
                 const BnArgs* bn = reinterpret_cast<const BnArgs*>(g->tasks[v].args);
                 const Epilogue ep{bn->scale, bn->shift, bn->y, bn->relu};

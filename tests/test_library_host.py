@@ -649,7 +649,10 @@ def test_training_dag_registers_schedules_and_orders_every_weight_update():
             launched_by, ge = B.ng_get_graph_edges(r.g, fuse)
             ok, why = _graph_order_is_safe(tw, launched_by, ge)
             assert ok, (tw.name, fuse, why)
-            assert all(launched_by[v] == v for v in range(n) if tw.nodes[v].op != "input")   # a graph that trains launches every task
+            others = {tw.nodes[v].op for v in range(n) if tw.nodes[v].op != "input" and launched_by[v] != v}
+            # without fusion every task has its launch; with it only weight updates (gathered per stream), the halves of a
+            # batch-norm's backward pass and a batch-norm behind a 1 x 1 convolution may ride on another task's launch
+            assert others <= ({"sgd_update", "bn_act", "bn_act_dgrad", "bn_act_wgrad"} if fuse else set()), (tw.name, fuse, others)
         plan = B.ng_resident_dry_plan(r.g)
         assert plan["ok"]
         r.close()
