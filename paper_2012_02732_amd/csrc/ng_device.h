@@ -36,7 +36,7 @@ enum Kid : int {
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
     KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
     KID_PW_PX_FWD, KID_PW_PX_DGRAD,  // conv1x1 forward / input gradient for few channels: pixels read 128 bits at a time straight into matrix-instruction operands (HW % 4 == 0)
-    KID_PW_WGRAD_PX,                 // conv1x1 weight gradient with both operands read along the pixels, 128 bits at a time (HW % 16 == 0)
+    KID_PW_WGRAD_PX, KID_PW_WGRAD_PX2,  // conv1x1 weight gradient with both operands read along the pixels, 128 bits at a time (HW % 16 == 0): blocks of 16 x 16 / 32 x 32 weights
     KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_POOL_DGRAD_LDS, KID_GAP_DGRAD,
     KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,
     KID_SGD_BATCH,                   // several update nodes in one launch (launch-based replay modes only, in no build of the resident kernel)
@@ -264,9 +264,8 @@ struct GemmArgs {
     int Cin, Cout, H, W, Ho, Wo, stride, pad;
     int tiles_n;               // tiles along N
     int splits, k_per_split;   // k_per_split a multiple of the K slice
-    // conv1x1_wgrad_px: the partial tiles are added up in a tree with a fan-in of 4; ws = partial tiles
-    // [tiles][splits][64 * 64], then per level l >= 1 the sums [tiles][ceil(splits / 4^l)][64 * 64] down to two nodes;
-    // cnt = arrivals per node, per level from level 1 on, [tiles][ceil(splits / 4^l)]
+    // conv1x1_wgrad_px: tiles_n = blocks of 16 B x 16 B weights along N; ws = partial blocks [blocks][splits][256 B B],
+    // cnt = arrivals per block
     // conv1x1_px_fwd in the launch-based modes: a batch-norm (+ ReLU) of the result, applied while the sums are in
     // registers and stored to bn_y next to the convolution's own result (nullptr: none); parameters as they are
     const float* bn_gamma; const float* bn_beta; const float* bn_mean; const float* bn_var;

@@ -1550,6 +1550,8 @@ NG_KERNEL(KID_C3_Q128, C3Args, "conv3x3_patch_64x128_wide", conv3x3_patch_tile <
 NG_KERNEL(KID_GEMM_PW_FWD, GemmArgs, "gemm_conv1x1_fwd", gemm_tile < GEMM_PW_FWD)
 NG_KERNEL(KID_GEMM_PW_DGRAD, GemmArgs, "gemm_conv1x1_dgrad", gemm_tile < GEMM_PW_DGRAD)
 NG_KERNEL(KID_GEMM_PW_WGRAD, GemmArgs, "gemm_conv1x1_wgrad", gemm_tile < GEMM_PW_WGRAD)
+NG_KERNEL(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px_16", pw_wgrad_px_tile < 1)
+NG_KERNEL(KID_PW_WGRAD_PX2, GemmArgs, "conv1x1_wgrad_px_32", pw_wgrad_px_tile < 2)
 NG_KERNEL(KID_PW_PX_FWD, GemmArgs, "conv1x1_px_fwd", pw_px_tile < GEMM_PW_FWD)
 NG_KERNEL(KID_PW_PX_DGRAD, GemmArgs, "conv1x1_px_dgrad", pw_px_tile < GEMM_PW_DGRAD)
 NG_KERNEL(KID_GEMM_C3_FWD, GemmArgs, "gemm_conv3x3_fwd", gemm_tile < GEMM_C3_FWD)
@@ -1582,7 +1584,6 @@ NG_KERNEL0(KID_POOL_DGRAD, PoolGradArgs, "pool3x3_dgrad", pool_dgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD_LDS, PoolGradArgs, "pool3x3_dgrad_lds", pool_dgrad_lds_tile)
 NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
 NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
-NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
 #undef NG_KERNEL0
 
 // every kernel id that has a tile function
@@ -1600,7 +1601,7 @@ NG_KERNEL0(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px", pw_wgrad_px_tile)
     X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
-    X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
+    X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
@@ -2157,6 +2158,7 @@ long bn_wgrad_chunks(long channels, long images) {
 // How a weight-gradient node is computed: which kernel, how K is split, what workspace it needs.
 struct WgradPlan {
     bool px = false;              // conv1x1_wgrad_px (both operands 128 bits along the pixels) instead of the gather GEMM
+    int block = 0;                // px: fragments of 16 x 16 weights along each side of a workgroup's block (1 or 2)
     long tiles = 0;
     int splits = 1, k_per_split = 0;
     size_t ws_floats = 0;         // partial tiles (and group sums)
@@ -2172,17 +2174,22 @@ WgradPlan wgrad_plan(const ng_graph* g, int v) {
     p.tiles = ceil_div(m, kGemmTile) * ceil_div(n, kGemmTile);
     const size_t tile_floats = (size_t)kGemmTile * kGemmTile;
     p.px = nd.op == NG_OP_CONV1X1_WGRAD && (dy.h * dy.w) % 16 == 0 && dy.elems() * 4 < (1L << 31) && x.elems() * 4 < (1L << 31);
+    const long fm = ceil_div(m, 16), fn = ceil_div(n, 16);
+    p.px = p.px && fm * fn <= 256;
     if (p.px) {
-        // one workgroup per split, four wavefronts each, a wavefront wants two slices of 16 pixels at least; about one
-        // workgroup per compute unit over all tiles
-        const long want = std::max<long>(1, std::min<long>(ceil_div(k, 128), std::max<long>(1, 256 / p.tiles)));
+        // blocks of B x B fragments of 16 x 16 weights, each split over K so that the task has about two workgroups per
+        // compute unit; a wavefront wants four slices of 16 pixels at least, and the last workgroup of a block adds up
+        // `splits` partial blocks
+        p.block = fm * fn <= 16 ? 1 : 2;
+        p.tiles = ceil_div(fm, p.block) * ceil_div(fn, p.block);
+        const long most = p.block == 1 ? 64 : 32;
+        const long want = std::max<long>(1, std::min<long>({ceil_div(k, 256), std::max<long>(1, 512 / p.tiles), most}));
         p.k_per_split = (int)(ceil_div(ceil_div(k, want), 64) * 64);
         p.splits = (int)ceil_div(k, p.k_per_split);
-        // the tree of sums (fan-in 4): tiles of every level but the root, one counter per node from level 1 on
-        size_t nodes = 0, counters = 0;
-        for (long width = p.splits; width > 1; width = ceil_div(width, 4)) nodes += (size_t)width, counters += (size_t)ceil_div(width, 4);
-        p.ws_floats = (size_t)p.tiles * nodes * tile_floats;
-        p.cnt_words = ((size_t)p.tiles * counters + 63) & ~(size_t)63;
+        if (p.splits > 1) {
+            p.ws_floats = (size_t)p.tiles * p.splits * 256 * p.block * p.block;
+            p.cnt_words = ((size_t)p.tiles + 63) & ~(size_t)63;
+        }
         return p;
     }
     gemm_split(m, n, k, &p.splits, &p.k_per_split);
@@ -2552,7 +2559,9 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.ws = packed;
                 a.cnt = reinterpret_cast<unsigned*>(packed + p.ws_floats);
             }
-            if (p.px) set_kernel<KID_PW_WGRAD_PX>(t, a, tiles * a.splits);
+            if (p.px) a.tiles_n = (int)ceil_div(ceil_div(a.N, 16), p.block);
+            if (p.px && p.block == 1) set_kernel<KID_PW_WGRAD_PX>(t, a, tiles * a.splits);
+            else if (p.px) set_kernel<KID_PW_WGRAD_PX2>(t, a, tiles * a.splits);
             else if (c3) set_kernel<KID_GEMM_C3_WGRAD>(t, a, tiles * a.splits);
             else set_kernel<KID_GEMM_PW_WGRAD>(t, a, tiles * a.splits);
             break;
