@@ -400,12 +400,25 @@ __device__ __forceinline__ void dwconv_tile(const DwArgs& a, int tile, float*, i
 }
 
 // ------------------------------------------------------------------------------------
-// global_avgpool: one wavefront per (n, c) plane, shuffle reduction across 64 lanes
+// global_avgpool: one wavefront per (n, c) plane, reduction across 64 lanes
 // ------------------------------------------------------------------------------------
+// Sum over the 64 lanes of a wavefront with data-parallel-primitive moves (one vector instruction per step, no trip
+// through the LDS crossbar as a shuffle takes): a scan inside each row of 16 lanes (shifts by 1, 2, 4, 8, zeros shifted
+// in) leaves a row's sum in its lane 15; lane 15 of rows 0 and 2 is then added to rows 1 and 3, lane 31 to rows 2 and 3,
+// and lane 63 holds the total, which every lane gets back. The order of the additions is fixed.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROW_MASK, 0xf, true);
+    return v + __builtin_bit_cast(float, moved);
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-    return v;
+    v = dpp_add<0x111, 0xf>(v);                              // row_shr:1
+    v = dpp_add<0x112, 0xf>(v);                              // row_shr:2
+    v = dpp_add<0x114, 0xf>(v);                              // row_shr:4
+    v = dpp_add<0x118, 0xf>(v);                              // row_shr:8
+    v = dpp_add<0x142, 0xa>(v);                              // row_bcast:15 into rows 1 and 3
+    v = dpp_add<0x143, 0xc>(v);                              // row_bcast:31 into rows 2 and 3
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 
 template <bool FIN, class Wait>
@@ -2151,10 +2164,11 @@ bool wgrad_dims(const ng_graph* g, int v, long* m, long* n, long* k) {
     return true;
 }
 // Workgroups a channel of a batch-norm or depthwise parameter gradient is split over (by images): about 512 workgroups in all
-long bn_wgrad_chunks(long channels, long images) {
-    const long want = std::max<long>(1, std::min<long>(images, ceil_div(512, channels)));
+long bn_wgrad_chunks(long channels, long images, long workgroups = 512) {
+    const long want = std::max<long>(1, std::min<long>(images, ceil_div(workgroups, channels)));
     return ceil_div(images, ceil_div(images, want));            // no empty chunk
 }
+long dw_wgrad_chunks(long channels, long images) { return bn_wgrad_chunks(channels, images, knob_int("NG_DW_WGRAD_WGS", 1, 4096, 512)); }
 // How a weight-gradient node is computed: which kernel, how K is split, what workspace it needs.
 struct WgradPlan {
     bool px = false;              // conv1x1_wgrad_px (both operands 128 bits along the pixels) instead of the gather GEMM
@@ -2210,7 +2224,7 @@ size_t packed_floats(const ng_graph* g, int v) {
     }
     if (nd.op == NG_OP_DWCONV_WGRAD) {                         // per-chunk partial sums [C][chunks][K K] (padded), then one arrival counter per channel
         const Shape& x = g->nodes[nd.preds[1]].out;
-        const long chunks = bn_wgrad_chunks(x.c, x.n);
+        const long chunks = dw_wgrad_chunks(x.c, x.n);
         return chunks > 1 ? (size_t)((x.c * chunks * nd.p.k * nd.p.k + 63) & ~63L) + (size_t)((x.c + 63) & ~63L) : 0;
     }
     if (nd.op == NG_OP_BN_ACT_WGRAD) {                         // per-chunk sums [C][chunks][2] (padded), then one arrival counter per channel
@@ -2620,7 +2634,7 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.w = wf(0);
                 set_kernel<KID_DW_DGRAD>(t, a, ceil_div(a.total, kBlock));
             } else {
-                a.chunks = (int)bn_wgrad_chunks(a.C, a.N);
+                a.chunks = (int)dw_wgrad_chunks(a.C, a.N);
                 if (a.chunks > 1) {
                     if (!packed) return g->fail(NG_EINVAL, "node %d: no workspace for the per-chunk partial sums", v);
                     a.ws = packed;
