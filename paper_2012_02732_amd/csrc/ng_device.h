@@ -36,6 +36,7 @@ enum Kid : int {
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
     KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
     KID_PW_PX_FWD, KID_PW_PX_DGRAD,  // conv1x1 forward / input gradient for few channels: pixels read 128 bits at a time straight into matrix-instruction operands (HW % 4 == 0)
+    KID_C3_WGRAD_PX, KID_C3_WGRAD_PX2,  // the same for conv3x3 (stride 1, padding 1, rows of a multiple of 16 pixels): the second operand is the input shifted by the tap
     KID_PW_WGRAD_PX, KID_PW_WGRAD_PX2,  // conv1x1 weight gradient with both operands read along the pixels, 128 bits at a time (HW % 16 == 0): blocks of 16 x 16 / 32 x 32 weights
     KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_POOL_DGRAD_LDS, KID_GAP_DGRAD,
     KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,

@@ -1563,8 +1563,10 @@ NG_KERNEL(KID_C3_Q128, C3Args, "conv3x3_patch_64x128_wide", conv3x3_patch_tile <
 NG_KERNEL(KID_GEMM_PW_FWD, GemmArgs, "gemm_conv1x1_fwd", gemm_tile < GEMM_PW_FWD)
 NG_KERNEL(KID_GEMM_PW_DGRAD, GemmArgs, "gemm_conv1x1_dgrad", gemm_tile < GEMM_PW_DGRAD)
 NG_KERNEL(KID_GEMM_PW_WGRAD, GemmArgs, "gemm_conv1x1_wgrad", gemm_tile < GEMM_PW_WGRAD)
-NG_KERNEL(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px_16", pw_wgrad_px_tile < 1)
-NG_KERNEL(KID_PW_WGRAD_PX2, GemmArgs, "conv1x1_wgrad_px_32", pw_wgrad_px_tile < 2)
+NG_KERNEL(KID_PW_WGRAD_PX, GemmArgs, "conv1x1_wgrad_px_16", pw_wgrad_px_tile < 1, false)
+NG_KERNEL(KID_PW_WGRAD_PX2, GemmArgs, "conv1x1_wgrad_px_32", pw_wgrad_px_tile < 2, false)
+NG_KERNEL(KID_C3_WGRAD_PX, GemmArgs, "conv3x3_wgrad_px_16", pw_wgrad_px_tile < 1, true)
+NG_KERNEL(KID_C3_WGRAD_PX2, GemmArgs, "conv3x3_wgrad_px_32", pw_wgrad_px_tile < 2, true)
 NG_KERNEL(KID_PW_PX_FWD, GemmArgs, "conv1x1_px_fwd", pw_px_tile < GEMM_PW_FWD)
 NG_KERNEL(KID_PW_PX_DGRAD, GemmArgs, "conv1x1_px_dgrad", pw_px_tile < GEMM_PW_DGRAD)
 NG_KERNEL(KID_GEMM_C3_FWD, GemmArgs, "gemm_conv3x3_fwd", gemm_tile < GEMM_C3_FWD)
@@ -1614,7 +1616,7 @@ NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
     X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
-    X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
+    X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_C3_WGRAD_PX) X(KID_C3_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
@@ -2187,7 +2189,8 @@ WgradPlan wgrad_plan(const ng_graph* g, int v) {
     const Shape& x = g->nodes[nd.preds[1]].out;
     p.tiles = ceil_div(m, kGemmTile) * ceil_div(n, kGemmTile);
     const size_t tile_floats = (size_t)kGemmTile * kGemmTile;
-    p.px = nd.op == NG_OP_CONV1X1_WGRAD && (dy.h * dy.w) % 16 == 0 && dy.elems() * 4 < (1L << 31) && x.elems() * 4 < (1L << 31);
+    p.px = (dy.h * dy.w) % 16 == 0 && dy.elems() * 4 < (1L << 31) && x.elems() * 4 < (1L << 31) &&
+           (nd.op == NG_OP_CONV1X1_WGRAD || (nd.p.stride == 1 && nd.p.pad == 1 && dy.w % 16 == 0 && dy.h == x.h && dy.w == x.w));
     const long fm = ceil_div(m, 16), fn = ceil_div(n, 16);
     p.px = p.px && fm * fn <= 256;
     if (p.px) {
@@ -2574,7 +2577,9 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.cnt = reinterpret_cast<unsigned*>(packed + p.ws_floats);
             }
             if (p.px) a.tiles_n = (int)ceil_div(ceil_div(a.N, 16), p.block);
-            if (p.px && p.block == 1) set_kernel<KID_PW_WGRAD_PX>(t, a, tiles * a.splits);
+            if (p.px && c3 && p.block == 1) set_kernel<KID_C3_WGRAD_PX>(t, a, tiles * a.splits);
+            else if (p.px && c3) set_kernel<KID_C3_WGRAD_PX2>(t, a, tiles * a.splits);
+            else if (p.px && p.block == 1) set_kernel<KID_PW_WGRAD_PX>(t, a, tiles * a.splits);
             else if (p.px) set_kernel<KID_PW_WGRAD_PX2>(t, a, tiles * a.splits);
             else if (c3) set_kernel<KID_GEMM_C3_WGRAD>(t, a, tiles * a.splits);
             else set_kernel<KID_GEMM_PW_WGRAD>(t, a, tiles * a.splits);

@@ -104,9 +104,9 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
             base = 2.0, per_tile = 0.04 * a->k_per_split;             // per K slice of 16: gathered loads, LDS fill, 16 MFMAs per wavefront
             break;
         }
-        case KID_PW_WGRAD_PX: case KID_PW_WGRAD_PX2: {
+        case KID_PW_WGRAD_PX: case KID_PW_WGRAD_PX2: case KID_C3_WGRAD_PX: case KID_C3_WGRAD_PX2: {
             const GemmArgs* a = reinterpret_cast<const GemmArgs*>(g->tasks[v].args);
-            base = 4.0, per_tile = (kid == KID_PW_WGRAD_PX ? 0.001 : 0.002) * a->k_per_split;   // 4 or 16 MFMAs per wavefront and slice of 16 pixels, four wavefronts side by side; then the sum
+            base = 4.0, per_tile = ((kid == KID_PW_WGRAD_PX || kid == KID_C3_WGRAD_PX) ? 0.001 : 0.002) * a->k_per_split;   // 4 or 16 MFMAs per wavefront and slice of 16 pixels, four wavefronts side by side; then the sum
             break;
         }
         case KID_BN_RAW: case KID_BN_DGRAD: case KID_RELU_DGRAD: case KID_GAP_DGRAD: case KID_SLICE_PAD: case KID_SGD: base = 1.2, per_tile = 0.15; break;

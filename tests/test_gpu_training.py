@@ -196,6 +196,31 @@ def test_training_pool_backward_plane_sizes(shape, kernel):
     check_training(fwd, seeds, 0.01, (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT), end_to_end=False)
 
 
+@pytest.mark.parametrize("shape,cout,kernel", [((2, 3, 16, 16), 7, "conv3x3_wgrad_px_16"), ((3, 5, 8, 32), 44, "conv3x3_wgrad_px_16"),
+                                               ((1, 20, 16, 48), 40, "conv3x3_wgrad_px_32"), ((2, 3, 12, 20), 9, "gemm_conv3x3_wgrad")])
+def test_training_conv3x3_weight_gradient_kernels(shape, cout, kernel):
+    """conv3x3 weight gradient, stride 1 and padding 1: rows of a multiple of 16 pixels read the shifted input planes
+    128 bits at a time (both block sizes, row ends, first and last row, ragged channel counts); other widths take the
+    gather GEMM."""
+    from workloads.model import Builder
+    b = Builder("conv3x3_wgrad")
+    x = b.input(*shape)
+    c = b.bn_act(b.conv3x3(x, cout, 1, 1), relu=True)
+    f = b.fc(b.global_avgpool(c), 5)
+    rng = np.random.default_rng(6)
+    b.draw_weights(rng, 0.3, "random")
+    fwd = b.finish(rng, outputs=[f])
+    seeds = {f: rng.standard_normal(fwd.nodes[f].shape).astype(np.float32)}
+    tw = workloads.training_graph(fwd, 0.01, seeds)
+    r = GraphRunner(tw)
+    r.schedule()
+    r.plan()
+    names = {B.ng_planned_task_kernel(r.g, v) for v, nd in enumerate(tw.nodes) if nd.op == "conv3x3_wgrad"}
+    r.close()
+    assert names == {kernel}, names
+    check_training(fwd, seeds, 0.01, (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT), end_to_end=False)
+
+
 def test_training_step_nas_cell_batch32_cifar():
     """The paper's training setting: batch 32, 32 x 32 inputs. One normal and one reduction cell of the
     NASNet-style recipe between a 3x3 stem and a 10-way classifier; 259 tasks in one DAG."""

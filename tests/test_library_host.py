@@ -804,4 +804,5 @@ def test_kernel_choice_in_a_training_graph():
     assert by_op["pool_dgrad"] == {"pool3x3_dgrad_lds"}
     # 32 x 32 and 16 x 16 maps: the weight gradient reads both operands 128 bits along the pixels; the fc (1 x 1 maps) cannot
     assert by_op["conv1x1_wgrad"] == {"conv1x1_wgrad_px_16", "conv1x1_wgrad_px_32", "gemm_conv1x1_wgrad"}
+    assert by_op["conv3x3_wgrad"] == {"conv3x3_wgrad_px_16"}         # the stem: 44 x 27 weights, rows of 32 pixels
     assert sum(name == "gemm_conv1x1_wgrad" for name in k) == 1
