@@ -42,6 +42,9 @@ enum Kid : int {
     KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,
     KID_SGD_BATCH,                   // several update nodes in one launch (launch-based replay modes only, in no build of the resident kernel)
     KID_BN_BACKWARD,                 // batch-norm input gradient and parameter gradients of the same (dy, x) in one launch (likewise)
+    // two tasks that read the same gradient, in one launch with their workgroups interleaved (likewise): depthwise input and
+    // weight gradient; conv1x1 input gradient with the weight gradient in blocks of 16 x 16 / 32 x 32
+    KID_PAIR_DW, KID_PAIR_PW16, KID_PAIR_PW32,
     KID_COUNT
 };
 constexpr bool is_train_kernel(int kid) { return kid >= KID_GEMM_PW_FWD && kid <= KID_SGD; }
@@ -101,20 +104,21 @@ constexpr bool is_matrix_kernel(int kid_any) {
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
     return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) && !is_pool_row(kid) &&
-           !is_train_kernel(kid) && kid != KID_SGD_BATCH && kid != KID_BN_BACKWARD;
+           !is_train_kernel(kid) && !(kid >= KID_SGD_BATCH && kid <= KID_PAIR_PW32);
 }
 // Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean
 // kernels plus the training kernels: a graph that trains runs its convolutions through the GEMM kernels, never through
 // the repacked-weight kernels of the full build).
 enum { BUILD_LEAN = 0, BUILD_FULL = 1, BUILD_TRAIN = 2 };
 constexpr bool in_build(int build, int kid) {
-    return (kid == KID_SGD_BATCH || kid == KID_BN_BACKWARD) ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid));
+    return (kid >= KID_SGD_BATCH && kid <= KID_PAIR_PW32) ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid));
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
 constexpr int kSubs = 2;             // tiles a workgroup of the resident kernel works on at a time
 constexpr int kGroup = kBlock * kSubs;  // threads per workgroup of the resident kernel
-constexpr int kArgBytes = 256;       // size of the per-task argument block
+constexpr int kArgBytes = 256;       // size of the per-task argument block of the resident kernel's task table
+constexpr int kLaunchArgBytes = 384; // size of a launched kernel's argument block (a launch of two tasks carries both blocks)
 
 // ---- argument blocks (plain data, <= kArgBytes) ---------------------------------------
 struct BnArgs {
@@ -330,6 +334,14 @@ struct SgdTile {
 };
 struct SgdBatchArgs {
     const SgdTile* tiles;      // [ntiles]
+};
+
+// Two tasks in one launch: tiles of both, dealt out alternately while both have tiles left.
+template <class A, class B>
+struct PairArgs {
+    A a;
+    B b;
+    int na, nb;                // tiles of the first and of the second task
 };
 
 // ---- device-resident replay: the task schedule as data in device memory -------------------

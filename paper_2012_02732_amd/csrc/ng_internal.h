@@ -57,7 +57,7 @@ struct Task {
     unsigned grid[3] = {1, 1, 1};
     unsigned block[3] = {1, 1, 1};
     unsigned lds_bytes = 0;
-    alignas(16) unsigned char args[256];       // the kernel's single by-value argument struct
+    alignas(16) unsigned char args[kLaunchArgBytes];   // the kernel's single by-value argument struct
     unsigned args_bytes = 0;
 };
 
@@ -176,6 +176,8 @@ const void* xcd_probe_kernel_handle();
 // ng_launch_graph.cpp
 void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, bool fuse, bool one_stream, std::vector<int>& fused_into);
 void make_bn_backward_task(const Task& dgrad, const Task& wgrad, Task& t);
+bool can_pair(int kid_first, int kid_second);
+void make_pair_task(const Task& first, const Task& second, Task& t);
 void make_sgd_batch_task(const std::vector<Task>& tasks, const std::vector<int>& members, std::vector<SgdTile>& table,
                          const SgdTile* table_dev, Task& t);
 void build_launch_graph(const ng_graph* g, const std::vector<Task>& tasks, const std::vector<int>& fused_into, LaunchGraph& out);

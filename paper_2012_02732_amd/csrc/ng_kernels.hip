@@ -1598,6 +1598,33 @@ NG_KERNEL0(KID_DW_WGRAD, DwGradArgs, "dwconv_wgrad", dw_wgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD, PoolGradArgs, "pool3x3_dgrad", pool_dgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD_LDS, PoolGradArgs, "pool3x3_dgrad_lds", pool_dgrad_lds_tile)
 NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
+// Two tasks in one launch (they read the same tensor and neither waits for the other): the workgroups of both are dealt
+// out alternately while both have tiles left, so that the two - each bound by latency rather than by bandwidth when it runs
+// alone - share the compute units from the start.
+template <int KA, int KB, bool FIN, class Wait>
+__device__ __forceinline__ void pair_tile(const PairArgs<typename KernelOf<KA>::Args, typename KernelOf<KB>::Args>& p, int tile, float* smem,
+                                          int tid, bool live, Wait& wait) {
+    const int fewer = min(p.na, p.nb);
+    const bool first = tile < 2 * fewer ? (tile & 1) == 0 : p.na > p.nb;
+    const int t = tile < 2 * fewer ? tile >> 1 : tile - fewer;
+    if (first) KernelOf<KA>::template tile<FIN>(p.a, t, smem, tid, live, wait);
+    else KernelOf<KB>::template tile<FIN>(p.b, t, smem, tid, live, wait);
+}
+using PairDwArgs = PairArgs<DwGradArgs, DwGradArgs>;
+using PairPwArgs = PairArgs<GemmArgs, GemmArgs>;
+#define NG_PAIR(KID, ARGS, NAME, KA, KB)                                                       \
+    template <> struct KernelOf<KID> {                                                         \
+        using Args = ARGS;                                                                     \
+        static constexpr const char* name = NAME;                                              \
+        template <bool FIN, class Wait>                                                        \
+        static __device__ __forceinline__ void tile(const ARGS& a, int t, float* smem, int tid, bool live, Wait& wait) { \
+            pair_tile<KA, KB, FIN>(a, t, smem, tid, live, wait);                               \
+        }                                                                                      \
+    };
+NG_PAIR(KID_PAIR_DW, PairDwArgs, "dwconv_dgrad+wgrad", KID_DW_DGRAD, KID_DW_WGRAD)
+NG_PAIR(KID_PAIR_PW16, PairPwArgs, "conv1x1_px_dgrad+wgrad_16", KID_PW_PX_DGRAD, KID_PW_WGRAD_PX)
+NG_PAIR(KID_PAIR_PW32, PairPwArgs, "conv1x1_px_dgrad+wgrad_32", KID_PW_PX_DGRAD, KID_PW_WGRAD_PX2)
+#undef NG_PAIR
 NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
 #undef NG_KERNEL0
 
@@ -1617,7 +1644,7 @@ NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
     X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_C3_WGRAD_PX) X(KID_C3_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
-    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD)
+    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD) X(KID_PAIR_DW) X(KID_PAIR_PW16) X(KID_PAIR_PW32)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
 // different offsets): the predicates that name the type must agree with the type the kernel takes.
@@ -1859,7 +1886,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
             switch (kid) {
 #define NG_CASE(KID)                                                                                                         \
     case KID:                                                                                                                \
-        if (in_build(BUILD, KID)) {                                                                                          \
+        if constexpr (in_build(BUILD, KID)) {                                                                                \
             CounterWait<has_add_epilogue(KID)> wait{plan, rec, &s_abort, &s_late, epoch, task, np, n_late, lane, stamp, true, true, far_out}; \
             run_tiles<KID>(rec + 24, tile0, step, ntiles, subs, smem, sub, tid, far_in, wait);                               \
         }                                                                                                                    \
@@ -1909,7 +1936,7 @@ __global__ __launch_bounds__(kGroup) void resident_kernel(DevPlan plan, unsigned
 template <int KID>
 void set_kernel(Task& t, const typename KernelOf<KID>::Args& a, long ntiles) {
     using A = typename KernelOf<KID>::Args;
-    static_assert(sizeof(A) <= kArgBytes, "argument block too large");
+    static_assert(sizeof(A) <= kLaunchArgBytes, "argument block too large");
     static_assert(std::is_trivially_copyable<A>::value, "argument block must be plain data");
     t.kid = KID;
     t.fn = reinterpret_cast<const void*>(&standalone_kernel<KID>);
@@ -1965,6 +1992,33 @@ void make_sgd_batch_task(const std::vector<Task>& tasks, const std::vector<int>&
     t = Task();
     t.block[0] = kBlock;
     set_kernel<KID_SGD_BATCH>(t, SgdBatchArgs{table_dev + first}, (long)(table.size() - first));
+}
+
+// Which two stand-alone kernels have a launch of their own together (pair_tile): input gradient first, weight gradient second.
+static int pair_kid(int kid_first, int kid_second) {
+    if (kid_first == KID_DW_DGRAD && kid_second == KID_DW_WGRAD) return KID_PAIR_DW;
+    if (kid_first == KID_PW_PX_DGRAD && kid_second == KID_PW_WGRAD_PX) return KID_PAIR_PW16;
+    if (kid_first == KID_PW_PX_DGRAD && kid_second == KID_PW_WGRAD_PX2) return KID_PAIR_PW32;
+    return KID_NONE;
+}
+bool can_pair(int kid_first, int kid_second) { return pair_kid(kid_first, kid_second) != KID_NONE; }
+template <int KID>
+static void set_pair(const Task& first, const Task& second, Task& t) {
+    typename KernelOf<KID>::Args p{};
+    std::memcpy(&p.a, first.args, sizeof p.a);
+    std::memcpy(&p.b, second.args, sizeof p.b);
+    p.na = (int)first.ntiles, p.nb = (int)second.ntiles;
+    t = Task();
+    t.block[0] = kBlock;
+    set_kernel<KID>(t, p, first.ntiles + second.ntiles);
+}
+void make_pair_task(const Task& first, const Task& second, Task& t) {
+    switch (pair_kid(first.kid, second.kid)) {
+        case KID_PAIR_DW: set_pair<KID_PAIR_DW>(first, second, t); break;
+        case KID_PAIR_PW16: set_pair<KID_PAIR_PW16>(first, second, t); break;
+        case KID_PAIR_PW32: set_pair<KID_PAIR_PW32>(first, second, t); break;
+        default: t = first; break;
+    }
 }
 
 // The launch that computes a batch-norm's parameter gradients (task `wgrad`) and its input gradient (task `dgrad`, same

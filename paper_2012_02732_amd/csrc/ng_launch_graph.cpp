@@ -74,6 +74,27 @@ void decide_launch_fusion(const ng_graph* g, const std::vector<Task>& tasks, boo
             break;
         }
     }
+    // the input gradient and the weight gradient of a depthwise or 1 x 1 convolution read the same dy and are each bound by
+    // latency when alone: one launch with their workgroups interleaved, at the place of whichever comes first - if
+    // everything the later one reads is complete by then (its inputs all come before the earlier one on the stream)
+    for (int d = 0; d < n; ++d) {
+        const Node& nd = g->nodes[d];
+        if ((nd.op != NG_OP_DWCONV_DGRAD && nd.op != NG_OP_CONV1X1_DGRAD) || !tasks[d].fn || fused_into[d] >= 0) continue;
+        for (int w = 0; w < n; ++w) {
+            const Node& nw = g->nodes[w];
+            if (nw.op != (nd.op == NG_OP_DWCONV_DGRAD ? NG_OP_DWCONV_WGRAD : NG_OP_CONV1X1_WGRAD) || !tasks[w].fn || fused_into[w] >= 0 ||
+                nw.preds.empty() || nd.preds.empty() || nw.preds[0] != nd.preds[0] || !can_pair(tasks[d].kid, tasks[w].kid))
+                continue;
+            if (!one_stream && sc.stream_of[w] != sc.stream_of[d]) continue;
+            const int early = pos[d] < pos[w] ? d : w, late = early == d ? w : d;
+            bool ready = true, taken = false;
+            for (int u : g->nodes[late].preds) ready = ready && pos[u] < pos[early] && (one_stream || sc.stream_of[u] == sc.stream_of[early]);
+            for (int v = 0; v < n; ++v) taken = taken || fused_into[v] == w || fused_into[v] == d;
+            if (!ready || taken) continue;
+            fused_into[late] = early;
+            break;
+        }
+    }
     std::vector<char> is_read(n, 0);
     for (int v = 0; v < n; ++v)
         for (int u : g->nodes[v].preds) is_read[u] = 1;

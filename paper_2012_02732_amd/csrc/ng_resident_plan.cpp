@@ -554,7 +554,8 @@ int plan_resident(const ng_graph* g, int n_wg, int xcds, const PlanKnobs& knobs,
         if (!t.fn) continue;
         d.kid = best.kid[v];
         d.ntiles = (int)best.ntiles[v];
-        std::memcpy(d.args, t.args, sizeof t.args);
+        static_assert(sizeof d.args <= sizeof t.args, "argument blocks");
+        std::memcpy(d.args, t.args, sizeof d.args);
     }
     // A tensor crosses XCDs when a direct reader (any edge of E, not only E') runs elsewhere.
     for (int v = 0; v < n; ++v) {

@@ -653,6 +653,10 @@ int ng_bind(ng_graph* g, void* arena, size_t arena_bytes, void* const* hip_strea
                 make_bn_backward_task(g->tasks[v], g->tasks[u], out[u]);
             } else if (g->tasks[v].kid == KID_BN_WGRAD && g->tasks[u].kid == KID_BN_DGRAD) {
                 make_bn_backward_task(g->tasks[u], g->tasks[v], out[u]);
+            } else if (can_pair(g->tasks[u].kid, g->tasks[v].kid)) {
+                make_pair_task(g->tasks[u], g->tasks[v], out[u]);
+            } else if (can_pair(g->tasks[v].kid, g->tasks[u].kid)) {
+                make_pair_task(g->tasks[v], g->tasks[u], out[u]);
             } else if (g->tasks[v].kid == KID_BN_RAW && g->tasks[u].kid == KID_PW_PX_FWD) {
                 const BnRawArgs* bn = reinterpret_cast<const BnRawArgs*>(g->tasks[v].args);
                 GemmArgs* conv = reinterpret_cast<GemmArgs*>(out[u].args);
@@ -1112,8 +1116,8 @@ static bool executed_task(const ng_graph* g, int id, int mode, Task& out, const 
     out = Task();
     out.fn = fn, out.name = nm, out.kid = d.kid, out.ntiles = d.ntiles;
     out.grid[0] = (unsigned)d.ntiles, out.block[0] = kBlock;
-    static_assert(sizeof out.args == sizeof d.args, "argument blocks");
-    std::memcpy(out.args, d.args, sizeof out.args);
+    static_assert(sizeof out.args >= sizeof d.args, "argument blocks");
+    std::memcpy(out.args, d.args, sizeof d.args);
     if (name) *name = nm;
     return true;
 }
