@@ -38,13 +38,13 @@ enum Kid : int {
     KID_PW_PX_FWD, KID_PW_PX_DGRAD,  // conv1x1 forward / input gradient for few channels: pixels read 128 bits at a time straight into matrix-instruction operands (HW % 4 == 0)
     KID_C3_WGRAD_PX, KID_C3_WGRAD_PX2,  // the same for conv3x3 (stride 1, padding 1, rows of a multiple of 16 pixels): the second operand is the input shifted by the tap
     KID_PW_WGRAD_PX, KID_PW_WGRAD_PX2,  // conv1x1 weight gradient with both operands read along the pixels, 128 bits at a time (HW % 16 == 0): blocks of 16 x 16 / 32 x 32 weights
-    KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_WGRAD, KID_POOL_DGRAD, KID_POOL_DGRAD_LDS, KID_GAP_DGRAD,
+    KID_BN_RAW, KID_BN_DGRAD, KID_BN_WGRAD, KID_RELU_DGRAD, KID_DW_DGRAD, KID_DW_DGRAD_LDS, KID_DW_WGRAD, KID_POOL_DGRAD, KID_POOL_DGRAD_LDS, KID_GAP_DGRAD,
     KID_CHANNEL_SUM, KID_SLICE_PAD, KID_SGD,
     KID_SGD_BATCH,                   // several update nodes in one launch (launch-based replay modes only, in no build of the resident kernel)
     KID_BN_BACKWARD,                 // batch-norm input gradient and parameter gradients of the same (dy, x) in one launch (likewise)
     // two tasks that read the same gradient, in one launch with their workgroups interleaved (likewise): depthwise input and
     // weight gradient; conv1x1 input gradient with the weight gradient in blocks of 16 x 16 / 32 x 32
-    KID_PAIR_DW, KID_PAIR_PW16, KID_PAIR_PW32,
+    KID_PAIR_DW, KID_PAIR_DW_LDS, KID_PAIR_PW16, KID_PAIR_PW32,
     KID_COUNT
 };
 constexpr bool is_train_kernel(int kid) { return kid >= KID_GEMM_PW_FWD && kid <= KID_SGD; }
@@ -287,7 +287,7 @@ struct BnRawArgs {             // batch-norm with its four parameter vectors as 
     int relu, C, HW, N, total;
     float* ws;                 // wgrad, chunks > 1: per-chunk sums [C][chunks][2]
     unsigned* cnt;             // wgrad, chunks > 1: arrivals per channel, zero between replays
-    int chunks;                // wgrad: workgroups a channel's images are split over
+    int chunks;                // wgrad: workgroups a channel's images are split over; dwconv_dgrad_lds: planes per workgroup
     float* dx;                 // bn_act_backward: the input gradient, written by the kernel of the parameter gradients
 };
 struct EltGradArgs {           // relu / global-avgpool / slice-pad / channel-sum: small elementwise backward operators
@@ -304,7 +304,7 @@ struct DwGradArgs {            // depthwise backward; C, H, W, Ho, Wo, K, S of t
     int N, C, H, W, Ho, Wo, K, S, total;
     float* ws;                 // wgrad, chunks > 1: per-chunk partial sums [C][chunks][K K]
     unsigned* cnt;             // wgrad, chunks > 1: arrivals per channel, zero between replays
-    int chunks;                // wgrad: workgroups a channel's images are split over
+    int chunks;                // wgrad: workgroups a channel's images are split over; dwconv_dgrad_lds: planes per workgroup
 };
 struct PoolGradArgs {          // pool backward; geometry of the FORWARD operator
     const float* dy; const float* x;

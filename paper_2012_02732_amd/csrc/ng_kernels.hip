@@ -1594,6 +1594,7 @@ NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
 NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
 NG_KERNEL0(KID_CHANNEL_SUM, EltGradArgs, "channel_sum", channel_sum_tile)
 NG_KERNEL0(KID_DW_DGRAD, DwGradArgs, "dwconv_dgrad", dw_dgrad_tile)
+NG_KERNEL0(KID_DW_DGRAD_LDS, DwGradArgs, "dwconv_dgrad_lds", dw_dgrad_lds_tile)
 NG_KERNEL0(KID_DW_WGRAD, DwGradArgs, "dwconv_wgrad", dw_wgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD, PoolGradArgs, "pool3x3_dgrad", pool_dgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD_LDS, PoolGradArgs, "pool3x3_dgrad_lds", pool_dgrad_lds_tile)
@@ -1622,6 +1623,7 @@ using PairPwArgs = PairArgs<GemmArgs, GemmArgs>;
         }                                                                                      \
     };
 NG_PAIR(KID_PAIR_DW, PairDwArgs, "dwconv_dgrad+wgrad", KID_DW_DGRAD, KID_DW_WGRAD)
+NG_PAIR(KID_PAIR_DW_LDS, PairDwArgs, "dwconv_dgrad_lds+wgrad", KID_DW_DGRAD_LDS, KID_DW_WGRAD)
 NG_PAIR(KID_PAIR_PW16, PairPwArgs, "conv1x1_px_dgrad+wgrad_16", KID_PW_PX_DGRAD, KID_PW_WGRAD_PX)
 NG_PAIR(KID_PAIR_PW32, PairPwArgs, "conv1x1_px_dgrad+wgrad_32", KID_PW_PX_DGRAD, KID_PW_WGRAD_PX2)
 #undef NG_PAIR
@@ -1643,8 +1645,8 @@ NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
     X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
-    X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_C3_WGRAD_PX) X(KID_C3_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD)                \
-    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD) X(KID_PAIR_DW) X(KID_PAIR_PW16) X(KID_PAIR_PW32)
+    X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_C3_WGRAD_PX) X(KID_C3_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD) X(KID_DW_DGRAD_LDS)                \
+    X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD) X(KID_PAIR_DW) X(KID_PAIR_DW_LDS) X(KID_PAIR_PW16) X(KID_PAIR_PW32)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
 // different offsets): the predicates that name the type must agree with the type the kernel takes.
@@ -1997,6 +1999,7 @@ void make_sgd_batch_task(const std::vector<Task>& tasks, const std::vector<int>&
 // Which two stand-alone kernels have a launch of their own together (pair_tile): input gradient first, weight gradient second.
 static int pair_kid(int kid_first, int kid_second) {
     if (kid_first == KID_DW_DGRAD && kid_second == KID_DW_WGRAD) return KID_PAIR_DW;
+    if (kid_first == KID_DW_DGRAD_LDS && kid_second == KID_DW_WGRAD) return KID_PAIR_DW_LDS;
     if (kid_first == KID_PW_PX_DGRAD && kid_second == KID_PW_WGRAD_PX) return KID_PAIR_PW16;
     if (kid_first == KID_PW_PX_DGRAD && kid_second == KID_PW_WGRAD_PX2) return KID_PAIR_PW32;
     return KID_NONE;
@@ -2015,6 +2018,7 @@ static void set_pair(const Task& first, const Task& second, Task& t) {
 void make_pair_task(const Task& first, const Task& second, Task& t) {
     switch (pair_kid(first.kid, second.kid)) {
         case KID_PAIR_DW: set_pair<KID_PAIR_DW>(first, second, t); break;
+        case KID_PAIR_DW_LDS: set_pair<KID_PAIR_DW_LDS>(first, second, t); break;
         case KID_PAIR_PW16: set_pair<KID_PAIR_PW16>(first, second, t); break;
         case KID_PAIR_PW32: set_pair<KID_PAIR_PW32>(first, second, t); break;
         default: t = first; break;
@@ -2691,6 +2695,15 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.K = nd.p.k, a.S = nd.p.stride, a.total = (int)x.elems();
             if (nd.op == NG_OP_DWCONV_DGRAD) {
                 a.w = wf(0);
+                const long plane = (long)a.H * a.W, planes = a.total / plane;
+                const int bd = a.K / 2;
+                const long per_wg = plane <= 1024 ? 1024 / plane : 0;
+                if ((a.K == 3 || a.K == 5) && (a.S == 1 || a.S == 2) && a.W % 4 == 0 && a.Wo % 4 == 0 && per_wg > 0 &&
+                    (long)a.Ho * a.Wo <= plane && per_wg * (a.Ho + 2 * bd) * (a.Wo + 2 * bd) <= kSmemFloats) {
+                    a.chunks = (int)per_wg;                        // whole planes of dx per workgroup, their dy staged in LDS
+                    set_kernel<KID_DW_DGRAD_LDS>(t, a, ceil_div(planes, per_wg));
+                    break;
+                }
                 set_kernel<KID_DW_DGRAD>(t, a, ceil_div(a.total, kBlock));
             } else {
                 a.chunks = (int)dw_wgrad_chunks(a.C, a.N);

@@ -221,6 +221,32 @@ def test_training_conv3x3_weight_gradient_kernels(shape, cout, kernel):
     check_training(fwd, seeds, 0.01, (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT), end_to_end=False)
 
 
+@pytest.mark.parametrize("shape,kernel", [((2, 5, 8, 8), "dwconv_dgrad_lds"), ((3, 7, 16, 16), "dwconv_dgrad_lds"),
+                                          ((1, 3, 32, 32), "dwconv_dgrad_lds"), ((2, 4, 10, 14), "dwconv_dgrad"), ((1, 2, 40, 36), "dwconv_dgrad")])
+def test_training_depthwise_backward_kernels(shape, kernel):
+    """Depthwise backward, both filter sizes and strides in one graph: planes of up to 1024 pixels with rows of a multiple
+    of four go through LDS (several small planes per workgroup, a ragged last group), the others through the
+    element-wise kernel; the weight gradient likewise has its LDS path and its general one."""
+    from workloads.model import Builder
+    b = Builder("depthwise_backward")
+    x = b.input(*shape)
+    pw = b.conv1x1(x, shape[1])
+    outs = [b.global_avgpool(b.dwconv(pw, k, s)) for k in (3, 5) for s in (1, 2)]
+    f = b.fc(b.add_n(outs), 4)
+    rng = np.random.default_rng(7)
+    b.draw_weights(rng, 0.3, "random")
+    fwd = b.finish(rng, outputs=[f])
+    seeds = {f: rng.standard_normal(fwd.nodes[f].shape).astype(np.float32)}
+    tw = workloads.training_graph(fwd, 0.01, seeds)
+    r = GraphRunner(tw)
+    r.schedule()
+    r.plan()
+    names = {B.ng_planned_task_kernel(r.g, v) for v, nd in enumerate(tw.nodes) if nd.op == "dwconv_dgrad"}
+    r.close()
+    assert names == {kernel}, names
+    check_training(fwd, seeds, 0.01, (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT), end_to_end=False)
+
+
 def test_training_step_nas_cell_batch32_cifar():
     """The paper's training setting: batch 32, 32 x 32 inputs. One normal and one reduction cell of the
     NASNet-style recipe between a 3x3 stem and a 10-way classifier; 259 tasks in one DAG."""
