@@ -111,7 +111,7 @@ constexpr bool is_lean_kernel(int kid) {
 // the repacked-weight kernels of the full build).
 enum { BUILD_LEAN = 0, BUILD_FULL = 1, BUILD_TRAIN = 2 };
 constexpr bool in_build(int build, int kid) {
-    return (kid >= KID_SGD_BATCH && kid <= KID_PAIR_PW32) ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid));
+    return (kid >= KID_SGD_BATCH && kid <= KID_PAIR_PW32) ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid) || is_pool_row(kid));
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)

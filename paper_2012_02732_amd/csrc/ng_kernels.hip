@@ -2437,7 +2437,7 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             PoolArgs a{buf(nd.preds[0]), buf(v), (int)i0.h, (int)i0.w, (int)o.h, (int)o.w,
                        nd.p.stride, nd.p.pad, nd.p.pool_mode, total};
             // large tensors (batches): four outputs of a column per thread
-            if (total >= kPoolRowMinOutputs && !g->trainable && (nd.p.stride == 1 || nd.p.stride == 2)) {
+            if (total >= kPoolRowMinOutputs && (nd.p.stride == 1 || nd.p.stride == 2)) {
                 const long items = (long)o.n * o.c * ceil_div(o.h, 4) * o.w;
                 if (nd.p.stride == 1) set_kernel<KID_POOL_ROW_S1>(t, a, ceil_div(items, kBlock));
                 else set_kernel<KID_POOL_ROW_S2>(t, a, ceil_div(items, kBlock));

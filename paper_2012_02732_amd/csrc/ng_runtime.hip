@@ -307,6 +307,7 @@ int build_resident(ng_graph* g) {
         if (t.fn && is_train_kernel(t.kid)) rt.resident_build = BUILD_TRAIN;
     for (const Task& t : g->tasks)
         if (t.fn && !is_lean_kernel(t.kid) && !is_train_kernel(t.kid)) {
+            if (rt.resident_build == BUILD_TRAIN && in_build(BUILD_TRAIN, t.kid)) continue;
             if (rt.resident_build == BUILD_TRAIN) return g->fail(NG_EINVAL, "device-resident replay: kernel %s does not belong in a graph that trains", t.name);
             rt.resident_build = BUILD_FULL;
         }
