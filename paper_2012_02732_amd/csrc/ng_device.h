@@ -31,6 +31,7 @@ enum Kid : int {
     // conv1x1 for many output pixels on the same plan (activations pixel-major in LDS, 32 or 64 channels at a time, weights
     // straight from memory): 32 x 64 and 64 x 64 output tiles
     KID_PW_P32, KID_PW_P64,
+    KID_DW_LDS,                      // depthwise 3 x 3 / 5 x 5, stride 1 / 2 on planes of up to 1024 pixels staged in LDS, four outputs side by side per thread
     KID_POOL_ROW_S1, KID_POOL_ROW_S2,   // pool3x3 for large tensors: a thread computes 4 outputs of a column, lanes run along the row (stride 1 / 2)
     // graphs that train (weights change between replays, so nothing is repacked): convolutions and fc, forward and backward,
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
@@ -68,7 +69,8 @@ constexpr bool is_c3m(int kid) { return plain_variant(kid) >= KID_C3_M1 && plain
 constexpr bool has_add_epilogue(int kid) { return plain_variant(kid) != kid; }
 constexpr bool is_c3_patch(int kid) { return kid >= KID_C3_P64 && kid <= KID_C3_Q128; }
 constexpr bool is_pw_patch(int kid) { return kid == KID_PW_P32 || kid == KID_PW_P64; }
-constexpr bool is_pool_row(int kid) { return kid == KID_POOL_ROW_S1 || kid == KID_POOL_ROW_S2; }
+// windowed kernels for large tensors (batches): not in the lean build, but in the full and the train build
+constexpr bool is_large_tensor_kernel(int kid) { return kid == KID_POOL_ROW_S1 || kid == KID_POOL_ROW_S2 || kid == KID_DW_LDS; }
 constexpr bool is_c3_lds(int kid) { return kid == KID_C3_L32 || kid == KID_C3_L64 || is_c3_patch(kid); }
 // convolutions whose argument block is a C3Args (the others with a batch-norm epilogue take a PwArgs)
 constexpr bool takes_c3_args(int kid) { return is_c3m(kid) || is_c3_lds(kid) || (kid >= KID_C3_T16S1 && kid <= KID_C3_T8S2); }
@@ -103,7 +105,7 @@ constexpr bool is_matrix_kernel(int kid_any) {
 // kernels of the lean build of the resident kernel: everything except the 32 x 32 and LDS-tiled
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
-    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) && !is_pool_row(kid) &&
+    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) && !is_large_tensor_kernel(kid) &&
            !is_train_kernel(kid) && !(kid >= KID_SGD_BATCH && kid <= KID_PAIR_PW32);
 }
 // Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean
@@ -111,7 +113,7 @@ constexpr bool is_lean_kernel(int kid) {
 // the repacked-weight kernels of the full build).
 enum { BUILD_LEAN = 0, BUILD_FULL = 1, BUILD_TRAIN = 2 };
 constexpr bool in_build(int build, int kid) {
-    return (kid >= KID_SGD_BATCH && kid <= KID_PAIR_PW32) ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid) || is_pool_row(kid));
+    return (kid >= KID_SGD_BATCH && kid <= KID_PAIR_PW32) ? false : build == BUILD_LEAN ? is_lean_kernel(kid) : build == BUILD_FULL ? !is_train_kernel(kid) : (is_lean_kernel(kid) || is_train_kernel(kid) || is_large_tensor_kernel(kid));
 }
 
 constexpr int kBlock = 256;          // threads that work on one tile (a stand-alone kernel's workgroup)
@@ -182,6 +184,7 @@ struct DwArgs {
     float* y;
     int C, H, W, Ho, Wo;
     int total;                 // output elements
+    int K, S, planes_per_tile; // dwconv_lds: filter size, stride, whole (image, channel) planes per workgroup (the other kernels have K and S as template arguments)
 };
 
 struct GapArgs {

@@ -1479,6 +1479,60 @@ __device__ __forceinline__ void pool3x3_col_tile(const PoolArgs& a, int tile, fl
     }
 }
 
+// ------------------------------------------------------------------------------------
+// dwconv for large tensors of small planes (batches of CIFAR-sized maps): a workgroup takes as many whole
+// (image, channel) planes as fit 1024 input pixels, stages them in LDS with a border of zeros (one 128-bit load per
+// thread; the taps then need no bounds and no index arithmetic beyond a row pitch) and every thread computes four
+// outputs side by side from K rows of 3 S + K values, stored with one 128-bit store.
+// ------------------------------------------------------------------------------------
+template <int K, int S, bool FIN, class Wait>
+__device__ __forceinline__ void dwconv_lds_impl(const DwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    constexpr int p = K / 2, SPAN = 3 * S + K;
+    const bool fout = wait.far_out();
+    const int HW = a.H * a.W, HWo = a.Ho * a.Wo;
+    const int PW = a.W + 2 * p, PHW = (a.H + 2 * p) * PW;
+    const int G = a.planes_per_tile;
+    const int p0 = tile * G, np = live ? min(G, a.total / HWo - p0) : 0;
+    const int xq = 4 * tid, gi = xq / HW, xrem = xq - gi * HW, iy = xrem / a.W, ix = xrem - iy * a.W;
+    const int oq = 4 * tid, go = oq / HWo, orem = oq - go * HWo, oy = orem / a.Wo, ox = orem - oy * a.Wo;
+    const bool xin = gi < np, oin = go < np;
+    float w[K * K];
+    const float* wt = a.w + ((p0 + min(go, max(np - 1, 0))) % a.C) * (K * K);
+#pragma unroll
+    for (int q = 0; q < K * K; ++q) w[q] = wt[q];              // filter taps: not produced by any task
+    wait();
+    const float4 x4 = xin ? ldg4(a.x, a.x + (size_t)p0 * HW + xq, FIN) : make_float4(0.f, 0.f, 0.f, 0.f);
+    __syncthreads();                                            // a previous tile of this workgroup has been read to the end
+    for (int i = tid; i < G * PHW; i += kBlock) smem[i] = 0.f;
+    __syncthreads();
+    if (xin) {
+        float* dst = smem + gi * PHW + (iy + p) * PW + ix + p;
+        dst[0] = x4.x, dst[1] = x4.y, dst[2] = x4.z, dst[3] = x4.w;
+    }
+    __syncthreads();
+    if (!oin) return;
+    const float* src = smem + go * PHW + oy * S * PW + ox * S;  // tap (0, 0) of the first of the four outputs
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int da = 0; da < K; ++da) {
+        float v[SPAN];
+#pragma unroll
+        for (int s = 0; s < SPAN; ++s) v[s] = src[da * PW + s];
+#pragma unroll
+        for (int db = 0; db < K; ++db)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[j] = fmaf(w[da * K + db], v[j * S + db], acc[j]);   // taps in ascending order, as dwconv_tile
+    }
+    stg4(a.y, a.y + (size_t)p0 * HWo + oq, make_float4(acc[0], acc[1], acc[2], acc[3]), fout);
+}
+template <bool FIN, class Wait>
+__device__ __forceinline__ void dwconv_lds_tile(const DwArgs& a, int tile, float* smem, int tid, bool live, Wait& wait) {
+    if (a.K == 3 && a.S == 1) dwconv_lds_impl<3, 1, FIN>(a, tile, smem, tid, live, wait);
+    else if (a.K == 3) dwconv_lds_impl<3, 2, FIN>(a, tile, smem, tid, live, wait);
+    else if (a.S == 1) dwconv_lds_impl<5, 1, FIN>(a, tile, smem, tid, live, wait);
+    else dwconv_lds_impl<5, 2, FIN>(a, tile, smem, tid, live, wait);
+}
+
 #include "ng_train_tiles.inc"
 
 // ------------------------------------------------------------------------------------
@@ -1591,6 +1645,7 @@ NG_KERNEL(KID_SLICE_PAD, EltGradArgs, "slice_pad", elt_grad_tile < 2)
         }                                                                                      \
     };
 NG_KERNEL0(KID_GAP, GapArgs, "global_avgpool", global_avgpool_tile)
+NG_KERNEL0(KID_DW_LDS, DwArgs, "dwconv_lds", dwconv_lds_tile)
 NG_KERNEL0(KID_FC_GEMV, FcArgs, "fc_gemv", fc_gemv_tile)
 NG_KERNEL0(KID_CHANNEL_SUM, EltGradArgs, "channel_sum", channel_sum_tile)
 NG_KERNEL0(KID_DW_DGRAD, DwGradArgs, "dwconv_dgrad", dw_dgrad_tile)
@@ -1643,7 +1698,7 @@ NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
     X(KID_PW_S3A) X(KID_PW_S4A) X(KID_C3_M1A) X(KID_C3_M2A) X(KID_C3_M3A) X(KID_C3_M4A)                                 \
     X(KID_POOL_A) X(KID_POOL_P4A) X(KID_C3_L32) X(KID_C3_L64)                                                          \
     X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
-    X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2)                                                                               \
+    X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2) X(KID_DW_LDS)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
     X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_C3_WGRAD_PX) X(KID_C3_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD) X(KID_DW_DGRAD_LDS)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD) X(KID_PAIR_DW) X(KID_PAIR_DW_LDS) X(KID_PAIR_PW16) X(KID_PAIR_PW32)
@@ -2099,6 +2154,7 @@ void k4_split(long k_total, long cout, PwChoice& c) {
 }
 constexpr long kPwPatchMinCols = 2048;
 constexpr long kPoolRowMinOutputs = 1 << 20;   // pool3x3: from here on the kernel with four outputs of a column per thread
+constexpr long kDwLdsMinOutputs = 1 << 18;     // dwconv: from here on whole planes through LDS (dwconv_lds), where the planes allow
 PwChoice choose_pw(const ng_graph* g, int v) {
     PwChoice c;
     const Node& nd = g->nodes[v];
@@ -2449,6 +2505,16 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
         case NG_OP_DWCONV: {
             DwArgs a{buf(nd.preds[0]), wf(0), buf(v), (int)o.c, (int)i0.h, (int)i0.w, (int)o.h, (int)o.w, total};
             const long n = ceil_div(total, kBlock);
+            // large tensors of small planes (batches): whole planes through LDS, four outputs per thread
+            const long plane = (long)i0.h * i0.w, per_wg = plane <= 1024 ? 1024 / plane : 0;
+            const int bd = nd.p.k / 2;
+            if (total >= kDwLdsMinOutputs && (nd.p.k == 3 || nd.p.k == 5) && (nd.p.stride == 1 || nd.p.stride == 2) && i0.w % 4 == 0 &&
+                o.w % 4 == 0 && per_wg > 0 && (long)o.h * o.w <= plane &&
+                per_wg * (i0.h + 2 * bd) * (i0.w + 2 * bd) <= kSmemFloats) {
+                a.K = nd.p.k, a.S = nd.p.stride, a.planes_per_tile = (int)per_wg;
+                set_kernel<KID_DW_LDS>(t, a, ceil_div((long)o.n * o.c, per_wg));
+                break;
+            }
             if (nd.p.k == 3 && nd.p.stride == 1) set_kernel<KID_DW_K3S1>(t, a, n);
             else if (nd.p.k == 3) set_kernel<KID_DW_K3S2>(t, a, n);
             else if (nd.p.stride == 1) set_kernel<KID_DW_K5S1>(t, a, n);

@@ -111,7 +111,7 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
         }
         case KID_BN_RAW: case KID_BN_DGRAD: case KID_RELU_DGRAD: case KID_GAP_DGRAD: case KID_SLICE_PAD: case KID_SGD: base = 1.2, per_tile = 0.15; break;
         case KID_DW_DGRAD: case KID_POOL_DGRAD: base = 2.0, per_tile = 0.7; break;
-        case KID_POOL_DGRAD_LDS: case KID_DW_DGRAD_LDS: base = 2.5, per_tile = 1.0; break;
+        case KID_POOL_DGRAD_LDS: case KID_DW_DGRAD_LDS: case KID_DW_LDS: base = 2.5, per_tile = 1.0; break;
         case KID_BN_WGRAD: case KID_CHANNEL_SUM: {
             double count = (double)g->nodes[nd.preds[0]].out.elems() / std::max<double>(1.0, (double)g->nodes[nd.preds[0]].out.c);
             if (kid == KID_BN_WGRAD) count /= std::max(1, reinterpret_cast<const BnRawArgs*>(g->tasks[v].args)->chunks);   // a channel's images are split over workgroups

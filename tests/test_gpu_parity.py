@@ -189,6 +189,27 @@ def test_pool_large_tensors(shape):
     check_all_nodes(w, (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
 
 
+# dwconv on large tensors of small planes: whole planes through LDS, four outputs side by side per thread; both filter
+# sizes and strides; one, four and sixteen planes per workgroup with a ragged last group
+@pytest.mark.parametrize("shape", [(2, 130, 32, 32), (3, 343, 16, 16), (17, 250, 8, 8)])
+def test_dwconv_planes_through_lds(shape):
+    def build(b):
+        x = b.input(*shape)
+        for k in (3, 5):
+            for stride in (1, 2):
+                if shape[0] * shape[1] * (shape[2] // stride) * (shape[3] // stride) >= 1 << 18:
+                    b.dwconv(x, k, stride)
+    w = single_op(build)
+    r = GraphRunner(w, DEV)
+    r.prepare()
+    try:
+        names = {B.ng_task_kernel(r.g, v) for v in range(1, len(w.nodes))}
+    finally:
+        r.close()
+    assert names == {"dwconv_lds"}, names
+    check_all_nodes(w, (B.NG_MODE_GRAPH_MULTI, B.NG_MODE_DEVICE_RESIDENT))
+
+
 @pytest.mark.parametrize("n,cin,cout", [(1, 2048, 1000), (3, 100, 10), (8, 33, 5), (32, 2048, 1000), (9, 64, 7),
                                         (1024, 70, 1000),      # a batch large enough for the LDS-tiled kernel, with a bias
                                         (2048, 64, 100)])      # ... and for the kernel with the activations pixel-major in LDS

@@ -797,7 +797,11 @@ def test_kernel_choice_in_a_training_graph():
         by_op.setdefault(nd.op, set()).add(k[v])
     # weights change between replays: convolutions read the weights as they are, never a repacked copy; with 44 and 88
     # channels the 1 x 1 convolutions stream the pixels 128 bits at a time, forward and input gradient
-    assert by_op["conv1x1"] == {"conv1x1_px_fwd"} and by_op["conv3x3"] == {"gemm_conv3x3_fwd"} and by_op["pool"] == {"pool3x3"}
+    assert by_op["conv1x1"] == {"conv1x1_px_fwd"} and by_op["conv3x3"] == {"gemm_conv3x3_fwd"}
+    # tensors of 1.4 M elements: pooling with four outputs of a column per thread (0.7 M in the reduction cell: one per thread);
+    # depthwise convolutions, forward and backward, on whole 32 x 32 or 16 x 16 planes staged in LDS
+    assert by_op["pool"] == {"pool3x3", "pool3x3_col4_s1"}
+    assert by_op["dwconv"] == {"dwconv_lds"} and by_op["dwconv_dgrad"] == {"dwconv_dgrad_lds"} and by_op["dwconv_wgrad"] == {"dwconv_wgrad"}
     # the classifier (1 x 1 maps, a bias) stays on the gather GEMM, forward and backward
     assert by_op["conv1x1_dgrad"] == {"conv1x1_px_dgrad", "gemm_conv1x1_dgrad"} and by_op["fc"] == {"gemm_conv1x1_fwd"}
     assert sum(name == "gemm_conv1x1_dgrad" for name in k) == 1
