@@ -570,6 +570,16 @@ def test_multi_stream_graph_edges_of_a_training_graph_with_gathered_updates():
     for v in absorbed:
         u = launched_by[v]
         assert {ops[v], ops[u]} == {"bn_act_dgrad", "bn_act_wgrad"} and w.nodes[v].preds == w.nodes[u].preds and pos[u] < pos[v]
+    # ... and the input gradient and the weight gradient of a depthwise or 1 x 1 convolution (same dy) in one launch with
+    # their workgroups interleaved: the later one's inputs must all come before the earlier one
+    for kind in ("dwconv", "conv1x1"):
+        halves = [v for v in range(len(ops)) if ops[v] in (kind + "_dgrad", kind + "_wgrad")]
+        absorbed = [v for v in halves if launched_by[v] != v]
+        assert len(absorbed) >= len(halves) // 2 - 1, kind            # all but the classifier's pair (other kernels)
+        for v in absorbed:
+            u = launched_by[v]
+            assert {ops[v], ops[u]} == {kind + "_dgrad", kind + "_wgrad"} and w.nodes[v].preds[0] == w.nodes[u].preds[0]
+            assert pos[u] < pos[v] and all(pos[q] < pos[u] for q in w.nodes[v].preds)
 
 
 @pytest.mark.parametrize("seed", [11, 12, 13])
