@@ -36,6 +36,7 @@ enum Kid : int {
     // graphs that train (weights change between replays, so nothing is repacked): convolutions and fc, forward and backward,
     // as one LDS-staged MFMA GEMM that gathers its operands from the natural layouts; the other backward operators; the update
     KID_GEMM_PW_FWD, KID_GEMM_PW_DGRAD, KID_GEMM_PW_WGRAD, KID_GEMM_C3_FWD, KID_GEMM_C3_DGRAD, KID_GEMM_C3_WGRAD,
+    KID_SMALL_GEMM,                  // C = A B (+ bias) of a few thousand outputs at most (the classifier of a network that trains, forward and backward): no tiles, no LDS
     KID_PW_PX_FWD, KID_PW_PX_DGRAD,  // conv1x1 forward / input gradient for few channels: pixels read 128 bits at a time straight into matrix-instruction operands (HW % 4 == 0)
     KID_C3_WGRAD_PX, KID_C3_WGRAD_PX2,  // the same for conv3x3 (stride 1, padding 1, rows of a multiple of 16 pixels): the second operand is the input shifted by the tap
     KID_PW_WGRAD_PX, KID_PW_WGRAD_PX2,  // conv1x1 weight gradient with both operands read along the pixels, 128 bits at a time (HW % 16 == 0): blocks of 16 x 16 / 32 x 32 weights
@@ -314,6 +315,13 @@ struct PoolGradArgs {          // pool backward; geometry of the FORWARD operato
     float* y;                  // dx
     int H, W, Ho, Wo, stride, pad, mode, total;
     int planes_per_tile;       // pool3x3_dgrad_lds: whole (image, channel) planes a workgroup stages in LDS (planes_per_tile H W <= kPoolGradChunk)
+};
+// C[m][n] = sum_k A[m][k] B[k][n] (+ bias[m]) with every operand addressed by two strides (in floats)
+struct SmallGemmArgs {
+    const float* a; const float* b; float* c; const float* bias;
+    int M, N, K;
+    int sam, sak, sbk, sbn, scm, scn;
+    int by_wave;               // 1: one wavefront per output, K over the lanes (both operands contiguous along k); 0: one thread per output
 };
 constexpr int kPoolGradChunk = 1024;
 struct SgdArgs {

@@ -1654,6 +1654,7 @@ NG_KERNEL0(KID_DW_WGRAD, DwGradArgs, "dwconv_wgrad", dw_wgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD, PoolGradArgs, "pool3x3_dgrad", pool_dgrad_tile)
 NG_KERNEL0(KID_POOL_DGRAD_LDS, PoolGradArgs, "pool3x3_dgrad_lds", pool_dgrad_lds_tile)
 NG_KERNEL0(KID_SGD, SgdArgs, "sgd_update", sgd_tile)
+NG_KERNEL0(KID_SMALL_GEMM, SmallGemmArgs, "small_gemm", small_gemm_tile)
 // Two tasks in one launch (they read the same tensor and neither waits for the other): the workgroups of both are dealt
 // out alternately while both have tiles left, so that the two - each bound by latency rather than by bandwidth when it runs
 // alone - share the compute units from the start.
@@ -1700,7 +1701,7 @@ NG_KERNEL0(KID_SGD_BATCH, SgdBatchArgs, "sgd_update_batch", sgd_batch_tile)
     X(KID_C3_P64) X(KID_C3_P96) X(KID_C3_Q32) X(KID_C3_Q64) X(KID_C3_Q128) X(KID_PW_P32) X(KID_PW_P64)                    \
     X(KID_POOL_ROW_S1) X(KID_POOL_ROW_S2) X(KID_DW_LDS)                                                                               \
     X(KID_GEMM_PW_FWD) X(KID_GEMM_PW_DGRAD) X(KID_GEMM_PW_WGRAD) X(KID_GEMM_C3_FWD) X(KID_GEMM_C3_DGRAD)                \
-    X(KID_GEMM_C3_WGRAD) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_C3_WGRAD_PX) X(KID_C3_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD) X(KID_DW_DGRAD_LDS)                \
+    X(KID_GEMM_C3_WGRAD) X(KID_SMALL_GEMM) X(KID_PW_PX_FWD) X(KID_PW_PX_DGRAD) X(KID_PW_WGRAD_PX) X(KID_PW_WGRAD_PX2) X(KID_C3_WGRAD_PX) X(KID_C3_WGRAD_PX2) X(KID_BN_RAW) X(KID_BN_DGRAD) X(KID_BN_WGRAD) X(KID_RELU_DGRAD) X(KID_DW_DGRAD) X(KID_DW_DGRAD_LDS)                \
     X(KID_DW_WGRAD) X(KID_POOL_DGRAD) X(KID_POOL_DGRAD_LDS) X(KID_GAP_DGRAD) X(KID_CHANNEL_SUM) X(KID_SLICE_PAD) X(KID_SGD) X(KID_SGD_BATCH) X(KID_BN_BACKWARD) X(KID_PAIR_DW) X(KID_PAIR_DW_LDS) X(KID_PAIR_PW16) X(KID_PAIR_PW32)
 
 // A batch-norm epilogue is written into a task's argument block by type (C3Args or PwArgs, whose `ep` fields sit at
@@ -2013,6 +2014,13 @@ bool pw_px_applies(const GemmArgs& a) {
     return hw % 4 == 0 && a.K % 4 == 0 && a.M <= 256 && a.bias == nullptr && (long)a.K * a.N * 4 < (1L << 31) &&
            (long)a.M * a.N * 4 < (1L << 31);
 }
+// The classifier's GEMMs (1 x 1 maps, a few thousand outputs, K up to a few hundred): no tiles. K over the lanes of a
+// wavefront where both operands run along k and K is long, else a thread per output.
+constexpr long kSmallGemmOutputs = 1 << 16, kSmallGemmK = 1024;
+void set_small_gemm(Task& t, SmallGemmArgs a, void (*set)(Task&, const SmallGemmArgs&, long)) {
+    a.by_wave = a.sak == 1 && a.sbk == 1 && a.K >= 64;
+    set(t, a, a.by_wave ? ceil_div((long)a.M * a.N, kBlock / 64) : ceil_div((long)a.M * a.N, kBlock));
+}
 long pw_px_tiles(const GemmArgs& a) { return ceil_div(ceil_div(a.N / 4, 16) * ceil_div(a.M, 16), 4); }
 
 // Direct conv1x1: k steps per chunk by problem depth, and the padded step count of the packed copy.
@@ -2288,6 +2296,7 @@ long dw_wgrad_chunks(long channels, long images) { return bn_wgrad_chunks(channe
 // How a weight-gradient node is computed: which kernel, how K is split, what workspace it needs.
 struct WgradPlan {
     bool px = false;              // conv1x1_wgrad_px (both operands 128 bits along the pixels) instead of the gather GEMM
+    bool small = false;           // small_gemm: 1 x 1 maps and a few thousand weights (the classifier), no split, no workspace
     int block = 0;                // px: fragments of 16 x 16 weights along each side of a workgroup's block (1 or 2)
     long tiles = 0;
     int splits = 1, k_per_split = 0;
@@ -2303,6 +2312,10 @@ WgradPlan wgrad_plan(const ng_graph* g, int v) {
     const Shape& x = g->nodes[nd.preds[1]].out;
     p.tiles = ceil_div(m, kGemmTile) * ceil_div(n, kGemmTile);
     const size_t tile_floats = (size_t)kGemmTile * kGemmTile;
+    if (nd.op == NG_OP_CONV1X1_WGRAD && dy.h * dy.w == 1 && m * n <= kSmallGemmOutputs && k <= kSmallGemmK) {
+        p.small = true, p.splits = 1, p.k_per_split = (int)k;
+        return p;
+    }
     p.px = (dy.h * dy.w) % 16 == 0 && dy.elems() * 4 < (1L << 31) && x.elems() * 4 < (1L << 31) &&
            (nd.op == NG_OP_CONV1X1_WGRAD || (nd.p.stride == 1 && nd.p.pad == 1 && dy.w % 16 == 0 && dy.h == x.h && dy.w == x.w));
     const long fm = ceil_div(m, 16), fn = ceil_div(n, 16);
@@ -2535,6 +2548,12 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 a.M = (int)o.c, a.K = (int)i0.c, a.N = (int)(o.n * hw_out);
                 a.Cin = (int)i0.c, a.Cout = (int)o.c, a.H = a.Ho = (int)o.h, a.W = a.Wo = (int)o.w, a.stride = 1;
                 a.tiles_n = (int)ceil_div(a.N, kGemmTile), a.splits = 1, a.k_per_split = a.K;
+                if (hw_out == 1 && (long)a.M * a.N <= kSmallGemmOutputs && a.K <= kSmallGemmK) {
+                    // Y[n][o] = sum_k W[o][k] X[n][k] + b[o]
+                    SmallGemmArgs sg{a.a, a.b, a.c, a.bias, a.M, a.N, a.K, a.K, 1, 1, a.K, 1, a.M, 0};
+                    set_small_gemm(t, sg, [](Task& tt, const SmallGemmArgs& aa, long n) { set_kernel<KID_SMALL_GEMM>(tt, aa, n); });
+                    break;
+                }
                 if (!fc && pw_px_applies(a)) set_kernel<KID_PW_PX_FWD>(t, a, pw_px_tiles(a));
                 else set_kernel<KID_GEMM_PW_FWD>(t, a, (long)a.tiles_n * ceil_div(a.M, kGemmTile));
                 break;
@@ -2676,6 +2695,12 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
             a.M = a.Cin, a.K = a.Cout * (c3 ? 9 : 1), a.N = (int)(o.n * o.h * o.w);
             a.tiles_n = (int)ceil_div(a.N, kGemmTile), a.splits = 1, a.k_per_split = a.K;
             const long n = (long)a.tiles_n * ceil_div(a.M, kGemmTile);
+            if (!c3 && o.h * o.w == 1 && (long)a.M * a.N <= kSmallGemmOutputs && a.K <= kSmallGemmK) {
+                // dX[n][ci] = sum_co W[co][ci] dY[n][co]
+                SmallGemmArgs sg{a.a, a.b, a.c, nullptr, a.M, a.N, a.K, 1, a.M, 1, a.K, 1, a.M, 0};
+                set_small_gemm(t, sg, [](Task& tt, const SmallGemmArgs& aa, long n2) { set_kernel<KID_SMALL_GEMM>(tt, aa, n2); });
+                break;
+            }
             if (c3) set_kernel<KID_GEMM_C3_DGRAD>(t, a, n);
             else if (pw_px_applies(a)) set_kernel<KID_PW_PX_DGRAD>(t, a, pw_px_tiles(a));
             else set_kernel<KID_GEMM_PW_DGRAD>(t, a, n);
@@ -2699,6 +2724,12 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 if (!packed) return g->fail(NG_EINVAL, "node %d: no workspace for the split-K partial tiles", v);
                 a.ws = packed;
                 a.cnt = reinterpret_cast<unsigned*>(packed + p.ws_floats);
+            }
+            if (p.small) {
+                // dW[co][ci] = sum_n dY[n][co] X[n][ci]
+                SmallGemmArgs sg{a.a, a.b, a.c, nullptr, a.M, a.N, a.K, 1, a.M, a.N, 1, a.N, 1, 0};
+                set_small_gemm(t, sg, [](Task& tt, const SmallGemmArgs& aa, long n2) { set_kernel<KID_SMALL_GEMM>(tt, aa, n2); });
+                break;
             }
             if (p.px) a.tiles_n = (int)ceil_div(ceil_div(a.N, 16), p.block);
             if (p.px && c3 && p.block == 1) set_kernel<KID_C3_WGRAD_PX>(t, a, tiles * a.splits);

@@ -98,6 +98,7 @@ double tile_round_us(const ng_graph* g, int v, int kid_any, int subs) {
         case KID_C3_P96: base = 2.5, per_tile = 0.45 * cin; break;
         case KID_C3_Q128: base = 2.5, per_tile = 0.6 * cin; break;
         case KID_PW_PX_FWD: case KID_PW_PX_DGRAD: base = 2.0, per_tile = 0.6; break;
+        case KID_SMALL_GEMM: base = 2.5, per_tile = 0.3; break;
         case KID_GEMM_PW_FWD: case KID_GEMM_PW_DGRAD: case KID_GEMM_PW_WGRAD: case KID_GEMM_C3_FWD: case KID_GEMM_C3_DGRAD:
         case KID_GEMM_C3_WGRAD: {
             const GemmArgs* a = reinterpret_cast<const GemmArgs*>(g->tasks[v].args);

@@ -812,11 +812,10 @@ def test_kernel_choice_in_a_training_graph():
     # depthwise convolutions, forward and backward, on whole 32 x 32 or 16 x 16 planes staged in LDS
     assert by_op["pool"] == {"pool3x3", "pool3x3_col4_s1"}
     assert by_op["dwconv"] == {"dwconv_lds"} and by_op["dwconv_dgrad"] == {"dwconv_dgrad_lds"} and by_op["dwconv_wgrad"] == {"dwconv_wgrad"}
-    # the classifier (1 x 1 maps, a bias) stays on the gather GEMM, forward and backward
-    assert by_op["conv1x1_dgrad"] == {"conv1x1_px_dgrad", "gemm_conv1x1_dgrad"} and by_op["fc"] == {"gemm_conv1x1_fwd"}
-    assert sum(name == "gemm_conv1x1_dgrad" for name in k) == 1
+    # the classifier (1 x 1 maps, 10 x 264 weights, a bias): three GEMMs of a few thousand outputs, no tiles
+    assert by_op["conv1x1_dgrad"] == {"conv1x1_px_dgrad", "small_gemm"} and by_op["fc"] == {"small_gemm"}
+    assert sum(name == "small_gemm" for name in k) == 3
     assert by_op["pool_dgrad"] == {"pool3x3_dgrad_lds"}
     # 32 x 32 and 16 x 16 maps: the weight gradient reads both operands 128 bits along the pixels; the fc (1 x 1 maps) cannot
-    assert by_op["conv1x1_wgrad"] == {"conv1x1_wgrad_px_16", "conv1x1_wgrad_px_32", "gemm_conv1x1_wgrad"}
+    assert by_op["conv1x1_wgrad"] == {"conv1x1_wgrad_px_16", "conv1x1_wgrad_px_32", "small_gemm"}
     assert by_op["conv3x3_wgrad"] == {"conv3x3_wgrad_px_16"}         # the stem: 44 x 27 weights, rows of 32 pixels
-    assert sum(name == "gemm_conv1x1_wgrad" for name in k) == 1
