@@ -247,6 +247,36 @@ def test_training_depthwise_backward_kernels(shape, kernel):
     check_training(fwd, seeds, 0.01, (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT), end_to_end=False)
 
 
+@pytest.mark.parametrize("shape,cout", [((3, 20, 6, 6), 24), ((2, 20, 8, 8), 24), ((5, 12, 4, 4), 40), ((1, 36, 16, 16), 7), ((2, 8, 5, 4), 150)])
+def test_training_conv1x1_pixel_kernels(shape, cout):
+    """conv1x1 forward, input gradient and weight gradient through the kernels that read pixels 128 bits at a time:
+    ragged last pixel groups, row fragments beyond Cout, K that ends inside a slice of 16 channels, a K range of the
+    weight gradient that ends inside a split, the batch-norm applied by the forward kernel (with and without ReLU),
+    and two convolutions in a row so that both gradients of the first are needed."""
+    from workloads.model import Builder
+    b = Builder("conv1x1_pixels")
+    x = b.input(*shape)
+    c1 = b.bn_act(b.conv1x1(x, cout), relu=True)
+    c2 = b.bn_act(b.conv1x1(c1, shape[1]), relu=False)
+    f = b.fc(b.global_avgpool(b.add_n([c2, x])), 3)
+    rng = np.random.default_rng(8)
+    b.draw_weights(rng, 0.3, "random")
+    fwd = b.finish(rng, outputs=[f])
+    seeds = {f: rng.standard_normal(fwd.nodes[f].shape).astype(np.float32)}
+    tw = workloads.training_graph(fwd, 0.01, seeds)
+    r = GraphRunner(tw)
+    r.schedule()
+    r.plan()
+    names = {nd.op: set() for nd in tw.nodes}
+    for v, nd in enumerate(tw.nodes):
+        names[nd.op].add(B.ng_planned_task_kernel(r.g, v))
+    r.close()
+    hw = shape[2] * shape[3]
+    assert "conv1x1_px_fwd" in names["conv1x1"] and "conv1x1_px_dgrad" in names["conv1x1_dgrad"], names   # (a K that is no multiple of 4: gather GEMM forward)
+    assert (hw % 16 != 0) == ("gemm_conv1x1_wgrad" in names["conv1x1_wgrad"]), names
+    check_training(fwd, seeds, 0.01, (B.NG_MODE_GRAPH_SINGLE, B.NG_MODE_DEVICE_RESIDENT, B.NG_MODE_GRAPH_MULTI), end_to_end=False)
+
+
 def test_training_step_nas_cell_batch32_cifar():
     """The paper's training setting: batch 32, 32 x 32 inputs. One normal and one reduction cell of the
     NASNet-style recipe between a 3x3 stem and a 10-way classifier; 259 tasks in one DAG."""
