@@ -199,8 +199,10 @@ int ng_set_memory_reuse(ng_graph* g, int on);
  * 2: of the last of them in the submission order; same arithmetic per element), and the input gradient
  * and the parameter gradients of a batch-norm (NG_OP_BN_ACT_DGRAD, NG_OP_BN_ACT_WGRAD with the same dy
  * and x) are computed in one walk over dy and x by the launch of whichever of the two comes first, if
- * both are on one stream (always, in modes 1 and 2). on = 0 switches the exceptions off: one kernel
- * per task. Call before ng_bind (NG_ESTATE after). */
+ * both are on one stream (always, in modes 1 and 2); likewise the input gradient and the weight gradient
+ * of a depthwise or 1 x 1 convolution (same dy) share one launch, their workgroups interleaved, if
+ * everything the later one reads is complete when the earlier one starts. on = 0 switches the
+ * exceptions off: one kernel per task. Call before ng_bind (NG_ESTATE after). */
 int ng_set_launch_fusion(ng_graph* g, int on);
 /* offset[n_nodes], bytes[n_nodes] of each node's output inside the arena (host arrays). */
 int ng_get_offsets(const ng_graph* g, size_t* offset, size_t* bytes);
