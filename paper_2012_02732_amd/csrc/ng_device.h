@@ -106,7 +106,7 @@ constexpr bool is_matrix_kernel(int kid_any) {
 // kernels of the lean build of the resident kernel: everything except the 32 x 32 and LDS-tiled
 // conv1x1 and the vector-ALU conv3x3 (kernels of large problems with large register needs)
 constexpr bool is_lean_kernel(int kid) {
-    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) && !is_large_tensor_kernel(kid) &&
+    return (!(kid >= KID_PW_D4 && kid <= KID_C3_T8S2) || kid == KID_C3_T16S2 || kid == KID_C3_T8S2) && kid != KID_C3_L32 && kid != KID_C3_L64 && !is_c3_patch(kid) && !is_pw_patch(kid) && !is_large_tensor_kernel(kid) &&
            !is_train_kernel(kid) && !(kid >= KID_SGD_BATCH && kid <= KID_PAIR_PW32);
 }
 // Three builds of the resident kernel: lean (small inference problems), full (every inference kernel), train (the lean

@@ -1248,8 +1248,11 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     constexpr int LDP = IW + 1;
     constexpr int GROUPS = TP == 16 ? 1 : 4;           // channel groups per workgroup
     constexpr int CO = 8;
-    static_assert(CIC * IW * LDP <= kSmemFloats, "LDS budget");
+    constexpr int WROW = 12;                           // a (channel, input channel) pair's nine taps, padded to three 128-bit reads
+    constexpr int NW = GROUPS * CO * CIC;              // such pairs per slice
+    static_assert(CIC * IW * LDP + NW * WROW <= kSmemFloats && (CIC * IW * LDP) % 4 == 0, "LDS budget; the weights start 16-byte aligned");
     float* patch = smem;                               // [CIC][IW][LDP]
+    float* wsm = smem + CIC * IW * LDP;                // [GROUPS CO][CIC][WROW]: the slice's weights of every output channel of the workgroup
 
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int local = TP == 16 ? tid : (tid & 63);
@@ -1265,10 +1268,12 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
     float acc[CO];
 #pragma unroll
     for (int j = 0; j < CO; ++j) acc[j] = 0.f;
-    // clamped weight rows: out-of-range channels repeat the last one and are masked at the store
-    const float* wrow[CO];
-#pragma unroll
-    for (int j = 0; j < CO; ++j) wrow[j] = a.w + (size_t)min(co0 + j, a.Cout - 1) * a.Cin * 9;
+    // The weights go through LDS with the patch (one batch of loads, one barrier): read through uniform addresses
+    // straight from memory they arrived a few at a time, each batch a trip to L2 that the wavefront waited for, and
+    // that, not arithmetic or bandwidth, was the tile's 8 us on a stem. Out-of-range channels repeat the last one and are
+    // masked at the store.
+    const int cbase = cog * GROUPS * CO;               // first output channel of the workgroup
+    const int wgroup = TP == 16 ? 0 : wave;
 
     for (int c0 = 0; c0 < a.Cin; c0 += CIC) {
         if (live) {
@@ -1284,6 +1289,15 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
                 const float v = ldg(a.x, xin + ((size_t)min(gc, a.Cin - 1) * a.H + min(max(gy, 0), a.H - 1)) * a.W + min(max(gx, 0), a.W - 1), FIN);
                 pv[q] = in ? v : 0.f;
             }
+            constexpr int NWL = (NW * 9 + kBlock - 1) / kBlock;         // weight loads per thread
+            float wv[NWL];
+#pragma unroll
+            for (int q = 0; q < NWL; ++q) {
+                const int e = min(tid + q * kBlock, NW * 9 - 1);
+                const int tap = e % 9, pair = e / 9, ci = pair % CIC, jj = pair / CIC;
+                const float v = a.w[((size_t)min(cbase + jj, a.Cout - 1) * a.Cin + min(c0 + ci, a.Cin - 1)) * 9 + tap];
+                wv[q] = c0 + ci < a.Cin ? v : 0.f;
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int q = 0; q < NL; ++q) {
@@ -1293,6 +1307,11 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
                     const int cy = t % IW, ci = t / IW;
                     patch[(ci * IW + cy) * LDP + cx] = pv[q];
                 }
+            }
+#pragma unroll
+            for (int q = 0; q < NWL; ++q) {
+                const int e = tid + q * kBlock;
+                if (e < NW * 9) wsm[(e / 9) * WROW + e % 9] = wv[q];
             }
         }
         __syncthreads();
@@ -1305,9 +1324,11 @@ __device__ __forceinline__ void conv3x3_tile(const C3Args& a, int tile, float* s
                 for (int dc = 0; dc < 3; ++dc) in[dr * 3 + dc] = patch[(ci * IW + ty * S + dr) * LDP + tx * S + dc];
 #pragma unroll
             for (int j = 0; j < CO; ++j) {
-                const float* wp = wrow[j] + (c0 + ci) * 9;
+                const float4* wp = reinterpret_cast<const float4*>(wsm + ((wgroup * CO + j) * CIC + ci) * WROW);   // the same address in every lane: a broadcast
+                const float4 w0 = wp[0], w1 = wp[1], w2 = wp[2];
+                const float wq[9] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w, w2.x};
 #pragma unroll
-                for (int q = 0; q < 9; ++q) acc[j] = fmaf(wp[q], in[q], acc[j]);
+                for (int q = 0; q < 9; ++q) acc[j] = fmaf(wq[q], in[q], acc[j]);
             }
         }
         __syncthreads();
@@ -2670,7 +2691,9 @@ int build_task(ng_graph* g, int v, char* arena, float* packed, Task& t) {
                 else set_kernel<KID_C3_M4>(t, a, n);
                 break;
             }
-            const bool small = o.h * o.w <= 24 * 24;       // small maps: 8 x 8 tiles waste fewer lanes
+            // small maps: 8 x 8 tiles waste fewer lanes; a stem at batch 1 (3 input channels, a large map): four times the
+            // workgroups, each with a quarter of the patch to load
+            const bool small = o.h * o.w <= 24 * 24 || (a.Cin <= 4 && o.n == 1);
             const int tp = small ? 8 : 16;
             a.tiles_x = (int)ceil_div(o.w, tp);
             a.tiles_xy = a.tiles_x * (int)ceil_div(o.h, tp);
